@@ -1,0 +1,209 @@
+"""numpy front-end of the CPU oracle (``gnn_oracle.c``) -- TEST INFRASTRUCTURE ONLY.
+
+The oracle is the plain definition of every operation on the message-passing
+path (paper section 3, "Message Passing": apply_edges, aggregate_neighbors,
+propagate; layers named in "Graph Convolutional Layers" / "Training Example").
+Only tests, the smoke check and the benchmark's CPU-baseline leg import this
+package; the GPU library never does, and this package never imports it.
+
+The wrapper does argument marshalling only: it checks dtypes/shapes, allocates
+outputs and calls the C functions.  ``build()`` compiles the C file with gcc.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "gnn_oracle.c")
+_LIB = os.path.join(_HERE, "libgnn_oracle.so")
+
+MSG_COPY_XJ, MSG_E_MUL_XJ = 0, 1
+AGGR_SUM, AGGR_MEAN, AGGR_MAX = 0, 1, 2
+
+_lib = None
+
+
+class OracleError(RuntimeError):
+    pass
+
+
+def build(force: bool = True) -> str:
+    """Compile the oracle (plain gcc, no fast-math, no FMA contraction)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp.%d" % os.getpid()
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-ffp-contract=off", "-fno-fast-math",
+                               "-Wall", "-Wextra", "-shared", "-fPIC", "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build(force=False)
+        _lib = ctypes.CDLL(_LIB)
+    return _lib
+
+
+def _i32(a, name):
+    a = np.ascontiguousarray(a)
+    if a.dtype != np.int32:
+        raise TypeError(f"{name} must be int32")
+    return a
+
+
+def _f32(a, name):
+    a = np.ascontiguousarray(a)
+    if a.dtype != np.float32:
+        raise TypeError(f"{name} must be float32")
+    return a
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _check(rc, what):
+    if rc != 0:
+        reason = {1: "index out of range", 2: "bad size or enum", 3: "out of memory"}.get(rc, "?")
+        raise OracleError(f"{what}: {reason} (code {rc})")
+
+
+def build_csr(src, dst, num_nodes: int):
+    """-> (rowptr[N+1], colidx[E], perm[E], indeg[N]) int32; stable within a row."""
+    src, dst = _i32(src, "src"), _i32(dst, "dst")
+    e = src.shape[0]
+    rowptr = np.empty(num_nodes + 1, np.int32)
+    colidx = np.empty(e, np.int32)
+    perm = np.empty(e, np.int32)
+    indeg = np.empty(num_nodes, np.int32)
+    rc = _load().oracle_build_csr(_p(src), _p(dst), ctypes.c_int64(e), ctypes.c_int32(num_nodes),
+                                  _p(rowptr), _p(colidx), _p(perm), _p(indeg))
+    _check(rc, "build_csr")
+    return rowptr, colidx, perm, indeg
+
+
+def _edge_data(e, num_edges, feat):
+    if e is None:
+        return None, 1
+    e = _f32(e, "e")
+    if e.ndim == 1:
+        e = e.reshape(num_edges, 1)
+    if e.shape[0] != num_edges:
+        raise ValueError("e must have one row per edge")
+    return e, int(e.shape[1])
+
+
+def apply_edges(src, num_nodes: int, x, e=None, msg: int = MSG_COPY_XJ) -> np.ndarray:
+    src, x = _i32(src, "src"), _f32(x, "x")
+    ne, f = src.shape[0], x.shape[1]
+    e, e_dim = _edge_data(e, ne, f)
+    m = np.empty((ne, f), np.float32)
+    rc = _load().oracle_apply_edges(_p(src), ctypes.c_int64(ne), ctypes.c_int32(num_nodes), _p(x),
+                                    ctypes.c_int32(f), _p(e), ctypes.c_int32(e_dim),
+                                    ctypes.c_int32(msg), _p(m))
+    _check(rc, "apply_edges")
+    return m
+
+
+def aggregate_neighbors(dst, num_nodes: int, m, aggr: int = AGGR_SUM, with_sabs: bool = False):
+    dst, m = _i32(dst, "dst"), _f32(m, "m")
+    ne, f = m.shape
+    out = np.empty((num_nodes, f), np.float32)
+    sabs = np.empty((num_nodes, f), np.float64) if with_sabs else None
+    rc = _load().oracle_aggregate_neighbors(_p(dst), ctypes.c_int64(ne), ctypes.c_int32(num_nodes),
+                                            _p(m), ctypes.c_int32(f), ctypes.c_int32(aggr),
+                                            _p(out), _p(sabs))
+    _check(rc, "aggregate_neighbors")
+    return (out, sabs) if with_sabs else out
+
+
+def propagate(src, dst, num_nodes: int, x, e=None, msg: int = MSG_COPY_XJ, aggr: int = AGGR_SUM,
+              with_sabs: bool = False):
+    src, dst, x = _i32(src, "src"), _i32(dst, "dst"), _f32(x, "x")
+    ne, f = src.shape[0], x.shape[1]
+    e, e_dim = _edge_data(e, ne, f)
+    if msg == MSG_E_MUL_XJ and e is None:
+        raise ValueError("e_mul_xj needs edge data")
+    out = np.empty((num_nodes, f), np.float32)
+    sabs = np.empty((num_nodes, f), np.float64) if with_sabs else None
+    rc = _load().oracle_propagate(_p(src), _p(dst), ctypes.c_int64(ne), ctypes.c_int32(num_nodes),
+                                  _p(x), ctypes.c_int32(f), _p(e), ctypes.c_int32(e_dim),
+                                  ctypes.c_int32(msg), ctypes.c_int32(aggr), _p(out), _p(sabs))
+    _check(rc, "propagate")
+    return (out, sabs) if with_sabs else out
+
+
+def gcnconv(src, dst, num_nodes: int, x, w, bias=None, add_self_loops: bool = True,
+            with_sabs: bool = False):
+    src, dst, x, w = _i32(src, "src"), _i32(dst, "dst"), _f32(x, "x"), _f32(w, "w")
+    bias = None if bias is None else _f32(bias, "bias")
+    ne, f_in, f_out = src.shape[0], x.shape[1], w.shape[1]
+    if w.shape[0] != f_in:
+        raise ValueError("w must be [f_in, f_out]")
+    out = np.empty((num_nodes, f_out), np.float32)
+    sabs = np.empty((num_nodes, f_out), np.float64) if with_sabs else None
+    rc = _load().oracle_gcnconv(_p(src), _p(dst), ctypes.c_int64(ne), ctypes.c_int32(num_nodes),
+                                _p(x), ctypes.c_int32(f_in), _p(w), _p(bias), ctypes.c_int32(f_out),
+                                ctypes.c_int32(1 if add_self_loops else 0), _p(out), _p(sabs))
+    _check(rc, "gcnconv")
+    return (out, sabs) if with_sabs else out
+
+
+def segment_softmax(dst, num_nodes: int, scores) -> np.ndarray:
+    dst, s = _i32(dst, "dst"), _f32(scores, "scores")
+    ne = dst.shape[0]
+    s2 = s.reshape(ne, -1)
+    h = s2.shape[1] if ne else (s.shape[1] if s.ndim == 2 else 1)
+    alpha = np.empty_like(s2)
+    rc = _load().oracle_segment_softmax(_p(dst), ctypes.c_int64(ne), ctypes.c_int32(num_nodes),
+                                        _p(s2), ctypes.c_int32(h), _p(alpha))
+    _check(rc, "segment_softmax")
+    return alpha.reshape(s.shape)
+
+
+def gatconv(src, dst, num_nodes: int, x, w, a_src, a_dst, negative_slope: float = 0.2,
+            with_sabs: bool = False):
+    src, dst, x, w = _i32(src, "src"), _i32(dst, "dst"), _f32(x, "x"), _f32(w, "w")
+    a_src, a_dst = _f32(a_src, "a_src"), _f32(a_dst, "a_dst")
+    heads, ch = a_src.shape
+    ne, f_in = src.shape[0], x.shape[1]
+    if w.shape != (f_in, heads * ch) or a_dst.shape != (heads, ch):
+        raise ValueError("shape mismatch")
+    out = np.empty((num_nodes, heads * ch), np.float32)
+    sabs = np.empty((num_nodes, heads * ch), np.float64) if with_sabs else None
+    rc = _load().oracle_gatconv(_p(src), _p(dst), ctypes.c_int64(ne), ctypes.c_int32(num_nodes),
+                                _p(x), ctypes.c_int32(f_in), _p(w), _p(a_src), _p(a_dst),
+                                ctypes.c_int32(heads), ctypes.c_int32(ch),
+                                ctypes.c_float(negative_slope), _p(out), _p(sabs))
+    _check(rc, "gatconv")
+    return (out, sabs) if with_sabs else out
+
+
+def gin_update(src, dst, num_nodes: int, x, eps: float = 0.0, with_sabs: bool = False):
+    src, dst, x = _i32(src, "src"), _i32(dst, "dst"), _f32(x, "x")
+    ne, f = src.shape[0], x.shape[1]
+    out = np.empty((num_nodes, f), np.float32)
+    sabs = np.empty((num_nodes, f), np.float64) if with_sabs else None
+    rc = _load().oracle_gin_update(_p(src), _p(dst), ctypes.c_int64(ne), ctypes.c_int32(num_nodes),
+                                   _p(x), ctypes.c_int32(f), ctypes.c_float(eps), _p(out), _p(sabs))
+    _check(rc, "gin_update")
+    return (out, sabs) if with_sabs else out
+
+
+def graph_pool(graph_indicator, num_graphs: int, x, aggr: int = AGGR_SUM, with_sabs: bool = False):
+    gi, x = _i32(graph_indicator, "graph_indicator"), _f32(x, "x")
+    n, f = x.shape
+    if gi.shape[0] != n:
+        raise ValueError("graph_indicator must have one entry per node")
+    out = np.empty((num_graphs, f), np.float32)
+    sabs = np.empty((num_graphs, f), np.float64) if with_sabs else None
+    rc = _load().oracle_graph_pool(_p(gi), ctypes.c_int32(n), ctypes.c_int32(num_graphs), _p(x),
+                                   ctypes.c_int32(f), ctypes.c_int32(aggr), _p(out), _p(sabs))
+    _check(rc, "graph_pool")
+    return (out, sabs) if with_sabs else out

@@ -1,0 +1,448 @@
+/*
+ * CPU oracle for graph message passing -- TEST INFRASTRUCTURE ONLY.
+ *
+ * Plain, slow, single-threaded C loops over the COO edge list in its given
+ * order, with double accumulators rounded to float once at the end.  It is the
+ * definition the GPU library is checked against and shares no code with it.
+ * Only the test-suite, the smoke check and the benchmark's CPU-baseline leg may
+ * call it; the product never does.
+ *
+ * What is computed follows the paper's description of message passing
+ * (section 3, "Message Passing"): a per-edge message built from the source
+ * node's features x_j and the edge's own data e_(j->i) (apply_edges), followed
+ * by a reduction of the messages over each destination node's neighbourhood
+ * (aggregate_neighbors); propagate is the two combined and must give the same
+ * result.  The paper only names the layers (GCNConv, GAT, GIN, GlobalPool:
+ * section 3, "Graph Convolutional Layers" and "Training Example") and prints no
+ * formulas, so the layer arithmetic below is the textbook definition of each;
+ * every choice the paper leaves open is listed next to the function.
+ *
+ * Conventions: nodes 0..N-1, edges 0..E-1; edge k carries a message from
+ * j = src[k] to i = dst[k] and is reduced at i.  Features are row-major
+ * [N x F] float.  Multi-edges and self-loops count with multiplicity.
+ * A node without incoming edges gets 0 for sum, mean and max alike.
+ * Inputs are finite by contract (behaviour on NaN/Inf: parity unpinned).
+ *
+ * Every function returns 0 on success, 1 for an index out of range,
+ * 2 for a bad size/enum, 3 if memory could not be obtained.
+ *
+ * Optional output `sabs` (may be NULL) receives, per output element, the sum of
+ * the absolute values of the terms that were added up to produce it -- the
+ * condition number the tests scale their floating-point tolerance with.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+enum { MSG_COPY_XJ = 0, MSG_E_MUL_XJ = 1 };
+enum { AGGR_SUM = 0, AGGR_MEAN = 1, AGGR_MAX = 2 };
+
+static int check_edges(const int32_t *src, const int32_t *dst, int64_t E, int32_t N)
+{
+    for (int64_t k = 0; k < E; ++k) {
+        if (src && (src[k] < 0 || src[k] >= N)) return 1;
+        if (dst && (dst[k] < 0 || dst[k] >= N)) return 1;
+    }
+    return 0;
+}
+
+/* IEEE-754 "maximum" on finite floats: the larger value; +0 beats -0. */
+static float max_f32(float a, float b)
+{
+    if (a > b) return a;
+    if (b > a) return b;
+    uint32_t ua, ub;
+    memcpy(&ua, &a, 4);
+    memcpy(&ub, &b, 4);
+    ua &= ub;                       /* equal values: only the zero pair differs in encoding */
+    memcpy(&a, &ua, 4);
+    return a;
+}
+
+/* The product of an edge datum and a feature, rounded to float as one operation. */
+static float mul_f32(float a, float b)
+{
+    volatile float p = a * b;
+    return p;
+}
+
+/*
+ * COO -> CSR by destination (the sparse form of the same topology; section 3,
+ * "Graph Data Structures").  Counting sort: rows list their edges in increasing
+ * original edge index, so perm/colidx are unique even with duplicate edges.
+ *   rowptr[N+1], colidx[E] = src[perm[p]], perm[E], indeg[N].
+ */
+int oracle_build_csr(const int32_t *src, const int32_t *dst, int64_t E, int32_t N,
+                     int32_t *rowptr, int32_t *colidx, int32_t *perm, int32_t *indeg)
+{
+    if (N <= 0 || E < 0) return 2;
+    if (check_edges(src, dst, E, N)) return 1;
+    for (int32_t i = 0; i < N; ++i) indeg[i] = 0;
+    for (int64_t k = 0; k < E; ++k) indeg[dst[k]]++;
+    rowptr[0] = 0;
+    for (int32_t i = 0; i < N; ++i) rowptr[i + 1] = rowptr[i] + indeg[i];
+    int32_t *cursor = (int32_t *)malloc((size_t)N * sizeof(int32_t));
+    if (!cursor) return 3;
+    for (int32_t i = 0; i < N; ++i) cursor[i] = rowptr[i];
+    for (int64_t k = 0; k < E; ++k) {
+        int32_t p = cursor[dst[k]]++;
+        colidx[p] = src[k];
+        perm[p] = (int32_t)k;
+    }
+    free(cursor);
+    return 0;
+}
+
+/*
+ * apply_edges: one message row per edge.
+ *   copy_xj : m[k,f] = x[src[k], f]
+ *   e_mul_xj: m[k,f] = float(e[k, f or 0] * x[src[k], f])   (e_dim = F or 1)
+ */
+int oracle_apply_edges(const int32_t *src, int64_t E, int32_t N, const float *x, int32_t F,
+                       const float *e, int32_t e_dim, int32_t msg, float *m)
+{
+    if (N <= 0 || E < 0 || F <= 0) return 2;
+    if (msg != MSG_COPY_XJ && msg != MSG_E_MUL_XJ) return 2;
+    if (msg == MSG_E_MUL_XJ && e_dim != 1 && e_dim != F) return 2;
+    if (check_edges(src, NULL, E, N)) return 1;
+    for (int64_t k = 0; k < E; ++k) {
+        const float *xj = x + (int64_t)src[k] * F;
+        for (int32_t f = 0; f < F; ++f) {
+            float v = xj[f];
+            if (msg == MSG_E_MUL_XJ) v = mul_f32(e[k * e_dim + (e_dim == 1 ? 0 : f)], v);
+            m[k * F + f] = v;
+        }
+    }
+    return 0;
+}
+
+/* Shared finishing step of a neighbourhood reduction held in double. */
+static void finish_rows(int32_t N, int32_t F, int32_t aggr, const double *acc, const int64_t *cnt,
+                        double *sabs_acc, float *out, double *sabs)
+{
+    for (int32_t i = 0; i < N; ++i)
+        for (int32_t f = 0; f < F; ++f) {
+            int64_t q = (int64_t)i * F + f;
+            double v = 0.0, s = sabs_acc ? sabs_acc[q] : 0.0;
+            if (cnt[i] > 0) {
+                v = acc[q];
+                if (aggr == AGGR_MEAN) { v /= (double)cnt[i]; s /= (double)cnt[i]; }
+            }
+            out[q] = (float)v;
+            if (sabs) sabs[q] = (cnt[i] > 0) ? s : 0.0;
+        }
+}
+
+/*
+ * aggregate_neighbors: reduce the message rows m[E x F] onto their destinations.
+ * mean divides by the number of incoming edges (not by any sum of weights).
+ */
+int oracle_aggregate_neighbors(const int32_t *dst, int64_t E, int32_t N, const float *m, int32_t F,
+                               int32_t aggr, float *out, double *sabs)
+{
+    if (N <= 0 || E < 0 || F <= 0) return 2;
+    if (aggr < AGGR_SUM || aggr > AGGR_MAX) return 2;
+    if (check_edges(NULL, dst, E, N)) return 1;
+    size_t nf = (size_t)N * F;
+    double *acc = (double *)calloc(nf, sizeof(double));
+    double *sa = (double *)calloc(nf, sizeof(double));
+    int64_t *cnt = (int64_t *)calloc((size_t)N, sizeof(int64_t));
+    if (!acc || !sa || !cnt) { free(acc); free(sa); free(cnt); return 3; }
+    for (int64_t k = 0; k < E; ++k) {
+        int64_t i = dst[k];
+        for (int32_t f = 0; f < F; ++f) {
+            float v = m[k * F + f];
+            int64_t q = i * F + f;
+            if (aggr == AGGR_MAX) {
+                acc[q] = (cnt[i] == 0) ? (double)v : (double)max_f32((float)acc[q], v);
+                sa[q] = fabs(acc[q]);
+            } else {
+                acc[q] += (double)v;
+                sa[q] += fabs((double)v);
+            }
+        }
+        cnt[i]++;
+    }
+    finish_rows(N, F, aggr, acc, cnt, sa, out, sabs);
+    free(acc); free(sa); free(cnt);
+    return 0;
+}
+
+/*
+ * propagate = apply_edges then aggregate_neighbors, without storing the
+ * [E x F] messages (same values, same order of edges).
+ */
+int oracle_propagate(const int32_t *src, const int32_t *dst, int64_t E, int32_t N,
+                     const float *x, int32_t F, const float *e, int32_t e_dim,
+                     int32_t msg, int32_t aggr, float *out, double *sabs)
+{
+    if (N <= 0 || E < 0 || F <= 0) return 2;
+    if (msg != MSG_COPY_XJ && msg != MSG_E_MUL_XJ) return 2;
+    if (aggr < AGGR_SUM || aggr > AGGR_MAX) return 2;
+    if (msg == MSG_E_MUL_XJ && e_dim != 1 && e_dim != F) return 2;
+    if (check_edges(src, dst, E, N)) return 1;
+    size_t nf = (size_t)N * F;
+    double *acc = (double *)calloc(nf, sizeof(double));
+    double *sa = (double *)calloc(nf, sizeof(double));
+    int64_t *cnt = (int64_t *)calloc((size_t)N, sizeof(int64_t));
+    if (!acc || !sa || !cnt) { free(acc); free(sa); free(cnt); return 3; }
+    for (int64_t k = 0; k < E; ++k) {
+        int64_t i = dst[k];
+        const float *xj = x + (int64_t)src[k] * F;
+        for (int32_t f = 0; f < F; ++f) {
+            float v = xj[f];
+            if (msg == MSG_E_MUL_XJ) v = mul_f32(e[k * e_dim + (e_dim == 1 ? 0 : f)], v);
+            int64_t q = i * F + f;
+            if (aggr == AGGR_MAX) {
+                acc[q] = (cnt[i] == 0) ? (double)v : (double)max_f32((float)acc[q], v);
+                sa[q] = fabs(acc[q]);
+            } else {
+                acc[q] += (double)v;
+                sa[q] += fabs((double)v);
+            }
+        }
+        cnt[i]++;
+    }
+    finish_rows(N, F, aggr, acc, cnt, sa, out, sabs);
+    free(acc); free(sa); free(cnt);
+    return 0;
+}
+
+/* Z = X W and Zabs = |X| |W| in double, [N x f_out]. */
+static int dense_xw(const float *x, int32_t N, int32_t f_in, const float *w, int32_t f_out,
+                    double **z_out, double **zabs_out)
+{
+    double *z = (double *)calloc((size_t)N * f_out, sizeof(double));
+    double *za = (double *)calloc((size_t)N * f_out, sizeof(double));
+    if (!z || !za) { free(z); free(za); return 3; }
+    for (int32_t i = 0; i < N; ++i)
+        for (int32_t k = 0; k < f_in; ++k) {
+            double xv = (double)x[(int64_t)i * f_in + k];
+            for (int32_t o = 0; o < f_out; ++o) {
+                double t = xv * (double)w[(int64_t)k * f_out + o];
+                z[(int64_t)i * f_out + o] += t;
+                za[(int64_t)i * f_out + o] += fabs(t);
+            }
+        }
+    *z_out = z;
+    *zabs_out = za;
+    return 0;
+}
+
+/*
+ * GCNConv forward: out = D^-1/2 (A [+ I]) D^-1/2 X W + b.
+ * Choices the paper leaves open: d_i is the in-degree of i in the edge list
+ * (after one self-loop per node has been appended when add_self_loops != 0, with
+ * no de-duplication) and is used for both endpoints, so an edge j->i carries the
+ * coefficient 1/sqrt(d_i d_j); a node with d = 0 (possible only without
+ * self-loops) contributes the coefficient 0; bias is added last; no activation.
+ * sabs = sum over edges of coefficient * (|X||W|)[j] + |b|.
+ */
+int oracle_gcnconv(const int32_t *src, const int32_t *dst, int64_t E, int32_t N,
+                   const float *x, int32_t f_in, const float *w, const float *bias, int32_t f_out,
+                   int32_t add_self_loops, float *out, double *sabs)
+{
+    if (N <= 0 || E < 0 || f_in <= 0 || f_out <= 0) return 2;
+    if (check_edges(src, dst, E, N)) return 1;
+    int64_t E2 = E + (add_self_loops ? N : 0);
+    int32_t *s2 = (int32_t *)malloc((size_t)(E2 > 0 ? E2 : 1) * sizeof(int32_t));
+    int32_t *d2 = (int32_t *)malloc((size_t)(E2 > 0 ? E2 : 1) * sizeof(int32_t));
+    double *deg = (double *)calloc((size_t)N, sizeof(double));
+    double *acc = (double *)calloc((size_t)N * f_out, sizeof(double));
+    double *sa = (double *)calloc((size_t)N * f_out, sizeof(double));
+    double *z = NULL, *za = NULL;
+    int rc = 3;
+    if (!s2 || !d2 || !deg || !acc || !sa) goto done;
+    for (int64_t k = 0; k < E; ++k) { s2[k] = src[k]; d2[k] = dst[k]; }
+    if (add_self_loops)
+        for (int32_t i = 0; i < N; ++i) { s2[E + i] = i; d2[E + i] = i; }
+    for (int64_t k = 0; k < E2; ++k) deg[d2[k]] += 1.0;
+    if (dense_xw(x, N, f_in, w, f_out, &z, &za)) goto done;
+    for (int64_t k = 0; k < E2; ++k) {
+        int64_t i = d2[k], j = s2[k];
+        double dd = deg[i] * deg[j];
+        double c = dd > 0.0 ? 1.0 / sqrt(dd) : 0.0;
+        for (int32_t o = 0; o < f_out; ++o) {
+            acc[i * f_out + o] += c * z[j * f_out + o];
+            sa[i * f_out + o] += c * za[j * f_out + o];
+        }
+    }
+    for (int32_t i = 0; i < N; ++i)
+        for (int32_t o = 0; o < f_out; ++o) {
+            double b = bias ? (double)bias[o] : 0.0;
+            out[(int64_t)i * f_out + o] = (float)(acc[(int64_t)i * f_out + o] + b);
+            if (sabs) sabs[(int64_t)i * f_out + o] = sa[(int64_t)i * f_out + o] + fabs(b);
+        }
+    rc = 0;
+done:
+    free(s2); free(d2); free(deg); free(acc); free(sa); free(z); free(za);
+    return rc;
+}
+
+/*
+ * Segment softmax over each destination's incoming edges, per head:
+ *   alpha[k,h] = exp(s[k,h] - mx[i,h]) / sum_{q: dst[q]=i} exp(s[q,h] - mx[i,h]),  i = dst[k],
+ * with mx the segment maximum (so the denominator is >= 1 and needs no epsilon).
+ * Input and output are [E x H] in the caller's edge order.
+ */
+int oracle_segment_softmax(const int32_t *dst, int64_t E, int32_t N, const float *s, int32_t H,
+                           float *alpha)
+{
+    if (N <= 0 || E < 0 || H <= 0) return 2;
+    if (check_edges(NULL, dst, E, N)) return 1;
+    size_t nh = (size_t)N * H;
+    double *mx = (double *)malloc(nh * sizeof(double));
+    double *den = (double *)calloc(nh, sizeof(double));
+    if (!mx || !den) { free(mx); free(den); return 3; }
+    for (size_t q = 0; q < nh; ++q) mx[q] = -INFINITY;
+    for (int64_t k = 0; k < E; ++k)
+        for (int32_t h = 0; h < H; ++h) {
+            double v = (double)s[k * H + h];
+            if (v > mx[(int64_t)dst[k] * H + h]) mx[(int64_t)dst[k] * H + h] = v;
+        }
+    for (int64_t k = 0; k < E; ++k)
+        for (int32_t h = 0; h < H; ++h)
+            den[(int64_t)dst[k] * H + h] += exp((double)s[k * H + h] - mx[(int64_t)dst[k] * H + h]);
+    for (int64_t k = 0; k < E; ++k)
+        for (int32_t h = 0; h < H; ++h) {
+            int64_t q = (int64_t)dst[k] * H + h;
+            alpha[k * H + h] = (float)(exp((double)s[k * H + h] - mx[q]) / den[q]);
+        }
+    free(mx); free(den);
+    return 0;
+}
+
+/*
+ * GAT-style attention layer (multi-head, heads concatenated, no bias, no
+ * activation, self-loops only if the edge list holds them):
+ *   h = float(X W)                      [N x heads*ch], rounded once (a stored tensor)
+ *   sl[j,hd] = sum_c a_src[hd,c] h[j,hd,c],  sr[i,hd] = sum_c a_dst[hd,c] h[i,hd,c]
+ *   s[k,hd]  = lrelu(sl[src[k],hd] + sr[dst[k],hd]),  lrelu(v) = v > 0 ? v : slope * v
+ *   alpha    = segment softmax of s over each destination
+ *   out[i,hd,:] = sum_{k: dst[k]=i} alpha[k,hd] * h[src[k],hd,:]
+ * sabs = sum_k alpha[k,hd] * (|X||W|)[src[k]].
+ */
+int oracle_gatconv(const int32_t *src, const int32_t *dst, int64_t E, int32_t N,
+                   const float *x, int32_t f_in, const float *w,
+                   const float *a_src, const float *a_dst, int32_t heads, int32_t ch,
+                   float negative_slope, float *out, double *sabs)
+{
+    if (N <= 0 || E < 0 || f_in <= 0 || heads <= 0 || ch <= 0) return 2;
+    if (check_edges(src, dst, E, N)) return 1;
+    int32_t fo = heads * ch;
+    size_t nh = (size_t)N * heads;
+    double *z = NULL, *za = NULL;
+    double *sl = (double *)calloc(nh, sizeof(double));
+    double *sr = (double *)calloc(nh, sizeof(double));
+    double *mx = (double *)malloc(nh * sizeof(double));
+    double *den = (double *)calloc(nh, sizeof(double));
+    double *acc = (double *)calloc((size_t)N * fo, sizeof(double));
+    double *sa = (double *)calloc((size_t)N * fo, sizeof(double));
+    int rc = 3;
+    if (!sl || !sr || !mx || !den || !acc || !sa) goto done;
+    if (dense_xw(x, N, f_in, w, fo, &z, &za)) goto done;
+    for (size_t q = 0; q < (size_t)N * fo; ++q) z[q] = (double)(float)z[q];
+    for (int32_t i = 0; i < N; ++i)
+        for (int32_t hd = 0; hd < heads; ++hd)
+            for (int32_t c = 0; c < ch; ++c) {
+                double hv = z[(int64_t)i * fo + hd * ch + c];
+                sl[(int64_t)i * heads + hd] += (double)a_src[hd * ch + c] * hv;
+                sr[(int64_t)i * heads + hd] += (double)a_dst[hd * ch + c] * hv;
+            }
+    double slope = (double)negative_slope;
+#define SCORE(k, hd, v) do { (v) = sl[(int64_t)src[k] * heads + (hd)] + sr[(int64_t)dst[k] * heads + (hd)]; \
+                             if (!((v) > 0.0)) (v) *= slope; } while (0)
+    for (size_t q = 0; q < nh; ++q) mx[q] = -INFINITY;
+    for (int64_t k = 0; k < E; ++k)
+        for (int32_t hd = 0; hd < heads; ++hd) {
+            double v; SCORE(k, hd, v);
+            if (v > mx[(int64_t)dst[k] * heads + hd]) mx[(int64_t)dst[k] * heads + hd] = v;
+        }
+    for (int64_t k = 0; k < E; ++k)
+        for (int32_t hd = 0; hd < heads; ++hd) {
+            double v; SCORE(k, hd, v);
+            den[(int64_t)dst[k] * heads + hd] += exp(v - mx[(int64_t)dst[k] * heads + hd]);
+        }
+    for (int64_t k = 0; k < E; ++k)
+        for (int32_t hd = 0; hd < heads; ++hd) {
+            double v; SCORE(k, hd, v);
+            int64_t q = (int64_t)dst[k] * heads + hd;
+            double alpha = exp(v - mx[q]) / den[q];
+            for (int32_t c = 0; c < ch; ++c) {
+                acc[(int64_t)dst[k] * fo + hd * ch + c] += alpha * z[(int64_t)src[k] * fo + hd * ch + c];
+                sa[(int64_t)dst[k] * fo + hd * ch + c] += alpha * za[(int64_t)src[k] * fo + hd * ch + c];
+            }
+        }
+#undef SCORE
+    for (size_t q = 0; q < (size_t)N * fo; ++q) {
+        out[q] = (float)acc[q];
+        if (sabs) sabs[q] = sa[q];
+    }
+    rc = 0;
+done:
+    free(z); free(za); free(sl); free(sr); free(mx); free(den); free(acc); free(sa);
+    return rc;
+}
+
+/*
+ * GIN-style node update without the MLP:  out[i,:] = (1 + eps) x[i,:] + sum_{j->i} x[j,:].
+ */
+int oracle_gin_update(const int32_t *src, const int32_t *dst, int64_t E, int32_t N,
+                      const float *x, int32_t F, float eps, float *out, double *sabs)
+{
+    if (N <= 0 || E < 0 || F <= 0) return 2;
+    if (check_edges(src, dst, E, N)) return 1;
+    size_t nf = (size_t)N * F;
+    double *acc = (double *)calloc(nf, sizeof(double));
+    double *sa = (double *)calloc(nf, sizeof(double));
+    if (!acc || !sa) { free(acc); free(sa); return 3; }
+    double scale = 1.0 + (double)eps;
+    for (size_t q = 0; q < nf; ++q) { acc[q] = scale * (double)x[q]; sa[q] = fabs(acc[q]); }
+    for (int64_t k = 0; k < E; ++k)
+        for (int32_t f = 0; f < F; ++f) {
+            double v = (double)x[(int64_t)src[k] * F + f];
+            acc[(int64_t)dst[k] * F + f] += v;
+            sa[(int64_t)dst[k] * F + f] += fabs(v);
+        }
+    for (size_t q = 0; q < nf; ++q) { out[q] = (float)acc[q]; if (sabs) sabs[q] = sa[q]; }
+    free(acc); free(sa);
+    return 0;
+}
+
+/*
+ * Graph-level readout of a batch of graphs:  pooled[g,:] = AGG_{i: gi[i]=g} x[i,:]
+ * (sum, mean over the graph's node count, or max); a graph without nodes gives 0.
+ * gi must lie in [0, G); it is what batching produces, one graph id per node.
+ */
+int oracle_graph_pool(const int32_t *gi, int32_t N, int32_t G, const float *x, int32_t F,
+                      int32_t aggr, float *out, double *sabs)
+{
+    if (N < 0 || G <= 0 || F <= 0) return 2;
+    if (aggr < AGGR_SUM || aggr > AGGR_MAX) return 2;
+    for (int32_t i = 0; i < N; ++i)
+        if (gi[i] < 0 || gi[i] >= G) return 1;
+    size_t gf = (size_t)G * F;
+    double *acc = (double *)calloc(gf, sizeof(double));
+    double *sa = (double *)calloc(gf, sizeof(double));
+    int64_t *cnt = (int64_t *)calloc((size_t)G, sizeof(int64_t));
+    if (!acc || !sa || !cnt) { free(acc); free(sa); free(cnt); return 3; }
+    for (int32_t i = 0; i < N; ++i) {
+        int64_t g = gi[i];
+        for (int32_t f = 0; f < F; ++f) {
+            float v = x[(int64_t)i * F + f];
+            int64_t q = g * F + f;
+            if (aggr == AGGR_MAX) {
+                acc[q] = (cnt[g] == 0) ? (double)v : (double)max_f32((float)acc[q], v);
+                sa[q] = fabs(acc[q]);
+            } else {
+                acc[q] += (double)v;
+                sa[q] += fabs((double)v);
+            }
+        }
+        cnt[g]++;
+    }
+    finish_rows(G, F, aggr, acc, cnt, sa, out, sabs);
+    free(acc); free(sa); free(cnt);
+    return 0;
+}

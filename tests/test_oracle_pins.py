@@ -1,0 +1,364 @@
+"""Pins of the CPU oracle against things other than itself (CPU only).
+
+The paper prints no numeric example, so each pin is a hand-worked tiny graph
+(tests/golden), an invariant, a reduction to a library routine (dense matmul,
+stable argsort, plain softmax) or brute force on graphs of at most 64 nodes.
+"""
+import numpy as np
+import pytest
+
+import oracle
+from oracle import (AGGR_MAX, AGGR_MEAN, AGGR_SUM, MSG_COPY_XJ, MSG_E_MUL_XJ)
+from paper_2412_06354_amd import synth
+from util import dense_adjacency, incoming, load_golden
+
+AGGRS = {"sum": AGGR_SUM, "mean": AGGR_MEAN, "max": AGGR_MAX}
+
+
+def rng_graph(seed, n, e, star=False):
+    """Seeded random multigraph with self-loops, duplicates and isolated nodes."""
+    src, dst = synth.multigraph_uniform(n, e, seed)
+    if star:  # hub 0 receives an edge from every other node
+        src = np.concatenate([src, np.arange(1, n, dtype=np.int32)])
+        dst = np.concatenate([dst, np.zeros(n - 1, dtype=np.int32)])
+    # make a few nodes isolated on the incoming side
+    keep = dst % 7 != 3
+    return src[keep], dst[keep]
+
+
+# ----------------------------------------------------------------------------- hand-worked
+
+def test_g5_csr(golden_dir):
+    g = load_golden(golden_dir, "g5_propagate.json")
+    src, dst = np.array(g["src"], np.int32), np.array(g["dst"], np.int32)
+    rowptr, colidx, perm, indeg = oracle.build_csr(src, dst, g["num_nodes"])
+    assert rowptr.tolist() == g["rowptr"]
+    assert colidx.tolist() == g["colidx"]
+    assert perm.tolist() == g["perm"]
+    assert indeg.tolist() == g["indeg"]
+
+
+@pytest.mark.parametrize("msg_name", ["copy_xj", "e_mul_xj"])
+@pytest.mark.parametrize("aggr_name", ["sum", "mean", "max"])
+def test_g5_propagate(golden_dir, msg_name, aggr_name):
+    g = load_golden(golden_dir, "g5_propagate.json")
+    src, dst = np.array(g["src"], np.int32), np.array(g["dst"], np.int32)
+    x = np.array(g["x"], np.float32)
+    w = np.array(g["w"], np.float32)
+    msg = MSG_COPY_XJ if msg_name == "copy_xj" else MSG_E_MUL_XJ
+    out = oracle.propagate(src, dst, g["num_nodes"], x, w if msg else None, msg, AGGRS[aggr_name])
+    want = np.array(g[msg_name][aggr_name], np.float64).astype(np.float32)
+    np.testing.assert_array_equal(out, want)
+
+
+def test_g5_gin(golden_dir):
+    g = load_golden(golden_dir, "g5_propagate.json")
+    src, dst = np.array(g["src"], np.int32), np.array(g["dst"], np.int32)
+    x = np.array(g["x"], np.float32)
+    np.testing.assert_array_equal(oracle.gin_update(src, dst, 4, x, 0.0), np.array(g["gin_eps0"], np.float32))
+    np.testing.assert_array_equal(oracle.gin_update(src, dst, 4, x, 0.5), np.array(g["gin_eps_half"], np.float32))
+
+
+def test_g5_softmax(golden_dir):
+    g = load_golden(golden_dir, "g5_softmax.json")
+    dst = np.array(g["dst"], np.int32)
+    s = np.array(g["scores"], np.float32).reshape(-1, 1)
+    alpha = oracle.segment_softmax(dst, g["num_nodes"], s)
+    np.testing.assert_allclose(alpha[:, 0], g["alpha"], rtol=3e-7)
+    assert alpha[0, 0] == 1.0 and alpha[4, 0] == 1.0
+    # shift invariance per destination, no overflow for huge scores
+    s2 = s.copy()
+    s2[1:4] += 1000.0
+    alpha2 = oracle.segment_softmax(dst, g["num_nodes"], s2)
+    np.testing.assert_allclose(alpha2[:, 0], g["alpha"], rtol=2e-4)  # fp32 input rounding of ln 2 + 1000
+    assert np.isfinite(alpha2).all()
+
+
+def test_path3_gcn(golden_dir):
+    g = load_golden(golden_dir, "path3_gcn.json")
+    src, dst = np.array(g["src"], np.int32), np.array(g["dst"], np.int32)
+    x = np.array(g["x"], np.float32)
+    out = oracle.gcnconv(src, dst, 3, x, np.array(g["w"], np.float32), None, True)
+    np.testing.assert_allclose(out, np.array(g["out"]), rtol=1e-7)
+    out2 = oracle.gcnconv(src, dst, 3, x, np.array(g["w2"], np.float32), np.array(g["bias2"], np.float32), True)
+    np.testing.assert_allclose(out2, np.array(g["out2"]), rtol=1e-7)
+
+
+# ----------------------------------------------------------------------------- library routines
+
+@pytest.mark.parametrize("seed,n,e", [(1, 1, 5), (2, 7, 0), (3, 64, 700), (4, 1000, 20000)])
+def test_csr_is_stable_sort(seed, n, e):
+    src, dst = synth.multigraph_uniform(n, e, seed)
+    rowptr, colidx, perm, indeg = oracle.build_csr(src, dst, n)
+    order = np.argsort(dst, kind="stable")
+    np.testing.assert_array_equal(perm, order.astype(np.int32))
+    np.testing.assert_array_equal(colidx, src[order])
+    np.testing.assert_array_equal(indeg, np.bincount(dst, minlength=n))
+    np.testing.assert_array_equal(rowptr, np.searchsorted(dst[order], np.arange(n + 1)))
+
+
+def test_csr_equals_dense_adjacency():
+    src, dst = rng_graph(11, 40, 300, star=True)
+    rowptr, colidx, _, _ = oracle.build_csr(src, dst, 40)
+    a = np.zeros((40, 40))
+    for i in range(40):
+        for p in range(rowptr[i], rowptr[i + 1]):
+            a[i, colidx[p]] += 1
+    np.testing.assert_array_equal(a, dense_adjacency(src, dst, 40))
+
+
+@pytest.mark.parametrize("seed,n,e,f", [(21, 64, 900, 5), (22, 33, 100, 8), (23, 64, 64, 3)])
+def test_propagate_is_dense_matmul(seed, n, e, f):
+    src, dst = rng_graph(seed, n, e, star=True)
+    ne = src.shape[0]
+    x = synth.normal_f32(seed, 2, n * f).reshape(n, f)
+    w = synth.uniform_f32(seed, 3, ne, -1.0, 1.0)
+    a = dense_adjacency(src, dst, n)
+    deg = a.sum(1, keepdims=True)
+    xs = x.astype(np.float64)
+    # copy_xj + sum = (multiplicity adjacency) @ X ; mean = D^-1 A X
+    np.testing.assert_allclose(oracle.propagate(src, dst, n, x), (a @ xs).astype(np.float32), rtol=0, atol=0)
+    mean_ref = np.where(deg > 0, (a @ xs) / np.maximum(deg, 1), 0.0)
+    np.testing.assert_allclose(oracle.propagate(src, dst, n, x, None, MSG_COPY_XJ, AGGR_MEAN),
+                               mean_ref.astype(np.float32), rtol=1e-7, atol=1e-7)
+    # e_mul_xj + sum = (weighted adjacency) @ X, up to the float rounding of each product
+    aw = dense_adjacency(src, dst, n, w)
+    got = oracle.propagate(src, dst, n, x, w, MSG_E_MUL_XJ, AGGR_SUM)
+    np.testing.assert_allclose(got, aw @ xs, rtol=0, atol=1e-6 * (np.abs(aw) @ np.abs(xs)).max())
+    # mean divides by the edge count, not by the weight sum
+    got = oracle.propagate(src, dst, n, x, w, MSG_E_MUL_XJ, AGGR_MEAN)
+    ref = np.where(deg > 0, (aw @ xs) / np.maximum(deg, 1), 0.0)
+    np.testing.assert_allclose(got, ref, rtol=0, atol=1e-6 * (np.abs(aw) @ np.abs(xs)).max())
+
+
+@pytest.mark.parametrize("seed,n,e,f", [(31, 64, 500, 4), (32, 20, 30, 6)])
+def test_propagate_max_brute_force(seed, n, e, f):
+    src, dst = rng_graph(seed, n, e, star=True)
+    ne = src.shape[0]
+    x = synth.normal_f32(seed, 2, n * f).reshape(n, f)
+    w = synth.uniform_f32(seed, 3, ne, -1.0, 1.0)
+    inc = incoming(dst, n)
+    for msg, e_arg in ((MSG_COPY_XJ, None), (MSG_E_MUL_XJ, w)):
+        got = oracle.propagate(src, dst, n, x, e_arg, msg, AGGR_MAX)
+        for i in range(n):
+            if inc[i].size == 0:
+                assert (got[i] == 0).all()
+                continue
+            rows = x[src[inc[i]]]
+            if msg == MSG_E_MUL_XJ:
+                rows = (w[inc[i]][:, None] * rows).astype(np.float32)   # float32 products
+            np.testing.assert_array_equal(got[i], rows.max(0))
+
+
+def test_max_of_signed_zeros_is_plus_zero():
+    src = np.array([0, 1, 1, 0], np.int32)
+    dst = np.array([2, 2, 3, 3], np.int32)
+    x = np.array([[-0.0], [0.0], [5.0], [5.0]], np.float32)
+    out = oracle.propagate(src, dst, 4, x, None, MSG_COPY_XJ, AGGR_MAX)
+    assert not np.signbit(out[2, 0]) and not np.signbit(out[3, 0])
+    x2 = np.array([[-0.0], [-0.0], [5.0], [5.0]], np.float32)
+    out2 = oracle.propagate(src, dst, 4, x2, None, MSG_COPY_XJ, AGGR_MAX)
+    assert np.signbit(out2[2, 0])   # all messages are -0 -> -0
+
+
+def test_elementwise_edge_features():
+    n, f = 30, 6
+    src, dst = rng_graph(41, n, 200)
+    ne = src.shape[0]
+    x = synth.normal_f32(41, 2, n * f).reshape(n, f)
+    ef = synth.normal_f32(41, 3, ne * f).reshape(ne, f)
+    got = oracle.propagate(src, dst, n, x, ef, MSG_E_MUL_XJ, AGGR_SUM)
+    ref = np.zeros((n, f))
+    for k in range(ne):
+        ref[dst[k]] += (ef[k] * x[src[k]]).astype(np.float64)
+    np.testing.assert_allclose(got, ref, rtol=0, atol=2e-6 * np.abs(ref).max())
+
+
+def test_two_step_equals_fused():
+    n, f = 50, 7
+    src, dst = rng_graph(51, n, 600, star=True)
+    ne = src.shape[0]
+    x = synth.normal_f32(51, 2, n * f).reshape(n, f)
+    w = synth.uniform_f32(51, 3, ne)
+    for msg, e_arg in ((MSG_COPY_XJ, None), (MSG_E_MUL_XJ, w)):
+        m = oracle.apply_edges(src, n, x, e_arg, msg)
+        assert m.shape == (ne, f)
+        if msg == MSG_COPY_XJ:
+            np.testing.assert_array_equal(m, x[src])          # gather
+        else:
+            np.testing.assert_array_equal(m, w[:, None] * x[src])
+        for aggr in (AGGR_SUM, AGGR_MEAN, AGGR_MAX):
+            two = oracle.aggregate_neighbors(dst, n, m, aggr)
+            one = oracle.propagate(src, dst, n, x, e_arg, msg, aggr)
+            np.testing.assert_array_equal(one, two)
+
+
+# ----------------------------------------------------------------------------- invariants
+
+def test_invariants_small_powerlaw():
+    wl = synth.config2_weighted(num_nodes=3000, num_edges=40000, feat=8, cap=400.0)
+    n, src, dst = wl.num_nodes, wl.src, wl.dst
+    rowptr, _, _, indeg = oracle.build_csr(src, dst, n)
+    ones = np.ones((n, 8), np.float32)
+    s = oracle.propagate(src, dst, n, ones)
+    np.testing.assert_array_equal(s[:, 0], indeg.astype(np.float32))         # sum of ones = in-degree
+    np.testing.assert_array_equal(s[:, 0], np.diff(rowptr).astype(np.float32))
+    c = np.full((n, 8), 2.5, np.float32)
+    has = np.repeat((indeg > 0)[:, None], 8, axis=1)
+    np.testing.assert_array_equal(oracle.propagate(src, dst, n, c, None, MSG_COPY_XJ, AGGR_MEAN), np.where(has, 2.5, 0).astype(np.float32))
+    np.testing.assert_array_equal(oracle.propagate(src, dst, n, c, None, MSG_COPY_XJ, AGGR_MAX), np.where(has, 2.5, 0).astype(np.float32))
+    # unit weights: e_mul_xj == copy_xj bit for bit
+    w1 = np.ones(wl.num_edges, np.float32)
+    for aggr in (AGGR_SUM, AGGR_MEAN, AGGR_MAX):
+        np.testing.assert_array_equal(oracle.propagate(src, dst, n, wl.x, w1, MSG_E_MUL_XJ, aggr),
+                                      oracle.propagate(src, dst, n, wl.x, None, MSG_COPY_XJ, aggr))
+    # GIN of ones = 1 + in-degree
+    np.testing.assert_array_equal(oracle.gin_update(src, dst, n, ones, 0.0)[:, 0], 1.0 + indeg)
+    # sabs of a non-negative input equals the sum itself
+    out, sabs = oracle.propagate(src, dst, n, np.abs(wl.x), None, MSG_COPY_XJ, AGGR_SUM, with_sabs=True)
+    np.testing.assert_allclose(out, sabs, rtol=1e-6)
+
+
+def test_gcn_sqrt_degree_is_fixed_point():
+    wl = synth.config1_gcn(num_nodes=500, pairs=2000, f_in=4, f_out=4)
+    n = wl.num_nodes
+    d = np.bincount(wl.dst, minlength=n) + 1.0
+    x = np.sqrt(d).astype(np.float32).reshape(n, 1)
+    out = oracle.gcnconv(wl.src, wl.dst, n, x, np.ones((1, 1), np.float32), None, True)
+    np.testing.assert_allclose(out, x, rtol=3e-7)
+
+
+def test_gcn_regular_graph_rows_sum_to_one():
+    n = 12  # ring: every node has in-degree 2 (+1 self-loop) -> each row of the operator sums to 1
+    i = np.arange(n, dtype=np.int32)
+    src = np.concatenate([i, (i + 1) % n]).astype(np.int32)
+    dst = np.concatenate([(i + 1) % n, i]).astype(np.int32)
+    x = np.full((n, 3), 7.0, np.float32)
+    out = oracle.gcnconv(src, dst, n, x, np.eye(3, dtype=np.float32), None, True)
+    np.testing.assert_allclose(out, x, rtol=3e-7)
+
+
+@pytest.mark.parametrize("loops", [True, False])
+def test_gcn_is_dense_operator(loops):
+    n, f_in, f_out = 48, 5, 3
+    src, dst = rng_graph(61, n, 400, star=True)
+    x = synth.normal_f32(61, 2, n * f_in).reshape(n, f_in)
+    w = synth.glorot_uniform(61, 4, f_in, f_out, (f_in, f_out))
+    b = synth.uniform_f32(61, 5, f_out, -1, 1)
+    a = dense_adjacency(src, dst, n) + (np.eye(n) if loops else 0.0)
+    d = a.sum(1)
+    dinv = np.where(d > 0, 1.0 / np.sqrt(np.maximum(d, 1e-300)), 0.0)
+    ref = (dinv[:, None] * a * dinv[None, :]) @ (x.astype(np.float64) @ w.astype(np.float64)) + b
+    got = oracle.gcnconv(src, dst, n, x, w, b, loops)
+    np.testing.assert_allclose(got, ref, rtol=0, atol=2e-7 * np.abs(ref).max())
+
+
+def test_gcn_equals_unfused_weighted_propagate():
+    wl = synth.config1_gcn(num_nodes=800, pairs=3000, f_in=6, f_out=5)
+    n = wl.num_nodes
+    loops = np.arange(n, dtype=np.int32)
+    s2, d2 = np.concatenate([wl.src, loops]), np.concatenate([wl.dst, loops])
+    deg = np.bincount(d2, minlength=n).astype(np.float64)
+    coef = (1.0 / np.sqrt(deg[s2] * deg[d2])).astype(np.float32)
+    z = (wl.x.astype(np.float64) @ wl.params["w"].astype(np.float64)).astype(np.float32)
+    unfused = oracle.propagate(s2, d2, n, z, coef, MSG_E_MUL_XJ, AGGR_SUM)
+    fused, sabs = oracle.gcnconv(wl.src, wl.dst, n, wl.x, wl.params["w"], None, True, with_sabs=True)
+    assert (np.abs(fused - unfused) <= 1e-6 * sabs + 1e-12).all()
+
+
+def test_softmax_rows_and_plain_softmax():
+    n, h = 40, 3
+    src, dst = rng_graph(71, n, 500, star=True)
+    ne = dst.shape[0]
+    s = (4.0 * synth.normal_f32(71, 2, ne * h)).reshape(ne, h)
+    alpha = oracle.segment_softmax(dst, n, s)
+    inc = incoming(dst, n)
+    for i in range(n):
+        if inc[i].size == 0:
+            continue
+        seg = s[inc[i]].astype(np.float64)
+        ex = np.exp(seg - seg.max(0))
+        np.testing.assert_allclose(alpha[inc[i]], ex / ex.sum(0), rtol=2e-7)
+        np.testing.assert_allclose(alpha[inc[i]].sum(0), 1.0, rtol=1e-6)
+    # one-dimensional scores are accepted as one head
+    a1 = oracle.segment_softmax(dst, n, s[:, 0].copy())
+    np.testing.assert_array_equal(a1, alpha[:, 0])
+
+
+def test_gat_brute_force():
+    n, f_in, heads, ch = 30, 7, 3, 4
+    src, dst = rng_graph(81, n, 300, star=True)
+    loops = np.arange(n, dtype=np.int32)[::2]                      # some self-loops in the list
+    src, dst = np.concatenate([src, loops]), np.concatenate([dst, loops])
+    x = synth.normal_f32(81, 2, n * f_in).reshape(n, f_in)
+    w = synth.glorot_uniform(81, 4, f_in, heads * ch, (f_in, heads * ch))
+    a_s = synth.uniform_f32(81, 5, heads * ch, -1, 1).reshape(heads, ch)
+    a_d = synth.uniform_f32(81, 6, heads * ch, -1, 1).reshape(heads, ch)
+    got = oracle.gatconv(src, dst, n, x, w, a_s, a_d, 0.2)
+    h = (x.astype(np.float64) @ w.astype(np.float64)).astype(np.float32).astype(np.float64).reshape(n, heads, ch)
+    sl = (h * a_s[None]).sum(-1)
+    sr = (h * a_d[None]).sum(-1)
+    ref = np.zeros((n, heads, ch))
+    inc = incoming(dst, n)
+    for i in range(n):
+        if inc[i].size == 0:
+            continue
+        j = src[inc[i]]
+        sc = sl[j] + sr[i][None]
+        sc = np.where(sc > 0, sc, 0.2 * sc)
+        ex = np.exp(sc - sc.max(0))
+        al = ex / ex.sum(0)
+        ref[i] = (al[:, :, None] * h[j]).sum(0)
+    np.testing.assert_allclose(got.reshape(n, heads, ch), ref, rtol=0, atol=3e-7 * np.abs(ref).max())
+
+
+def test_gat_zero_attention_is_mean():
+    wl = synth.config4_gat(num_nodes=400, num_edges=3000, f_in=10, heads=2, ch=4, cap=100.0)
+    n = wl.num_nodes
+    zero = np.zeros((2, 4), np.float32)
+    got, sabs = oracle.gatconv(wl.src, wl.dst, n, wl.x, wl.params["w"], zero, zero, 0.2, with_sabs=True)
+    hfeat = (wl.x.astype(np.float64) @ wl.params["w"].astype(np.float64)).astype(np.float32)
+    ref = oracle.propagate(wl.src, wl.dst, n, hfeat, None, MSG_COPY_XJ, AGGR_MEAN)
+    assert (np.abs(got - ref) <= 1e-6 * sabs + 1e-12).all()
+
+
+def test_pool_and_batching():
+    wl = synth.config3_batched(num_graphs=37, feat=4)
+    n, g = wl.num_nodes, wl.num_graphs
+    gi = wl.graph_indicator
+    assert (np.diff(gi) >= 0).all()
+    sizes = np.bincount(gi, minlength=g)
+    ones = np.ones((n, 4), np.float32)
+    np.testing.assert_array_equal(oracle.graph_pool(gi, g, ones)[:, 0], sizes)
+    # sum-pool of propagate(ones) = edges per graph
+    deg = oracle.propagate(wl.src, wl.dst, n, ones)
+    np.testing.assert_array_equal(oracle.graph_pool(gi, g, deg)[:, 0], np.bincount(gi[wl.dst], minlength=g))
+    c = np.full((n, 4), -3.0, np.float32)
+    np.testing.assert_array_equal(oracle.graph_pool(gi, g, c, AGGR_MEAN), np.full((g, 4), -3.0, np.float32))
+    # against per-graph numpy reductions
+    off = np.concatenate([[0], np.cumsum(sizes)])
+    for aggr, fn in ((AGGR_SUM, np.sum), (AGGR_MEAN, np.mean), (AGGR_MAX, np.max)):
+        got = oracle.graph_pool(gi, g, wl.x, aggr)
+        for q in range(g):
+            np.testing.assert_allclose(got[q], fn(wl.x[off[q]:off[q + 1]].astype(np.float64), axis=0), rtol=1e-6, atol=1e-7)
+    # a graph id without nodes gives a zero row
+    got = oracle.graph_pool(gi, g + 2, wl.x, AGGR_MAX)
+    assert (got[g:] == 0).all()
+    # batched propagate = per-graph propagate, concatenated
+    full = oracle.propagate(wl.src, wl.dst, n, wl.x)
+    for q in (0, 5, g - 1):
+        m = gi[wl.dst] == q
+        part = oracle.propagate((wl.src[m] - off[q]).astype(np.int32), (wl.dst[m] - off[q]).astype(np.int32), int(sizes[q]), wl.x[off[q]:off[q + 1]])
+        np.testing.assert_array_equal(part, full[off[q]:off[q + 1]])
+
+
+def test_error_codes():
+    src = np.array([0, 5], np.int32)
+    dst = np.array([1, 0], np.int32)
+    x = np.zeros((3, 2), np.float32)
+    with pytest.raises(oracle.OracleError):
+        oracle.build_csr(src, dst, 3)
+    with pytest.raises(oracle.OracleError):
+        oracle.propagate(src, dst, 3, x)
+    with pytest.raises(oracle.OracleError):
+        oracle.graph_pool(np.array([0, 1, 9], np.int32), 2, x)
