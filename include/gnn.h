@@ -1,0 +1,195 @@
+/*
+ * gnn.h -- C ABI of the MI355X (gfx950) message-passing library.
+ *
+ * The library implements the forward hot path of graph message passing as the
+ * paper describes it (section 3, "Message Passing"): for every edge j -> i a
+ * message is built from the source node's features x_j and the edge's own data
+ * e_(j->i) (apply_edges), and the messages are reduced over each destination
+ * node's neighbourhood (aggregate_neighbors); `propagate` fuses the two, and
+ * particular (message, reduction) pairs are sparse-times-dense products.
+ *
+ * Conventions (all entry points):
+ *   - nodes are 0..N-1, edges 0..E-1, indices are int32_t; edge k carries a
+ *     message from src[k] (j) to dst[k] (i) and is reduced at i;
+ *   - features are float, row-major [N x F] (one node's F values contiguous);
+ *     this is byte-identical to the paper's column-major [F x N] Julia arrays;
+ *   - multi-edges and self-loops are legal and count with multiplicity;
+ *   - a node without incoming edges receives 0 for sum, mean and max alike;
+ *   - every pointer named d_* is DEVICE memory owned by the caller; the library
+ *     neither frees nor keeps it after the call returns (the call only enqueues
+ *     work: the memory must stay valid until that work has run);
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream);
+ *     compute calls enqueue kernels and return without synchronising;
+ *   - outputs must not alias inputs;
+ *   - errors are reported by return code only.  Argument errors are found on the
+ *     host before anything is launched.  Inputs are finite by contract.
+ *
+ * All device work runs on the device that is current when gnn_build_csr is
+ * called; the caller keeps that device current for later calls on the graph.
+ */
+#ifndef GNN_MI355X_H
+#define GNN_MI355X_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct gnn_graph gnn_graph; /* opaque: owns device rowptr/colidx/perm/in-degree + work lists */
+
+typedef enum {
+    GNN_OK = 0,
+    GNN_ERR_NULL = 1,        /* a required pointer is NULL */
+    GNN_ERR_BAD_SIZE = 2,    /* N <= 0, E < 0, E >= 2^31, a dimension <= 0, unknown enum, short workspace */
+    GNN_ERR_INDEX_RANGE = 3, /* a node id outside [0, N) (or a graph id outside [0, G)) */
+    GNN_ERR_UNSUPPORTED = 4, /* combination not implemented */
+    GNN_ERR_ALLOC = 5,       /* device allocation failed */
+    GNN_ERR_DEVICE = 6,      /* a HIP call or launch failed */
+    GNN_ERR_NOT_SORTED = 7   /* graph_indicator is not non-decreasing */
+} gnn_status;
+
+typedef enum { GNN_MSG_COPY_XJ = 0, GNN_MSG_E_MUL_XJ = 1 } gnn_msg_op;
+typedef enum { GNN_AGGR_SUM = 0, GNN_AGGR_MEAN = 1, GNN_AGGR_MAX = 2 } gnn_aggr;
+typedef enum { GNN_EDGE_ORDER_COO = 0, GNN_EDGE_ORDER_CSR = 1 } gnn_edge_order;
+
+const char *gnn_status_string(gnn_status s);
+
+/*
+ * COO -> CSR by destination (paper section 3, "Graph Data Structures": COO is
+ * the default topology encoding and a sparse adjacency encodes the same graph).
+ *
+ * d_src, d_dst : device, [num_edges] each (may be NULL only if num_edges == 0).
+ * On success *out_graph owns device arrays
+ *   rowptr[N+1] (exclusive prefix sum of the in-degrees), in-degree[N],
+ *   perm[E]   = the STABLE permutation that sorts the edges by destination
+ *               (a row lists its edges in increasing original edge index),
+ *   colidx[E] = src[perm[p]],
+ * plus the degree-bucketed work lists the compute calls use.  The sort is a
+ * least-significant-digit radix sort on the destination id.
+ * Synchronises the stream (it reads back the range-check flag and list sizes).
+ * Errors: GNN_ERR_NULL, GNN_ERR_BAD_SIZE, GNN_ERR_INDEX_RANGE (no graph is
+ * returned), GNN_ERR_ALLOC, GNN_ERR_DEVICE.  num_edges == 0 is valid.
+ */
+gnn_status gnn_build_csr(const int32_t *d_src, const int32_t *d_dst, int64_t num_edges,
+                         int32_t num_nodes, void *stream, gnn_graph **out_graph);
+
+/*
+ * Same, with the two scheduling thresholds exposed (0 = library default):
+ * rows with in-degree <= small_max_degree are reduced by a sub-group of a
+ * wavefront; longer rows are cut into pieces of at most chunk_edges edges, one
+ * wavefront each (pieces of one row are combined in a fixed order afterwards).
+ * The thresholds change scheduling only, never which edges a row holds.
+ * small_max_degree in [0, 64], chunk_edges a multiple of 64 in [64, 65536].
+ */
+gnn_status gnn_build_csr_ex(const int32_t *d_src, const int32_t *d_dst, int64_t num_edges,
+                            int32_t num_nodes, int32_t small_max_degree, int32_t chunk_edges,
+                            void *stream, gnn_graph **out_graph);
+
+/* Frees everything the graph owns.  The caller makes sure no enqueued work still uses it. */
+gnn_status gnn_graph_destroy(gnn_graph *g);
+
+/* Borrowed device pointers / sizes, valid until gnn_graph_destroy.  NULL / 0 for a NULL graph. */
+const int32_t *gnn_graph_rowptr(const gnn_graph *g);   /* [N+1] */
+const int32_t *gnn_graph_colidx(const gnn_graph *g);   /* [E]   */
+const int32_t *gnn_graph_perm(const gnn_graph *g);     /* [E]   */
+const int32_t *gnn_graph_indegree(const gnn_graph *g); /* [N]   */
+int32_t gnn_graph_num_nodes(const gnn_graph *g);
+int64_t gnn_graph_num_edges(const gnn_graph *g);
+/* Host-side sizes of the work lists: rows reduced by a sub-group, wavefront work items, split rows. */
+void gnn_graph_work_sizes(const gnn_graph *g, int32_t *n_small_rows, int32_t *n_items, int32_t *n_split_rows);
+
+/*
+ * Per-edge data from the caller's COO order into CSR order:
+ *   d_e_csr[p, :] = d_e[perm[p], :],  both [E x e_dim] float.
+ * Done once per graph and edge tensor so that compute calls stream edge data.
+ */
+gnn_status gnn_edge_data_to_csr(const gnn_graph *g, const float *d_e, int32_t e_dim,
+                                float *d_e_csr, void *stream);
+
+/*
+ * propagate (paper section 3, "Message Passing"): for every node i
+ *   out[i,:] = AGGR over edges k with dst[k] = i of  msg(x[src[k],:], e[k,:])
+ * msg  = COPY_XJ: x_j;   E_MUL_XJ: float(e * x_j) with e_dim == 1 (one weight per edge,
+ *        broadcast over features) or e_dim == feat_dim (element-wise).
+ * aggr = SUM, MEAN (divides by the number of incoming edges, not by a weight sum), MAX
+ *        (the larger value; +0 beats -0).  No incoming edge -> 0.
+ * d_x [N x feat_dim], d_out [N x feat_dim]; d_e [E x e_dim] in the order e_order names
+ * (COO = the order the edges were given in, CSR = after gnn_edge_data_to_csr), NULL for COPY_XJ.
+ * Any feat_dim > 0 is accepted; 16-byte aligned pointers with feat_dim % 4 == 0 take the
+ * 128-bit path.  Calls on one graph must not overlap in time (they share the graph's
+ * scratch buffer for rows that are split across wavefronts).
+ * Errors: GNN_ERR_NULL, GNN_ERR_BAD_SIZE, GNN_ERR_ALLOC, GNN_ERR_DEVICE.
+ */
+gnn_status gnn_propagate(const gnn_graph *g, const float *d_x, int32_t feat_dim,
+                         const float *d_e, int32_t e_dim, gnn_edge_order e_order,
+                         gnn_msg_op msg, gnn_aggr aggr, float *d_out, void *stream);
+
+/*
+ * GCNConv forward (layer named in the paper's training example; fused form of
+ * propagate per section 3):   out = D^-1/2 (A [+ I]) D^-1/2 X W + b
+ * with d_i = in-degree of i (+1 when add_self_loops != 0; one loop per node is
+ * added without looking for loops already present); an edge j -> i carries
+ * 1/sqrt(d_i d_j); a node with d = 0 contributes the coefficient 0.  No activation.
+ * d_x [N x f_in], d_w [f_in x f_out] row-major, d_bias [f_out] or NULL, d_out [N x f_out].
+ * d_workspace: device scratch of at least gnn_gcnconv_workspace_bytes(N, f_out) bytes.
+ */
+size_t gnn_gcnconv_workspace_bytes(int32_t num_nodes, int32_t f_out);
+gnn_status gnn_gcnconv(const gnn_graph *g, const float *d_x, int32_t f_in, const float *d_w,
+                       const float *d_bias, int32_t f_out, int32_t add_self_loops, float *d_out,
+                       void *d_workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Segment softmax over each destination's incoming edges, independently per head:
+ *   out[k,h] = exp(s[k,h] - m[i,h]) / sum_{q: dst[q] = i} exp(s[q,h] - m[i,h]),  i = dst[k],
+ * m = the segment maximum.  d_scores and d_out are [E x heads], both in the order `order` names.
+ */
+gnn_status gnn_segment_softmax(const gnn_graph *g, const float *d_scores, int32_t heads,
+                               gnn_edge_order order, float *d_out, void *stream);
+
+/*
+ * GAT-style attention layer (layer named in the paper, section 3 "Graph Convolutional Layers"):
+ *   h = X W  [N x heads*ch];  sl[j,hd] = <a_src[hd,:], h[j,hd,:]>;  sr[i,hd] = <a_dst[hd,:], h[i,hd,:]>
+ *   s[k,hd] = lrelu(sl[src[k],hd] + sr[dst[k],hd]),  lrelu(v) = v > 0 ? v : negative_slope * v
+ *   out[i,hd,:] = sum_k softmax_i(s)[k,hd] * h[src[k],hd,:]      (heads concatenated)
+ * No bias, no activation; self-loops only if the edge list holds them.
+ * d_w [f_in x heads*ch] row-major, d_a_src / d_a_dst [heads x ch], d_out [N x heads*ch].
+ * d_workspace: at least gnn_gatconv_workspace_bytes(N, heads, ch) bytes of device scratch.
+ */
+size_t gnn_gatconv_workspace_bytes(int32_t num_nodes, int32_t heads, int32_t ch);
+gnn_status gnn_gatconv(const gnn_graph *g, const float *d_x, int32_t f_in, const float *d_w,
+                       const float *d_a_src, const float *d_a_dst, int32_t heads, int32_t ch,
+                       float negative_slope, float *d_out, void *d_workspace,
+                       size_t workspace_bytes, void *stream);
+
+/*
+ * Graph-level readout of a batch of graphs (GlobalPool in the paper's example):
+ *   out[g,:] = AGGR over nodes i with graph_indicator[i] = g of x[i,:]
+ * d_graph_indicator [num_nodes] must be non-decreasing with values in [0, num_graphs)
+ * (what batching produces); a graph without nodes gets a zero row.  Sortedness and range
+ * are the caller's contract; they are not checked on the device.
+ */
+gnn_status gnn_graph_pool(const int32_t *d_graph_indicator, int32_t num_nodes, int32_t num_graphs,
+                          const float *d_x, int32_t feat_dim, gnn_aggr aggr, float *d_out,
+                          void *stream);
+
+/*
+ * GIN-style node update without the MLP (layer named in the paper, section 3):
+ *   out[i,:] = (1 + eps) * x[i,:] + sum_{j -> i} x[j,:]
+ */
+gnn_status gnn_gin_update(const gnn_graph *g, const float *d_x, int32_t feat_dim, float eps,
+                          float *d_out, void *stream);
+
+/*
+ * Dense projection Z = X W on the matrix cores (fp32 MFMA, fp32 accumulate), the
+ * contraction inside GCNConv and the GAT layer.  d_x [rows x k], d_w [k x n] row-major,
+ * d_z [rows x n].  d_row_scale [rows] or NULL: Z[r,:] is multiplied by d_row_scale[r].
+ */
+gnn_status gnn_dense_xw(const float *d_x, int64_t rows, int32_t k, const float *d_w, int32_t n,
+                        const float *d_row_scale, float *d_z, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GNN_MI355X_H */

@@ -1,0 +1,285 @@
+"""Thin ctypes binding of libgnn_mi355x.so (argument marshalling only).
+
+PyTorch-ROCm supplies device memory (``tensor.data_ptr()``) and the HIP stream
+(``torch.cuda.current_stream().cuda_stream``); every step of the path runs in the
+library's kernels.  There is no CPU or eager fallback: if the library is missing
+or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libgnn_mi355x.so")
+
+MSG_COPY_XJ, MSG_E_MUL_XJ = 0, 1
+AGGR_SUM, AGGR_MEAN, AGGR_MAX = 0, 1, 2
+EDGE_ORDER_COO, EDGE_ORDER_CSR = 0, 1
+
+_c = ctypes
+_vp, _i32, _i64, _f32, _sz = _c.c_void_p, _c.c_int32, _c.c_int64, _c.c_float, _c.c_size_t
+
+# name -> (restype, argtypes); every symbol declared in include/gnn.h
+SIGNATURES = {
+    "gnn_status_string": (_c.c_char_p, [_c.c_int]),
+    "gnn_build_csr": (_c.c_int, [_vp, _vp, _i64, _i32, _vp, _c.POINTER(_vp)]),
+    "gnn_build_csr_ex": (_c.c_int, [_vp, _vp, _i64, _i32, _i32, _i32, _vp, _c.POINTER(_vp)]),
+    "gnn_graph_destroy": (_c.c_int, [_vp]),
+    "gnn_graph_rowptr": (_vp, [_vp]),
+    "gnn_graph_colidx": (_vp, [_vp]),
+    "gnn_graph_perm": (_vp, [_vp]),
+    "gnn_graph_indegree": (_vp, [_vp]),
+    "gnn_graph_num_nodes": (_i32, [_vp]),
+    "gnn_graph_num_edges": (_i64, [_vp]),
+    "gnn_graph_work_sizes": (None, [_vp, _c.POINTER(_i32), _c.POINTER(_i32), _c.POINTER(_i32)]),
+    "gnn_edge_data_to_csr": (_c.c_int, [_vp, _vp, _i32, _vp, _vp]),
+    "gnn_propagate": (_c.c_int, [_vp, _vp, _i32, _vp, _i32, _c.c_int, _c.c_int, _c.c_int, _vp, _vp]),
+    "gnn_gcnconv_workspace_bytes": (_sz, [_i32, _i32]),
+    "gnn_gcnconv": (_c.c_int, [_vp, _vp, _i32, _vp, _vp, _i32, _i32, _vp, _vp, _sz, _vp]),
+    "gnn_segment_softmax": (_c.c_int, [_vp, _vp, _i32, _c.c_int, _vp, _vp]),
+    "gnn_gatconv_workspace_bytes": (_sz, [_i32, _i32, _i32]),
+    "gnn_gatconv": (_c.c_int, [_vp, _vp, _i32, _vp, _vp, _vp, _i32, _i32, _f32, _vp, _vp, _sz, _vp]),
+    "gnn_graph_pool": (_c.c_int, [_vp, _i32, _i32, _vp, _i32, _c.c_int, _vp, _vp]),
+    "gnn_gin_update": (_c.c_int, [_vp, _vp, _i32, _f32, _vp, _vp]),
+    "gnn_dense_xw": (_c.c_int, [_vp, _i64, _i32, _vp, _i32, _vp, _vp, _vp]),
+}
+
+_lib = None
+
+
+class GnnError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        self.code = code
+        msg = lib().gnn_status_string(code).decode() if _lib is not None else "?"
+        super().__init__(f"{what}: {msg} (gnn_status {code})")
+
+
+def lib():
+    """Loads the shared library (raises if it has not been built)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2412_06354_amd.build`")
+        handle = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in SIGNATURES.items():
+            fn = getattr(handle, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = handle
+    return _lib
+
+
+def _check(code: int, what: str):
+    if code != 0:
+        raise GnnError(code, what)
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _dev(t: Optional[torch.Tensor], dtype, name: str) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise TypeError(f"{name} must live in device memory")
+    if t.dtype != dtype:
+        raise TypeError(f"{name} must be {dtype}")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    return t.data_ptr()
+
+
+class Graph:
+    """Owner of a ``gnn_graph`` handle (CSR by destination + work lists, all in device memory)."""
+
+    def __init__(self, handle: int, device: torch.device):
+        self._h = handle
+        self.device = device
+        self.num_nodes = int(lib().gnn_graph_num_nodes(handle))
+        self.num_edges = int(lib().gnn_graph_num_edges(handle))
+
+    def _view(self, ptr: int, count: int) -> torch.Tensor:
+        """Copy of a library-owned int32 device array as a tensor."""
+        out = torch.empty(count, dtype=torch.int32, device=self.device)
+        if count:
+            torch.cuda.current_stream().synchronize()
+            _hip_memcpy_d2d(out.data_ptr(), ptr, 4 * count)
+        return out
+
+    @property
+    def rowptr(self):
+        return self._view(lib().gnn_graph_rowptr(self._h), self.num_nodes + 1)
+
+    @property
+    def colidx(self):
+        return self._view(lib().gnn_graph_colidx(self._h), self.num_edges)
+
+    @property
+    def perm(self):
+        return self._view(lib().gnn_graph_perm(self._h), self.num_edges)
+
+    @property
+    def indegree(self):
+        return self._view(lib().gnn_graph_indegree(self._h), self.num_nodes)
+
+    def work_sizes(self):
+        a, b, c = _i32(), _i32(), _i32()
+        lib().gnn_graph_work_sizes(self._h, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c))
+        return {"small_rows": a.value, "items": b.value, "split_rows": c.value}
+
+    def close(self):
+        if self._h:
+            torch.cuda.synchronize()
+            lib().gnn_graph_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+_hip = None
+
+
+def _hip_memcpy_d2d(dst: int, src: int, nbytes: int):
+    global _hip
+    if _hip is None:
+        _hip = ctypes.CDLL("libamdhip64.so")
+        _hip.hipMemcpy.restype = ctypes.c_int
+        _hip.hipMemcpy.argtypes = [_vp, _vp, _sz, ctypes.c_int]
+    rc = _hip.hipMemcpy(dst, src, nbytes, 3)  # hipMemcpyDeviceToDevice
+    if rc != 0:
+        raise RuntimeError(f"hipMemcpy failed ({rc})")
+
+
+def build_csr(src: torch.Tensor, dst: torch.Tensor, num_nodes: int, small_max_degree: int = 0,
+              chunk_edges: int = 0) -> Graph:
+    e = int(src.shape[0])
+    if int(dst.shape[0]) != e:
+        raise ValueError("src and dst must have the same length")
+    out = _vp()
+    rc = lib().gnn_build_csr_ex(_dev(src, torch.int32, "src"), _dev(dst, torch.int32, "dst"), e, num_nodes,
+                                small_max_degree, chunk_edges, _stream(), ctypes.byref(out))
+    _check(rc, "gnn_build_csr")
+    return Graph(out.value, src.device)
+
+
+def edge_data_to_csr(g: Graph, e: torch.Tensor) -> torch.Tensor:
+    e2 = e.reshape(g.num_edges, -1)
+    out = torch.empty_like(e2)
+    _check(lib().gnn_edge_data_to_csr(g._h, _dev(e2, torch.float32, "e"), e2.shape[1],
+                                      out.data_ptr(), _stream()), "gnn_edge_data_to_csr")
+    return out.reshape(e.shape)
+
+
+def propagate(g: Graph, x: torch.Tensor, e: Optional[torch.Tensor] = None, msg: int = MSG_COPY_XJ,
+              aggr: int = AGGR_SUM, e_order: int = EDGE_ORDER_COO,
+              out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    n, f = x.shape
+    if n != g.num_nodes:
+        raise ValueError("x must have one row per node")
+    e_dim = 1
+    if e is not None:
+        e = e.reshape(g.num_edges, -1)
+        e_dim = int(e.shape[1])
+    if out is None:
+        out = torch.empty_like(x)
+    rc = lib().gnn_propagate(g._h, _dev(x, torch.float32, "x"), f, _dev(e, torch.float32, "e"), e_dim,
+                             e_order, msg, aggr, _dev(out, torch.float32, "out"), _stream())
+    _check(rc, "gnn_propagate")
+    return out
+
+
+def gcnconv(g: Graph, x: torch.Tensor, w: torch.Tensor, bias: Optional[torch.Tensor] = None,
+            add_self_loops: bool = True, out: Optional[torch.Tensor] = None,
+            workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    n, f_in = x.shape
+    f_out = int(w.shape[1])
+    if n != g.num_nodes or w.shape[0] != f_in:
+        raise ValueError("shape mismatch")
+    need = int(lib().gnn_gcnconv_workspace_bytes(n, f_out))
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+    if out is None:
+        out = torch.empty((n, f_out), dtype=torch.float32, device=x.device)
+    rc = lib().gnn_gcnconv(g._h, _dev(x, torch.float32, "x"), f_in, _dev(w, torch.float32, "w"),
+                           _dev(bias, torch.float32, "bias"), f_out, 1 if add_self_loops else 0,
+                           _dev(out, torch.float32, "out"), workspace.data_ptr(), workspace.numel(), _stream())
+    _check(rc, "gnn_gcnconv")
+    return out
+
+
+def segment_softmax(g: Graph, scores: torch.Tensor, order: int = EDGE_ORDER_COO,
+                    out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    s2 = scores.reshape(g.num_edges, -1)
+    if out is None:
+        out = torch.empty_like(scores)
+    rc = lib().gnn_segment_softmax(g._h, _dev(s2, torch.float32, "scores"), int(s2.shape[1]) if g.num_edges else 1,
+                                   order, _dev(out, torch.float32, "out"), _stream())
+    _check(rc, "gnn_segment_softmax")
+    return out
+
+
+def gatconv(g: Graph, x: torch.Tensor, w: torch.Tensor, a_src: torch.Tensor, a_dst: torch.Tensor,
+            negative_slope: float = 0.2, out: Optional[torch.Tensor] = None,
+            workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    n, f_in = x.shape
+    heads, ch = a_src.shape
+    if n != g.num_nodes or tuple(w.shape) != (f_in, heads * ch) or tuple(a_dst.shape) != (heads, ch):
+        raise ValueError("shape mismatch")
+    need = int(lib().gnn_gatconv_workspace_bytes(n, heads, ch))
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+    if out is None:
+        out = torch.empty((n, heads * ch), dtype=torch.float32, device=x.device)
+    rc = lib().gnn_gatconv(g._h, _dev(x, torch.float32, "x"), f_in, _dev(w, torch.float32, "w"),
+                           _dev(a_src, torch.float32, "a_src"), _dev(a_dst, torch.float32, "a_dst"), heads, ch,
+                           float(negative_slope), _dev(out, torch.float32, "out"), workspace.data_ptr(),
+                           workspace.numel(), _stream())
+    _check(rc, "gnn_gatconv")
+    return out
+
+
+def graph_pool(graph_indicator: torch.Tensor, num_graphs: int, x: torch.Tensor, aggr: int = AGGR_SUM,
+               out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    n, f = x.shape
+    if int(graph_indicator.shape[0]) != n:
+        raise ValueError("graph_indicator must have one entry per node")
+    if out is None:
+        out = torch.empty((num_graphs, f), dtype=torch.float32, device=x.device)
+    rc = lib().gnn_graph_pool(_dev(graph_indicator, torch.int32, "graph_indicator"), n, num_graphs,
+                              _dev(x, torch.float32, "x"), f, aggr, _dev(out, torch.float32, "out"), _stream())
+    _check(rc, "gnn_graph_pool")
+    return out
+
+
+def gin_update(g: Graph, x: torch.Tensor, eps: float = 0.0, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    n, f = x.shape
+    if n != g.num_nodes:
+        raise ValueError("x must have one row per node")
+    if out is None:
+        out = torch.empty_like(x)
+    rc = lib().gnn_gin_update(g._h, _dev(x, torch.float32, "x"), f, float(eps), _dev(out, torch.float32, "out"),
+                              _stream())
+    _check(rc, "gnn_gin_update")
+    return out
+
+
+def dense_xw(x: torch.Tensor, w: torch.Tensor, row_scale: Optional[torch.Tensor] = None,
+             out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    rows, k = x.shape
+    n = int(w.shape[1])
+    if w.shape[0] != k:
+        raise ValueError("shape mismatch")
+    if out is None:
+        out = torch.empty((rows, n), dtype=torch.float32, device=x.device)
+    rc = lib().gnn_dense_xw(_dev(x, torch.float32, "x"), rows, k, _dev(w, torch.float32, "w"), n,
+                            _dev(row_scale, torch.float32, "row_scale"), _dev(out, torch.float32, "out"), _stream())
+    _check(rc, "gnn_dense_xw")
+    return out

@@ -1,0 +1,453 @@
+// COO -> CSR by destination: in-degree histogram with range check, exclusive scan to rowptr,
+// stable least-significant-digit radix sort of (dst; src, edge id), and the degree-bucketed
+// work lists used by the compute kernels.
+//
+// The paper (section 3, "Graph Data Structures") keeps topology in COO form by default and
+// treats the sparse adjacency as another encoding of the same graph; this file derives the
+// by-destination sparse form once per graph so that every later reduction over a node's
+// neighbourhood is a contiguous segment.
+#include "gnn_internal.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+
+// ---------------------------------------------------------------- in-degree histogram
+
+__global__ __launch_bounds__(kThreads) void indegree_kernel(const int32_t *__restrict__ src,
+                                                            const int32_t *__restrict__ dst, int64_t E, int32_t N,
+                                                            int32_t *__restrict__ indeg, int32_t *__restrict__ bad)
+{
+    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    int any_bad = 0;
+    for (int64_t k = (int64_t)blockIdx.x * kThreads + threadIdx.x; k < E; k += stride) {
+        const int32_t s = src[k], d = dst[k];
+        if ((uint32_t)s >= (uint32_t)N || (uint32_t)d >= (uint32_t)N) {
+            any_bad = 1;
+        } else {
+            atomicAdd(&indeg[d], 1);
+        }
+    }
+    if (any_bad) atomicOr(bad, 1);
+}
+
+// ---------------------------------------------------------------- radix sort passes
+
+constexpr int kSortItems = 16;                       // keys per thread
+constexpr int kSortTile = kThreads * kSortItems;     // keys per block
+constexpr int kWaves = kThreads / 64;
+constexpr int kRadixMax = 256;
+
+// Per-tile digit counts, laid out [digit][tile] so that one exclusive scan over the whole
+// array yields, for every (digit, tile), the first output position of that tile's keys.
+__global__ __launch_bounds__(kThreads) void sort_count_kernel(const int32_t *__restrict__ keys, int64_t n, int shift,
+                                                              int bits, int32_t *__restrict__ tile_counts,
+                                                              int num_tiles)
+{
+    __shared__ int cnt[kRadixMax];
+    const int radix = 1 << bits, mask = radix - 1;
+    for (int d = threadIdx.x; d < radix; d += kThreads) cnt[d] = 0;
+    __syncthreads();
+    const int64_t base = (int64_t)blockIdx.x * kSortTile;
+#pragma unroll 4
+    for (int i = 0; i < kSortItems; ++i) {
+        const int64_t idx = base + i * kThreads + threadIdx.x;
+        if (idx < n) atomicAdd(&cnt[(keys[idx] >> shift) & mask], 1);
+    }
+    __syncthreads();
+    for (int d = threadIdx.x; d < radix; d += kThreads) tile_counts[(int64_t)d * num_tiles + blockIdx.x] = cnt[d];
+}
+
+// Stable scatter of one pass.  Inside a tile the order is: wavefront, then item, then lane;
+// key `idx` of wavefront w is tile_base + w*64*items + item*64 + lane, so this order is the
+// input order.  A key's output position is
+//   (first position of its digit in this tile) + (same-digit keys of earlier wavefronts)
+//   + (same-digit keys of this wavefront in earlier items or lower lanes).
+// The last term comes from ballots: the lanes holding the same digit are found bit by bit.
+__global__ __launch_bounds__(kThreads) void sort_scatter_kernel(
+    const int32_t *__restrict__ keys_in, const int32_t *__restrict__ val_in, const int32_t *__restrict__ eid_in,
+    int64_t n, int shift, int bits, const int32_t *__restrict__ tile_offsets, int num_tiles,
+    int32_t *__restrict__ keys_out, int32_t *__restrict__ val_out, int32_t *__restrict__ eid_out)
+{
+    __shared__ int wcnt[kWaves][kRadixMax];
+    const int radix = 1 << bits, mask = radix - 1;
+    const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    for (int d = threadIdx.x; d < kWaves * kRadixMax; d += kThreads) (&wcnt[0][0])[d] = 0;
+    __syncthreads();
+
+    const int64_t wbase = (int64_t)blockIdx.x * kSortTile + (int64_t)w * 64 * kSortItems;
+    const uint64_t lt_mask = (1ull << lane) - 1ull;
+    volatile int *my_cnt = wcnt[w];
+    int key[kSortItems];
+    int rank[kSortItems];
+#pragma unroll
+    for (int i = 0; i < kSortItems; ++i) {
+        const int64_t idx = wbase + i * 64 + lane;
+        const bool valid = idx < n;
+        const int k = valid ? keys_in[idx] : 0;
+        const int d = (k >> shift) & mask;
+        uint64_t peers = __ballot(valid);
+        for (int b = 0; b < bits; ++b) {
+            const bool bit = (d >> b) & 1;
+            const uint64_t m = __ballot(bit);
+            peers &= bit ? m : ~m;
+        }
+        const int r = __popcll(peers & lt_mask);
+        int before = 0;
+        if (valid) before = my_cnt[d];
+        __builtin_amdgcn_wave_barrier();
+        if (valid && r == 0) my_cnt[d] = before + __popcll(peers);
+        __builtin_amdgcn_wave_barrier();
+        key[i] = k;
+        rank[i] = before + r;
+    }
+    __syncthreads();
+    for (int d = threadIdx.x; d < radix; d += kThreads) {
+        int run = tile_offsets[(int64_t)d * num_tiles + blockIdx.x];
+#pragma unroll
+        for (int q = 0; q < kWaves; ++q) {
+            const int c = wcnt[q][d];
+            wcnt[q][d] = run;
+            run += c;
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < kSortItems; ++i) {
+        const int64_t idx = wbase + i * 64 + lane;
+        if (idx < n) {
+            const int d = (key[i] >> shift) & mask;
+            const int pos = wcnt[w][d] + rank[i];
+            if (keys_out) keys_out[pos] = key[i];
+            val_out[pos] = val_in[idx];
+            eid_out[pos] = eid_in ? eid_in[idx] : (int32_t)idx;
+        }
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void iota_copy_kernel(const int32_t *__restrict__ key_in,
+                                                             const int32_t *__restrict__ val_in, int64_t n,
+                                                             int32_t *__restrict__ key_out,
+                                                             int32_t *__restrict__ val_out,
+                                                             int32_t *__restrict__ eid_out)
+{
+    const int64_t k = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (k < n) {
+        key_out[k] = key_in[k];
+        val_out[k] = val_in[k];
+        eid_out[k] = (int32_t)k;
+    }
+}
+
+// ---------------------------------------------------------------- work lists
+
+// Per row: is it a short row, how many wavefront pieces it needs, how many partial-result
+// slots (pieces of rows made of more than one piece), is it split.
+__global__ __launch_bounds__(kThreads) void classify_rows_kernel(const int32_t *__restrict__ indeg, int32_t N,
+                                                                 int32_t small_max, int32_t chunk,
+                                                                 int32_t *__restrict__ f_small,
+                                                                 int32_t *__restrict__ f_items,
+                                                                 int32_t *__restrict__ f_slots,
+                                                                 int32_t *__restrict__ f_split)
+{
+    const int32_t r = blockIdx.x * kThreads + threadIdx.x;
+    if (r >= N) return;
+    const int32_t deg = indeg[r];
+    const int small = deg <= small_max;
+    const int items = small ? 0 : (deg + chunk - 1) / chunk;
+    f_small[r] = small;
+    f_items[r] = items;
+    f_slots[r] = items > 1 ? items : 0;
+    f_split[r] = items > 1;
+}
+
+__global__ __launch_bounds__(kThreads) void fill_lists_kernel(
+    const int32_t *__restrict__ rowptr, int32_t N, int32_t small_max, int32_t chunk,
+    const int32_t *__restrict__ p_small, const int32_t *__restrict__ p_items, const int32_t *__restrict__ p_slots,
+    const int32_t *__restrict__ p_split, int32_t *__restrict__ small_rows, int32_t *__restrict__ item_row,
+    int32_t *__restrict__ item_start, int32_t *__restrict__ item_slot, int32_t *__restrict__ split_rows,
+    int32_t *__restrict__ split_slot0)
+{
+    const int32_t r = blockIdx.x * kThreads + threadIdx.x;
+    if (r >= N) return;
+    const int32_t start = rowptr[r], deg = rowptr[r + 1] - start;
+    if (deg <= small_max) {
+        small_rows[p_small[r]] = r;
+        return;
+    }
+    const int items = (deg + chunk - 1) / chunk;
+    const int32_t it0 = p_items[r];
+    if (items == 1) {
+        item_row[it0] = r;
+        item_start[it0] = start;
+        item_slot[it0] = -1;
+        return;
+    }
+    const int32_t slot0 = p_slots[r];
+    split_rows[p_split[r]] = r;
+    split_slot0[p_split[r]] = slot0;
+    for (int c = 0; c < items; ++c) {
+        item_row[it0 + c] = r;
+        item_start[it0 + c] = start + c * chunk;
+        item_slot[it0 + c] = slot0 + c;
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void permute_rows_kernel(const int32_t *__restrict__ perm, int64_t E,
+                                                                const float *__restrict__ e, int32_t e_dim,
+                                                                float *__restrict__ e_csr)
+{
+    const int64_t total = E * e_dim;
+    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    for (int64_t q = (int64_t)blockIdx.x * kThreads + threadIdx.x; q < total; q += stride) {
+        const int64_t p = q / e_dim;
+        const int32_t c = (int32_t)(q - p * e_dim);
+        e_csr[q] = e[(int64_t)perm[p] * e_dim + c];
+    }
+}
+
+int ceil_log2(uint32_t n)
+{
+    int b = 0;
+    while ((1ull << b) < n) ++b;
+    return b;
+}
+
+void free_graph_arrays(gnn_graph *g)
+{
+    void *ptrs[] = {g->rowptr,     g->indeg,     g->colidx,     g->perm,       g->rowidx,  g->small_rows,
+                    g->item_row,   g->item_start, g->item_slot, g->split_rows, g->split_slot0, g->scratch};
+    for (void *p : ptrs)
+        if (p) (void)hipFree(p);
+}
+
+template <typename T>
+gnn_status dev_alloc(T **out, size_t count)
+{
+    void *p = nullptr;
+    if (hipMalloc(&p, (count ? count : 1) * sizeof(T)) != hipSuccess) {
+        (void)hipGetLastError();
+        return GNN_ERR_ALLOC;
+    }
+    *out = static_cast<T *>(p);
+    return GNN_OK;
+}
+
+gnn_status build_impl(const int32_t *d_src, const int32_t *d_dst, int64_t E, int32_t N, hipStream_t stream,
+                      gnn_graph *g)
+{
+    gnn_temp_pool tmp;
+    GNN_TRY(dev_alloc(&g->rowptr, (size_t)N + 1));
+    GNN_TRY(dev_alloc(&g->indeg, (size_t)N));
+    GNN_TRY(dev_alloc(&g->colidx, (size_t)E));
+    GNN_TRY(dev_alloc(&g->perm, (size_t)E));
+    GNN_TRY(dev_alloc(&g->rowidx, (size_t)E));
+
+    // ---- in-degree + range check
+    int32_t *d_flag;
+    GNN_TRY(tmp.get(&d_flag, 8));
+    GNN_HIP(hipMemsetAsync(d_flag, 0, 8 * sizeof(int32_t), stream));
+    GNN_HIP(hipMemsetAsync(g->indeg, 0, (size_t)N * sizeof(int32_t), stream));
+    if (E > 0) {
+        const int blocks = (int)std::min<int64_t>(gnn_div_up(E, kThreads), 256 * 32);
+        hipLaunchKernelGGL(indegree_kernel, dim3(blocks), dim3(kThreads), 0, stream, d_src, d_dst, E, N, g->indeg,
+                           d_flag);
+        GNN_LAUNCH_CHECK();
+    }
+    int32_t h_flag = 0;
+    GNN_HIP(hipMemcpyAsync(&h_flag, d_flag, sizeof(int32_t), hipMemcpyDeviceToHost, stream));
+    GNN_HIP(hipStreamSynchronize(stream));
+    if (h_flag) return GNN_ERR_INDEX_RANGE;
+
+    // ---- rowptr
+    int32_t *scan_tmp;
+    const int64_t num_tiles = gnn_div_up(E, kSortTile);
+    const size_t scan_elems = std::max(gnn_scan_tmp_elems((int64_t)N + 1), gnn_scan_tmp_elems(num_tiles * kRadixMax));
+    GNN_TRY(tmp.get(&scan_tmp, scan_elems));
+    GNN_TRY(gnn_scan_exclusive_i32(g->indeg, g->rowptr, N, true, scan_tmp, stream));
+
+    // ---- stable radix sort by destination
+    if (E > 0) {
+        const int key_bits = ceil_log2((uint32_t)N);
+        if (key_bits == 0) {
+            const int blocks = (int)gnn_div_up(E, kThreads);
+            hipLaunchKernelGGL(iota_copy_kernel, dim3(blocks), dim3(kThreads), 0, stream, d_dst, d_src, E, g->rowidx,
+                               g->colidx, g->perm);
+            GNN_LAUNCH_CHECK();
+        } else {
+            const int passes = (key_bits + 7) / 8;
+            const int bits = (key_bits + passes - 1) / passes;
+            int32_t *kb, *vb, *eb, *counts;
+            GNN_TRY(tmp.get(&kb, (size_t)E));
+            GNN_TRY(tmp.get(&vb, (size_t)E));
+            GNN_TRY(tmp.get(&eb, (size_t)E));
+            GNN_TRY(tmp.get(&counts, (size_t)num_tiles * kRadixMax));
+            // Ping-pong between (kb, vb, eb) and the arrays the graph keeps, arranged so that
+            // the last pass writes into the graph's arrays.
+            int32_t *bufk[2] = {kb, g->rowidx}, *bufv[2] = {vb, g->colidx}, *bufe[2] = {eb, g->perm};
+            int dst_sel = (passes % 2 == 1) ? 1 : 0;   // buffer written by the first pass
+            const int32_t *ki = d_dst, *vi = d_src, *ei = nullptr;
+            for (int p = 0; p < passes; ++p) {
+                const int shift = p * bits;
+                hipLaunchKernelGGL(sort_count_kernel, dim3((unsigned)num_tiles), dim3(kThreads), 0, stream, ki, E,
+                                   shift, bits, counts, (int)num_tiles);
+                GNN_LAUNCH_CHECK();
+                GNN_TRY(gnn_scan_exclusive_i32(counts, counts, num_tiles << bits, false, scan_tmp, stream));
+                hipLaunchKernelGGL(sort_scatter_kernel, dim3((unsigned)num_tiles), dim3(kThreads), 0, stream, ki, vi,
+                                   ei, E, shift, bits, counts, (int)num_tiles, bufk[dst_sel], bufv[dst_sel],
+                                   bufe[dst_sel]);
+                GNN_LAUNCH_CHECK();
+                ki = bufk[dst_sel];
+                vi = bufv[dst_sel];
+                ei = bufe[dst_sel];
+                dst_sel ^= 1;
+            }
+        }
+    }
+
+    // ---- work lists
+    int32_t *flags, *pos;
+    const size_t np1 = (size_t)N + 1;
+    GNN_TRY(tmp.get(&flags, 4 * np1));
+    GNN_TRY(tmp.get(&pos, 4 * np1));
+    const int nblocks = (int)gnn_div_up(N, kThreads);
+    hipLaunchKernelGGL(classify_rows_kernel, dim3(nblocks), dim3(kThreads), 0, stream, g->indeg, N, g->small_max,
+                       g->chunk, flags, flags + np1, flags + 2 * np1, flags + 3 * np1);
+    GNN_LAUNCH_CHECK();
+    for (int q = 0; q < 4; ++q)
+        GNN_TRY(gnn_scan_exclusive_i32(flags + q * np1, pos + q * np1, N, true, scan_tmp, stream));
+    int32_t totals[4] = {0, 0, 0, 0};
+    for (int q = 0; q < 4; ++q)
+        GNN_HIP(hipMemcpyAsync(&totals[q], pos + q * np1 + N, sizeof(int32_t), hipMemcpyDeviceToHost, stream));
+    GNN_HIP(hipStreamSynchronize(stream));
+    g->n_small = totals[0];
+    g->n_items = totals[1];
+    g->n_slots = totals[2];
+    g->n_split = totals[3];
+    GNN_TRY(dev_alloc(&g->small_rows, (size_t)g->n_small));
+    GNN_TRY(dev_alloc(&g->item_row, (size_t)g->n_items));
+    GNN_TRY(dev_alloc(&g->item_start, (size_t)g->n_items));
+    GNN_TRY(dev_alloc(&g->item_slot, (size_t)g->n_items));
+    GNN_TRY(dev_alloc(&g->split_rows, (size_t)g->n_split));
+    GNN_TRY(dev_alloc(&g->split_slot0, (size_t)g->n_split));
+    hipLaunchKernelGGL(fill_lists_kernel, dim3(nblocks), dim3(kThreads), 0, stream, g->rowptr, N, g->small_max,
+                       g->chunk, pos, pos + np1, pos + 2 * np1, pos + 3 * np1, g->small_rows, g->item_row,
+                       g->item_start, g->item_slot, g->split_rows, g->split_slot0);
+    GNN_LAUNCH_CHECK();
+    GNN_HIP(hipStreamSynchronize(stream));   // temporaries are freed when `tmp` goes out of scope
+    return GNN_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+gnn_status gnn_build_csr_ex(const int32_t *d_src, const int32_t *d_dst, int64_t num_edges, int32_t num_nodes,
+                            int32_t small_max_degree, int32_t chunk_edges, void *stream, gnn_graph **out_graph)
+{
+    if (!out_graph) return GNN_ERR_NULL;
+    *out_graph = nullptr;
+    if (num_nodes <= 0 || num_edges < 0 || num_edges >= (1ll << 31)) return GNN_ERR_BAD_SIZE;
+    if (num_edges > 0 && (!d_src || !d_dst)) return GNN_ERR_NULL;
+    if (small_max_degree == 0 && chunk_edges == 0) {
+        small_max_degree = 16;
+        chunk_edges = 512;
+    } else if (chunk_edges == 0) {
+        chunk_edges = 512;
+    }
+    if (small_max_degree < 0 || small_max_degree > 64) return GNN_ERR_BAD_SIZE;
+    if (chunk_edges < 64 || chunk_edges > 65536 || chunk_edges % 64 != 0) return GNN_ERR_BAD_SIZE;
+
+    gnn_graph *g = new (std::nothrow) gnn_graph();
+    if (!g) return GNN_ERR_ALLOC;
+    g->num_nodes = num_nodes;
+    g->num_edges = num_edges;
+    g->small_max = small_max_degree;
+    g->chunk = chunk_edges;
+    gnn_status st = build_impl(d_src, d_dst, num_edges, num_nodes, static_cast<hipStream_t>(stream), g);
+    if (st != GNN_OK) {
+        (void)hipStreamSynchronize(static_cast<hipStream_t>(stream));
+        free_graph_arrays(g);
+        delete g;
+        return st;
+    }
+    *out_graph = g;
+    return GNN_OK;
+}
+
+gnn_status gnn_build_csr(const int32_t *d_src, const int32_t *d_dst, int64_t num_edges, int32_t num_nodes,
+                         void *stream, gnn_graph **out_graph)
+{
+    return gnn_build_csr_ex(d_src, d_dst, num_edges, num_nodes, 0, 0, stream, out_graph);
+}
+
+gnn_status gnn_graph_destroy(gnn_graph *g)
+{
+    if (!g) return GNN_OK;
+    free_graph_arrays(g);
+    delete g;
+    return GNN_OK;
+}
+
+const int32_t *gnn_graph_rowptr(const gnn_graph *g) { return g ? g->rowptr : nullptr; }
+const int32_t *gnn_graph_colidx(const gnn_graph *g) { return g ? g->colidx : nullptr; }
+const int32_t *gnn_graph_perm(const gnn_graph *g) { return g ? g->perm : nullptr; }
+const int32_t *gnn_graph_indegree(const gnn_graph *g) { return g ? g->indeg : nullptr; }
+int32_t gnn_graph_num_nodes(const gnn_graph *g) { return g ? g->num_nodes : 0; }
+int64_t gnn_graph_num_edges(const gnn_graph *g) { return g ? g->num_edges : 0; }
+
+void gnn_graph_work_sizes(const gnn_graph *g, int32_t *n_small_rows, int32_t *n_items, int32_t *n_split_rows)
+{
+    if (n_small_rows) *n_small_rows = g ? g->n_small : 0;
+    if (n_items) *n_items = g ? g->n_items : 0;
+    if (n_split_rows) *n_split_rows = g ? g->n_split : 0;
+}
+
+gnn_status gnn_edge_data_to_csr(const gnn_graph *g, const float *d_e, int32_t e_dim, float *d_e_csr, void *stream)
+{
+    if (!g) return GNN_ERR_NULL;
+    if (e_dim <= 0) return GNN_ERR_BAD_SIZE;
+    if (g->num_edges == 0) return GNN_OK;
+    if (!d_e || !d_e_csr) return GNN_ERR_NULL;
+    const int64_t total = g->num_edges * e_dim;
+    const int blocks = (int)std::min<int64_t>(gnn_div_up(total, kThreads), 256 * 64);
+    hipLaunchKernelGGL(permute_rows_kernel, dim3(blocks), dim3(kThreads), 0, static_cast<hipStream_t>(stream),
+                       g->perm, g->num_edges, d_e, e_dim, d_e_csr);
+    GNN_LAUNCH_CHECK();
+    return GNN_OK;
+}
+
+const char *gnn_status_string(gnn_status s)
+{
+    switch (s) {
+    case GNN_OK: return "ok";
+    case GNN_ERR_NULL: return "a required pointer is NULL";
+    case GNN_ERR_BAD_SIZE: return "bad size, dimension or enum value";
+    case GNN_ERR_INDEX_RANGE: return "node or graph index out of range";
+    case GNN_ERR_UNSUPPORTED: return "combination not supported";
+    case GNN_ERR_ALLOC: return "device allocation failed";
+    case GNN_ERR_DEVICE: return "HIP call or kernel launch failed";
+    case GNN_ERR_NOT_SORTED: return "graph_indicator is not sorted";
+    }
+    return "unknown status";
+}
+
+}  // extern "C"
+
+gnn_status gnn_graph_reserve_scratch(const gnn_graph *g, size_t floats)
+{
+    if (floats <= g->scratch_floats) return GNN_OK;
+    // Earlier kernels may still be reading the old buffer.
+    GNN_HIP(hipDeviceSynchronize());
+    if (g->scratch) (void)hipFree(g->scratch);
+    g->scratch = nullptr;
+    g->scratch_floats = 0;
+    void *p = nullptr;
+    if (hipMalloc(&p, floats * sizeof(float)) != hipSuccess) {
+        (void)hipGetLastError();
+        return GNN_ERR_ALLOC;
+    }
+    g->scratch = static_cast<float *>(p);
+    g->scratch_floats = floats;
+    return GNN_OK;
+}

@@ -1,0 +1,358 @@
+// GAT-style attention layer (layer named in the paper, section 3, "Graph Convolutional
+// Layers"): an apply_edges step that scores every edge from its two endpoints, a softmax of the
+// scores over each destination's neighbourhood, and a weighted-sum aggregation -- fused here
+// into one pass over the by-destination CSR so that neither the [E x heads] scores nor the
+// attention weights are ever written to memory.
+//
+//   h = X W (MFMA projection);  sl = <a_src, h> and sr = <a_dst, h> per node and head;
+//   per destination row: running (max, denominator, weighted feature sum) per head updated edge
+//   by edge ("online" softmax), divided once at the end.
+// Work decomposition is the one of propagate: sub-group per short row, wavefront per piece of a
+// long row, split rows merged afterwards in piece order.
+#include "gnn_internal.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWavesPerBlock = kThreads / 64;
+
+struct GatParams {
+    const int32_t *rowptr, *colidx;
+    const float *h, *sl, *sr;
+    float *out;
+    float *slot_acc, *slot_m, *slot_d;   // [slots x HC] each
+    const int32_t *small_rows, *item_row, *item_start, *item_slot, *split_rows, *split_slot0;
+    int32_t n_small, n_items, n_split, chunk, HC, H, ch, item_blocks;
+    float slope;
+};
+
+template <int VEC>
+struct State {
+    float m, d;
+    float acc[VEC];
+};
+
+template <int VEC>
+__device__ __forceinline__ void state_init(State<VEC> &s)
+{
+    s.m = -INFINITY;
+    s.d = 0.0f;
+#pragma unroll
+    for (int c = 0; c < VEC; ++c) s.acc[c] = 0.0f;
+}
+
+// Adds one edge with score `sc` and feature slice `hv` to the running softmax-weighted sum.
+template <int VEC>
+__device__ __forceinline__ void state_add(State<VEC> &s, bool ok, float sc, const float *hv)
+{
+    const float delta = sc - s.m;
+    const float e = expf(-fabsf(delta));          // exp(-inf) = 0 covers the first edge (m = -inf)
+    const bool up = delta > 0.0f;
+    const float scale = ok ? (up ? e : 1.0f) : 1.0f;
+    const float pe = ok ? (up ? 1.0f : e) : 0.0f;
+    s.m = (ok && up) ? sc : s.m;
+    s.d = s.d * scale + pe;
+#pragma unroll
+    for (int c = 0; c < VEC; ++c) s.acc[c] = s.acc[c] * scale + pe * hv[c];
+}
+
+// Merges state b into a (b's edges come after a's).
+template <int VEC>
+__device__ __forceinline__ void state_merge(State<VEC> &a, float bm, float bd, const float *bacc)
+{
+    const float m = fmaxf(a.m, bm);
+    const float fa = (a.m == -INFINITY) ? 0.0f : expf(a.m - m);
+    const float fb = (bm == -INFINITY) ? 0.0f : expf(bm - m);
+    a.m = m;
+    a.d = a.d * fa + bd * fb;
+#pragma unroll
+    for (int c = 0; c < VEC; ++c) a.acc[c] = a.acc[c] * fa + bacc[c] * fb;
+}
+
+template <int VEC>
+__device__ __forceinline__ void load_vec(float *v, const float *__restrict__ p)
+{
+    if constexpr (VEC == 4) {
+        const float4 t = *reinterpret_cast<const float4 *>(p);
+        v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+    } else {
+        v[0] = *p;
+    }
+}
+
+template <int VEC>
+__device__ __forceinline__ void store_vec(float *__restrict__ p, const float *v)
+{
+    if constexpr (VEC == 4)
+        *reinterpret_cast<float4 *>(p) = make_float4(v[0], v[1], v[2], v[3]);
+    else
+        *p = v[0];
+}
+
+template <int VEC>
+__device__ __forceinline__ void write_out(const GatParams &p, int row, int col, const State<VEC> &s)
+{
+    float v[VEC];
+#pragma unroll
+    for (int c = 0; c < VEC; ++c) v[c] = s.d > 0.0f ? s.acc[c] / s.d : 0.0f;
+    store_vec<VEC>(p.out + (int64_t)row * p.HC + col, v);
+}
+
+__device__ __forceinline__ float lrelu(float v, float slope) { return v > 0.0f ? v : slope * v; }
+
+template <int LPR, int VEC>
+__device__ __forceinline__ void gat_short_rows(const GatParams &p, int block)
+{
+    constexpr int NSG = 64 / LPR;
+    constexpr int U = 4;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int sl_ = lane % LPR, sg = lane / LPR;
+    const int64_t sgid = ((int64_t)block * kWavesPerBlock + wave) * NSG + sg;
+    const bool have = sgid < p.n_small;
+    int row = 0, start = 0, deg = 0;
+    if (have) {
+        row = p.small_rows[sgid];
+        start = p.rowptr[row];
+        deg = p.rowptr[row + 1] - start;
+    }
+    int wmax = deg;
+#pragma unroll
+    for (int off = LPR; off < 64; off <<= 1) wmax = max(wmax, __shfl_xor(wmax, off, 64));
+
+    for (int cb = 0; cb * LPR * VEC < p.HC; ++cb) {
+        const int col = (cb * LPR + sl_) * VEC;
+        const bool colok = have && col < p.HC;
+        const int hd = colok ? col / p.ch : 0;
+        const float sr_i = colok ? p.sr[(int64_t)row * p.H + hd] : 0.0f;
+        State<VEC> st;
+        state_init(st);
+        for (int base = 0; base < wmax; base += LPR) {
+            int my_j = 0;
+            if (base + sl_ < deg) my_j = p.colidx[start + base + sl_];
+            const int cnt = min(LPR, wmax - base);
+            for (int t0 = 0; t0 < cnt; t0 += U) {
+                float hv[U][VEC], sc[U];
+                bool ok[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int t = t0 + u;
+                    const int j = __shfl(my_j, t, LPR);
+                    ok[u] = colok && (base + t < deg);
+                    sc[u] = 0.0f;
+#pragma unroll
+                    for (int c = 0; c < VEC; ++c) hv[u][c] = 0.0f;
+                    if (ok[u]) {
+                        load_vec<VEC>(hv[u], p.h + (int64_t)j * p.HC + col);
+                        sc[u] = p.sl[(int64_t)j * p.H + hd];
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) state_add<VEC>(st, ok[u], lrelu(sc[u] + sr_i, p.slope), hv[u]);
+            }
+        }
+        if (colok) write_out<VEC>(p, row, col, st);
+    }
+}
+
+template <int LPR, int VEC>
+__device__ __forceinline__ void gat_long_pieces(const GatParams &p, int block)
+{
+    constexpr int NSG = 64 / LPR;
+    constexpr int U = (LPR >= 8) ? 8 : LPR;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int sl_ = lane % LPR, sg = lane / LPR;
+    const int it = block * kWavesPerBlock + wave;
+    if (it >= p.n_items) return;
+    const int row = p.item_row[it];
+    const int start = p.item_start[it];
+    const int slot = p.item_slot[it];
+    const int end = min(start + p.chunk, p.rowptr[row + 1]);
+
+    for (int cb = 0; cb * LPR * VEC < p.HC; ++cb) {
+        const int col = (cb * LPR + sl_) * VEC;
+        const bool colok = col < p.HC;
+        const int hd = colok ? col / p.ch : 0;
+        const float sr_i = colok ? p.sr[(int64_t)row * p.H + hd] : 0.0f;
+        State<VEC> st;
+        state_init(st);
+        for (int base = start; base < end; base += 64) {
+            const int n = min(64, end - base);
+            int my_j = 0;
+            if (lane < n) my_j = p.colidx[base + lane];
+            for (int t0 = 0; t0 * NSG < n; t0 += U) {
+                float hv[U][VEC], sc[U];
+                bool ok[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int pos = (t0 + u) * NSG + sg;
+                    const int j = __shfl(my_j, pos, 64);
+                    ok[u] = colok && pos < n;
+                    sc[u] = 0.0f;
+#pragma unroll
+                    for (int c = 0; c < VEC; ++c) hv[u][c] = 0.0f;
+                    if (ok[u]) {
+                        load_vec<VEC>(hv[u], p.h + (int64_t)j * p.HC + col);
+                        sc[u] = p.sl[(int64_t)j * p.H + hd];
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) state_add<VEC>(st, ok[u], lrelu(sc[u] + sr_i, p.slope), hv[u]);
+            }
+        }
+#pragma unroll
+        for (int off = LPR; off < 64; off <<= 1) {
+            const float om = __shfl_xor(st.m, off, 64), od = __shfl_xor(st.d, off, 64);
+            float oacc[VEC];
+#pragma unroll
+            for (int c = 0; c < VEC; ++c) oacc[c] = __shfl_xor(st.acc[c], off, 64);
+            state_merge<VEC>(st, om, od, oacc);
+        }
+        if (sg == 0 && colok) {
+            if (slot < 0) {
+                write_out<VEC>(p, row, col, st);
+            } else {
+                const int64_t q = (int64_t)slot * p.HC + col;
+                float mv[VEC], dv[VEC];
+#pragma unroll
+                for (int c = 0; c < VEC; ++c) { mv[c] = st.m; dv[c] = st.d; }
+                store_vec<VEC>(p.slot_acc + q, st.acc);
+                store_vec<VEC>(p.slot_m + q, mv);
+                store_vec<VEC>(p.slot_d + q, dv);
+            }
+        }
+    }
+}
+
+template <int LPR, int VEC>
+__global__ __launch_bounds__(kThreads) void gat_kernel(const GatParams p)
+{
+    if ((int)blockIdx.x < p.item_blocks)
+        gat_long_pieces<LPR, VEC>(p, blockIdx.x);
+    else
+        gat_short_rows<LPR, VEC>(p, blockIdx.x - p.item_blocks);
+}
+
+template <int LPR, int VEC>
+__global__ __launch_bounds__(kThreads) void gat_merge_kernel(const GatParams p)
+{
+    const int64_t s = ((int64_t)blockIdx.x * kThreads + threadIdx.x) / LPR;
+    const int sl_ = threadIdx.x % LPR;
+    if (s >= p.n_split) return;
+    const int row = p.split_rows[s];
+    const int slot0 = p.split_slot0[s];
+    const int deg = p.rowptr[row + 1] - p.rowptr[row];
+    const int pieces = (deg + p.chunk - 1) / p.chunk;
+    for (int cb = 0; cb * LPR * VEC < p.HC; ++cb) {
+        const int col = (cb * LPR + sl_) * VEC;
+        if (col >= p.HC) continue;
+        State<VEC> st;
+        state_init(st);
+        for (int c = 0; c < pieces; ++c) {
+            const int64_t q = (int64_t)(slot0 + c) * p.HC + col;
+            float acc[VEC];
+            load_vec<VEC>(acc, p.slot_acc + q);
+            state_merge<VEC>(st, p.slot_m[q], p.slot_d[q], acc);
+        }
+        write_out<VEC>(p, row, col, st);
+    }
+}
+
+// sl[i,hd] = <a_src[hd,:], h[i,hd,:]>,  sr[i,hd] = <a_dst[hd,:], h[i,hd,:]>
+__global__ __launch_bounds__(kThreads) void node_scores_kernel(const float *__restrict__ h, int64_t N, int H, int ch,
+                                                               const float *__restrict__ a_src,
+                                                               const float *__restrict__ a_dst,
+                                                               float *__restrict__ sl, float *__restrict__ sr)
+{
+    const int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (idx >= N * H) return;
+    const int hd = (int)(idx % H);
+    const float *hp = h + idx * ch;   // (i*H + hd)*ch
+    float l = 0.0f, r = 0.0f;
+    for (int c = 0; c < ch; ++c) {
+        const float v = hp[c];
+        l = fmaf(a_src[hd * ch + c], v, l);
+        r = fmaf(a_dst[hd * ch + c], v, r);
+    }
+    sl[idx] = l;
+    sr[idx] = r;
+}
+
+template <int LPR, int VEC>
+gnn_status launch_gat(const GatParams &p, hipStream_t stream)
+{
+    constexpr int NSG = 64 / LPR;
+    const int64_t blocks = p.item_blocks + gnn_div_up(p.n_small, kWavesPerBlock * NSG);
+    if (blocks > 0) {
+        hipLaunchKernelGGL((gat_kernel<LPR, VEC>), dim3((unsigned)blocks), dim3(kThreads), 0, stream, p);
+        GNN_LAUNCH_CHECK();
+    }
+    if (p.n_split > 0) {
+        const int64_t cblocks = gnn_div_up((int64_t)p.n_split * LPR, kThreads);
+        hipLaunchKernelGGL((gat_merge_kernel<LPR, VEC>), dim3((unsigned)cblocks), dim3(kThreads), 0, stream, p);
+        GNN_LAUNCH_CHECK();
+    }
+    return GNN_OK;
+}
+
+size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
+
+}  // namespace
+
+extern "C" {
+
+size_t gnn_gatconv_workspace_bytes(int32_t num_nodes, int32_t heads, int32_t ch)
+{
+    if (num_nodes <= 0 || heads <= 0 || ch <= 0) return 0;
+    return align256((size_t)num_nodes * heads * ch * sizeof(float)) +
+           2 * align256((size_t)num_nodes * heads * sizeof(float));
+}
+
+gnn_status gnn_gatconv(const gnn_graph *g, const float *d_x, int32_t f_in, const float *d_w, const float *d_a_src,
+                       const float *d_a_dst, int32_t heads, int32_t ch, float negative_slope, float *d_out,
+                       void *d_workspace, size_t workspace_bytes, void *stream)
+{
+    if (!g || !d_x || !d_w || !d_a_src || !d_a_dst || !d_out || !d_workspace) return GNN_ERR_NULL;
+    if (f_in <= 0 || heads <= 0 || ch <= 0) return GNN_ERR_BAD_SIZE;
+    const int32_t N = g->num_nodes;
+    if (workspace_bytes < gnn_gatconv_workspace_bytes(N, heads, ch)) return GNN_ERR_BAD_SIZE;
+    if (reinterpret_cast<uintptr_t>(d_workspace) & 255u) return GNN_ERR_BAD_SIZE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int HC = heads * ch;
+    char *ws = static_cast<char *>(d_workspace);
+    float *h = reinterpret_cast<float *>(ws);
+    float *sl = reinterpret_cast<float *>(ws + align256((size_t)N * HC * sizeof(float)));
+    float *sr = reinterpret_cast<float *>(ws + align256((size_t)N * HC * sizeof(float)) +
+                                          align256((size_t)N * heads * sizeof(float)));
+
+    GNN_TRY(gnn_dense_xw(d_x, N, f_in, d_w, HC, nullptr, h, stream));
+    hipLaunchKernelGGL(node_scores_kernel, dim3((unsigned)gnn_div_up((int64_t)N * heads, kThreads)), dim3(kThreads),
+                       0, s, h, (int64_t)N, heads, ch, d_a_src, d_a_dst, sl, sr);
+    GNN_LAUNCH_CHECK();
+
+    GatParams p{};
+    p.rowptr = g->rowptr; p.colidx = g->colidx;
+    p.h = h; p.sl = sl; p.sr = sr; p.out = d_out;
+    p.small_rows = g->small_rows; p.item_row = g->item_row; p.item_start = g->item_start;
+    p.item_slot = g->item_slot; p.split_rows = g->split_rows; p.split_slot0 = g->split_slot0;
+    p.n_small = g->n_small; p.n_items = g->n_items; p.n_split = g->n_split; p.chunk = g->chunk;
+    p.HC = HC; p.H = heads; p.ch = ch; p.slope = negative_slope;
+    p.item_blocks = (int32_t)gnn_div_up(g->n_items, kWavesPerBlock);
+    if (g->n_slots > 0) {
+        GNN_TRY(gnn_graph_reserve_scratch(g, 3 * (size_t)g->n_slots * HC));
+        p.slot_acc = g->scratch;
+        p.slot_m = g->scratch + (size_t)g->n_slots * HC;
+        p.slot_d = g->scratch + 2 * (size_t)g->n_slots * HC;
+    }
+    const bool vec4 = (ch % 4 == 0) && ((reinterpret_cast<uintptr_t>(d_out) & 15u) == 0);
+    if (vec4) {
+        const int cols = HC / 4;
+        if (cols <= 8) return launch_gat<8, 4>(p, s);
+        if (cols <= 16) return launch_gat<16, 4>(p, s);
+        if (cols <= 32) return launch_gat<32, 4>(p, s);
+        return launch_gat<64, 4>(p, s);
+    }
+    if (HC <= 16) return launch_gat<16, 1>(p, s);
+    return launch_gat<64, 1>(p, s);
+}
+
+}  // extern "C"

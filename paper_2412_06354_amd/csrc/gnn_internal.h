@@ -1,0 +1,109 @@
+// Internal declarations shared by the translation units of the library (not part of the ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <vector>
+
+#include "gnn.h"
+
+#define GNN_WAVE 64
+
+// Turns a failing HIP call into GNN_ERR_DEVICE (or GNN_ERR_ALLOC for allocations).
+#define GNN_HIP(call)                                  \
+    do {                                               \
+        hipError_t e_ = (call);                        \
+        if (e_ != hipSuccess) {                        \
+            (void)hipGetLastError();                   \
+            return GNN_ERR_DEVICE;                     \
+        }                                              \
+    } while (0)
+
+#define GNN_TRY(call)                  \
+    do {                               \
+        gnn_status s_ = (call);        \
+        if (s_ != GNN_OK) return s_;   \
+    } while (0)
+
+#define GNN_LAUNCH_CHECK() GNN_HIP(hipGetLastError())
+
+static inline int64_t gnn_div_up(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// Device allocations that are released together (temporaries of one call).
+struct gnn_temp_pool {
+    std::vector<void *> ptrs;
+    ~gnn_temp_pool() { release(); }
+    void release() {
+        for (void *p : ptrs) (void)hipFree(p);
+        ptrs.clear();
+    }
+    template <typename T>
+    gnn_status get(T **out, size_t count) {
+        void *p = nullptr;
+        if (hipMalloc(&p, (count ? count : 1) * sizeof(T)) != hipSuccess) {
+            (void)hipGetLastError();
+            return GNN_ERR_ALLOC;
+        }
+        ptrs.push_back(p);
+        *out = static_cast<T *>(p);
+        return GNN_OK;
+    }
+    // Hands ownership of p to the caller (it is no longer freed by the pool).
+    void keep(void *p) {
+        for (auto &q : ptrs)
+            if (q == p) { q = ptrs.back(); ptrs.pop_back(); return; }
+    }
+};
+
+struct gnn_graph {
+    int32_t num_nodes = 0;
+    int64_t num_edges = 0;
+    int32_t small_max = 0;   // rows with in-degree <= small_max: one sub-group of a wavefront each
+    int32_t chunk = 0;       // longer rows: pieces of <= chunk edges, one wavefront each
+
+    int32_t *rowptr = nullptr;   // [N+1]
+    int32_t *indeg = nullptr;    // [N]
+    int32_t *colidx = nullptr;   // [E]
+    int32_t *perm = nullptr;     // [E]
+    int32_t *rowidx = nullptr;   // [E] destination of CSR position p (the sorted keys)
+
+    int32_t n_small = 0;
+    int32_t *small_rows = nullptr;      // [n_small] row ids, ascending
+    int32_t n_items = 0;
+    int32_t *item_row = nullptr;        // [n_items]
+    int32_t *item_start = nullptr;      // [n_items] first CSR position of the piece
+    int32_t *item_slot = nullptr;       // [n_items] partial-result slot, or -1 if the piece is a whole row
+    int32_t n_slots = 0;
+    int32_t n_split = 0;
+    int32_t *split_rows = nullptr;      // [n_split] rows made of several pieces
+    int32_t *split_slot0 = nullptr;     // [n_split] first slot of the row (slots are consecutive)
+
+    // Partial results of split rows; grown on demand, shared by all calls on this graph.
+    mutable float *scratch = nullptr;
+    mutable size_t scratch_floats = 0;
+};
+
+// Makes sure g->scratch holds at least `floats` floats.
+gnn_status gnn_graph_reserve_scratch(const gnn_graph *g, size_t floats);
+
+// Exclusive prefix sum of n int32 values; writes n outputs, plus the grand total as
+// output n when append_total.  d_tmp must hold gnn_scan_tmp_elems(n) int32.  in == out is allowed.
+size_t gnn_scan_tmp_elems(int64_t n);
+gnn_status gnn_scan_exclusive_i32(const int32_t *d_in, int32_t *d_out, int64_t n, bool append_total,
+                                  int32_t *d_tmp, hipStream_t stream);
+
+// Epilogue applied to a finished row reduction:  out = post * (acc + self_scale * x[row]) + bias
+// with post = row_scale[row] (or 1), or acc / in-degree for the mean.
+struct gnn_epilogue {
+    int mean = 0;                    // divide by the in-degree (0 stays 0)
+    float self_scale = 0.f;          // adds self_scale * x[row,:] when non-zero
+    const float *row_scale = nullptr;
+    const float *bias = nullptr;
+};
+
+// Shared launcher behind gnn_propagate / gnn_gin_update / the sparse half of gnn_gcnconv.
+gnn_status gnn_launch_propagate(const gnn_graph *g, const float *d_x, int32_t feat_dim,
+                                const float *d_e, int32_t e_dim, gnn_edge_order e_order,
+                                gnn_msg_op msg, int use_max, const gnn_epilogue &epi,
+                                float *d_out, hipStream_t stream);

@@ -1,0 +1,397 @@
+// propagate: gather of source-node feature rows along edges, per-edge message, segmented
+// reduction onto destination nodes (paper section 3, "Message Passing": apply_edges followed
+// by aggregate_neighbors, fused so that the [E x F] messages never exist in memory).
+//
+// Work decomposition over the by-destination CSR, chosen per row by in-degree when the graph
+// is built:
+//   * short rows  (in-degree <= small_max): one sub-group of LPR lanes per row, 64/LPR rows per
+//     wavefront; the sub-group's lanes first fetch the row's neighbour ids (and weights) in one
+//     coalesced load and hand them round by cross-lane shuffles, so all feature-row gathers of
+//     a row are independent loads;
+//   * long rows: pieces of at most `chunk` edges, one wavefront per piece; 64 neighbour ids are
+//     fetched per step, the 64/LPR sub-groups take them round-robin and are combined with
+//     xor-shuffles at the end;
+//   * rows made of several pieces write per-piece partial rows to a scratch buffer and a second
+//     kernel combines them in piece order, so results do not depend on scheduling (no atomics).
+// A lane owns VEC consecutive features (VEC = 4: one 128-bit load per gathered row and lane).
+#include "gnn_internal.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWavesPerBlock = kThreads / 64;
+
+enum { kMsgCopy = 0, kMsgMulScalar = 1, kMsgMulVector = 2 };
+
+struct PropParams {
+    const int32_t *rowptr, *colidx, *perm;
+    const float *x, *e;
+    float *out, *scratch;
+    const int32_t *small_rows, *item_row, *item_start, *item_slot, *split_rows, *split_slot0;
+    int32_t n_small, n_items, n_split, chunk, F, e_coo, item_blocks;
+    int32_t mean;
+    float self_scale;
+    const float *row_scale, *bias;
+};
+
+template <int VEC>
+struct Row {
+    float v[VEC];
+};
+
+template <int VEC>
+__device__ __forceinline__ void load_row(Row<VEC> &r, const float *__restrict__ p)
+{
+    if constexpr (VEC == 4) {
+        const float4 t = *reinterpret_cast<const float4 *>(p);
+        r.v[0] = t.x; r.v[1] = t.y; r.v[2] = t.z; r.v[3] = t.w;
+    } else {
+        r.v[0] = *p;
+    }
+}
+
+template <int VEC>
+__device__ __forceinline__ void store_row(float *__restrict__ p, const Row<VEC> &r)
+{
+    if constexpr (VEC == 4) {
+        *reinterpret_cast<float4 *>(p) = make_float4(r.v[0], r.v[1], r.v[2], r.v[3]);
+    } else {
+        *p = r.v[0];
+    }
+}
+
+// The larger of two finite floats; for the pair (-0, +0) the result is +0.
+__device__ __forceinline__ float max_pz(float a, float b)
+{
+    if (a > b) return a;
+    if (b > a) return b;
+    return __uint_as_float(__float_as_uint(a) & __float_as_uint(b));
+}
+
+template <int VEC, bool MAX>
+__device__ __forceinline__ void set_identity(Row<VEC> &r)
+{
+#pragma unroll
+    for (int c = 0; c < VEC; ++c) r.v[c] = MAX ? -INFINITY : 0.0f;
+}
+
+template <int VEC, bool MAX>
+__device__ __forceinline__ void combine(Row<VEC> &acc, const Row<VEC> &m)
+{
+#pragma unroll
+    for (int c = 0; c < VEC; ++c) acc.v[c] = MAX ? max_pz(acc.v[c], m.v[c]) : acc.v[c] + m.v[c];
+}
+
+// Finishes one output row slice (VEC features starting at col) and stores it.
+template <int VEC, bool MAX>
+__device__ __forceinline__ void finish_row(const PropParams &p, int row, int deg, int col, Row<VEC> acc)
+{
+    if (deg == 0) {
+#pragma unroll
+        for (int c = 0; c < VEC; ++c) acc.v[c] = 0.0f;
+    }
+    if (p.mean && deg > 0) {
+        const float d = (float)deg;
+#pragma unroll
+        for (int c = 0; c < VEC; ++c) acc.v[c] = acc.v[c] / d;
+    }
+    if (p.self_scale != 0.0f) {
+        Row<VEC> xs;
+        load_row<VEC>(xs, p.x + (int64_t)row * p.F + col);
+#pragma unroll
+        for (int c = 0; c < VEC; ++c) acc.v[c] = fmaf(p.self_scale, xs.v[c], acc.v[c]);
+    }
+    if (p.row_scale) {
+        const float s = p.row_scale[row];
+#pragma unroll
+        for (int c = 0; c < VEC; ++c) acc.v[c] *= s;
+    }
+    if (p.bias) {
+#pragma unroll
+        for (int c = 0; c < VEC; ++c) acc.v[c] += p.bias[col + c];
+    }
+    store_row<VEC>(p.out + (int64_t)row * p.F + col, acc);
+}
+
+// One gathered message: loads x[j, col..] (and the element-wise edge row), applies the message op.
+template <int VEC, int MSG, bool MAX>
+__device__ __forceinline__ void fetch_message(const PropParams &p, bool ok, int j, float w, int eid, int col,
+                                              Row<VEC> &m)
+{
+    set_identity<VEC, MAX>(m);
+    if (ok) {
+        load_row<VEC>(m, p.x + (int64_t)j * p.F + col);
+        if constexpr (MSG == kMsgMulScalar) {
+#pragma unroll
+            for (int c = 0; c < VEC; ++c) m.v[c] = w * m.v[c];
+        } else if constexpr (MSG == kMsgMulVector) {
+            Row<VEC> ev;
+            load_row<VEC>(ev, p.e + (int64_t)eid * p.F + col);
+#pragma unroll
+            for (int c = 0; c < VEC; ++c) m.v[c] = ev.v[c] * m.v[c];
+        }
+    }
+}
+
+template <int LPR, int VEC, int MSG, bool MAX>
+__device__ __forceinline__ void short_rows(const PropParams &p, int block)
+{
+    constexpr int NSG = 64 / LPR;
+    constexpr int U = 4;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int sl = lane % LPR, sg = lane / LPR;
+    const int64_t sgid = ((int64_t)block * kWavesPerBlock + wave) * NSG + sg;
+    const bool have = sgid < p.n_small;
+    int row = 0, start = 0, deg = 0;
+    if (have) {
+        row = p.small_rows[sgid];
+        start = p.rowptr[row];
+        deg = p.rowptr[row + 1] - start;
+    }
+    int wmax = deg;   // loop bounds are kept uniform over the wavefront: shuffles run with all lanes active
+#pragma unroll
+    for (int off = LPR; off < 64; off <<= 1) wmax = max(wmax, __shfl_xor(wmax, off, 64));
+
+    for (int cb = 0; cb * LPR * VEC < p.F; ++cb) {
+        const int col = (cb * LPR + sl) * VEC;
+        const bool colok = have && col < p.F;
+        Row<VEC> acc;
+        set_identity<VEC, MAX>(acc);
+        for (int base = 0; base < wmax; base += LPR) {
+            int my_j = 0, my_eid = 0;
+            float my_w = 0.0f;
+            if (base + sl < deg) {
+                const int q = start + base + sl;
+                my_j = p.colidx[q];
+                if constexpr (MSG != kMsgCopy) {
+                    my_eid = p.e_coo ? p.perm[q] : q;
+                    if constexpr (MSG == kMsgMulScalar) my_w = p.e[my_eid];
+                }
+            }
+            const int cnt = min(LPR, wmax - base);
+            for (int t0 = 0; t0 < cnt; t0 += U) {
+                Row<VEC> m[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int t = t0 + u;
+                    const int j = __shfl(my_j, t, LPR);
+                    float w = 0.0f;
+                    int eid = 0;
+                    if constexpr (MSG == kMsgMulScalar) w = __shfl(my_w, t, LPR);
+                    if constexpr (MSG == kMsgMulVector) eid = __shfl(my_eid, t, LPR);
+                    fetch_message<VEC, MSG, MAX>(p, colok && (base + t < deg) && (t < LPR), j, w, eid, col, m[u]);
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) combine<VEC, MAX>(acc, m[u]);
+            }
+        }
+        if (colok) finish_row<VEC, MAX>(p, row, deg, col, acc);
+    }
+}
+
+template <int LPR, int VEC, int MSG, bool MAX>
+__device__ __forceinline__ void long_row_pieces(const PropParams &p, int block)
+{
+    constexpr int NSG = 64 / LPR;
+    constexpr int U = (LPR >= 8) ? 8 : LPR;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int sl = lane % LPR, sg = lane / LPR;
+    const int it = block * kWavesPerBlock + wave;
+    if (it >= p.n_items) return;   // whole wavefront leaves together
+    const int row = p.item_row[it];
+    const int start = p.item_start[it];
+    const int slot = p.item_slot[it];
+    const int row_start = p.rowptr[row], row_end = p.rowptr[row + 1];
+    const int end = min(start + p.chunk, row_end);
+
+    for (int cb = 0; cb * LPR * VEC < p.F; ++cb) {
+        const int col = (cb * LPR + sl) * VEC;
+        const bool colok = col < p.F;
+        Row<VEC> acc;
+        set_identity<VEC, MAX>(acc);
+        for (int base = start; base < end; base += 64) {
+            const int n = min(64, end - base);
+            int my_j = 0, my_eid = 0;
+            float my_w = 0.0f;
+            if (lane < n) {
+                const int q = base + lane;
+                my_j = p.colidx[q];
+                if constexpr (MSG != kMsgCopy) {
+                    my_eid = p.e_coo ? p.perm[q] : q;
+                    if constexpr (MSG == kMsgMulScalar) my_w = p.e[my_eid];
+                }
+            }
+            // sub-group sg takes batch positions sg, sg + NSG, sg + 2*NSG, ...
+            for (int t0 = 0; t0 * NSG < n; t0 += U) {
+                Row<VEC> m[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int pos = (t0 + u) * NSG + sg;   // <= 63 because t0 + u < LPR
+                    const int j = __shfl(my_j, pos, 64);
+                    float w = 0.0f;
+                    int eid = 0;
+                    if constexpr (MSG == kMsgMulScalar) w = __shfl(my_w, pos, 64);
+                    if constexpr (MSG == kMsgMulVector) eid = __shfl(my_eid, pos, 64);
+                    fetch_message<VEC, MSG, MAX>(p, colok && pos < n, j, w, eid, col, m[u]);
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) combine<VEC, MAX>(acc, m[u]);
+            }
+        }
+#pragma unroll
+        for (int off = LPR; off < 64; off <<= 1) {
+            Row<VEC> other;
+#pragma unroll
+            for (int c = 0; c < VEC; ++c) other.v[c] = __shfl_xor(acc.v[c], off, 64);
+            combine<VEC, MAX>(acc, other);
+        }
+        if (sg == 0 && colok) {
+            if (slot < 0)
+                finish_row<VEC, MAX>(p, row, row_end - row_start, col, acc);
+            else
+                store_row<VEC>(p.scratch + (int64_t)slot * p.F + col, acc);
+        }
+    }
+}
+
+// Blocks [0, item_blocks) take the long-row pieces (scheduled first: they are the heaviest),
+// the remaining blocks take the short rows.
+template <int LPR, int VEC, int MSG, bool MAX>
+__global__ __launch_bounds__(kThreads) void propagate_kernel(const PropParams p)
+{
+    if ((int)blockIdx.x < p.item_blocks)
+        long_row_pieces<LPR, VEC, MSG, MAX>(p, blockIdx.x);
+    else
+        short_rows<LPR, VEC, MSG, MAX>(p, blockIdx.x - p.item_blocks);
+}
+
+// Combines the per-piece partial rows of split rows, in piece order.
+template <int LPR, int VEC, bool MAX>
+__global__ __launch_bounds__(kThreads) void combine_pieces_kernel(const PropParams p)
+{
+    const int64_t s = ((int64_t)blockIdx.x * kThreads + threadIdx.x) / LPR;
+    const int sl = threadIdx.x % LPR;
+    if (s >= p.n_split) return;
+    const int row = p.split_rows[s];
+    const int slot0 = p.split_slot0[s];
+    const int deg = p.rowptr[row + 1] - p.rowptr[row];
+    const int pieces = (deg + p.chunk - 1) / p.chunk;
+    for (int cb = 0; cb * LPR * VEC < p.F; ++cb) {
+        const int col = (cb * LPR + sl) * VEC;
+        if (col >= p.F) continue;
+        Row<VEC> acc;
+        set_identity<VEC, MAX>(acc);
+        for (int c = 0; c < pieces; ++c) {
+            Row<VEC> part;
+            load_row<VEC>(part, p.scratch + (int64_t)(slot0 + c) * p.F + col);
+            combine<VEC, MAX>(acc, part);
+        }
+        finish_row<VEC, MAX>(p, row, deg, col, acc);
+    }
+}
+
+template <int LPR, int VEC, int MSG, bool MAX>
+gnn_status launch_typed(const PropParams &p, hipStream_t stream)
+{
+    constexpr int NSG = 64 / LPR;
+    const int64_t small_blocks = gnn_div_up(p.n_small, kWavesPerBlock * NSG);
+    const int64_t blocks = p.item_blocks + small_blocks;
+    if (blocks > 0) {
+        hipLaunchKernelGGL((propagate_kernel<LPR, VEC, MSG, MAX>), dim3((unsigned)blocks), dim3(kThreads), 0, stream,
+                           p);
+        GNN_LAUNCH_CHECK();
+    }
+    if (p.n_split > 0) {
+        const int64_t cblocks = gnn_div_up((int64_t)p.n_split * LPR, kThreads);
+        hipLaunchKernelGGL((combine_pieces_kernel<LPR, VEC, MAX>), dim3((unsigned)cblocks), dim3(kThreads), 0, stream,
+                           p);
+        GNN_LAUNCH_CHECK();
+    }
+    return GNN_OK;
+}
+
+template <int LPR, int VEC>
+gnn_status launch_shape(const PropParams &p, int msg, bool use_max, hipStream_t stream)
+{
+    switch (msg * 2 + (use_max ? 1 : 0)) {
+    case 0: return launch_typed<LPR, VEC, kMsgCopy, false>(p, stream);
+    case 1: return launch_typed<LPR, VEC, kMsgCopy, true>(p, stream);
+    case 2: return launch_typed<LPR, VEC, kMsgMulScalar, false>(p, stream);
+    case 3: return launch_typed<LPR, VEC, kMsgMulScalar, true>(p, stream);
+    case 4: return launch_typed<LPR, VEC, kMsgMulVector, false>(p, stream);
+    case 5: return launch_typed<LPR, VEC, kMsgMulVector, true>(p, stream);
+    }
+    return GNN_ERR_BAD_SIZE;
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+}  // namespace
+
+gnn_status gnn_launch_propagate(const gnn_graph *g, const float *d_x, int32_t feat_dim, const float *d_e,
+                                int32_t e_dim, gnn_edge_order e_order, gnn_msg_op msg, int use_max,
+                                const gnn_epilogue &epi, float *d_out, hipStream_t stream)
+{
+    const int F = feat_dim;
+    int kmsg = kMsgCopy;
+    if (msg == GNN_MSG_E_MUL_XJ) kmsg = (e_dim == 1) ? kMsgMulScalar : kMsgMulVector;
+
+    PropParams p{};
+    p.rowptr = g->rowptr; p.colidx = g->colidx; p.perm = g->perm;
+    p.x = d_x; p.e = d_e; p.out = d_out;
+    p.small_rows = g->small_rows; p.item_row = g->item_row; p.item_start = g->item_start;
+    p.item_slot = g->item_slot; p.split_rows = g->split_rows; p.split_slot0 = g->split_slot0;
+    p.n_small = g->n_small; p.n_items = g->n_items; p.n_split = g->n_split; p.chunk = g->chunk;
+    p.F = F; p.e_coo = (e_order == GNN_EDGE_ORDER_COO) ? 1 : 0;
+    p.item_blocks = (int32_t)gnn_div_up(g->n_items, kWavesPerBlock);
+    p.mean = epi.mean; p.self_scale = epi.self_scale; p.row_scale = epi.row_scale; p.bias = epi.bias;
+
+    if (g->n_slots > 0) GNN_TRY(gnn_graph_reserve_scratch(g, (size_t)g->n_slots * F));
+    p.scratch = g->scratch;
+
+    const bool vec4 = (F % 4 == 0) && aligned16(d_x) && aligned16(d_out) &&
+                      (kmsg != kMsgMulVector || aligned16(d_e));
+    const bool mx = use_max != 0;
+    if (vec4) {
+        const int cols = F / 4;
+        if (cols <= 8) return launch_shape<8, 4>(p, kmsg, mx, stream);
+        if (cols <= 16) return launch_shape<16, 4>(p, kmsg, mx, stream);
+        if (cols <= 32) return launch_shape<32, 4>(p, kmsg, mx, stream);
+        return launch_shape<64, 4>(p, kmsg, mx, stream);
+    }
+    if (F <= 16) return launch_shape<16, 1>(p, kmsg, mx, stream);
+    return launch_shape<64, 1>(p, kmsg, mx, stream);
+}
+
+extern "C" {
+
+gnn_status gnn_propagate(const gnn_graph *g, const float *d_x, int32_t feat_dim, const float *d_e, int32_t e_dim,
+                         gnn_edge_order e_order, gnn_msg_op msg, gnn_aggr aggr, float *d_out, void *stream)
+{
+    if (!g || !d_x || !d_out) return GNN_ERR_NULL;
+    if (feat_dim <= 0) return GNN_ERR_BAD_SIZE;
+    if (msg != GNN_MSG_COPY_XJ && msg != GNN_MSG_E_MUL_XJ) return GNN_ERR_BAD_SIZE;
+    if (aggr != GNN_AGGR_SUM && aggr != GNN_AGGR_MEAN && aggr != GNN_AGGR_MAX) return GNN_ERR_BAD_SIZE;
+    if (msg == GNN_MSG_E_MUL_XJ) {
+        if (e_dim != 1 && e_dim != feat_dim) return GNN_ERR_BAD_SIZE;
+        if (e_order != GNN_EDGE_ORDER_COO && e_order != GNN_EDGE_ORDER_CSR) return GNN_ERR_BAD_SIZE;
+        if (!d_e && g->num_edges > 0) return GNN_ERR_NULL;
+    }
+    gnn_epilogue epi;
+    epi.mean = (aggr == GNN_AGGR_MEAN);
+    return gnn_launch_propagate(g, d_x, feat_dim, d_e, e_dim, e_order, msg, aggr == GNN_AGGR_MAX, epi, d_out,
+                                static_cast<hipStream_t>(stream));
+}
+
+gnn_status gnn_gin_update(const gnn_graph *g, const float *d_x, int32_t feat_dim, float eps, float *d_out,
+                          void *stream)
+{
+    if (!g || !d_x || !d_out) return GNN_ERR_NULL;
+    if (feat_dim <= 0) return GNN_ERR_BAD_SIZE;
+    gnn_epilogue epi;
+    epi.self_scale = 1.0f + eps;
+    return gnn_launch_propagate(g, d_x, feat_dim, nullptr, 1, GNN_EDGE_ORDER_CSR, GNN_MSG_COPY_XJ, 0, epi, d_out,
+                                static_cast<hipStream_t>(stream));
+}
+
+}  // extern "C"

@@ -1,0 +1,65 @@
+"""The C-ABI library loads and exports every symbol include/gnn.h declares (no GPU needed)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+LIB = os.path.join(ROOT, "paper_2412_06354_amd", "libgnn_mi355x.so")
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "gnn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(gnn_[a-z0-9_]+)\s*\(", text)))
+
+
+@pytest.fixture(scope="module")
+def handle():
+    if not os.path.exists(LIB):
+        from paper_2412_06354_amd import build
+        build.build(verbose=False)
+    return ctypes.CDLL(LIB)
+
+
+def test_header_declares_the_five_named_calls():
+    names = declared_symbols()
+    for must in ("gnn_build_csr", "gnn_propagate", "gnn_gcnconv", "gnn_segment_softmax", "gnn_graph_pool"):
+        assert must in names
+
+
+def test_every_declared_symbol_is_exported(handle):
+    for name in declared_symbols():
+        assert hasattr(handle, name), name
+
+
+def test_binding_signatures_cover_the_header():
+    pytest.importorskip("torch")
+    from paper_2412_06354_amd import binding
+    assert sorted(binding.SIGNATURES) == declared_symbols()
+
+
+def test_status_strings(handle):
+    handle.gnn_status_string.restype = ctypes.c_char_p
+    seen = {handle.gnn_status_string(c) for c in range(8)}
+    assert len(seen) == 8 and handle.gnn_status_string(0) == b"ok"
+
+
+def test_host_side_argument_errors_need_no_gpu(handle):
+    # These are rejected before any HIP call is made.
+    out = ctypes.c_void_p()
+    f = handle.gnn_build_csr
+    f.restype = ctypes.c_int
+    f.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p,
+                  ctypes.POINTER(ctypes.c_void_p)]
+    assert f(None, None, 0, 0, None, ctypes.byref(out)) == 2          # N <= 0
+    assert f(None, None, 5, 3, None, ctypes.byref(out)) == 1          # NULL edge arrays
+    assert f(None, None, 1 << 31, 3, None, ctypes.byref(out)) == 2    # too many edges
+    assert f(None, None, 0, 3, None, None) == 1                       # NULL out pointer
+    handle.gnn_gcnconv_workspace_bytes.restype = ctypes.c_size_t
+    handle.gnn_gcnconv_workspace_bytes.argtypes = [ctypes.c_int32, ctypes.c_int32]
+    assert handle.gnn_gcnconv_workspace_bytes(1000, 128) >= 1000 * 128 * 4 + 1000 * 4
+    p = handle.gnn_propagate
+    p.restype = ctypes.c_int
+    assert p(None, None, 4, None, 1, 0, 0, 0, None, None) == 1        # NULL graph

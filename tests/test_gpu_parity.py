@@ -1,0 +1,334 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle, element by element,
+on the same seeded inputs.  Integer / index work and max are compared bit for bit; sums, means,
+softmax and the layers within 1e-5 (see util.assert_close_sabs)."""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+import oracle
+from oracle import AGGR_MAX, AGGR_MEAN, AGGR_SUM, MSG_COPY_XJ, MSG_E_MUL_XJ
+from paper_2412_06354_amd import synth
+from util import assert_close_rel, assert_close_sabs, load_golden
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gnn():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2412_06354_amd import binding
+    binding.lib()   # fails loudly if the library has not been built
+    return binding
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def host(t):
+    return t.cpu().numpy()
+
+
+def powerlaw(n, e, feat, cap):
+    return synth.config2_weighted(num_nodes=n, num_edges=e, feat=feat, cap=cap)
+
+
+GRAPHS = {
+    # name: (builder, small_max, chunk)  -- thresholds chosen so every work-list kind appears
+    "tiny": (lambda: synth.config0_tiny(), 0, 0),
+    "powerlaw_default": (lambda: powerlaw(20_000, 300_000, 64, 6000.0), 0, 0),
+    "powerlaw_split64": (lambda: powerlaw(5_000, 120_000, 64, 3000.0), 4, 64),
+    "uniform_multi": (lambda: synth.Workload("u", 3000, *synth.multigraph_uniform(3000, 50_000, 77),
+                                             synth.normal_f32(77, 2, 3000 * 64).reshape(3000, 64),
+                                             edge_weight=synth.uniform_f32(77, 3, 50_000)), 16, 128),
+}
+
+
+@pytest.fixture(scope="module", params=list(GRAPHS))
+def case(request, gnn):
+    build, small_max, chunk = GRAPHS[request.param]
+    wl = build()
+    if wl.edge_weight is None:
+        wl.edge_weight = synth.uniform_f32(5, 3, wl.num_edges)
+    g = gnn.build_csr(dev(wl.src), dev(wl.dst), wl.num_nodes, small_max, chunk)
+    yield request.param, wl, g
+    g.close()
+
+
+# ----------------------------------------------------------------------------- CSR build
+
+def test_csr_bit_exact(case, gnn):
+    name, wl, g = case
+    rowptr, colidx, perm, indeg = oracle.build_csr(wl.src, wl.dst, wl.num_nodes)
+    np.testing.assert_array_equal(host(g.indegree), indeg)
+    np.testing.assert_array_equal(host(g.rowptr), rowptr)
+    np.testing.assert_array_equal(host(g.perm), perm)
+    np.testing.assert_array_equal(host(g.colidx), colidx)
+    sizes = g.work_sizes()
+    if name == "powerlaw_split64":
+        assert sizes["split_rows"] > 0 and sizes["items"] > sizes["split_rows"] and sizes["small_rows"] > 0
+
+
+def test_csr_hand_worked_and_edge_cases(gnn, golden_dir):
+    gd = load_golden(golden_dir, "g5_propagate.json")
+    src, dst = np.array(gd["src"], np.int32), np.array(gd["dst"], np.int32)
+    g = gnn.build_csr(dev(src), dev(dst), 4)
+    assert host(g.rowptr).tolist() == gd["rowptr"]
+    assert host(g.colidx).tolist() == gd["colidx"]
+    assert host(g.perm).tolist() == gd["perm"]
+    assert host(g.indegree).tolist() == gd["indeg"]
+    x = dev(np.array(gd["x"], np.float32))
+    w = dev(np.array(gd["w"], np.float32))
+    for msg_name, msg in (("copy_xj", MSG_COPY_XJ), ("e_mul_xj", MSG_E_MUL_XJ)):
+        for aggr_name, aggr in (("sum", AGGR_SUM), ("mean", AGGR_MEAN), ("max", AGGR_MAX)):
+            out = gnn.propagate(g, x, w if msg else None, msg, aggr)
+            want = np.array(gd[msg_name][aggr_name], np.float64).astype(np.float32)
+            np.testing.assert_allclose(host(out), want, rtol=1e-6, atol=0, err_msg=f"{msg_name} {aggr_name}")
+    g.close()
+    # no edges at all
+    empty = torch.empty(0, dtype=torch.int32, device="cuda")
+    g0 = gnn.build_csr(empty, empty, 5)
+    assert host(g0.rowptr).tolist() == [0] * 6
+    xx = dev(np.ones((5, 8), np.float32))
+    for aggr in (AGGR_SUM, AGGR_MEAN, AGGR_MAX):
+        assert (host(gnn.propagate(g0, xx, None, MSG_COPY_XJ, aggr)) == 0).all()
+    g0.close()
+    # one node, only self-loops
+    s1 = dev(np.zeros(70, np.int32))
+    g1 = gnn.build_csr(s1, s1, 1)
+    assert host(g1.rowptr).tolist() == [0, 70]
+    assert host(g1.perm).tolist() == list(range(70))
+    assert host(gnn.propagate(g1, dev(np.full((1, 4), 2.0, np.float32))))[0].tolist() == [140.0] * 4
+    g1.close()
+
+
+def test_csr_rejects_out_of_range(gnn):
+    src = dev(np.array([0, 1, 7], np.int32))
+    dst = dev(np.array([1, 2, 0], np.int32))
+    with pytest.raises(gnn.GnnError) as ei:
+        gnn.build_csr(src, dst, 3)
+    assert ei.value.code == 3
+    with pytest.raises(gnn.GnnError):
+        gnn.build_csr(dst, dev(np.array([0, -1, 2], np.int32)), 3)
+
+
+def test_edge_data_to_csr(case, gnn):
+    _, wl, g = case
+    _, _, perm, _ = oracle.build_csr(wl.src, wl.dst, wl.num_nodes)
+    got = host(gnn.edge_data_to_csr(g, dev(wl.edge_weight)))
+    np.testing.assert_array_equal(got, wl.edge_weight[perm])
+    e3 = synth.normal_f32(9, 3, wl.num_edges * 3).reshape(wl.num_edges, 3)
+    np.testing.assert_array_equal(host(gnn.edge_data_to_csr(g, dev(e3))), e3[perm])
+
+
+# ----------------------------------------------------------------------------- propagate
+
+@pytest.mark.parametrize("msg", [MSG_COPY_XJ, MSG_E_MUL_XJ])
+@pytest.mark.parametrize("aggr", [AGGR_SUM, AGGR_MEAN, AGGR_MAX])
+def test_propagate_f64(case, gnn, msg, aggr):
+    name, wl, g = case
+    e = wl.edge_weight if msg == MSG_E_MUL_XJ else None
+    ref, sabs = oracle.propagate(wl.src, wl.dst, wl.num_nodes, wl.x, e, msg, aggr, with_sabs=True)
+    x = dev(wl.x)
+    got = host(gnn.propagate(g, x, dev(e) if e is not None else None, msg, aggr))
+    if aggr == AGGR_MAX:
+        np.testing.assert_array_equal(got.view(np.uint32), ref.view(np.uint32))
+    else:
+        assert_close_sabs(got, ref, sabs, what=f"{name} msg={msg} aggr={aggr}")
+    if msg == MSG_E_MUL_XJ:   # edge data already in CSR order gives the same bits
+        e_csr = gnn.edge_data_to_csr(g, dev(e))
+        got2 = host(gnn.propagate(g, x, e_csr, msg, aggr, e_order=gnn.EDGE_ORDER_CSR))
+        np.testing.assert_array_equal(got2.view(np.uint32), got.view(np.uint32))
+    # run-to-run determinism (no atomics on the path)
+    again = host(gnn.propagate(g, x, dev(e) if e is not None else None, msg, aggr))
+    np.testing.assert_array_equal(again.view(np.uint32), got.view(np.uint32))
+
+
+@pytest.mark.parametrize("feat", [4, 7, 32, 100, 128, 260, 515])
+def test_propagate_feature_widths(gnn, feat):
+    wl = powerlaw(4000, 60_000, feat, 2500.0)
+    g = gnn.build_csr(dev(wl.src), dev(wl.dst), wl.num_nodes, 8, 128)
+    x = dev(wl.x)
+    for msg, e in ((MSG_COPY_XJ, None), (MSG_E_MUL_XJ, wl.edge_weight)):
+        for aggr in (AGGR_SUM, AGGR_MEAN, AGGR_MAX):
+            ref, sabs = oracle.propagate(wl.src, wl.dst, wl.num_nodes, wl.x, e, msg, aggr, with_sabs=True)
+            got = host(gnn.propagate(g, x, dev(e) if e is not None else None, msg, aggr))
+            if aggr == AGGR_MAX:
+                np.testing.assert_array_equal(got.view(np.uint32), ref.view(np.uint32))
+            else:
+                assert_close_sabs(got, ref, sabs, what=f"F={feat} msg={msg} aggr={aggr}")
+    g.close()
+
+
+@pytest.mark.parametrize("feat", [8, 64, 6])
+def test_propagate_elementwise_edge_features(gnn, feat):
+    wl = powerlaw(3000, 40_000, feat, 1500.0)
+    g = gnn.build_csr(dev(wl.src), dev(wl.dst), wl.num_nodes, 8, 64)
+    ef = synth.normal_f32(13, 3, wl.num_edges * feat).reshape(wl.num_edges, feat)
+    for aggr in (AGGR_SUM, AGGR_MEAN, AGGR_MAX):
+        ref, sabs = oracle.propagate(wl.src, wl.dst, wl.num_nodes, wl.x, ef, MSG_E_MUL_XJ, aggr, with_sabs=True)
+        got = host(gnn.propagate(g, dev(wl.x), dev(ef), MSG_E_MUL_XJ, aggr))
+        if aggr == AGGR_MAX:
+            np.testing.assert_array_equal(got.view(np.uint32), ref.view(np.uint32))
+        else:
+            assert_close_sabs(got, ref, sabs, what=f"elementwise F={feat} aggr={aggr}")
+        got_csr = host(gnn.propagate(g, dev(wl.x), gnn.edge_data_to_csr(g, dev(ef)), MSG_E_MUL_XJ, aggr,
+                                     e_order=gnn.EDGE_ORDER_CSR))
+        np.testing.assert_array_equal(got_csr.view(np.uint32), got.view(np.uint32))
+    g.close()
+
+
+def test_propagate_invariants(case, gnn):
+    _, wl, g = case
+    n = wl.num_nodes
+    indeg = np.bincount(wl.dst, minlength=n)
+    ones = dev(np.ones((n, 64), np.float32))
+    np.testing.assert_array_equal(host(gnn.propagate(g, ones))[:, 0], indeg.astype(np.float32))
+    c = dev(np.full((n, 64), 2.5, np.float32))
+    want = np.where(indeg > 0, 2.5, 0.0).astype(np.float32)
+    np.testing.assert_array_equal(host(gnn.propagate(g, c, None, MSG_COPY_XJ, AGGR_MAX))[:, 5], want)
+    np.testing.assert_allclose(host(gnn.propagate(g, c, None, MSG_COPY_XJ, AGGR_MEAN))[:, 5], want, rtol=1e-6)
+
+
+def test_max_signed_zero(gnn):
+    src = dev(np.array([0, 1, 1, 0, 0, 0], np.int32))
+    dst = dev(np.array([2, 2, 3, 3, 1, 1], np.int32))
+    g = gnn.build_csr(src, dst, 4)
+    x = np.array([[-0.0] * 4, [0.0] * 4, [5.0] * 4, [5.0] * 4], np.float32)
+    ref = oracle.propagate(host(src), host(dst), 4, x, None, MSG_COPY_XJ, AGGR_MAX)
+    got = host(gnn.propagate(g, dev(x), None, MSG_COPY_XJ, AGGR_MAX))
+    np.testing.assert_array_equal(got.view(np.uint32), ref.view(np.uint32))
+    assert np.signbit(got[1]).all() and not np.signbit(got[2]).any()
+    g.close()
+
+
+def test_propagate_argument_errors(case, gnn):
+    _, wl, g = case
+    x = dev(wl.x)
+    with pytest.raises(gnn.GnnError):
+        gnn.propagate(g, x, None, MSG_E_MUL_XJ, AGGR_SUM)              # missing edge data
+    with pytest.raises(gnn.GnnError):
+        gnn.propagate(g, x, None, MSG_COPY_XJ, 7)                       # unknown aggregation
+    with pytest.raises(gnn.GnnError):
+        gnn.propagate(g, x, dev(np.zeros((wl.num_edges, 3), np.float32)), MSG_E_MUL_XJ, AGGR_SUM)  # e_dim
+
+
+# ----------------------------------------------------------------------------- layers
+
+def test_dense_xw_matches_numpy(gnn):
+    for rows, k, n in ((1000, 128, 128), (777, 100, 64), (130, 37, 50), (5, 8, 200), (4096, 16, 64)):
+        x = synth.normal_f32(rows + k, 2, rows * k).reshape(rows, k)
+        w = synth.glorot_uniform(n, 4, k, n, (k, n))
+        sc = synth.uniform_f32(3, 5, rows, 0.5, 2.0)
+        ref = x.astype(np.float64) @ w.astype(np.float64)
+        sabs = np.abs(x).astype(np.float64) @ np.abs(w).astype(np.float64)
+        assert_close_sabs(host(gnn.dense_xw(dev(x), dev(w))), ref, sabs, what=f"xw {rows}x{k}x{n}")
+        assert_close_sabs(host(gnn.dense_xw(dev(x), dev(w), dev(sc))), ref * sc[:, None], sabs * sc[:, None],
+                          what=f"xw scaled {rows}x{k}x{n}")
+
+
+@pytest.mark.parametrize("loops", [True, False])
+def test_gcnconv(gnn, loops, golden_dir):
+    gd = load_golden(golden_dir, "path3_gcn.json")
+    g = gnn.build_csr(dev(np.array(gd["src"], np.int32)), dev(np.array(gd["dst"], np.int32)), 3)
+    if loops:
+        out = gnn.gcnconv(g, dev(np.array(gd["x"], np.float32)), dev(np.array(gd["w2"], np.float32)),
+                          dev(np.array(gd["bias2"], np.float32)), True)
+        np.testing.assert_allclose(host(out), np.array(gd["out2"]), rtol=1e-6)
+    g.close()
+    wl = synth.config1_gcn(num_nodes=20_000, pairs=100_000, f_in=128, f_out=128)
+    bias = synth.uniform_f32(8, 5, 128, -1, 1)
+    g = gnn.build_csr(dev(wl.src), dev(wl.dst), wl.num_nodes, 8, 64)
+    ref, sabs = oracle.gcnconv(wl.src, wl.dst, wl.num_nodes, wl.x, wl.params["w"], bias, loops, with_sabs=True)
+    got = host(gnn.gcnconv(g, dev(wl.x), dev(wl.params["w"]), dev(bias), loops))
+    assert_close_sabs(got, ref, sabs, what=f"gcnconv loops={loops}")
+    # fixed point: X = sqrt(d) is reproduced by the normalised operator (W = 1)
+    if loops:
+        d = np.sqrt(np.bincount(wl.dst, minlength=wl.num_nodes) + 1.0).astype(np.float32).reshape(-1, 1)
+        out = host(gnn.gcnconv(g, dev(d), dev(np.ones((1, 1), np.float32)), None, True))
+        np.testing.assert_allclose(out, d, rtol=2e-6)
+    g.close()
+
+
+@pytest.mark.parametrize("heads", [1, 8, 3])
+def test_segment_softmax(case, gnn, heads):
+    name, wl, g = case
+    e = wl.num_edges
+    s = (3.0 * synth.normal_f32(31 + heads, 2, e * heads)).reshape(e, heads)
+    ref = oracle.segment_softmax(wl.dst, wl.num_nodes, s)
+    got = host(gnn.segment_softmax(g, dev(s)))
+    assert_close_rel(got, ref, what=f"softmax {name} H={heads}")
+    # CSR-ordered input/output
+    _, _, perm, _ = oracle.build_csr(wl.src, wl.dst, wl.num_nodes)
+    got_csr = host(gnn.segment_softmax(g, dev(s[perm]), order=gnn.EDGE_ORDER_CSR))
+    np.testing.assert_array_equal(got_csr, got[perm])
+    # sums to one per non-empty destination; shift invariance
+    sums = np.zeros((wl.num_nodes, heads))
+    np.add.at(sums, wl.dst, got.astype(np.float64))
+    has = np.bincount(wl.dst, minlength=wl.num_nodes) > 0
+    np.testing.assert_allclose(sums[has], 1.0, rtol=2e-5)
+    shift = (50.0 * synth.normal_f32(3, 9, wl.num_nodes)).astype(np.float32)
+    got_shift = host(gnn.segment_softmax(g, dev((s + shift[wl.dst][:, None]).astype(np.float32))))
+    np.testing.assert_allclose(got_shift, got, rtol=2e-4, atol=1e-9)
+
+
+@pytest.mark.parametrize("heads,ch,f_in", [(8, 8, 100), (2, 4, 16), (3, 5, 12), (1, 64, 32)])
+def test_gatconv(gnn, heads, ch, f_in):
+    wl = synth.config4_gat(num_nodes=6000, num_edges=150_000, f_in=f_in, heads=heads, ch=ch, cap=3000.0)
+    p = wl.params
+    g = gnn.build_csr(dev(wl.src), dev(wl.dst), wl.num_nodes, 8, 128)
+    ref, sabs = oracle.gatconv(wl.src, wl.dst, wl.num_nodes, wl.x, p["w"], p["a_src"], p["a_dst"], 0.2, with_sabs=True)
+    got = host(gnn.gatconv(g, dev(wl.x), dev(p["w"]), dev(p["a_src"]), dev(p["a_dst"]), 0.2))
+    assert_close_sabs(got, ref, sabs, what=f"gatconv H={heads} ch={ch}")
+    # zero attention vectors: uniform weights -> mean of the projected features
+    zero = np.zeros((heads, ch), np.float32)
+    got0 = host(gnn.gatconv(g, dev(wl.x), dev(p["w"]), dev(zero), dev(zero), 0.2))
+    ref0, sabs0 = oracle.gatconv(wl.src, wl.dst, wl.num_nodes, wl.x, p["w"], zero, zero, 0.2, with_sabs=True)
+    assert_close_sabs(got0, ref0, sabs0, what="gatconv zero attention")
+    g.close()
+
+
+def test_gin_and_pool_batched(gnn):
+    wl = synth.config3_batched()
+    n, ng = wl.num_nodes, wl.num_graphs
+    g = gnn.build_csr(dev(wl.src), dev(wl.dst), n)
+    for eps in (0.0, 0.25):
+        ref, sabs = oracle.gin_update(wl.src, wl.dst, n, wl.x, eps, with_sabs=True)
+        got = gnn.gin_update(g, dev(wl.x), eps)
+        assert_close_sabs(host(got), ref, sabs, what=f"gin eps={eps}")
+    gi = dev(wl.graph_indicator)
+    upd = gnn.gin_update(g, dev(wl.x), 0.0)
+    upd_h = host(upd)
+    for aggr in (AGGR_SUM, AGGR_MEAN, AGGR_MAX):
+        ref, sabs = oracle.graph_pool(wl.graph_indicator, ng, upd_h, aggr, with_sabs=True)
+        got = host(gnn.graph_pool(gi, ng, upd, aggr))
+        if aggr == AGGR_MAX:
+            np.testing.assert_array_equal(got.view(np.uint32), ref.view(np.uint32))
+        else:
+            assert_close_sabs(got, ref, sabs, what=f"pool aggr={aggr}")
+    ones = dev(np.ones((n, 32), np.float32))
+    np.testing.assert_array_equal(host(gnn.graph_pool(gi, ng, ones))[:, 0], np.bincount(wl.graph_indicator, minlength=ng))
+    np.testing.assert_array_equal(host(gnn.gin_update(g, ones, 0.0))[:, 0], 1.0 + np.bincount(wl.dst, minlength=n))
+    # more graph ids than graphs present: trailing empty graphs give zero rows; odd feature width
+    x7 = synth.normal_f32(4, 2, n * 7).reshape(n, 7)
+    ref = oracle.graph_pool(wl.graph_indicator, ng + 3, x7, AGGR_MEAN)
+    got = host(gnn.graph_pool(gi, ng + 3, dev(x7), AGGR_MEAN))
+    np.testing.assert_allclose(got, ref, rtol=1e-5, atol=1e-6)
+    assert (got[ng:] == 0).all()
+    g.close()
+
+
+def test_pool_one_big_graph(gnn):
+    n, f = 50_000, 48
+    x = synth.normal_f32(6, 2, n * f).reshape(n, f)
+    gi = np.zeros(n, np.int32)
+    gi[n // 2:] = 2          # graph 1 is empty
+    for aggr in (AGGR_SUM, AGGR_MEAN, AGGR_MAX):
+        ref, sabs = oracle.graph_pool(gi, 3, x, aggr, with_sabs=True)
+        got = host(gnn.graph_pool(dev(gi), 3, dev(x), aggr))
+        if aggr == AGGR_MAX:
+            np.testing.assert_array_equal(got, ref)
+        else:
+            assert_close_sabs(got, ref, sabs, what=f"big pool aggr={aggr}")
