@@ -24,6 +24,11 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E peak
 
+# Bytes per launch that left the L2s for the default workload, from the hardware-counter runs
+# summarised in profiles/propagate_copy_sum_1M_20M_F64.md (FETCH_SIZE x 2.000 calibration factor
+# + WRITE_SIZE x 1.000).  Only meaningful for the default N/E/F; other sizes report null.
+MEASURED_TRAFFIC_BYTES = {(1_000_000, 20_000_000, 64): int((1302746.4 * 2.0 + 254475.0) * 1024)}
+
 
 def b_alg(n, e, f, weighted=False):
     return e * (4 * f + 4 + (4 if weighted else 0)) + n * 4 * f + (n + 1) * 4
@@ -111,14 +116,16 @@ def main():
     extra = {"graph": stats, "work_lists": g.work_sizes(), "B_alg_bytes": bytes_alg,
              "B_min_bytes": b_min(n, e, f), "t_min_over_t": b_min(n, e, f) / 8e12 / (ms * 1e-3),
              "edge_feature_per_s": e * f / (ms * 1e-3), "csr_build_first_call_ms": build_first_ms}
+    # a plain streaming kernel (read 1 GiB, write 1 GiB) as a second denominator and as the
+    # calibration dispatch for hardware-counter runs
+    big = torch.zeros(256 * 1024 * 1024, dtype=torch.float32, device="cuda")
+    big2 = torch.empty_like(big)
+    copy_ms = time_calls(torch, lambda: torch.add(big, 1.0, out=big2), 10, 2)
+    extra["copy_kernel_GBs"] = 2 * big.numel() * 4 / (copy_ms * 1e-3) / 1e9
+    extra["copy_kernel_bytes_each_way"] = big.numel() * 4
+    del big, big2
     if not args.no_extra:
         k = max(5, args.steps // 10)
-        # plain device-to-device copy as a second denominator
-        big = torch.empty(256 * 1024 * 1024, dtype=torch.float32, device="cuda")
-        big2 = torch.empty_like(big)
-        copy_ms = time_calls(torch, lambda: big2.copy_(big), 20, 3)
-        extra["copy_kernel_GBs"] = 2 * big.numel() * 4 / (copy_ms * 1e-3) / 1e9
-        del big, big2
         e_csr = gnn.edge_data_to_csr(g, ew)
         for name, msg, aggr in (("e_mul_xj_sum", 1, 0), ("e_mul_xj_mean", 1, 1), ("e_mul_xj_max", 1, 2),
                                 ("copy_xj_mean", 0, 1), ("copy_xj_max", 0, 2)):
@@ -146,7 +153,7 @@ def main():
         "config": {"workload": wl.name, "N": n, "E": e, "F": f, "msg": "copy_xj", "aggr": "sum",
                    "seed": synth.seed_of(2)},
         "roofline": {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": gbs / HBM_PEAK_GBS, "traffic": None,
+                     "frac": gbs / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get((n, e, f)),
                      "kernel": "propagate_kernel<16,4,copy_xj,sum> (+ combine_pieces_kernel, a few us)"},
         "extra": extra,
     }

@@ -34,6 +34,8 @@ struct PropParams {
     const float *row_scale, *bias;
 };
 
+typedef float v4f __attribute__((ext_vector_type(4)));
+
 template <int VEC>
 struct Row {
     float v[VEC];
@@ -43,10 +45,23 @@ template <int VEC>
 __device__ __forceinline__ void load_row(Row<VEC> &r, const float *__restrict__ p)
 {
     if constexpr (VEC == 4) {
-        const float4 t = *reinterpret_cast<const float4 *>(p);
+        const v4f t = *reinterpret_cast<const v4f *>(p);
         r.v[0] = t.x; r.v[1] = t.y; r.v[2] = t.z; r.v[3] = t.w;
     } else {
         r.v[0] = *p;
+    }
+}
+
+// Streaming variants: data touched once (edge data, output rows) should not displace the
+// feature rows that are gathered again and again from the caches.
+template <int VEC>
+__device__ __forceinline__ void load_row_stream(Row<VEC> &r, const float *__restrict__ p)
+{
+    if constexpr (VEC == 4) {
+        const v4f t = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(p));
+        r.v[0] = t.x; r.v[1] = t.y; r.v[2] = t.z; r.v[3] = t.w;
+    } else {
+        r.v[0] = __builtin_nontemporal_load(p);
     }
 }
 
@@ -54,11 +69,26 @@ template <int VEC>
 __device__ __forceinline__ void store_row(float *__restrict__ p, const Row<VEC> &r)
 {
     if constexpr (VEC == 4) {
-        *reinterpret_cast<float4 *>(p) = make_float4(r.v[0], r.v[1], r.v[2], r.v[3]);
+        v4f t = {r.v[0], r.v[1], r.v[2], r.v[3]};
+        *reinterpret_cast<v4f *>(p) = t;
     } else {
         *p = r.v[0];
     }
 }
+
+template <int VEC>
+__device__ __forceinline__ void store_row_stream(float *__restrict__ p, const Row<VEC> &r)
+{
+    if constexpr (VEC == 4) {
+        v4f t = {r.v[0], r.v[1], r.v[2], r.v[3]};
+        __builtin_nontemporal_store(t, reinterpret_cast<v4f *>(p));
+    } else {
+        __builtin_nontemporal_store(r.v[0], p);
+    }
+}
+
+__device__ __forceinline__ int load_stream(const int32_t *p) { return __builtin_nontemporal_load(p); }
+__device__ __forceinline__ float load_stream(const float *p) { return __builtin_nontemporal_load(p); }
 
 // The larger of two finite floats; for the pair (-0, +0) the result is +0.
 __device__ __forceinline__ float max_pz(float a, float b)
@@ -110,26 +140,36 @@ __device__ __forceinline__ void finish_row(const PropParams &p, int row, int deg
 #pragma unroll
         for (int c = 0; c < VEC; ++c) acc.v[c] += p.bias[col + c];
     }
-    store_row<VEC>(p.out + (int64_t)row * p.F + col, acc);
+    store_row_stream<VEC>(p.out + (int64_t)row * p.F + col, acc);
 }
 
-// One gathered message: loads x[j, col..] (and the element-wise edge row), applies the message op.
-template <int VEC, int MSG, bool MAX>
-__device__ __forceinline__ void fetch_message(const PropParams &p, bool ok, int j, float w, int eid, int col,
-                                              Row<VEC> &m)
+// Issues the loads of one gathered message: x[j, col..] and, for element-wise edge data, e[eid, col..].
+// Nothing is computed here, so that the loads of several edges are in flight together; the
+// message op is applied afterwards by apply_message.
+template <int VEC, int MSG>
+__device__ __forceinline__ void fetch_message(const PropParams &p, bool ok, int j, int eid, int col, Row<VEC> &xv,
+                                              Row<VEC> &ev)
 {
-    set_identity<VEC, MAX>(m);
+#pragma unroll
+    for (int c = 0; c < VEC; ++c) { xv.v[c] = 0.0f; ev.v[c] = 0.0f; }
     if (ok) {
-        load_row<VEC>(m, p.x + (int64_t)j * p.F + col);
-        if constexpr (MSG == kMsgMulScalar) {
+        load_row<VEC>(xv, p.x + (int64_t)j * p.F + col);
+        if constexpr (MSG == kMsgMulVector) load_row_stream<VEC>(ev, p.e + (int64_t)eid * p.F + col);
+    }
+}
+
+template <int VEC, int MSG, bool MAX>
+__device__ __forceinline__ void apply_message(Row<VEC> &acc, bool ok, const Row<VEC> &xv, float w, const Row<VEC> &ev)
+{
 #pragma unroll
-            for (int c = 0; c < VEC; ++c) m.v[c] = w * m.v[c];
-        } else if constexpr (MSG == kMsgMulVector) {
-            Row<VEC> ev;
-            load_row<VEC>(ev, p.e + (int64_t)eid * p.F + col);
-#pragma unroll
-            for (int c = 0; c < VEC; ++c) m.v[c] = ev.v[c] * m.v[c];
-        }
+    for (int c = 0; c < VEC; ++c) {
+        float m = xv.v[c];
+        if constexpr (MSG == kMsgMulScalar) m = w * m;
+        if constexpr (MSG == kMsgMulVector) m = ev.v[c] * m;
+        if constexpr (MAX)
+            acc.v[c] = ok ? max_pz(acc.v[c], m) : acc.v[c];
+        else
+            acc.v[c] = acc.v[c] + m;   // masked-off edges carry x = 0
     }
 }
 
@@ -162,27 +202,30 @@ __device__ __forceinline__ void short_rows(const PropParams &p, int block)
             float my_w = 0.0f;
             if (base + sl < deg) {
                 const int q = start + base + sl;
-                my_j = p.colidx[q];
+                my_j = load_stream(p.colidx + q);
                 if constexpr (MSG != kMsgCopy) {
-                    my_eid = p.e_coo ? p.perm[q] : q;
-                    if constexpr (MSG == kMsgMulScalar) my_w = p.e[my_eid];
+                    my_eid = p.e_coo ? load_stream(p.perm + q) : q;
+                    if constexpr (MSG == kMsgMulScalar) my_w = load_stream(p.e + my_eid);
                 }
             }
             const int cnt = min(LPR, wmax - base);
             for (int t0 = 0; t0 < cnt; t0 += U) {
-                Row<VEC> m[U];
+                Row<VEC> xv[U], ev[U];
+                float w[U];
+                bool ok[U];
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     const int t = t0 + u;
                     const int j = __shfl(my_j, t, LPR);
-                    float w = 0.0f;
                     int eid = 0;
-                    if constexpr (MSG == kMsgMulScalar) w = __shfl(my_w, t, LPR);
+                    w[u] = 0.0f;
+                    if constexpr (MSG == kMsgMulScalar) w[u] = __shfl(my_w, t, LPR);
                     if constexpr (MSG == kMsgMulVector) eid = __shfl(my_eid, t, LPR);
-                    fetch_message<VEC, MSG, MAX>(p, colok && (base + t < deg) && (t < LPR), j, w, eid, col, m[u]);
+                    ok[u] = colok && (base + t < deg);
+                    fetch_message<VEC, MSG>(p, ok[u], j, eid, col, xv[u], ev[u]);
                 }
 #pragma unroll
-                for (int u = 0; u < U; ++u) combine<VEC, MAX>(acc, m[u]);
+                for (int u = 0; u < U; ++u) apply_message<VEC, MSG, MAX>(acc, ok[u], xv[u], w[u], ev[u]);
             }
         }
         if (colok) finish_row<VEC, MAX>(p, row, deg, col, acc);
@@ -215,27 +258,30 @@ __device__ __forceinline__ void long_row_pieces(const PropParams &p, int block)
             float my_w = 0.0f;
             if (lane < n) {
                 const int q = base + lane;
-                my_j = p.colidx[q];
+                my_j = load_stream(p.colidx + q);
                 if constexpr (MSG != kMsgCopy) {
-                    my_eid = p.e_coo ? p.perm[q] : q;
-                    if constexpr (MSG == kMsgMulScalar) my_w = p.e[my_eid];
+                    my_eid = p.e_coo ? load_stream(p.perm + q) : q;
+                    if constexpr (MSG == kMsgMulScalar) my_w = load_stream(p.e + my_eid);
                 }
             }
             // sub-group sg takes batch positions sg, sg + NSG, sg + 2*NSG, ...
             for (int t0 = 0; t0 * NSG < n; t0 += U) {
-                Row<VEC> m[U];
+                Row<VEC> xv[U], ev[U];
+                float w[U];
+                bool ok[U];
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     const int pos = (t0 + u) * NSG + sg;   // <= 63 because t0 + u < LPR
                     const int j = __shfl(my_j, pos, 64);
-                    float w = 0.0f;
                     int eid = 0;
-                    if constexpr (MSG == kMsgMulScalar) w = __shfl(my_w, pos, 64);
+                    w[u] = 0.0f;
+                    if constexpr (MSG == kMsgMulScalar) w[u] = __shfl(my_w, pos, 64);
                     if constexpr (MSG == kMsgMulVector) eid = __shfl(my_eid, pos, 64);
-                    fetch_message<VEC, MSG, MAX>(p, colok && pos < n, j, w, eid, col, m[u]);
+                    ok[u] = colok && pos < n;
+                    fetch_message<VEC, MSG>(p, ok[u], j, eid, col, xv[u], ev[u]);
                 }
 #pragma unroll
-                for (int u = 0; u < U; ++u) combine<VEC, MAX>(acc, m[u]);
+                for (int u = 0; u < U; ++u) apply_message<VEC, MSG, MAX>(acc, ok[u], xv[u], w[u], ev[u]);
             }
         }
 #pragma unroll
@@ -265,28 +311,46 @@ __global__ __launch_bounds__(kThreads) void propagate_kernel(const PropParams p)
         short_rows<LPR, VEC, MSG, MAX>(p, blockIdx.x - p.item_blocks);
 }
 
-// Combines the per-piece partial rows of split rows, in piece order.
+// Combines the per-piece partial rows of split rows: one wavefront per split row, its sub-groups
+// take the pieces round-robin (four loads in flight each) and are folded with xor-shuffles; the
+// order of combination is a fixed function of the piece count.
 template <int LPR, int VEC, bool MAX>
 __global__ __launch_bounds__(kThreads) void combine_pieces_kernel(const PropParams p)
 {
-    const int64_t s = ((int64_t)blockIdx.x * kThreads + threadIdx.x) / LPR;
-    const int sl = threadIdx.x % LPR;
-    if (s >= p.n_split) return;
+    constexpr int NSG = 64 / LPR;
+    constexpr int U = 4;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int sl = lane % LPR, sg = lane / LPR;
+    const int s = blockIdx.x * kWavesPerBlock + wave;
+    if (s >= p.n_split) return;   // whole wavefront leaves together
     const int row = p.split_rows[s];
     const int slot0 = p.split_slot0[s];
     const int deg = p.rowptr[row + 1] - p.rowptr[row];
     const int pieces = (deg + p.chunk - 1) / p.chunk;
     for (int cb = 0; cb * LPR * VEC < p.F; ++cb) {
         const int col = (cb * LPR + sl) * VEC;
-        if (col >= p.F) continue;
+        const bool colok = col < p.F;
         Row<VEC> acc;
         set_identity<VEC, MAX>(acc);
-        for (int c = 0; c < pieces; ++c) {
-            Row<VEC> part;
-            load_row<VEC>(part, p.scratch + (int64_t)(slot0 + c) * p.F + col);
-            combine<VEC, MAX>(acc, part);
+        for (int c0 = sg; c0 < pieces; c0 += NSG * U) {
+            Row<VEC> part[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int c = c0 + u * NSG;
+                set_identity<VEC, MAX>(part[u]);
+                if (colok && c < pieces) load_row<VEC>(part[u], p.scratch + (int64_t)(slot0 + c) * p.F + col);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) combine<VEC, MAX>(acc, part[u]);
         }
-        finish_row<VEC, MAX>(p, row, deg, col, acc);
+#pragma unroll
+        for (int off = LPR; off < 64; off <<= 1) {
+            Row<VEC> other;
+#pragma unroll
+            for (int c = 0; c < VEC; ++c) other.v[c] = __shfl_xor(acc.v[c], off, 64);
+            combine<VEC, MAX>(acc, other);
+        }
+        if (sg == 0 && colok) finish_row<VEC, MAX>(p, row, deg, col, acc);
     }
 }
 
@@ -302,7 +366,7 @@ gnn_status launch_typed(const PropParams &p, hipStream_t stream)
         GNN_LAUNCH_CHECK();
     }
     if (p.n_split > 0) {
-        const int64_t cblocks = gnn_div_up((int64_t)p.n_split * LPR, kThreads);
+        const int64_t cblocks = gnn_div_up(p.n_split, kWavesPerBlock);
         hipLaunchKernelGGL((combine_pieces_kernel<LPR, VEC, MAX>), dim3((unsigned)cblocks), dim3(kThreads), 0, stream,
                            p);
         GNN_LAUNCH_CHECK();
