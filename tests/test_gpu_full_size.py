@@ -1,0 +1,173 @@
+"""GPU parity at the benchmark configurations' full sizes, in the launch configuration bench.py times.
+
+The kernels run on the whole graph; the CPU oracle either runs on the whole graph too (where that takes
+seconds) or on sampled destination rows: a destination's result depends only on its incoming edges and on
+the features of their endpoints, so the test extracts those edges, relabels the touched nodes compactly and
+runs the oracle on that subgraph (tests/util.subgraph_for_rows).  Hub rows, ordinary rows and rows without
+incoming edges are all in the sample.
+"""
+import sys
+
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+import oracle
+from oracle import AGGR_MAX, AGGR_MEAN, AGGR_SUM, MSG_COPY_XJ, MSG_E_MUL_XJ
+from paper_2412_06354_amd import synth
+from util import assert_close_rel, assert_close_sabs, subgraph_for_rows
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(msg, file=sys.stderr, flush=True)
+
+
+@pytest.fixture(scope="module")
+def gnn():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2412_06354_amd import binding
+    binding.lib()
+    return binding
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def host(t):
+    return t.cpu().numpy()
+
+
+def sample_rows(dst, n, count, seed):
+    """Random rows + the highest in-degree rows + some rows without incoming edges."""
+    indeg = np.bincount(dst, minlength=n)
+    rnd = synth.randint(seed, 9, 0, count, 0, n - 1)
+    hubs = np.argsort(indeg)[-4:]
+    empty = np.flatnonzero(indeg == 0)[:8]
+    mid = np.flatnonzero((indeg > 400) & (indeg < 3000))[:16]
+    return np.unique(np.concatenate([rnd, hubs, empty, mid])).astype(np.int64)
+
+
+# ----------------------------------------------------------------------------- configuration 2
+
+@pytest.fixture(scope="module")
+def cfg2(gnn):
+    say("config 2: generating 1M nodes / 20M edges")
+    wl = synth.config2_weighted()
+    g = gnn.build_csr(dev(wl.src), dev(wl.dst), wl.num_nodes)
+    say("config 2: graph built")
+    yield wl, g
+    g.close()
+
+
+def test_config2_csr_bit_exact(cfg2):
+    wl, g = cfg2
+    rowptr, colidx, perm, indeg = oracle.build_csr(wl.src, wl.dst, wl.num_nodes)
+    np.testing.assert_array_equal(host(g.indegree), indeg)
+    np.testing.assert_array_equal(host(g.rowptr), rowptr)
+    np.testing.assert_array_equal(host(g.perm), perm)
+    np.testing.assert_array_equal(host(g.colidx), colidx)
+
+
+@pytest.mark.parametrize("msg", [MSG_COPY_XJ, MSG_E_MUL_XJ])
+def test_config2_propagate_sampled_rows(cfg2, gnn, msg):
+    wl, g = cfg2
+    n = wl.num_nodes
+    rows = sample_rows(wl.dst, n, 3000, 21)
+    s_src, s_dst, nodes, local_rows, eid = subgraph_for_rows(wl.src, wl.dst, rows)
+    xs = wl.x[nodes]
+    es = wl.edge_weight[eid] if msg == MSG_E_MUL_XJ else None
+    x = dev(wl.x)
+    e_csr = gnn.edge_data_to_csr(g, dev(wl.edge_weight)) if msg == MSG_E_MUL_XJ else None
+    for aggr in (AGGR_SUM, AGGR_MEAN, AGGR_MAX):
+        ref, sabs = oracle.propagate(s_src, s_dst, nodes.shape[0], xs, es, msg, aggr, with_sabs=True)
+        got = host(gnn.propagate(g, x, e_csr, msg, aggr, e_order=gnn.EDGE_ORDER_CSR)[torch.from_numpy(rows).cuda()])
+        if aggr == AGGR_MAX:
+            np.testing.assert_array_equal(got.view(np.uint32), ref[local_rows].view(np.uint32))
+        else:
+            assert_close_sabs(got, ref[local_rows], sabs[local_rows], what=f"config2 msg={msg} aggr={aggr}")
+        say(f"config 2: msg={msg} aggr={aggr} ok on {rows.shape[0]} sampled rows ({eid.shape[0]} edges)")
+
+
+def test_config2_invariants_at_full_size(cfg2, gnn):
+    wl, g = cfg2
+    n = wl.num_nodes
+    indeg = np.bincount(wl.dst, minlength=n)
+    ones = torch.ones((n, 64), dtype=torch.float32, device="cuda")
+    out = gnn.propagate(g, ones)
+    np.testing.assert_array_equal(host(out[:, 0]), indeg.astype(np.float32))      # exact: integers < 2^24
+    np.testing.assert_array_equal(host(out[:, 63]), indeg.astype(np.float32))
+    mx = gnn.propagate(g, ones * 2.5, None, MSG_COPY_XJ, AGGR_MAX)
+    np.testing.assert_array_equal(host(mx[:, 7]), np.where(indeg > 0, 2.5, 0.0).astype(np.float32))
+    # unit weights reproduce copy_xj bit for bit
+    x = dev(wl.x)
+    w1 = torch.ones(wl.num_edges, dtype=torch.float32, device="cuda")
+    a = gnn.propagate(g, x)
+    b = gnn.propagate(g, x, w1, MSG_E_MUL_XJ, AGGR_SUM)
+    assert torch.equal(a, b)
+
+
+def test_config2_segment_softmax_sampled_rows(cfg2, gnn):
+    wl, g = cfg2
+    n, e, heads = wl.num_nodes, wl.num_edges, 8
+    s = (3.0 * synth.normal_f32(55, 2, e * heads)).reshape(e, heads)
+    got_all = gnn.segment_softmax(g, dev(s))
+    rows = sample_rows(wl.dst, n, 3000, 22)
+    s_src, s_dst, nodes, local_rows, eid = subgraph_for_rows(wl.src, wl.dst, rows)
+    ref = oracle.segment_softmax(s_dst, nodes.shape[0], s[eid])
+    got = host(got_all[torch.from_numpy(eid).cuda()])
+    assert_close_rel(got, ref, what="config2 segment softmax")
+
+
+# ----------------------------------------------------------------------------- configuration 1
+
+def test_config1_gcnconv_full(gnn):
+    say("config 1: generating 100k nodes / 1M edges")
+    wl = synth.config1_gcn()
+    g = gnn.build_csr(dev(wl.src), dev(wl.dst), wl.num_nodes)
+    rowptr, colidx, perm, _ = oracle.build_csr(wl.src, wl.dst, wl.num_nodes)
+    np.testing.assert_array_equal(host(g.rowptr), rowptr)
+    np.testing.assert_array_equal(host(g.perm), perm)
+    w, b = wl.params["w"], wl.params["bias"]
+    ref, sabs = oracle.gcnconv(wl.src, wl.dst, wl.num_nodes, wl.x, w, b, True, with_sabs=True)
+    got = host(gnn.gcnconv(g, dev(wl.x), dev(w), dev(b), True))
+    assert_close_sabs(got, ref, sabs, what="config1 gcnconv")
+    g.close()
+
+
+# ----------------------------------------------------------------------------- configuration 4
+
+def test_config4_gatconv_sampled_rows(gnn):
+    say("config 4: generating 2.45M nodes / 126M edges (about a minute)")
+    wl = synth.config4_gat()
+    p = wl.params
+    n = wl.num_nodes
+    say("config 4: building CSR on the GPU")
+    g = gnn.build_csr(dev(wl.src), dev(wl.dst), n)
+    indeg = np.bincount(wl.dst, minlength=n)
+    np.testing.assert_array_equal(host(g.indegree), indeg)
+    rp = host(g.rowptr)
+    assert rp[0] == 0 and rp[-1] == wl.num_edges
+    np.testing.assert_array_equal(np.diff(rp), indeg)
+    say("config 4: running the layer")
+    out = gnn.gatconv(g, dev(wl.x), dev(p["w"]), dev(p["a_src"]), dev(p["a_dst"]), p["negative_slope"])
+    torch.cuda.synchronize()
+    rows = sample_rows(wl.dst, n, 400, 23)
+    s_src, s_dst, nodes, local_rows, eid = subgraph_for_rows(wl.src, wl.dst, rows)
+    say(f"config 4: oracle on {rows.shape[0]} sampled rows, {eid.shape[0]} edges, {nodes.shape[0]} nodes")
+    # CSR order of the sampled rows: stable by original edge id
+    perm = host(g.perm)
+    colidx = host(g.colidx)
+    for r in rows[:50]:
+        seg = perm[rp[r]:rp[r + 1]]
+        assert (np.diff(seg) > 0).all() and (wl.dst[seg] == r).all()
+        np.testing.assert_array_equal(colidx[rp[r]:rp[r + 1]], wl.src[seg])
+    ref, sabs = oracle.gatconv(s_src, s_dst, nodes.shape[0], wl.x[nodes], p["w"], p["a_src"], p["a_dst"],
+                               p["negative_slope"], with_sabs=True)
+    got = host(out[torch.from_numpy(rows).cuda()])
+    assert_close_sabs(got, ref[local_rows], sabs[local_rows], what="config4 gatconv")
+    g.close()

@@ -73,7 +73,9 @@ def subgraph_for_rows(src, dst, rows):
     features, so running a reference on this subgraph reproduces those rows of the full result.
     Returns (sub_src, sub_dst, nodes, local_rows, edge_ids)."""
     rows = np.asarray(rows)
-    mask = np.isin(dst, rows)
+    lut = np.zeros(int(max(dst.max(initial=0), rows.max(initial=0))) + 1, dtype=bool)
+    lut[rows] = True
+    mask = lut[dst]
     eid = np.flatnonzero(mask)
     nodes = np.unique(np.concatenate([rows, src[eid], dst[eid]]))
     s = np.searchsorted(nodes, src[eid]).astype(np.int32)
