@@ -1,6 +1,7 @@
-// COO -> CSR by destination: in-degree histogram with range check, exclusive scan to rowptr,
-// stable least-significant-digit radix sort of (dst; src, edge id), and the degree-bucketed
-// work lists used by the compute kernels.
+// COO -> CSR by destination: index range check, stable least-significant-digit radix sort of
+// (dst; src, edge id), in-degree histogram (read off the runs of the sorted destinations, so
+// hub nodes cost no contended atomics), exclusive scan to rowptr, and the degree-bucketed work
+// lists used by the compute kernels.
 //
 // The paper (section 3, "Graph Data Structures") keeps topology in COO form by default and
 // treats the sparse adjacency as another encoding of the same graph; this file derives the
@@ -12,23 +13,42 @@ namespace {
 
 constexpr int kThreads = 256;
 
-// ---------------------------------------------------------------- in-degree histogram
+// ---------------------------------------------------------------- range check, in-degree histogram
 
-__global__ __launch_bounds__(kThreads) void indegree_kernel(const int32_t *__restrict__ src,
-                                                            const int32_t *__restrict__ dst, int64_t E, int32_t N,
-                                                            int32_t *__restrict__ indeg, int32_t *__restrict__ bad)
+__global__ __launch_bounds__(kThreads) void check_range_kernel(const int32_t *__restrict__ src,
+                                                               const int32_t *__restrict__ dst, int64_t E, int32_t N,
+                                                               int32_t *__restrict__ bad)
 {
     const int64_t stride = (int64_t)gridDim.x * kThreads;
     int any_bad = 0;
     for (int64_t k = (int64_t)blockIdx.x * kThreads + threadIdx.x; k < E; k += stride) {
-        const int32_t s = src[k], d = dst[k];
-        if ((uint32_t)s >= (uint32_t)N || (uint32_t)d >= (uint32_t)N) {
-            any_bad = 1;
-        } else {
-            atomicAdd(&indeg[d], 1);
-        }
+        const int32_t s = __builtin_nontemporal_load(src + k), d = __builtin_nontemporal_load(dst + k);
+        any_bad |= ((uint32_t)s >= (uint32_t)N) | ((uint32_t)d >= (uint32_t)N);
     }
     if (any_bad) atomicOr(bad, 1);
+}
+
+// In-degree histogram from the sorted destinations: every destination that occurs forms one run;
+// the first kernel records where each run starts, the second (a separate launch, so that all
+// starts are visible) writes run length = in-degree at each run's last element.  Rows that do not
+// occur keep the 0 they were cleared to.
+__global__ __launch_bounds__(kThreads) void run_starts_kernel(const int32_t *__restrict__ keys, int64_t E,
+                                                              int32_t *__restrict__ starts)
+{
+    const int64_t p = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (p >= E) return;
+    const int32_t k = keys[p];
+    if (p == 0 || keys[p - 1] != k) starts[k] = (int32_t)p;
+}
+
+__global__ __launch_bounds__(kThreads) void run_lengths_kernel(const int32_t *__restrict__ keys, int64_t E,
+                                                               const int32_t *__restrict__ starts,
+                                                               int32_t *__restrict__ indeg)
+{
+    const int64_t p = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (p >= E) return;
+    const int32_t k = keys[p];
+    if (p == E - 1 || keys[p + 1] != k) indeg[k] = (int32_t)(p + 1) - starts[k];
 }
 
 // ---------------------------------------------------------------- radix sort passes
@@ -58,28 +78,54 @@ __global__ __launch_bounds__(kThreads) void sort_count_kernel(const int32_t *__r
     for (int d = threadIdx.x; d < radix; d += kThreads) tile_counts[(int64_t)d * num_tiles + blockIdx.x] = cnt[d];
 }
 
+__device__ __forceinline__ int block_exclusive_scan_256(int v, int *wave_sums /* [kWaves] in LDS */)
+{
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    int inc = v;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int t = __shfl_up(inc, off, 64);
+        if (lane >= off) inc += t;
+    }
+    if (lane == 63) wave_sums[w] = inc;
+    __syncthreads();
+    int base = 0;
+#pragma unroll
+    for (int i = 0; i < kWaves; ++i)
+        if (i < w) base += wave_sums[i];
+    return base + inc - v;
+}
+
 // Stable scatter of one pass.  Inside a tile the order is: wavefront, then item, then lane;
 // key `idx` of wavefront w is tile_base + w*64*items + item*64 + lane, so this order is the
-// input order.  A key's output position is
-//   (first position of its digit in this tile) + (same-digit keys of earlier wavefronts)
-//   + (same-digit keys of this wavefront in earlier items or lower lanes).
-// The last term comes from ballots: the lanes holding the same digit are found bit by bit.
+// input order.  A key's position inside the tile's digit-sorted order is
+//   (keys of smaller digits in the tile) + (same-digit keys of earlier wavefronts)
+//   + (same-digit keys of this wavefront in earlier items or lower lanes);
+// the last term comes from ballots: the lanes holding the same digit are found bit by bit.
+// Keys, values and edge ids are then passed through LDS in that order, so that consecutive
+// threads write consecutive global addresses (each digit of a tile is one contiguous run).
 __global__ __launch_bounds__(kThreads) void sort_scatter_kernel(
     const int32_t *__restrict__ keys_in, const int32_t *__restrict__ val_in, const int32_t *__restrict__ eid_in,
     int64_t n, int shift, int bits, const int32_t *__restrict__ tile_offsets, int num_tiles,
     int32_t *__restrict__ keys_out, int32_t *__restrict__ val_out, int32_t *__restrict__ eid_out)
 {
     __shared__ int wcnt[kWaves][kRadixMax];
+    __shared__ int dbase[kRadixMax];   // first tile-local position of each digit
+    __shared__ int gbase[kRadixMax];   // global position of that element minus dbase
+    __shared__ int wave_sums[kWaves];
+    __shared__ int stage[kSortTile];
     const int radix = 1 << bits, mask = radix - 1;
     const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
     for (int d = threadIdx.x; d < kWaves * kRadixMax; d += kThreads) (&wcnt[0][0])[d] = 0;
     __syncthreads();
 
-    const int64_t wbase = (int64_t)blockIdx.x * kSortTile + (int64_t)w * 64 * kSortItems;
+    const int64_t tile_base = (int64_t)blockIdx.x * kSortTile;
+    const int64_t wbase = tile_base + (int64_t)w * 64 * kSortItems;
+    const int tile_count = (int)min((int64_t)kSortTile, n - tile_base);
     const uint64_t lt_mask = (1ull << lane) - 1ull;
     volatile int *my_cnt = wcnt[w];
     int key[kSortItems];
-    int rank[kSortItems];
+    int lpos[kSortItems];
 #pragma unroll
     for (int i = 0; i < kSortItems; ++i) {
         const int64_t idx = wbase + i * 64 + lane;
@@ -99,17 +145,24 @@ __global__ __launch_bounds__(kThreads) void sort_scatter_kernel(
         if (valid && r == 0) my_cnt[d] = before + __popcll(peers);
         __builtin_amdgcn_wave_barrier();
         key[i] = k;
-        rank[i] = before + r;
+        lpos[i] = before + r;
     }
     __syncthreads();
-    for (int d = threadIdx.x; d < radix; d += kThreads) {
-        int run = tile_offsets[(int64_t)d * num_tiles + blockIdx.x];
+    // per digit: offsets of the wavefronts inside the digit, digit totals -> tile-local digit bases
+    int total = 0;
+    if ((int)threadIdx.x < radix) {
+        const int d = threadIdx.x;
 #pragma unroll
         for (int q = 0; q < kWaves; ++q) {
             const int c = wcnt[q][d];
-            wcnt[q][d] = run;
-            run += c;
+            wcnt[q][d] = total;
+            total += c;
         }
+    }
+    const int excl = block_exclusive_scan_256(total, wave_sums);
+    if ((int)threadIdx.x < radix) {
+        dbase[threadIdx.x] = excl;
+        gbase[threadIdx.x] = tile_offsets[(int64_t)threadIdx.x * num_tiles + blockIdx.x] - excl;
     }
     __syncthreads();
 #pragma unroll
@@ -117,12 +170,42 @@ __global__ __launch_bounds__(kThreads) void sort_scatter_kernel(
         const int64_t idx = wbase + i * 64 + lane;
         if (idx < n) {
             const int d = (key[i] >> shift) & mask;
-            const int pos = wcnt[w][d] + rank[i];
-            if (keys_out) keys_out[pos] = key[i];
-            val_out[pos] = val_in[idx];
-            eid_out[pos] = eid_in ? eid_in[idx] : (int32_t)idx;
+            lpos[i] += dbase[d] + wcnt[w][d];
+            stage[lpos[i]] = key[i];
         }
     }
+    __syncthreads();
+    int gpos[kSortItems];
+#pragma unroll
+    for (int i = 0; i < kSortItems; ++i) {
+        const int s = i * kThreads + threadIdx.x;
+        gpos[i] = -1;
+        if (s < tile_count) {
+            const int k = stage[s];
+            gpos[i] = gbase[(k >> shift) & mask] + s;
+            if (keys_out) keys_out[gpos[i]] = k;
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < kSortItems; ++i) {
+        const int64_t idx = wbase + i * 64 + lane;
+        if (idx < n) stage[lpos[i]] = val_in[idx];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < kSortItems; ++i)
+        if (gpos[i] >= 0) val_out[gpos[i]] = stage[i * kThreads + threadIdx.x];
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < kSortItems; ++i) {
+        const int64_t idx = wbase + i * 64 + lane;
+        if (idx < n) stage[lpos[i]] = eid_in ? eid_in[idx] : (int32_t)idx;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < kSortItems; ++i)
+        if (gpos[i] >= 0) eid_out[gpos[i]] = stage[i * kThreads + threadIdx.x];
 }
 
 __global__ __launch_bounds__(kThreads) void iota_copy_kernel(const int32_t *__restrict__ key_in,
@@ -215,56 +298,78 @@ int ceil_log2(uint32_t n)
 
 void free_graph_arrays(gnn_graph *g)
 {
-    void *ptrs[] = {g->rowptr,     g->indeg,     g->colidx,     g->perm,       g->rowidx,  g->small_rows,
-                    g->item_row,   g->item_start, g->item_slot, g->split_rows, g->split_slot0, g->scratch};
+    void *ptrs[] = {g->slab_csr, g->slab_lists, g->scratch};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
+    g->slab_csr = g->slab_lists = nullptr;
+    g->scratch = nullptr;
 }
 
-template <typename T>
-gnn_status dev_alloc(T **out, size_t count)
+// Carves 256-byte aligned int32 arrays out of one device allocation.
+struct slab_plan {
+    size_t bytes = 0;
+    size_t add(size_t count) {
+        const size_t off = bytes;
+        bytes += ((count ? count : 1) * sizeof(int32_t) + 255) & ~(size_t)255;
+        return off;
+    }
+};
+
+gnn_status slab_alloc(void **out, size_t bytes)
 {
-    void *p = nullptr;
-    if (hipMalloc(&p, (count ? count : 1) * sizeof(T)) != hipSuccess) {
+    *out = nullptr;
+    if (hipMalloc(out, bytes ? bytes : 256) != hipSuccess) {
         (void)hipGetLastError();
+        *out = nullptr;
         return GNN_ERR_ALLOC;
     }
-    *out = static_cast<T *>(p);
     return GNN_OK;
 }
+
+int32_t *at(void *slab, size_t off) { return reinterpret_cast<int32_t *>(static_cast<char *>(slab) + off); }
 
 gnn_status build_impl(const int32_t *d_src, const int32_t *d_dst, int64_t E, int32_t N, hipStream_t stream,
                       gnn_graph *g)
 {
-    gnn_temp_pool tmp;
-    GNN_TRY(dev_alloc(&g->rowptr, (size_t)N + 1));
-    GNN_TRY(dev_alloc(&g->indeg, (size_t)N));
-    GNN_TRY(dev_alloc(&g->colidx, (size_t)E));
-    GNN_TRY(dev_alloc(&g->perm, (size_t)E));
-    GNN_TRY(dev_alloc(&g->rowidx, (size_t)E));
+    const size_t np1 = (size_t)N + 1;
+    const int64_t num_tiles = gnn_div_up(E, kSortTile);
 
-    // ---- in-degree + range check
-    int32_t *d_flag;
-    GNN_TRY(tmp.get(&d_flag, 8));
-    GNN_HIP(hipMemsetAsync(d_flag, 0, 8 * sizeof(int32_t), stream));
+    // ---- arrays the graph keeps
+    slab_plan pa;
+    const size_t o_rowptr = pa.add(np1), o_indeg = pa.add(N), o_colidx = pa.add(E), o_perm = pa.add(E),
+                 o_rowidx = pa.add(E);
+    GNN_TRY(slab_alloc(&g->slab_csr, pa.bytes));
+    g->rowptr = at(g->slab_csr, o_rowptr);
+    g->indeg = at(g->slab_csr, o_indeg);
+    g->colidx = at(g->slab_csr, o_colidx);
+    g->perm = at(g->slab_csr, o_perm);
+    g->rowidx = at(g->slab_csr, o_rowidx);
+
+    // ---- temporaries, one allocation, freed when this function returns
+    slab_plan pt;
+    const size_t scan_elems = std::max(gnn_scan_tmp_elems((int64_t)np1), gnn_scan_tmp_elems(num_tiles * kRadixMax));
+    const size_t o_flag = pt.add(64), o_scan = pt.add(scan_elems), o_kb = pt.add(E), o_vb = pt.add(E),
+                 o_eb = pt.add(E), o_counts = pt.add((size_t)num_tiles * kRadixMax), o_starts = pt.add(N),
+                 o_flags = pt.add(4 * np1), o_pos = pt.add(4 * np1);
+    gnn_temp_pool tmp;
+    char *ts;
+    GNN_TRY(tmp.get(&ts, pt.bytes));
+    int32_t *d_flag = at(ts, o_flag), *scan_tmp = at(ts, o_scan), *kb = at(ts, o_kb), *vb = at(ts, o_vb),
+            *eb = at(ts, o_eb), *counts = at(ts, o_counts), *starts = at(ts, o_starts), *flags = at(ts, o_flags),
+            *pos = at(ts, o_pos);
+
+    // ---- index range check (one flag read back)
+    GNN_HIP(hipMemsetAsync(d_flag, 0, 64 * sizeof(int32_t), stream));
     GNN_HIP(hipMemsetAsync(g->indeg, 0, (size_t)N * sizeof(int32_t), stream));
     if (E > 0) {
-        const int blocks = (int)std::min<int64_t>(gnn_div_up(E, kThreads), 256 * 32);
-        hipLaunchKernelGGL(indegree_kernel, dim3(blocks), dim3(kThreads), 0, stream, d_src, d_dst, E, N, g->indeg,
-                           d_flag);
+        const int blocks = (int)std::min<int64_t>(gnn_div_up(E, kThreads), 256 * 16);
+        hipLaunchKernelGGL(check_range_kernel, dim3(blocks), dim3(kThreads), 0, stream, d_src, d_dst, E, N, d_flag);
         GNN_LAUNCH_CHECK();
     }
     int32_t h_flag = 0;
     GNN_HIP(hipMemcpyAsync(&h_flag, d_flag, sizeof(int32_t), hipMemcpyDeviceToHost, stream));
     GNN_HIP(hipStreamSynchronize(stream));
     if (h_flag) return GNN_ERR_INDEX_RANGE;
-
-    // ---- rowptr
-    int32_t *scan_tmp;
-    const int64_t num_tiles = gnn_div_up(E, kSortTile);
-    const size_t scan_elems = std::max(gnn_scan_tmp_elems((int64_t)N + 1), gnn_scan_tmp_elems(num_tiles * kRadixMax));
-    GNN_TRY(tmp.get(&scan_tmp, scan_elems));
-    GNN_TRY(gnn_scan_exclusive_i32(g->indeg, g->rowptr, N, true, scan_tmp, stream));
 
     // ---- stable radix sort by destination
     if (E > 0) {
@@ -277,11 +382,6 @@ gnn_status build_impl(const int32_t *d_src, const int32_t *d_dst, int64_t E, int
         } else {
             const int passes = (key_bits + 7) / 8;
             const int bits = (key_bits + passes - 1) / passes;
-            int32_t *kb, *vb, *eb, *counts;
-            GNN_TRY(tmp.get(&kb, (size_t)E));
-            GNN_TRY(tmp.get(&vb, (size_t)E));
-            GNN_TRY(tmp.get(&eb, (size_t)E));
-            GNN_TRY(tmp.get(&counts, (size_t)num_tiles * kRadixMax));
             // Ping-pong between (kb, vb, eb) and the arrays the graph keeps, arranged so that
             // the last pass writes into the graph's arrays.
             int32_t *bufk[2] = {kb, g->rowidx}, *bufv[2] = {vb, g->colidx}, *bufe[2] = {eb, g->perm};
@@ -303,13 +403,19 @@ gnn_status build_impl(const int32_t *d_src, const int32_t *d_dst, int64_t E, int
                 dst_sel ^= 1;
             }
         }
+        // ---- in-degree histogram from the runs of the sorted destinations
+        const unsigned eblocks = (unsigned)gnn_div_up(E, kThreads);
+        hipLaunchKernelGGL(run_starts_kernel, dim3(eblocks), dim3(kThreads), 0, stream, g->rowidx, E, starts);
+        GNN_LAUNCH_CHECK();
+        hipLaunchKernelGGL(run_lengths_kernel, dim3(eblocks), dim3(kThreads), 0, stream, g->rowidx, E, starts,
+                           g->indeg);
+        GNN_LAUNCH_CHECK();
     }
 
+    // ---- rowptr = exclusive scan of the in-degrees
+    GNN_TRY(gnn_scan_exclusive_i32(g->indeg, g->rowptr, N, true, scan_tmp, stream));
+
     // ---- work lists
-    int32_t *flags, *pos;
-    const size_t np1 = (size_t)N + 1;
-    GNN_TRY(tmp.get(&flags, 4 * np1));
-    GNN_TRY(tmp.get(&pos, 4 * np1));
     const int nblocks = (int)gnn_div_up(N, kThreads);
     hipLaunchKernelGGL(classify_rows_kernel, dim3(nblocks), dim3(kThreads), 0, stream, g->indeg, N, g->small_max,
                        g->chunk, flags, flags + np1, flags + 2 * np1, flags + 3 * np1);
@@ -324,12 +430,16 @@ gnn_status build_impl(const int32_t *d_src, const int32_t *d_dst, int64_t E, int
     g->n_items = totals[1];
     g->n_slots = totals[2];
     g->n_split = totals[3];
-    GNN_TRY(dev_alloc(&g->small_rows, (size_t)g->n_small));
-    GNN_TRY(dev_alloc(&g->item_row, (size_t)g->n_items));
-    GNN_TRY(dev_alloc(&g->item_start, (size_t)g->n_items));
-    GNN_TRY(dev_alloc(&g->item_slot, (size_t)g->n_items));
-    GNN_TRY(dev_alloc(&g->split_rows, (size_t)g->n_split));
-    GNN_TRY(dev_alloc(&g->split_slot0, (size_t)g->n_split));
+    slab_plan pl;
+    const size_t o_small = pl.add(g->n_small), o_irow = pl.add(g->n_items), o_istart = pl.add(g->n_items),
+                 o_islot = pl.add(g->n_items), o_srows = pl.add(g->n_split), o_sslot = pl.add(g->n_split);
+    GNN_TRY(slab_alloc(&g->slab_lists, pl.bytes));
+    g->small_rows = at(g->slab_lists, o_small);
+    g->item_row = at(g->slab_lists, o_irow);
+    g->item_start = at(g->slab_lists, o_istart);
+    g->item_slot = at(g->slab_lists, o_islot);
+    g->split_rows = at(g->slab_lists, o_srows);
+    g->split_slot0 = at(g->slab_lists, o_sslot);
     hipLaunchKernelGGL(fill_lists_kernel, dim3(nblocks), dim3(kThreads), 0, stream, g->rowptr, N, g->small_max,
                        g->chunk, pos, pos + np1, pos + 2 * np1, pos + 3 * np1, g->small_rows, g->item_row,
                        g->item_start, g->item_slot, g->split_rows, g->split_slot0);

@@ -62,6 +62,9 @@ struct gnn_graph {
     int32_t small_max = 0;   // rows with in-degree <= small_max: one sub-group of a wavefront each
     int32_t chunk = 0;       // longer rows: pieces of <= chunk edges, one wavefront each
 
+    void *slab_csr = nullptr;     // one allocation holding rowptr, indeg, colidx, perm, rowidx
+    void *slab_lists = nullptr;   // one allocation holding the work lists
+
     int32_t *rowptr = nullptr;   // [N+1]
     int32_t *indeg = nullptr;    // [N]
     int32_t *colidx = nullptr;   // [E]
