@@ -1,17 +1,25 @@
 #!/usr/bin/env python3
-"""Benchmark of the propagate hot path on one MI355X.
+"""Benchmark of the message-passing hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
 
-Workload: the weighted-propagate-at-scale configuration (1 M nodes, 20 M directed edges from a
-seeded power-law multigraph, fp32 features F = 64), all inputs resident in HBM before timing.
-One step = one gnn_propagate(copy_xj, sum) over the whole graph (the by-destination CSR is built
-once per graph, as a training loop reuses it across layers and epochs; its build time and the
-other message/aggregation variants are reported in the same line under "extra").
+Default workload `propagate` (the headline): the weighted-propagate-at-scale configuration (1 M nodes,
+20 M directed edges from a seeded power-law multigraph, fp32 features F = 64), all inputs resident in
+HBM before timing.  One step = one gnn_propagate(copy_xj, sum) over the whole graph; the
+by-destination CSR is built once per graph, as a training loop reuses it across layers and epochs
+(its build time and the other message/aggregation variants are reported under "extra").
 
-Prints ONE JSON line.  value = algorithmic GB/s of the step:
-  B_alg = E*(4F + 4) + N*4F + (N+1)*4  bytes  (one source row gathered per edge + neighbour ids
-          + output rows + rowptr), divided by the mean step time.
+Other workloads measure the remaining steps of the path, one JSON line each:
+  csr      COO -> CSR build (range check, radix sort, degree histogram, scan, work lists) on the same graph
+  softmax  gnn_segment_softmax, 8 heads, on the same graph
+  gcn      gnn_gcnconv on the 100 k-node / 1 M-edge symmetrised power-law graph, 128 -> 128 features
+  gat      gnn_gatconv on the 2.45 M-node / 126 M-edge graph, 100 -> 8 heads x 8 channels
+  batched  gnn_gin_update + gnn_graph_pool on 4 096 batched small graphs, F = 32
+  tiny     gnn_propagate sum / mean / max on the 2 708-node graph (launch-latency bound)
+
+Every line carries `value` (algorithmic GB/s = the byte model of the step / mean step time), a
+`roofline` object for the dominant kernel and a `cpu_baseline` object (the parity oracle, one thread,
+timed in the same run on a bounded sample).  Byte models are spelled out next to each workload.
 """
 import argparse
 import json
@@ -22,7 +30,8 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-HBM_PEAK_GBS = 8000.0   # MI355X HBM3E peak
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E peak
+MFMA_FP32_PEAK_TFLOPS = 157.3
 
 # Bytes per launch that left the L2s for the default workload, from the hardware-counter runs
 # summarised in profiles/propagate_copy_sum_1M_20M_F64.md (FETCH_SIZE x 2.000 calibration factor
@@ -30,12 +39,14 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E peak
 MEASURED_TRAFFIC_BYTES = {(1_000_000, 20_000_000, 64): int((1302746.4 * 2.0 + 254475.0) * 1024)}
 
 
-def b_alg(n, e, f, weighted=False):
-    return e * (4 * f + 4 + (4 if weighted else 0)) + n * 4 * f + (n + 1) * 4
+def b_alg_propagate(n, e, f, e_dim=0):
+    """One source row gathered per edge + neighbour id (+ edge data) + output rows + rowptr."""
+    return e * (4 * f + 4 + 4 * e_dim) + n * 4 * f + (n + 1) * 4
 
 
-def b_min(n, e, f, weighted=False):
-    return 2 * n * 4 * f + e * (4 + (4 if weighted else 0)) + (n + 1) * 4
+def b_min_propagate(n, e, f, e_dim=0):
+    """Every array touched exactly once."""
+    return 2 * n * 4 * f + e * (4 + 4 * e_dim) + (n + 1) * 4
 
 
 def time_calls(torch, fn, steps, warmup):
@@ -52,18 +63,303 @@ def time_calls(torch, fn, steps, warmup):
     return start.elapsed_time(stop) / steps
 
 
-def cpu_baseline(wl, sample_edges):
-    """The parity oracle as it stands (one thread, double accumulators) on a prefix of the edge list."""
-    import oracle
-    e = min(sample_edges, wl.num_edges)
-    src, dst = wl.src[:e].copy(), wl.dst[:e].copy()
+def streaming_probe(torch):
+    """A plain streaming kernel (reads 1 GiB, writes 1 GiB): second denominator next to the spec-sheet
+    peak, and the calibration dispatch for hardware-counter runs."""
+    big = torch.zeros(256 * 1024 * 1024, dtype=torch.float32, device="cuda")
+    big2 = torch.empty_like(big)
+    ms = time_calls(torch, lambda: torch.add(big, 1.0, out=big2), 10, 2)
+    return {"copy_kernel_GBs": 2 * big.numel() * 4 / (ms * 1e-3) / 1e9, "copy_kernel_bytes_each_way": big.numel() * 4}
+
+
+def hbm_roofline(gbs, kernel, traffic=None):
+    return {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
+            "traffic": traffic, "kernel": kernel}
+
+
+def base_line(metric, gbs, ms, args, workload, config):
+    cfg = {"workload": workload}
+    cfg.update(config)
+    return {"metric": metric, "value": gbs, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+            "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+            "data": "synthetic", "config": cfg}
+
+
+def to_dev(torch, a):
+    return torch.from_numpy(a).cuda()
+
+
+# ----------------------------------------------------------------------------- workloads
+
+def run_propagate(args, torch, gnn, synth):
+    wl = synth.config2_weighted(num_nodes=args.nodes, num_edges=args.edges, feat=args.feat)
+    n, e, f = wl.num_nodes, wl.num_edges, args.feat
+    src, dst, x, ew = (to_dev(torch, a) for a in (wl.src, wl.dst, wl.x, wl.edge_weight))
+    out = torch.empty_like(x)
     t0 = time.perf_counter()
-    oracle.propagate(src, dst, wl.num_nodes, wl.x)
-    dt = time.perf_counter() - t0
-    n, f = wl.x.shape
-    return {"value": b_alg(n, e, f) / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
-            "sample": f"copy_xj+sum over the first {e} of {wl.num_edges} edges (all {n} nodes, F={f}), "
-                      f"one pass, {dt:.1f} s", "seconds": dt, "edge_feature_per_s": e * f / dt}
+    g = gnn.build_csr(src, dst, n)
+    torch.cuda.synchronize()
+    build_first_ms = (time.perf_counter() - t0) * 1e3
+
+    ms = time_calls(torch, lambda: gnn.propagate(g, x, None, gnn.MSG_COPY_XJ, gnn.AGGR_SUM, out=out),
+                    args.steps, args.warmup)
+    bytes_alg = b_alg_propagate(n, e, f)
+    gbs = bytes_alg / (ms * 1e-3) / 1e9
+    extra = {"graph": wl.stats(), "work_lists": g.work_sizes(), "B_alg_bytes": bytes_alg,
+             "B_min_bytes": b_min_propagate(n, e, f), "t_min_over_t": b_min_propagate(n, e, f) / 8e12 / (ms * 1e-3),
+             "edge_feature_per_s": e * f / (ms * 1e-3), "csr_build_first_call_ms": build_first_ms}
+    extra.update(streaming_probe(torch))
+    if not args.no_extra:
+        k = max(5, args.steps // 10)
+        e_csr = gnn.edge_data_to_csr(g, ew)
+        for name, msg, aggr in (("e_mul_xj_sum", 1, 0), ("e_mul_xj_mean", 1, 1), ("e_mul_xj_max", 1, 2),
+                                ("copy_xj_mean", 0, 1), ("copy_xj_max", 0, 2)):
+            ed = e_csr if msg else None
+            t = time_calls(torch, lambda: gnn.propagate(g, x, ed, msg, aggr, e_order=gnn.EDGE_ORDER_CSR, out=out), k, 3)
+            extra[name] = {"ms": t, "GBs_alg": b_alg_propagate(n, e, f, msg) / (t * 1e-3) / 1e9}
+        t = time_calls(torch, lambda: gnn.propagate(g, x, ew, 1, 0, e_order=gnn.EDGE_ORDER_COO, out=out), k, 3)
+        extra["e_mul_xj_sum_coo_order"] = {"ms": t, "GBs_alg": b_alg_propagate(n, e, f, 1) / (t * 1e-3) / 1e9}
+        extra["edge_data_to_csr_ms"] = time_calls(torch, lambda: gnn.edge_data_to_csr(g, ew), k, 2)
+        t0 = time.perf_counter()
+        for _ in range(3):
+            gnn.build_csr(src, dst, n).close()
+        extra["csr_build_ms"] = (time.perf_counter() - t0) / 3 * 1e3
+        extra["full_path_ms"] = extra["csr_build_ms"] + extra["edge_data_to_csr_ms"] + ms
+
+    line = base_line("propagate(copy_xj,sum) algorithmic GB/s, 1M-node/20M-edge power-law graph, F=64", gbs, ms, args,
+                     wl.name, {"N": n, "E": e, "F": f, "msg": "copy_xj", "aggr": "sum", "seed": synth.seed_of(2)})
+    line["roofline"] = hbm_roofline(gbs, "propagate_kernel<16,4,copy_xj,sum> (+ combine_pieces_kernel, ~10 us)",
+                                    MEASURED_TRAFFIC_BYTES.get((n, e, f)))
+    line["extra"] = extra
+    if not args.no_cpu_baseline:
+        import oracle
+        es = min(args.cpu_sample_edges, e)
+        t0 = time.perf_counter()
+        oracle.propagate(wl.src[:es].copy(), wl.dst[:es].copy(), n, wl.x)
+        dt = time.perf_counter() - t0
+        line["cpu_baseline"] = {"value": b_alg_propagate(n, es, f) / dt / 1e9, "unit": "GB/s", "cores": 1,
+                                "kind": "oracle", "seconds": dt, "edge_feature_per_s": es * f / dt,
+                                "sample": f"copy_xj+sum over the first {es} of {e} edges (all {n} nodes, F={f}), one pass"}
+    g.close()
+    return line
+
+
+def run_csr(args, torch, gnn, synth):
+    wl = synth.config2_weighted(num_nodes=args.nodes, num_edges=args.edges, feat=4)
+    n, e = wl.num_nodes, wl.num_edges
+    src, dst = to_dev(torch, wl.src), to_dev(torch, wl.dst)
+    gnn.build_csr(src, dst, n).close()
+    torch.cuda.synchronize()
+    k = max(3, min(args.steps, 20))
+    t0 = time.perf_counter()
+    for _ in range(k):
+        gnn.build_csr(src, dst, n).close()     # synchronises internally
+    ms = (time.perf_counter() - t0) / k * 1e3
+    passes = max(1, ((max(n - 1, 1)).bit_length() + 7) // 8)
+    # per pass: keys read twice (count + scatter) + two payloads read + three arrays written = 28 B/edge;
+    # plus range check (8 B/edge), run detection (2 x 4 B/edge) and the row-sized scans and lists (~60 B/node)
+    bytes_alg = e * (28 * passes + 16) + n * 60
+    gbs = bytes_alg / (ms * 1e-3) / 1e9
+    line = base_line("CSR-by-destination build, algorithmic GB/s (host wall clock per gnn_build_csr incl. allocations)",
+                     gbs, ms, args, wl.name + ":csr_build", {"N": n, "E": e, "radix_passes": passes})
+    line["steps"] = k
+    line["roofline"] = hbm_roofline(gbs, "sort_scatter_kernel x%d dominates" % passes)
+    line["extra"] = {"B_alg_bytes": bytes_alg, "edges_per_s": e / (ms * 1e-3)}
+    if not args.no_cpu_baseline:
+        import oracle
+        t0 = time.perf_counter()
+        oracle.build_csr(wl.src, wl.dst, n)
+        dt = time.perf_counter() - t0
+        line["cpu_baseline"] = {"value": bytes_alg / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+                                "seconds": dt, "sample": "the whole edge list, one counting sort"}
+    return line
+
+
+def run_softmax(args, torch, gnn, synth):
+    heads = 8
+    wl = synth.config2_weighted(num_nodes=args.nodes, num_edges=args.edges, feat=4)
+    n, e = wl.num_nodes, wl.num_edges
+    g = gnn.build_csr(to_dev(torch, wl.src), to_dev(torch, wl.dst), n)
+    s_host = (3.0 * synth.normal_f32(55, 2, e * heads)).reshape(e, heads)
+    s = to_dev(torch, s_host)
+    out = torch.empty_like(s)
+    ms = time_calls(torch, lambda: gnn.segment_softmax(g, s, out=out), args.steps, args.warmup)
+    # scores read twice, weights written once, perm + row id per edge for each pass, (max, den) per row and head
+    bytes_alg = e * heads * 4 * 3 + e * 4 * 3 + n * heads * 8 * 2
+    gbs = bytes_alg / (ms * 1e-3) / 1e9
+    line = base_line("segment softmax (8 heads, COO-ordered scores) algorithmic GB/s", gbs, ms, args,
+                     wl.name + ":segment_softmax", {"N": n, "E": e, "heads": heads})
+    line["roofline"] = hbm_roofline(gbs, "normalise_kernel + stats kernels")
+    line["extra"] = {"B_alg_bytes": bytes_alg, "edge_head_per_s": e * heads / (ms * 1e-3)}
+    s_csr = gnn.edge_data_to_csr(g, s)
+    t = time_calls(torch, lambda: gnn.segment_softmax(g, s_csr, order=gnn.EDGE_ORDER_CSR, out=out), max(5, args.steps // 4), 3)
+    line["extra"]["csr_ordered_ms"] = t
+    if not args.no_cpu_baseline:
+        import oracle
+        es = min(args.cpu_sample_edges, e)
+        t0 = time.perf_counter()
+        oracle.segment_softmax(wl.dst[:es].copy(), n, s_host[:es])
+        dt = time.perf_counter() - t0
+        line["cpu_baseline"] = {"value": (es * heads * 12 + es * 12 + n * heads * 16) / dt / 1e9, "unit": "GB/s",
+                                "cores": 1, "kind": "oracle", "seconds": dt,
+                                "sample": f"the first {es} of {e} edges, 8 heads"}
+    g.close()
+    return line
+
+
+def run_gcn(args, torch, gnn, synth):
+    wl = synth.config1_gcn()
+    n, e, f_in = wl.num_nodes, wl.num_edges, wl.x.shape[1]
+    w_h, b_h = wl.params["w"], wl.params["bias"]
+    f_out = w_h.shape[1]
+    g = gnn.build_csr(to_dev(torch, wl.src), to_dev(torch, wl.dst), n)
+    x, w, b = to_dev(torch, wl.x), to_dev(torch, w_h), to_dev(torch, b_h)
+    out = torch.empty((n, f_out), dtype=torch.float32, device="cuda")
+    ws = torch.empty(int(gnn.lib().gnn_gcnconv_workspace_bytes(n, f_out)), dtype=torch.uint8, device="cuda")
+    ms = time_calls(torch, lambda: gnn.gcnconv(g, x, w, b, True, out=out, workspace=ws), args.steps, args.warmup)
+    z = torch.empty_like(out)
+    ms_xw = time_calls(torch, lambda: gnn.dense_xw(x, w, out=z), args.steps, args.warmup)
+    ms_sp = time_calls(torch, lambda: gnn.gin_update(g, z, 0.0, out=out), args.steps, args.warmup)
+    flops = 2.0 * n * f_in * f_out
+    bytes_xw = 4 * (n * f_in + f_in * f_out + n * f_out)
+    # sparse half: one Z row per edge and per (analytic) self-loop + ids + output + rowptr + degree factors
+    bytes_sp = (e + n) * (4 * f_out + 4) + n * 4 * f_out + (n + 1) * 4 + n * 8
+    gbs = (bytes_xw + bytes_sp) / (ms * 1e-3) / 1e9
+    line = base_line("GCNConv forward (X W on MFMA + fused normalised SpMM) algorithmic GB/s", gbs, ms, args, wl.name,
+                     {"N": n, "E": e, "f_in": f_in, "f_out": f_out, "add_self_loops": True})
+    line["roofline"] = hbm_roofline(bytes_sp / (ms_sp * 1e-3) / 1e9,
+                                    "propagate_kernel<32,4,copy_xj,sum> with GCN epilogue (timed alone through "
+                                    "gnn_gin_update on Z: same gathers, same epilogue shape)")
+    line["extra"] = {"graph": wl.stats(), "xw_ms": ms_xw, "spmm_ms": ms_sp, "B_alg_spmm_bytes": bytes_sp,
+                     "xw_roofline": {"bound": "mfma", "achieved": flops / (ms_xw * 1e-3) / 1e12,
+                                     "peak": MFMA_FP32_PEAK_TFLOPS, "unit": "TFLOP/s",
+                                     "frac": flops / (ms_xw * 1e-3) / 1e12 / MFMA_FP32_PEAK_TFLOPS,
+                                     "hbm_GBs": bytes_xw / (ms_xw * 1e-3) / 1e9, "kernel": "xw_kernel<4,true>"}}
+    if not args.no_cpu_baseline:
+        import oracle
+        t0 = time.perf_counter()
+        oracle.gcnconv(wl.src, wl.dst, n, wl.x, w_h, b_h, True)
+        dt = time.perf_counter() - t0
+        line["cpu_baseline"] = {"value": (bytes_xw + bytes_sp) / dt / 1e9, "unit": "GB/s", "cores": 1,
+                                "kind": "oracle", "seconds": dt, "sample": "the whole layer, one pass"}
+    g.close()
+    return line
+
+
+def run_gat(args, torch, gnn, synth):
+    wl = synth.config4_gat()
+    p = wl.params
+    n, e, f_in = wl.num_nodes, wl.num_edges, wl.x.shape[1]
+    heads, ch = p["heads"], p["ch"]
+    hc = heads * ch
+    g = gnn.build_csr(to_dev(torch, wl.src), to_dev(torch, wl.dst), n)
+    x, w, a_s, a_d = (to_dev(torch, a) for a in (wl.x, p["w"], p["a_src"], p["a_dst"]))
+    out = torch.empty((n, hc), dtype=torch.float32, device="cuda")
+    ws = torch.empty(int(gnn.lib().gnn_gatconv_workspace_bytes(n, heads, ch)), dtype=torch.uint8, device="cuda")
+    steps = max(3, min(args.steps, 30))
+    ms = time_calls(torch, lambda: gnn.gatconv(g, x, w, a_s, a_d, 0.2, out=out, workspace=ws), steps, 3)
+    h = torch.empty_like(out)
+    ms_xw = time_calls(torch, lambda: gnn.dense_xw(x, w, out=h), steps, 3)
+    flops = 2.0 * n * f_in * hc
+    bytes_xw = 4 * (n * f_in + f_in * hc + n * hc)
+    # attention pass: per edge one h row + its source scores + neighbour id; per node output, both score rows, rowptr
+    bytes_att = e * (4 * hc + 4 * heads + 4) + n * (4 * hc + 8 * heads + 4) + n * 4 * hc + n * 8 * heads
+    ms_att = ms - ms_xw
+    gbs = (bytes_xw + bytes_att) / (ms * 1e-3) / 1e9
+    line = base_line("GAT layer forward (X W on MFMA + fused score/softmax/aggregate) algorithmic GB/s", gbs, ms, args,
+                     wl.name, {"N": n, "E": e, "f_in": f_in, "heads": heads, "ch": ch})
+    line["steps"] = steps
+    line["roofline"] = hbm_roofline(bytes_att / (ms_att * 1e-3) / 1e9,
+                                    "gat_kernel<16,4> (+ node_scores_kernel, gat_merge_kernel); time = layer - X W")
+    line["extra"] = {"xw_ms": ms_xw, "attention_ms": ms_att, "B_alg_attention_bytes": bytes_att,
+                     "edge_feature_per_s": e * hc / (ms_att * 1e-3), "work_lists": g.work_sizes(),
+                     "xw_roofline": {"bound": "mfma", "achieved": flops / (ms_xw * 1e-3) / 1e12,
+                                     "peak": MFMA_FP32_PEAK_TFLOPS, "unit": "TFLOP/s",
+                                     "frac": flops / (ms_xw * 1e-3) / 1e12 / MFMA_FP32_PEAK_TFLOPS,
+                                     "hbm_GBs": bytes_xw / (ms_xw * 1e-3) / 1e9, "kernel": "xw_kernel<2,true>"}}
+    if not args.no_cpu_baseline:
+        import oracle
+        es = min(args.cpu_sample_edges // 4, e)        # a prefix of the edge list over a node prefix
+        ns = min(n, 200_000)
+        m = (wl.src[:es] < ns) & (wl.dst[:es] < ns)
+        s_src, s_dst = wl.src[:es][m].copy(), wl.dst[:es][m].copy()
+        t0 = time.perf_counter()
+        oracle.gatconv(s_src, s_dst, ns, wl.x[:ns], p["w"], p["a_src"], p["a_dst"], 0.2)
+        dt = time.perf_counter() - t0
+        ee = int(s_src.shape[0])
+        b = 4 * (ns * f_in + f_in * hc + ns * hc) + ee * (4 * hc + 4 * heads + 4) + ns * (8 * hc + 16 * heads + 4)
+        line["cpu_baseline"] = {"value": b / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle", "seconds": dt,
+                                "sample": f"the layer on the first {ns} nodes and the {ee} edges among them"}
+    g.close()
+    return line
+
+
+def run_batched(args, torch, gnn, synth):
+    wl = synth.config3_batched()
+    n, e, f, ng = wl.num_nodes, wl.num_edges, wl.x.shape[1], wl.num_graphs
+    g = gnn.build_csr(to_dev(torch, wl.src), to_dev(torch, wl.dst), n)
+    x, gi = to_dev(torch, wl.x), to_dev(torch, wl.graph_indicator)
+    upd = torch.empty_like(x)
+    pooled = torch.empty((ng, f), dtype=torch.float32, device="cuda")
+
+    def step():
+        gnn.gin_update(g, x, 0.0, out=upd)
+        gnn.graph_pool(gi, ng, upd, gnn.AGGR_SUM, out=pooled)
+
+    ms = time_calls(torch, step, args.steps, args.warmup)
+    ms_gin = time_calls(torch, lambda: gnn.gin_update(g, x, 0.0, out=upd), args.steps, args.warmup)
+    ms_pool = time_calls(torch, lambda: gnn.graph_pool(gi, ng, upd, gnn.AGGR_SUM, out=pooled), args.steps, args.warmup)
+    bytes_gin = e * (4 * f + 4) + 3 * n * 4 * f + (n + 1) * 4
+    bytes_pool = n * 4 * f + n * 4 + ng * 4 * f
+    gbs = (bytes_gin + bytes_pool) / (ms * 1e-3) / 1e9
+    line = base_line("GIN update + sum pooling on 4096 batched small graphs, algorithmic GB/s", gbs, ms, args, wl.name,
+                     {"N": n, "E": e, "F": f, "graphs": ng})
+    line["roofline"] = hbm_roofline(bytes_gin / (ms_gin * 1e-3) / 1e9, "propagate_kernel<8,4,copy_xj,sum> with self term")
+    line["extra"] = {"gin_ms": ms_gin, "pool_ms": ms_pool, "pool_GBs": bytes_pool / (ms_pool * 1e-3) / 1e9,
+                     "note": "the whole problem (13 MB of features) fits the caches: launch latency dominates"}
+    if not args.no_cpu_baseline:
+        import oracle
+        t0 = time.perf_counter()
+        u = oracle.gin_update(wl.src, wl.dst, n, wl.x, 0.0)
+        oracle.graph_pool(wl.graph_indicator, ng, u)
+        dt = time.perf_counter() - t0
+        line["cpu_baseline"] = {"value": (bytes_gin + bytes_pool) / dt / 1e9, "unit": "GB/s", "cores": 1,
+                                "kind": "oracle", "seconds": dt, "sample": "the whole batch, one pass"}
+    g.close()
+    return line
+
+
+def run_tiny(args, torch, gnn, synth):
+    wl = synth.config0_tiny()
+    n, e, f = wl.num_nodes, wl.num_edges, wl.x.shape[1]
+    g = gnn.build_csr(to_dev(torch, wl.src), to_dev(torch, wl.dst), n)
+    x = to_dev(torch, wl.x)
+    out = torch.empty_like(x)
+    times = {}
+    for name, aggr in (("sum", 0), ("mean", 1), ("max", 2)):
+        times[name] = time_calls(torch, lambda: gnn.propagate(g, x, None, 0, aggr, out=out), args.steps, args.warmup)
+    ms = times["sum"]
+    bytes_alg = b_alg_propagate(n, e, f)
+    gbs = bytes_alg / (ms * 1e-3) / 1e9
+    line = base_line("tiny propagate (2708 nodes): algorithmic GB/s (launch-latency bound; see us_per_call)", gbs, ms,
+                     args, wl.name, {"N": n, "E": e, "F": f})
+    line["roofline"] = hbm_roofline(gbs, "propagate_kernel<16,4,copy_xj,sum>")
+    line["extra"] = {"us_per_call": {k: v * 1e3 for k, v in times.items()}}
+    if not args.no_cpu_baseline:
+        import oracle
+        t0 = time.perf_counter()
+        reps = 200
+        for _ in range(reps):
+            oracle.propagate(wl.src, wl.dst, n, wl.x)
+        dt = (time.perf_counter() - t0) / reps
+        line["cpu_baseline"] = {"value": bytes_alg / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+                                "seconds": dt, "sample": "the whole graph, mean of 200 passes"}
+    g.close()
+    return line
+
+
+WORKLOADS = {"propagate": run_propagate, "csr": run_csr, "softmax": run_softmax, "gcn": run_gcn, "gat": run_gat,
+             "batched": run_batched, "tiny": run_tiny}
 
 
 def main():
@@ -71,6 +367,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", choices=sorted(WORKLOADS), default="propagate")
     ap.add_argument("--nodes", type=int, default=1_000_000)
     ap.add_argument("--edges", type=int, default=20_000_000)
     ap.add_argument("--feat", type=int, default=64)
@@ -79,88 +376,19 @@ def main():
     ap.add_argument("--no-extra", action="store_true", help="time only the headline step")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on exactly one GPU (no sharding, no collectives); "
-              "use --gpus 1", file=sys.stderr)
+        print("bench.py: this build runs on exactly one GPU (no sharding, no collectives); use --gpus 1",
+              file=sys.stderr)
         sys.exit(2)
 
-    import numpy as np
     import torch
     from paper_2412_06354_amd import binding as gnn, synth
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(3)
-    gnn.lib()
+    gnn.lib()    # raises if the HIP library has not been built
     torch.cuda.set_device(0)
-
-    wl = synth.config2_weighted(num_nodes=args.nodes, num_edges=args.edges, feat=args.feat)
-    n, e, f = wl.num_nodes, wl.num_edges, args.feat
-    stats = wl.stats()
-    src, dst = torch.from_numpy(wl.src).cuda(), torch.from_numpy(wl.dst).cuda()
-    x = torch.from_numpy(wl.x).cuda()
-    ew = torch.from_numpy(wl.edge_weight).cuda()
-    out = torch.empty_like(x)
-
-    t0 = time.perf_counter()
-    g = gnn.build_csr(src, dst, n)
-    torch.cuda.synchronize()
-    build_first_ms = (time.perf_counter() - t0) * 1e3
-
-    def step():
-        gnn.propagate(g, x, None, gnn.MSG_COPY_XJ, gnn.AGGR_SUM, out=out)
-
-    ms = time_calls(torch, step, args.steps, args.warmup)
-    bytes_alg = b_alg(n, e, f)
-    gbs = bytes_alg / (ms * 1e-3) / 1e9
-
-    extra = {"graph": stats, "work_lists": g.work_sizes(), "B_alg_bytes": bytes_alg,
-             "B_min_bytes": b_min(n, e, f), "t_min_over_t": b_min(n, e, f) / 8e12 / (ms * 1e-3),
-             "edge_feature_per_s": e * f / (ms * 1e-3), "csr_build_first_call_ms": build_first_ms}
-    # a plain streaming kernel (read 1 GiB, write 1 GiB) as a second denominator and as the
-    # calibration dispatch for hardware-counter runs
-    big = torch.zeros(256 * 1024 * 1024, dtype=torch.float32, device="cuda")
-    big2 = torch.empty_like(big)
-    copy_ms = time_calls(torch, lambda: torch.add(big, 1.0, out=big2), 10, 2)
-    extra["copy_kernel_GBs"] = 2 * big.numel() * 4 / (copy_ms * 1e-3) / 1e9
-    extra["copy_kernel_bytes_each_way"] = big.numel() * 4
-    del big, big2
-    if not args.no_extra:
-        k = max(5, args.steps // 10)
-        e_csr = gnn.edge_data_to_csr(g, ew)
-        for name, msg, aggr in (("e_mul_xj_sum", 1, 0), ("e_mul_xj_mean", 1, 1), ("e_mul_xj_max", 1, 2),
-                                ("copy_xj_mean", 0, 1), ("copy_xj_max", 0, 2)):
-            ed = e_csr if msg else None
-            t = time_calls(torch, lambda: gnn.propagate(g, x, ed, msg, aggr, e_order=gnn.EDGE_ORDER_CSR, out=out), k, 3)
-            extra[name] = {"ms": t, "GBs_alg": b_alg(n, e, f, bool(msg)) / (t * 1e-3) / 1e9}
-        t = time_calls(torch, lambda: gnn.propagate(g, x, ew, 1, 0, e_order=gnn.EDGE_ORDER_COO, out=out), k, 3)
-        extra["e_mul_xj_sum_coo_order"] = {"ms": t, "GBs_alg": b_alg(n, e, f, True) / (t * 1e-3) / 1e9}
-        t = time_calls(torch, lambda: gnn.edge_data_to_csr(g, ew), k, 2)
-        extra["edge_data_to_csr_ms"] = t
-
-        def rebuild():
-            gnn.build_csr(src, dst, n).close()
-        t0 = time.perf_counter()
-        for _ in range(3):
-            rebuild()
-        torch.cuda.synchronize()
-        extra["csr_build_ms"] = (time.perf_counter() - t0) / 3 * 1e3
-
-    line = {
-        "metric": "propagate(copy_xj,sum) algorithmic GB/s, 1M-node/20M-edge power-law graph, F=64",
-        "value": gbs, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
-        "config": {"workload": wl.name, "N": n, "E": e, "F": f, "msg": "copy_xj", "aggr": "sum",
-                   "seed": synth.seed_of(2)},
-        "roofline": {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": gbs / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES.get((n, e, f)),
-                     "kernel": "propagate_kernel<16,4,copy_xj,sum> (+ combine_pieces_kernel, a few us)"},
-        "extra": extra,
-    }
-    if not args.no_cpu_baseline:
-        line["cpu_baseline"] = cpu_baseline(wl, args.cpu_sample_edges)
-    g.close()
-    print(json.dumps(line))
+    print(json.dumps(WORKLOADS[args.workload](args, torch, gnn, synth)))
 
 
 if __name__ == "__main__":
