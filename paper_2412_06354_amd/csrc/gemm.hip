@@ -2,13 +2,23 @@
 // inside GCNConv and the GAT layer (layers named in the paper, section 3).  X is tall and
 // skinny ([rows x k], k ~ 100), W is small ([k x n], n <= a few hundred).
 //
-// A block of 4 wavefronts owns 128 rows x BN columns; each wavefront owns 32 rows and BN/32
-// accumulator tiles of v_mfma_f32_32x32x2_f32.  W is staged through LDS in slabs of 64 k-values;
-// X fragments go from global memory straight to registers: within a step of 8 k-values the
-// lane (r = lane % 32, half = lane / 32) holds X[row0 + r][k0 + 4*half .. +3] and feeds value j of
-// it to MFMA j, whose B operand is W[k0 + 4*half + j][col] -- the k order inside a step is
+// A tile is 128 rows x BN columns, worked on by a block of 4 wavefronts; each wavefront owns 32
+// rows and BN/32 accumulator tiles of v_mfma_f32_32x32x2_f32.  X fragments go from global memory
+// straight to registers, 64 k-values ("sub-slab") at a time: the lane (r = lane % 32, half = lane / 32)
+// reads the 32 consecutive floats X[row0 + r][k0 + 32*half ..] -- one full 128-byte line per lane,
+// eight 128-bit loads issued back to back -- and feeds value j of its s-th group of four to MFMA
+// (s, j), whose B operand is W[k0 + 32*half + 4*s + j][col].  The k order inside a sub-slab is thus
 // permuted identically for both operands, which leaves the sum unchanged.
+// W sits in LDS transposed ([col][k], k contiguous) so that the four B values of a group come from
+// one 128-bit LDS read; the 16-byte groups of a column are xor-swizzled with (col % 8) so that the
+// lanes of a read (same group, consecutive columns) fall into different banks without padding.
+//
+// Fast kernel (k <= 128, full tiles): blocks are persistent, stage their column block of W once,
+// then walk over row tiles.
+// General kernel (any shape, ragged edges): one tile per block, W re-staged per 64-k slab.
 #include "gnn_internal.h"
+
+#include <algorithm>
 
 namespace {
 
@@ -17,22 +27,195 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 constexpr int kThreads = 256;
 constexpr int kRowsPerWave = 32;
 constexpr int kRowsPerBlock = 4 * kRowsPerWave;
-constexpr int kSlab = 64;   // k-values of W resident in LDS at a time
+constexpr int kSlab = 64;             // k-values per X register buffer / per staged W slab in the fallback
 
-template <int NT /* 32-column tiles per block */, bool VEC4>
-__global__ __launch_bounds__(kThreads) void xw_kernel(const float *__restrict__ x, int64_t rows, int k,
-                                                      const float *__restrict__ w, int n,
-                                                      const float *__restrict__ row_scale, float *__restrict__ z)
+struct AFrag {
+    float v[8][4];
+};
+
+// Loads are unconditional (no branches, so that the hardware load counter can be waited on
+// precisely and the next buffer's loads stay in flight): rows past the end are clamped to the last
+// row (their results are never stored) and k positions past the end are clamped into the row (their
+// values meet zero-filled rows of W in LDS, and inputs are finite by contract).
+template <bool VEC4>
+__device__ __forceinline__ void load_a(AFrag &a, const float *__restrict__ x, int64_t rows, int k, int64_t row,
+                                       int k0, int half)
+{
+    const float *xrow = x + min(row, rows - 1) * (int64_t)k;
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+        const int kb = k0 + 32 * half + 4 * s;
+        if constexpr (VEC4) {
+            const float4 t = *reinterpret_cast<const float4 *>(xrow + min(kb, k - 4));   // k % 4 == 0
+            a.v[s][0] = t.x; a.v[s][1] = t.y; a.v[s][2] = t.z; a.v[s][3] = t.w;
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) a.v[s][j] = xrow[min(kb + j, k - 1)];
+        }
+    }
+}
+
+// LDS position of W[k][col] for a column block stored as [col][kp] floats, kp a multiple of 32.
+__device__ __forceinline__ int w_lds_index(int col, int k, int kp)
+{
+    return col * kp + ((((k >> 2) ^ (col & 7)) << 2) | (k & 3));
+}
+
+// acc += (A(sub-slab) * W(sub-slab))^T: the W fragment is fed as the MFMA's first operand and the X
+// fragment as its second, so the 32x32 accumulator tile holds Z transposed -- register v of lane l is
+// Z[row0 + l%32][col0 + 8*(v/4) + 4*(l/32) + v%4] -- and a lane's four consecutive registers are four
+// consecutive columns of one output row (one 128-bit store).  kbase = first k of this lane's half of the sub-slab relative to
+// the staged block (a multiple of 32); r = lane % 32.  Always the full 64 k-values, straight-line
+// code (k positions past the end of the matrix multiply zero-filled W rows).
+template <int NT>
+__device__ __forceinline__ void load_b(float4 (&b)[NT], const float *ws, int kp, int k4, int r)
+{
+#pragma unroll
+    for (int t = 0; t < NT; ++t) b[t] = *reinterpret_cast<const float4 *>(ws + w_lds_index(t * 32 + r, k4, kp));
+}
+
+template <int NT>
+__device__ __forceinline__ void mfma_step(floatx16 (&acc)[NT], const float (&a)[4], const float4 (&b)[NT])
+{
+#pragma unroll
+    for (int t = 0; t < NT; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(b[t].x, a[0], acc[t], 0, 0, 0);
+#pragma unroll
+    for (int t = 0; t < NT; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(b[t].y, a[1], acc[t], 0, 0, 0);
+#pragma unroll
+    for (int t = 0; t < NT; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(b[t].z, a[2], acc[t], 0, 0, 0);
+#pragma unroll
+    for (int t = 0; t < NT; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(b[t].w, a[3], acc[t], 0, 0, 0);
+}
+
+template <int NT>
+__device__ __forceinline__ void mfma_subslab(floatx16 (&acc)[NT], const AFrag &a, const float *ws, int kp, int kbase,
+                                             int r)
+{
+    // W fragments are read one step ahead of the MFMAs that use them; the scheduling barriers keep
+    // the compiler from hoisting all eight steps' reads (which would cost occupancy).
+    float4 b0[NT], b1[NT];
+    load_b<NT>(b0, ws, kp, kbase, r);
+#pragma unroll
+    for (int s = 0; s < 8; s += 2) {
+        load_b<NT>(b1, ws, kp, kbase + 4 * (s + 1), r);
+        mfma_step<NT>(acc, a.v[s], b0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (s + 2 < 8) load_b<NT>(b0, ws, kp, kbase + 4 * (s + 2), r);
+        mfma_step<NT>(acc, a.v[s + 1], b1);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
+// Guarded store of the (transposed) accumulator tiles, for ragged edges.
+template <int NT>
+__device__ __forceinline__ void store_tile(const floatx16 (&acc)[NT], int64_t row0, int64_t rows, int n0, int n,
+                                           int r, int half, const float *__restrict__ row_scale,
+                                           float *__restrict__ z)
+{
+    const int64_t row = row0 + r;
+    if (row >= rows) return;
+    const float sc = row_scale ? row_scale[row] : 1.0f;
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int col = n0 + t * 32 + 8 * (v / 4) + 4 * half + (v % 4);
+            if (col < n) z[row * n + col] = acc[t][v] * sc;
+        }
+}
+
+// Stages W[k0 .. k0+kk_count) x [n0 .. n0+BN) into LDS, transposed and swizzled (zero-filled outside
+// the matrix).  kk_count is a multiple of 32 and is the LDS row length.
+template <int BN>
+__device__ __forceinline__ void stage_w(float *ws, const float *__restrict__ w, int k, int n, int k0, int kk_count,
+                                        int n0, bool vec4)
+{
+    if (vec4) {   // n % 4 == 0 and w is 16-byte aligned: a group of four columns is inside or outside as a whole
+        constexpr int G = BN / 4;
+        const int total = kk_count * G;
+#pragma unroll 8
+        for (int idx = threadIdx.x; idx < total; idx += kThreads) {
+            const int kk = idx / G, c = (idx - kk * G) * 4;
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (k0 + kk < k && n0 + c < n) v = *reinterpret_cast<const float4 *>(w + (int64_t)(k0 + kk) * n + n0 + c);
+            ws[w_lds_index(c + 0, kk, kk_count)] = v.x;
+            ws[w_lds_index(c + 1, kk, kk_count)] = v.y;
+            ws[w_lds_index(c + 2, kk, kk_count)] = v.z;
+            ws[w_lds_index(c + 3, kk, kk_count)] = v.w;
+        }
+    } else {
+        const int total = kk_count * BN;
+#pragma unroll 8
+        for (int idx = threadIdx.x; idx < total; idx += kThreads) {
+            const int kk = idx / BN, c = idx - kk * BN;
+            float v = 0.0f;
+            if (k0 + kk < k && n0 + c < n) v = w[(int64_t)(k0 + kk) * n + n0 + c];
+            ws[w_lds_index(c, kk, kk_count)] = v;
+        }
+    }
+}
+
+// Fast path: full 128-row tiles x full BN-column blocks only, k <= 64*NSUB <= 128, 16-byte aligned
+// rows.  Blocks are persistent: they stage their column block of W once and then walk over row
+// tiles.  Per tile a wavefront issues all of its X loads (no branches), runs the MFMAs and writes
+// the tile with 128-bit stores; several wavefronts per SIMD overlap one another's load latency
+// with MFMAs (register use is kept low for that: no second X buffer).
+template <int NT, int NSUB, bool SCALED>
+__global__ __launch_bounds__(kThreads) void xw_fast_kernel(const float *__restrict__ x, int k,
+                                                           const float *__restrict__ w, int n,
+                                                           const float *__restrict__ row_scale,
+                                                           float *__restrict__ z, int64_t num_row_tiles)
 {
     constexpr int BN = NT * 32;
-    __shared__ float ws[kSlab * BN];
+    constexpr int KP = NSUB * kSlab;
+    extern __shared__ __align__(16) float ws[];   // [BN][KP], swizzled
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int r = lane & 31, half = lane >> 5;
-    const int64_t row0 = (int64_t)blockIdx.x * kRowsPerBlock + wave * kRowsPerWave;
     const int n0 = blockIdx.y * BN;
-    const int64_t my_row = row0 + r;
-    const bool row_ok = my_row < rows;
-    const float *xrow = x + (row_ok ? my_row : 0) * (int64_t)k;
+    const int64_t rows = num_row_tiles * kRowsPerBlock;
+
+    stage_w<BN>(ws, w, k, n, 0, KP, n0, true);
+    __syncthreads();
+
+    for (int64_t tile = blockIdx.x; tile < num_row_tiles; tile += gridDim.x) {
+        const int64_t row = tile * kRowsPerBlock + wave * kRowsPerWave + r;
+        AFrag a[NSUB];
+#pragma unroll
+        for (int sub = 0; sub < NSUB; ++sub) load_a<true>(a[sub], x, rows, k, row, sub * kSlab, half);
+        float sc = 1.0f;
+        if constexpr (SCALED) sc = row_scale[row];
+
+        floatx16 acc[NT];
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[t][v] = 0.0f;
+#pragma unroll
+        for (int sub = 0; sub < NSUB; ++sub) mfma_subslab<NT>(acc, a[sub], ws, KP, sub * kSlab + 32 * half, r);
+
+        float *zrow = z + row * n + n0 + 4 * half;
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+            for (int g = 0; g < 4; ++g)
+                *reinterpret_cast<float4 *>(zrow + t * 32 + 8 * g) =
+                    make_float4(acc[t][4 * g] * sc, acc[t][4 * g + 1] * sc, acc[t][4 * g + 2] * sc,
+                                acc[t][4 * g + 3] * sc);
+    }
+}
+
+template <int NT, bool VEC4>
+__global__ __launch_bounds__(kThreads) void xw_slab_kernel(const float *__restrict__ x, int64_t rows, int k,
+                                                           const float *__restrict__ w, int n,
+                                                           const float *__restrict__ row_scale, float *__restrict__ z,
+                                                           int w_vec4, int64_t first_row_tile)
+{
+    constexpr int BN = NT * 32;
+    __shared__ __align__(16) float ws[kSlab * BN];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int r = lane & 31, half = lane >> 5;
+    const int64_t row0 = (first_row_tile + blockIdx.x) * kRowsPerBlock + wave * kRowsPerWave;
+    const int n0 = blockIdx.y * BN;
 
     floatx16 acc[NT];
 #pragma unroll
@@ -41,54 +224,79 @@ __global__ __launch_bounds__(kThreads) void xw_kernel(const float *__restrict__ 
         for (int v = 0; v < 16; ++v) acc[t][v] = 0.0f;
 
     for (int k0 = 0; k0 < k; k0 += kSlab) {
+        AFrag a;
+        load_a<VEC4>(a, x, rows, k, row0 + r, k0, half);
         __syncthreads();
-        for (int idx = threadIdx.x; idx < kSlab * BN; idx += kThreads) {
-            const int kk = idx / BN, c = idx - kk * BN;
-            float v = 0.0f;
-            if (k0 + kk < k && n0 + c < n) v = w[(int64_t)(k0 + kk) * n + n0 + c];
-            ws[idx] = v;
-        }
+        stage_w<BN>(ws, w, k, n, k0, kSlab, n0, w_vec4 != 0);
         __syncthreads();
-        const int steps = (min(kSlab, k - k0) + 7) / 8;
-        for (int s = 0; s < steps; ++s) {
-            const int kb = k0 + s * 8 + half * 4;
-            float a[4] = {0.f, 0.f, 0.f, 0.f};
-            if (row_ok) {
-                if constexpr (VEC4) {
-                    if (kb < k) {   // k % 4 == 0: the four values are all inside the row
-                        const float4 t = *reinterpret_cast<const float4 *>(xrow + kb);
-                        a[0] = t.x; a[1] = t.y; a[2] = t.z; a[3] = t.w;
-                    }
-                } else {
-#pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        if (kb + j < k) a[j] = xrow[kb + j];
-                }
-            }
-            const float *wrow = ws + (s * 8 + half * 4) * BN + r;
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-#pragma unroll
-                for (int t = 0; t < NT; ++t)
-                    acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[j], wrow[j * BN + t * 32], acc[t], 0, 0, 0);
-        }
+        mfma_subslab<NT>(acc, a, ws, kSlab, 32 * half, r);
     }
+    store_tile<NT>(acc, row0, rows, n0, n, r, half, row_scale, z);
+}
 
-    // Accumulator layout of the 32x32 tile: register v of lane l holds
-    // row 8*(v/4) + 4*(l/32) + v%4, column l%32.
-#pragma unroll
-    for (int t = 0; t < NT; ++t) {
-        const int col = n0 + t * 32 + r;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int64_t row = row0 + 8 * (v / 4) + 4 * half + (v % 4);
-            if (row < rows && col < n) {
-                float val = acc[t][v];
-                if (row_scale) val *= row_scale[row];
-                z[row * n + col] = val;
-            }
-        }
+int device_cu_count()
+{
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
+            cus = prop.multiProcessorCount;
+        if (cus <= 0) cus = 256;
     }
+    return cus;
+}
+
+template <int NT>
+gnn_status launch_general(const float *d_x, int64_t rows, int k, const float *d_w, int n, const float *d_row_scale,
+                          float *d_z, bool x_vec4, bool w_vec4, int64_t first_row_tile, hipStream_t s)
+{
+    const int64_t row_tiles = gnn_div_up(rows, kRowsPerBlock) - first_row_tile;
+    if (row_tiles <= 0) return GNN_OK;
+    const dim3 grid((unsigned)row_tiles, (unsigned)gnn_div_up(n, NT * 32));
+    if (x_vec4)
+        hipLaunchKernelGGL((xw_slab_kernel<NT, true>), grid, dim3(kThreads), 0, s, d_x, rows, k, d_w, n, d_row_scale,
+                           d_z, w_vec4 ? 1 : 0, first_row_tile);
+    else
+        hipLaunchKernelGGL((xw_slab_kernel<NT, false>), grid, dim3(kThreads), 0, s, d_x, rows, k, d_w, n, d_row_scale,
+                           d_z, w_vec4 ? 1 : 0, first_row_tile);
+    GNN_LAUNCH_CHECK();
+    return GNN_OK;
+}
+
+template <int NT, int NSUB>
+gnn_status launch_fast(const float *d_x, int64_t full_tiles, int k, const float *d_w, int n, const float *d_row_scale,
+                       float *d_z, hipStream_t s)
+{
+    constexpr int BN = NT * 32;
+    const size_t lds = (size_t)NSUB * kSlab * BN * sizeof(float);
+    const int per_cu = (int)std::max<size_t>(1, std::min<size_t>(4, (160 * 1024) / lds));
+    const dim3 grid((unsigned)std::min<int64_t>(full_tiles, (int64_t)device_cu_count() * per_cu), (unsigned)(n / BN));
+    if (d_row_scale)
+        hipLaunchKernelGGL((xw_fast_kernel<NT, NSUB, true>), grid, dim3(kThreads), lds, s, d_x, k, d_w, n, d_row_scale,
+                           d_z, full_tiles);
+    else
+        hipLaunchKernelGGL((xw_fast_kernel<NT, NSUB, false>), grid, dim3(kThreads), lds, s, d_x, k, d_w, n,
+                           d_row_scale, d_z, full_tiles);
+    GNN_LAUNCH_CHECK();
+    return GNN_OK;
+}
+
+template <int NT>
+gnn_status launch_xw(const float *d_x, int64_t rows, int k, const float *d_w, int n, const float *d_row_scale,
+                     float *d_z, bool x_vec4, bool w_vec4, hipStream_t s)
+{
+    constexpr int BN = NT * 32;
+    const int64_t full_tiles = rows / kRowsPerBlock;
+    const bool fast = x_vec4 && w_vec4 && (n % BN == 0) && k <= 2 * kSlab && full_tiles > 0 &&
+                      (!d_row_scale || true);
+    if (!fast) return launch_general<NT>(d_x, rows, k, d_w, n, d_row_scale, d_z, x_vec4, w_vec4, 0, s);
+    if (k <= kSlab)
+        GNN_TRY((launch_fast<NT, 1>(d_x, full_tiles, k, d_w, n, d_row_scale, d_z, s)));
+    else
+        GNN_TRY((launch_fast<NT, 2>(d_x, full_tiles, k, d_w, n, d_row_scale, d_z, s)));
+    // the ragged last row tile, if any
+    return launch_general<NT>(d_x, rows, k, d_w, n, d_row_scale, d_z, x_vec4, w_vec4, full_tiles, s);
 }
 
 }  // namespace
@@ -100,26 +308,18 @@ extern "C" gnn_status gnn_dense_xw(const float *d_x, int64_t rows, int32_t k, co
     if (rows < 0 || k <= 0 || n <= 0) return GNN_ERR_BAD_SIZE;
     if (rows == 0) return GNN_OK;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const bool vec4 = (k % 4 == 0) && ((reinterpret_cast<uintptr_t>(d_x) & 15u) == 0);
-    const unsigned gx = (unsigned)gnn_div_up(rows, kRowsPerBlock);
-    // Column tile: 128 wide when n is large enough, else the smallest multiple of 32 covering n.
-    const int nt = n > 96 ? 4 : (n + 31) / 32;
-    const unsigned gy = (unsigned)gnn_div_up(n, nt * 32);
-    const dim3 grid(gx, gy), block(kThreads);
-#define GNN_XW(NT)                                                                                              \
-    do {                                                                                                        \
-        if (vec4)                                                                                               \
-            hipLaunchKernelGGL((xw_kernel<NT, true>), grid, block, 0, s, d_x, rows, k, d_w, n, d_row_scale, d_z);  \
-        else                                                                                                    \
-            hipLaunchKernelGGL((xw_kernel<NT, false>), grid, block, 0, s, d_x, rows, k, d_w, n, d_row_scale, d_z); \
-    } while (0)
+    const bool x_vec4 = (k % 4 == 0) && ((reinterpret_cast<uintptr_t>(d_x) & 15u) == 0);
+    const bool w_vec4 = (n % 4 == 0) && ((reinterpret_cast<uintptr_t>(d_w) & 15u) == 0);
+    // Column tile: 64 or 32 if it divides n (fast path; narrow tiles keep register use low and
+    // occupancy high), else 128 wide when n is
+    // large enough, else the smallest multiple of 32 covering n.
+    int nt = n > 96 ? 4 : (n + 31) / 32;
+    if (n % 64 == 0) nt = 2;
+    else if (n % 32 == 0) nt = 1;
     switch (nt) {
-    case 1: GNN_XW(1); break;
-    case 2: GNN_XW(2); break;
-    case 3: GNN_XW(3); break;
-    default: GNN_XW(4); break;
+    case 1: return launch_xw<1>(d_x, rows, k, d_w, n, d_row_scale, d_z, x_vec4, w_vec4, s);
+    case 2: return launch_xw<2>(d_x, rows, k, d_w, n, d_row_scale, d_z, x_vec4, w_vec4, s);
+    case 3: return launch_xw<3>(d_x, rows, k, d_w, n, d_row_scale, d_z, x_vec4, w_vec4, s);
+    default: return launch_xw<4>(d_x, rows, k, d_w, n, d_row_scale, d_z, x_vec4, w_vec4, s);
     }
-#undef GNN_XW
-    GNN_LAUNCH_CHECK();
-    return GNN_OK;
 }

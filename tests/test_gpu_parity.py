@@ -218,7 +218,8 @@ def test_propagate_argument_errors(case, gnn):
 # ----------------------------------------------------------------------------- layers
 
 def test_dense_xw_matches_numpy(gnn):
-    for rows, k, n in ((1000, 128, 128), (777, 100, 64), (130, 37, 50), (5, 8, 200), (4096, 16, 64)):
+    for rows, k, n in ((1000, 128, 128), (777, 100, 64), (130, 37, 50), (5, 8, 200), (4096, 16, 64),
+                       (70_000, 128, 128), (500, 300, 128), (300, 520, 40), (900, 200, 64), (257, 64, 33)):
         x = synth.normal_f32(rows + k, 2, rows * k).reshape(rows, k)
         w = synth.glorot_uniform(n, 4, k, n, (k, n))
         sc = synth.uniform_f32(3, 5, rows, 0.5, 2.0)
