@@ -337,13 +337,14 @@ gnn_status build_impl(const int32_t *d_src, const int32_t *d_dst, int64_t E, int
     // ---- arrays the graph keeps
     slab_plan pa;
     const size_t o_rowptr = pa.add(np1), o_indeg = pa.add(N), o_colidx = pa.add(E), o_perm = pa.add(E),
-                 o_rowidx = pa.add(E);
+                 o_rowidx = pa.add(E), o_dstcoo = pa.add(E);
     GNN_TRY(slab_alloc(&g->slab_csr, pa.bytes));
     g->rowptr = at(g->slab_csr, o_rowptr);
     g->indeg = at(g->slab_csr, o_indeg);
     g->colidx = at(g->slab_csr, o_colidx);
     g->perm = at(g->slab_csr, o_perm);
     g->rowidx = at(g->slab_csr, o_rowidx);
+    g->dst_coo = at(g->slab_csr, o_dstcoo);
 
     // ---- temporaries, one allocation, freed when this function returns
     slab_plan pt;
@@ -373,6 +374,7 @@ gnn_status build_impl(const int32_t *d_src, const int32_t *d_dst, int64_t E, int
 
     // ---- stable radix sort by destination
     if (E > 0) {
+        GNN_HIP(hipMemcpyAsync(g->dst_coo, d_dst, (size_t)E * sizeof(int32_t), hipMemcpyDeviceToDevice, stream));
         const int key_bits = ceil_log2((uint32_t)N);
         if (key_bits == 0) {
             const int blocks = (int)gnn_div_up(E, kThreads);

@@ -258,6 +258,8 @@ __global__ __launch_bounds__(kThreads) void gat_merge_kernel(const GatParams p)
 }
 
 // sl[i,hd] = <a_src[hd,:], h[i,hd,:]>,  sr[i,hd] = <a_dst[hd,:], h[i,hd,:]>
+// One thread per (node, head); with VEC = 4 the head's channels are read as 128-bit pieces.
+template <int VEC>
 __global__ __launch_bounds__(kThreads) void node_scores_kernel(const float *__restrict__ h, int64_t N, int H, int ch,
                                                                const float *__restrict__ a_src,
                                                                const float *__restrict__ a_dst,
@@ -268,10 +270,14 @@ __global__ __launch_bounds__(kThreads) void node_scores_kernel(const float *__re
     const int hd = (int)(idx % H);
     const float *hp = h + idx * ch;   // (i*H + hd)*ch
     float l = 0.0f, r = 0.0f;
-    for (int c = 0; c < ch; ++c) {
-        const float v = hp[c];
-        l = fmaf(a_src[hd * ch + c], v, l);
-        r = fmaf(a_dst[hd * ch + c], v, r);
+    for (int c = 0; c < ch; c += VEC) {
+        float v[VEC];
+        load_vec<VEC>(v, hp + c);
+#pragma unroll
+        for (int q = 0; q < VEC; ++q) {
+            l = fmaf(a_src[hd * ch + c + q], v[q], l);
+            r = fmaf(a_dst[hd * ch + c + q], v[q], r);
+        }
     }
     sl[idx] = l;
     sr[idx] = r;
@@ -325,8 +331,13 @@ gnn_status gnn_gatconv(const gnn_graph *g, const float *d_x, int32_t f_in, const
                                           align256((size_t)N * heads * sizeof(float)));
 
     GNN_TRY(gnn_dense_xw(d_x, N, f_in, d_w, HC, nullptr, h, stream));
-    hipLaunchKernelGGL(node_scores_kernel, dim3((unsigned)gnn_div_up((int64_t)N * heads, kThreads)), dim3(kThreads),
-                       0, s, h, (int64_t)N, heads, ch, d_a_src, d_a_dst, sl, sr);
+    const dim3 ns_grid((unsigned)gnn_div_up((int64_t)N * heads, kThreads));
+    if (ch % 4 == 0)
+        hipLaunchKernelGGL(node_scores_kernel<4>, ns_grid, dim3(kThreads), 0, s, h, (int64_t)N, heads, ch, d_a_src,
+                           d_a_dst, sl, sr);
+    else
+        hipLaunchKernelGGL(node_scores_kernel<1>, ns_grid, dim3(kThreads), 0, s, h, (int64_t)N, heads, ch, d_a_src,
+                           d_a_dst, sl, sr);
     GNN_LAUNCH_CHECK();
 
     GatParams p{};

@@ -155,8 +155,8 @@ __device__ __forceinline__ void stage_w(float *ws, const float *__restrict__ w, 
     }
 }
 
-// Fast path: full 128-row tiles x full BN-column blocks only, k <= 64*NSUB <= 128, 16-byte aligned
-// rows.  Blocks are persistent: they stage their column block of W once and then walk over row
+// Fast path: full BN-column blocks, k <= 64*NSUB <= 128, 16-byte aligned rows (a ragged last row
+// tile is handled by clamped loads and a guarded store).  Blocks are persistent: they stage their column block of W once and then walk over row
 // tiles.  Per tile a wavefront issues all of its X loads (no branches), runs the MFMAs and writes
 // the tile with 128-bit stores; several wavefronts per SIMD overlap one another's load latency
 // with MFMAs (register use is kept low for that: no second X buffer).
@@ -164,7 +164,7 @@ template <int NT, int NSUB, bool SCALED>
 __global__ __launch_bounds__(kThreads) void xw_fast_kernel(const float *__restrict__ x, int k,
                                                            const float *__restrict__ w, int n,
                                                            const float *__restrict__ row_scale,
-                                                           float *__restrict__ z, int64_t num_row_tiles)
+                                                           float *__restrict__ z, int64_t rows)
 {
     constexpr int BN = NT * 32;
     constexpr int KP = NSUB * kSlab;
@@ -172,7 +172,7 @@ __global__ __launch_bounds__(kThreads) void xw_fast_kernel(const float *__restri
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int r = lane & 31, half = lane >> 5;
     const int n0 = blockIdx.y * BN;
-    const int64_t rows = num_row_tiles * kRowsPerBlock;
+    const int64_t num_row_tiles = (rows + kRowsPerBlock - 1) / kRowsPerBlock;
 
     stage_w<BN>(ws, w, k, n, 0, KP, n0, true);
     __syncthreads();
@@ -183,7 +183,7 @@ __global__ __launch_bounds__(kThreads) void xw_fast_kernel(const float *__restri
 #pragma unroll
         for (int sub = 0; sub < NSUB; ++sub) load_a<true>(a[sub], x, rows, k, row, sub * kSlab, half);
         float sc = 1.0f;
-        if constexpr (SCALED) sc = row_scale[row];
+        if constexpr (SCALED) sc = row_scale[min(row, rows - 1)];
 
         floatx16 acc[NT];
 #pragma unroll
@@ -193,14 +193,16 @@ __global__ __launch_bounds__(kThreads) void xw_fast_kernel(const float *__restri
 #pragma unroll
         for (int sub = 0; sub < NSUB; ++sub) mfma_subslab<NT>(acc, a[sub], ws, KP, sub * kSlab + 32 * half, r);
 
-        float *zrow = z + row * n + n0 + 4 * half;
+        if (row < rows) {   // false only for lanes past the end in a ragged last tile
+            float *zrow = z + row * n + n0 + 4 * half;
 #pragma unroll
-        for (int t = 0; t < NT; ++t)
+            for (int t = 0; t < NT; ++t)
 #pragma unroll
-            for (int g = 0; g < 4; ++g)
-                *reinterpret_cast<float4 *>(zrow + t * 32 + 8 * g) =
-                    make_float4(acc[t][4 * g] * sc, acc[t][4 * g + 1] * sc, acc[t][4 * g + 2] * sc,
-                                acc[t][4 * g + 3] * sc);
+                for (int g = 0; g < 4; ++g)
+                    *reinterpret_cast<float4 *>(zrow + t * 32 + 8 * g) =
+                        make_float4(acc[t][4 * g] * sc, acc[t][4 * g + 1] * sc, acc[t][4 * g + 2] * sc,
+                                    acc[t][4 * g + 3] * sc);
+        }
     }
 }
 
@@ -265,19 +267,20 @@ gnn_status launch_general(const float *d_x, int64_t rows, int k, const float *d_
 }
 
 template <int NT, int NSUB>
-gnn_status launch_fast(const float *d_x, int64_t full_tiles, int k, const float *d_w, int n, const float *d_row_scale,
+gnn_status launch_fast(const float *d_x, int64_t rows, int k, const float *d_w, int n, const float *d_row_scale,
                        float *d_z, hipStream_t s)
 {
     constexpr int BN = NT * 32;
+    const int64_t full_tiles = gnn_div_up(rows, kRowsPerBlock);
     const size_t lds = (size_t)NSUB * kSlab * BN * sizeof(float);
     const int per_cu = (int)std::max<size_t>(1, std::min<size_t>(4, (160 * 1024) / lds));
     const dim3 grid((unsigned)std::min<int64_t>(full_tiles, (int64_t)device_cu_count() * per_cu), (unsigned)(n / BN));
     if (d_row_scale)
         hipLaunchKernelGGL((xw_fast_kernel<NT, NSUB, true>), grid, dim3(kThreads), lds, s, d_x, k, d_w, n, d_row_scale,
-                           d_z, full_tiles);
+                           d_z, rows);
     else
         hipLaunchKernelGGL((xw_fast_kernel<NT, NSUB, false>), grid, dim3(kThreads), lds, s, d_x, k, d_w, n,
-                           d_row_scale, d_z, full_tiles);
+                           d_row_scale, d_z, rows);
     GNN_LAUNCH_CHECK();
     return GNN_OK;
 }
@@ -287,16 +290,10 @@ gnn_status launch_xw(const float *d_x, int64_t rows, int k, const float *d_w, in
                      float *d_z, bool x_vec4, bool w_vec4, hipStream_t s)
 {
     constexpr int BN = NT * 32;
-    const int64_t full_tiles = rows / kRowsPerBlock;
-    const bool fast = x_vec4 && w_vec4 && (n % BN == 0) && k <= 2 * kSlab && full_tiles > 0 &&
-                      (!d_row_scale || true);
+    const bool fast = x_vec4 && w_vec4 && (n % BN == 0) && k <= 2 * kSlab;
     if (!fast) return launch_general<NT>(d_x, rows, k, d_w, n, d_row_scale, d_z, x_vec4, w_vec4, 0, s);
-    if (k <= kSlab)
-        GNN_TRY((launch_fast<NT, 1>(d_x, full_tiles, k, d_w, n, d_row_scale, d_z, s)));
-    else
-        GNN_TRY((launch_fast<NT, 2>(d_x, full_tiles, k, d_w, n, d_row_scale, d_z, s)));
-    // the ragged last row tile, if any
-    return launch_general<NT>(d_x, rows, k, d_w, n, d_row_scale, d_z, x_vec4, w_vec4, full_tiles, s);
+    if (k <= kSlab) return launch_fast<NT, 1>(d_x, rows, k, d_w, n, d_row_scale, d_z, s);
+    return launch_fast<NT, 2>(d_x, rows, k, d_w, n, d_row_scale, d_z, s);
 }
 
 }  // namespace

@@ -70,6 +70,7 @@ struct gnn_graph {
     int32_t *colidx = nullptr;   // [E]
     int32_t *perm = nullptr;     // [E]
     int32_t *rowidx = nullptr;   // [E] destination of CSR position p (the sorted keys)
+    int32_t *dst_coo = nullptr;  // [E] destination of edge k in the caller's order (a copy of the input)
 
     int32_t n_small = 0;
     int32_t *small_rows = nullptr;      // [n_small] row ids, ascending

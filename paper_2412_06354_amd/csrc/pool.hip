@@ -2,7 +2,7 @@
 // batch is the block-diagonal union of many small graphs with one graph id per node, ids
 // non-decreasing, so every graph is a contiguous run of node rows.
 //
-// One block per graph: the run's bounds come from two binary searches in the sorted ids; the
+// One block per graph: the run's bounds come from two block-wide searches in the sorted ids; the
 // block's threads are arranged as (node slot, feature lane), node slots stride over the run and
 // are combined through LDS in slot order, so the result does not depend on scheduling.
 #include "gnn_internal.h"
@@ -18,12 +18,22 @@ __device__ __forceinline__ float max_pz(float a, float b)
     return __uint_as_float(__float_as_uint(a) & __float_as_uint(b));
 }
 
-__device__ __forceinline__ int lower_bound(const int32_t *__restrict__ a, int n, int key)
+// First index whose value is >= key in the sorted array a[0..n), found by the whole block: every
+// round the 256 threads probe evenly spaced positions of the remaining range and count how many
+// are still below the key, which narrows the range 256-fold (a handful of rounds instead of
+// log2(n) dependent loads).
+__device__ __forceinline__ int block_lower_bound(const int32_t *__restrict__ a, int n, int key)
 {
-    int lo = 0, hi = n;
+    int lo = 0, hi = n;   // the answer lies in [lo, hi]
     while (lo < hi) {
-        const int mid = (lo + hi) >> 1;
-        if (a[mid] < key) lo = mid + 1; else hi = mid;
+        const int step = (hi - lo + kThreads - 1) / kThreads;
+        const int pos = lo + (int)threadIdx.x * step;
+        const int below = (pos < hi) && (a[pos] < key);
+        const int c = __syncthreads_count(below);   // the array is sorted: exactly probes 0 .. c-1 are below the key
+        if (c == 0) return lo;
+        const int new_hi = min(hi, lo + c * step);  // probe c (if inside) is >= key
+        lo = lo + (c - 1) * step + 1;               // probe c-1 is below the key
+        hi = new_hi;
     }
     return lo;
 }
@@ -35,7 +45,7 @@ __global__ __launch_bounds__(kThreads) void pool_kernel(const int32_t *__restric
 {
     __shared__ float part[kThreads];
     const int g = blockIdx.x;
-    const int lo = lower_bound(gi, N, g), hi = lower_bound(gi, N, g + 1);
+    const int lo = block_lower_bound(gi, N, g), hi = block_lower_bound(gi, N, g + 1);
     const int fl = threadIdx.x % lanes, slot = threadIdx.x / lanes, slots = kThreads / lanes;
     for (int f0 = 0; f0 < F; f0 += lanes) {
         const int f = f0 + fl;

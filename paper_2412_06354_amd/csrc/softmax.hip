@@ -3,57 +3,114 @@
 // section 3, "Graph Convolutional Layers"; a per-edge score is an apply_edges result and
 // the normalisation is a reduction over each neighbourhood followed by a per-edge rescale).
 //
-// Two phases over the by-destination CSR:
-//   1. per (row, head) statistics  m = max of the scores, den = sum exp(score - m):
-//      short rows: one thread per (row, head);
-//      long rows : one wavefront per piece of <= chunk edges, lanes = (edge slot, head),
-//                  xor-shuffle reductions; pieces of a split row are merged in piece order;
-//   2. one thread per (edge, head):  out = exp(score - m[row]) / den[row]   (perfectly balanced).
+// Two phases:
+//   1. per (row, head) statistics  m = max of the scores, den = sum exp(score - m), over the
+//      by-destination CSR with the propagate work decomposition: a sub-group of HP lanes (one lane
+//      per head) per short row, a wavefront per piece of a long row with lanes = (edge slot, head);
+//      edge ids are fetched in batches and the score loads of a batch are independent; the
+//      running (m, den) pair is updated edge by edge and pairs are merged with the usual
+//      rescaling; pieces of a split row are merged in piece order;
+//   2. one thread per (edge, head), in the order the scores are stored in (so reads and writes
+//      stream):  out = exp(score - m[row]) / den[row], the row coming from the stored copy of the
+//      destination array (caller's order) or from the sorted destinations (CSR order).
 #include "gnn_internal.h"
+
+#include <algorithm>
 
 namespace {
 
 constexpr int kThreads = 256;
+constexpr int kWavesPerBlock = kThreads / 64;
 
 struct SmParams {
-    const int32_t *rowptr, *perm, *rowidx;
+    const int32_t *rowptr, *perm, *row_of_edge;
     const float *s;
     float *out;
     float2 *rowstat;    // [N x H]  (m, den)
     float2 *slotstat;   // [slots x H]
     const int32_t *small_rows, *item_row, *item_start, *item_slot, *split_rows, *split_slot0;
-    int32_t n_small, n_items, n_split, chunk, H, coo;
+    int32_t n_small, n_items, n_split, chunk, H, coo, item_blocks;
     int64_t E;
 };
 
-__global__ __launch_bounds__(kThreads) void stats_short_kernel(const SmParams p)
+// (m, d) <- (m, d) + one score v
+__device__ __forceinline__ void online_add(float &m, float &d, bool ok, float v)
 {
-    const int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    const int64_t ri = idx / p.H;
-    const int h = (int)(idx - ri * p.H);
-    if (ri >= p.n_small) return;
-    const int row = p.small_rows[ri];
-    const int start = p.rowptr[row], end = p.rowptr[row + 1];
-    float m = -INFINITY;
-    for (int q = start; q < end; ++q) {
-        const int64_t eid = p.coo ? p.perm[q] : q;
-        m = fmaxf(m, p.s[eid * p.H + h]);
+    const float delta = v - m;
+    const float e = expf(-fabsf(delta));     // exp(-inf) = 0 covers the first score (m = -inf)
+    const bool up = delta > 0.0f;
+    if (ok) {
+        d = up ? d * e + 1.0f : d + e;
+        m = up ? v : m;
     }
-    float den = 0.0f;
-    for (int q = start; q < end; ++q) {
-        const int64_t eid = p.coo ? p.perm[q] : q;
-        den += expf(p.s[eid * p.H + h] - m);
-    }
-    p.rowstat[(int64_t)row * p.H + h] = make_float2(m, den);
 }
 
-template <int HP /* heads per pass, power of two <= 64 */>
-__global__ __launch_bounds__(kThreads) void stats_long_kernel(const SmParams p)
+// (m, d) <- (m, d) merged with (m2, d2)
+__device__ __forceinline__ void online_merge(float &m, float &d, float m2, float d2)
+{
+    const float mm = fmaxf(m, m2);
+    const float f1 = (m == -INFINITY) ? 0.0f : expf(m - mm);
+    const float f2 = (m2 == -INFINITY) ? 0.0f : expf(m2 - mm);
+    d = d * f1 + d2 * f2;
+    m = mm;
+}
+
+template <int HP>
+__device__ __forceinline__ void stats_short_rows(const SmParams &p, int block)
+{
+    constexpr int NSG = 64 / HP;
+    constexpr int U = 4;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int hl = lane % HP, sg = lane / HP;
+    const int64_t sgid = ((int64_t)block * kWavesPerBlock + wave) * NSG + sg;
+    const bool have = sgid < p.n_small;
+    int row = 0, start = 0, deg = 0;
+    if (have) {
+        row = p.small_rows[sgid];
+        start = p.rowptr[row];
+        deg = p.rowptr[row + 1] - start;
+    }
+    int wmax = deg;   // wavefront-uniform loop bound: shuffles run with all lanes active
+#pragma unroll
+    for (int off = HP; off < 64; off <<= 1) wmax = max(wmax, __shfl_xor(wmax, off, 64));
+    for (int hb = 0; hb < p.H; hb += HP) {
+        const int h = hb + hl;
+        const bool hok = have && h < p.H;
+        float m = -INFINITY, d = 0.0f;
+        for (int base = 0; base < wmax; base += HP) {
+            int my_eid = 0;
+            if (base + hl < deg) {
+                const int q = start + base + hl;
+                my_eid = p.coo ? __builtin_nontemporal_load(p.perm + q) : q;
+            }
+            const int cnt = min(HP, wmax - base);
+            for (int t0 = 0; t0 < cnt; t0 += U) {
+                float v[U];
+                bool ok[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int t = t0 + u;
+                    const int eid = __shfl(my_eid, t, HP);
+                    ok[u] = hok && (t < HP) && (base + t < deg);
+                    v[u] = 0.0f;
+                    if (ok[u]) v[u] = p.s[(int64_t)eid * p.H + h];
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) online_add(m, d, ok[u], v[u]);
+            }
+        }
+        if (hok) p.rowstat[(int64_t)row * p.H + h] = make_float2(m, d);
+    }
+}
+
+template <int HP>
+__device__ __forceinline__ void stats_long_pieces(const SmParams &p, int block)
 {
     constexpr int ES = 64 / HP;   // edges per step
+    constexpr int U = 4;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int it = blockIdx.x * (kThreads / 64) + wave;
-    if (it >= p.n_items) return;
+    const int it = block * kWavesPerBlock + wave;
+    if (it >= p.n_items) return;   // whole wavefront leaves together
     const int row = p.item_row[it];
     const int start = p.item_start[it];
     const int slot = p.item_slot[it];
@@ -62,27 +119,47 @@ __global__ __launch_bounds__(kThreads) void stats_long_kernel(const SmParams p)
     for (int hb = 0; hb < p.H; hb += HP) {
         const int h = hb + hl;
         const bool hok = h < p.H;
-        float m = -INFINITY;
-        for (int q = start + es; q < end; q += ES) {
-            const int64_t eid = p.coo ? p.perm[q] : q;
-            if (hok) m = fmaxf(m, p.s[eid * p.H + h]);
+        float m = -INFINITY, d = 0.0f;
+        for (int q0 = start; q0 < end; q0 += ES * U) {
+            int eid[U];
+            float v[U];
+            bool ok[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int q = q0 + u * ES + es;
+                ok[u] = hok && q < end;
+                eid[u] = 0;
+                if (ok[u]) eid[u] = p.coo ? __builtin_nontemporal_load(p.perm + q) : q;
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                v[u] = 0.0f;
+                if (ok[u]) v[u] = p.s[(int64_t)eid[u] * p.H + h];
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) online_add(m, d, ok[u], v[u]);
         }
 #pragma unroll
-        for (int off = HP; off < 64; off <<= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
-        float den = 0.0f;
-        for (int q = start + es; q < end; q += ES) {
-            const int64_t eid = p.coo ? p.perm[q] : q;
-            if (hok) den += expf(p.s[eid * p.H + h] - m);
+        for (int off = HP; off < 64; off <<= 1) {
+            const float m2 = __shfl_xor(m, off, 64), d2 = __shfl_xor(d, off, 64);
+            online_merge(m, d, m2, d2);
         }
-#pragma unroll
-        for (int off = HP; off < 64; off <<= 1) den += __shfl_xor(den, off, 64);
         if (es == 0 && hok) {
             if (slot < 0)
-                p.rowstat[(int64_t)row * p.H + h] = make_float2(m, den);
+                p.rowstat[(int64_t)row * p.H + h] = make_float2(m, d);
             else
-                p.slotstat[(int64_t)slot * p.H + h] = make_float2(m, den);
+                p.slotstat[(int64_t)slot * p.H + h] = make_float2(m, d);
         }
     }
+}
+
+template <int HP>
+__global__ __launch_bounds__(kThreads) void stats_kernel(const SmParams p)
+{
+    if ((int)blockIdx.x < p.item_blocks)
+        stats_long_pieces<HP>(p, blockIdx.x);
+    else
+        stats_short_rows<HP>(p, blockIdx.x - p.item_blocks);
 }
 
 __global__ __launch_bounds__(kThreads) void stats_merge_kernel(const SmParams p)
@@ -95,28 +172,38 @@ __global__ __launch_bounds__(kThreads) void stats_merge_kernel(const SmParams p)
     const int slot0 = p.split_slot0[si];
     const int deg = p.rowptr[row + 1] - p.rowptr[row];
     const int pieces = (deg + p.chunk - 1) / p.chunk;
-    float m = -INFINITY;
-    for (int c = 0; c < pieces; ++c) m = fmaxf(m, p.slotstat[(int64_t)(slot0 + c) * p.H + h].x);
-    float den = 0.0f;
+    float m = -INFINITY, d = 0.0f;
     for (int c = 0; c < pieces; ++c) {
         const float2 st = p.slotstat[(int64_t)(slot0 + c) * p.H + h];
-        den += st.y * expf(st.x - m);
+        online_merge(m, d, st.x, st.y);
     }
-    p.rowstat[(int64_t)row * p.H + h] = make_float2(m, den);
+    p.rowstat[(int64_t)row * p.H + h] = make_float2(m, d);
 }
 
+// Position k of the score array belongs to row row_of_edge[k]; scores and weights stream.
 __global__ __launch_bounds__(kThreads) void normalise_kernel(const SmParams p)
 {
     const int64_t total = p.E * p.H;
     const int64_t stride = (int64_t)gridDim.x * kThreads;
     for (int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x; idx < total; idx += stride) {
-        const int64_t q = idx / p.H;
-        const int h = (int)(idx - q * p.H);
-        const int row = p.rowidx[q];
-        const int64_t eid = p.coo ? p.perm[q] : q;
+        const int64_t k = idx / p.H;
+        const int h = (int)(idx - k * p.H);
+        const int row = __builtin_nontemporal_load(p.row_of_edge + k);
         const float2 st = p.rowstat[(int64_t)row * p.H + h];
-        p.out[eid * p.H + h] = expf(p.s[eid * p.H + h] - st.x) / st.y;
+        const float v = __builtin_nontemporal_load(p.s + idx);
+        __builtin_nontemporal_store(expf(v - st.x) / st.y, p.out + idx);
     }
+}
+
+template <int HP>
+gnn_status launch_stats(const SmParams &p, hipStream_t s)
+{
+    const int64_t blocks = p.item_blocks + gnn_div_up(p.n_small, kWavesPerBlock * (64 / HP));
+    if (blocks > 0) {
+        hipLaunchKernelGGL(stats_kernel<HP>, dim3((unsigned)blocks), dim3(kThreads), 0, s, p);
+        GNN_LAUNCH_CHECK();
+    }
+    return GNN_OK;
 }
 
 }  // namespace
@@ -134,34 +221,28 @@ extern "C" gnn_status gnn_segment_softmax(const gnn_graph *g, const float *d_sco
     GNN_TRY(gnn_graph_reserve_scratch(g, stat_floats));
 
     SmParams p{};
-    p.rowptr = g->rowptr; p.perm = g->perm; p.rowidx = g->rowidx;
+    p.coo = (order == GNN_EDGE_ORDER_COO) ? 1 : 0;
+    p.rowptr = g->rowptr; p.perm = g->perm;
+    p.row_of_edge = p.coo ? g->dst_coo : g->rowidx;
     p.s = d_scores; p.out = d_out;
     p.rowstat = reinterpret_cast<float2 *>(g->scratch);
     p.slotstat = p.rowstat + (size_t)g->num_nodes * heads;
     p.small_rows = g->small_rows; p.item_row = g->item_row; p.item_start = g->item_start;
     p.item_slot = g->item_slot; p.split_rows = g->split_rows; p.split_slot0 = g->split_slot0;
     p.n_small = g->n_small; p.n_items = g->n_items; p.n_split = g->n_split; p.chunk = g->chunk;
-    p.H = heads; p.coo = (order == GNN_EDGE_ORDER_COO) ? 1 : 0; p.E = g->num_edges;
+    p.H = heads; p.E = g->num_edges;
+    p.item_blocks = (int32_t)gnn_div_up(g->n_items, kWavesPerBlock);
 
-    if (g->n_items > 0) {
-        const unsigned blocks = (unsigned)gnn_div_up(g->n_items, kThreads / 64);
-        int hp = 1;
-        while (hp < heads && hp < 64) hp <<= 1;
-        switch (hp) {
-        case 1: hipLaunchKernelGGL(stats_long_kernel<1>, dim3(blocks), dim3(kThreads), 0, s, p); break;
-        case 2: hipLaunchKernelGGL(stats_long_kernel<2>, dim3(blocks), dim3(kThreads), 0, s, p); break;
-        case 4: hipLaunchKernelGGL(stats_long_kernel<4>, dim3(blocks), dim3(kThreads), 0, s, p); break;
-        case 8: hipLaunchKernelGGL(stats_long_kernel<8>, dim3(blocks), dim3(kThreads), 0, s, p); break;
-        case 16: hipLaunchKernelGGL(stats_long_kernel<16>, dim3(blocks), dim3(kThreads), 0, s, p); break;
-        case 32: hipLaunchKernelGGL(stats_long_kernel<32>, dim3(blocks), dim3(kThreads), 0, s, p); break;
-        default: hipLaunchKernelGGL(stats_long_kernel<64>, dim3(blocks), dim3(kThreads), 0, s, p); break;
-        }
-        GNN_LAUNCH_CHECK();
-    }
-    if (g->n_small > 0) {
-        const unsigned blocks = (unsigned)gnn_div_up((int64_t)g->n_small * heads, kThreads);
-        hipLaunchKernelGGL(stats_short_kernel, dim3(blocks), dim3(kThreads), 0, s, p);
-        GNN_LAUNCH_CHECK();
+    int hp = 1;
+    while (hp < heads && hp < 64) hp <<= 1;
+    switch (hp) {
+    case 1: GNN_TRY(launch_stats<1>(p, s)); break;
+    case 2: GNN_TRY(launch_stats<2>(p, s)); break;
+    case 4: GNN_TRY(launch_stats<4>(p, s)); break;
+    case 8: GNN_TRY(launch_stats<8>(p, s)); break;
+    case 16: GNN_TRY(launch_stats<16>(p, s)); break;
+    case 32: GNN_TRY(launch_stats<32>(p, s)); break;
+    default: GNN_TRY(launch_stats<64>(p, s)); break;
     }
     if (g->n_split > 0) {
         const unsigned blocks = (unsigned)gnn_div_up((int64_t)g->n_split * heads, kThreads);
@@ -170,7 +251,7 @@ extern "C" gnn_status gnn_segment_softmax(const gnn_graph *g, const float *d_sco
     }
     {
         const int64_t total = g->num_edges * heads;
-        const unsigned blocks = (unsigned)std::min<int64_t>(gnn_div_up(total, kThreads), 256 * 256);
+        const unsigned blocks = (unsigned)std::min<int64_t>(gnn_div_up(total, kThreads), 256 * 64);
         hipLaunchKernelGGL(normalise_kernel, dim3(blocks), dim3(kThreads), 0, s, p);
         GNN_LAUNCH_CHECK();
     }
