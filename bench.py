@@ -33,10 +33,14 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E peak
 MFMA_FP32_PEAK_TFLOPS = 157.3
 
-# Bytes per launch that left the L2s for the default workload, from the hardware-counter runs
-# summarised in profiles/propagate_copy_sum_1M_20M_F64.md (FETCH_SIZE x 2.000 calibration factor
-# + WRITE_SIZE x 1.000).  Only meaningful for the default N/E/F; other sizes report null.
-MEASURED_TRAFFIC_BYTES = {(1_000_000, 20_000_000, 64): int((1302746.4 * 2.0 + 254475.0) * 1024)}
+# Bytes per launch that left the L2s, from the hardware-counter runs summarised under profiles/
+# (FETCH_SIZE x 2.000 calibration factor + WRITE_SIZE x 1.000, calibrated on a 1 GiB streaming kernel
+# in the same run).  Only meaningful for the default sizes of each workload; other sizes report null.
+MEASURED_TRAFFIC_BYTES = {
+    ("propagate", 1_000_000, 20_000_000, 64): 2_928_763_241,   # propagate_kernel<16,4,0,false>
+    ("gat", 2_449_029, 126_167_309, 64): 42_071_136_213,       # gat_kernel<16,4>
+    ("gcn", 100_000, 1_000_000, 128): 405_388_176,             # propagate_kernel<32,4,0,false>, GCN epilogue
+}
 
 
 def b_alg_propagate(n, e, f, e_dim=0):
@@ -129,7 +133,7 @@ def run_propagate(args, torch, gnn, synth):
     line = base_line("propagate(copy_xj,sum) algorithmic GB/s, 1M-node/20M-edge power-law graph, F=64", gbs, ms, args,
                      wl.name, {"N": n, "E": e, "F": f, "msg": "copy_xj", "aggr": "sum", "seed": synth.seed_of(2)})
     line["roofline"] = hbm_roofline(gbs, "propagate_kernel<16,4,copy_xj,sum> (+ combine_pieces_kernel, ~10 us)",
-                                    MEASURED_TRAFFIC_BYTES.get((n, e, f)))
+                                    MEASURED_TRAFFIC_BYTES.get(("propagate", n, e, f)))
     line["extra"] = extra
     if not args.no_cpu_baseline:
         import oracle
@@ -229,7 +233,8 @@ def run_gcn(args, torch, gnn, synth):
                      {"N": n, "E": e, "f_in": f_in, "f_out": f_out, "add_self_loops": True})
     line["roofline"] = hbm_roofline(bytes_sp / (ms_sp * 1e-3) / 1e9,
                                     "propagate_kernel<32,4,copy_xj,sum> with GCN epilogue (timed alone through "
-                                    "gnn_gin_update on Z: same gathers, same epilogue shape)")
+                                    "gnn_gin_update on Z: same gathers, same epilogue shape)",
+                                    MEASURED_TRAFFIC_BYTES.get(("gcn", n, e, f_out)))
     line["extra"] = {"graph": wl.stats(), "xw_ms": ms_xw, "spmm_ms": ms_sp, "B_alg_spmm_bytes": bytes_sp,
                      "xw_roofline": {"bound": "mfma", "achieved": flops / (ms_xw * 1e-3) / 1e12,
                                      "peak": MFMA_FP32_PEAK_TFLOPS, "unit": "TFLOP/s",
@@ -270,7 +275,8 @@ def run_gat(args, torch, gnn, synth):
                      wl.name, {"N": n, "E": e, "f_in": f_in, "heads": heads, "ch": ch})
     line["steps"] = steps
     line["roofline"] = hbm_roofline(bytes_att / (ms_att * 1e-3) / 1e9,
-                                    "gat_kernel<16,4> (+ node_scores_kernel, gat_merge_kernel); time = layer - X W")
+                                    "gat_kernel<16,4> (+ node_scores_kernel, gat_merge_kernel); time = layer - X W",
+                                    MEASURED_TRAFFIC_BYTES.get(("gat", n, e, hc)))
     line["extra"] = {"xw_ms": ms_xw, "attention_ms": ms_att, "B_alg_attention_bytes": bytes_att,
                      "edge_feature_per_s": e * hc / (ms_att * 1e-3), "work_lists": g.work_sizes(),
                      "xw_roofline": {"bound": "mfma", "achieved": flops / (ms_xw * 1e-3) / 1e12,
@@ -371,7 +377,7 @@ def main():
     ap.add_argument("--nodes", type=int, default=1_000_000)
     ap.add_argument("--edges", type=int, default=20_000_000)
     ap.add_argument("--feat", type=int, default=64)
-    ap.add_argument("--cpu-sample-edges", type=int, default=10_000_000)
+    ap.add_argument("--cpu-sample-edges", type=int, default=20_000_000)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="time only the headline step")
     args = ap.parse_args()
