@@ -5,8 +5,9 @@
 //
 // Two phases:
 //   1. per (row, head) statistics  m = max of the scores, den = sum exp(score - m), over the
-//      by-destination CSR with the propagate work decomposition: a sub-group of HP lanes (one lane
-//      per head) per short row, a wavefront per piece of a long row with lanes = (edge slot, head);
+//      by-destination CSR with the propagate work decomposition: a sub-group of HP lanes per short
+//      row, a wavefront per piece of a long row with lanes = (edge slot, head group); a lane owns
+//      one head, or four consecutive heads read with one 128-bit load;
 //      edge ids are fetched in batches and the score loads of a batch are independent; the
 //      running (m, den) pair is updated edge by edge and pairs are merged with the usual
 //      rescaling; pieces of a split row are merged in piece order;
@@ -55,7 +56,31 @@ __device__ __forceinline__ void online_merge(float &m, float &d, float m2, float
     m = mm;
 }
 
-template <int HP>
+template <int HV>
+__device__ __forceinline__ void load_heads(float (&v)[HV], const float *__restrict__ p)
+{
+    if constexpr (HV == 4) {
+        const float4 t = *reinterpret_cast<const float4 *>(p);
+        v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+    } else {
+        v[0] = *p;
+    }
+}
+
+template <int HV>
+__device__ __forceinline__ void store_stats(float2 *__restrict__ dst, const float (&m)[HV], const float (&d)[HV])
+{
+    if constexpr (HV == 4) {
+        float4 *q = reinterpret_cast<float4 *>(dst);
+        q[0] = make_float4(m[0], d[0], m[1], d[1]);
+        q[1] = make_float4(m[2], d[2], m[3], d[3]);
+    } else {
+        dst[0] = make_float2(m[0], d[0]);
+    }
+}
+
+// HP lanes per edge, each lane owns HV consecutive heads (HV = 4: 128-bit score loads).
+template <int HP, int HV>
 __device__ __forceinline__ void stats_short_rows(const SmParams &p, int block)
 {
     constexpr int NSG = 64 / HP;
@@ -73,10 +98,12 @@ __device__ __forceinline__ void stats_short_rows(const SmParams &p, int block)
     int wmax = deg;   // wavefront-uniform loop bound: shuffles run with all lanes active
 #pragma unroll
     for (int off = HP; off < 64; off <<= 1) wmax = max(wmax, __shfl_xor(wmax, off, 64));
-    for (int hb = 0; hb < p.H; hb += HP) {
-        const int h = hb + hl;
+    for (int hb = 0; hb < p.H; hb += HP * HV) {
+        const int h = hb + hl * HV;
         const bool hok = have && h < p.H;
-        float m = -INFINITY, d = 0.0f;
+        float m[HV], d[HV];
+#pragma unroll
+        for (int c = 0; c < HV; ++c) { m[c] = -INFINITY; d[c] = 0.0f; }
         for (int base = 0; base < wmax; base += HP) {
             int my_eid = 0;
             if (base + hl < deg) {
@@ -85,25 +112,28 @@ __device__ __forceinline__ void stats_short_rows(const SmParams &p, int block)
             }
             const int cnt = min(HP, wmax - base);
             for (int t0 = 0; t0 < cnt; t0 += U) {
-                float v[U];
+                float v[U][HV];
                 bool ok[U];
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     const int t = t0 + u;
                     const int eid = __shfl(my_eid, t, HP);
                     ok[u] = hok && (t < HP) && (base + t < deg);
-                    v[u] = 0.0f;
-                    if (ok[u]) v[u] = p.s[(int64_t)eid * p.H + h];
+#pragma unroll
+                    for (int c = 0; c < HV; ++c) v[u][c] = 0.0f;
+                    if (ok[u]) load_heads<HV>(v[u], p.s + (int64_t)eid * p.H + h);
                 }
 #pragma unroll
-                for (int u = 0; u < U; ++u) online_add(m, d, ok[u], v[u]);
+                for (int u = 0; u < U; ++u)
+#pragma unroll
+                    for (int c = 0; c < HV; ++c) online_add(m[c], d[c], ok[u], v[u][c]);
             }
         }
-        if (hok) p.rowstat[(int64_t)row * p.H + h] = make_float2(m, d);
+        if (hok) store_stats<HV>(p.rowstat + (int64_t)row * p.H + h, m, d);
     }
 }
 
-template <int HP>
+template <int HP, int HV>
 __device__ __forceinline__ void stats_long_pieces(const SmParams &p, int block)
 {
     constexpr int ES = 64 / HP;   // edges per step
@@ -116,13 +146,15 @@ __device__ __forceinline__ void stats_long_pieces(const SmParams &p, int block)
     const int slot = p.item_slot[it];
     const int end = min(start + p.chunk, p.rowptr[row + 1]);
     const int hl = lane % HP, es = lane / HP;
-    for (int hb = 0; hb < p.H; hb += HP) {
-        const int h = hb + hl;
+    for (int hb = 0; hb < p.H; hb += HP * HV) {
+        const int h = hb + hl * HV;
         const bool hok = h < p.H;
-        float m = -INFINITY, d = 0.0f;
+        float m[HV], d[HV];
+#pragma unroll
+        for (int c = 0; c < HV; ++c) { m[c] = -INFINITY; d[c] = 0.0f; }
         for (int q0 = start; q0 < end; q0 += ES * U) {
             int eid[U];
-            float v[U];
+            float v[U][HV];
             bool ok[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
@@ -133,33 +165,35 @@ __device__ __forceinline__ void stats_long_pieces(const SmParams &p, int block)
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                v[u] = 0.0f;
-                if (ok[u]) v[u] = p.s[(int64_t)eid[u] * p.H + h];
+#pragma unroll
+                for (int c = 0; c < HV; ++c) v[u][c] = 0.0f;
+                if (ok[u]) load_heads<HV>(v[u], p.s + (int64_t)eid[u] * p.H + h);
             }
 #pragma unroll
-            for (int u = 0; u < U; ++u) online_add(m, d, ok[u], v[u]);
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int c = 0; c < HV; ++c) online_add(m[c], d[c], ok[u], v[u][c]);
         }
 #pragma unroll
         for (int off = HP; off < 64; off <<= 1) {
-            const float m2 = __shfl_xor(m, off, 64), d2 = __shfl_xor(d, off, 64);
-            online_merge(m, d, m2, d2);
+#pragma unroll
+            for (int c = 0; c < HV; ++c) {
+                const float m2 = __shfl_xor(m[c], off, 64), d2 = __shfl_xor(d[c], off, 64);
+                online_merge(m[c], d[c], m2, d2);
+            }
         }
-        if (es == 0 && hok) {
-            if (slot < 0)
-                p.rowstat[(int64_t)row * p.H + h] = make_float2(m, d);
-            else
-                p.slotstat[(int64_t)slot * p.H + h] = make_float2(m, d);
-        }
+        if (es == 0 && hok)
+            store_stats<HV>((slot < 0 ? p.rowstat + (int64_t)row * p.H : p.slotstat + (int64_t)slot * p.H) + h, m, d);
     }
 }
 
-template <int HP>
+template <int HP, int HV>
 __global__ __launch_bounds__(kThreads) void stats_kernel(const SmParams p)
 {
     if ((int)blockIdx.x < p.item_blocks)
-        stats_long_pieces<HP>(p, blockIdx.x);
+        stats_long_pieces<HP, HV>(p, blockIdx.x);
     else
-        stats_short_rows<HP>(p, blockIdx.x - p.item_blocks);
+        stats_short_rows<HP, HV>(p, blockIdx.x - p.item_blocks);
 }
 
 __global__ __launch_bounds__(kThreads) void stats_merge_kernel(const SmParams p)
@@ -181,29 +215,57 @@ __global__ __launch_bounds__(kThreads) void stats_merge_kernel(const SmParams p)
 }
 
 // Position k of the score array belongs to row row_of_edge[k]; scores and weights stream.
+// A thread handles HV consecutive heads of one edge.
+template <int HV>
 __global__ __launch_bounds__(kThreads) void normalise_kernel(const SmParams p)
 {
-    const int64_t total = p.E * p.H;
+    const int hg = p.H / HV;                       // head groups per edge
+    const int64_t total = p.E * hg;
     const int64_t stride = (int64_t)gridDim.x * kThreads;
     for (int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x; idx < total; idx += stride) {
-        const int64_t k = idx / p.H;
-        const int h = (int)(idx - k * p.H);
+        const int64_t k = idx / hg;
+        const int h = (int)(idx - k * hg) * HV;
         const int row = __builtin_nontemporal_load(p.row_of_edge + k);
-        const float2 st = p.rowstat[(int64_t)row * p.H + h];
-        const float v = __builtin_nontemporal_load(p.s + idx);
-        __builtin_nontemporal_store(expf(v - st.x) / st.y, p.out + idx);
+        const float2 *st = p.rowstat + (int64_t)row * p.H + h;
+        if constexpr (HV == 4) {
+            typedef float v4f __attribute__((ext_vector_type(4)));
+            const float4 s0 = reinterpret_cast<const float4 *>(st)[0], s1 = reinterpret_cast<const float4 *>(st)[1];
+            const v4f v = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(p.s + k * p.H + h));
+            v4f o = {expf(v.x - s0.x) / s0.y, expf(v.y - s0.z) / s0.w, expf(v.z - s1.x) / s1.y, expf(v.w - s1.z) / s1.w};
+            __builtin_nontemporal_store(o, reinterpret_cast<v4f *>(p.out + k * p.H + h));
+        } else {
+            const float2 q = st[0];
+            const float v = __builtin_nontemporal_load(p.s + k * p.H + h);
+            __builtin_nontemporal_store(expf(v - q.x) / q.y, p.out + k * p.H + h);
+        }
     }
 }
 
-template <int HP>
+template <int HP, int HV>
 gnn_status launch_stats(const SmParams &p, hipStream_t s)
 {
     const int64_t blocks = p.item_blocks + gnn_div_up(p.n_small, kWavesPerBlock * (64 / HP));
     if (blocks > 0) {
-        hipLaunchKernelGGL(stats_kernel<HP>, dim3((unsigned)blocks), dim3(kThreads), 0, s, p);
+        hipLaunchKernelGGL((stats_kernel<HP, HV>), dim3((unsigned)blocks), dim3(kThreads), 0, s, p);
         GNN_LAUNCH_CHECK();
     }
     return GNN_OK;
+}
+
+template <int HV>
+gnn_status launch_stats_hv(const SmParams &p, int lanes_needed, hipStream_t s)
+{
+    int hp = 1;
+    while (hp < lanes_needed && hp < 64) hp <<= 1;
+    switch (hp) {
+    case 1: return launch_stats<1, HV>(p, s);
+    case 2: return launch_stats<2, HV>(p, s);
+    case 4: return launch_stats<4, HV>(p, s);
+    case 8: return launch_stats<8, HV>(p, s);
+    case 16: return launch_stats<16, HV>(p, s);
+    case 32: return launch_stats<32, HV>(p, s);
+    default: return launch_stats<64, HV>(p, s);
+    }
 }
 
 }  // namespace
@@ -233,26 +295,24 @@ extern "C" gnn_status gnn_segment_softmax(const gnn_graph *g, const float *d_sco
     p.H = heads; p.E = g->num_edges;
     p.item_blocks = (int32_t)gnn_div_up(g->n_items, kWavesPerBlock);
 
-    int hp = 1;
-    while (hp < heads && hp < 64) hp <<= 1;
-    switch (hp) {
-    case 1: GNN_TRY(launch_stats<1>(p, s)); break;
-    case 2: GNN_TRY(launch_stats<2>(p, s)); break;
-    case 4: GNN_TRY(launch_stats<4>(p, s)); break;
-    case 8: GNN_TRY(launch_stats<8>(p, s)); break;
-    case 16: GNN_TRY(launch_stats<16>(p, s)); break;
-    case 32: GNN_TRY(launch_stats<32>(p, s)); break;
-    default: GNN_TRY(launch_stats<64>(p, s)); break;
-    }
+    const bool vec4 = (heads % 4 == 0) && ((reinterpret_cast<uintptr_t>(d_scores) & 15u) == 0) &&
+                      ((reinterpret_cast<uintptr_t>(d_out) & 15u) == 0);
+    if (vec4)
+        GNN_TRY(launch_stats_hv<4>(p, heads / 4, s));
+    else
+        GNN_TRY(launch_stats_hv<1>(p, heads, s));
     if (g->n_split > 0) {
         const unsigned blocks = (unsigned)gnn_div_up((int64_t)g->n_split * heads, kThreads);
         hipLaunchKernelGGL(stats_merge_kernel, dim3(blocks), dim3(kThreads), 0, s, p);
         GNN_LAUNCH_CHECK();
     }
     {
-        const int64_t total = g->num_edges * heads;
+        const int64_t total = g->num_edges * (vec4 ? heads / 4 : heads);
         const unsigned blocks = (unsigned)std::min<int64_t>(gnn_div_up(total, kThreads), 256 * 64);
-        hipLaunchKernelGGL(normalise_kernel, dim3(blocks), dim3(kThreads), 0, s, p);
+        if (vec4)
+            hipLaunchKernelGGL(normalise_kernel<4>, dim3(blocks), dim3(kThreads), 0, s, p);
+        else
+            hipLaunchKernelGGL(normalise_kernel<1>, dim3(blocks), dim3(kThreads), 0, s, p);
         GNN_LAUNCH_CHECK();
     }
     return GNN_OK;

@@ -275,7 +275,7 @@ def test_segment_softmax(case, gnn, heads):
     np.testing.assert_allclose(got_shift, got, rtol=2e-4, atol=1e-9)
 
 
-@pytest.mark.parametrize("heads,ch,f_in", [(8, 8, 100), (2, 4, 16), (3, 5, 12), (1, 64, 32)])
+@pytest.mark.parametrize("heads,ch,f_in", [(8, 8, 100), (2, 4, 16), (3, 5, 12), (1, 64, 32), (5, 64, 20), (3, 30, 8)])
 def test_gatconv(gnn, heads, ch, f_in):
     wl = synth.config4_gat(num_nodes=6000, num_edges=150_000, f_in=f_in, heads=heads, ch=ch, cap=3000.0)
     p = wl.params
@@ -288,6 +288,30 @@ def test_gatconv(gnn, heads, ch, f_in):
     got0 = host(gnn.gatconv(g, dev(wl.x), dev(p["w"]), dev(zero), dev(zero), 0.2))
     ref0, sabs0 = oracle.gatconv(wl.src, wl.dst, wl.num_nodes, wl.x, p["w"], zero, zero, 0.2, with_sabs=True)
     assert_close_sabs(got0, ref0, sabs0, what="gatconv zero attention")
+    g.close()
+
+
+def test_segment_softmax_many_heads(gnn):
+    wl = powerlaw(2000, 30_000, 4, 1500.0)
+    g = gnn.build_csr(dev(wl.src), dev(wl.dst), wl.num_nodes, 4, 64)
+    for heads in (2, 16, 70):
+        s = (2.0 * synth.normal_f32(heads, 2, wl.num_edges * heads)).reshape(wl.num_edges, heads)
+        ref = oracle.segment_softmax(wl.dst, wl.num_nodes, s)
+        assert_close_rel(host(gnn.segment_softmax(g, dev(s))), ref, what=f"softmax H={heads}")
+    g.close()
+
+
+def test_propagate_feature_width_one(gnn):
+    wl = powerlaw(1500, 20_000, 1, 900.0)
+    g = gnn.build_csr(dev(wl.src), dev(wl.dst), wl.num_nodes, 4, 64)
+    for msg, e in ((MSG_COPY_XJ, None), (MSG_E_MUL_XJ, wl.edge_weight)):
+        for aggr in (AGGR_SUM, AGGR_MEAN, AGGR_MAX):
+            ref, sabs = oracle.propagate(wl.src, wl.dst, wl.num_nodes, wl.x, e, msg, aggr, with_sabs=True)
+            got = host(gnn.propagate(g, dev(wl.x), dev(e) if e is not None else None, msg, aggr))
+            if aggr == AGGR_MAX:
+                np.testing.assert_array_equal(got.view(np.uint32), ref.view(np.uint32))
+            else:
+                assert_close_sabs(got, ref, sabs, what=f"F=1 msg={msg} aggr={aggr}")
     g.close()
 
 
