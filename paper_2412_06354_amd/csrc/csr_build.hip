@@ -28,26 +28,36 @@ __global__ __launch_bounds__(kThreads) void check_range_kernel(const int32_t *__
     if (any_bad) atomicOr(bad, 1);
 }
 
+// Copies the range flag and the four list sizes into one small array (one host read-back).
+__global__ void gather_totals_kernel(const int32_t *__restrict__ flag, const int32_t *__restrict__ pos, int64_t np1,
+                                     int32_t N, int32_t *__restrict__ out)
+{
+    if (threadIdx.x == 0) out[0] = flag[0];
+    if (threadIdx.x < 4) out[1 + threadIdx.x] = pos[threadIdx.x * np1 + N];
+}
+
 // In-degree histogram from the sorted destinations: every destination that occurs forms one run;
 // the first kernel records where each run starts, the second (a separate launch, so that all
 // starts are visible) writes run length = in-degree at each run's last element.  Rows that do not
 // occur keep the 0 they were cleared to.
-__global__ __launch_bounds__(kThreads) void run_starts_kernel(const int32_t *__restrict__ keys, int64_t E,
+__global__ __launch_bounds__(kThreads) void run_starts_kernel(const int32_t *__restrict__ keys, int64_t E, int32_t N,
                                                               int32_t *__restrict__ starts)
 {
     const int64_t p = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (p >= E) return;
     const int32_t k = keys[p];
+    if ((uint32_t)k >= (uint32_t)N) return;   // invalid input: reported through the range flag, never indexed with
     if (p == 0 || keys[p - 1] != k) starts[k] = (int32_t)p;
 }
 
-__global__ __launch_bounds__(kThreads) void run_lengths_kernel(const int32_t *__restrict__ keys, int64_t E,
+__global__ __launch_bounds__(kThreads) void run_lengths_kernel(const int32_t *__restrict__ keys, int64_t E, int32_t N,
                                                                const int32_t *__restrict__ starts,
                                                                int32_t *__restrict__ indeg)
 {
     const int64_t p = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (p >= E) return;
     const int32_t k = keys[p];
+    if ((uint32_t)k >= (uint32_t)N) return;
     if (p == E - 1 || keys[p + 1] != k) indeg[k] = (int32_t)(p + 1) - starts[k];
 }
 
@@ -298,10 +308,10 @@ int ceil_log2(uint32_t n)
 
 void free_graph_arrays(gnn_graph *g)
 {
-    void *ptrs[] = {g->slab_csr, g->slab_lists, g->scratch};
+    void *ptrs[] = {g->slab, g->scratch};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
-    g->slab_csr = g->slab_lists = nullptr;
+    g->slab = nullptr;
     g->scratch = nullptr;
 }
 
@@ -333,18 +343,29 @@ gnn_status build_impl(const int32_t *d_src, const int32_t *d_dst, int64_t E, int
 {
     const size_t np1 = (size_t)N + 1;
     const int64_t num_tiles = gnn_div_up(E, kSortTile);
+    // Upper bounds of the work-list sizes, so that everything the graph keeps is one allocation made
+    // before any kernel runs: a row is short or gives ceil(deg / chunk) pieces.
+    const size_t max_items = (size_t)std::min<int64_t>(N, E) + (size_t)(E / g->chunk) + 1;
+    const size_t max_split = (size_t)(E / g->chunk) + 1;
 
-    // ---- arrays the graph keeps
     slab_plan pa;
     const size_t o_rowptr = pa.add(np1), o_indeg = pa.add(N), o_colidx = pa.add(E), o_perm = pa.add(E),
-                 o_rowidx = pa.add(E), o_dstcoo = pa.add(E);
-    GNN_TRY(slab_alloc(&g->slab_csr, pa.bytes));
-    g->rowptr = at(g->slab_csr, o_rowptr);
-    g->indeg = at(g->slab_csr, o_indeg);
-    g->colidx = at(g->slab_csr, o_colidx);
-    g->perm = at(g->slab_csr, o_perm);
-    g->rowidx = at(g->slab_csr, o_rowidx);
-    g->dst_coo = at(g->slab_csr, o_dstcoo);
+                 o_rowidx = pa.add(E), o_dstcoo = pa.add(E), o_small = pa.add(N), o_irow = pa.add(max_items),
+                 o_istart = pa.add(max_items), o_islot = pa.add(max_items), o_srows = pa.add(max_split),
+                 o_sslot = pa.add(max_split);
+    GNN_TRY(slab_alloc(&g->slab, pa.bytes));
+    g->rowptr = at(g->slab, o_rowptr);
+    g->indeg = at(g->slab, o_indeg);
+    g->colidx = at(g->slab, o_colidx);
+    g->perm = at(g->slab, o_perm);
+    g->rowidx = at(g->slab, o_rowidx);
+    g->dst_coo = at(g->slab, o_dstcoo);
+    g->small_rows = at(g->slab, o_small);
+    g->item_row = at(g->slab, o_irow);
+    g->item_start = at(g->slab, o_istart);
+    g->item_slot = at(g->slab, o_islot);
+    g->split_rows = at(g->slab, o_srows);
+    g->split_slot0 = at(g->slab, o_sslot);
 
     // ---- temporaries, one allocation, freed when this function returns
     slab_plan pt;
@@ -359,7 +380,8 @@ gnn_status build_impl(const int32_t *d_src, const int32_t *d_dst, int64_t E, int
             *eb = at(ts, o_eb), *counts = at(ts, o_counts), *starts = at(ts, o_starts), *flags = at(ts, o_flags),
             *pos = at(ts, o_pos);
 
-    // ---- index range check (one flag read back)
+    // ---- index range check (the flag is read back at the end; nothing below indexes with an
+    //      unchecked node id: the sort only uses masked digits and the run kernels skip bad keys)
     GNN_HIP(hipMemsetAsync(d_flag, 0, 64 * sizeof(int32_t), stream));
     GNN_HIP(hipMemsetAsync(g->indeg, 0, (size_t)N * sizeof(int32_t), stream));
     if (E > 0) {
@@ -367,10 +389,6 @@ gnn_status build_impl(const int32_t *d_src, const int32_t *d_dst, int64_t E, int
         hipLaunchKernelGGL(check_range_kernel, dim3(blocks), dim3(kThreads), 0, stream, d_src, d_dst, E, N, d_flag);
         GNN_LAUNCH_CHECK();
     }
-    int32_t h_flag = 0;
-    GNN_HIP(hipMemcpyAsync(&h_flag, d_flag, sizeof(int32_t), hipMemcpyDeviceToHost, stream));
-    GNN_HIP(hipStreamSynchronize(stream));
-    if (h_flag) return GNN_ERR_INDEX_RANGE;
 
     // ---- stable radix sort by destination
     if (E > 0) {
@@ -407,9 +425,9 @@ gnn_status build_impl(const int32_t *d_src, const int32_t *d_dst, int64_t E, int
         }
         // ---- in-degree histogram from the runs of the sorted destinations
         const unsigned eblocks = (unsigned)gnn_div_up(E, kThreads);
-        hipLaunchKernelGGL(run_starts_kernel, dim3(eblocks), dim3(kThreads), 0, stream, g->rowidx, E, starts);
+        hipLaunchKernelGGL(run_starts_kernel, dim3(eblocks), dim3(kThreads), 0, stream, g->rowidx, E, N, starts);
         GNN_LAUNCH_CHECK();
-        hipLaunchKernelGGL(run_lengths_kernel, dim3(eblocks), dim3(kThreads), 0, stream, g->rowidx, E, starts,
+        hipLaunchKernelGGL(run_lengths_kernel, dim3(eblocks), dim3(kThreads), 0, stream, g->rowidx, E, N, starts,
                            g->indeg);
         GNN_LAUNCH_CHECK();
     }
@@ -417,36 +435,27 @@ gnn_status build_impl(const int32_t *d_src, const int32_t *d_dst, int64_t E, int
     // ---- rowptr = exclusive scan of the in-degrees
     GNN_TRY(gnn_scan_exclusive_i32(g->indeg, g->rowptr, N, true, scan_tmp, stream));
 
-    // ---- work lists
+    // ---- work lists (positions from scans; sizes are read back afterwards)
     const int nblocks = (int)gnn_div_up(N, kThreads);
     hipLaunchKernelGGL(classify_rows_kernel, dim3(nblocks), dim3(kThreads), 0, stream, g->indeg, N, g->small_max,
                        g->chunk, flags, flags + np1, flags + 2 * np1, flags + 3 * np1);
     GNN_LAUNCH_CHECK();
     for (int q = 0; q < 4; ++q)
         GNN_TRY(gnn_scan_exclusive_i32(flags + q * np1, pos + q * np1, N, true, scan_tmp, stream));
-    int32_t totals[4] = {0, 0, 0, 0};
-    for (int q = 0; q < 4; ++q)
-        GNN_HIP(hipMemcpyAsync(&totals[q], pos + q * np1 + N, sizeof(int32_t), hipMemcpyDeviceToHost, stream));
-    GNN_HIP(hipStreamSynchronize(stream));
-    g->n_small = totals[0];
-    g->n_items = totals[1];
-    g->n_slots = totals[2];
-    g->n_split = totals[3];
-    slab_plan pl;
-    const size_t o_small = pl.add(g->n_small), o_irow = pl.add(g->n_items), o_istart = pl.add(g->n_items),
-                 o_islot = pl.add(g->n_items), o_srows = pl.add(g->n_split), o_sslot = pl.add(g->n_split);
-    GNN_TRY(slab_alloc(&g->slab_lists, pl.bytes));
-    g->small_rows = at(g->slab_lists, o_small);
-    g->item_row = at(g->slab_lists, o_irow);
-    g->item_start = at(g->slab_lists, o_istart);
-    g->item_slot = at(g->slab_lists, o_islot);
-    g->split_rows = at(g->slab_lists, o_srows);
-    g->split_slot0 = at(g->slab_lists, o_sslot);
     hipLaunchKernelGGL(fill_lists_kernel, dim3(nblocks), dim3(kThreads), 0, stream, g->rowptr, N, g->small_max,
                        g->chunk, pos, pos + np1, pos + 2 * np1, pos + 3 * np1, g->small_rows, g->item_row,
                        g->item_start, g->item_slot, g->split_rows, g->split_slot0);
     GNN_LAUNCH_CHECK();
-    GNN_HIP(hipStreamSynchronize(stream));   // temporaries are freed when `tmp` goes out of scope
+    hipLaunchKernelGGL(gather_totals_kernel, dim3(1), dim3(64), 0, stream, d_flag, pos, (int64_t)np1, N, d_flag + 8);
+    GNN_LAUNCH_CHECK();
+    int32_t h_info[5] = {0, 0, 0, 0, 0};
+    GNN_HIP(hipMemcpyAsync(h_info, d_flag + 8, sizeof(h_info), hipMemcpyDeviceToHost, stream));
+    GNN_HIP(hipStreamSynchronize(stream));   // everything has run: temporaries may be freed on return
+    if (h_info[0]) return GNN_ERR_INDEX_RANGE;
+    g->n_small = h_info[1];
+    g->n_items = h_info[2];
+    g->n_slots = h_info[3];
+    g->n_split = h_info[4];
     return GNN_OK;
 }
 

@@ -8,8 +8,6 @@
 
 #include "gnn.h"
 
-#define GNN_WAVE 64
-
 // Turns a failing HIP call into GNN_ERR_DEVICE (or GNN_ERR_ALLOC for allocations).
 #define GNN_HIP(call)                                  \
     do {                                               \
@@ -49,11 +47,6 @@ struct gnn_temp_pool {
         *out = static_cast<T *>(p);
         return GNN_OK;
     }
-    // Hands ownership of p to the caller (it is no longer freed by the pool).
-    void keep(void *p) {
-        for (auto &q : ptrs)
-            if (q == p) { q = ptrs.back(); ptrs.pop_back(); return; }
-    }
 };
 
 struct gnn_graph {
@@ -62,8 +55,7 @@ struct gnn_graph {
     int32_t small_max = 0;   // rows with in-degree <= small_max: one sub-group of a wavefront each
     int32_t chunk = 0;       // longer rows: pieces of <= chunk edges, one wavefront each
 
-    void *slab_csr = nullptr;     // one allocation holding rowptr, indeg, colidx, perm, rowidx
-    void *slab_lists = nullptr;   // one allocation holding the work lists
+    void *slab = nullptr;        // the one allocation holding every array below
 
     int32_t *rowptr = nullptr;   // [N+1]
     int32_t *indeg = nullptr;    // [N]
