@@ -63,3 +63,24 @@ def test_host_side_argument_errors_need_no_gpu(handle):
     p = handle.gnn_propagate
     p.restype = ctypes.c_int
     assert p(None, None, 4, None, 1, 0, 0, 0, None, None) == 1        # NULL graph
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    pytest.importorskip("torch")
+    from paper_2412_06354_amd import binding
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "absent.so"))
+    with pytest.raises(RuntimeError, match="is missing"):
+        binding.lib()
+
+
+def test_product_never_imports_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2412_06354_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for name in files:
+            if name.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, name)).read()
+                assert "import oracle" not in text and "from oracle" not in text and "gnn_oracle" not in text, name
+    for name in ("__init__.py", "gnn_oracle.c"):
+        text = open(os.path.join(ROOT, "oracle", name)).read()
+        assert "paper_2412_06354_amd" not in text and "libgnn_mi355x" not in text, name
