@@ -470,12 +470,8 @@ gnn_status gnn_build_csr_ex(const int32_t *d_src, const int32_t *d_dst, int64_t 
     *out_graph = nullptr;
     if (num_nodes <= 0 || num_edges < 0 || num_edges >= (1ll << 31)) return GNN_ERR_BAD_SIZE;
     if (num_edges > 0 && (!d_src || !d_dst)) return GNN_ERR_NULL;
-    if (small_max_degree == 0 && chunk_edges == 0) {
-        small_max_degree = 16;
-        chunk_edges = 512;
-    } else if (chunk_edges == 0) {
-        chunk_edges = 512;
-    }
+    if (small_max_degree == 0 && chunk_edges == 0) small_max_degree = 16;
+    if (chunk_edges == 0) chunk_edges = 1024;
     if (small_max_degree < 0 || small_max_degree > 64) return GNN_ERR_BAD_SIZE;
     if (chunk_edges < 64 || chunk_edges > 65536 || chunk_edges % 64 != 0) return GNN_ERR_BAD_SIZE;
 
