@@ -127,6 +127,24 @@ gnn_status gnn_propagate(const gnn_graph *g, const float *d_x, int32_t feat_dim,
                          gnn_msg_op msg, gnn_aggr aggr, float *d_out, void *stream);
 
 /*
+ * The two un-fused primitives of the paper's listing (section 3, "Message Passing"):
+ *
+ * apply_edges: one message row per edge,  m[k,:] = msg(x[src[k],:], e[k,:])  with the message
+ * ops of gnn_propagate.  d_m is [E x feat_dim], written in the order m_order names (COO = the
+ * order the edges were given in, CSR = by destination, stable); d_e is read in e_order.
+ *
+ * aggregate_neighbors: reduces message rows onto their destinations,
+ *   out[i,:] = AGGR over edges k with dst[k] = i of m[k,:]      (sum, mean over the edge count, max)
+ * with d_m [E x feat_dim] stored in m_order.  gnn_propagate gives the same result as the two
+ * calls in a row without ever storing the messages.
+ */
+gnn_status gnn_apply_edges(const gnn_graph *g, const float *d_x, int32_t feat_dim, const float *d_e,
+                           int32_t e_dim, gnn_edge_order e_order, gnn_msg_op msg, float *d_m,
+                           gnn_edge_order m_order, void *stream);
+gnn_status gnn_aggregate_neighbors(const gnn_graph *g, const float *d_m, int32_t feat_dim,
+                                   gnn_edge_order m_order, gnn_aggr aggr, float *d_out, void *stream);
+
+/*
  * GCNConv forward (layer named in the paper's training example; fused form of
  * propagate per section 3):   out = D^-1/2 (A [+ I]) D^-1/2 X W + b
  * with d_i = in-degree of i (+1 when add_self_loops != 0; one loop per node is

@@ -38,6 +38,8 @@ SIGNATURES = {
     "gnn_graph_work_sizes": (None, [_vp, _c.POINTER(_i32), _c.POINTER(_i32), _c.POINTER(_i32)]),
     "gnn_edge_data_to_csr": (_c.c_int, [_vp, _vp, _i32, _vp, _vp]),
     "gnn_propagate": (_c.c_int, [_vp, _vp, _i32, _vp, _i32, _c.c_int, _c.c_int, _c.c_int, _vp, _vp]),
+    "gnn_apply_edges": (_c.c_int, [_vp, _vp, _i32, _vp, _i32, _c.c_int, _c.c_int, _vp, _c.c_int, _vp]),
+    "gnn_aggregate_neighbors": (_c.c_int, [_vp, _vp, _i32, _c.c_int, _c.c_int, _vp, _vp]),
     "gnn_gcnconv_workspace_bytes": (_sz, [_i32, _i32]),
     "gnn_gcnconv": (_c.c_int, [_vp, _vp, _i32, _vp, _vp, _i32, _i32, _vp, _vp, _sz, _vp]),
     "gnn_segment_softmax": (_c.c_int, [_vp, _vp, _i32, _c.c_int, _vp, _vp]),
@@ -193,6 +195,37 @@ def propagate(g: Graph, x: torch.Tensor, e: Optional[torch.Tensor] = None, msg: 
     rc = lib().gnn_propagate(g._h, _dev(x, torch.float32, "x"), f, _dev(e, torch.float32, "e"), e_dim,
                              e_order, msg, aggr, _dev(out, torch.float32, "out"), _stream())
     _check(rc, "gnn_propagate")
+    return out
+
+
+def apply_edges(g: Graph, x: torch.Tensor, e: Optional[torch.Tensor] = None, msg: int = MSG_COPY_XJ,
+                e_order: int = EDGE_ORDER_COO, m_order: int = EDGE_ORDER_COO,
+                out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    n, f = x.shape
+    if n != g.num_nodes:
+        raise ValueError("x must have one row per node")
+    e_dim = 1
+    if e is not None:
+        e = e.reshape(g.num_edges, -1)
+        e_dim = int(e.shape[1])
+    if out is None:
+        out = torch.empty((g.num_edges, f), dtype=torch.float32, device=x.device)
+    rc = lib().gnn_apply_edges(g._h, _dev(x, torch.float32, "x"), f, _dev(e, torch.float32, "e"), e_dim, e_order, msg,
+                               _dev(out, torch.float32, "out"), m_order, _stream())
+    _check(rc, "gnn_apply_edges")
+    return out
+
+
+def aggregate_neighbors(g: Graph, m: torch.Tensor, aggr: int = AGGR_SUM, m_order: int = EDGE_ORDER_COO,
+                        out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    ne, f = m.shape
+    if ne != g.num_edges:
+        raise ValueError("m must have one row per edge")
+    if out is None:
+        out = torch.empty((g.num_nodes, f), dtype=torch.float32, device=m.device)
+    rc = lib().gnn_aggregate_neighbors(g._h, _dev(m, torch.float32, "m"), f, m_order, aggr,
+                                       _dev(out, torch.float32, "out"), _stream())
+    _check(rc, "gnn_aggregate_neighbors")
     return out
 
 

@@ -98,8 +98,15 @@ struct gnn_epilogue {
     const float *bias = nullptr;
 };
 
-// Shared launcher behind gnn_propagate / gnn_gin_update / the sparse half of gnn_gcnconv.
+// Which row of `x` CSR position p gathers: x[colidx[p]] for node features (the default),
+// x[perm[p]] for per-edge rows stored in the caller's edge order, x[p] for per-edge rows stored in
+// CSR order.
+enum gnn_gather_index { GNN_GATHER_SOURCE_NODE = 0, GNN_GATHER_EDGE_COO = 1, GNN_GATHER_EDGE_CSR = 2 };
+
+// Shared launcher behind gnn_propagate / gnn_aggregate_neighbors / gnn_gin_update / the sparse half
+// of gnn_gcnconv.
 gnn_status gnn_launch_propagate(const gnn_graph *g, const float *d_x, int32_t feat_dim,
                                 const float *d_e, int32_t e_dim, gnn_edge_order e_order,
                                 gnn_msg_op msg, int use_max, const gnn_epilogue &epi,
-                                float *d_out, hipStream_t stream);
+                                float *d_out, hipStream_t stream,
+                                gnn_gather_index gather = GNN_GATHER_SOURCE_NODE);

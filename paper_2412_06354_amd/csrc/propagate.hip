@@ -16,6 +16,8 @@
 // A lane owns VEC consecutive features (VEC = 4: one 128-bit load per gathered row and lane).
 #include "gnn_internal.h"
 
+#include <algorithm>
+
 namespace {
 
 constexpr int kThreads = 256;
@@ -202,7 +204,7 @@ __device__ __forceinline__ void short_rows(const PropParams &p, int block)
             float my_w = 0.0f;
             if (base + sl < deg) {
                 const int q = start + base + sl;
-                my_j = load_stream(p.colidx + q);
+                my_j = p.colidx ? load_stream(p.colidx + q) : q;   // no index array: row q itself
                 if constexpr (MSG != kMsgCopy) {
                     my_eid = p.e_coo ? load_stream(p.perm + q) : q;
                     if constexpr (MSG == kMsgMulScalar) my_w = load_stream(p.e + my_eid);
@@ -258,7 +260,7 @@ __device__ __forceinline__ void long_row_pieces(const PropParams &p, int block)
             float my_w = 0.0f;
             if (lane < n) {
                 const int q = base + lane;
-                my_j = load_stream(p.colidx + q);
+                my_j = p.colidx ? load_stream(p.colidx + q) : q;   // no index array: row q itself
                 if constexpr (MSG != kMsgCopy) {
                     my_eid = p.e_coo ? load_stream(p.perm + q) : q;
                     if constexpr (MSG == kMsgMulScalar) my_w = load_stream(p.e + my_eid);
@@ -354,6 +356,39 @@ __global__ __launch_bounds__(kThreads) void combine_pieces_kernel(const PropPara
     }
 }
 
+// apply_edges: one message row per edge, m[k,:] = msg(x[src[k],:], e[k,:]), written in the caller's edge
+// order or in CSR order.  One thread per (CSR position, VEC features).
+template <int VEC, int MSG>
+__global__ __launch_bounds__(kThreads) void apply_edges_kernel(const int32_t *__restrict__ colidx,
+                                                               const int32_t *__restrict__ perm, int64_t E, int F,
+                                                               const float *__restrict__ x,
+                                                               const float *__restrict__ e, int e_coo, int m_coo,
+                                                               float *__restrict__ m)
+{
+    const int cols = F / VEC;
+    const int64_t total = E * cols;
+    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    for (int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x; idx < total; idx += stride) {
+        const int64_t q = idx / cols;
+        const int col = (int)(idx - q * cols) * VEC;
+        const int j = load_stream(colidx + q);
+        const int64_t eid = (e_coo || m_coo) ? load_stream(perm + q) : q;
+        Row<VEC> v;
+        load_row<VEC>(v, x + (int64_t)j * F + col);
+        if constexpr (MSG == kMsgMulScalar) {
+            const float w = load_stream(e + (e_coo ? eid : q));
+#pragma unroll
+            for (int c = 0; c < VEC; ++c) v.v[c] = w * v.v[c];
+        } else if constexpr (MSG == kMsgMulVector) {
+            Row<VEC> ev;
+            load_row_stream<VEC>(ev, e + (e_coo ? eid : q) * F + col);
+#pragma unroll
+            for (int c = 0; c < VEC; ++c) v.v[c] = ev.v[c] * v.v[c];
+        }
+        store_row_stream<VEC>(m + (m_coo ? eid : q) * F + col, v);
+    }
+}
+
 template <int LPR, int VEC, int MSG, bool MAX>
 gnn_status launch_typed(const PropParams &p, hipStream_t stream)
 {
@@ -394,14 +429,15 @@ bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 
 gnn_status gnn_launch_propagate(const gnn_graph *g, const float *d_x, int32_t feat_dim, const float *d_e,
                                 int32_t e_dim, gnn_edge_order e_order, gnn_msg_op msg, int use_max,
-                                const gnn_epilogue &epi, float *d_out, hipStream_t stream)
+                                const gnn_epilogue &epi, float *d_out, hipStream_t stream, gnn_gather_index gather)
 {
     const int F = feat_dim;
     int kmsg = kMsgCopy;
     if (msg == GNN_MSG_E_MUL_XJ) kmsg = (e_dim == 1) ? kMsgMulScalar : kMsgMulVector;
 
     PropParams p{};
-    p.rowptr = g->rowptr; p.colidx = g->colidx; p.perm = g->perm;
+    p.rowptr = g->rowptr; p.perm = g->perm;
+    p.colidx = gather == GNN_GATHER_SOURCE_NODE ? g->colidx : (gather == GNN_GATHER_EDGE_COO ? g->perm : nullptr);
     p.x = d_x; p.e = d_e; p.out = d_out;
     p.small_rows = g->small_rows; p.item_row = g->item_row; p.item_start = g->item_start;
     p.item_slot = g->item_slot; p.split_rows = g->split_rows; p.split_slot0 = g->split_slot0;
@@ -445,6 +481,59 @@ gnn_status gnn_propagate(const gnn_graph *g, const float *d_x, int32_t feat_dim,
     epi.mean = (aggr == GNN_AGGR_MEAN);
     return gnn_launch_propagate(g, d_x, feat_dim, d_e, e_dim, e_order, msg, aggr == GNN_AGGR_MAX, epi, d_out,
                                 static_cast<hipStream_t>(stream));
+}
+
+gnn_status gnn_apply_edges(const gnn_graph *g, const float *d_x, int32_t feat_dim, const float *d_e, int32_t e_dim,
+                           gnn_edge_order e_order, gnn_msg_op msg, float *d_m, gnn_edge_order m_order, void *stream)
+{
+    if (!g) return GNN_ERR_NULL;
+    if (feat_dim <= 0) return GNN_ERR_BAD_SIZE;
+    if (msg != GNN_MSG_COPY_XJ && msg != GNN_MSG_E_MUL_XJ) return GNN_ERR_BAD_SIZE;
+    if (m_order != GNN_EDGE_ORDER_COO && m_order != GNN_EDGE_ORDER_CSR) return GNN_ERR_BAD_SIZE;
+    if (msg == GNN_MSG_E_MUL_XJ) {
+        if (e_dim != 1 && e_dim != feat_dim) return GNN_ERR_BAD_SIZE;
+        if (e_order != GNN_EDGE_ORDER_COO && e_order != GNN_EDGE_ORDER_CSR) return GNN_ERR_BAD_SIZE;
+    }
+    if (g->num_edges == 0) return GNN_OK;
+    if (!d_x || !d_m || (msg == GNN_MSG_E_MUL_XJ && !d_e)) return GNN_ERR_NULL;
+    int kmsg = kMsgCopy;
+    if (msg == GNN_MSG_E_MUL_XJ) kmsg = (e_dim == 1) ? kMsgMulScalar : kMsgMulVector;
+    const int F = feat_dim;
+    const bool vec4 = (F % 4 == 0) && aligned16(d_x) && aligned16(d_m) && (kmsg != kMsgMulVector || aligned16(d_e));
+    const int64_t total = g->num_edges * (vec4 ? F / 4 : F);
+    const dim3 grid((unsigned)std::min<int64_t>(gnn_div_up(total, kThreads), 256 * 128)), block(kThreads);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int e_coo = (e_order == GNN_EDGE_ORDER_COO), m_coo = (m_order == GNN_EDGE_ORDER_COO);
+#define GNN_APPLY(VEC, MSG)                                                                                        \
+    hipLaunchKernelGGL((apply_edges_kernel<VEC, MSG>), grid, block, 0, s, g->colidx, g->perm, g->num_edges, F, d_x, \
+                       d_e, e_coo, m_coo, d_m)
+    if (vec4) {
+        if (kmsg == kMsgCopy) GNN_APPLY(4, kMsgCopy);
+        else if (kmsg == kMsgMulScalar) GNN_APPLY(4, kMsgMulScalar);
+        else GNN_APPLY(4, kMsgMulVector);
+    } else {
+        if (kmsg == kMsgCopy) GNN_APPLY(1, kMsgCopy);
+        else if (kmsg == kMsgMulScalar) GNN_APPLY(1, kMsgMulScalar);
+        else GNN_APPLY(1, kMsgMulVector);
+    }
+#undef GNN_APPLY
+    GNN_LAUNCH_CHECK();
+    return GNN_OK;
+}
+
+gnn_status gnn_aggregate_neighbors(const gnn_graph *g, const float *d_m, int32_t feat_dim, gnn_edge_order m_order,
+                                   gnn_aggr aggr, float *d_out, void *stream)
+{
+    if (!g || !d_out) return GNN_ERR_NULL;
+    if (feat_dim <= 0) return GNN_ERR_BAD_SIZE;
+    if (aggr != GNN_AGGR_SUM && aggr != GNN_AGGR_MEAN && aggr != GNN_AGGR_MAX) return GNN_ERR_BAD_SIZE;
+    if (m_order != GNN_EDGE_ORDER_COO && m_order != GNN_EDGE_ORDER_CSR) return GNN_ERR_BAD_SIZE;
+    if (!d_m && g->num_edges > 0) return GNN_ERR_NULL;
+    gnn_epilogue epi;
+    epi.mean = (aggr == GNN_AGGR_MEAN);
+    return gnn_launch_propagate(g, d_m, feat_dim, nullptr, 1, GNN_EDGE_ORDER_CSR, GNN_MSG_COPY_XJ,
+                                aggr == GNN_AGGR_MAX, epi, d_out, static_cast<hipStream_t>(stream),
+                                m_order == GNN_EDGE_ORDER_COO ? GNN_GATHER_EDGE_COO : GNN_GATHER_EDGE_CSR);
 }
 
 gnn_status gnn_gin_update(const gnn_graph *g, const float *d_x, int32_t feat_dim, float eps, float *d_out,

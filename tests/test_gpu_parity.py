@@ -180,6 +180,48 @@ def test_propagate_elementwise_edge_features(gnn, feat):
     g.close()
 
 
+@pytest.mark.parametrize("msg", [MSG_COPY_XJ, MSG_E_MUL_XJ])
+def test_apply_edges_then_aggregate(case, gnn, msg):
+    name, wl, g = case
+    n = wl.num_nodes
+    e = wl.edge_weight if msg == MSG_E_MUL_XJ else None
+    x = dev(wl.x)
+    m_ref = oracle.apply_edges(wl.src, n, wl.x, e, msg)
+    m = gnn.apply_edges(g, x, dev(e) if e is not None else None, msg)
+    np.testing.assert_array_equal(host(m).view(np.uint32), m_ref.view(np.uint32))      # gather / one rounded product
+    _, _, perm, _ = oracle.build_csr(wl.src, wl.dst, n)
+    m_csr = gnn.apply_edges(g, x, dev(e) if e is not None else None, msg, m_order=gnn.EDGE_ORDER_CSR)
+    np.testing.assert_array_equal(host(m_csr).view(np.uint32), m_ref[perm].view(np.uint32))
+    for aggr in (AGGR_SUM, AGGR_MEAN, AGGR_MAX):
+        ref, sabs = oracle.aggregate_neighbors(wl.dst, n, m_ref, aggr, with_sabs=True)
+        got = host(gnn.aggregate_neighbors(g, m, aggr))
+        got_csr = host(gnn.aggregate_neighbors(g, m_csr, aggr, m_order=gnn.EDGE_ORDER_CSR))
+        np.testing.assert_array_equal(got.view(np.uint32), got_csr.view(np.uint32))
+        if aggr == AGGR_MAX:
+            np.testing.assert_array_equal(got.view(np.uint32), ref.view(np.uint32))
+        else:
+            assert_close_sabs(got, ref, sabs, what=f"{name} aggregate msg={msg} aggr={aggr}")
+        if msg == MSG_COPY_XJ or aggr == AGGR_MAX:
+            # the fused call walks the same rows in the same order: identical bits
+            fused = host(gnn.propagate(g, x, dev(e) if e is not None else None, msg, aggr))
+            np.testing.assert_array_equal(got.view(np.uint32), fused.view(np.uint32))
+
+
+def test_apply_edges_elementwise_and_odd_width(gnn):
+    wl = powerlaw(2000, 30_000, 6, 900.0)
+    g = gnn.build_csr(dev(wl.src), dev(wl.dst), wl.num_nodes, 4, 64)
+    ef = synth.normal_f32(19, 3, wl.num_edges * 6).reshape(wl.num_edges, 6)
+    m_ref = oracle.apply_edges(wl.src, wl.num_nodes, wl.x, ef, MSG_E_MUL_XJ)
+    m = gnn.apply_edges(g, dev(wl.x), dev(ef), MSG_E_MUL_XJ)
+    np.testing.assert_array_equal(host(m).view(np.uint32), m_ref.view(np.uint32))
+    ef_csr = gnn.edge_data_to_csr(g, dev(ef))
+    m2 = gnn.apply_edges(g, dev(wl.x), ef_csr, MSG_E_MUL_XJ, e_order=gnn.EDGE_ORDER_CSR)
+    np.testing.assert_array_equal(host(m2).view(np.uint32), m_ref.view(np.uint32))
+    ref, sabs = oracle.aggregate_neighbors(wl.dst, wl.num_nodes, m_ref, AGGR_SUM, with_sabs=True)
+    assert_close_sabs(host(gnn.aggregate_neighbors(g, m, AGGR_SUM)), ref, sabs, what="aggregate F=6")
+    g.close()
+
+
 def test_propagate_invariants(case, gnn):
     _, wl, g = case
     n = wl.num_nodes
