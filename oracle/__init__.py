@@ -139,6 +139,28 @@ def propagate(src, dst, num_nodes: int, x, e=None, msg: int = MSG_COPY_XJ, aggr:
     return (out, sabs) if with_sabs else out
 
 
+def propagate_backward(src, dst, num_nodes: int, x, grad_out, e=None, msg: int = MSG_COPY_XJ,
+                       aggr: int = AGGR_SUM, with_sabs: bool = False):
+    """-> dict(grad_x, grad_e (None for copy_xj), argmax (max only), [sabs_x, sabs_e])."""
+    src, dst, x, g = _i32(src, "src"), _i32(dst, "dst"), _f32(x, "x"), _f32(grad_out, "grad_out")
+    ne, f = src.shape[0], x.shape[1]
+    e, e_dim = _edge_data(e, ne, f)
+    if msg == MSG_E_MUL_XJ and e is None:
+        raise ValueError("e_mul_xj needs edge data")
+    if g.shape != (num_nodes, f):
+        raise ValueError("grad_out must be [N, F]")
+    gx = np.empty((num_nodes, f), np.float32)
+    ge = np.empty((ne, e_dim), np.float32) if msg == MSG_E_MUL_XJ else None
+    am = np.empty((num_nodes, f), np.int32)
+    sx = np.empty((num_nodes, f), np.float64) if with_sabs else None
+    se = np.empty((ne, e_dim), np.float64) if (with_sabs and ge is not None) else None
+    rc = _load().oracle_propagate_backward(_p(src), _p(dst), ctypes.c_int64(ne), ctypes.c_int32(num_nodes), _p(x),
+                                           ctypes.c_int32(f), _p(e), ctypes.c_int32(e_dim), ctypes.c_int32(msg),
+                                           ctypes.c_int32(aggr), _p(g), _p(gx), _p(ge), _p(am), _p(sx), _p(se))
+    _check(rc, "propagate_backward")
+    return {"grad_x": gx, "grad_e": ge, "argmax": am if aggr == AGGR_MAX else None, "sabs_x": sx, "sabs_e": se}
+
+
 def gcnconv(src, dst, num_nodes: int, x, w, bias=None, add_self_loops: bool = True,
             with_sabs: bool = False):
     src, dst, x, w = _i32(src, "src"), _i32(dst, "dst"), _f32(x, "x"), _f32(w, "w")

@@ -209,6 +209,93 @@ int oracle_propagate(const int32_t *src, const int32_t *dst, int64_t E, int32_t 
     return 0;
 }
 
+/*
+ * Backward of propagate (reverse-mode derivative of the forward definition above; the paper's
+ * training example differentiates through its layers, section 3 "Training Example").
+ * Given g = dL/d out [N x F]:
+ *   sum : dL/dx[j,f] = sum_{k: src[k]=j} w[k,f] g[dst[k],f],   w = 1 (copy_xj) or e (e_mul_xj)
+ *         dL/de[k]   = sum_f x[src[k],f] g[dst[k],f]  (e_dim = 1)  or  x[src[k],f] g[dst[k],f]  (e_dim = F)
+ *   mean: the same with g[i,:] divided by the number of incoming edges of i
+ *   max : only the winning edge of each output element carries gradient; the winner of (i,f) is
+ *         the FIRST edge in increasing edge index whose message equals out[i,f] (with +0 above -0).
+ * grad_x [N x F] and grad_e [E x e_dim] may each be NULL.  argmax_out [N x F] (may be NULL, max
+ * only) receives the winning edge index or -1.  sabs_x / sabs_e (may be NULL) receive the sums of
+ * absolute values of the terms behind each element.
+ */
+int oracle_propagate_backward(const int32_t *src, const int32_t *dst, int64_t E, int32_t N,
+                              const float *x, int32_t F, const float *e, int32_t e_dim,
+                              int32_t msg, int32_t aggr, const float *grad_out,
+                              float *grad_x, float *grad_e, int32_t *argmax_out,
+                              double *sabs_x, double *sabs_e)
+{
+    if (N <= 0 || E < 0 || F <= 0) return 2;
+    if (msg != MSG_COPY_XJ && msg != MSG_E_MUL_XJ) return 2;
+    if (aggr < AGGR_SUM || aggr > AGGR_MAX) return 2;
+    if (msg == MSG_E_MUL_XJ && e_dim != 1 && e_dim != F) return 2;
+    if (check_edges(src, dst, E, N)) return 1;
+    const int has_e = (msg == MSG_E_MUL_XJ);
+    size_t nf = (size_t)N * F;
+    size_t ne = has_e ? (size_t)E * e_dim : 0;
+    double *gx = (double *)calloc(nf, sizeof(double));
+    double *sx = (double *)calloc(nf, sizeof(double));
+    double *ge = (double *)calloc(ne ? ne : 1, sizeof(double));
+    double *se = (double *)calloc(ne ? ne : 1, sizeof(double));
+    int64_t *cnt = (int64_t *)calloc((size_t)N, sizeof(int64_t));
+    float *best = NULL;
+    int64_t *win = NULL;
+    int rc = 3;
+    if (!gx || !sx || !ge || !se || !cnt) goto done;
+    for (int64_t k = 0; k < E; ++k) cnt[dst[k]]++;
+    if (aggr == AGGR_MAX) {
+        best = (float *)malloc(nf * sizeof(float));
+        win = (int64_t *)malloc(nf * sizeof(int64_t));
+        if (!best || !win) goto done;
+        for (size_t q = 0; q < nf; ++q) win[q] = -1;
+        for (int64_t k = 0; k < E; ++k)
+            for (int32_t f = 0; f < F; ++f) {
+                float v = x[(int64_t)src[k] * F + f];
+                if (has_e) v = mul_f32(e[k * e_dim + (e_dim == 1 ? 0 : f)], v);
+                int64_t q = (int64_t)dst[k] * F + f;
+                /* strictly better than the current winner (+0 is better than -0): replaces it;
+                   equal: the earlier edge stays */
+                if (win[q] < 0 || v > best[q] || (v == best[q] && signbit(best[q]) && !signbit(v))) {
+                    best[q] = v;
+                    win[q] = k;
+                }
+            }
+    }
+    for (int64_t k = 0; k < E; ++k) {
+        int64_t i = dst[k], j = src[k];
+        for (int32_t f = 0; f < F; ++f) {
+            int64_t qi = i * F + f, qj = j * F + f;
+            double g = (double)grad_out[qi];
+            if (aggr == AGGR_MEAN) g /= (double)cnt[i];
+            if (aggr == AGGR_MAX && win[qi] != k) continue;
+            double wv = has_e ? (double)e[k * e_dim + (e_dim == 1 ? 0 : f)] : 1.0;
+            gx[qj] += wv * g;
+            sx[qj] += fabs(wv * g);
+            if (has_e) {
+                int64_t qe = k * e_dim + (e_dim == 1 ? 0 : f);
+                ge[qe] += (double)x[qj] * g;
+                se[qe] += fabs((double)x[qj] * g);
+            }
+        }
+    }
+    for (size_t q = 0; q < nf; ++q) {
+        if (grad_x) grad_x[q] = (float)gx[q];
+        if (sabs_x) sabs_x[q] = sx[q];
+        if (argmax_out) argmax_out[q] = (aggr == AGGR_MAX) ? (int32_t)win[q] : -1;
+    }
+    for (size_t q = 0; q < ne; ++q) {
+        if (grad_e) grad_e[q] = (float)ge[q];
+        if (sabs_e) sabs_e[q] = se[q];
+    }
+    rc = 0;
+done:
+    free(gx); free(sx); free(ge); free(se); free(cnt); free(best); free(win);
+    return rc;
+}
+
 /* Z = X W and Zabs = |X| |W| in double, [N x f_out]. */
 static int dense_xw(const float *x, int32_t N, int32_t f_in, const float *w, int32_t f_out,
                     double **z_out, double **zabs_out)

@@ -352,6 +352,88 @@ def test_pool_and_batching():
         np.testing.assert_array_equal(part, full[off[q]:off[q + 1]])
 
 
+# ----------------------------------------------------------------------------- backward
+
+@pytest.mark.parametrize("aggr", [AGGR_SUM, AGGR_MEAN])
+@pytest.mark.parametrize("e_kind", ["none", "scalar", "vector"])
+def test_backward_is_the_adjoint(aggr, e_kind):
+    """sum and mean are linear in x and in e, so <propagate(x), g> = <x, grad_x> = <e, grad_e>."""
+    n, f = 50, 5
+    src, dst = rng_graph(91, n, 600, star=True)
+    ne = src.shape[0]
+    x = synth.normal_f32(91, 2, n * f).reshape(n, f)
+    g = synth.normal_f32(91, 7, n * f).reshape(n, f)
+    e = {"none": None, "scalar": synth.uniform_f32(91, 3, ne, -1, 1),
+         "vector": synth.normal_f32(91, 3, ne * f).reshape(ne, f)}[e_kind]
+    msg = MSG_COPY_XJ if e is None else MSG_E_MUL_XJ
+    out = oracle.propagate(src, dst, n, x, e, msg, aggr).astype(np.float64)
+    bw = oracle.propagate_backward(src, dst, n, x, g, e, msg, aggr)
+    lhs = (out * g).sum()
+    np.testing.assert_allclose((x.astype(np.float64) * bw["grad_x"]).sum(), lhs, rtol=2e-5)
+    if e is not None:
+        np.testing.assert_allclose((e.reshape(ne, -1).astype(np.float64) * bw["grad_e"]).sum(), lhs, rtol=2e-5)
+    else:
+        assert bw["grad_e"] is None
+    # dense form: grad_x = A^T (D^-1) g with A the (weighted) adjacency
+    if e_kind != "vector":
+        a = dense_adjacency(src, dst, n, e)
+        gg = g.astype(np.float64)
+        if aggr == AGGR_MEAN:
+            deg = np.maximum(dense_adjacency(src, dst, n).sum(1, keepdims=True), 1)
+            gg = gg / deg
+        np.testing.assert_allclose(bw["grad_x"], a.T @ gg, rtol=0, atol=2e-6 * np.abs(a.T @ gg).max())
+
+
+@pytest.mark.parametrize("e_kind", ["none", "scalar"])
+def test_backward_max_finite_differences(e_kind):
+    n, f = 25, 3
+    src, dst = rng_graph(93, n, 160)
+    ne = src.shape[0]
+    x = synth.normal_f32(93, 2, n * f).reshape(n, f)
+    g = synth.normal_f32(93, 7, n * f).reshape(n, f)
+    e = None if e_kind == "none" else synth.uniform_f32(93, 3, ne, 0.5, 1.5)
+    msg = MSG_COPY_XJ if e is None else MSG_E_MUL_XJ
+    bw = oracle.propagate_backward(src, dst, n, x, g, e, msg, AGGR_MAX)
+
+    def loss(xx, ee):
+        return (oracle.propagate(src, dst, n, xx, ee, msg, AGGR_MAX).astype(np.float64) * g).sum()
+
+    h = 1e-2   # messages are generic: no winner changes for this step
+    for (j, c) in ((0, 0), (3, 1), (7, 2), (11, 0), (20, 1)):
+        xp, xm = x.copy(), x.copy()
+        xp[j, c] += h
+        xm[j, c] -= h
+        np.testing.assert_allclose(bw["grad_x"][j, c], (loss(xp, e) - loss(xm, e)) / (xp[j, c] - xm[j, c]), rtol=2e-3, atol=2e-3)
+    if e is not None:
+        for k in (0, 5, 17, 40):
+            ep, em = e.copy(), e.copy()
+            ep[k] += h
+            em[k] -= h
+            np.testing.assert_allclose(bw["grad_e"][k, 0], (loss(x, ep) - loss(x, em)) / (ep[k] - em[k]), rtol=2e-3, atol=2e-3)
+    # the winner is an incoming edge whose message equals the forward output; ties go to the first edge
+    out = oracle.propagate(src, dst, n, x, e, msg, AGGR_MAX)
+    am = bw["argmax"]
+    indeg = np.bincount(dst, minlength=n)
+    assert ((am >= 0) == (indeg > 0)[:, None]).all()
+    m = oracle.apply_edges(src, n, x, e, msg)
+    for i in range(n):
+        for c in range(f):
+            if am[i, c] >= 0:
+                k = am[i, c]
+                assert dst[k] == i and m[k, c] == out[i, c]
+                assert not (m[:k][dst[:k] == i][:, c] == out[i, c]).any()
+
+
+def test_backward_max_ties_go_to_the_first_edge():
+    src = np.array([0, 1, 2, 1], np.int32)
+    dst = np.array([3, 3, 3, 3], np.int32)
+    x = np.array([[1.0], [5.0], [5.0], [0.0]], np.float32)
+    g = np.array([[0.0], [0.0], [0.0], [2.0]], np.float32)
+    bw = oracle.propagate_backward(src, dst, 4, x, g, None, MSG_COPY_XJ, AGGR_MAX)
+    assert bw["argmax"][3, 0] == 1
+    np.testing.assert_array_equal(bw["grad_x"][:, 0], [0.0, 2.0, 0.0, 0.0])
+
+
 def test_error_codes():
     src = np.array([0, 5], np.int32)
     dst = np.array([1, 0], np.int32)
