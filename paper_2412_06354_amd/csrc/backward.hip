@@ -1,0 +1,165 @@
+// Backward of propagate: given g = dL/d out, the gradients with respect to the node features and
+// the edge data.  The paper's purpose is training (its example differentiates through the layers,
+// section 3 "Training Example"); the forward definition is that of section 3, "Message Passing".
+//
+//   sum : dL/dx[j,:] = sum_{k: src[k]=j} w[k,:] * g[dst[k],:]   -- a propagate over the graph sorted by
+//         SOURCE (built by the caller with the roles of src and dst exchanged), gathering rows of g;
+//         the edge data stay in the caller's edge order, which both graphs share through their perm.
+//         dL/de[k] = <x[src[k],:], g[dst[k],:]>  (one weight per edge)  or the element-wise product:
+//         one sub-group per edge of the by-destination CSR, perfectly balanced, two row gathers.
+//   mean: the same with g[i,:] / in-degree(i) (scaled once into the workspace).
+#include "gnn_internal.h"
+
+#include <algorithm>
+
+namespace {
+
+constexpr int kThreads = 256;
+
+__global__ __launch_bounds__(kThreads) void scale_rows_by_inverse_degree_kernel(const int32_t *__restrict__ indeg,
+                                                                               int64_t N, int F,
+                                                                               const float *__restrict__ g,
+                                                                               float *__restrict__ out)
+{
+    const int64_t total = N * F;
+    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    for (int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x; idx < total; idx += stride) {
+        const int d = indeg[idx / F];
+        out[idx] = d > 0 ? g[idx] / (float)d : 0.0f;
+    }
+}
+
+template <int VEC>
+__device__ __forceinline__ void load_vec(float (&v)[VEC], const float *__restrict__ p)
+{
+    if constexpr (VEC == 4) {
+        const float4 t = *reinterpret_cast<const float4 *>(p);
+        v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+    } else {
+        v[0] = *p;
+    }
+}
+
+// One sub-group of LPR lanes per CSR position q (edge perm[q] from colidx[q] to rowidx[q]); a lane owns
+// VEC features per column block.  EVEC: element-wise edge data (no reduction), else one dot product.
+template <int LPR, int VEC, bool EVEC>
+__global__ __launch_bounds__(kThreads) void edge_gradient_kernel(const int32_t *__restrict__ rowidx,
+                                                                 const int32_t *__restrict__ colidx,
+                                                                 const int32_t *__restrict__ perm, int64_t E, int F,
+                                                                 const float *__restrict__ x,
+                                                                 const float *__restrict__ gp,
+                                                                 float *__restrict__ grad_e)
+{
+    const int sl = threadIdx.x % LPR;
+    const int64_t q = ((int64_t)blockIdx.x * kThreads + threadIdx.x) / LPR;
+    const bool have = q < E;   // no early return: the shuffles below run with every lane active
+    const int64_t qc = have ? q : E - 1;
+    const int64_t i = rowidx[qc], j = colidx[qc], k = perm[qc];
+    float dot = 0.0f;
+    for (int cb = 0; cb * LPR * VEC < F; ++cb) {
+        const int col = (cb * LPR + sl) * VEC;
+        if (col < F) {
+            float xv[VEC], gv[VEC];
+            load_vec<VEC>(xv, x + j * F + col);
+            load_vec<VEC>(gv, gp + i * F + col);
+            if constexpr (EVEC) {
+                if (have) {
+#pragma unroll
+                    for (int c = 0; c < VEC; ++c) grad_e[k * F + col + c] = xv[c] * gv[c];
+                }
+            } else {
+#pragma unroll
+                for (int c = 0; c < VEC; ++c) dot = fmaf(xv[c], gv[c], dot);
+            }
+        }
+    }
+    if constexpr (!EVEC) {
+#pragma unroll
+        for (int off = LPR / 2; off > 0; off >>= 1) dot += __shfl_xor(dot, off, LPR);
+        if (have && sl == 0) grad_e[k] = dot;
+    }
+}
+
+template <int LPR, int VEC>
+gnn_status launch_edge_gradient(const gnn_graph *g, int F, bool evec, const float *x, const float *gp, float *grad_e,
+                                hipStream_t s)
+{
+    const int64_t blocks = gnn_div_up(g->num_edges * LPR, kThreads);
+    if (evec)
+        hipLaunchKernelGGL((edge_gradient_kernel<LPR, VEC, true>), dim3((unsigned)blocks), dim3(kThreads), 0, s,
+                           g->rowidx, g->colidx, g->perm, g->num_edges, F, x, gp, grad_e);
+    else
+        hipLaunchKernelGGL((edge_gradient_kernel<LPR, VEC, false>), dim3((unsigned)blocks), dim3(kThreads), 0, s,
+                           g->rowidx, g->colidx, g->perm, g->num_edges, F, x, gp, grad_e);
+    GNN_LAUNCH_CHECK();
+    return GNN_OK;
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+}  // namespace
+
+extern "C" {
+
+size_t gnn_propagate_backward_workspace_bytes(int32_t num_nodes, int32_t feat_dim, gnn_aggr aggr)
+{
+    if (num_nodes <= 0 || feat_dim <= 0 || aggr != GNN_AGGR_MEAN) return 0;
+    return (size_t)num_nodes * feat_dim * sizeof(float);
+}
+
+gnn_status gnn_propagate_backward(const gnn_graph *g, const gnn_graph *g_by_source, const float *d_x,
+                                  int32_t feat_dim, const float *d_e, int32_t e_dim, gnn_msg_op msg, gnn_aggr aggr,
+                                  const float *d_grad_out, float *d_grad_x, float *d_grad_e, void *d_workspace,
+                                  size_t workspace_bytes, void *stream)
+{
+    if (!g || !d_grad_out) return GNN_ERR_NULL;
+    if (feat_dim <= 0) return GNN_ERR_BAD_SIZE;
+    if (msg != GNN_MSG_COPY_XJ && msg != GNN_MSG_E_MUL_XJ) return GNN_ERR_BAD_SIZE;
+    if (aggr == GNN_AGGR_MAX) return GNN_ERR_UNSUPPORTED;
+    if (aggr != GNN_AGGR_SUM && aggr != GNN_AGGR_MEAN) return GNN_ERR_BAD_SIZE;
+    if (msg == GNN_MSG_E_MUL_XJ) {
+        if (e_dim != 1 && e_dim != feat_dim) return GNN_ERR_BAD_SIZE;
+        if (!d_e && g->num_edges > 0) return GNN_ERR_NULL;
+    }
+    if (d_grad_x) {
+        if (!g_by_source) return GNN_ERR_NULL;
+        if (g_by_source->num_nodes != g->num_nodes || g_by_source->num_edges != g->num_edges) return GNN_ERR_BAD_SIZE;
+    }
+    if (d_grad_e && msg == GNN_MSG_E_MUL_XJ && !d_x) return GNN_ERR_NULL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int F = feat_dim;
+    const int64_t N = g->num_nodes;
+
+    const float *gp = d_grad_out;
+    if (aggr == GNN_AGGR_MEAN) {
+        if (!d_workspace) return GNN_ERR_NULL;
+        if (workspace_bytes < gnn_propagate_backward_workspace_bytes(g->num_nodes, F, aggr)) return GNN_ERR_BAD_SIZE;
+        if (!aligned16(d_workspace)) return GNN_ERR_BAD_SIZE;
+        float *scaled = static_cast<float *>(d_workspace);
+        const int blocks = (int)std::min<int64_t>(gnn_div_up(N * F, kThreads), 256 * 64);
+        hipLaunchKernelGGL(scale_rows_by_inverse_degree_kernel, dim3(blocks), dim3(kThreads), 0, s, g->indeg, N, F,
+                           d_grad_out, scaled);
+        GNN_LAUNCH_CHECK();
+        gp = scaled;
+    }
+    if (d_grad_x) {
+        gnn_epilogue epi;
+        GNN_TRY(gnn_launch_propagate(g_by_source, gp, F, d_e, e_dim, GNN_EDGE_ORDER_COO, msg, 0, epi, d_grad_x, s));
+    }
+    if (d_grad_e && msg == GNN_MSG_E_MUL_XJ && g->num_edges > 0) {
+        const bool evec = (e_dim != 1);
+        const bool vec4 = (F % 4 == 0) && aligned16(d_x) && aligned16(gp) && (!evec || aligned16(d_grad_e));
+        if (vec4) {
+            const int cols = F / 4;
+            if (cols <= 4) return launch_edge_gradient<4, 4>(g, F, evec, d_x, gp, d_grad_e, s);
+            if (cols <= 8) return launch_edge_gradient<8, 4>(g, F, evec, d_x, gp, d_grad_e, s);
+            if (cols <= 16) return launch_edge_gradient<16, 4>(g, F, evec, d_x, gp, d_grad_e, s);
+            return launch_edge_gradient<32, 4>(g, F, evec, d_x, gp, d_grad_e, s);
+        }
+        if (F <= 16) return launch_edge_gradient<16, 1>(g, F, evec, d_x, gp, d_grad_e, s);
+        return launch_edge_gradient<64, 1>(g, F, evec, d_x, gp, d_grad_e, s);
+    }
+    return GNN_OK;
+}
+
+}  // extern "C"

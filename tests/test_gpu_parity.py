@@ -222,6 +222,46 @@ def test_apply_edges_elementwise_and_odd_width(gnn):
     g.close()
 
 
+@pytest.mark.parametrize("aggr", [AGGR_SUM, AGGR_MEAN])
+@pytest.mark.parametrize("e_kind", ["none", "scalar", "vector"])
+def test_propagate_backward(case, gnn, aggr, e_kind):
+    name, wl, g = case
+    n, ne, f = wl.num_nodes, wl.num_edges, wl.x.shape[1]
+    gt = gnn.build_csr(dev(wl.dst), dev(wl.src), n, 4, 64)         # the same edges sorted by source
+    gout = synth.normal_f32(17, 7, n * f).reshape(n, f)
+    e = {"none": None, "scalar": wl.edge_weight,
+         "vector": synth.normal_f32(23, 3, ne * f).reshape(ne, f)}[e_kind]
+    msg = MSG_COPY_XJ if e is None else MSG_E_MUL_XJ
+    ref = oracle.propagate_backward(wl.src, wl.dst, n, wl.x, gout, e, msg, aggr, with_sabs=True)
+    gx, ge = gnn.propagate_backward(g, gt, dev(wl.x), dev(gout), dev(e) if e is not None else None, msg, aggr)
+    assert_close_sabs(host(gx), ref["grad_x"], ref["sabs_x"], what=f"{name} grad_x {e_kind} aggr={aggr}")
+    if e is None:
+        assert ge is None
+    else:
+        assert_close_sabs(host(ge).reshape(ne, -1), ref["grad_e"], ref["sabs_e"], what=f"{name} grad_e {e_kind} aggr={aggr}")
+    gt.close()
+
+
+def test_propagate_backward_odd_width_and_errors(gnn):
+    wl = powerlaw(2000, 30_000, 7, 900.0)
+    n = wl.num_nodes
+    g = gnn.build_csr(dev(wl.src), dev(wl.dst), n)
+    gt = gnn.build_csr(dev(wl.dst), dev(wl.src), n)
+    gout = synth.normal_f32(18, 7, n * 7).reshape(n, 7)
+    ref = oracle.propagate_backward(wl.src, wl.dst, n, wl.x, gout, wl.edge_weight, MSG_E_MUL_XJ, AGGR_MEAN, with_sabs=True)
+    gx, ge = gnn.propagate_backward(g, gt, dev(wl.x), dev(gout), dev(wl.edge_weight), MSG_E_MUL_XJ, AGGR_MEAN)
+    assert_close_sabs(host(gx), ref["grad_x"], ref["sabs_x"], what="grad_x F=7")
+    assert_close_sabs(host(ge).reshape(-1, 1), ref["grad_e"], ref["sabs_e"], what="grad_e F=7")
+    with pytest.raises(gnn.GnnError) as ei:
+        gnn.propagate_backward(g, gt, dev(wl.x), dev(gout), None, MSG_COPY_XJ, AGGR_MAX)
+    assert ei.value.code == 4
+    small = gnn.build_csr(dev(wl.dst[:100]), dev(wl.src[:100]), n)
+    with pytest.raises(gnn.GnnError):
+        gnn.propagate_backward(g, small, dev(wl.x), dev(gout), None, MSG_COPY_XJ, AGGR_SUM)
+    for h in (g, gt, small):
+        h.close()
+
+
 def test_propagate_invariants(case, gnn):
     _, wl, g = case
     n = wl.num_nodes
