@@ -16,6 +16,7 @@ Other workloads measure the remaining steps of the path, one JSON line each:
   gat      gnn_gatconv on the 2.45 M-node / 126 M-edge graph, 100 -> 8 heads x 8 channels
   batched  gnn_gin_update + gnn_graph_pool on 4 096 batched small graphs, F = 32
   tiny     gnn_propagate sum / mean / max on the 2 708-node graph (launch-latency bound)
+  backward gnn_propagate_backward (e_mul_xj, sum: grad_x and grad_e) on the headline graph
 
 Every line carries `value` (algorithmic GB/s = the byte model of the step / mean step time), a
 `roofline` object for the dominant kernel and a `cpu_baseline` object (the parity oracle, one thread,
@@ -367,7 +368,46 @@ def run_tiny(args, torch, gnn, synth):
     return line
 
 
-WORKLOADS = {"propagate": run_propagate, "csr": run_csr, "softmax": run_softmax, "gcn": run_gcn, "gat": run_gat,
+def run_backward(args, torch, gnn, synth):
+    wl = synth.config2_weighted(num_nodes=args.nodes, num_edges=args.edges, feat=args.feat)
+    n, e, f = wl.num_nodes, wl.num_edges, args.feat
+    src, dst, x, ew = (to_dev(torch, a) for a in (wl.src, wl.dst, wl.x, wl.edge_weight))
+    g = gnn.build_csr(src, dst, n)
+    gt = gnn.build_csr(dst, src, n)      # the same edges sorted by source
+    gout_h = synth.normal_f32(17, 7, n * f).reshape(n, f)
+    gout = to_dev(torch, gout_h)
+    steps = max(5, args.steps // 4)
+    ms = time_calls(torch, lambda: gnn.propagate_backward(g, gt, x, gout, ew, gnn.MSG_E_MUL_XJ, gnn.AGGR_SUM), steps, 3)
+    ms_x = time_calls(torch, lambda: gnn.propagate_backward(g, gt, x, gout, ew, gnn.MSG_E_MUL_XJ, gnn.AGGR_SUM,
+                                                            want_grad_e=False), steps, 3)
+    ms_e = time_calls(torch, lambda: gnn.propagate_backward(g, gt, x, gout, ew, gnn.MSG_E_MUL_XJ, gnn.AGGR_SUM,
+                                                            want_grad_x=False), steps, 3)
+    # grad_x: a propagate over the by-source graph with weights fetched through perm;
+    # grad_e: two feature rows, three indices and one result per edge
+    bytes_x = e * (4 * f + 4 + 4 + 4) + n * 4 * f + (n + 1) * 4
+    bytes_e = e * (8 * f + 12 + 4)
+    gbs = (bytes_x + bytes_e) / (ms * 1e-3) / 1e9
+    line = base_line("backward of propagate(e_mul_xj, sum): grad_x and grad_e, algorithmic GB/s", gbs, ms, args,
+                     wl.name + ":backward", {"N": n, "E": e, "F": f, "msg": "e_mul_xj", "aggr": "sum"})
+    line["steps"] = steps
+    line["roofline"] = hbm_roofline(bytes_x / (ms_x * 1e-3) / 1e9, "propagate_kernel<16,4,e_mul_xj,sum> on the by-source graph")
+    line["extra"] = {"grad_x_ms": ms_x, "grad_e_ms": ms_e, "grad_e_GBs": bytes_e / (ms_e * 1e-3) / 1e9,
+                     "B_alg_grad_x_bytes": bytes_x, "B_alg_grad_e_bytes": bytes_e}
+    if not args.no_cpu_baseline:
+        import oracle
+        es = min(args.cpu_sample_edges // 2, e)
+        t0 = time.perf_counter()
+        oracle.propagate_backward(wl.src[:es].copy(), wl.dst[:es].copy(), n, wl.x, gout_h, wl.edge_weight[:es].copy(),
+                                  1, 0)
+        dt = time.perf_counter() - t0
+        line["cpu_baseline"] = {"value": (es * (12 * f + 28) + n * 4 * f) / dt / 1e9, "unit": "GB/s", "cores": 1,
+                                "kind": "oracle", "seconds": dt, "sample": f"the first {es} of {e} edges, one pass"}
+    g.close()
+    gt.close()
+    return line
+
+
+WORKLOADS = {"backward": run_backward, "propagate": run_propagate, "csr": run_csr, "softmax": run_softmax, "gcn": run_gcn, "gat": run_gat,
              "batched": run_batched, "tiny": run_tiny}
 
 

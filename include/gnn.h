@@ -145,12 +145,22 @@ gnn_status gnn_aggregate_neighbors(const gnn_graph *g, const float *d_m, int32_t
                                    gnn_edge_order m_order, gnn_aggr aggr, float *d_out, void *stream);
 
 /*
- * Backward of gnn_propagate for SUM and MEAN (MAX: GNN_ERR_UNSUPPORTED): given d_grad_out =
- * dL/d out [N x feat_dim],
+ * Winners of a max aggregation: d_argmax[i,f] = the edge (id in the caller's numbering) whose message
+ * is out[i,f], the FIRST such edge in increasing edge id on ties, -1 where node i has no incoming
+ * edge.  d_out_max must be the result of gnn_propagate(..., GNN_AGGR_MAX, ...) on the same inputs.
+ * d_argmax is [N x feat_dim] int32.
+ */
+gnn_status gnn_propagate_argmax(const gnn_graph *g, const float *d_x, int32_t feat_dim, const float *d_e,
+                                int32_t e_dim, gnn_edge_order e_order, gnn_msg_op msg,
+                                const float *d_out_max, int32_t *d_argmax, void *stream);
+
+/*
+ * Backward of gnn_propagate: given d_grad_out = dL/d out [N x feat_dim],
  *   d_grad_x [N x feat_dim]  = dL/dx:  row j = sum over edges k with src[k] = j of w[k,:] * g'[dst[k],:]
  *   d_grad_e [E x e_dim]     = dL/de in the caller's edge order (E_MUL_XJ only):
  *                              <x[src[k],:], g'[dst[k],:]> for e_dim == 1, the element-wise product otherwise
- * with w = 1 (COPY_XJ) or e, and g' = grad_out (SUM) or grad_out[i,:] / in-degree(i) (MEAN).
+ * with w = 1 (COPY_XJ) or e, and g' = grad_out (SUM), grad_out[i,:] / in-degree(i) (MEAN), or
+ * grad_out masked to the elements this edge won (MAX; d_argmax from gnn_propagate_argmax, else NULL).
  * g is the graph the forward call used; g_by_source is the same edge list sorted by source, i.e.
  * gnn_build_csr(d_dst, d_src, ...) with the two arrays exchanged (needed for d_grad_x only).
  * d_e is in the caller's edge order (both graphs share it through their perm arrays).
@@ -160,8 +170,9 @@ gnn_status gnn_aggregate_neighbors(const gnn_graph *g, const float *d_m, int32_t
 size_t gnn_propagate_backward_workspace_bytes(int32_t num_nodes, int32_t feat_dim, gnn_aggr aggr);
 gnn_status gnn_propagate_backward(const gnn_graph *g, const gnn_graph *g_by_source, const float *d_x,
                                   int32_t feat_dim, const float *d_e, int32_t e_dim, gnn_msg_op msg,
-                                  gnn_aggr aggr, const float *d_grad_out, float *d_grad_x, float *d_grad_e,
-                                  void *d_workspace, size_t workspace_bytes, void *stream);
+                                  gnn_aggr aggr, const float *d_grad_out, const int32_t *d_argmax,
+                                  float *d_grad_x, float *d_grad_e, void *d_workspace,
+                                  size_t workspace_bytes, void *stream);
 
 /*
  * GCNConv forward (layer named in the paper's training example; fused form of

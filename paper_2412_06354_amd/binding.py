@@ -41,8 +41,9 @@ SIGNATURES = {
     "gnn_apply_edges": (_c.c_int, [_vp, _vp, _i32, _vp, _i32, _c.c_int, _c.c_int, _vp, _c.c_int, _vp]),
     "gnn_aggregate_neighbors": (_c.c_int, [_vp, _vp, _i32, _c.c_int, _c.c_int, _vp, _vp]),
     "gnn_propagate_backward_workspace_bytes": (_sz, [_i32, _i32, _c.c_int]),
-    "gnn_propagate_backward": (_c.c_int, [_vp, _vp, _vp, _i32, _vp, _i32, _c.c_int, _c.c_int, _vp, _vp, _vp, _vp, _sz,
-                                          _vp]),
+    "gnn_propagate_argmax": (_c.c_int, [_vp, _vp, _i32, _vp, _i32, _c.c_int, _c.c_int, _vp, _vp, _vp]),
+    "gnn_propagate_backward": (_c.c_int, [_vp, _vp, _vp, _i32, _vp, _i32, _c.c_int, _c.c_int, _vp, _vp, _vp, _vp, _vp,
+                                          _sz, _vp]),
     "gnn_gcnconv_workspace_bytes": (_sz, [_i32, _i32]),
     "gnn_gcnconv": (_c.c_int, [_vp, _vp, _i32, _vp, _vp, _i32, _i32, _vp, _vp, _sz, _vp]),
     "gnn_segment_softmax": (_c.c_int, [_vp, _vp, _i32, _c.c_int, _vp, _vp]),
@@ -232,9 +233,24 @@ def aggregate_neighbors(g: Graph, m: torch.Tensor, aggr: int = AGGR_SUM, m_order
     return out
 
 
+def propagate_argmax(g: Graph, x: torch.Tensor, out_max: torch.Tensor, e: Optional[torch.Tensor] = None,
+                     msg: int = MSG_COPY_XJ, e_order: int = EDGE_ORDER_COO) -> torch.Tensor:
+    n, f = x.shape
+    e_dim = 1
+    if e is not None:
+        e = e.reshape(g.num_edges, -1)
+        e_dim = int(e.shape[1])
+    am = torch.empty((n, f), dtype=torch.int32, device=x.device)
+    rc = lib().gnn_propagate_argmax(g._h, _dev(x, torch.float32, "x"), f, _dev(e, torch.float32, "e"), e_dim, e_order,
+                                    msg, _dev(out_max, torch.float32, "out_max"), am.data_ptr(), _stream())
+    _check(rc, "gnn_propagate_argmax")
+    return am
+
+
 def propagate_backward(g: Graph, g_by_source: Optional[Graph], x: torch.Tensor, grad_out: torch.Tensor,
                        e: Optional[torch.Tensor] = None, msg: int = MSG_COPY_XJ, aggr: int = AGGR_SUM,
-                       want_grad_x: bool = True, want_grad_e: bool = True):
+                       want_grad_x: bool = True, want_grad_e: bool = True,
+                       argmax: Optional[torch.Tensor] = None):
     """-> (grad_x or None, grad_e or None); edge data and grad_e are in the caller's edge order."""
     n, f = grad_out.shape
     e_dim = 1
@@ -248,7 +264,8 @@ def propagate_backward(g: Graph, g_by_source: Optional[Graph], x: torch.Tensor, 
     ws = torch.empty(max(need, 16), dtype=torch.uint8, device=grad_out.device)
     rc = lib().gnn_propagate_backward(g._h, g_by_source._h if g_by_source is not None else None,
                                       _dev(x, torch.float32, "x"), f, _dev(e2, torch.float32, "e"), e_dim, msg, aggr,
-                                      _dev(grad_out, torch.float32, "grad_out"), _dev(grad_x, torch.float32, "grad_x"),
+                                      _dev(grad_out, torch.float32, "grad_out"), _dev(argmax, torch.int32, "argmax"),
+                                      _dev(grad_x, torch.float32, "grad_x"),
                                       _dev(grad_e, torch.float32, "grad_e"), ws.data_ptr(), ws.numel(), _stream())
     _check(rc, "gnn_propagate_backward")
     if grad_e is not None and e is not None:

@@ -103,10 +103,14 @@ struct gnn_epilogue {
 // CSR order.
 enum gnn_gather_index { GNN_GATHER_SOURCE_NODE = 0, GNN_GATHER_EDGE_COO = 1, GNN_GATHER_EDGE_CSR = 2 };
 
+// d_winners (optional, sum only, edge data in the caller's order): [rows of x][feat_dim] edge ids; a
+// gathered element x[j,f] only contributes to the edge whose id equals d_winners[j,f] (the routing
+// step of a max aggregation's backward pass).
 // Shared launcher behind gnn_propagate / gnn_aggregate_neighbors / gnn_gin_update / the sparse half
 // of gnn_gcnconv.
 gnn_status gnn_launch_propagate(const gnn_graph *g, const float *d_x, int32_t feat_dim,
                                 const float *d_e, int32_t e_dim, gnn_edge_order e_order,
                                 gnn_msg_op msg, int use_max, const gnn_epilogue &epi,
                                 float *d_out, hipStream_t stream,
-                                gnn_gather_index gather = GNN_GATHER_SOURCE_NODE);
+                                gnn_gather_index gather = GNN_GATHER_SOURCE_NODE,
+                                const int32_t *d_winners = nullptr);

@@ -23,7 +23,12 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kWavesPerBlock = kThreads / 64;
 
-enum { kMsgCopy = 0, kMsgMulScalar = 1, kMsgMulVector = 2 };
+// Message kinds.  The "routed" kinds (+3) are used by the backward pass of a max aggregation: the
+// gathered row is the upstream gradient of the edge's destination and a feature only contributes
+// if the recorded winner of that (destination, feature) is this very edge.
+enum { kMsgCopy = 0, kMsgMulScalar = 1, kMsgMulVector = 2, kMsgRouted = 3 };
+constexpr int msg_base(int msg) { return msg % kMsgRouted; }
+constexpr bool msg_routed(int msg) { return msg >= kMsgRouted; }
 
 struct PropParams {
     const int32_t *rowptr, *colidx, *perm;
@@ -34,6 +39,7 @@ struct PropParams {
     int32_t mean;
     float self_scale;
     const float *row_scale, *bias;
+    const int32_t *winners;   // [rows of x][F] winning edge id per element (routed kinds only)
 };
 
 typedef float v4f __attribute__((ext_vector_type(4)));
@@ -150,24 +156,28 @@ __device__ __forceinline__ void finish_row(const PropParams &p, int row, int deg
 // message op is applied afterwards by apply_message.
 template <int VEC, int MSG>
 __device__ __forceinline__ void fetch_message(const PropParams &p, bool ok, int j, int eid, int col, Row<VEC> &xv,
-                                              Row<VEC> &ev)
+                                              Row<VEC> &ev, Row<VEC> &wv)
 {
 #pragma unroll
-    for (int c = 0; c < VEC; ++c) { xv.v[c] = 0.0f; ev.v[c] = 0.0f; }
+    for (int c = 0; c < VEC; ++c) { xv.v[c] = 0.0f; ev.v[c] = 0.0f; wv.v[c] = 0.0f; }
     if (ok) {
         load_row<VEC>(xv, p.x + (int64_t)j * p.F + col);
-        if constexpr (MSG == kMsgMulVector) load_row_stream<VEC>(ev, p.e + (int64_t)eid * p.F + col);
+        if constexpr (msg_base(MSG) == kMsgMulVector) load_row_stream<VEC>(ev, p.e + (int64_t)eid * p.F + col);
+        if constexpr (msg_routed(MSG))   // winner ids travel as raw bits in a float row
+            load_row<VEC>(wv, reinterpret_cast<const float *>(p.winners) + (int64_t)j * p.F + col);
     }
 }
 
 template <int VEC, int MSG, bool MAX>
-__device__ __forceinline__ void apply_message(Row<VEC> &acc, bool ok, const Row<VEC> &xv, float w, const Row<VEC> &ev)
+__device__ __forceinline__ void apply_message(Row<VEC> &acc, bool ok, const Row<VEC> &xv, float w, const Row<VEC> &ev,
+                                              const Row<VEC> &wv, int eid)
 {
 #pragma unroll
     for (int c = 0; c < VEC; ++c) {
         float m = xv.v[c];
-        if constexpr (MSG == kMsgMulScalar) m = w * m;
-        if constexpr (MSG == kMsgMulVector) m = ev.v[c] * m;
+        if constexpr (msg_base(MSG) == kMsgMulScalar) m = w * m;
+        if constexpr (msg_base(MSG) == kMsgMulVector) m = ev.v[c] * m;
+        if constexpr (msg_routed(MSG)) m = (__float_as_int(wv.v[c]) == eid) ? m : 0.0f;
         if constexpr (MAX)
             acc.v[c] = ok ? max_pz(acc.v[c], m) : acc.v[c];
         else
@@ -207,27 +217,29 @@ __device__ __forceinline__ void short_rows(const PropParams &p, int block)
                 my_j = p.colidx ? load_stream(p.colidx + q) : q;   // no index array: row q itself
                 if constexpr (MSG != kMsgCopy) {
                     my_eid = p.e_coo ? load_stream(p.perm + q) : q;
-                    if constexpr (MSG == kMsgMulScalar) my_w = load_stream(p.e + my_eid);
+                    if constexpr (msg_base(MSG) == kMsgMulScalar) my_w = load_stream(p.e + my_eid);
                 }
             }
             const int cnt = min(LPR, wmax - base);
             for (int t0 = 0; t0 < cnt; t0 += U) {
-                Row<VEC> xv[U], ev[U];
+                Row<VEC> xv[U], ev[U], wv[U];
                 float w[U];
+                int eid[U];
                 bool ok[U];
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     const int t = t0 + u;
                     const int j = __shfl(my_j, t, LPR);
-                    int eid = 0;
+                    eid[u] = 0;
                     w[u] = 0.0f;
-                    if constexpr (MSG == kMsgMulScalar) w[u] = __shfl(my_w, t, LPR);
-                    if constexpr (MSG == kMsgMulVector) eid = __shfl(my_eid, t, LPR);
+                    if constexpr (msg_base(MSG) == kMsgMulScalar) w[u] = __shfl(my_w, t, LPR);
+                    if constexpr (msg_base(MSG) == kMsgMulVector || msg_routed(MSG)) eid[u] = __shfl(my_eid, t, LPR);
                     ok[u] = colok && (base + t < deg);
-                    fetch_message<VEC, MSG>(p, ok[u], j, eid, col, xv[u], ev[u]);
+                    fetch_message<VEC, MSG>(p, ok[u], j, eid[u], col, xv[u], ev[u], wv[u]);
                 }
 #pragma unroll
-                for (int u = 0; u < U; ++u) apply_message<VEC, MSG, MAX>(acc, ok[u], xv[u], w[u], ev[u]);
+                for (int u = 0; u < U; ++u)
+                    apply_message<VEC, MSG, MAX>(acc, ok[u], xv[u], w[u], ev[u], wv[u], eid[u]);
             }
         }
         if (colok) finish_row<VEC, MAX>(p, row, deg, col, acc);
@@ -263,27 +275,29 @@ __device__ __forceinline__ void long_row_pieces(const PropParams &p, int block)
                 my_j = p.colidx ? load_stream(p.colidx + q) : q;   // no index array: row q itself
                 if constexpr (MSG != kMsgCopy) {
                     my_eid = p.e_coo ? load_stream(p.perm + q) : q;
-                    if constexpr (MSG == kMsgMulScalar) my_w = load_stream(p.e + my_eid);
+                    if constexpr (msg_base(MSG) == kMsgMulScalar) my_w = load_stream(p.e + my_eid);
                 }
             }
             // sub-group sg takes batch positions sg, sg + NSG, sg + 2*NSG, ...
             for (int t0 = 0; t0 * NSG < n; t0 += U) {
-                Row<VEC> xv[U], ev[U];
+                Row<VEC> xv[U], ev[U], wv[U];
                 float w[U];
+                int eid[U];
                 bool ok[U];
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     const int pos = (t0 + u) * NSG + sg;   // <= 63 because t0 + u < LPR
                     const int j = __shfl(my_j, pos, 64);
-                    int eid = 0;
+                    eid[u] = 0;
                     w[u] = 0.0f;
-                    if constexpr (MSG == kMsgMulScalar) w[u] = __shfl(my_w, pos, 64);
-                    if constexpr (MSG == kMsgMulVector) eid = __shfl(my_eid, pos, 64);
+                    if constexpr (msg_base(MSG) == kMsgMulScalar) w[u] = __shfl(my_w, pos, 64);
+                    if constexpr (msg_base(MSG) == kMsgMulVector || msg_routed(MSG)) eid[u] = __shfl(my_eid, pos, 64);
                     ok[u] = colok && pos < n;
-                    fetch_message<VEC, MSG>(p, ok[u], j, eid, col, xv[u], ev[u]);
+                    fetch_message<VEC, MSG>(p, ok[u], j, eid[u], col, xv[u], ev[u], wv[u]);
                 }
 #pragma unroll
-                for (int u = 0; u < U; ++u) apply_message<VEC, MSG, MAX>(acc, ok[u], xv[u], w[u], ev[u]);
+                for (int u = 0; u < U; ++u)
+                    apply_message<VEC, MSG, MAX>(acc, ok[u], xv[u], w[u], ev[u], wv[u], eid[u]);
             }
         }
 #pragma unroll
@@ -419,6 +433,9 @@ gnn_status launch_shape(const PropParams &p, int msg, bool use_max, hipStream_t 
     case 3: return launch_typed<LPR, VEC, kMsgMulScalar, true>(p, stream);
     case 4: return launch_typed<LPR, VEC, kMsgMulVector, false>(p, stream);
     case 5: return launch_typed<LPR, VEC, kMsgMulVector, true>(p, stream);
+    case 6: return launch_typed<LPR, VEC, kMsgRouted + kMsgCopy, false>(p, stream);
+    case 8: return launch_typed<LPR, VEC, kMsgRouted + kMsgMulScalar, false>(p, stream);
+    case 10: return launch_typed<LPR, VEC, kMsgRouted + kMsgMulVector, false>(p, stream);
     }
     return GNN_ERR_BAD_SIZE;
 }
@@ -429,11 +446,16 @@ bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 
 gnn_status gnn_launch_propagate(const gnn_graph *g, const float *d_x, int32_t feat_dim, const float *d_e,
                                 int32_t e_dim, gnn_edge_order e_order, gnn_msg_op msg, int use_max,
-                                const gnn_epilogue &epi, float *d_out, hipStream_t stream, gnn_gather_index gather)
+                                const gnn_epilogue &epi, float *d_out, hipStream_t stream, gnn_gather_index gather,
+                                const int32_t *d_winners)
 {
     const int F = feat_dim;
     int kmsg = kMsgCopy;
     if (msg == GNN_MSG_E_MUL_XJ) kmsg = (e_dim == 1) ? kMsgMulScalar : kMsgMulVector;
+    if (d_winners) {
+        if (use_max || e_order != GNN_EDGE_ORDER_COO) return GNN_ERR_UNSUPPORTED;   // edge ids are compared
+        kmsg += kMsgRouted;
+    }
 
     PropParams p{};
     p.rowptr = g->rowptr; p.perm = g->perm;
@@ -445,12 +467,13 @@ gnn_status gnn_launch_propagate(const gnn_graph *g, const float *d_x, int32_t fe
     p.F = F; p.e_coo = (e_order == GNN_EDGE_ORDER_COO) ? 1 : 0;
     p.item_blocks = (int32_t)gnn_div_up(g->n_items, kWavesPerBlock);
     p.mean = epi.mean; p.self_scale = epi.self_scale; p.row_scale = epi.row_scale; p.bias = epi.bias;
+    p.winners = d_winners;
 
     if (g->n_slots > 0) GNN_TRY(gnn_graph_reserve_scratch(g, (size_t)g->n_slots * F));
     p.scratch = g->scratch;
 
     const bool vec4 = (F % 4 == 0) && aligned16(d_x) && aligned16(d_out) &&
-                      (kmsg != kMsgMulVector || aligned16(d_e));
+                      (msg_base(kmsg) != kMsgMulVector || aligned16(d_e)) && aligned16(d_winners);
     const bool mx = use_max != 0;
     if (vec4) {
         const int cols = F / 4;

@@ -242,6 +242,32 @@ def test_propagate_backward(case, gnn, aggr, e_kind):
     gt.close()
 
 
+@pytest.mark.parametrize("e_kind", ["none", "scalar", "vector"])
+def test_propagate_backward_max(case, gnn, e_kind):
+    name, wl, g = case
+    n, ne, f = wl.num_nodes, wl.num_edges, wl.x.shape[1]
+    gt = gnn.build_csr(dev(wl.dst), dev(wl.src), n, 4, 64)
+    gout = synth.normal_f32(27, 7, n * f).reshape(n, f)
+    e = {"none": None, "scalar": wl.edge_weight,
+         "vector": synth.normal_f32(29, 3, ne * f).reshape(ne, f)}[e_kind]
+    msg = MSG_COPY_XJ if e is None else MSG_E_MUL_XJ
+    x = wl.x.copy()
+    x[:, :3] = np.round(x[:, :3])            # plenty of exact ties (and signed zeros) in three columns
+    ref = oracle.propagate_backward(wl.src, wl.dst, n, x, gout, e, msg, AGGR_MAX, with_sabs=True)
+    dx, de = dev(x), (dev(e) if e is not None else None)
+    out = gnn.propagate(g, dx, de, msg, AGGR_MAX)
+    am = gnn.propagate_argmax(g, dx, out, de, msg)
+    np.testing.assert_array_equal(host(am), ref["argmax"])
+    gx, ge = gnn.propagate_backward(g, gt, dx, dev(gout), de, msg, AGGR_MAX, argmax=am)
+    assert_close_sabs(host(gx), ref["grad_x"], ref["sabs_x"], what=f"{name} max grad_x {e_kind}")
+    if e is not None:
+        assert_close_sabs(host(ge).reshape(ne, -1), ref["grad_e"], ref["sabs_e"], what=f"{name} max grad_e {e_kind}")
+    if e_kind == "scalar":   # winners from CSR-ordered weights are the same edges
+        am2 = gnn.propagate_argmax(g, dx, out, gnn.edge_data_to_csr(g, de), msg, e_order=gnn.EDGE_ORDER_CSR)
+        assert torch.equal(am, am2)
+    gt.close()
+
+
 def test_propagate_backward_odd_width_and_errors(gnn):
     wl = powerlaw(2000, 30_000, 7, 900.0)
     n = wl.num_nodes
@@ -253,8 +279,8 @@ def test_propagate_backward_odd_width_and_errors(gnn):
     assert_close_sabs(host(gx), ref["grad_x"], ref["sabs_x"], what="grad_x F=7")
     assert_close_sabs(host(ge).reshape(-1, 1), ref["grad_e"], ref["sabs_e"], what="grad_e F=7")
     with pytest.raises(gnn.GnnError) as ei:
-        gnn.propagate_backward(g, gt, dev(wl.x), dev(gout), None, MSG_COPY_XJ, AGGR_MAX)
-    assert ei.value.code == 4
+        gnn.propagate_backward(g, gt, dev(wl.x), dev(gout), None, MSG_COPY_XJ, AGGR_MAX)   # winners missing
+    assert ei.value.code == 1
     small = gnn.build_csr(dev(wl.dst[:100]), dev(wl.src[:100]), n)
     with pytest.raises(gnn.GnnError):
         gnn.propagate_backward(g, small, dev(wl.x), dev(gout), None, MSG_COPY_XJ, AGGR_SUM)
