@@ -177,6 +177,23 @@ def gcnconv(src, dst, num_nodes: int, x, w, bias=None, add_self_loops: bool = Tr
     return (out, sabs) if with_sabs else out
 
 
+def gcnconv_backward(src, dst, num_nodes: int, x, w, grad_out, add_self_loops: bool = True):
+    """-> dict(grad_x, grad_w, grad_b, sabs_x, sabs_w, sabs_b)."""
+    src, dst, x, w, g = _i32(src, "src"), _i32(dst, "dst"), _f32(x, "x"), _f32(w, "w"), _f32(grad_out, "grad_out")
+    ne, f_in, f_out = src.shape[0], x.shape[1], w.shape[1]
+    if w.shape[0] != f_in or g.shape != (num_nodes, f_out):
+        raise ValueError("shape mismatch")
+    gx, sx = np.empty((num_nodes, f_in), np.float32), np.empty((num_nodes, f_in), np.float64)
+    gw, sw = np.empty((f_in, f_out), np.float32), np.empty((f_in, f_out), np.float64)
+    gb, sb = np.empty(f_out, np.float32), np.empty(f_out, np.float64)
+    rc = _load().oracle_gcnconv_backward(_p(src), _p(dst), ctypes.c_int64(ne), ctypes.c_int32(num_nodes), _p(x),
+                                         ctypes.c_int32(f_in), _p(w), ctypes.c_int32(f_out),
+                                         ctypes.c_int32(1 if add_self_loops else 0), _p(g), _p(gx), _p(gw), _p(gb),
+                                         _p(sx), _p(sw), _p(sb))
+    _check(rc, "gcnconv_backward")
+    return {"grad_x": gx, "grad_w": gw, "grad_b": gb, "sabs_x": sx, "sabs_w": sw, "sabs_b": sb}
+
+
 def segment_softmax(dst, num_nodes: int, scores) -> np.ndarray:
     dst, s = _i32(dst, "dst"), _f32(scores, "scores")
     ne = dst.shape[0]

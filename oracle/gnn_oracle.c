@@ -368,6 +368,74 @@ done:
 }
 
 /*
+ * Backward of the GCNConv forward above.  With Ahat = D^-1/2 (A [+ I]) D^-1/2, Z = X W and
+ * G = dL/d out [N x f_out]:
+ *   T = Ahat^T G,   dL/dX = T W^T,   dL/dW = X^T T,   dL/db[o] = sum_i G[i,o].
+ * Any output may be NULL.  sabs_* (may be NULL) are the sums of absolute values of the terms.
+ */
+int oracle_gcnconv_backward(const int32_t *src, const int32_t *dst, int64_t E, int32_t N,
+                            const float *x, int32_t f_in, const float *w, int32_t f_out,
+                            int32_t add_self_loops, const float *grad_out,
+                            float *grad_x, float *grad_w, float *grad_b,
+                            double *sabs_x, double *sabs_w, double *sabs_b)
+{
+    if (N <= 0 || E < 0 || f_in <= 0 || f_out <= 0) return 2;
+    if (check_edges(src, dst, E, N)) return 1;
+    double *deg = (double *)calloc((size_t)N, sizeof(double));
+    double *t = (double *)calloc((size_t)N * f_out, sizeof(double));
+    double *ta = (double *)calloc((size_t)N * f_out, sizeof(double));
+    if (!deg || !t || !ta) { free(deg); free(t); free(ta); return 3; }
+    for (int64_t k = 0; k < E; ++k) deg[dst[k]] += 1.0;
+    if (add_self_loops)
+        for (int32_t i = 0; i < N; ++i) deg[i] += 1.0;
+    /* T[j,:] += c(i,j) G[i,:] for every edge j -> i (and every self-loop) */
+    for (int64_t k = 0; k < E + (add_self_loops ? N : 0); ++k) {
+        int64_t i = k < E ? dst[k] : k - E, j = k < E ? src[k] : k - E;
+        double dd = deg[i] * deg[j];
+        double c = dd > 0.0 ? 1.0 / sqrt(dd) : 0.0;
+        for (int32_t o = 0; o < f_out; ++o) {
+            double g = (double)grad_out[i * f_out + o];
+            t[j * f_out + o] += c * g;
+            ta[j * f_out + o] += c * fabs(g);
+        }
+    }
+    if (grad_x || sabs_x)
+        for (int32_t i = 0; i < N; ++i)
+            for (int32_t q = 0; q < f_in; ++q) {
+                double a = 0.0, sa = 0.0;
+                for (int32_t o = 0; o < f_out; ++o) {
+                    a += t[(int64_t)i * f_out + o] * (double)w[(int64_t)q * f_out + o];
+                    sa += ta[(int64_t)i * f_out + o] * fabs((double)w[(int64_t)q * f_out + o]);
+                }
+                if (grad_x) grad_x[(int64_t)i * f_in + q] = (float)a;
+                if (sabs_x) sabs_x[(int64_t)i * f_in + q] = sa;
+            }
+    if (grad_w || sabs_w)
+        for (int32_t q = 0; q < f_in; ++q)
+            for (int32_t o = 0; o < f_out; ++o) {
+                double a = 0.0, sa = 0.0;
+                for (int32_t i = 0; i < N; ++i) {
+                    a += (double)x[(int64_t)i * f_in + q] * t[(int64_t)i * f_out + o];
+                    sa += fabs((double)x[(int64_t)i * f_in + q]) * ta[(int64_t)i * f_out + o];
+                }
+                if (grad_w) grad_w[(int64_t)q * f_out + o] = (float)a;
+                if (sabs_w) sabs_w[(int64_t)q * f_out + o] = sa;
+            }
+    if (grad_b || sabs_b)
+        for (int32_t o = 0; o < f_out; ++o) {
+            double a = 0.0, sa = 0.0;
+            for (int32_t i = 0; i < N; ++i) {
+                a += (double)grad_out[(int64_t)i * f_out + o];
+                sa += fabs((double)grad_out[(int64_t)i * f_out + o]);
+            }
+            if (grad_b) grad_b[o] = (float)a;
+            if (sabs_b) sabs_b[o] = sa;
+        }
+    free(deg); free(t); free(ta);
+    return 0;
+}
+
+/*
  * Segment softmax over each destination's incoming edges, per head:
  *   alpha[k,h] = exp(s[k,h] - mx[i,h]) / sum_{q: dst[q]=i} exp(s[q,h] - mx[i,h]),  i = dst[k],
  * with mx the segment maximum (so the denominator is >= 1 and needs no epsilon).

@@ -434,6 +434,33 @@ def test_backward_max_ties_go_to_the_first_edge():
     np.testing.assert_array_equal(bw["grad_x"][:, 0], [0.0, 2.0, 0.0, 0.0])
 
 
+@pytest.mark.parametrize("loops", [True, False])
+def test_gcn_backward_dense_and_adjoint(loops):
+    n, f_in, f_out = 40, 5, 3
+    src, dst = rng_graph(95, n, 300, star=True)
+    x = synth.normal_f32(95, 2, n * f_in).reshape(n, f_in)
+    w = synth.glorot_uniform(95, 4, f_in, f_out, (f_in, f_out))
+    b = synth.uniform_f32(95, 5, f_out, -1, 1)
+    g = synth.normal_f32(95, 7, n * f_out).reshape(n, f_out)
+    bw = oracle.gcnconv_backward(src, dst, n, x, w, g, loops)
+    # dense operator
+    a = dense_adjacency(src, dst, n) + (np.eye(n) if loops else 0.0)
+    d = a.sum(1)
+    dinv = np.where(d > 0, 1.0 / np.sqrt(np.maximum(d, 1e-300)), 0.0)
+    ahat = dinv[:, None] * a * dinv[None, :]
+    t = ahat.T @ g.astype(np.float64)
+    np.testing.assert_allclose(bw["grad_x"], t @ w.astype(np.float64).T, rtol=0, atol=2e-7 * np.abs(t).max() * 3)
+    np.testing.assert_allclose(bw["grad_w"], x.astype(np.float64).T @ t, rtol=0, atol=3e-7 * np.abs(x.T @ t).max())
+    np.testing.assert_allclose(bw["grad_b"], g.astype(np.float64).sum(0), rtol=1e-6, atol=1e-6)
+    # the loss <out, g> is linear in X, in W and in b: each gradient paired with its variable gives it back
+    out = oracle.gcnconv(src, dst, n, x, w, b, loops).astype(np.float64)
+    loss = (out * g).sum()
+    bias_part = (b.astype(np.float64)[None, :] * g).sum()
+    np.testing.assert_allclose((bw["grad_x"].astype(np.float64) * x).sum(), loss - bias_part, rtol=1e-5, atol=1e-5)
+    np.testing.assert_allclose((bw["grad_w"].astype(np.float64) * w).sum(), loss - bias_part, rtol=1e-5, atol=1e-5)
+    np.testing.assert_allclose((bw["grad_b"].astype(np.float64) * b).sum(), bias_part, rtol=1e-5, atol=1e-5)
+
+
 def test_error_codes():
     src = np.array([0, 5], np.int32)
     dst = np.array([1, 0], np.int32)
