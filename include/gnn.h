@@ -189,6 +189,20 @@ gnn_status gnn_gcnconv(const gnn_graph *g, const float *d_x, int32_t f_in, const
                        void *d_workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Backward of gnn_gcnconv: with Ahat the normalised (self-looped) adjacency of the forward call and
+ * G = d_grad_out [N x f_out]:   T = Ahat^T G;
+ *   d_grad_x [N x f_in] = T W^T,   d_grad_w [f_in x f_out] = X^T T,   d_grad_b [f_out] = column sums of G.
+ * Each output may be NULL.  g is the forward graph, g_by_source the same edges sorted by source
+ * (gnn_build_csr with d_src and d_dst exchanged).  d_workspace: 256-byte aligned device scratch of
+ * gnn_gcnconv_backward_workspace_bytes(N, f_in, f_out) bytes.
+ */
+size_t gnn_gcnconv_backward_workspace_bytes(int32_t num_nodes, int32_t f_in, int32_t f_out);
+gnn_status gnn_gcnconv_backward(const gnn_graph *g, const gnn_graph *g_by_source, const float *d_x, int32_t f_in,
+                                const float *d_w, int32_t f_out, int32_t add_self_loops,
+                                const float *d_grad_out, float *d_grad_x, float *d_grad_w, float *d_grad_b,
+                                void *d_workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Segment softmax over each destination's incoming edges, independently per head:
  *   out[k,h] = exp(s[k,h] - m[i,h]) / sum_{q: dst[q] = i} exp(s[q,h] - m[i,h]),  i = dst[k],
  * m = the segment maximum.  d_scores and d_out are [E x heads], both in the order `order` names.

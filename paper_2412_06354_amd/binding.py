@@ -46,6 +46,8 @@ SIGNATURES = {
                                           _sz, _vp]),
     "gnn_gcnconv_workspace_bytes": (_sz, [_i32, _i32]),
     "gnn_gcnconv": (_c.c_int, [_vp, _vp, _i32, _vp, _vp, _i32, _i32, _vp, _vp, _sz, _vp]),
+    "gnn_gcnconv_backward_workspace_bytes": (_sz, [_i32, _i32, _i32]),
+    "gnn_gcnconv_backward": (_c.c_int, [_vp, _vp, _vp, _i32, _vp, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "gnn_segment_softmax": (_c.c_int, [_vp, _vp, _i32, _c.c_int, _vp, _vp]),
     "gnn_gatconv_workspace_bytes": (_sz, [_i32, _i32, _i32]),
     "gnn_gatconv": (_c.c_int, [_vp, _vp, _i32, _vp, _vp, _vp, _i32, _i32, _f32, _vp, _vp, _sz, _vp]),
@@ -290,6 +292,27 @@ def gcnconv(g: Graph, x: torch.Tensor, w: torch.Tensor, bias: Optional[torch.Ten
                            _dev(out, torch.float32, "out"), workspace.data_ptr(), workspace.numel(), _stream())
     _check(rc, "gnn_gcnconv")
     return out
+
+
+def gcnconv_backward(g: Graph, g_by_source: Graph, x: torch.Tensor, w: torch.Tensor, grad_out: torch.Tensor,
+                     add_self_loops: bool = True, workspace: Optional[torch.Tensor] = None):
+    """-> (grad_x [N, f_in], grad_w [f_in, f_out], grad_b [f_out])."""
+    n, f_in = x.shape
+    f_out = int(w.shape[1])
+    if tuple(grad_out.shape) != (n, f_out) or w.shape[0] != f_in:
+        raise ValueError("shape mismatch")
+    need = int(lib().gnn_gcnconv_backward_workspace_bytes(n, f_in, f_out))
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+    gx = torch.empty_like(x)
+    gw = torch.empty_like(w)
+    gb = torch.empty(f_out, dtype=torch.float32, device=x.device)
+    rc = lib().gnn_gcnconv_backward(g._h, g_by_source._h, _dev(x, torch.float32, "x"), f_in, _dev(w, torch.float32, "w"),
+                                    f_out, 1 if add_self_loops else 0, _dev(grad_out, torch.float32, "grad_out"),
+                                    gx.data_ptr(), gw.data_ptr(), gb.data_ptr(), workspace.data_ptr(),
+                                    workspace.numel(), _stream())
+    _check(rc, "gnn_gcnconv_backward")
+    return gx, gw, gb
 
 
 def segment_softmax(g: Graph, scores: torch.Tensor, order: int = EDGE_ORDER_COO,

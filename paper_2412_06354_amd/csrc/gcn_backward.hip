@@ -1,0 +1,219 @@
+// Backward of GCNConv (the layer of the paper's training example, which is differentiated end to
+// end).  With Ahat = D^-1/2 (A [+ I]) D^-1/2 and G = dL/d out:
+//     T = Ahat^T G,    dL/dX = T W^T,    dL/dW = X^T T,    dL/db = column sums of G.
+//   * T is a propagate over the graph sorted by source: rows of G are pre-scaled by the destination
+//     side factor, gathered and summed, and the epilogue adds the self-loop term and applies the
+//     source side factor -- the forward's fused kernel run on the transposed topology (the degree
+//     factors always come from the forward graph's in-degrees);
+//   * T W^T is the MFMA projection kernel on a transposed copy of W;
+//   * X^T T contracts over the N rows: v_mfma_f32_32x32x2_f32 consumes two rows per instruction and
+//     both operands are read along rows (coalesced); row chunks give partial [f_in x f_out] blocks
+//     that a second kernel adds up in chunk order (deterministic);
+//   * the bias gradient uses the same two-stage scheme.
+#include "gnn_internal.h"
+
+#include <algorithm>
+
+namespace {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+constexpr int kThreads = 256;
+
+__global__ __launch_bounds__(kThreads) void inv_sqrt_degree_kernel(const int32_t *__restrict__ indeg, int32_t N,
+                                                                   int32_t extra, float *__restrict__ dinv)
+{
+    const int32_t i = blockIdx.x * kThreads + threadIdx.x;
+    if (i >= N) return;
+    const int32_t d = indeg[i] + extra;
+    dinv[i] = d > 0 ? 1.0f / sqrtf((float)d) : 0.0f;
+}
+
+__global__ __launch_bounds__(kThreads) void scale_rows_kernel(const float *__restrict__ scale, int64_t N, int F,
+                                                              const float *__restrict__ in, float *__restrict__ out)
+{
+    const int64_t total = N * F;
+    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    for (int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x; idx < total; idx += stride)
+        out[idx] = in[idx] * scale[idx / F];
+}
+
+__global__ __launch_bounds__(kThreads) void transpose_kernel(const float *__restrict__ w, int rows, int cols,
+                                                             float *__restrict__ wt)
+{
+    const int idx = blockIdx.x * kThreads + threadIdx.x;
+    if (idx >= rows * cols) return;
+    const int r = idx / cols, c = idx - r * cols;
+    wt[c * rows + r] = w[idx];
+}
+
+// partial[chunk][i][j] = sum over the chunk's rows of X[row][i] * Y[row][j].
+// Block = 4 wavefronts = four 32-wide strips of i; a wavefront holds NT 32x32 accumulator tiles.
+template <int NT>
+__global__ __launch_bounds__(kThreads) void xty_partial_kernel(const float *__restrict__ x, const float *__restrict__ y,
+                                                               int64_t rows, int f_in, int f_out,
+                                                               int64_t rows_per_chunk, float *__restrict__ partial)
+{
+    constexpr int U = 4;   // row pairs in flight
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int c = lane & 31, kk = lane >> 5;
+    const int i0 = (blockIdx.y * 4 + wave) * 32;
+    const int j0 = blockIdx.z * NT * 32;
+    const int64_t r0 = (int64_t)blockIdx.x * rows_per_chunk, r1 = min(rows, r0 + rows_per_chunk);
+    const bool i_ok = i0 + c < f_in;
+
+    floatx16 acc[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[t][v] = 0.0f;
+
+    if (i0 < f_in) {   // wavefront-uniform
+        for (int64_t rp = r0; rp < r1; rp += 2 * U) {
+            float a[U], b[U][NT];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int64_t row = rp + 2 * u + kk;
+                const bool ok = row < r1;
+                a[u] = (ok && i_ok) ? x[row * f_in + i0 + c] : 0.0f;
+#pragma unroll
+                for (int t = 0; t < NT; ++t) {
+                    const int j = j0 + t * 32 + c;
+                    b[u][t] = (ok && j < f_out) ? y[row * f_out + j] : 0.0f;
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int t = 0; t < NT; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u], b[u][t], acc[t], 0, 0, 0);
+        }
+        // accumulator register v of lane l: row 8*(v/4) + 4*(l/32) + v%4, column l%32
+        float *out = partial + (int64_t)blockIdx.x * f_in * f_out;
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int i = i0 + 8 * (v / 4) + 4 * kk + (v % 4);
+                const int j = j0 + t * 32 + c;
+                if (i < f_in && j < f_out) out[(int64_t)i * f_out + j] = acc[t][v];
+            }
+    }
+}
+
+// partial[chunk][j] = sum over the chunk's rows of G[row][j]
+__global__ __launch_bounds__(kThreads) void colsum_partial_kernel(const float *__restrict__ g, int64_t rows, int F,
+                                                                  int64_t rows_per_chunk, float *__restrict__ partial)
+{
+    const int64_t r0 = (int64_t)blockIdx.x * rows_per_chunk, r1 = min(rows, r0 + rows_per_chunk);
+    for (int j = threadIdx.x; j < F; j += kThreads) {
+        float s = 0.0f;
+        for (int64_t r = r0; r < r1; ++r) s += g[r * F + j];
+        partial[(int64_t)blockIdx.x * F + j] = s;
+    }
+}
+
+// out[q] = sum over chunks (in chunk order) of partial[chunk][q]
+__global__ __launch_bounds__(kThreads) void sum_partials_kernel(const float *__restrict__ partial, int chunks,
+                                                                int64_t elems, float *__restrict__ out)
+{
+    const int64_t q = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (q >= elems) return;
+    float s = 0.0f;
+    for (int ch = 0; ch < chunks; ++ch) s += partial[(int64_t)ch * elems + q];
+    out[q] = s;
+}
+
+size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
+
+int chunk_count(int64_t rows) { return (int)std::max<int64_t>(1, std::min<int64_t>(1024, gnn_div_up(rows, 128))); }
+
+struct BackwardLayout {
+    size_t gs, t, dinv, wt, part, total;
+};
+
+BackwardLayout layout(int64_t N, int f_in, int f_out)
+{
+    BackwardLayout l{};
+    const size_t nf = align256((size_t)N * f_out * sizeof(float));
+    const int chunks = chunk_count(N);
+    l.gs = 0;
+    l.t = nf;
+    l.dinv = 2 * nf;
+    l.wt = l.dinv + align256((size_t)N * sizeof(float));
+    l.part = l.wt + align256((size_t)f_in * f_out * sizeof(float));
+    l.total = l.part + align256((size_t)chunks * std::max(f_in, 1) * f_out * sizeof(float));
+    return l;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t gnn_gcnconv_backward_workspace_bytes(int32_t num_nodes, int32_t f_in, int32_t f_out)
+{
+    if (num_nodes <= 0 || f_in <= 0 || f_out <= 0) return 0;
+    return layout(num_nodes, f_in, f_out).total;
+}
+
+gnn_status gnn_gcnconv_backward(const gnn_graph *g, const gnn_graph *g_by_source, const float *d_x, int32_t f_in,
+                                const float *d_w, int32_t f_out, int32_t add_self_loops, const float *d_grad_out,
+                                float *d_grad_x, float *d_grad_w, float *d_grad_b, void *d_workspace,
+                                size_t workspace_bytes, void *stream)
+{
+    if (!g || !g_by_source || !d_grad_out || !d_workspace) return GNN_ERR_NULL;
+    if (f_in <= 0 || f_out <= 0) return GNN_ERR_BAD_SIZE;
+    if (g_by_source->num_nodes != g->num_nodes || g_by_source->num_edges != g->num_edges) return GNN_ERR_BAD_SIZE;
+    if ((d_grad_x && !d_w) || (d_grad_w && !d_x)) return GNN_ERR_NULL;
+    const int64_t N = g->num_nodes;
+    const BackwardLayout l = layout(N, f_in, f_out);
+    if (workspace_bytes < l.total) return GNN_ERR_BAD_SIZE;
+    if (reinterpret_cast<uintptr_t>(d_workspace) & 255u) return GNN_ERR_BAD_SIZE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    char *ws = static_cast<char *>(d_workspace);
+    float *gs = reinterpret_cast<float *>(ws + l.gs), *t = reinterpret_cast<float *>(ws + l.t),
+          *dinv = reinterpret_cast<float *>(ws + l.dinv), *wt = reinterpret_cast<float *>(ws + l.wt),
+          *part = reinterpret_cast<float *>(ws + l.part);
+    const int chunks = chunk_count(N);
+    const int64_t rows_per_chunk = gnn_div_up(N, chunks);
+
+    if (d_grad_x || d_grad_w) {
+        hipLaunchKernelGGL(inv_sqrt_degree_kernel, dim3((unsigned)gnn_div_up(N, kThreads)), dim3(kThreads), 0, s,
+                           g->indeg, (int32_t)N, add_self_loops ? 1 : 0, dinv);
+        GNN_LAUNCH_CHECK();
+        const int blocks = (int)std::min<int64_t>(gnn_div_up(N * f_out, kThreads), 256 * 64);
+        hipLaunchKernelGGL(scale_rows_kernel, dim3(blocks), dim3(kThreads), 0, s, dinv, N, f_out, d_grad_out, gs);
+        GNN_LAUNCH_CHECK();
+        gnn_epilogue epi;
+        epi.self_scale = add_self_loops ? 1.0f : 0.0f;
+        epi.row_scale = dinv;
+        GNN_TRY(gnn_launch_propagate(g_by_source, gs, f_out, nullptr, 1, GNN_EDGE_ORDER_CSR, GNN_MSG_COPY_XJ, 0, epi,
+                                     t, s));
+    }
+    if (d_grad_x) {
+        hipLaunchKernelGGL(transpose_kernel, dim3((unsigned)gnn_div_up((int64_t)f_in * f_out, kThreads)),
+                           dim3(kThreads), 0, s, d_w, f_in, f_out, wt);
+        GNN_LAUNCH_CHECK();
+        GNN_TRY(gnn_dense_xw(t, N, f_out, wt, f_in, nullptr, d_grad_x, stream));
+    }
+    if (d_grad_w) {
+        constexpr int NT = 4;
+        const dim3 grid((unsigned)chunks, (unsigned)gnn_div_up(f_in, 128), (unsigned)gnn_div_up(f_out, NT * 32));
+        hipLaunchKernelGGL(xty_partial_kernel<NT>, grid, dim3(kThreads), 0, s, d_x, t, N, f_in, f_out, rows_per_chunk,
+                           part);
+        GNN_LAUNCH_CHECK();
+        const int64_t elems = (int64_t)f_in * f_out;
+        hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)gnn_div_up(elems, kThreads)), dim3(kThreads), 0, s, part,
+                           chunks, elems, d_grad_w);
+        GNN_LAUNCH_CHECK();
+    }
+    if (d_grad_b) {
+        hipLaunchKernelGGL(colsum_partial_kernel, dim3((unsigned)chunks), dim3(kThreads), 0, s, d_grad_out, N, f_out,
+                           rows_per_chunk, part);
+        GNN_LAUNCH_CHECK();
+        hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)gnn_div_up(f_out, kThreads)), dim3(kThreads), 0, s, part,
+                           chunks, (int64_t)f_out, d_grad_b);
+        GNN_LAUNCH_CHECK();
+    }
+    return GNN_OK;
+}
+
+}  // extern "C"

@@ -361,6 +361,23 @@ def test_gcnconv(gnn, loops, golden_dir):
     g.close()
 
 
+@pytest.mark.parametrize("loops,f_in,f_out", [(True, 128, 128), (False, 128, 128), (True, 16, 64), (True, 37, 50)])
+def test_gcnconv_backward(gnn, loops, f_in, f_out):
+    wl = synth.config1_gcn(num_nodes=20_000, pairs=100_000, f_in=f_in, f_out=f_out)
+    n = wl.num_nodes
+    w = wl.params["w"]
+    gout = synth.normal_f32(33, 7, n * f_out).reshape(n, f_out)
+    g = gnn.build_csr(dev(wl.src), dev(wl.dst), n, 8, 64)
+    gt = gnn.build_csr(dev(wl.dst), dev(wl.src), n, 8, 64)
+    ref = oracle.gcnconv_backward(wl.src, wl.dst, n, wl.x, w, gout, loops)
+    gx, gw, gb = gnn.gcnconv_backward(g, gt, dev(wl.x), dev(w), dev(gout), loops)
+    assert_close_sabs(host(gx), ref["grad_x"], ref["sabs_x"], what="gcn grad_x")
+    assert_close_sabs(host(gw), ref["grad_w"], ref["sabs_w"], what="gcn grad_w")
+    assert_close_sabs(host(gb), ref["grad_b"], ref["sabs_b"], what="gcn grad_b")
+    g.close()
+    gt.close()
+
+
 @pytest.mark.parametrize("heads", [1, 8, 3])
 def test_segment_softmax(case, gnn, heads):
     name, wl, g = case
