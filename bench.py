@@ -17,6 +17,7 @@ Other workloads measure the remaining steps of the path, one JSON line each:
   batched  gnn_gin_update + gnn_graph_pool on 4 096 batched small graphs, F = 32
   tiny     gnn_propagate sum / mean / max on the 2 708-node graph (launch-latency bound)
   backward gnn_propagate_backward (e_mul_xj, sum: grad_x and grad_e) on the headline graph
+  gcn_backward gnn_gcnconv_backward (grad X, W, b) on the GCN graph
 
 Every line carries `value` (algorithmic GB/s = the byte model of the step / mean step time), a
 `roofline` object for the dominant kernel and a `cpu_baseline` object (the parity oracle, one thread,
@@ -407,7 +408,41 @@ def run_backward(args, torch, gnn, synth):
     return line
 
 
-WORKLOADS = {"backward": run_backward, "propagate": run_propagate, "csr": run_csr, "softmax": run_softmax, "gcn": run_gcn, "gat": run_gat,
+def run_gcn_backward(args, torch, gnn, synth):
+    wl = synth.config1_gcn()
+    n, e, f_in = wl.num_nodes, wl.num_edges, wl.x.shape[1]
+    w_h = wl.params["w"]
+    f_out = w_h.shape[1]
+    src, dst = to_dev(torch, wl.src), to_dev(torch, wl.dst)
+    g, gt = gnn.build_csr(src, dst, n), gnn.build_csr(dst, src, n)
+    x, w = to_dev(torch, wl.x), to_dev(torch, w_h)
+    gout_h = synth.normal_f32(33, 7, n * f_out).reshape(n, f_out)
+    gout = to_dev(torch, gout_h)
+    ws = torch.empty(int(gnn.lib().gnn_gcnconv_backward_workspace_bytes(n, f_in, f_out)), dtype=torch.uint8, device="cuda")
+    ms = time_calls(torch, lambda: gnn.gcnconv_backward(g, gt, x, w, gout, True, workspace=ws), args.steps, args.warmup)
+    # T = Ahat^T G (a GCN sparse half on G), T W^T and X^T T (each reads two N x f matrices and W), column sums
+    bytes_sp = (e + n) * (4 * f_out + 4) + 3 * n * 4 * f_out + (n + 1) * 4 + n * 8
+    bytes_dense = 4 * (n * f_out + f_in * f_out + n * f_in) + 4 * (n * f_in + n * f_out + f_in * f_out) + 4 * n * f_out
+    flops = 4.0 * n * f_in * f_out
+    gbs = (bytes_sp + bytes_dense) / (ms * 1e-3) / 1e9
+    line = base_line("GCNConv backward (grad X, W, b) algorithmic GB/s", gbs, ms, args, wl.name + ":backward",
+                     {"N": n, "E": e, "f_in": f_in, "f_out": f_out})
+    line["roofline"] = hbm_roofline(gbs, "whole call: propagate_kernel<32,4> on the by-source graph, xw_fast_kernel, "
+                                         "xty_partial_kernel, reductions")
+    line["extra"] = {"dense_flops": flops, "dense_TFLOPs_if_all_time_were_dense": flops / (ms * 1e-3) / 1e12}
+    if not args.no_cpu_baseline:
+        import oracle
+        t0 = time.perf_counter()
+        oracle.gcnconv_backward(wl.src, wl.dst, n, wl.x, w_h, gout_h, True)
+        dt = time.perf_counter() - t0
+        line["cpu_baseline"] = {"value": (bytes_sp + bytes_dense) / dt / 1e9, "unit": "GB/s", "cores": 1,
+                                "kind": "oracle", "seconds": dt, "sample": "the whole layer, one pass"}
+    g.close()
+    gt.close()
+    return line
+
+
+WORKLOADS = {"gcn_backward": run_gcn_backward, "backward": run_backward, "propagate": run_propagate, "csr": run_csr, "softmax": run_softmax, "gcn": run_gcn, "gat": run_gat,
              "batched": run_batched, "tiny": run_tiny}
 
 

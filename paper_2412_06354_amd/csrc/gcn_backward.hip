@@ -105,26 +105,45 @@ __global__ __launch_bounds__(kThreads) void colsum_partial_kernel(const float *_
 {
     const int64_t r0 = (int64_t)blockIdx.x * rows_per_chunk, r1 = min(rows, r0 + rows_per_chunk);
     for (int j = threadIdx.x; j < F; j += kThreads) {
-        float s = 0.0f;
-        for (int64_t r = r0; r < r1; ++r) s += g[r * F + j];
-        partial[(int64_t)blockIdx.x * F + j] = s;
+        float s[4] = {0.0f, 0.0f, 0.0f, 0.0f};   // four interleaved running sums: loads stay independent
+        int64_t r = r0;
+        for (; r + 4 <= r1; r += 4) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) s[u] += g[(r + u) * F + j];
+        }
+        for (; r < r1; ++r) s[0] += g[r * F + j];
+        partial[(int64_t)blockIdx.x * F + j] = (s[0] + s[1]) + (s[2] + s[3]);
     }
 }
 
-// out[q] = sum over chunks (in chunk order) of partial[chunk][q]
+// out[q] = sum over chunks of partial[chunk][q], in a fixed order: a block owns 64 elements, its four
+// thread rows take the chunks round-robin (eight loads in flight each) and are folded through LDS.
 __global__ __launch_bounds__(kThreads) void sum_partials_kernel(const float *__restrict__ partial, int chunks,
                                                                 int64_t elems, float *__restrict__ out)
 {
-    const int64_t q = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (q >= elems) return;
+    __shared__ float fold[4][64];
+    const int lane = threadIdx.x & 63, slice = threadIdx.x >> 6;
+    const int64_t q = (int64_t)blockIdx.x * 64 + lane;
     float s = 0.0f;
-    for (int ch = 0; ch < chunks; ++ch) s += partial[(int64_t)ch * elems + q];
-    out[q] = s;
+    if (q < elems) {
+        int ch = slice;
+        for (; ch + 28 < chunks; ch += 32) {
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = partial[(int64_t)(ch + 4 * u) * elems + q];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) s += v[u];
+        }
+        for (; ch < chunks; ch += 4) s += partial[(int64_t)ch * elems + q];
+    }
+    fold[slice][lane] = s;
+    __syncthreads();
+    if (slice == 0 && q < elems) out[q] = (fold[0][lane] + fold[1][lane]) + (fold[2][lane] + fold[3][lane]);
 }
 
 size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
 
-int chunk_count(int64_t rows) { return (int)std::max<int64_t>(1, std::min<int64_t>(1024, gnn_div_up(rows, 128))); }
+int chunk_count(int64_t rows) { return (int)std::max<int64_t>(1, std::min<int64_t>(512, gnn_div_up(rows, 256))); }
 
 struct BackwardLayout {
     size_t gs, t, dinv, wt, part, total;
@@ -201,7 +220,7 @@ gnn_status gnn_gcnconv_backward(const gnn_graph *g, const gnn_graph *g_by_source
                            part);
         GNN_LAUNCH_CHECK();
         const int64_t elems = (int64_t)f_in * f_out;
-        hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)gnn_div_up(elems, kThreads)), dim3(kThreads), 0, s, part,
+        hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)gnn_div_up(elems, 64)), dim3(kThreads), 0, s, part,
                            chunks, elems, d_grad_w);
         GNN_LAUNCH_CHECK();
     }
@@ -209,7 +228,7 @@ gnn_status gnn_gcnconv_backward(const gnn_graph *g, const gnn_graph *g_by_source
         hipLaunchKernelGGL(colsum_partial_kernel, dim3((unsigned)chunks), dim3(kThreads), 0, s, d_grad_out, N, f_out,
                            rows_per_chunk, part);
         GNN_LAUNCH_CHECK();
-        hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)gnn_div_up(f_out, kThreads)), dim3(kThreads), 0, s, part,
+        hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)gnn_div_up(f_out, 64)), dim3(kThreads), 0, s, part,
                            chunks, (int64_t)f_out, d_grad_b);
         GNN_LAUNCH_CHECK();
     }
