@@ -45,10 +45,16 @@ __device__ __forceinline__ void load_vec(float (&v)[VEC], const float *__restric
     }
 }
 
-// One sub-group of LPR lanes per CSR position q (edge perm[q] from colidx[q] to rowidx[q]); a lane owns
-// VEC features per column block.  EVEC: element-wise edge data (no reduction), else one dot product.
-// winners (or NULL): only features whose recorded winner is this edge contribute (max aggregation).
-template <int LPR, int VEC, bool EVEC>
+// A wavefront takes 64 consecutive CSR positions (edge perm[q] from colidx[q] to rowidx[q]) per round: every
+// lane fetches the indices of one position (coalesced), then each sub-group of LPR lanes walks over its own
+// LPR consecutive positions in batches of U, a lane owning VEC features per column block; the row gathers of
+// a batch are issued before their products are taken.  EVEC: element-wise edge data (rows written directly);
+// else one dot product per position: the U partial dots a lane holds are folded by a halving exchange (a
+// lane gives away the half it does not keep; U-1 shuffles for U positions) and then across the remaining
+// lane bits, in a fixed order; lane t of the sub-group ends up with the total of its own position.
+// WIN: only features whose recorded winner is this edge contribute (max aggregation); a template
+// parameter because a run-time branch between the gathers would make the compiler wait for each of them.
+template <int LPR, int VEC, bool EVEC, bool WIN>
 __global__ __launch_bounds__(kThreads) void edge_gradient_kernel(const int32_t *__restrict__ rowidx,
                                                                  const int32_t *__restrict__ colidx,
                                                                  const int32_t *__restrict__ perm, int64_t E, int F,
@@ -57,40 +63,75 @@ __global__ __launch_bounds__(kThreads) void edge_gradient_kernel(const int32_t *
                                                                  const int32_t *__restrict__ winners,
                                                                  float *__restrict__ grad_e)
 {
-    const int sl = threadIdx.x % LPR;
-    const int64_t q = ((int64_t)blockIdx.x * kThreads + threadIdx.x) / LPR;
-    const bool have = q < E;   // no early return: the shuffles below run with every lane active
-    const int64_t qc = have ? q : E - 1;
-    const int64_t i = rowidx[qc], j = colidx[qc], k = perm[qc];
-    float dot = 0.0f;
-    for (int cb = 0; cb * LPR * VEC < F; ++cb) {
-        const int col = (cb * LPR + sl) * VEC;
-        if (col < F) {
-            float xv[VEC], gv[VEC];
-            load_vec<VEC>(xv, x + j * F + col);
-            load_vec<VEC>(gv, gp + i * F + col);
-            if (winners) {
-                float wv[VEC];   // edge ids as raw bits
-                load_vec<VEC>(wv, reinterpret_cast<const float *>(winners) + i * F + col);
+    constexpr int U = LPR < 8 ? LPR : 8;
+    const int lane = threadIdx.x & 63, sl = lane % LPR;
+    const int64_t waves = (int64_t)gridDim.x * (kThreads / 64);
+    for (int64_t q0 = (((int64_t)blockIdx.x * kThreads + threadIdx.x) >> 6) * 64; q0 < E; q0 += waves * 64) {
+        const int64_t q = q0 + lane;
+        const bool have = q < E;
+        const int64_t qc = have ? q : E - 1;   // clamped: loads stay in bounds, results are dropped
+        const int i_own = rowidx[qc], j_own = colidx[qc], k_own = perm[qc];
+        const int64_t group_q0 = q0 + (lane - sl);
+        float mine = 0.0f;
+        for (int cb = 0; cb * LPR * VEC < F; ++cb) {
+            const int col = (cb * LPR + sl) * VEC;
+            const bool ok = col < F;
+            const int colc = ok ? col : 0;
+            for (int t0 = 0; t0 < LPR; t0 += U) {
+                float xv[U][VEC], gv[U][VEC], d[U];
+                int kk[U];
 #pragma unroll
-                for (int c = 0; c < VEC; ++c)
-                    if (__float_as_int(wv[c]) != (int)k) gv[c] = 0.0f;
-            }
-            if constexpr (EVEC) {
-                if (have) {
+                for (int u = 0; u < U; ++u) {
+                    const int64_t i = __shfl(i_own, t0 + u, LPR), j = __shfl(j_own, t0 + u, LPR);
+                    load_vec<VEC>(xv[u], x + j * F + colc);
+                    load_vec<VEC>(gv[u], gp + i * F + colc);
+                    if constexpr (EVEC || WIN) kk[u] = __shfl(k_own, t0 + u, LPR);
+                    if constexpr (WIN) {
+                        float wv[VEC];   // edge ids as raw bits
+                        load_vec<VEC>(wv, reinterpret_cast<const float *>(winners) + i * F + colc);
 #pragma unroll
-                    for (int c = 0; c < VEC; ++c) grad_e[k * F + col + c] = xv[c] * gv[c];
+                        for (int c = 0; c < VEC; ++c)
+                            if (__float_as_int(wv[c]) != kk[u]) gv[u][c] = 0.0f;
+                    }
                 }
-            } else {
+                // all gathers of the batch are in flight before the first product: without the barrier the
+                // scheduler interleaves them pairwise with the arithmetic to save registers
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int c = 0; c < VEC; ++c) dot = fmaf(xv[c], gv[c], dot);
+                for (int u = 0; u < U; ++u) {
+                    if constexpr (EVEC) {
+                        if (ok && group_q0 + t0 + u < E) {
+#pragma unroll
+                            for (int c = 0; c < VEC; ++c) grad_e[(int64_t)kk[u] * F + col + c] = xv[u][c] * gv[u][c];
+                        }
+                    } else {
+                        float acc = 0.0f;
+#pragma unroll
+                        for (int c = 0; c < VEC; ++c) acc = fmaf(xv[u][c], gv[u][c], acc);
+                        d[u] = ok ? acc : 0.0f;
+                    }
+                }
+                if constexpr (!EVEC) {
+#pragma unroll
+                    for (int off = U / 2; off > 0; off >>= 1) {
+                        const bool upper = (sl & off) != 0;
+#pragma unroll
+                        for (int t = 0; t < off; ++t) {
+                            const float give = upper ? d[t] : d[t + off];
+                            const float keep = upper ? d[t + off] : d[t];
+                            d[t] = keep + __shfl_xor(give, off, LPR);
+                        }
+                    }
+                    float r = d[0];   // position t0 + sl % U, summed over this lane's aligned group of U lanes
+#pragma unroll
+                    for (int off = U; off < LPR; off <<= 1) r += __shfl_xor(r, off, LPR);
+                    if (sl / U == t0 / U) mine += r;
+                }
             }
         }
-    }
-    if constexpr (!EVEC) {
-#pragma unroll
-        for (int off = LPR / 2; off > 0; off >>= 1) dot += __shfl_xor(dot, off, LPR);
-        if (have && sl == 0) grad_e[k] = dot;
+        if constexpr (!EVEC) {
+            if (have) grad_e[k_own] = mine;
+        }
     }
 }
 
@@ -98,13 +139,18 @@ template <int LPR, int VEC>
 gnn_status launch_edge_gradient(const gnn_graph *g, int F, bool evec, const float *x, const float *gp,
                                 const int32_t *winners, float *grad_e, hipStream_t s)
 {
-    const int64_t blocks = gnn_div_up(g->num_edges * LPR, kThreads);
-    if (evec)
-        hipLaunchKernelGGL((edge_gradient_kernel<LPR, VEC, true>), dim3((unsigned)blocks), dim3(kThreads), 0, s,
-                           g->rowidx, g->colidx, g->perm, g->num_edges, F, x, gp, winners, grad_e);
-    else
-        hipLaunchKernelGGL((edge_gradient_kernel<LPR, VEC, false>), dim3((unsigned)blocks), dim3(kThreads), 0, s,
-                           g->rowidx, g->colidx, g->perm, g->num_edges, F, x, gp, winners, grad_e);
+    const int64_t blocks = std::min<int64_t>(gnn_div_up(g->num_edges, kThreads), 256 * 16);
+#define GNN_EDGE_GRADIENT(EV, WN)                                                                                   \
+    hipLaunchKernelGGL((edge_gradient_kernel<LPR, VEC, EV, WN>), dim3((unsigned)blocks), dim3(kThreads), 0, s, g->rowidx, \
+                       g->colidx, g->perm, g->num_edges, F, x, gp, winners, grad_e)
+    if (evec) {
+        if (winners) GNN_EDGE_GRADIENT(true, true);
+        else GNN_EDGE_GRADIENT(true, false);
+    } else {
+        if (winners) GNN_EDGE_GRADIENT(false, true);
+        else GNN_EDGE_GRADIENT(false, false);
+    }
+#undef GNN_EDGE_GRADIENT
     GNN_LAUNCH_CHECK();
     return GNN_OK;
 }
