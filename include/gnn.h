@@ -76,7 +76,8 @@ gnn_status gnn_build_csr(const int32_t *d_src, const int32_t *d_dst, int64_t num
                          int32_t num_nodes, void *stream, gnn_graph **out_graph);
 
 /*
- * Same, with the two scheduling thresholds exposed (0 = library default):
+ * Same, with the two scheduling thresholds exposed (0 = library default: 16, and
+ * 256 / 512 / 1024 edges per piece growing with the number of edges):
  * rows with in-degree <= small_max_degree are reduced by a sub-group of a
  * wavefront; longer rows are cut into pieces of at most chunk_edges edges, one
  * wavefront each (pieces of one row are combined in a fixed order afterwards).
