@@ -224,6 +224,45 @@ def gatconv(src, dst, num_nodes: int, x, w, a_src, a_dst, negative_slope: float 
     return (out, sabs) if with_sabs else out
 
 
+def segment_softmax_backward(dst, num_nodes: int, alpha, grad_alpha, with_sabs: bool = False):
+    """d scores from d alpha for the per-destination softmax (alpha = the forward result)."""
+    dst, a, ga = _i32(dst, "dst"), _f32(alpha, "alpha"), _f32(grad_alpha, "grad_alpha")
+    ne = dst.shape[0]
+    if a.shape != ga.shape:
+        raise ValueError("shape mismatch")
+    a2, ga2 = a.reshape(ne, -1), ga.reshape(ne, -1)
+    h = a2.shape[1] if ne else (a.shape[1] if a.ndim == 2 else 1)
+    gs = np.empty_like(a2)
+    sabs = np.empty(a2.shape, np.float64) if with_sabs else None
+    rc = _load().oracle_segment_softmax_backward(_p(dst), ctypes.c_int64(ne), ctypes.c_int32(num_nodes), _p(a2),
+                                                 _p(ga2), ctypes.c_int32(h), _p(gs), _p(sabs))
+    _check(rc, "segment_softmax_backward")
+    return (gs.reshape(a.shape), sabs.reshape(a.shape)) if with_sabs else gs.reshape(a.shape)
+
+
+def gatconv_backward(src, dst, num_nodes: int, x, w, a_src, a_dst, grad_out, negative_slope: float = 0.2):
+    """Gradients of the attention layer; returns a dict with grad_x, grad_w, grad_a_src, grad_a_dst and
+    the matching sabs_* magnitudes."""
+    src, dst, x, w = _i32(src, "src"), _i32(dst, "dst"), _f32(x, "x"), _f32(w, "w")
+    a_src, a_dst, gout = _f32(a_src, "a_src"), _f32(a_dst, "a_dst"), _f32(grad_out, "grad_out")
+    heads, ch = a_src.shape
+    ne, f_in = src.shape[0], x.shape[1]
+    if w.shape != (f_in, heads * ch) or a_dst.shape != (heads, ch) or gout.shape != (num_nodes, heads * ch):
+        raise ValueError("shape mismatch")
+    res = {"grad_x": np.empty((num_nodes, f_in), np.float32), "grad_w": np.empty((f_in, heads * ch), np.float32),
+           "grad_a_src": np.empty((heads, ch), np.float32), "grad_a_dst": np.empty((heads, ch), np.float32),
+           "sabs_x": np.empty((num_nodes, f_in), np.float64), "sabs_w": np.empty((f_in, heads * ch), np.float64),
+           "sabs_a_src": np.empty((heads, ch), np.float64), "sabs_a_dst": np.empty((heads, ch), np.float64)}
+    rc = _load().oracle_gatconv_backward(_p(src), _p(dst), ctypes.c_int64(ne), ctypes.c_int32(num_nodes),
+                                         _p(x), ctypes.c_int32(f_in), _p(w), _p(a_src), _p(a_dst),
+                                         ctypes.c_int32(heads), ctypes.c_int32(ch), ctypes.c_float(negative_slope),
+                                         _p(gout), _p(res["grad_x"]), _p(res["grad_w"]), _p(res["grad_a_src"]),
+                                         _p(res["grad_a_dst"]), _p(res["sabs_x"]), _p(res["sabs_w"]),
+                                         _p(res["sabs_a_src"]), _p(res["sabs_a_dst"]))
+    _check(rc, "gatconv_backward")
+    return res
+
+
 def gin_update(src, dst, num_nodes: int, x, eps: float = 0.0, with_sabs: bool = False):
     src, dst, x = _i32(src, "src"), _i32(dst, "dst"), _f32(x, "x")
     ne, f = src.shape[0], x.shape[1]

@@ -541,6 +541,183 @@ done:
 }
 
 /*
+ * Backward of the segment softmax (the Jacobian of a softmax, per destination segment):
+ *   gs[k,h] = alpha[k,h] * (galpha[k,h] - sum_{k': dst[k']=dst[k]} alpha[k',h] galpha[k',h]).
+ * alpha is the forward result, galpha = dL/d alpha.  sabs = alpha (|galpha| + sum alpha |galpha|).
+ */
+int oracle_segment_softmax_backward(const int32_t *dst, int64_t E, int32_t N, const float *alpha,
+                                    const float *galpha, int32_t H, float *gs, double *sabs)
+{
+    if (N <= 0 || E < 0 || H <= 0) return 2;
+    for (int64_t k = 0; k < E; ++k)
+        if (dst[k] < 0 || dst[k] >= N) return 1;
+    size_t nh = (size_t)N * H;
+    double *t = (double *)calloc(nh, sizeof(double));
+    double *ta = (double *)calloc(nh, sizeof(double));
+    if (!t || !ta) { free(t); free(ta); return 3; }
+    for (int64_t k = 0; k < E; ++k)
+        for (int32_t h = 0; h < H; ++h) {
+            double p = (double)alpha[k * H + h] * (double)galpha[k * H + h];
+            t[(int64_t)dst[k] * H + h] += p;
+            ta[(int64_t)dst[k] * H + h] += fabs(p);
+        }
+    for (int64_t k = 0; k < E; ++k)
+        for (int32_t h = 0; h < H; ++h) {
+            int64_t q = (int64_t)dst[k] * H + h;
+            double a = (double)alpha[k * H + h], g = (double)galpha[k * H + h];
+            gs[k * H + h] = (float)(a * (g - t[q]));
+            if (sabs) sabs[k * H + h] = fabs(a) * (fabs(g) + ta[q]);
+        }
+    free(t); free(ta);
+    return 0;
+}
+
+/*
+ * Backward of the attention layer above, by the chain rule through its steps in reverse
+ * (G = dL/d out; the rounding of h to float is treated as the identity):
+ *   dalpha[k,hd] = sum_c G[dst[k],hd,c] h[src[k],hd,c]
+ *   ds[k,hd]     = alpha (dalpha - sum_{k' into dst[k]} alpha' dalpha')          (softmax Jacobian)
+ *   dv[k,hd]     = ds * (v > 0 ? 1 : slope),  v = sl[src[k],hd] + sr[dst[k],hd]  (lrelu', slope at v = 0
+ *                                                                                  as in the forward's branch)
+ *   dsl[j,hd] = sum_{k: src[k]=j} dv,   dsr[i,hd] = sum_{k: dst[k]=i} dv
+ *   dh[j,hd,c] = sum_{k: src[k]=j} alpha[k,hd] G[dst[k],hd,c] + dsl[j,hd] a_src[hd,c] + dsr[j,hd] a_dst[hd,c]
+ *   d a_src[hd,c] = sum_j dsl[j,hd] h[j,hd,c],   d a_dst[hd,c] = sum_i dsr[i,hd] h[i,hd,c]
+ *   dW = X^T dh,   dX = dh W^T.
+ * The sabs outputs carry the same recurrences on absolute values (|h| replaced by |X||W|).
+ */
+int oracle_gatconv_backward(const int32_t *src, const int32_t *dst, int64_t E, int32_t N,
+                            const float *x, int32_t f_in, const float *w,
+                            const float *a_src, const float *a_dst, int32_t heads, int32_t ch,
+                            float negative_slope, const float *gout,
+                            float *gx, float *gw, float *ga_src, float *ga_dst,
+                            double *sabs_x, double *sabs_w, double *sabs_as, double *sabs_ad)
+{
+    if (N <= 0 || E < 0 || f_in <= 0 || heads <= 0 || ch <= 0) return 2;
+    if (check_edges(src, dst, E, N)) return 1;
+    int32_t fo = heads * ch;
+    size_t nh = (size_t)N * heads, nfo = (size_t)N * fo, eh = (size_t)(E > 0 ? E : 1) * heads;
+    double *z = NULL, *za = NULL;
+    double *sl = (double *)calloc(nh, sizeof(double)), *sr = (double *)calloc(nh, sizeof(double));
+    double *mx = (double *)malloc(nh * sizeof(double)), *den = (double *)calloc(nh, sizeof(double));
+    double *t = (double *)calloc(nh, sizeof(double)), *tb = (double *)calloc(nh, sizeof(double));
+    double *dsl = (double *)calloc(nh, sizeof(double)), *dslb = (double *)calloc(nh, sizeof(double));
+    double *dsr = (double *)calloc(nh, sizeof(double)), *dsrb = (double *)calloc(nh, sizeof(double));
+    double *al = (double *)calloc(eh, sizeof(double)), *pre = (double *)calloc(eh, sizeof(double));
+    double *da = (double *)calloc(eh, sizeof(double)), *dab = (double *)calloc(eh, sizeof(double));
+    double *dh = (double *)calloc(nfo, sizeof(double)), *dhb = (double *)calloc(nfo, sizeof(double));
+    int rc = 3;
+    if (!sl || !sr || !mx || !den || !t || !tb || !dsl || !dslb || !dsr || !dsrb || !al || !pre || !da || !dab ||
+        !dh || !dhb)
+        goto done;
+    if (dense_xw(x, N, f_in, w, fo, &z, &za)) goto done;
+    for (size_t q = 0; q < nfo; ++q) z[q] = (double)(float)z[q];
+    for (int32_t i = 0; i < N; ++i)
+        for (int32_t hd = 0; hd < heads; ++hd)
+            for (int32_t c = 0; c < ch; ++c) {
+                double hv = z[(int64_t)i * fo + hd * ch + c];
+                sl[(int64_t)i * heads + hd] += (double)a_src[hd * ch + c] * hv;
+                sr[(int64_t)i * heads + hd] += (double)a_dst[hd * ch + c] * hv;
+            }
+    double slope = (double)negative_slope;
+    /* forward: pre-activations, scores, attention weights */
+    for (size_t q = 0; q < nh; ++q) mx[q] = -INFINITY;
+    for (int64_t k = 0; k < E; ++k)
+        for (int32_t hd = 0; hd < heads; ++hd) {
+            double v = sl[(int64_t)src[k] * heads + hd] + sr[(int64_t)dst[k] * heads + hd];
+            pre[k * heads + hd] = v;
+            double sc = v > 0.0 ? v : v * slope;
+            if (sc > mx[(int64_t)dst[k] * heads + hd]) mx[(int64_t)dst[k] * heads + hd] = sc;
+        }
+    for (int64_t k = 0; k < E; ++k)
+        for (int32_t hd = 0; hd < heads; ++hd) {
+            double v = pre[k * heads + hd], sc = v > 0.0 ? v : v * slope;
+            al[k * heads + hd] = exp(sc - mx[(int64_t)dst[k] * heads + hd]);
+            den[(int64_t)dst[k] * heads + hd] += al[k * heads + hd];
+        }
+    for (int64_t k = 0; k < E; ++k)
+        for (int32_t hd = 0; hd < heads; ++hd) al[k * heads + hd] /= den[(int64_t)dst[k] * heads + hd];
+    /* d alpha and the per-destination sums of alpha * d alpha */
+    for (int64_t k = 0; k < E; ++k)
+        for (int32_t hd = 0; hd < heads; ++hd) {
+            double d = 0.0, db = 0.0;
+            for (int32_t c = 0; c < ch; ++c) {
+                double g = (double)gout[(int64_t)dst[k] * fo + hd * ch + c];
+                d += g * z[(int64_t)src[k] * fo + hd * ch + c];
+                db += fabs(g) * za[(int64_t)src[k] * fo + hd * ch + c];
+            }
+            da[k * heads + hd] = d;
+            dab[k * heads + hd] = db;
+            t[(int64_t)dst[k] * heads + hd] += al[k * heads + hd] * d;
+            tb[(int64_t)dst[k] * heads + hd] += al[k * heads + hd] * db;
+        }
+    /* through the softmax and the leaky ReLU; reductions onto both endpoints; the alpha * G part of dh */
+    for (int64_t k = 0; k < E; ++k)
+        for (int32_t hd = 0; hd < heads; ++hd) {
+            int64_t qi = (int64_t)dst[k] * heads + hd, qj = (int64_t)src[k] * heads + hd;
+            double a = al[k * heads + hd];
+            double slopek = pre[k * heads + hd] > 0.0 ? 1.0 : slope;
+            double dv = a * (da[k * heads + hd] - t[qi]) * slopek;
+            double dvb = a * (dab[k * heads + hd] + tb[qi]) * fabs(slopek);
+            dsl[qj] += dv; dslb[qj] += dvb;
+            dsr[qi] += dv; dsrb[qi] += dvb;
+            for (int32_t c = 0; c < ch; ++c) {
+                double g = (double)gout[(int64_t)dst[k] * fo + hd * ch + c];
+                dh[(int64_t)src[k] * fo + hd * ch + c] += a * g;
+                dhb[(int64_t)src[k] * fo + hd * ch + c] += a * fabs(g);
+            }
+        }
+    for (int32_t hd = 0; hd < heads; ++hd)
+        for (int32_t c = 0; c < ch; ++c) {
+            double s1 = 0.0, s2 = 0.0, b1 = 0.0, b2 = 0.0;
+            for (int32_t i = 0; i < N; ++i) {
+                s1 += dsl[(int64_t)i * heads + hd] * z[(int64_t)i * fo + hd * ch + c];
+                s2 += dsr[(int64_t)i * heads + hd] * z[(int64_t)i * fo + hd * ch + c];
+                b1 += dslb[(int64_t)i * heads + hd] * za[(int64_t)i * fo + hd * ch + c];
+                b2 += dsrb[(int64_t)i * heads + hd] * za[(int64_t)i * fo + hd * ch + c];
+            }
+            ga_src[hd * ch + c] = (float)s1;
+            ga_dst[hd * ch + c] = (float)s2;
+            if (sabs_as) sabs_as[hd * ch + c] = b1;
+            if (sabs_ad) sabs_ad[hd * ch + c] = b2;
+        }
+    for (int32_t i = 0; i < N; ++i)
+        for (int32_t hd = 0; hd < heads; ++hd)
+            for (int32_t c = 0; c < ch; ++c) {
+                int64_t q = (int64_t)i * fo + hd * ch + c;
+                dh[q] += dsl[(int64_t)i * heads + hd] * (double)a_src[hd * ch + c] +
+                         dsr[(int64_t)i * heads + hd] * (double)a_dst[hd * ch + c];
+                dhb[q] += dslb[(int64_t)i * heads + hd] * fabs((double)a_src[hd * ch + c]) +
+                          dsrb[(int64_t)i * heads + hd] * fabs((double)a_dst[hd * ch + c]);
+            }
+    /* dW = X^T dh, dX = dh W^T */
+    for (int32_t k = 0; k < f_in; ++k)
+        for (int32_t o = 0; o < fo; ++o) {
+            double s1 = 0.0, b1 = 0.0;
+            for (int32_t i = 0; i < N; ++i) {
+                s1 += (double)x[(int64_t)i * f_in + k] * dh[(int64_t)i * fo + o];
+                b1 += fabs((double)x[(int64_t)i * f_in + k]) * dhb[(int64_t)i * fo + o];
+            }
+            gw[(int64_t)k * fo + o] = (float)s1;
+            if (sabs_w) sabs_w[(int64_t)k * fo + o] = b1;
+        }
+    for (int32_t i = 0; i < N; ++i)
+        for (int32_t k = 0; k < f_in; ++k) {
+            double s1 = 0.0, b1 = 0.0;
+            for (int32_t o = 0; o < fo; ++o) {
+                s1 += dh[(int64_t)i * fo + o] * (double)w[(int64_t)k * fo + o];
+                b1 += dhb[(int64_t)i * fo + o] * fabs((double)w[(int64_t)k * fo + o]);
+            }
+            gx[(int64_t)i * f_in + k] = (float)s1;
+            if (sabs_x) sabs_x[(int64_t)i * f_in + k] = b1;
+        }
+    rc = 0;
+done:
+    free(z); free(za); free(sl); free(sr); free(mx); free(den); free(t); free(tb); free(dsl); free(dslb);
+    free(dsr); free(dsrb); free(al); free(pre); free(da); free(dab); free(dh); free(dhb);
+    return rc;
+}
+
+/*
  * GIN-style node update without the MLP:  out[i,:] = (1 + eps) x[i,:] + sum_{j->i} x[j,:].
  */
 int oracle_gin_update(const int32_t *src, const int32_t *dst, int64_t E, int32_t N,

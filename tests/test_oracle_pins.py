@@ -461,6 +461,118 @@ def test_gcn_backward_dense_and_adjoint(loops):
     np.testing.assert_allclose((bw["grad_b"].astype(np.float64) * b).sum(), bias_part, rtol=1e-5, atol=1e-5)
 
 
+def _gat_inputs(seed, n, e, f_in, heads, ch):
+    src, dst = rng_graph(seed, n, e, star=True)
+    loops = np.arange(n, dtype=np.int32)[::3]
+    src, dst = np.concatenate([src, loops]), np.concatenate([dst, loops])
+    x = synth.normal_f32(seed, 2, n * f_in).reshape(n, f_in)
+    w = synth.glorot_uniform(seed, 4, f_in, heads * ch, (f_in, heads * ch))
+    a_s = synth.uniform_f32(seed, 5, heads * ch, -1, 1).reshape(heads, ch)
+    a_d = synth.uniform_f32(seed, 6, heads * ch, -1, 1).reshape(heads, ch)
+    gout = synth.normal_f32(seed, 7, n * heads * ch).reshape(n, heads * ch)
+    return src, dst, x, w, a_s, a_d, gout
+
+
+def test_softmax_backward_is_the_autograd_gradient():
+    """The segment-softmax Jacobian against reverse-mode differentiation of a float64 forward built from
+    library scatter operations, plus what the Jacobian fixes: gradients of a segment sum to zero, a
+    gradient that is constant over a segment gives zero, a one-edge segment gives zero."""
+    import torch
+    n, heads = 40, 3
+    src, dst = rng_graph(95, n, 400, star=True)
+    dst = np.concatenate([dst, np.array([n - 1], np.int32)])      # node n-1: make sure of a one-edge segment
+    dst[:-1][dst[:-1] == n - 1] = 0
+    e = dst.shape[0]
+    s = (2.0 * synth.normal_f32(95, 2, e * heads)).reshape(e, heads)
+    galpha = synth.normal_f32(95, 3, e * heads).reshape(e, heads)
+    alpha = oracle.segment_softmax(dst, n, s)
+    got = oracle.segment_softmax_backward(dst, n, alpha, galpha)
+    st = torch.tensor(s, dtype=torch.float64, requires_grad=True)
+    dt = torch.tensor(dst, dtype=torch.int64)
+    ex = torch.exp(st - st.max())
+    den = torch.zeros(n, heads, dtype=torch.float64).index_add_(0, dt, ex)
+    (ex / den[dt] * torch.tensor(galpha, dtype=torch.float64)).sum().backward()
+    ref = st.grad.numpy()
+    np.testing.assert_allclose(got, ref, rtol=0, atol=2e-6 * np.abs(ref).max())
+    sums = np.zeros((n, heads))
+    np.add.at(sums, dst, got.astype(np.float64))
+    assert np.abs(sums).max() <= 1e-6
+    assert np.abs(got[-1]).max() <= 1e-7                            # the one-edge segment
+    per_seg = synth.normal_f32(95, 4, n * heads).reshape(n, heads)[dst]
+    const = oracle.segment_softmax_backward(dst, n, alpha, per_seg)
+    assert np.abs(const).max() <= 1e-6
+
+
+def test_gat_backward_is_the_autograd_gradient():
+    """All four gradients of the attention layer against reverse-mode differentiation (float64, library
+    gather / scatter-add operations) of an independent forward on a multigraph with a hub, duplicate
+    edges, self-loops and nodes without incoming edges."""
+    import torch
+    n, f_in, heads, ch = 36, 6, 3, 4
+    src, dst, x, w, a_s, a_d, gout = _gat_inputs(91, n, 350, f_in, heads, ch)
+    res = oracle.gatconv_backward(src, dst, n, x, w, a_s, a_d, gout, 0.2)
+    t = lambda a: torch.tensor(a, dtype=torch.float64, requires_grad=True)
+    xt, wt, ast, adt = t(x), t(w), t(a_s), t(a_d)
+    st, dt = torch.tensor(src, dtype=torch.int64), torch.tensor(dst, dtype=torch.int64)
+    xw = xt @ wt
+    h = (xw + (xw.detach().float().double() - xw.detach())).reshape(n, heads, ch)   # stored in float: value only
+    sl, sr = (h * ast[None]).sum(-1), (h * adt[None]).sum(-1)
+    v = sl[st] + sr[dt]
+    sc = torch.where(v > 0, v, 0.2 * v)
+    ex = torch.exp(sc - sc.max())
+    den = torch.zeros(n, heads, dtype=torch.float64).index_add_(0, dt, ex)
+    alpha = ex / den[dt]
+    out = torch.zeros(n, heads, ch, dtype=torch.float64).index_add_(0, dt, alpha[:, :, None] * h[st])
+    (out.reshape(n, heads * ch) * torch.tensor(gout, dtype=torch.float64)).sum().backward()
+    for name, ref in (("grad_x", xt.grad), ("grad_w", wt.grad), ("grad_a_src", ast.grad), ("grad_a_dst", adt.grad)):
+        ref = ref.numpy()
+        np.testing.assert_allclose(res[name], ref, rtol=0, atol=2e-6 * np.abs(ref).max(), err_msg=name)
+        # the magnitude outputs bound the values they belong to
+        assert (np.abs(ref) <= res["sabs" + name[4:]] * (1 + 1e-6) + 1e-30).all(), name
+
+
+def test_gat_backward_finite_differences():
+    """Central differences of L = <G, out> through the oracle's own forward, in a few coordinates of
+    every input (step 2e-3 on float inputs and a float result: agreement to ~1e-2 of the largest entry)."""
+    n, f_in, heads, ch = 20, 5, 2, 3
+    src, dst, x, w, a_s, a_d, gout = _gat_inputs(92, n, 120, f_in, heads, ch)
+    res = oracle.gatconv_backward(src, dst, n, x, w, a_s, a_d, gout, 0.2)
+
+    def loss(x_, w_, as_, ad_):
+        return float((oracle.gatconv(src, dst, n, x_, w_, as_, ad_, 0.2).astype(np.float64) * gout).sum())
+
+    args = [x, w, a_s, a_d]
+    names = ["grad_x", "grad_w", "grad_a_src", "grad_a_dst"]
+    step = 1.0 / 512
+    for which in range(4):
+        flat_n = args[which].size
+        for q in range(0, flat_n, max(1, flat_n // 5)):
+            hi = [a.copy() for a in args]
+            lo = [a.copy() for a in args]
+            hi[which].reshape(-1)[q] += step
+            lo[which].reshape(-1)[q] -= step
+            fd = (loss(*hi) - loss(*lo)) / (2 * step)
+            an = float(res[names[which]].reshape(-1)[q])
+            scale = max(1.0, float(np.abs(res[names[which]]).max()))
+            assert abs(fd - an) <= 1e-2 * scale, (names[which], q, fd, an)
+
+
+def test_gat_backward_zero_attention_is_mean_backward():
+    """With zero attention vectors every weight is 1/in-degree, so grad_x reduces to the (already pinned)
+    backward of mean aggregation followed by W^T."""
+    wl = synth.config4_gat(num_nodes=300, num_edges=2500, f_in=9, heads=2, ch=4, cap=80.0)
+    n = wl.num_nodes
+    zero = np.zeros((2, 4), np.float32)
+    gout = synth.normal_f32(93, 7, n * 8).reshape(n, 8)
+    res = oracle.gatconv_backward(wl.src, wl.dst, n, wl.x, wl.params["w"], zero, zero, gout, 0.2)
+    hfeat = (wl.x.astype(np.float64) @ wl.params["w"].astype(np.float64)).astype(np.float32)
+    dh = oracle.propagate_backward(wl.src, wl.dst, n, hfeat, gout, None, MSG_COPY_XJ, AGGR_MEAN)["grad_x"]
+    ref = dh.astype(np.float64) @ wl.params["w"].astype(np.float64).T
+    np.testing.assert_allclose(res["grad_x"], ref, rtol=0, atol=3e-6 * np.abs(ref).max())
+    ref_w = wl.x.astype(np.float64).T @ dh.astype(np.float64)
+    np.testing.assert_allclose(res["grad_w"], ref_w, rtol=0, atol=3e-6 * np.abs(ref_w).max())
+
+
 def test_error_codes():
     src = np.array([0, 5], np.int32)
     dst = np.array([1, 0], np.int32)
