@@ -218,13 +218,38 @@ gnn_status gnn_segment_softmax(const gnn_graph *g, const float *d_scores, int32_
  *   out[i,hd,:] = sum_k softmax_i(s)[k,hd] * h[src[k],hd,:]      (heads concatenated)
  * No bias, no activation; self-loops only if the edge list holds them.
  * d_w [f_in x heads*ch] row-major, d_a_src / d_a_dst [heads x ch], d_out [N x heads*ch].
+ * d_softmax_stats (optional, may be NULL): [N x heads x 2] floats that receive, per destination and
+ * head, the segment maximum of the scores and the softmax denominator relative to it (-inf and 0
+ * for a node without incoming edges) -- what gnn_gatconv_backward needs from the forward pass.
  * d_workspace: at least gnn_gatconv_workspace_bytes(N, heads, ch) bytes of device scratch.
  */
 size_t gnn_gatconv_workspace_bytes(int32_t num_nodes, int32_t heads, int32_t ch);
 gnn_status gnn_gatconv(const gnn_graph *g, const float *d_x, int32_t f_in, const float *d_w,
                        const float *d_a_src, const float *d_a_dst, int32_t heads, int32_t ch,
-                       float negative_slope, float *d_out, void *d_workspace,
+                       float negative_slope, float *d_out, float *d_softmax_stats, void *d_workspace,
                        size_t workspace_bytes, void *stream);
+
+/*
+ * Backward of gnn_gatconv (training is the paper's purpose, section 3 "Training Example"): given
+ * d_grad_out = dL/d out [N x heads*ch], the forward result d_out and the statistics the forward call
+ * wrote to d_softmax_stats, computes
+ *   d_grad_x [N x f_in], d_grad_w [f_in x heads*ch], d_grad_a_src, d_grad_a_dst [heads x ch]
+ * (each may be NULL to skip it).  The attention weights are recomputed from per-node records, so no
+ * [E x heads] tensor is stored.  g_by_source is a second handle built from the same edge list with
+ * the roles of src and dst exchanged: gnn_build_csr(dst, src, ...).  The derivative of the leaky
+ * ReLU at exactly 0 is negative_slope (the branch the forward takes).  No atomics: results are
+ * bitwise reproducible.
+ * Restriction: ch (or ch / 4 when ch is a multiple of 4) must be a power of two, at most 64 lanes per
+ * head; otherwise GNN_ERR_BAD_SIZE.
+ * d_workspace: at least gnn_gatconv_backward_workspace_bytes(N, f_in, heads, ch) bytes, 256-byte aligned.
+ */
+size_t gnn_gatconv_backward_workspace_bytes(int32_t num_nodes, int32_t f_in, int32_t heads, int32_t ch);
+gnn_status gnn_gatconv_backward(const gnn_graph *g, const gnn_graph *g_by_source, const float *d_x, int32_t f_in,
+                                const float *d_w, const float *d_a_src, const float *d_a_dst, int32_t heads,
+                                int32_t ch, float negative_slope, const float *d_out,
+                                const float *d_softmax_stats, const float *d_grad_out, float *d_grad_x,
+                                float *d_grad_w, float *d_grad_a_src, float *d_grad_a_dst, void *d_workspace,
+                                size_t workspace_bytes, void *stream);
 
 /*
  * Graph-level readout of a batch of graphs (GlobalPool in the paper's example):

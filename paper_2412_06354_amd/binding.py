@@ -50,7 +50,10 @@ SIGNATURES = {
     "gnn_gcnconv_backward": (_c.c_int, [_vp, _vp, _vp, _i32, _vp, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "gnn_segment_softmax": (_c.c_int, [_vp, _vp, _i32, _c.c_int, _vp, _vp]),
     "gnn_gatconv_workspace_bytes": (_sz, [_i32, _i32, _i32]),
-    "gnn_gatconv": (_c.c_int, [_vp, _vp, _i32, _vp, _vp, _vp, _i32, _i32, _f32, _vp, _vp, _sz, _vp]),
+    "gnn_gatconv": (_c.c_int, [_vp, _vp, _i32, _vp, _vp, _vp, _i32, _i32, _f32, _vp, _vp, _vp, _sz, _vp]),
+    "gnn_gatconv_backward_workspace_bytes": (_sz, [_i32, _i32, _i32, _i32]),
+    "gnn_gatconv_backward": (_c.c_int, [_vp, _vp, _vp, _i32, _vp, _vp, _vp, _i32, _i32, _f32, _vp, _vp, _vp, _vp, _vp,
+                                        _vp, _vp, _vp, _sz, _vp]),
     "gnn_graph_pool": (_c.c_int, [_vp, _i32, _i32, _vp, _i32, _c.c_int, _vp, _vp]),
     "gnn_gin_update": (_c.c_int, [_vp, _vp, _i32, _f32, _vp, _vp]),
     "gnn_dense_xw": (_c.c_int, [_vp, _i64, _i32, _vp, _i32, _vp, _vp, _vp]),
@@ -328,11 +331,14 @@ def segment_softmax(g: Graph, scores: torch.Tensor, order: int = EDGE_ORDER_COO,
 
 def gatconv(g: Graph, x: torch.Tensor, w: torch.Tensor, a_src: torch.Tensor, a_dst: torch.Tensor,
             negative_slope: float = 0.2, out: Optional[torch.Tensor] = None,
-            workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+            workspace: Optional[torch.Tensor] = None, softmax_stats: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """softmax_stats: optional [N, heads, 2] float32 tensor that receives what gatconv_backward needs."""
     n, f_in = x.shape
     heads, ch = a_src.shape
     if n != g.num_nodes or tuple(w.shape) != (f_in, heads * ch) or tuple(a_dst.shape) != (heads, ch):
         raise ValueError("shape mismatch")
+    if softmax_stats is not None and tuple(softmax_stats.shape) != (n, heads, 2):
+        raise ValueError("softmax_stats must be [N, heads, 2]")
     need = int(lib().gnn_gatconv_workspace_bytes(n, heads, ch))
     if workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
@@ -340,10 +346,39 @@ def gatconv(g: Graph, x: torch.Tensor, w: torch.Tensor, a_src: torch.Tensor, a_d
         out = torch.empty((n, heads * ch), dtype=torch.float32, device=x.device)
     rc = lib().gnn_gatconv(g._h, _dev(x, torch.float32, "x"), f_in, _dev(w, torch.float32, "w"),
                            _dev(a_src, torch.float32, "a_src"), _dev(a_dst, torch.float32, "a_dst"), heads, ch,
-                           float(negative_slope), _dev(out, torch.float32, "out"), workspace.data_ptr(),
+                           float(negative_slope), _dev(out, torch.float32, "out"),
+                           _dev(softmax_stats, torch.float32, "softmax_stats"), workspace.data_ptr(),
                            workspace.numel(), _stream())
     _check(rc, "gnn_gatconv")
     return out
+
+
+def gatconv_backward(g: Graph, g_by_source: Graph, x: torch.Tensor, w: torch.Tensor, a_src: torch.Tensor,
+                     a_dst: torch.Tensor, out: torch.Tensor, softmax_stats: torch.Tensor, grad_out: torch.Tensor,
+                     negative_slope: float = 0.2, workspace: Optional[torch.Tensor] = None):
+    """-> (grad_x, grad_w, grad_a_src, grad_a_dst); `out` and `softmax_stats` come from gatconv."""
+    n, f_in = x.shape
+    heads, ch = a_src.shape
+    hc = heads * ch
+    if (n != g.num_nodes or tuple(w.shape) != (f_in, hc) or tuple(a_dst.shape) != (heads, ch) or
+            tuple(out.shape) != (n, hc) or tuple(grad_out.shape) != (n, hc) or
+            tuple(softmax_stats.shape) != (n, heads, 2)):
+        raise ValueError("shape mismatch")
+    need = int(lib().gnn_gatconv_backward_workspace_bytes(n, f_in, heads, ch))
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+    gx = torch.empty((n, f_in), dtype=torch.float32, device=x.device)
+    gw = torch.empty((f_in, hc), dtype=torch.float32, device=x.device)
+    gas = torch.empty((heads, ch), dtype=torch.float32, device=x.device)
+    gad = torch.empty((heads, ch), dtype=torch.float32, device=x.device)
+    rc = lib().gnn_gatconv_backward(g._h, g_by_source._h, _dev(x, torch.float32, "x"), f_in,
+                                    _dev(w, torch.float32, "w"), _dev(a_src, torch.float32, "a_src"),
+                                    _dev(a_dst, torch.float32, "a_dst"), heads, ch, float(negative_slope),
+                                    _dev(out, torch.float32, "out"), _dev(softmax_stats, torch.float32, "softmax_stats"),
+                                    _dev(grad_out, torch.float32, "grad_out"), gx.data_ptr(), gw.data_ptr(),
+                                    gas.data_ptr(), gad.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream())
+    _check(rc, "gnn_gatconv_backward")
+    return gx, gw, gas, gad
 
 
 def graph_pool(graph_indicator: torch.Tensor, num_graphs: int, x: torch.Tensor, aggr: int = AGGR_SUM,

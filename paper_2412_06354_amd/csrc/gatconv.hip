@@ -20,6 +20,7 @@ struct GatParams {
     const int32_t *rowptr, *colidx;
     const float *h, *sl, *sr;
     float *out;
+    float *stats;                        // optional [N x H x 2]: (segment maximum, denominator) per row and head
     float *slot_acc, *slot_m, *slot_d;   // [slots x HC] each
     const int32_t *small_rows, *item_row, *item_start, *item_slot, *split_rows, *split_slot0;
     int32_t n_small, n_items, n_split, chunk, HC, H, ch, item_blocks;
@@ -96,6 +97,11 @@ __device__ __forceinline__ void write_out(const GatParams &p, int row, int col, 
 #pragma unroll
     for (int c = 0; c < VEC; ++c) v[c] = s.d > 0.0f ? s.acc[c] / s.d : 0.0f;
     store_vec<VEC>(p.out + (int64_t)row * p.HC + col, v);
+    if (p.stats && col % p.ch == 0) {
+        float *st = p.stats + ((int64_t)row * p.H + col / p.ch) * 2;
+        st[0] = s.m;
+        st[1] = s.d;
+    }
 }
 
 __device__ __forceinline__ float lrelu(float v, float slope) { return v > 0.0f ? v : slope * v; }
@@ -304,6 +310,20 @@ size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
 
 }  // namespace
 
+gnn_status gnn_launch_node_scores(const float *d_h, int64_t N, int heads, int ch, const float *d_a_src,
+                                  const float *d_a_dst, float *d_sl, float *d_sr, hipStream_t s)
+{
+    const dim3 ns_grid((unsigned)gnn_div_up(N * heads, kThreads));
+    if (ch % 4 == 0)
+        hipLaunchKernelGGL(node_scores_kernel<4>, ns_grid, dim3(kThreads), 0, s, d_h, N, heads, ch, d_a_src, d_a_dst,
+                           d_sl, d_sr);
+    else
+        hipLaunchKernelGGL(node_scores_kernel<1>, ns_grid, dim3(kThreads), 0, s, d_h, N, heads, ch, d_a_src, d_a_dst,
+                           d_sl, d_sr);
+    GNN_LAUNCH_CHECK();
+    return GNN_OK;
+}
+
 extern "C" {
 
 size_t gnn_gatconv_workspace_bytes(int32_t num_nodes, int32_t heads, int32_t ch)
@@ -315,7 +335,7 @@ size_t gnn_gatconv_workspace_bytes(int32_t num_nodes, int32_t heads, int32_t ch)
 
 gnn_status gnn_gatconv(const gnn_graph *g, const float *d_x, int32_t f_in, const float *d_w, const float *d_a_src,
                        const float *d_a_dst, int32_t heads, int32_t ch, float negative_slope, float *d_out,
-                       void *d_workspace, size_t workspace_bytes, void *stream)
+                       float *d_softmax_stats, void *d_workspace, size_t workspace_bytes, void *stream)
 {
     if (!g || !d_x || !d_w || !d_a_src || !d_a_dst || !d_out || !d_workspace) return GNN_ERR_NULL;
     if (f_in <= 0 || heads <= 0 || ch <= 0) return GNN_ERR_BAD_SIZE;
@@ -331,18 +351,11 @@ gnn_status gnn_gatconv(const gnn_graph *g, const float *d_x, int32_t f_in, const
                                           align256((size_t)N * heads * sizeof(float)));
 
     GNN_TRY(gnn_dense_xw(d_x, N, f_in, d_w, HC, nullptr, h, stream));
-    const dim3 ns_grid((unsigned)gnn_div_up((int64_t)N * heads, kThreads));
-    if (ch % 4 == 0)
-        hipLaunchKernelGGL(node_scores_kernel<4>, ns_grid, dim3(kThreads), 0, s, h, (int64_t)N, heads, ch, d_a_src,
-                           d_a_dst, sl, sr);
-    else
-        hipLaunchKernelGGL(node_scores_kernel<1>, ns_grid, dim3(kThreads), 0, s, h, (int64_t)N, heads, ch, d_a_src,
-                           d_a_dst, sl, sr);
-    GNN_LAUNCH_CHECK();
+    GNN_TRY(gnn_launch_node_scores(h, N, heads, ch, d_a_src, d_a_dst, sl, sr, s));
 
     GatParams p{};
     p.rowptr = g->rowptr; p.colidx = g->colidx;
-    p.h = h; p.sl = sl; p.sr = sr; p.out = d_out;
+    p.h = h; p.sl = sl; p.sr = sr; p.out = d_out; p.stats = d_softmax_stats;
     p.small_rows = g->small_rows; p.item_row = g->item_row; p.item_start = g->item_start;
     p.item_slot = g->item_slot; p.split_rows = g->split_rows; p.split_slot0 = g->split_slot0;
     p.n_small = g->n_small; p.n_items = g->n_items; p.n_split = g->n_split; p.chunk = g->chunk;

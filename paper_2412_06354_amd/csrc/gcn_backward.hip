@@ -143,7 +143,7 @@ __global__ __launch_bounds__(kThreads) void sum_partials_kernel(const float *__r
 
 size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
 
-int chunk_count(int64_t rows) { return (int)std::max<int64_t>(1, std::min<int64_t>(512, gnn_div_up(rows, 256))); }
+int chunk_count(int64_t rows) { return gnn_row_chunk_count(rows); }
 
 struct BackwardLayout {
     size_t gs, t, dinv, wt, part, total;
@@ -164,6 +164,41 @@ BackwardLayout layout(int64_t N, int f_in, int f_out)
 }
 
 }  // namespace
+
+int gnn_row_chunk_count(int64_t rows)
+{
+    return (int)std::max<int64_t>(1, std::min<int64_t>(512, gnn_div_up(rows, 256)));
+}
+
+gnn_status gnn_launch_sum_partials(const float *d_partial, int chunks, int64_t elems, float *d_out, hipStream_t s)
+{
+    if (elems <= 0) return GNN_OK;
+    hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)gnn_div_up(elems, 64)), dim3(kThreads), 0, s, d_partial,
+                       chunks, elems, d_out);
+    GNN_LAUNCH_CHECK();
+    return GNN_OK;
+}
+
+gnn_status gnn_launch_xty(const float *d_x, const float *d_y, int64_t rows, int f_in, int f_out, float *d_partial,
+                          float *d_out, hipStream_t s)
+{
+    constexpr int NT = 4;
+    const int chunks = gnn_row_chunk_count(rows);
+    const int64_t rows_per_chunk = gnn_div_up(rows, chunks);
+    const dim3 grid((unsigned)chunks, (unsigned)gnn_div_up(f_in, 128), (unsigned)gnn_div_up(f_out, NT * 32));
+    hipLaunchKernelGGL(xty_partial_kernel<NT>, grid, dim3(kThreads), 0, s, d_x, d_y, rows, f_in, f_out, rows_per_chunk,
+                       d_partial);
+    GNN_LAUNCH_CHECK();
+    return gnn_launch_sum_partials(d_partial, chunks, (int64_t)f_in * f_out, d_out, s);
+}
+
+gnn_status gnn_launch_transpose(const float *d_w, int rows, int cols, float *d_wt, hipStream_t s)
+{
+    hipLaunchKernelGGL(transpose_kernel, dim3((unsigned)gnn_div_up((int64_t)rows * cols, kThreads)), dim3(kThreads), 0,
+                       s, d_w, rows, cols, d_wt);
+    GNN_LAUNCH_CHECK();
+    return GNN_OK;
+}
 
 extern "C" {
 
@@ -208,29 +243,15 @@ gnn_status gnn_gcnconv_backward(const gnn_graph *g, const gnn_graph *g_by_source
                                      t, s));
     }
     if (d_grad_x) {
-        hipLaunchKernelGGL(transpose_kernel, dim3((unsigned)gnn_div_up((int64_t)f_in * f_out, kThreads)),
-                           dim3(kThreads), 0, s, d_w, f_in, f_out, wt);
-        GNN_LAUNCH_CHECK();
+        GNN_TRY(gnn_launch_transpose(d_w, f_in, f_out, wt, s));
         GNN_TRY(gnn_dense_xw(t, N, f_out, wt, f_in, nullptr, d_grad_x, stream));
     }
-    if (d_grad_w) {
-        constexpr int NT = 4;
-        const dim3 grid((unsigned)chunks, (unsigned)gnn_div_up(f_in, 128), (unsigned)gnn_div_up(f_out, NT * 32));
-        hipLaunchKernelGGL(xty_partial_kernel<NT>, grid, dim3(kThreads), 0, s, d_x, t, N, f_in, f_out, rows_per_chunk,
-                           part);
-        GNN_LAUNCH_CHECK();
-        const int64_t elems = (int64_t)f_in * f_out;
-        hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)gnn_div_up(elems, 64)), dim3(kThreads), 0, s, part,
-                           chunks, elems, d_grad_w);
-        GNN_LAUNCH_CHECK();
-    }
+    if (d_grad_w) GNN_TRY(gnn_launch_xty(d_x, t, N, f_in, f_out, part, d_grad_w, s));
     if (d_grad_b) {
         hipLaunchKernelGGL(colsum_partial_kernel, dim3((unsigned)chunks), dim3(kThreads), 0, s, d_grad_out, N, f_out,
                            rows_per_chunk, part);
         GNN_LAUNCH_CHECK();
-        hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)gnn_div_up(f_out, 64)), dim3(kThreads), 0, s, part,
-                           chunks, (int64_t)f_out, d_grad_b);
-        GNN_LAUNCH_CHECK();
+        GNN_TRY(gnn_launch_sum_partials(part, chunks, (int64_t)f_out, d_grad_b, s));
     }
     return GNN_OK;
 }

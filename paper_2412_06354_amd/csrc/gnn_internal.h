@@ -114,3 +114,20 @@ gnn_status gnn_launch_propagate(const gnn_graph *g, const float *d_x, int32_t fe
                                 float *d_out, hipStream_t stream,
                                 gnn_gather_index gather = GNN_GATHER_SOURCE_NODE,
                                 const int32_t *d_winners = nullptr);
+
+// ---- dense helpers shared by the backward passes (gcn_backward.hip)
+// Number of row chunks the two-stage reductions over N rows use.
+int gnn_row_chunk_count(int64_t rows);
+// out[f_in x f_out] = X^T Y over `rows` rows (fp32 MFMA, fixed summation order).  d_partial holds
+// gnn_row_chunk_count(rows) * f_in * f_out floats.
+gnn_status gnn_launch_xty(const float *d_x, const float *d_y, int64_t rows, int f_in, int f_out, float *d_partial,
+                          float *d_out, hipStream_t stream);
+// out[q] = sum over chunks (fixed order) of partial[chunk * elems + q]
+gnn_status gnn_launch_sum_partials(const float *d_partial, int chunks, int64_t elems, float *d_out,
+                                   hipStream_t stream);
+// wt[cols x rows] = w[rows x cols]^T
+gnn_status gnn_launch_transpose(const float *d_w, int rows, int cols, float *d_wt, hipStream_t stream);
+// sl[i,hd] = <a_src[hd,:], h[i,hd,:]>, sr[i,hd] = <a_dst[hd,:], h[i,hd,:]>  (gatconv.hip)
+gnn_status gnn_launch_node_scores(const float *d_h, int64_t N, int heads, int ch, const float *d_a_src,
+                                  const float *d_a_dst, float *d_sl, float *d_sr, hipStream_t stream);
+

@@ -416,6 +416,66 @@ def test_gatconv(gnn, heads, ch, f_in):
     g.close()
 
 
+@pytest.mark.parametrize("heads,ch,f_in", [(8, 8, 100), (2, 4, 16), (1, 64, 32), (4, 16, 24), (3, 2, 10), (2, 1, 6),
+                                           (2, 128, 40)])
+def test_gatconv_backward(gnn, heads, ch, f_in):
+    wl = synth.config4_gat(num_nodes=5000, num_edges=120_000, f_in=f_in, heads=heads, ch=ch, cap=2500.0)
+    p, n, hc = wl.params, wl.num_nodes, heads * ch
+    gout = synth.normal_f32(41 + heads, 7, n * hc).reshape(n, hc)
+    # the derivative of the leaky ReLU jumps at 0, and float and double may disagree about the sign of a
+    # pre-activation within rounding of 0: the few edges that close are left out of the input (a
+    # pre-activation depends on the endpoints' features only, so the others are unchanged)
+    h64 = (wl.x.astype(np.float64) @ p["w"].astype(np.float64)).reshape(n, heads, ch)
+    nl, nr = (h64 * p["a_src"][None]).sum(-1), (h64 * p["a_dst"][None]).sum(-1)
+    keep = np.abs(nl[wl.src] + nr[wl.dst]).min(axis=1) > 1e-5
+    assert keep.mean() > 0.999
+    src, dst = wl.src[keep], wl.dst[keep]
+    v = nl[src] + nr[dst]
+    g = gnn.build_csr(dev(src), dev(dst), n, 8, 128)
+    gt = gnn.build_csr(dev(dst), dev(src), n, 8, 128)
+    assert g.work_sizes()["split_rows"] > 0 and gt.work_sizes()["split_rows"] > 0
+    ref = oracle.gatconv_backward(src, dst, n, wl.x, p["w"], p["a_src"], p["a_dst"], gout, 0.2)
+    stats = torch.empty((n, heads, 2), dtype=torch.float32, device="cuda")
+    args = (dev(wl.x), dev(p["w"]), dev(p["a_src"]), dev(p["a_dst"]))
+    out = gnn.gatconv(g, *args, 0.2, softmax_stats=stats)
+    # the statistics: maximum of the scores and the denominator relative to it
+    sc = np.where(v > 0, v, 0.2 * v)
+    mx = np.full((n, heads), -np.inf)
+    np.maximum.at(mx, dst, sc)
+    den = np.zeros((n, heads))
+    np.add.at(den, dst, np.exp(sc - mx[dst]))
+    st = host(stats).astype(np.float64)
+    has = np.isfinite(mx[:, 0])
+    np.testing.assert_allclose(st[has, :, 0], mx[has], rtol=1e-5, atol=1e-5)
+    np.testing.assert_allclose(st[has, :, 1] * np.exp(st[has, :, 0] - mx[has]), den[has], rtol=2e-4)
+    assert (st[~has, :, 1] == 0).all()
+    gx, gw, gas, gad = gnn.gatconv_backward(g, gt, *args, out, stats, dev(gout), 0.2)
+    assert_close_sabs(host(gx), ref["grad_x"], ref["sabs_x"], what="gat grad_x")
+    assert_close_sabs(host(gw), ref["grad_w"], ref["sabs_w"], what="gat grad_w")
+    assert_close_sabs(host(gas), ref["grad_a_src"], ref["sabs_a_src"], what="gat grad_a_src")
+    assert_close_sabs(host(gad), ref["grad_a_dst"], ref["sabs_a_dst"], what="gat grad_a_dst")
+    # bitwise reproducible
+    gx2, gw2, gas2, gad2 = gnn.gatconv_backward(g, gt, *args, out, stats, dev(gout), 0.2)
+    for a, b in ((gx, gx2), (gw, gw2), (gas, gas2), (gad, gad2)):
+        assert torch.equal(a, b)
+    g.close()
+    gt.close()
+
+
+def test_gatconv_backward_rejects_unsupported_head_width(gnn):
+    wl = synth.config4_gat(num_nodes=300, num_edges=2000, f_in=6, heads=3, ch=5, cap=100.0)
+    p, n = wl.params, wl.num_nodes
+    g = gnn.build_csr(dev(wl.src), dev(wl.dst), n)
+    gt = gnn.build_csr(dev(wl.dst), dev(wl.src), n)
+    stats = torch.empty((n, 3, 2), dtype=torch.float32, device="cuda")
+    args = (dev(wl.x), dev(p["w"]), dev(p["a_src"]), dev(p["a_dst"]))
+    out = gnn.gatconv(g, *args, 0.2, softmax_stats=stats)
+    with pytest.raises(RuntimeError):
+        gnn.gatconv_backward(g, gt, *args, out, stats, torch.ones_like(out), 0.2)
+    g.close()
+    gt.close()
+
+
 def test_segment_softmax_many_heads(gnn):
     wl = powerlaw(2000, 30_000, 4, 1500.0)
     g = gnn.build_csr(dev(wl.src), dev(wl.dst), wl.num_nodes, 4, 64)
