@@ -14,6 +14,7 @@ Other workloads measure the remaining steps of the path, one JSON line each:
   softmax  gnn_segment_softmax, 8 heads, on the same graph
   gcn      gnn_gcnconv on the 100 k-node / 1 M-edge symmetrised power-law graph, 128 -> 128 features
   gat      gnn_gatconv on the 2.45 M-node / 126 M-edge graph, 100 -> 8 heads x 8 channels
+  gat_backward  gnn_gatconv_backward on the same graph
   batched  gnn_gin_update + gnn_graph_pool on 4 096 batched small graphs, F = 32
   tiny     gnn_propagate sum / mean / max on the 2 708-node graph (launch-latency bound)
   backward gnn_propagate_backward (e_mul_xj, sum: grad_x and grad_e) on the headline graph
@@ -305,6 +306,55 @@ def run_gat(args, torch, gnn, synth):
     return line
 
 
+def run_gat_backward(args, torch, gnn, synth):
+    wl = synth.config4_gat()
+    p = wl.params
+    n, e, f_in = wl.num_nodes, wl.num_edges, wl.x.shape[1]
+    heads, ch = p["heads"], p["ch"]
+    hc = heads * ch
+    src, dst = to_dev(torch, wl.src), to_dev(torch, wl.dst)
+    g, gt = gnn.build_csr(src, dst, n), gnn.build_csr(dst, src, n)
+    del src, dst
+    x, w, a_s, a_d = (to_dev(torch, a) for a in (wl.x, p["w"], p["a_src"], p["a_dst"]))
+    gout_h = synth.normal_f32(47, 7, n * hc).reshape(n, hc)
+    gout = to_dev(torch, gout_h)
+    stats = torch.empty((n, heads, 2), dtype=torch.float32, device="cuda")
+    out = gnn.gatconv(g, x, w, a_s, a_d, 0.2, softmax_stats=stats)
+    ws = torch.empty(int(gnn.lib().gnn_gatconv_backward_workspace_bytes(n, f_in, heads, ch)), dtype=torch.uint8,
+                     device="cuda")
+    steps = max(3, min(args.steps, 20))
+    ms = time_calls(torch, lambda: gnn.gatconv_backward(g, gt, x, w, a_s, a_d, out, stats, gout, 0.2, workspace=ws),
+                    steps, 2)
+    # two edge passes: each gathers one feature row and the scalars of the other endpoint per edge
+    bytes_dst_pass = e * (4 * hc + 4 * heads + 4) + n * (4 * hc + 16 * heads + 4 * heads + 4)
+    bytes_src_pass = e * (4 * hc + 16 * heads + 4) + n * (8 * hc + 4 * heads + 4 * heads + 4)
+    bytes_dense = 3 * 4 * (n * f_in + f_in * hc + n * hc) + 6 * 4 * n * hc   # X W, dh W^T, X^T dh; records, score terms
+    gbs = (bytes_dst_pass + bytes_src_pass + bytes_dense) / (ms * 1e-3) / 1e9
+    line = base_line("GAT layer backward (grad X, W, a_src, a_dst) algorithmic GB/s", gbs, ms, args,
+                     wl.name + ":backward", {"N": n, "E": e, "f_in": f_in, "heads": heads, "ch": ch})
+    line["steps"] = steps
+    line["roofline"] = hbm_roofline(gbs, "whole call; dominated by gat_backward_kernel<16,4,false> and <16,4,true>")
+    line["extra"] = {"B_alg_dst_pass_bytes": bytes_dst_pass, "B_alg_src_pass_bytes": bytes_src_pass,
+                     "B_alg_dense_bytes": bytes_dense, "work_lists_by_source": gt.work_sizes()}
+    if not args.no_cpu_baseline:
+        import oracle
+        es = min(args.cpu_sample_edges, e)
+        ns = min(n, 200_000)
+        m = (wl.src[:es] < ns) & (wl.dst[:es] < ns)
+        s_src, s_dst = wl.src[:es][m].copy(), wl.dst[:es][m].copy()
+        t0 = time.perf_counter()
+        oracle.gatconv_backward(s_src, s_dst, ns, wl.x[:ns], p["w"], p["a_src"], p["a_dst"], gout_h[:ns], 0.2)
+        dt = time.perf_counter() - t0
+        ee = int(s_src.shape[0])
+        b = (ee * (8 * hc + 20 * heads + 8) + ns * (12 * hc + 32 * heads) +
+             3 * 4 * (ns * f_in + f_in * hc + ns * hc) + 6 * 4 * ns * hc)
+        line["cpu_baseline"] = {"value": b / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle", "seconds": dt,
+                                "sample": f"the backward on the first {ns} nodes and the {ee} edges among them"}
+    g.close()
+    gt.close()
+    return line
+
+
 def run_batched(args, torch, gnn, synth):
     wl = synth.config3_batched()
     n, e, f, ng = wl.num_nodes, wl.num_edges, wl.x.shape[1], wl.num_graphs
@@ -442,7 +492,7 @@ def run_gcn_backward(args, torch, gnn, synth):
     return line
 
 
-WORKLOADS = {"gcn_backward": run_gcn_backward, "backward": run_backward, "propagate": run_propagate, "csr": run_csr, "softmax": run_softmax, "gcn": run_gcn, "gat": run_gat,
+WORKLOADS = {"gat_backward": run_gat_backward, "gcn_backward": run_gcn_backward, "backward": run_backward, "propagate": run_propagate, "csr": run_csr, "softmax": run_softmax, "gcn": run_gcn, "gat": run_gat,
              "batched": run_batched, "tiny": run_tiny}
 
 

@@ -605,9 +605,13 @@ int oracle_gatconv_backward(const int32_t *src, const int32_t *dst, int64_t E, i
     double *al = (double *)calloc(eh, sizeof(double)), *pre = (double *)calloc(eh, sizeof(double));
     double *da = (double *)calloc(eh, sizeof(double)), *dab = (double *)calloc(eh, sizeof(double));
     double *dh = (double *)calloc(nfo, sizeof(double)), *dhb = (double *)calloc(nfo, sizeof(double));
+    double *acc_as = (double *)calloc((size_t)fo, sizeof(double)), *acc_ad = (double *)calloc((size_t)fo, sizeof(double));
+    double *abs_as = (double *)calloc((size_t)fo, sizeof(double)), *abs_ad = (double *)calloc((size_t)fo, sizeof(double));
+    double *acc_w = (double *)calloc((size_t)f_in * fo, sizeof(double));
+    double *abs_w = (double *)calloc((size_t)f_in * fo, sizeof(double));
     int rc = 3;
     if (!sl || !sr || !mx || !den || !t || !tb || !dsl || !dslb || !dsr || !dsrb || !al || !pre || !da || !dab ||
-        !dh || !dhb)
+        !dh || !dhb || !acc_as || !acc_ad || !abs_as || !abs_ad || !acc_w || !abs_w)
         goto done;
     if (dense_xw(x, N, f_in, w, fo, &z, &za)) goto done;
     for (size_t q = 0; q < nfo; ++q) z[q] = (double)(float)z[q];
@@ -666,20 +670,22 @@ int oracle_gatconv_backward(const int32_t *src, const int32_t *dst, int64_t E, i
                 dhb[(int64_t)src[k] * fo + hd * ch + c] += a * fabs(g);
             }
         }
-    for (int32_t hd = 0; hd < heads; ++hd)
-        for (int32_t c = 0; c < ch; ++c) {
-            double s1 = 0.0, s2 = 0.0, b1 = 0.0, b2 = 0.0;
-            for (int32_t i = 0; i < N; ++i) {
-                s1 += dsl[(int64_t)i * heads + hd] * z[(int64_t)i * fo + hd * ch + c];
-                s2 += dsr[(int64_t)i * heads + hd] * z[(int64_t)i * fo + hd * ch + c];
-                b1 += dslb[(int64_t)i * heads + hd] * za[(int64_t)i * fo + hd * ch + c];
-                b2 += dsrb[(int64_t)i * heads + hd] * za[(int64_t)i * fo + hd * ch + c];
+    /* d a_src, d a_dst: sums over the nodes, accumulated node by node */
+    for (int32_t i = 0; i < N; ++i)
+        for (int32_t hd = 0; hd < heads; ++hd)
+            for (int32_t c = 0; c < ch; ++c) {
+                int64_t q = (int64_t)i * fo + hd * ch + c;
+                acc_as[hd * ch + c] += dsl[(int64_t)i * heads + hd] * z[q];
+                acc_ad[hd * ch + c] += dsr[(int64_t)i * heads + hd] * z[q];
+                abs_as[hd * ch + c] += dslb[(int64_t)i * heads + hd] * za[q];
+                abs_ad[hd * ch + c] += dsrb[(int64_t)i * heads + hd] * za[q];
             }
-            ga_src[hd * ch + c] = (float)s1;
-            ga_dst[hd * ch + c] = (float)s2;
-            if (sabs_as) sabs_as[hd * ch + c] = b1;
-            if (sabs_ad) sabs_ad[hd * ch + c] = b2;
-        }
+    for (int32_t q = 0; q < fo; ++q) {
+        ga_src[q] = (float)acc_as[q];
+        ga_dst[q] = (float)acc_ad[q];
+        if (sabs_as) sabs_as[q] = abs_as[q];
+        if (sabs_ad) sabs_ad[q] = abs_ad[q];
+    }
     for (int32_t i = 0; i < N; ++i)
         for (int32_t hd = 0; hd < heads; ++hd)
             for (int32_t c = 0; c < ch; ++c) {
@@ -689,17 +695,19 @@ int oracle_gatconv_backward(const int32_t *src, const int32_t *dst, int64_t E, i
                 dhb[q] += dslb[(int64_t)i * heads + hd] * fabs((double)a_src[hd * ch + c]) +
                           dsrb[(int64_t)i * heads + hd] * fabs((double)a_dst[hd * ch + c]);
             }
-    /* dW = X^T dh, dX = dh W^T */
-    for (int32_t k = 0; k < f_in; ++k)
-        for (int32_t o = 0; o < fo; ++o) {
-            double s1 = 0.0, b1 = 0.0;
-            for (int32_t i = 0; i < N; ++i) {
-                s1 += (double)x[(int64_t)i * f_in + k] * dh[(int64_t)i * fo + o];
-                b1 += fabs((double)x[(int64_t)i * f_in + k]) * dhb[(int64_t)i * fo + o];
+    /* dW = X^T dh (accumulated node by node), dX = dh W^T */
+    for (int32_t i = 0; i < N; ++i)
+        for (int32_t k = 0; k < f_in; ++k) {
+            double xv = (double)x[(int64_t)i * f_in + k];
+            for (int32_t o = 0; o < fo; ++o) {
+                acc_w[(int64_t)k * fo + o] += xv * dh[(int64_t)i * fo + o];
+                abs_w[(int64_t)k * fo + o] += fabs(xv) * dhb[(int64_t)i * fo + o];
             }
-            gw[(int64_t)k * fo + o] = (float)s1;
-            if (sabs_w) sabs_w[(int64_t)k * fo + o] = b1;
         }
+    for (int64_t q = 0; q < (int64_t)f_in * fo; ++q) {
+        gw[q] = (float)acc_w[q];
+        if (sabs_w) sabs_w[q] = abs_w[q];
+    }
     for (int32_t i = 0; i < N; ++i)
         for (int32_t k = 0; k < f_in; ++k) {
             double s1 = 0.0, b1 = 0.0;
@@ -714,6 +722,7 @@ int oracle_gatconv_backward(const int32_t *src, const int32_t *dst, int64_t E, i
 done:
     free(z); free(za); free(sl); free(sr); free(mx); free(den); free(t); free(tb); free(dsl); free(dslb);
     free(dsr); free(dsrb); free(al); free(pre); free(da); free(dab); free(dh); free(dhb);
+    free(acc_as); free(acc_ad); free(abs_as); free(abs_ad); free(acc_w); free(abs_w);
     return rc;
 }
 

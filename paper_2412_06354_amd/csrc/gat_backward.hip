@@ -283,12 +283,20 @@ __global__ __launch_bounds__(kThreads) void node_records_kernel(const float *__r
                                                                 const float *__restrict__ stats,
                                                                 const float *__restrict__ gout,
                                                                 const float *__restrict__ out, int64_t N, int H,
-                                                                int ch, float4 *__restrict__ rec)
+                                                                int ch, int vec4, float4 *__restrict__ rec)
 {
     const int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (idx >= N * H) return;
     float t = 0.0f;
-    for (int c = 0; c < ch; ++c) t = fmaf(gout[idx * ch + c], out[idx * ch + c], t);
+    if (vec4) {   // ch % 4 == 0 and both arrays 16-byte aligned
+        const float4 *gp = reinterpret_cast<const float4 *>(gout + idx * ch), *op = reinterpret_cast<const float4 *>(out + idx * ch);
+        for (int c = 0; c < ch / 4; ++c) {
+            const float4 a = gp[c], b = op[c];
+            t = fmaf(a.x, b.x, fmaf(a.y, b.y, fmaf(a.z, b.z, fmaf(a.w, b.w, t))));
+        }
+    } else {
+        for (int c = 0; c < ch; ++c) t = fmaf(gout[idx * ch + c], out[idx * ch + c], t);
+    }
     const float m = stats[2 * idx], d = stats[2 * idx + 1];
     rec[idx] = make_float4(sr[idx], d > 0.0f ? m : 0.0f, d > 0.0f ? 1.0f / d : 0.0f, t);
 }
@@ -312,6 +320,8 @@ __global__ __launch_bounds__(kThreads) void add_score_terms_kernel(float *__rest
 }
 
 // partial_l[chunk][col] = sum over the chunk's rows of dsl[row,hd] h[row,col]; partial_r with dsr.
+// A block's threads form (row slice, column) pairs: slice s takes rows s, s + slices, ... of the chunk
+// and the slices are folded through LDS in slice order.
 __global__ __launch_bounds__(kThreads) void attention_vector_partial_kernel(const float *__restrict__ h, int64_t N,
                                                                             int H, int ch,
                                                                             const float *__restrict__ dsl,
@@ -320,27 +330,45 @@ __global__ __launch_bounds__(kThreads) void attention_vector_partial_kernel(cons
                                                                             float *__restrict__ partial_l,
                                                                             float *__restrict__ partial_r)
 {
+    __shared__ float fold_l[kThreads], fold_r[kThreads];
     const int HC = H * ch;
+    const int cw = min(HC, kThreads), slices = kThreads / cw;
+    const int rs = threadIdx.x / cw, c0 = threadIdx.x % cw;
     const int64_t r0 = (int64_t)blockIdx.x * rows_per_chunk, r1 = min(N, r0 + rows_per_chunk);
-    for (int col = threadIdx.x; col < HC; col += kThreads) {
-        const int hd = col / ch;
+    for (int cbase = 0; cbase < HC; cbase += cw) {
+        const int col = cbase + c0;
         float l[2] = {0.0f, 0.0f}, r[2] = {0.0f, 0.0f};   // two interleaved running sums each
-        int64_t row = r0;
-        for (; row + 2 <= r1; row += 2) {
+        if (rs < slices && col < HC) {
+            const int hd = col / ch;
+            int64_t row = r0 + rs;
+            for (; row + slices < r1; row += 2 * slices) {
 #pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                const float hv = h[(row + u) * HC + col];
-                l[u] = fmaf(dsl[(row + u) * H + hd], hv, l[u]);
-                r[u] = fmaf(dsr[(row + u) * H + hd], hv, r[u]);
+                for (int u = 0; u < 2; ++u) {
+                    const int64_t q = row + u * slices;
+                    const float hv = h[q * HC + col];
+                    l[u] = fmaf(dsl[q * H + hd], hv, l[u]);
+                    r[u] = fmaf(dsr[q * H + hd], hv, r[u]);
+                }
+            }
+            if (row < r1) {
+                const float hv = h[row * HC + col];
+                l[0] = fmaf(dsl[row * H + hd], hv, l[0]);
+                r[0] = fmaf(dsr[row * H + hd], hv, r[0]);
             }
         }
-        for (; row < r1; ++row) {
-            const float hv = h[row * HC + col];
-            l[0] = fmaf(dsl[row * H + hd], hv, l[0]);
-            r[0] = fmaf(dsr[row * H + hd], hv, r[0]);
+        fold_l[threadIdx.x] = l[0] + l[1];
+        fold_r[threadIdx.x] = r[0] + r[1];
+        __syncthreads();
+        if (rs == 0 && col < HC) {
+            float sl_ = 0.0f, sr_ = 0.0f;
+            for (int q = 0; q < slices; ++q) {
+                sl_ += fold_l[q * cw + c0];
+                sr_ += fold_r[q * cw + c0];
+            }
+            partial_l[(int64_t)blockIdx.x * HC + col] = sl_;
+            partial_r[(int64_t)blockIdx.x * HC + col] = sr_;
         }
-        partial_l[(int64_t)blockIdx.x * HC + col] = l[0] + l[1];
-        partial_r[(int64_t)blockIdx.x * HC + col] = r[0] + r[1];
+        __syncthreads();
     }
 }
 
@@ -454,7 +482,8 @@ gnn_status gnn_gatconv_backward(const gnn_graph *g, const gnn_graph *g_by_source
     GNN_TRY(gnn_dense_xw(d_x, N, f_in, d_w, HC, nullptr, h, stream));
     GNN_TRY(gnn_launch_node_scores(h, N, heads, ch, d_a_src, d_a_dst, sl, sr, s));
     hipLaunchKernelGGL(node_records_kernel, dim3((unsigned)gnn_div_up(N * heads, kThreads)), dim3(kThreads), 0, s, sr,
-                       d_softmax_stats, d_grad_out, d_out, N, heads, ch, rec);
+                       d_softmax_stats, d_grad_out, d_out, N, heads, ch,
+                       (vec4 && (reinterpret_cast<uintptr_t>(d_out) & 15u) == 0) ? 1 : 0, rec);
     GNN_LAUNCH_CHECK();
 
     GatBwdParams p{};

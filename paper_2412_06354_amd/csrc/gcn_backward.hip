@@ -167,7 +167,7 @@ BackwardLayout layout(int64_t N, int f_in, int f_out)
 
 int gnn_row_chunk_count(int64_t rows)
 {
-    return (int)std::max<int64_t>(1, std::min<int64_t>(512, gnn_div_up(rows, 256)));
+    return (int)std::max<int64_t>(1, std::min<int64_t>(2048, gnn_div_up(rows, 256)));
 }
 
 gnn_status gnn_launch_sum_partials(const float *d_partial, int chunks, int64_t elems, float *d_out, hipStream_t s)

@@ -13,7 +13,7 @@
 // one 128-bit LDS read; the 16-byte groups of a column are xor-swizzled with (col % 8) so that the
 // lanes of a read (same group, consecutive columns) fall into different banks without padding.
 //
-// Fast kernel (k <= 128, full tiles): blocks are persistent, stage their column block of W once,
+// Fast kernel (k <= 128, k and n multiples of 4): blocks are persistent, stage their column block of W once,
 // then walk over row tiles.
 // General kernel (any shape, ragged edges): one tile per block, W re-staged per 64-k slab.
 #include "gnn_internal.h"
@@ -155,8 +155,9 @@ __device__ __forceinline__ void stage_w(float *ws, const float *__restrict__ w, 
     }
 }
 
-// Fast path: full BN-column blocks, k <= 64*NSUB <= 128, 16-byte aligned rows (a ragged last row
-// tile is handled by clamped loads and a guarded store).  Blocks are persistent: they stage their column block of W once and then walk over row
+// Fast path: k <= 64*NSUB <= 128, k and n multiples of 4, 16-byte aligned rows (a ragged last row tile
+// is handled by clamped loads and a guarded store, a ragged last column block by zero-filled W and a
+// guarded store).  Blocks are persistent: they stage their column block of W once and then walk over row
 // tiles.  Per tile a wavefront issues all of its X loads (no branches), runs the MFMAs and writes
 // the tile with 128-bit stores; several wavefronts per SIMD overlap one another's load latency
 // with MFMAs (register use is kept low for that: no second X buffer).
@@ -195,13 +196,15 @@ __global__ __launch_bounds__(kThreads) void xw_fast_kernel(const float *__restri
 
         if (row < rows) {   // false only for lanes past the end in a ragged last tile
             float *zrow = z + row * n + n0 + 4 * half;
+            const int ncols = n - n0 - 4 * half;   // n % 4 == 0: a group of four columns is inside or outside as a whole
 #pragma unroll
             for (int t = 0; t < NT; ++t)
 #pragma unroll
                 for (int g = 0; g < 4; ++g)
-                    *reinterpret_cast<float4 *>(zrow + t * 32 + 8 * g) =
-                        make_float4(acc[t][4 * g] * sc, acc[t][4 * g + 1] * sc, acc[t][4 * g + 2] * sc,
-                                    acc[t][4 * g + 3] * sc);
+                    if (t * 32 + 8 * g < ncols)
+                        *reinterpret_cast<float4 *>(zrow + t * 32 + 8 * g) =
+                            make_float4(acc[t][4 * g] * sc, acc[t][4 * g + 1] * sc, acc[t][4 * g + 2] * sc,
+                                        acc[t][4 * g + 3] * sc);
         }
     }
 }
@@ -274,7 +277,8 @@ gnn_status launch_fast(const float *d_x, int64_t rows, int k, const float *d_w, 
     const int64_t full_tiles = gnn_div_up(rows, kRowsPerBlock);
     const size_t lds = (size_t)NSUB * kSlab * BN * sizeof(float);
     const int per_cu = (int)std::max<size_t>(1, std::min<size_t>(4, (160 * 1024) / lds));
-    const dim3 grid((unsigned)std::min<int64_t>(full_tiles, (int64_t)device_cu_count() * per_cu), (unsigned)(n / BN));
+    const dim3 grid((unsigned)std::min<int64_t>(full_tiles, (int64_t)device_cu_count() * per_cu),
+                    (unsigned)gnn_div_up(n, BN));
     if (d_row_scale)
         hipLaunchKernelGGL((xw_fast_kernel<NT, NSUB, true>), grid, dim3(kThreads), lds, s, d_x, k, d_w, n, d_row_scale,
                            d_z, rows);
@@ -290,7 +294,7 @@ gnn_status launch_xw(const float *d_x, int64_t rows, int k, const float *d_w, in
                      float *d_z, bool x_vec4, bool w_vec4, hipStream_t s)
 {
     constexpr int BN = NT * 32;
-    const bool fast = x_vec4 && w_vec4 && (n % BN == 0) && k <= 2 * kSlab;
+    const bool fast = x_vec4 && w_vec4 && k <= 2 * kSlab;   // w_vec4 implies n % 4 == 0
     if (!fast) return launch_general<NT>(d_x, rows, k, d_w, n, d_row_scale, d_z, x_vec4, w_vec4, 0, s);
     if (k <= kSlab) return launch_fast<NT, 1>(d_x, rows, k, d_w, n, d_row_scale, d_z, s);
     return launch_fast<NT, 2>(d_x, rows, k, d_w, n, d_row_scale, d_z, s);

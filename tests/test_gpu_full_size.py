@@ -170,4 +170,76 @@ def test_config4_gatconv_sampled_rows(gnn):
                                p["negative_slope"], with_sabs=True)
     got = host(out[torch.from_numpy(rows).cuda()])
     assert_close_sabs(got, ref[local_rows], sabs[local_rows], what="config4 gatconv")
+
+    # backward at the same size: grad_x of sampled source nodes.  Such a row needs the node's own
+    # incoming edges and, for every edge it sends, the whole neighbourhood of that edge's destination.
+    say("config 4: backward")
+    hc = p["heads"] * p["ch"]
+    gt = gnn.build_csr(dev(wl.dst), dev(wl.src), n)
+    stats = torch.empty((n, p["heads"], 2), dtype=torch.float32, device="cuda")
+    args = (dev(wl.x), dev(p["w"]), dev(p["a_src"]), dev(p["a_dst"]))
+    out = gnn.gatconv(g, *args, p["negative_slope"], softmax_stats=stats)
+    gout = synth.normal_f32(53, 7, n * hc).reshape(n, hc)
+    gx, gw, gas, gad = gnn.gatconv_backward(g, gt, *args, out, stats, dev(gout), p["negative_slope"])
+    torch.cuda.synchronize()
+    assert all(bool(torch.isfinite(t).all()) for t in (gx, gw, gas, gad))
+    # candidates: random nodes whose destinations' neighbourhoods total at most 30 000 edges (about a
+    # third of all nodes; the oracle runs on everything those neighbourhoods touch), the first 12 of them
+    pool = np.unique(synth.randint(29, 9, 0, 600, 0, n - 1)).astype(np.int64)
+    lut = np.zeros(n, dtype=bool)
+    lut[pool] = True
+    pool_edges = np.flatnonzero(lut[wl.src])
+    cost = np.zeros(n, dtype=np.int64)
+    np.add.at(cost, wl.src[pool_edges], indeg[wl.dst[pool_edges]])
+    cand = pool[(cost[pool] > 0) & (cost[pool] <= 30_000)][:12]
+    lut[:] = False
+    lut[cand] = True
+    out_edges = np.flatnonzero(lut[wl.src])
+    rows_b = np.unique(np.concatenate([cand, wl.dst[out_edges]]))
+    b_src, b_dst, b_nodes, b_local, b_eid = subgraph_for_rows(wl.src, wl.dst, rows_b)
+    say(f"config 4: backward oracle on {cand.shape[0]} sampled nodes: {b_eid.shape[0]} edges, {b_nodes.shape[0]} nodes")
+    # leave out sampled nodes with an incident edge whose pre-activation is within rounding of the
+    # leaky ReLU's kink (float and double may take different slopes there)
+    h64 = (wl.x[b_nodes].astype(np.float64) @ p["w"].astype(np.float64)).reshape(-1, p["heads"], p["ch"])
+    nl, nr = (h64 * p["a_src"][None]).sum(-1), (h64 * p["a_dst"][None]).sum(-1)
+    near = np.abs(nl[b_src] + nr[b_dst]).min(axis=1) < 1e-5
+    cand_local = np.searchsorted(b_nodes, cand)
+    touched = np.zeros(b_nodes.shape[0], dtype=bool)
+    touched[b_src[near]] = True
+    touched[b_dst[near]] = True
+    ok = ~touched[cand_local]
+    assert ok.sum() >= 8
+    ref_b = oracle.gatconv_backward(b_src, b_dst, b_nodes.shape[0], wl.x[b_nodes], p["w"], p["a_src"], p["a_dst"],
+                                    gout[b_nodes], p["negative_slope"])
+    got_b = host(gx[torch.from_numpy(cand[ok]).cuda()])
+    assert_close_sabs(got_b, ref_b["grad_x"][cand_local[ok]], ref_b["sabs_x"][cand_local[ok]],
+                      what="config4 gatconv backward grad_x")
     g.close()
+    gt.close()
+
+
+def test_gatconv_backward_mid_size_all_gradients(gnn):
+    """All four gradients against the oracle on the whole graph, at a size where the row-chunked
+    reductions use their maximum number of chunks and the default thresholds apply."""
+    say("GAT backward, 100k nodes / 2M edges: generating")
+    wl = synth.config4_gat(num_nodes=100_000, num_edges=2_000_000, cap=5000.0)
+    p, n = wl.params, wl.num_nodes
+    hc = p["heads"] * p["ch"]
+    h64 = (wl.x.astype(np.float64) @ p["w"].astype(np.float64)).reshape(n, p["heads"], p["ch"])
+    nl, nr = (h64 * p["a_src"][None]).sum(-1), (h64 * p["a_dst"][None]).sum(-1)
+    keep = np.abs(nl[wl.src] + nr[wl.dst]).min(axis=1) > 1e-5     # see test_gatconv_backward in test_gpu_parity
+    src, dst = wl.src[keep], wl.dst[keep]
+    gout = synth.normal_f32(59, 7, n * hc).reshape(n, hc)
+    g, gt = gnn.build_csr(dev(src), dev(dst), n), gnn.build_csr(dev(dst), dev(src), n)
+    stats = torch.empty((n, p["heads"], 2), dtype=torch.float32, device="cuda")
+    args = (dev(wl.x), dev(p["w"]), dev(p["a_src"]), dev(p["a_dst"]))
+    out = gnn.gatconv(g, *args, p["negative_slope"], softmax_stats=stats)
+    gx, gw, gas, gad = gnn.gatconv_backward(g, gt, *args, out, stats, dev(gout), p["negative_slope"])
+    say("GAT backward: oracle")
+    ref = oracle.gatconv_backward(src, dst, n, wl.x, p["w"], p["a_src"], p["a_dst"], gout, p["negative_slope"])
+    assert_close_sabs(host(gx), ref["grad_x"], ref["sabs_x"], what="gat grad_x")
+    assert_close_sabs(host(gw), ref["grad_w"], ref["sabs_w"], what="gat grad_w")
+    assert_close_sabs(host(gas), ref["grad_a_src"], ref["sabs_a_src"], what="gat grad_a_src")
+    assert_close_sabs(host(gad), ref["grad_a_dst"], ref["sabs_a_dst"], what="gat grad_a_dst")
+    g.close()
+    gt.close()
