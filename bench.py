@@ -204,6 +204,13 @@ def run_softmax(args, torch, gnn, synth):
     s_csr = gnn.edge_data_to_csr(g, s)
     t = time_calls(torch, lambda: gnn.segment_softmax(g, s_csr, order=gnn.EDGE_ORDER_CSR, out=out), max(5, args.steps // 4), 3)
     line["extra"]["csr_ordered_ms"] = t
+    galpha = to_dev(torch, synth.normal_f32(55, 3, e * heads).reshape(e, heads))
+    alpha = gnn.segment_softmax(g, s)
+    gs = torch.empty_like(s)
+    tb = time_calls(torch, lambda: gnn.segment_softmax_backward(g, alpha, galpha, out=gs), max(5, args.steps // 4), 3)
+    line["extra"]["backward_ms"] = tb
+    line["extra"]["backward_GBs_alg"] = (e * heads * 4 * 5 + e * 4 * 3 + n * heads * 8 * 2) / (tb * 1e-3) / 1e9
+    del galpha, alpha, gs
     if not args.no_cpu_baseline:
         import oracle
         es = min(args.cpu_sample_edges, e)

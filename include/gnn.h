@@ -212,6 +212,17 @@ gnn_status gnn_segment_softmax(const gnn_graph *g, const float *d_scores, int32_
                                gnn_edge_order order, float *d_out, void *stream);
 
 /*
+ * Backward of gnn_segment_softmax (training is the paper's purpose, section 3 "Training Example"):
+ * the Jacobian of a softmax applied per destination segment and head,
+ *   grad_scores[k,h] = alpha[k,h] * (grad_alpha[k,h] - sum_{q: dst[q] = dst[k]} alpha[q,h] grad_alpha[q,h]).
+ * d_alpha is the forward result, d_grad_alpha = dL/d alpha, all three arrays [E x heads] in the order
+ * `order` names.  No atomics: bitwise reproducible.  d_grad_scores must not alias the inputs.
+ */
+gnn_status gnn_segment_softmax_backward(const gnn_graph *g, const float *d_alpha, const float *d_grad_alpha,
+                                        int32_t heads, gnn_edge_order order, float *d_grad_scores,
+                                        void *stream);
+
+/*
  * GAT-style attention layer (layer named in the paper, section 3 "Graph Convolutional Layers"):
  *   h = X W  [N x heads*ch];  sl[j,hd] = <a_src[hd,:], h[j,hd,:]>;  sr[i,hd] = <a_dst[hd,:], h[i,hd,:]>
  *   s[k,hd] = lrelu(sl[src[k],hd] + sr[dst[k],hd]),  lrelu(v) = v > 0 ? v : negative_slope * v

@@ -49,6 +49,7 @@ SIGNATURES = {
     "gnn_gcnconv_backward_workspace_bytes": (_sz, [_i32, _i32, _i32]),
     "gnn_gcnconv_backward": (_c.c_int, [_vp, _vp, _vp, _i32, _vp, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "gnn_segment_softmax": (_c.c_int, [_vp, _vp, _i32, _c.c_int, _vp, _vp]),
+    "gnn_segment_softmax_backward": (_c.c_int, [_vp, _vp, _vp, _i32, _c.c_int, _vp, _vp]),
     "gnn_gatconv_workspace_bytes": (_sz, [_i32, _i32, _i32]),
     "gnn_gatconv": (_c.c_int, [_vp, _vp, _i32, _vp, _vp, _vp, _i32, _i32, _f32, _vp, _vp, _vp, _sz, _vp]),
     "gnn_gatconv_backward_workspace_bytes": (_sz, [_i32, _i32, _i32, _i32]),
@@ -326,6 +327,21 @@ def segment_softmax(g: Graph, scores: torch.Tensor, order: int = EDGE_ORDER_COO,
     rc = lib().gnn_segment_softmax(g._h, _dev(s2, torch.float32, "scores"), int(s2.shape[1]) if g.num_edges else 1,
                                    order, _dev(out, torch.float32, "out"), _stream())
     _check(rc, "gnn_segment_softmax")
+    return out
+
+
+def segment_softmax_backward(g: Graph, alpha: torch.Tensor, grad_alpha: torch.Tensor, order: int = EDGE_ORDER_COO,
+                             out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    if alpha.shape != grad_alpha.shape:
+        raise ValueError("shape mismatch")
+    a2, g2 = alpha.reshape(g.num_edges, -1), grad_alpha.reshape(g.num_edges, -1)
+    if out is None:
+        out = torch.empty_like(alpha)
+    rc = lib().gnn_segment_softmax_backward(g._h, _dev(a2, torch.float32, "alpha"),
+                                            _dev(g2, torch.float32, "grad_alpha"),
+                                            int(a2.shape[1]) if g.num_edges else 1, order,
+                                            _dev(out, torch.float32, "out"), _stream())
+    _check(rc, "gnn_segment_softmax_backward")
     return out
 
 

@@ -26,6 +26,7 @@ constexpr int kWavesPerBlock = kThreads / 64;
 struct SmParams {
     const int32_t *rowptr, *perm, *row_of_edge;
     const float *s;
+    const float *s2;    // backward only: dL/d alpha (s then holds alpha)
     float *out;
     float2 *rowstat;    // [N x H]  (m, den)
     float2 *slotstat;   // [slots x H]
@@ -56,6 +57,21 @@ __device__ __forceinline__ void online_merge(float &m, float &d, float m2, float
     m = mm;
 }
 
+// Forward: running (max, denominator).  Backward: d accumulates alpha * dalpha (m is unused).
+template <bool BWD>
+__device__ __forceinline__ void acc_add(float &m, float &d, bool ok, float v, float w)
+{
+    if constexpr (BWD) d += ok ? v * w : 0.0f;
+    else online_add(m, d, ok, v);
+}
+
+template <bool BWD>
+__device__ __forceinline__ void acc_merge(float &m, float &d, float m2, float d2)
+{
+    if constexpr (BWD) d += d2;
+    else online_merge(m, d, m2, d2);
+}
+
 template <int HV>
 __device__ __forceinline__ void load_heads(float (&v)[HV], const float *__restrict__ p)
 {
@@ -80,7 +96,7 @@ __device__ __forceinline__ void store_stats(float2 *__restrict__ dst, const floa
 }
 
 // HP lanes per edge, each lane owns HV consecutive heads (HV = 4: 128-bit score loads).
-template <int HP, int HV>
+template <int HP, int HV, bool BWD>
 __device__ __forceinline__ void stats_short_rows(const SmParams &p, int block)
 {
     constexpr int NSG = 64 / HP;
@@ -112,7 +128,7 @@ __device__ __forceinline__ void stats_short_rows(const SmParams &p, int block)
             }
             const int cnt = min(HP, wmax - base);
             for (int t0 = 0; t0 < cnt; t0 += U) {
-                float v[U][HV];
+                float v[U][HV], w[U][HV];
                 bool ok[U];
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
@@ -120,20 +136,23 @@ __device__ __forceinline__ void stats_short_rows(const SmParams &p, int block)
                     const int eid = __shfl(my_eid, t, HP);
                     ok[u] = hok && (t < HP) && (base + t < deg);
 #pragma unroll
-                    for (int c = 0; c < HV; ++c) v[u][c] = 0.0f;
-                    if (ok[u]) load_heads<HV>(v[u], p.s + (int64_t)eid * p.H + h);
+                    for (int c = 0; c < HV; ++c) { v[u][c] = 0.0f; w[u][c] = 0.0f; }
+                    if (ok[u]) {
+                        load_heads<HV>(v[u], p.s + (int64_t)eid * p.H + h);
+                        if constexpr (BWD) load_heads<HV>(w[u], p.s2 + (int64_t)eid * p.H + h);
+                    }
                 }
 #pragma unroll
                 for (int u = 0; u < U; ++u)
 #pragma unroll
-                    for (int c = 0; c < HV; ++c) online_add(m[c], d[c], ok[u], v[u][c]);
+                    for (int c = 0; c < HV; ++c) acc_add<BWD>(m[c], d[c], ok[u], v[u][c], w[u][c]);
             }
         }
         if (hok) store_stats<HV>(p.rowstat + (int64_t)row * p.H + h, m, d);
     }
 }
 
-template <int HP, int HV>
+template <int HP, int HV, bool BWD>
 __device__ __forceinline__ void stats_long_pieces(const SmParams &p, int block)
 {
     constexpr int ES = 64 / HP;   // edges per step
@@ -154,7 +173,7 @@ __device__ __forceinline__ void stats_long_pieces(const SmParams &p, int block)
         for (int c = 0; c < HV; ++c) { m[c] = -INFINITY; d[c] = 0.0f; }
         for (int q0 = start; q0 < end; q0 += ES * U) {
             int eid[U];
-            float v[U][HV];
+            float v[U][HV], w[U][HV];
             bool ok[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
@@ -166,20 +185,23 @@ __device__ __forceinline__ void stats_long_pieces(const SmParams &p, int block)
 #pragma unroll
             for (int u = 0; u < U; ++u) {
 #pragma unroll
-                for (int c = 0; c < HV; ++c) v[u][c] = 0.0f;
-                if (ok[u]) load_heads<HV>(v[u], p.s + (int64_t)eid[u] * p.H + h);
+                for (int c = 0; c < HV; ++c) { v[u][c] = 0.0f; w[u][c] = 0.0f; }
+                if (ok[u]) {
+                    load_heads<HV>(v[u], p.s + (int64_t)eid[u] * p.H + h);
+                    if constexpr (BWD) load_heads<HV>(w[u], p.s2 + (int64_t)eid[u] * p.H + h);
+                }
             }
 #pragma unroll
             for (int u = 0; u < U; ++u)
 #pragma unroll
-                for (int c = 0; c < HV; ++c) online_add(m[c], d[c], ok[u], v[u][c]);
+                for (int c = 0; c < HV; ++c) acc_add<BWD>(m[c], d[c], ok[u], v[u][c], w[u][c]);
         }
 #pragma unroll
         for (int off = HP; off < 64; off <<= 1) {
 #pragma unroll
             for (int c = 0; c < HV; ++c) {
                 const float m2 = __shfl_xor(m[c], off, 64), d2 = __shfl_xor(d[c], off, 64);
-                online_merge(m[c], d[c], m2, d2);
+                acc_merge<BWD>(m[c], d[c], m2, d2);
             }
         }
         if (es == 0 && hok)
@@ -187,15 +209,16 @@ __device__ __forceinline__ void stats_long_pieces(const SmParams &p, int block)
     }
 }
 
-template <int HP, int HV>
+template <int HP, int HV, bool BWD>
 __global__ __launch_bounds__(kThreads) void stats_kernel(const SmParams p)
 {
     if ((int)blockIdx.x < p.item_blocks)
-        stats_long_pieces<HP, HV>(p, blockIdx.x);
+        stats_long_pieces<HP, HV, BWD>(p, blockIdx.x);
     else
-        stats_short_rows<HP, HV>(p, blockIdx.x - p.item_blocks);
+        stats_short_rows<HP, HV, BWD>(p, blockIdx.x - p.item_blocks);
 }
 
+template <bool BWD>
 __global__ __launch_bounds__(kThreads) void stats_merge_kernel(const SmParams p)
 {
     const int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x;
@@ -209,7 +232,7 @@ __global__ __launch_bounds__(kThreads) void stats_merge_kernel(const SmParams p)
     float m = -INFINITY, d = 0.0f;
     for (int c = 0; c < pieces; ++c) {
         const float2 st = p.slotstat[(int64_t)(slot0 + c) * p.H + h];
-        online_merge(m, d, st.x, st.y);
+        acc_merge<BWD>(m, d, st.x, st.y);
     }
     p.rowstat[(int64_t)row * p.H + h] = make_float2(m, d);
 }
@@ -241,43 +264,69 @@ __global__ __launch_bounds__(kThreads) void normalise_kernel(const SmParams p)
     }
 }
 
-template <int HP, int HV>
+// Backward: gs = alpha * (dalpha - t[row]) with t = the row's sum of alpha * dalpha (rowstat.y).
+template <int HV>
+__global__ __launch_bounds__(kThreads) void jacobian_kernel(const SmParams p)
+{
+    const int hg = p.H / HV;
+    const int64_t total = p.E * hg;
+    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    for (int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x; idx < total; idx += stride) {
+        const int64_t k = idx / hg;
+        const int h = (int)(idx - k * hg) * HV;
+        const int row = __builtin_nontemporal_load(p.row_of_edge + k);
+        const float2 *st = p.rowstat + (int64_t)row * p.H + h;
+        if constexpr (HV == 4) {
+            typedef float v4f __attribute__((ext_vector_type(4)));
+            const float4 s0 = reinterpret_cast<const float4 *>(st)[0], s1 = reinterpret_cast<const float4 *>(st)[1];
+            const v4f a = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(p.s + k * p.H + h));
+            const v4f g = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(p.s2 + k * p.H + h));
+            v4f o = {a.x * (g.x - s0.y), a.y * (g.y - s0.w), a.z * (g.z - s1.y), a.w * (g.w - s1.w)};
+            __builtin_nontemporal_store(o, reinterpret_cast<v4f *>(p.out + k * p.H + h));
+        } else {
+            const float a = __builtin_nontemporal_load(p.s + k * p.H + h);
+            const float g = __builtin_nontemporal_load(p.s2 + k * p.H + h);
+            __builtin_nontemporal_store(a * (g - st[0].y), p.out + k * p.H + h);
+        }
+    }
+}
+
+template <int HP, int HV, bool BWD>
 gnn_status launch_stats(const SmParams &p, hipStream_t s)
 {
     const int64_t blocks = p.item_blocks + gnn_div_up(p.n_small, kWavesPerBlock * (64 / HP));
     if (blocks > 0) {
-        hipLaunchKernelGGL((stats_kernel<HP, HV>), dim3((unsigned)blocks), dim3(kThreads), 0, s, p);
+        hipLaunchKernelGGL((stats_kernel<HP, HV, BWD>), dim3((unsigned)blocks), dim3(kThreads), 0, s, p);
         GNN_LAUNCH_CHECK();
     }
     return GNN_OK;
 }
 
-template <int HV>
+template <int HV, bool BWD>
 gnn_status launch_stats_hv(const SmParams &p, int lanes_needed, hipStream_t s)
 {
     int hp = 1;
     while (hp < lanes_needed && hp < 64) hp <<= 1;
     switch (hp) {
-    case 1: return launch_stats<1, HV>(p, s);
-    case 2: return launch_stats<2, HV>(p, s);
-    case 4: return launch_stats<4, HV>(p, s);
-    case 8: return launch_stats<8, HV>(p, s);
-    case 16: return launch_stats<16, HV>(p, s);
-    case 32: return launch_stats<32, HV>(p, s);
-    default: return launch_stats<64, HV>(p, s);
+    case 1: return launch_stats<1, HV, BWD>(p, s);
+    case 2: return launch_stats<2, HV, BWD>(p, s);
+    case 4: return launch_stats<4, HV, BWD>(p, s);
+    case 8: return launch_stats<8, HV, BWD>(p, s);
+    case 16: return launch_stats<16, HV, BWD>(p, s);
+    case 32: return launch_stats<32, HV, BWD>(p, s);
+    default: return launch_stats<64, HV, BWD>(p, s);
     }
 }
 
-}  // namespace
-
-extern "C" gnn_status gnn_segment_softmax(const gnn_graph *g, const float *d_scores, int32_t heads,
-                                          gnn_edge_order order, float *d_out, void *stream)
+template <bool BWD>
+gnn_status run_softmax(const gnn_graph *g, const float *d_in, const float *d_in2, int32_t heads, gnn_edge_order order,
+                       float *d_out, void *stream)
 {
     if (!g) return GNN_ERR_NULL;
     if (heads <= 0) return GNN_ERR_BAD_SIZE;
     if (order != GNN_EDGE_ORDER_COO && order != GNN_EDGE_ORDER_CSR) return GNN_ERR_BAD_SIZE;
     if (g->num_edges == 0) return GNN_OK;
-    if (!d_scores || !d_out) return GNN_ERR_NULL;
+    if (!d_in || !d_out || (BWD && !d_in2)) return GNN_ERR_NULL;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const size_t stat_floats = 2 * ((size_t)g->num_nodes + (size_t)g->n_slots) * heads;
     GNN_TRY(gnn_graph_reserve_scratch(g, stat_floats));
@@ -286,7 +335,7 @@ extern "C" gnn_status gnn_segment_softmax(const gnn_graph *g, const float *d_sco
     p.coo = (order == GNN_EDGE_ORDER_COO) ? 1 : 0;
     p.rowptr = g->rowptr; p.perm = g->perm;
     p.row_of_edge = p.coo ? g->dst_coo : g->rowidx;
-    p.s = d_scores; p.out = d_out;
+    p.s = d_in; p.s2 = d_in2; p.out = d_out;
     p.rowstat = reinterpret_cast<float2 *>(g->scratch);
     p.slotstat = p.rowstat + (size_t)g->num_nodes * heads;
     p.small_rows = g->small_rows; p.item_row = g->item_row; p.item_start = g->item_start;
@@ -295,25 +344,48 @@ extern "C" gnn_status gnn_segment_softmax(const gnn_graph *g, const float *d_sco
     p.H = heads; p.E = g->num_edges;
     p.item_blocks = (int32_t)gnn_div_up(g->n_items, kWavesPerBlock);
 
-    const bool vec4 = (heads % 4 == 0) && ((reinterpret_cast<uintptr_t>(d_scores) & 15u) == 0) &&
-                      ((reinterpret_cast<uintptr_t>(d_out) & 15u) == 0);
+    const bool vec4 = (heads % 4 == 0) && ((reinterpret_cast<uintptr_t>(d_in) & 15u) == 0) &&
+                      ((reinterpret_cast<uintptr_t>(d_out) & 15u) == 0) &&
+                      ((reinterpret_cast<uintptr_t>(d_in2) & 15u) == 0);
     if (vec4)
-        GNN_TRY(launch_stats_hv<4>(p, heads / 4, s));
+        GNN_TRY((launch_stats_hv<4, BWD>(p, heads / 4, s)));
     else
-        GNN_TRY(launch_stats_hv<1>(p, heads, s));
+        GNN_TRY((launch_stats_hv<1, BWD>(p, heads, s)));
     if (g->n_split > 0) {
         const unsigned blocks = (unsigned)gnn_div_up((int64_t)g->n_split * heads, kThreads);
-        hipLaunchKernelGGL(stats_merge_kernel, dim3(blocks), dim3(kThreads), 0, s, p);
+        hipLaunchKernelGGL(stats_merge_kernel<BWD>, dim3(blocks), dim3(kThreads), 0, s, p);
         GNN_LAUNCH_CHECK();
     }
     {
         const int64_t total = g->num_edges * (vec4 ? heads / 4 : heads);
         const unsigned blocks = (unsigned)std::min<int64_t>(gnn_div_up(total, kThreads), 256 * 64);
-        if (vec4)
-            hipLaunchKernelGGL(normalise_kernel<4>, dim3(blocks), dim3(kThreads), 0, s, p);
-        else
-            hipLaunchKernelGGL(normalise_kernel<1>, dim3(blocks), dim3(kThreads), 0, s, p);
+        if (BWD) {
+            if (vec4)
+                hipLaunchKernelGGL(jacobian_kernel<4>, dim3(blocks), dim3(kThreads), 0, s, p);
+            else
+                hipLaunchKernelGGL(jacobian_kernel<1>, dim3(blocks), dim3(kThreads), 0, s, p);
+        } else {
+            if (vec4)
+                hipLaunchKernelGGL(normalise_kernel<4>, dim3(blocks), dim3(kThreads), 0, s, p);
+            else
+                hipLaunchKernelGGL(normalise_kernel<1>, dim3(blocks), dim3(kThreads), 0, s, p);
+        }
         GNN_LAUNCH_CHECK();
     }
     return GNN_OK;
+}
+
+}  // namespace
+
+extern "C" gnn_status gnn_segment_softmax(const gnn_graph *g, const float *d_scores, int32_t heads,
+                                          gnn_edge_order order, float *d_out, void *stream)
+{
+    return run_softmax<false>(g, d_scores, nullptr, heads, order, d_out, stream);
+}
+
+extern "C" gnn_status gnn_segment_softmax_backward(const gnn_graph *g, const float *d_alpha, const float *d_grad_alpha,
+                                                   int32_t heads, gnn_edge_order order, float *d_grad_scores,
+                                                   void *stream)
+{
+    return run_softmax<true>(g, d_alpha, d_grad_alpha, heads, order, d_grad_scores, stream);
 }

@@ -477,6 +477,25 @@ def test_gatconv_backward_rejects_unsupported_head_width(gnn):
     gt.close()
 
 
+@pytest.mark.parametrize("heads", [1, 8, 3])
+def test_segment_softmax_backward(case, gnn, heads):
+    name, wl, g = case
+    e = wl.num_edges
+    s = (3.0 * synth.normal_f32(61 + heads, 2, e * heads)).reshape(e, heads)
+    galpha = synth.normal_f32(61 + heads, 3, e * heads).reshape(e, heads)
+    alpha = oracle.segment_softmax(wl.dst, wl.num_nodes, s)
+    ref, sabs = oracle.segment_softmax_backward(wl.dst, wl.num_nodes, alpha, galpha, with_sabs=True)
+    got = host(gnn.segment_softmax_backward(g, dev(alpha), dev(galpha)))
+    assert_close_sabs(got, ref, sabs, what=f"softmax backward {name} H={heads}")
+    _, _, perm, _ = oracle.build_csr(wl.src, wl.dst, wl.num_nodes)
+    got_csr = host(gnn.segment_softmax_backward(g, dev(alpha[perm]), dev(galpha[perm]), order=gnn.EDGE_ORDER_CSR))
+    np.testing.assert_array_equal(got_csr, got[perm])
+    # a gradient that is constant over every segment is annihilated
+    per_seg = synth.normal_f32(5, 4, wl.num_nodes * heads).reshape(wl.num_nodes, heads)[wl.dst]
+    zero = host(gnn.segment_softmax_backward(g, dev(alpha), dev(np.ascontiguousarray(per_seg))))
+    assert np.abs(zero).max() <= 2e-6
+
+
 def test_segment_softmax_many_heads(gnn):
     wl = powerlaw(2000, 30_000, 4, 1500.0)
     g = gnn.build_csr(dev(wl.src), dev(wl.dst), wl.num_nodes, 4, 64)
