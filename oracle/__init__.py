@@ -22,8 +22,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "gnn_oracle.c")
 _LIB = os.path.join(_HERE, "libgnn_oracle.so")
 
-MSG_COPY_XJ, MSG_E_MUL_XJ = 0, 1
-AGGR_SUM, AGGR_MEAN, AGGR_MAX = 0, 1, 2
+MSG_COPY_XJ, MSG_E_MUL_XJ, MSG_XJ_SUB_XI, MSG_XI_DOT_XJ = 0, 1, 2, 3
+AGGR_SUM, AGGR_MEAN, AGGR_MAX, AGGR_MIN, AGGR_PROD = 0, 1, 2, 3, 4
 
 _lib = None
 
@@ -99,16 +99,19 @@ def _edge_data(e, num_edges, feat):
     return e, int(e.shape[1])
 
 
-def apply_edges(src, num_nodes: int, x, e=None, msg: int = MSG_COPY_XJ) -> np.ndarray:
+def apply_edges(src, num_nodes: int, x, e=None, msg: int = MSG_COPY_XJ, dst=None, with_sabs: bool = False):
+    """[E, F] message rows; for MSG_XI_DOT_XJ one scalar per edge, [E, 1] (with_sabs applies to it only)."""
     src, x = _i32(src, "src"), _f32(x, "x")
+    dst = None if dst is None else _i32(dst, "dst")
     ne, f = src.shape[0], x.shape[1]
     e, e_dim = _edge_data(e, ne, f)
-    m = np.empty((ne, f), np.float32)
-    rc = _load().oracle_apply_edges(_p(src), ctypes.c_int64(ne), ctypes.c_int32(num_nodes), _p(x),
+    m = np.empty((ne, 1 if msg == MSG_XI_DOT_XJ else f), np.float32)
+    sabs = np.empty((ne, 1), np.float64) if (with_sabs and msg == MSG_XI_DOT_XJ) else None
+    rc = _load().oracle_apply_edges(_p(src), _p(dst), ctypes.c_int64(ne), ctypes.c_int32(num_nodes), _p(x),
                                     ctypes.c_int32(f), _p(e), ctypes.c_int32(e_dim),
-                                    ctypes.c_int32(msg), _p(m))
+                                    ctypes.c_int32(msg), _p(m), _p(sabs))
     _check(rc, "apply_edges")
-    return m
+    return (m, sabs) if with_sabs else m
 
 
 def aggregate_neighbors(dst, num_nodes: int, m, aggr: int = AGGR_SUM, with_sabs: bool = False):

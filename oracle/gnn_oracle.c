@@ -35,8 +35,8 @@
 #include <stdlib.h>
 #include <string.h>
 
-enum { MSG_COPY_XJ = 0, MSG_E_MUL_XJ = 1 };
-enum { AGGR_SUM = 0, AGGR_MEAN = 1, AGGR_MAX = 2 };
+enum { MSG_COPY_XJ = 0, MSG_E_MUL_XJ = 1, MSG_XJ_SUB_XI = 2, MSG_XI_DOT_XJ = 3 };
+enum { AGGR_SUM = 0, AGGR_MEAN = 1, AGGR_MAX = 2, AGGR_MIN = 3, AGGR_PROD = 4 };
 
 static int check_edges(const int32_t *src, const int32_t *dst, int64_t E, int32_t N)
 {
@@ -56,6 +56,19 @@ static float max_f32(float a, float b)
     memcpy(&ua, &a, 4);
     memcpy(&ub, &b, 4);
     ua &= ub;                       /* equal values: only the zero pair differs in encoding */
+    memcpy(&a, &ua, 4);
+    return a;
+}
+
+/* IEEE-754 "minimum" on finite floats: the smaller value; -0 is below +0. */
+static float min_f32(float a, float b)
+{
+    if (a < b) return a;
+    if (b < a) return b;
+    uint32_t ua, ub;
+    memcpy(&ua, &a, 4);
+    memcpy(&ub, &b, 4);
+    ua |= ub;
     memcpy(&a, &ua, 4);
     return a;
 }
@@ -95,23 +108,67 @@ int oracle_build_csr(const int32_t *src, const int32_t *dst, int64_t E, int32_t 
 }
 
 /*
- * apply_edges: one message row per edge.
- *   copy_xj : m[k,f] = x[src[k], f]
- *   e_mul_xj: m[k,f] = float(e[k, f or 0] * x[src[k], f])   (e_dim = F or 1)
+ * The message of edge k = (j -> i) at feature f, from the target's features x_i, the source's
+ * features x_j and the edge's own data (section 3, "Message Passing": the message function takes
+ * xi, xj and e):
+ *   copy_xj  : x[j,f]
+ *   e_mul_xj : float(e[k, f or 0] * x[j,f])       (e_dim = F or 1)
+ *   xj_sub_xi: float(x[j,f] - x[i,f])
  */
-int oracle_apply_edges(const int32_t *src, int64_t E, int32_t N, const float *x, int32_t F,
-                       const float *e, int32_t e_dim, int32_t msg, float *m)
+static float message_value(int32_t msg, const float *x, int32_t F, int64_t i, int64_t j, const float *e,
+                           int32_t e_dim, int64_t k, int32_t f)
+{
+    float v = x[j * F + f];
+    if (msg == MSG_E_MUL_XJ) v = mul_f32(e[k * e_dim + (e_dim == 1 ? 0 : f)], v);
+    if (msg == MSG_XJ_SUB_XI) { volatile float d = v - x[i * F + f]; v = d; }
+    return v;
+}
+
+/* One step of a neighbourhood reduction: message v joins element q of a row that held cnt messages. */
+static void reduce_step(int32_t aggr, double *acc, double *sa, int64_t q, int64_t cnt, float v)
+{
+    if (aggr == AGGR_MAX) {
+        acc[q] = (cnt == 0) ? (double)v : (double)max_f32((float)acc[q], v);
+        sa[q] = fabs(acc[q]);
+    } else if (aggr == AGGR_MIN) {
+        acc[q] = (cnt == 0) ? (double)v : (double)min_f32((float)acc[q], v);
+        sa[q] = fabs(acc[q]);
+    } else if (aggr == AGGR_PROD) {
+        acc[q] = (cnt == 0) ? (double)v : acc[q] * (double)v;
+        sa[q] = fabs(acc[q]) * (double)(cnt + 1);   /* one rounding per factor in any float evaluation */
+    } else {
+        acc[q] += (double)v;
+        sa[q] += fabs((double)v);
+    }
+}
+
+/*
+ * apply_edges: one message row per edge, [E x F]; for xi_dot_xj one scalar per edge, [E x 1]:
+ *   xi_dot_xj: m[k] = float(sum_f x[i,f] x[j,f]).
+ * dst may be NULL for the messages that do not use the target.  sabs (may be NULL) is filled for
+ * xi_dot_xj only (sum of |x_i x_j|).
+ */
+int oracle_apply_edges(const int32_t *src, const int32_t *dst, int64_t E, int32_t N, const float *x, int32_t F,
+                       const float *e, int32_t e_dim, int32_t msg, float *m, double *sabs)
 {
     if (N <= 0 || E < 0 || F <= 0) return 2;
-    if (msg != MSG_COPY_XJ && msg != MSG_E_MUL_XJ) return 2;
+    if (msg < MSG_COPY_XJ || msg > MSG_XI_DOT_XJ) return 2;
     if (msg == MSG_E_MUL_XJ && e_dim != 1 && e_dim != F) return 2;
-    if (check_edges(src, NULL, E, N)) return 1;
+    if ((msg == MSG_XJ_SUB_XI || msg == MSG_XI_DOT_XJ) && !dst && E > 0) return 2;
+    if (check_edges(src, dst, E, N)) return 1;
     for (int64_t k = 0; k < E; ++k) {
-        const float *xj = x + (int64_t)src[k] * F;
-        for (int32_t f = 0; f < F; ++f) {
-            float v = xj[f];
-            if (msg == MSG_E_MUL_XJ) v = mul_f32(e[k * e_dim + (e_dim == 1 ? 0 : f)], v);
-            m[k * F + f] = v;
+        int64_t j = src[k], i = dst ? dst[k] : 0;
+        if (msg == MSG_XI_DOT_XJ) {
+            double d = 0.0, a = 0.0;
+            for (int32_t f = 0; f < F; ++f) {
+                double t = (double)x[i * F + f] * (double)x[j * F + f];
+                d += t;
+                a += fabs(t);
+            }
+            m[k] = (float)d;
+            if (sabs) sabs[k] = a;
+        } else {
+            for (int32_t f = 0; f < F; ++f) m[k * F + f] = message_value(msg, x, F, i, j, e, e_dim, k, f);
         }
     }
     return 0;
@@ -135,14 +192,15 @@ static void finish_rows(int32_t N, int32_t F, int32_t aggr, const double *acc, c
 }
 
 /*
- * aggregate_neighbors: reduce the message rows m[E x F] onto their destinations.
- * mean divides by the number of incoming edges (not by any sum of weights).
+ * aggregate_neighbors: reduce the message rows m[E x F] onto their destinations with
+ * sum, mean, max, min or prod.  mean divides by the number of incoming edges (not by any sum of
+ * weights); a node without incoming edges gets 0 under every reduction.
  */
 int oracle_aggregate_neighbors(const int32_t *dst, int64_t E, int32_t N, const float *m, int32_t F,
                                int32_t aggr, float *out, double *sabs)
 {
     if (N <= 0 || E < 0 || F <= 0) return 2;
-    if (aggr < AGGR_SUM || aggr > AGGR_MAX) return 2;
+    if (aggr < AGGR_SUM || aggr > AGGR_PROD) return 2;
     if (check_edges(NULL, dst, E, N)) return 1;
     size_t nf = (size_t)N * F;
     double *acc = (double *)calloc(nf, sizeof(double));
@@ -151,17 +209,7 @@ int oracle_aggregate_neighbors(const int32_t *dst, int64_t E, int32_t N, const f
     if (!acc || !sa || !cnt) { free(acc); free(sa); free(cnt); return 3; }
     for (int64_t k = 0; k < E; ++k) {
         int64_t i = dst[k];
-        for (int32_t f = 0; f < F; ++f) {
-            float v = m[k * F + f];
-            int64_t q = i * F + f;
-            if (aggr == AGGR_MAX) {
-                acc[q] = (cnt[i] == 0) ? (double)v : (double)max_f32((float)acc[q], v);
-                sa[q] = fabs(acc[q]);
-            } else {
-                acc[q] += (double)v;
-                sa[q] += fabs((double)v);
-            }
-        }
+        for (int32_t f = 0; f < F; ++f) reduce_step(aggr, acc, sa, i * F + f, cnt[i], m[k * F + f]);
         cnt[i]++;
     }
     finish_rows(N, F, aggr, acc, cnt, sa, out, sabs);
@@ -171,15 +219,16 @@ int oracle_aggregate_neighbors(const int32_t *dst, int64_t E, int32_t N, const f
 
 /*
  * propagate = apply_edges then aggregate_neighbors, without storing the
- * [E x F] messages (same values, same order of edges).
+ * [E x F] messages (same values, same order of edges).  xi_dot_xj (a message of another width)
+ * is not a propagate message.
  */
 int oracle_propagate(const int32_t *src, const int32_t *dst, int64_t E, int32_t N,
                      const float *x, int32_t F, const float *e, int32_t e_dim,
                      int32_t msg, int32_t aggr, float *out, double *sabs)
 {
     if (N <= 0 || E < 0 || F <= 0) return 2;
-    if (msg != MSG_COPY_XJ && msg != MSG_E_MUL_XJ) return 2;
-    if (aggr < AGGR_SUM || aggr > AGGR_MAX) return 2;
+    if (msg < MSG_COPY_XJ || msg > MSG_XJ_SUB_XI) return 2;
+    if (aggr < AGGR_SUM || aggr > AGGR_PROD) return 2;
     if (msg == MSG_E_MUL_XJ && e_dim != 1 && e_dim != F) return 2;
     if (check_edges(src, dst, E, N)) return 1;
     size_t nf = (size_t)N * F;
@@ -188,20 +237,9 @@ int oracle_propagate(const int32_t *src, const int32_t *dst, int64_t E, int32_t 
     int64_t *cnt = (int64_t *)calloc((size_t)N, sizeof(int64_t));
     if (!acc || !sa || !cnt) { free(acc); free(sa); free(cnt); return 3; }
     for (int64_t k = 0; k < E; ++k) {
-        int64_t i = dst[k];
-        const float *xj = x + (int64_t)src[k] * F;
-        for (int32_t f = 0; f < F; ++f) {
-            float v = xj[f];
-            if (msg == MSG_E_MUL_XJ) v = mul_f32(e[k * e_dim + (e_dim == 1 ? 0 : f)], v);
-            int64_t q = i * F + f;
-            if (aggr == AGGR_MAX) {
-                acc[q] = (cnt[i] == 0) ? (double)v : (double)max_f32((float)acc[q], v);
-                sa[q] = fabs(acc[q]);
-            } else {
-                acc[q] += (double)v;
-                sa[q] += fabs((double)v);
-            }
-        }
+        int64_t i = dst[k], j = src[k];
+        for (int32_t f = 0; f < F; ++f)
+            reduce_step(aggr, acc, sa, i * F + f, cnt[i], message_value(msg, x, F, i, j, e, e_dim, k, f));
         cnt[i]++;
     }
     finish_rows(N, F, aggr, acc, cnt, sa, out, sabs);

@@ -8,7 +8,8 @@ import numpy as np
 import pytest
 
 import oracle
-from oracle import (AGGR_MAX, AGGR_MEAN, AGGR_SUM, MSG_COPY_XJ, MSG_E_MUL_XJ)
+from oracle import (AGGR_MAX, AGGR_MEAN, AGGR_MIN, AGGR_PROD, AGGR_SUM, MSG_COPY_XJ, MSG_E_MUL_XJ, MSG_XI_DOT_XJ,
+                    MSG_XJ_SUB_XI)
 from paper_2412_06354_amd import synth
 from util import dense_adjacency, incoming, load_golden
 
@@ -571,6 +572,61 @@ def test_gat_backward_zero_attention_is_mean_backward():
     np.testing.assert_allclose(res["grad_x"], ref, rtol=0, atol=3e-6 * np.abs(ref).max())
     ref_w = wl.x.astype(np.float64).T @ dh.astype(np.float64)
     np.testing.assert_allclose(res["grad_w"], ref_w, rtol=0, atol=3e-6 * np.abs(ref_w).max())
+
+
+@pytest.mark.parametrize("seed,n,e,f", [(71, 40, 400, 5), (72, 12, 15, 3)])
+def test_min_prod_and_target_messages_brute_force(seed, n, e, f):
+    """min / prod reductions and the two messages that read the target node, against per-destination
+    numpy loops written from the definitions; plus what they must reduce to: min(x) = -max(-x),
+    sum of (x_j - x_i) = sum of x_j - indegree * x_i, and xi_dot_xj on a single feature = the product."""
+    src, dst = rng_graph(seed, n, e, star=True)
+    ne = src.shape[0]
+    x = synth.uniform_f32(seed, 2, n * f, 0.5, 1.5).reshape(n, f)
+    x[::3] *= -1.0
+    w = synth.uniform_f32(seed, 3, ne, -1.0, 1.0)
+    inc = incoming(dst, n)
+    # messages
+    sub = oracle.apply_edges(src, n, x, None, MSG_XJ_SUB_XI, dst=dst)
+    np.testing.assert_array_equal(sub, x[src] - x[dst])
+    dot, dot_abs = oracle.apply_edges(src, n, x, None, MSG_XI_DOT_XJ, dst=dst, with_sabs=True)
+    ref_dot = (x[src].astype(np.float64) * x[dst].astype(np.float64)).sum(1, keepdims=True)
+    assert dot.shape == (ne, 1)
+    np.testing.assert_allclose(dot, ref_dot, rtol=0, atol=1e-7 * dot_abs.max())
+    one = oracle.apply_edges(src, n, x[:, :1].copy(), None, MSG_XI_DOT_XJ, dst=dst)
+    np.testing.assert_array_equal(one[:, 0], x[src, 0] * x[dst, 0])
+    # reductions of a materialised message tensor and of the fused form
+    for msg, edata, msgs in ((MSG_COPY_XJ, None, x[src]), (MSG_E_MUL_XJ, w, w[:, None] * x[src]),
+                             (MSG_XJ_SUB_XI, None, x[src] - x[dst])):
+        ref_min, ref_prod = np.zeros((n, f)), np.zeros((n, f))
+        for i in range(n):
+            if inc[i].size:
+                ref_min[i] = msgs[inc[i]].min(0)
+                ref_prod[i] = np.prod(msgs[inc[i]].astype(np.float64), axis=0)
+        got_min = oracle.propagate(src, dst, n, x, edata, msg, AGGR_MIN)
+        np.testing.assert_array_equal(got_min, ref_min.astype(np.float32))
+        got_prod, sabs = oracle.propagate(src, dst, n, x, edata, msg, AGGR_PROD, with_sabs=True)
+        np.testing.assert_allclose(got_prod, ref_prod, rtol=1e-6, atol=1e-300)
+        assert (sabs >= np.abs(ref_prod) * (1 - 1e-12)).all()
+        two_step = oracle.aggregate_neighbors(dst, n, msgs.astype(np.float32), AGGR_MIN)
+        np.testing.assert_array_equal(two_step, got_min)
+        neg_max = oracle.aggregate_neighbors(dst, n, (-msgs).astype(np.float32), AGGR_MAX)
+        np.testing.assert_array_equal(got_min, -neg_max)
+    s_sub = oracle.propagate(src, dst, n, x, None, MSG_XJ_SUB_XI, AGGR_SUM).astype(np.float64)
+    s_cp = oracle.propagate(src, dst, n, x, None, MSG_COPY_XJ, AGGR_SUM).astype(np.float64)
+    deg = np.bincount(dst, minlength=n)[:, None]
+    np.testing.assert_allclose(s_sub, s_cp - deg * x, rtol=0, atol=2e-5)
+
+
+def test_min_of_signed_zeros_is_minus_zero():
+    src = np.array([1, 2, 2, 1], np.int32)
+    dst = np.array([0, 0, 3, 3], np.int32)
+    x = np.array([[0.0], [-0.0], [0.0], [0.0]], np.float32)
+    out = oracle.propagate(src, dst, 4, x, None, MSG_COPY_XJ, AGGR_MIN)
+    assert np.signbit(out[0, 0]) and np.signbit(out[3, 0])       # {-0, +0} in either order
+    assert out[1, 0] == 0 and not np.signbit(out[1, 0])           # empty neighbourhood: +0
+    prod = oracle.propagate(src, dst, 4, np.array([[3.0], [2.0], [-4.0], [1.0]], np.float32), None, MSG_COPY_XJ,
+                            AGGR_PROD)
+    np.testing.assert_array_equal(prod[:, 0], [-8.0, 0.0, 0.0, -8.0])
 
 
 def test_error_codes():
