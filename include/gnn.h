@@ -50,8 +50,16 @@ typedef enum {
     GNN_ERR_NOT_SORTED = 7   /* graph_indicator is not non-decreasing */
 } gnn_status;
 
-typedef enum { GNN_MSG_COPY_XJ = 0, GNN_MSG_E_MUL_XJ = 1 } gnn_msg_op;
-typedef enum { GNN_AGGR_SUM = 0, GNN_AGGR_MEAN = 1, GNN_AGGR_MAX = 2 } gnn_aggr;
+/*
+ * Message of edge k = (j -> i) built from the target's features x_i, the source's features x_j and the
+ * edge's data e (paper section 3, "Message Passing": the message function takes xi, xj, e):
+ *   COPY_XJ   m = x_j                       E_MUL_XJ  m = e * x_j (e_dim = 1 broadcasts, e_dim = F element-wise)
+ *   XJ_SUB_XI m = x_j - x_i                 XI_DOT_XJ m = <x_i, x_j>, one scalar per edge (gnn_apply_edges only)
+ * Reductions over a node's incoming edges; a node without incoming edges gets 0 under every one of
+ * them; MIN puts -0 below +0 as MAX puts +0 above -0; PROD multiplies in a fixed order.
+ */
+typedef enum { GNN_MSG_COPY_XJ = 0, GNN_MSG_E_MUL_XJ = 1, GNN_MSG_XJ_SUB_XI = 2, GNN_MSG_XI_DOT_XJ = 3 } gnn_msg_op;
+typedef enum { GNN_AGGR_SUM = 0, GNN_AGGR_MEAN = 1, GNN_AGGR_MAX = 2, GNN_AGGR_MIN = 3, GNN_AGGR_PROD = 4 } gnn_aggr;
 typedef enum { GNN_EDGE_ORDER_COO = 0, GNN_EDGE_ORDER_CSR = 1 } gnn_edge_order;
 
 const char *gnn_status_string(gnn_status s);
@@ -111,11 +119,11 @@ gnn_status gnn_edge_data_to_csr(const gnn_graph *g, const float *d_e, int32_t e_
 
 /*
  * propagate (paper section 3, "Message Passing"): for every node i
- *   out[i,:] = AGGR over edges k with dst[k] = i of  msg(x[src[k],:], e[k,:])
+ *   out[i,:] = AGGR over edges k with dst[k] = i of  msg(x[dst[k],:], x[src[k],:], e[k,:])
  * msg  = COPY_XJ: x_j;   E_MUL_XJ: float(e * x_j) with e_dim == 1 (one weight per edge,
- *        broadcast over features) or e_dim == feat_dim (element-wise).
+ *        broadcast over features) or e_dim == feat_dim (element-wise);   XJ_SUB_XI: float(x_j - x_i).
  * aggr = SUM, MEAN (divides by the number of incoming edges, not by a weight sum), MAX
- *        (the larger value; +0 beats -0).  No incoming edge -> 0.
+ *        (the larger value; +0 beats -0), MIN (the smaller; -0 below +0), PROD.  No incoming edge -> 0.
  * d_x [N x feat_dim], d_out [N x feat_dim]; d_e [E x e_dim] in the order e_order names
  * (COO = the order the edges were given in, CSR = after gnn_edge_data_to_csr), NULL for COPY_XJ.
  * Any feat_dim > 0 is accepted; 16-byte aligned pointers with feat_dim % 4 == 0 take the
@@ -130,12 +138,13 @@ gnn_status gnn_propagate(const gnn_graph *g, const float *d_x, int32_t feat_dim,
 /*
  * The two un-fused primitives of the paper's listing (section 3, "Message Passing"):
  *
- * apply_edges: one message row per edge,  m[k,:] = msg(x[src[k],:], e[k,:])  with the message
- * ops of gnn_propagate.  d_m is [E x feat_dim], written in the order m_order names (COO = the
+ * apply_edges: one message row per edge,  m[k,:] = msg(x[dst[k],:], x[src[k],:], e[k,:])  with the
+ * message ops of gnn_propagate, plus XI_DOT_XJ (one scalar per edge: d_m is then [E x 1]).
+ * d_m is [E x feat_dim], written in the order m_order names (COO = the
  * order the edges were given in, CSR = by destination, stable); d_e is read in e_order.
  *
  * aggregate_neighbors: reduces message rows onto their destinations,
- *   out[i,:] = AGGR over edges k with dst[k] = i of m[k,:]      (sum, mean over the edge count, max)
+ *   out[i,:] = AGGR over edges k with dst[k] = i of m[k,:]      (sum, mean over the edge count, max, min, prod)
  * with d_m [E x feat_dim] stored in m_order.  gnn_propagate gives the same result as the two
  * calls in a row without ever storing the messages.
  */
@@ -167,6 +176,8 @@ gnn_status gnn_propagate_argmax(const gnn_graph *g, const float *d_x, int32_t fe
  * d_e is in the caller's edge order (both graphs share it through their perm arrays).
  * Either output may be NULL.  d_workspace: gnn_propagate_backward_workspace_bytes() bytes of device
  * scratch, 16-byte aligned (0 bytes unless MEAN).
+ * Only COPY_XJ / E_MUL_XJ with SUM / MEAN / MAX are differentiated here; XJ_SUB_XI, MIN and PROD
+ * return GNN_ERR_UNSUPPORTED.
  */
 size_t gnn_propagate_backward_workspace_bytes(int32_t num_nodes, int32_t feat_dim, gnn_aggr aggr);
 gnn_status gnn_propagate_backward(const gnn_graph *g, const gnn_graph *g_by_source, const float *d_x,
@@ -251,7 +262,7 @@ gnn_status gnn_gatconv(const gnn_graph *g, const float *d_x, int32_t f_in, const
  * ReLU at exactly 0 is negative_slope (the branch the forward takes).  No atomics: results are
  * bitwise reproducible.
  * Restriction: ch (or ch / 4 when ch is a multiple of 4) must be a power of two, at most 64 lanes per
- * head; otherwise GNN_ERR_BAD_SIZE.
+ * head; otherwise GNN_ERR_UNSUPPORTED.
  * d_workspace: at least gnn_gatconv_backward_workspace_bytes(N, f_in, heads, ch) bytes, 256-byte aligned.
  */
 size_t gnn_gatconv_backward_workspace_bytes(int32_t num_nodes, int32_t f_in, int32_t heads, int32_t ch);

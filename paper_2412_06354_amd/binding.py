@@ -16,8 +16,8 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libgnn_mi355x.so")
 
-MSG_COPY_XJ, MSG_E_MUL_XJ = 0, 1
-AGGR_SUM, AGGR_MEAN, AGGR_MAX = 0, 1, 2
+MSG_COPY_XJ, MSG_E_MUL_XJ, MSG_XJ_SUB_XI, MSG_XI_DOT_XJ = 0, 1, 2, 3
+AGGR_SUM, AGGR_MEAN, AGGR_MAX, AGGR_MIN, AGGR_PROD = 0, 1, 2, 3, 4
 EDGE_ORDER_COO, EDGE_ORDER_CSR = 0, 1
 
 _c = ctypes
@@ -219,7 +219,7 @@ def apply_edges(g: Graph, x: torch.Tensor, e: Optional[torch.Tensor] = None, msg
         e = e.reshape(g.num_edges, -1)
         e_dim = int(e.shape[1])
     if out is None:
-        out = torch.empty((g.num_edges, f), dtype=torch.float32, device=x.device)
+        out = torch.empty((g.num_edges, 1 if msg == MSG_XI_DOT_XJ else f), dtype=torch.float32, device=x.device)
     rc = lib().gnn_apply_edges(g._h, _dev(x, torch.float32, "x"), f, _dev(e, torch.float32, "e"), e_dim, e_order, msg,
                                _dev(out, torch.float32, "out"), m_order, _stream())
     _check(rc, "gnn_apply_edges")

@@ -70,7 +70,7 @@ __global__ __launch_bounds__(kThreads) void edge_gradient_kernel(const int32_t *
         const int64_t q = q0 + lane;
         const bool have = q < E;
         const int64_t qc = have ? q : E - 1;   // clamped: loads stay in bounds, results are dropped
-        const int i_own = rowidx[qc], j_own = colidx[qc], k_own = perm[qc];
+        const int i_own = rowidx[qc], j_own = colidx[qc], k_own = perm ? perm[qc] : (int)qc;   // no perm: CSR-ordered output
         const int64_t group_q0 = q0 + (lane - sl);
         float mine = 0.0f;
         for (int cb = 0; cb * LPR * VEC < F; ++cb) {
@@ -137,12 +137,13 @@ __global__ __launch_bounds__(kThreads) void edge_gradient_kernel(const int32_t *
 
 template <int LPR, int VEC>
 gnn_status launch_edge_gradient(const gnn_graph *g, int F, bool evec, const float *x, const float *gp,
-                                const int32_t *winners, float *grad_e, hipStream_t s)
+                                const int32_t *winners, float *grad_e, hipStream_t s, bool csr_out = false)
 {
+    const int32_t *perm = csr_out ? nullptr : g->perm;
     const int64_t blocks = std::min<int64_t>(gnn_div_up(g->num_edges, kThreads), 256 * 16);
 #define GNN_EDGE_GRADIENT(EV, WN)                                                                                   \
     hipLaunchKernelGGL((edge_gradient_kernel<LPR, VEC, EV, WN>), dim3((unsigned)blocks), dim3(kThreads), 0, s, g->rowidx, \
-                       g->colidx, g->perm, g->num_edges, F, x, gp, winners, grad_e)
+                       g->colidx, perm, g->num_edges, F, x, gp, winners, grad_e)
     if (evec) {
         if (winners) GNN_EDGE_GRADIENT(true, true);
         else GNN_EDGE_GRADIENT(true, false);
@@ -200,7 +201,32 @@ __global__ __launch_bounds__(kThreads) void positions_to_edge_ids_kernel(const i
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// Per edge (j -> i): <x[j,:], y[i,:]> (or the element-wise product when evec), in the caller's edge
+// order or in CSR order.
+gnn_status edge_products(const gnn_graph *g, int F, bool evec, const float *x, const float *y, const int32_t *winners,
+                         float *out, hipStream_t s, bool csr_out)
+{
+    const bool vec4 = (F % 4 == 0) && aligned16(x) && aligned16(y) && (!evec || aligned16(out)) && aligned16(winners);
+    if (vec4) {
+        const int cols = F / 4;
+        if (cols <= 4) return launch_edge_gradient<4, 4>(g, F, evec, x, y, winners, out, s, csr_out);
+        if (cols <= 8) return launch_edge_gradient<8, 4>(g, F, evec, x, y, winners, out, s, csr_out);
+        if (cols <= 16) return launch_edge_gradient<16, 4>(g, F, evec, x, y, winners, out, s, csr_out);
+        return launch_edge_gradient<32, 4>(g, F, evec, x, y, winners, out, s, csr_out);
+    }
+    if (F <= 16) return launch_edge_gradient<16, 1>(g, F, evec, x, y, winners, out, s, csr_out);
+    return launch_edge_gradient<64, 1>(g, F, evec, x, y, winners, out, s, csr_out);
+}
+
 }  // namespace
+
+gnn_status gnn_launch_edge_dot(const gnn_graph *g, const float *d_x_src, const float *d_y_dst, int32_t feat_dim,
+                               float *d_out, gnn_edge_order out_order, void *stream)
+{
+    if (g->num_edges == 0) return GNN_OK;
+    return edge_products(g, feat_dim, false, d_x_src, d_y_dst, nullptr, d_out, static_cast<hipStream_t>(stream),
+                         out_order == GNN_EDGE_ORDER_CSR);
+}
 
 extern "C" {
 
@@ -216,6 +242,7 @@ gnn_status gnn_propagate_argmax(const gnn_graph *g, const float *d_x, int32_t fe
 {
     if (!g || !d_argmax) return GNN_ERR_NULL;
     if (feat_dim <= 0) return GNN_ERR_BAD_SIZE;
+    if (msg == GNN_MSG_XJ_SUB_XI || msg == GNN_MSG_XI_DOT_XJ) return GNN_ERR_UNSUPPORTED;
     if (msg != GNN_MSG_COPY_XJ && msg != GNN_MSG_E_MUL_XJ) return GNN_ERR_BAD_SIZE;
     if (msg == GNN_MSG_E_MUL_XJ) {
         if (e_dim != 1 && e_dim != feat_dim) return GNN_ERR_BAD_SIZE;
@@ -256,6 +283,8 @@ gnn_status gnn_propagate_backward(const gnn_graph *g, const gnn_graph *g_by_sour
 {
     if (!g || !d_grad_out) return GNN_ERR_NULL;
     if (feat_dim <= 0) return GNN_ERR_BAD_SIZE;
+    if (msg == GNN_MSG_XJ_SUB_XI || msg == GNN_MSG_XI_DOT_XJ || aggr == GNN_AGGR_MIN || aggr == GNN_AGGR_PROD)
+        return GNN_ERR_UNSUPPORTED;
     if (msg != GNN_MSG_COPY_XJ && msg != GNN_MSG_E_MUL_XJ) return GNN_ERR_BAD_SIZE;
     if (aggr != GNN_AGGR_SUM && aggr != GNN_AGGR_MEAN && aggr != GNN_AGGR_MAX) return GNN_ERR_BAD_SIZE;
     if (aggr == GNN_AGGR_MAX && !d_argmax) return GNN_ERR_NULL;
@@ -291,18 +320,7 @@ gnn_status gnn_propagate_backward(const gnn_graph *g, const gnn_graph *g_by_sour
                                      GNN_GATHER_SOURCE_NODE, winners));
     }
     if (d_grad_e && msg == GNN_MSG_E_MUL_XJ && g->num_edges > 0) {
-        const bool evec = (e_dim != 1);
-        const bool vec4 = (F % 4 == 0) && aligned16(d_x) && aligned16(gp) && (!evec || aligned16(d_grad_e)) &&
-                          aligned16(winners);
-        if (vec4) {
-            const int cols = F / 4;
-            if (cols <= 4) return launch_edge_gradient<4, 4>(g, F, evec, d_x, gp, winners, d_grad_e, s);
-            if (cols <= 8) return launch_edge_gradient<8, 4>(g, F, evec, d_x, gp, winners, d_grad_e, s);
-            if (cols <= 16) return launch_edge_gradient<16, 4>(g, F, evec, d_x, gp, winners, d_grad_e, s);
-            return launch_edge_gradient<32, 4>(g, F, evec, d_x, gp, winners, d_grad_e, s);
-        }
-        if (F <= 16) return launch_edge_gradient<16, 1>(g, F, evec, d_x, gp, winners, d_grad_e, s);
-        return launch_edge_gradient<64, 1>(g, F, evec, d_x, gp, winners, d_grad_e, s);
+        return edge_products(g, F, e_dim != 1, d_x, gp, winners, d_grad_e, s, false);
     }
     return GNN_OK;
 }

@@ -466,7 +466,7 @@ gnn_status gnn_gatconv_backward(const gnn_graph *g, const gnn_graph *g_by_source
     const int HC = heads * ch;
     const bool vec4 = (ch % 4 == 0) && ((reinterpret_cast<uintptr_t>(d_grad_out) & 15u) == 0);
     const int lh = vec4 ? ch / 4 : ch;   // lanes that share a head
-    if (!is_pow2(lh) || lh > 64) return GNN_ERR_BAD_SIZE;
+    if (!is_pow2(lh) || lh > 64) return GNN_ERR_UNSUPPORTED;
     const Layout l = layout(N, f_in, heads, ch);
     if (workspace_bytes < l.total) return GNN_ERR_BAD_SIZE;
     if (reinterpret_cast<uintptr_t>(d_workspace) & 255u) return GNN_ERR_BAD_SIZE;

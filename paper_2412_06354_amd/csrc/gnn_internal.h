@@ -103,6 +103,9 @@ struct gnn_epilogue {
 // CSR order.
 enum gnn_gather_index { GNN_GATHER_SOURCE_NODE = 0, GNN_GATHER_EDGE_COO = 1, GNN_GATHER_EDGE_CSR = 2 };
 
+// How a row's messages are reduced (the mean is a sum with gnn_epilogue::mean set).
+enum gnn_reduce { GNN_REDUCE_SUM = 0, GNN_REDUCE_MAX = 1, GNN_REDUCE_MIN = 2, GNN_REDUCE_PROD = 3 };
+
 // d_winners (optional, sum only, edge data in the caller's order): [rows of x][feat_dim] edge ids; a
 // gathered element x[j,f] only contributes to the edge whose id equals d_winners[j,f] (the routing
 // step of a max aggregation's backward pass).
@@ -110,10 +113,14 @@ enum gnn_gather_index { GNN_GATHER_SOURCE_NODE = 0, GNN_GATHER_EDGE_COO = 1, GNN
 // of gnn_gcnconv.
 gnn_status gnn_launch_propagate(const gnn_graph *g, const float *d_x, int32_t feat_dim,
                                 const float *d_e, int32_t e_dim, gnn_edge_order e_order,
-                                gnn_msg_op msg, int use_max, const gnn_epilogue &epi,
+                                gnn_msg_op msg, int reduce, const gnn_epilogue &epi,
                                 float *d_out, hipStream_t stream,
                                 gnn_gather_index gather = GNN_GATHER_SOURCE_NODE,
                                 const int32_t *d_winners = nullptr);
+
+// out[k] = <x[src[k],:], y[dst[k],:]> per edge, in the order out_order names (backward.hip)
+gnn_status gnn_launch_edge_dot(const gnn_graph *g, const float *d_x_src, const float *d_y_dst, int32_t feat_dim,
+                               float *d_out, gnn_edge_order out_order, void *stream);
 
 // ---- dense helpers shared by the backward passes (gcn_backward.hip)
 // Number of row chunks the two-stage reductions over N rows use.

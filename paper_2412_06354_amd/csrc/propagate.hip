@@ -23,10 +23,15 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kWavesPerBlock = kThreads / 64;
 
-// Message kinds.  The "routed" kinds (+3) are used by the backward pass of a max aggregation: the
+// Message kinds.  kMsgSubTarget is x_j - x_i (the row's own features are loaded once per row).
+// The "routed" kinds (+4) are used by the backward pass of a max aggregation: the
 // gathered row is the upstream gradient of the edge's destination and a feature only contributes
 // if the recorded winner of that (destination, feature) is this very edge.
-enum { kMsgCopy = 0, kMsgMulScalar = 1, kMsgMulVector = 2, kMsgRouted = 3 };
+enum { kMsgCopy = 0, kMsgMulScalar = 1, kMsgMulVector = 2, kMsgSubTarget = 3, kMsgRouted = 4 };
+// Reductions.  min runs as max over negated messages, negated back at the end: negation is exact and
+// turns "+0 above -0" into "-0 below +0".
+enum { kRedSum = 0, kRedMax = 1, kRedProd = 2, kRedMin = 3 };
+constexpr bool red_is_max(int red) { return red == kRedMax || red == kRedMin; }
 constexpr int msg_base(int msg) { return msg % kMsgRouted; }
 constexpr bool msg_routed(int msg) { return msg >= kMsgRouted; }
 
@@ -106,24 +111,29 @@ __device__ __forceinline__ float max_pz(float a, float b)
     return __uint_as_float(__float_as_uint(a) & __float_as_uint(b));
 }
 
-template <int VEC, bool MAX>
+template <int VEC, int RED>
 __device__ __forceinline__ void set_identity(Row<VEC> &r)
 {
 #pragma unroll
-    for (int c = 0; c < VEC; ++c) r.v[c] = MAX ? -INFINITY : 0.0f;
+    for (int c = 0; c < VEC; ++c) r.v[c] = red_is_max(RED) ? -INFINITY : (RED == kRedProd ? 1.0f : 0.0f);
 }
 
-template <int VEC, bool MAX>
+template <int VEC, int RED>
 __device__ __forceinline__ void combine(Row<VEC> &acc, const Row<VEC> &m)
 {
 #pragma unroll
-    for (int c = 0; c < VEC; ++c) acc.v[c] = MAX ? max_pz(acc.v[c], m.v[c]) : acc.v[c] + m.v[c];
+    for (int c = 0; c < VEC; ++c)
+        acc.v[c] = red_is_max(RED) ? max_pz(acc.v[c], m.v[c]) : (RED == kRedProd ? acc.v[c] * m.v[c] : acc.v[c] + m.v[c]);
 }
 
 // Finishes one output row slice (VEC features starting at col) and stores it.
-template <int VEC, bool MAX>
+template <int VEC, int RED>
 __device__ __forceinline__ void finish_row(const PropParams &p, int row, int deg, int col, Row<VEC> acc)
 {
+    if constexpr (RED == kRedMin) {
+#pragma unroll
+        for (int c = 0; c < VEC; ++c) acc.v[c] = -acc.v[c];
+    }
     if (deg == 0) {
 #pragma unroll
         for (int c = 0; c < VEC; ++c) acc.v[c] = 0.0f;
@@ -168,24 +178,30 @@ __device__ __forceinline__ void fetch_message(const PropParams &p, bool ok, int 
     }
 }
 
-template <int VEC, int MSG, bool MAX>
+template <int VEC, int MSG, int RED>
 __device__ __forceinline__ void apply_message(Row<VEC> &acc, bool ok, const Row<VEC> &xv, float w, const Row<VEC> &ev,
-                                              const Row<VEC> &wv, int eid)
+                                              const Row<VEC> &wv, int eid, const Row<VEC> &xi)
 {
 #pragma unroll
     for (int c = 0; c < VEC; ++c) {
         float m = xv.v[c];
         if constexpr (msg_base(MSG) == kMsgMulScalar) m = w * m;
         if constexpr (msg_base(MSG) == kMsgMulVector) m = ev.v[c] * m;
+        if constexpr (msg_base(MSG) == kMsgSubTarget) m = m - xi.v[c];
         if constexpr (msg_routed(MSG)) m = (__float_as_int(wv.v[c]) == eid) ? m : 0.0f;
-        if constexpr (MAX)
+        if constexpr (RED == kRedMin) m = -m;
+        if constexpr (red_is_max(RED))
             acc.v[c] = ok ? max_pz(acc.v[c], m) : acc.v[c];
+        else if constexpr (RED == kRedProd)
+            acc.v[c] = ok ? acc.v[c] * m : acc.v[c];
+        else if constexpr (msg_base(MSG) == kMsgSubTarget)
+            acc.v[c] = acc.v[c] + (ok ? m : 0.0f);
         else
             acc.v[c] = acc.v[c] + m;   // masked-off edges carry x = 0
     }
 }
 
-template <int LPR, int VEC, int MSG, bool MAX>
+template <int LPR, int VEC, int MSG, int RED>
 __device__ __forceinline__ void short_rows(const PropParams &p, int block)
 {
     constexpr int NSG = 64 / LPR;
@@ -207,8 +223,11 @@ __device__ __forceinline__ void short_rows(const PropParams &p, int block)
     for (int cb = 0; cb * LPR * VEC < p.F; ++cb) {
         const int col = (cb * LPR + sl) * VEC;
         const bool colok = have && col < p.F;
-        Row<VEC> acc;
-        set_identity<VEC, MAX>(acc);
+        Row<VEC> acc, xi;
+        set_identity<VEC, RED>(acc);
+        set_identity<VEC, kRedSum>(xi);
+        if constexpr (msg_base(MSG) == kMsgSubTarget)
+            if (colok) load_row<VEC>(xi, p.x + (int64_t)row * p.F + col);
         for (int base = 0; base < wmax; base += LPR) {
             int my_j = 0, my_eid = 0;
             float my_w = 0.0f;
@@ -239,14 +258,14 @@ __device__ __forceinline__ void short_rows(const PropParams &p, int block)
                 }
 #pragma unroll
                 for (int u = 0; u < U; ++u)
-                    apply_message<VEC, MSG, MAX>(acc, ok[u], xv[u], w[u], ev[u], wv[u], eid[u]);
+                    apply_message<VEC, MSG, RED>(acc, ok[u], xv[u], w[u], ev[u], wv[u], eid[u], xi);
             }
         }
-        if (colok) finish_row<VEC, MAX>(p, row, deg, col, acc);
+        if (colok) finish_row<VEC, RED>(p, row, deg, col, acc);
     }
 }
 
-template <int LPR, int VEC, int MSG, bool MAX>
+template <int LPR, int VEC, int MSG, int RED>
 __device__ __forceinline__ void long_row_pieces(const PropParams &p, int block)
 {
     constexpr int NSG = 64 / LPR;
@@ -264,8 +283,11 @@ __device__ __forceinline__ void long_row_pieces(const PropParams &p, int block)
     for (int cb = 0; cb * LPR * VEC < p.F; ++cb) {
         const int col = (cb * LPR + sl) * VEC;
         const bool colok = col < p.F;
-        Row<VEC> acc;
-        set_identity<VEC, MAX>(acc);
+        Row<VEC> acc, xi;
+        set_identity<VEC, RED>(acc);
+        set_identity<VEC, kRedSum>(xi);
+        if constexpr (msg_base(MSG) == kMsgSubTarget)
+            if (colok) load_row<VEC>(xi, p.x + (int64_t)row * p.F + col);
         for (int base = start; base < end; base += 64) {
             const int n = min(64, end - base);
             int my_j = 0, my_eid = 0;
@@ -297,7 +319,7 @@ __device__ __forceinline__ void long_row_pieces(const PropParams &p, int block)
                 }
 #pragma unroll
                 for (int u = 0; u < U; ++u)
-                    apply_message<VEC, MSG, MAX>(acc, ok[u], xv[u], w[u], ev[u], wv[u], eid[u]);
+                    apply_message<VEC, MSG, RED>(acc, ok[u], xv[u], w[u], ev[u], wv[u], eid[u], xi);
             }
         }
 #pragma unroll
@@ -305,11 +327,11 @@ __device__ __forceinline__ void long_row_pieces(const PropParams &p, int block)
             Row<VEC> other;
 #pragma unroll
             for (int c = 0; c < VEC; ++c) other.v[c] = __shfl_xor(acc.v[c], off, 64);
-            combine<VEC, MAX>(acc, other);
+            combine<VEC, RED>(acc, other);
         }
         if (sg == 0 && colok) {
             if (slot < 0)
-                finish_row<VEC, MAX>(p, row, row_end - row_start, col, acc);
+                finish_row<VEC, RED>(p, row, row_end - row_start, col, acc);
             else
                 store_row<VEC>(p.scratch + (int64_t)slot * p.F + col, acc);
         }
@@ -318,19 +340,19 @@ __device__ __forceinline__ void long_row_pieces(const PropParams &p, int block)
 
 // Blocks [0, item_blocks) take the long-row pieces (scheduled first: they are the heaviest),
 // the remaining blocks take the short rows.
-template <int LPR, int VEC, int MSG, bool MAX>
+template <int LPR, int VEC, int MSG, int RED>
 __global__ __launch_bounds__(kThreads) void propagate_kernel(const PropParams p)
 {
     if ((int)blockIdx.x < p.item_blocks)
-        long_row_pieces<LPR, VEC, MSG, MAX>(p, blockIdx.x);
+        long_row_pieces<LPR, VEC, MSG, RED>(p, blockIdx.x);
     else
-        short_rows<LPR, VEC, MSG, MAX>(p, blockIdx.x - p.item_blocks);
+        short_rows<LPR, VEC, MSG, RED>(p, blockIdx.x - p.item_blocks);
 }
 
 // Combines the per-piece partial rows of split rows: one wavefront per split row, its sub-groups
 // take the pieces round-robin (four loads in flight each) and are folded with xor-shuffles; the
 // order of combination is a fixed function of the piece count.
-template <int LPR, int VEC, bool MAX>
+template <int LPR, int VEC, int RED>
 __global__ __launch_bounds__(kThreads) void combine_pieces_kernel(const PropParams p)
 {
     constexpr int NSG = 64 / LPR;
@@ -347,33 +369,34 @@ __global__ __launch_bounds__(kThreads) void combine_pieces_kernel(const PropPara
         const int col = (cb * LPR + sl) * VEC;
         const bool colok = col < p.F;
         Row<VEC> acc;
-        set_identity<VEC, MAX>(acc);
+        set_identity<VEC, RED>(acc);
         for (int c0 = sg; c0 < pieces; c0 += NSG * U) {
             Row<VEC> part[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int c = c0 + u * NSG;
-                set_identity<VEC, MAX>(part[u]);
+                set_identity<VEC, RED>(part[u]);
                 if (colok && c < pieces) load_row<VEC>(part[u], p.scratch + (int64_t)(slot0 + c) * p.F + col);
             }
 #pragma unroll
-            for (int u = 0; u < U; ++u) combine<VEC, MAX>(acc, part[u]);
+            for (int u = 0; u < U; ++u) combine<VEC, RED>(acc, part[u]);
         }
 #pragma unroll
         for (int off = LPR; off < 64; off <<= 1) {
             Row<VEC> other;
 #pragma unroll
             for (int c = 0; c < VEC; ++c) other.v[c] = __shfl_xor(acc.v[c], off, 64);
-            combine<VEC, MAX>(acc, other);
+            combine<VEC, RED>(acc, other);
         }
-        if (sg == 0 && colok) finish_row<VEC, MAX>(p, row, deg, col, acc);
+        if (sg == 0 && colok) finish_row<VEC, RED>(p, row, deg, col, acc);
     }
 }
 
-// apply_edges: one message row per edge, m[k,:] = msg(x[src[k],:], e[k,:]), written in the caller's edge
+// apply_edges: one message row per edge, m[k,:] = msg(x[dst[k],:], x[src[k],:], e[k,:]), written in the caller's edge
 // order or in CSR order.  One thread per (CSR position, VEC features).
 template <int VEC, int MSG>
 __global__ __launch_bounds__(kThreads) void apply_edges_kernel(const int32_t *__restrict__ colidx,
+                                                               const int32_t *__restrict__ rowidx,
                                                                const int32_t *__restrict__ perm, int64_t E, int F,
                                                                const float *__restrict__ x,
                                                                const float *__restrict__ e, int e_coo, int m_coo,
@@ -398,25 +421,30 @@ __global__ __launch_bounds__(kThreads) void apply_edges_kernel(const int32_t *__
             load_row_stream<VEC>(ev, e + (e_coo ? eid : q) * F + col);
 #pragma unroll
             for (int c = 0; c < VEC; ++c) v.v[c] = ev.v[c] * v.v[c];
+        } else if constexpr (MSG == kMsgSubTarget) {
+            Row<VEC> xi;
+            load_row<VEC>(xi, x + (int64_t)load_stream(rowidx + q) * F + col);
+#pragma unroll
+            for (int c = 0; c < VEC; ++c) v.v[c] = v.v[c] - xi.v[c];
         }
         store_row_stream<VEC>(m + (m_coo ? eid : q) * F + col, v);
     }
 }
 
-template <int LPR, int VEC, int MSG, bool MAX>
+template <int LPR, int VEC, int MSG, int RED>
 gnn_status launch_typed(const PropParams &p, hipStream_t stream)
 {
     constexpr int NSG = 64 / LPR;
     const int64_t small_blocks = gnn_div_up(p.n_small, kWavesPerBlock * NSG);
     const int64_t blocks = p.item_blocks + small_blocks;
     if (blocks > 0) {
-        hipLaunchKernelGGL((propagate_kernel<LPR, VEC, MSG, MAX>), dim3((unsigned)blocks), dim3(kThreads), 0, stream,
+        hipLaunchKernelGGL((propagate_kernel<LPR, VEC, MSG, RED>), dim3((unsigned)blocks), dim3(kThreads), 0, stream,
                            p);
         GNN_LAUNCH_CHECK();
     }
     if (p.n_split > 0) {
         const int64_t cblocks = gnn_div_up(p.n_split, kWavesPerBlock);
-        hipLaunchKernelGGL((combine_pieces_kernel<LPR, VEC, MAX>), dim3((unsigned)cblocks), dim3(kThreads), 0, stream,
+        hipLaunchKernelGGL((combine_pieces_kernel<LPR, VEC, RED>), dim3((unsigned)cblocks), dim3(kThreads), 0, stream,
                            p);
         GNN_LAUNCH_CHECK();
     }
@@ -424,38 +452,71 @@ gnn_status launch_typed(const PropParams &p, hipStream_t stream)
 }
 
 template <int LPR, int VEC>
-gnn_status launch_shape(const PropParams &p, int msg, bool use_max, hipStream_t stream)
+gnn_status launch_shape(const PropParams &p, int msg, int red, hipStream_t stream)
 {
-    switch (msg * 2 + (use_max ? 1 : 0)) {
-    case 0: return launch_typed<LPR, VEC, kMsgCopy, false>(p, stream);
-    case 1: return launch_typed<LPR, VEC, kMsgCopy, true>(p, stream);
-    case 2: return launch_typed<LPR, VEC, kMsgMulScalar, false>(p, stream);
-    case 3: return launch_typed<LPR, VEC, kMsgMulScalar, true>(p, stream);
-    case 4: return launch_typed<LPR, VEC, kMsgMulVector, false>(p, stream);
-    case 5: return launch_typed<LPR, VEC, kMsgMulVector, true>(p, stream);
-    case 6: return launch_typed<LPR, VEC, kMsgRouted + kMsgCopy, false>(p, stream);
-    case 8: return launch_typed<LPR, VEC, kMsgRouted + kMsgMulScalar, false>(p, stream);
-    case 10: return launch_typed<LPR, VEC, kMsgRouted + kMsgMulVector, false>(p, stream);
+    switch (msg * 4 + red) {
+    case kMsgCopy * 4 + kRedSum: return launch_typed<LPR, VEC, kMsgCopy, kRedSum>(p, stream);
+    case kMsgCopy * 4 + kRedMax: return launch_typed<LPR, VEC, kMsgCopy, kRedMax>(p, stream);
+    case kMsgCopy * 4 + kRedProd: return launch_typed<LPR, VEC, kMsgCopy, kRedProd>(p, stream);
+    case kMsgCopy * 4 + kRedMin: return launch_typed<LPR, VEC, kMsgCopy, kRedMin>(p, stream);
+    case kMsgMulScalar * 4 + kRedSum: return launch_typed<LPR, VEC, kMsgMulScalar, kRedSum>(p, stream);
+    case kMsgMulScalar * 4 + kRedMax: return launch_typed<LPR, VEC, kMsgMulScalar, kRedMax>(p, stream);
+    case kMsgMulScalar * 4 + kRedProd: return launch_typed<LPR, VEC, kMsgMulScalar, kRedProd>(p, stream);
+    case kMsgMulScalar * 4 + kRedMin: return launch_typed<LPR, VEC, kMsgMulScalar, kRedMin>(p, stream);
+    case kMsgMulVector * 4 + kRedSum: return launch_typed<LPR, VEC, kMsgMulVector, kRedSum>(p, stream);
+    case kMsgMulVector * 4 + kRedMax: return launch_typed<LPR, VEC, kMsgMulVector, kRedMax>(p, stream);
+    case kMsgMulVector * 4 + kRedProd: return launch_typed<LPR, VEC, kMsgMulVector, kRedProd>(p, stream);
+    case kMsgMulVector * 4 + kRedMin: return launch_typed<LPR, VEC, kMsgMulVector, kRedMin>(p, stream);
+    case kMsgSubTarget * 4 + kRedSum: return launch_typed<LPR, VEC, kMsgSubTarget, kRedSum>(p, stream);
+    case kMsgSubTarget * 4 + kRedMax: return launch_typed<LPR, VEC, kMsgSubTarget, kRedMax>(p, stream);
+    case kMsgSubTarget * 4 + kRedProd: return launch_typed<LPR, VEC, kMsgSubTarget, kRedProd>(p, stream);
+    case kMsgSubTarget * 4 + kRedMin: return launch_typed<LPR, VEC, kMsgSubTarget, kRedMin>(p, stream);
+    case (kMsgRouted + kMsgCopy) * 4 + kRedSum:
+        return launch_typed<LPR, VEC, kMsgRouted + kMsgCopy, kRedSum>(p, stream);
+    case (kMsgRouted + kMsgMulScalar) * 4 + kRedSum:
+        return launch_typed<LPR, VEC, kMsgRouted + kMsgMulScalar, kRedSum>(p, stream);
+    case (kMsgRouted + kMsgMulVector) * 4 + kRedSum:
+        return launch_typed<LPR, VEC, kMsgRouted + kMsgMulVector, kRedSum>(p, stream);
     }
     return GNN_ERR_BAD_SIZE;
 }
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+bool valid_aggr(gnn_aggr a) { return a >= GNN_AGGR_SUM && a <= GNN_AGGR_PROD; }
+
+int reduce_of(gnn_aggr a)
+{
+    switch (a) {
+    case GNN_AGGR_MAX: return GNN_REDUCE_MAX;
+    case GNN_AGGR_MIN: return GNN_REDUCE_MIN;
+    case GNN_AGGR_PROD: return GNN_REDUCE_PROD;
+    default: return GNN_REDUCE_SUM;
+    }
+}
+
 }  // namespace
 
 gnn_status gnn_launch_propagate(const gnn_graph *g, const float *d_x, int32_t feat_dim, const float *d_e,
-                                int32_t e_dim, gnn_edge_order e_order, gnn_msg_op msg, int use_max,
+                                int32_t e_dim, gnn_edge_order e_order, gnn_msg_op msg, int reduce,
                                 const gnn_epilogue &epi, float *d_out, hipStream_t stream, gnn_gather_index gather,
                                 const int32_t *d_winners)
 {
     const int F = feat_dim;
     int kmsg = kMsgCopy;
     if (msg == GNN_MSG_E_MUL_XJ) kmsg = (e_dim == 1) ? kMsgMulScalar : kMsgMulVector;
+    if (msg == GNN_MSG_XJ_SUB_XI) {
+        if (gather != GNN_GATHER_SOURCE_NODE) return GNN_ERR_UNSUPPORTED;   // the row's own features are x[row]
+        kmsg = kMsgSubTarget;
+    }
+    if (reduce < GNN_REDUCE_SUM || reduce > GNN_REDUCE_PROD) return GNN_ERR_BAD_SIZE;
     if (d_winners) {
-        if (use_max || e_order != GNN_EDGE_ORDER_COO) return GNN_ERR_UNSUPPORTED;   // edge ids are compared
+        if (reduce != GNN_REDUCE_SUM || e_order != GNN_EDGE_ORDER_COO || msg == GNN_MSG_XJ_SUB_XI)
+            return GNN_ERR_UNSUPPORTED;   // edge ids are compared
         kmsg += kMsgRouted;
     }
+    const int red = reduce == GNN_REDUCE_SUM ? kRedSum
+                    : reduce == GNN_REDUCE_PROD ? kRedProd : reduce == GNN_REDUCE_MIN ? kRedMin : kRedMax;
 
     PropParams p{};
     p.rowptr = g->rowptr; p.perm = g->perm;
@@ -474,16 +535,15 @@ gnn_status gnn_launch_propagate(const gnn_graph *g, const float *d_x, int32_t fe
 
     const bool vec4 = (F % 4 == 0) && aligned16(d_x) && aligned16(d_out) &&
                       (msg_base(kmsg) != kMsgMulVector || aligned16(d_e)) && aligned16(d_winners);
-    const bool mx = use_max != 0;
     if (vec4) {
         const int cols = F / 4;
-        if (cols <= 8) return launch_shape<8, 4>(p, kmsg, mx, stream);
-        if (cols <= 16) return launch_shape<16, 4>(p, kmsg, mx, stream);
-        if (cols <= 32) return launch_shape<32, 4>(p, kmsg, mx, stream);
-        return launch_shape<64, 4>(p, kmsg, mx, stream);
+        if (cols <= 8) return launch_shape<8, 4>(p, kmsg, red, stream);
+        if (cols <= 16) return launch_shape<16, 4>(p, kmsg, red, stream);
+        if (cols <= 32) return launch_shape<32, 4>(p, kmsg, red, stream);
+        return launch_shape<64, 4>(p, kmsg, red, stream);
     }
-    if (F <= 16) return launch_shape<16, 1>(p, kmsg, mx, stream);
-    return launch_shape<64, 1>(p, kmsg, mx, stream);
+    if (F <= 16) return launch_shape<16, 1>(p, kmsg, red, stream);
+    return launch_shape<64, 1>(p, kmsg, red, stream);
 }
 
 extern "C" {
@@ -493,8 +553,8 @@ gnn_status gnn_propagate(const gnn_graph *g, const float *d_x, int32_t feat_dim,
 {
     if (!g || !d_x || !d_out) return GNN_ERR_NULL;
     if (feat_dim <= 0) return GNN_ERR_BAD_SIZE;
-    if (msg != GNN_MSG_COPY_XJ && msg != GNN_MSG_E_MUL_XJ) return GNN_ERR_BAD_SIZE;
-    if (aggr != GNN_AGGR_SUM && aggr != GNN_AGGR_MEAN && aggr != GNN_AGGR_MAX) return GNN_ERR_BAD_SIZE;
+    if (msg != GNN_MSG_COPY_XJ && msg != GNN_MSG_E_MUL_XJ && msg != GNN_MSG_XJ_SUB_XI) return GNN_ERR_BAD_SIZE;
+    if (!valid_aggr(aggr)) return GNN_ERR_BAD_SIZE;
     if (msg == GNN_MSG_E_MUL_XJ) {
         if (e_dim != 1 && e_dim != feat_dim) return GNN_ERR_BAD_SIZE;
         if (e_order != GNN_EDGE_ORDER_COO && e_order != GNN_EDGE_ORDER_CSR) return GNN_ERR_BAD_SIZE;
@@ -502,7 +562,7 @@ gnn_status gnn_propagate(const gnn_graph *g, const float *d_x, int32_t feat_dim,
     }
     gnn_epilogue epi;
     epi.mean = (aggr == GNN_AGGR_MEAN);
-    return gnn_launch_propagate(g, d_x, feat_dim, d_e, e_dim, e_order, msg, aggr == GNN_AGGR_MAX, epi, d_out,
+    return gnn_launch_propagate(g, d_x, feat_dim, d_e, e_dim, e_order, msg, reduce_of(aggr), epi, d_out,
                                 static_cast<hipStream_t>(stream));
 }
 
@@ -511,7 +571,7 @@ gnn_status gnn_apply_edges(const gnn_graph *g, const float *d_x, int32_t feat_di
 {
     if (!g) return GNN_ERR_NULL;
     if (feat_dim <= 0) return GNN_ERR_BAD_SIZE;
-    if (msg != GNN_MSG_COPY_XJ && msg != GNN_MSG_E_MUL_XJ) return GNN_ERR_BAD_SIZE;
+    if (msg < GNN_MSG_COPY_XJ || msg > GNN_MSG_XI_DOT_XJ) return GNN_ERR_BAD_SIZE;
     if (m_order != GNN_EDGE_ORDER_COO && m_order != GNN_EDGE_ORDER_CSR) return GNN_ERR_BAD_SIZE;
     if (msg == GNN_MSG_E_MUL_XJ) {
         if (e_dim != 1 && e_dim != feat_dim) return GNN_ERR_BAD_SIZE;
@@ -519,25 +579,29 @@ gnn_status gnn_apply_edges(const gnn_graph *g, const float *d_x, int32_t feat_di
     }
     if (g->num_edges == 0) return GNN_OK;
     if (!d_x || !d_m || (msg == GNN_MSG_E_MUL_XJ && !d_e)) return GNN_ERR_NULL;
+    if (msg == GNN_MSG_XI_DOT_XJ) return gnn_launch_edge_dot(g, d_x, d_x, feat_dim, d_m, m_order, stream);
     int kmsg = kMsgCopy;
     if (msg == GNN_MSG_E_MUL_XJ) kmsg = (e_dim == 1) ? kMsgMulScalar : kMsgMulVector;
+    if (msg == GNN_MSG_XJ_SUB_XI) kmsg = kMsgSubTarget;
     const int F = feat_dim;
     const bool vec4 = (F % 4 == 0) && aligned16(d_x) && aligned16(d_m) && (kmsg != kMsgMulVector || aligned16(d_e));
     const int64_t total = g->num_edges * (vec4 ? F / 4 : F);
     const dim3 grid((unsigned)std::min<int64_t>(gnn_div_up(total, kThreads), 256 * 128)), block(kThreads);
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int e_coo = (e_order == GNN_EDGE_ORDER_COO), m_coo = (m_order == GNN_EDGE_ORDER_COO);
-#define GNN_APPLY(VEC, MSG)                                                                                        \
-    hipLaunchKernelGGL((apply_edges_kernel<VEC, MSG>), grid, block, 0, s, g->colidx, g->perm, g->num_edges, F, d_x, \
-                       d_e, e_coo, m_coo, d_m)
+#define GNN_APPLY(VEC, MSG)                                                                                      \
+    hipLaunchKernelGGL((apply_edges_kernel<VEC, MSG>), grid, block, 0, s, g->colidx, g->rowidx, g->perm, g->num_edges, \
+                       F, d_x, d_e, e_coo, m_coo, d_m)
     if (vec4) {
         if (kmsg == kMsgCopy) GNN_APPLY(4, kMsgCopy);
         else if (kmsg == kMsgMulScalar) GNN_APPLY(4, kMsgMulScalar);
-        else GNN_APPLY(4, kMsgMulVector);
+        else if (kmsg == kMsgMulVector) GNN_APPLY(4, kMsgMulVector);
+        else GNN_APPLY(4, kMsgSubTarget);
     } else {
         if (kmsg == kMsgCopy) GNN_APPLY(1, kMsgCopy);
         else if (kmsg == kMsgMulScalar) GNN_APPLY(1, kMsgMulScalar);
-        else GNN_APPLY(1, kMsgMulVector);
+        else if (kmsg == kMsgMulVector) GNN_APPLY(1, kMsgMulVector);
+        else GNN_APPLY(1, kMsgSubTarget);
     }
 #undef GNN_APPLY
     GNN_LAUNCH_CHECK();
@@ -549,13 +613,13 @@ gnn_status gnn_aggregate_neighbors(const gnn_graph *g, const float *d_m, int32_t
 {
     if (!g || !d_out) return GNN_ERR_NULL;
     if (feat_dim <= 0) return GNN_ERR_BAD_SIZE;
-    if (aggr != GNN_AGGR_SUM && aggr != GNN_AGGR_MEAN && aggr != GNN_AGGR_MAX) return GNN_ERR_BAD_SIZE;
+    if (!valid_aggr(aggr)) return GNN_ERR_BAD_SIZE;
     if (m_order != GNN_EDGE_ORDER_COO && m_order != GNN_EDGE_ORDER_CSR) return GNN_ERR_BAD_SIZE;
     if (!d_m && g->num_edges > 0) return GNN_ERR_NULL;
     gnn_epilogue epi;
     epi.mean = (aggr == GNN_AGGR_MEAN);
     return gnn_launch_propagate(g, d_m, feat_dim, nullptr, 1, GNN_EDGE_ORDER_CSR, GNN_MSG_COPY_XJ,
-                                aggr == GNN_AGGR_MAX, epi, d_out, static_cast<hipStream_t>(stream),
+                                reduce_of(aggr), epi, d_out, static_cast<hipStream_t>(stream),
                                 m_order == GNN_EDGE_ORDER_COO ? GNN_GATHER_EDGE_COO : GNN_GATHER_EDGE_CSR);
 }
 

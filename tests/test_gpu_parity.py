@@ -7,7 +7,8 @@ import pytest
 torch = pytest.importorskip("torch")
 
 import oracle
-from oracle import AGGR_MAX, AGGR_MEAN, AGGR_SUM, MSG_COPY_XJ, MSG_E_MUL_XJ
+from oracle import (AGGR_MAX, AGGR_MEAN, AGGR_MIN, AGGR_PROD, AGGR_SUM, MSG_COPY_XJ, MSG_E_MUL_XJ, MSG_XI_DOT_XJ,
+                    MSG_XJ_SUB_XI)
 from paper_2412_06354_amd import synth
 from util import assert_close_rel, assert_close_sabs, load_golden
 
@@ -205,6 +206,73 @@ def test_apply_edges_then_aggregate(case, gnn, msg):
             # the fused call walks the same rows in the same order: identical bits
             fused = host(gnn.propagate(g, x, dev(e) if e is not None else None, msg, aggr))
             np.testing.assert_array_equal(got.view(np.uint32), fused.view(np.uint32))
+
+
+@pytest.mark.parametrize("msg", [MSG_COPY_XJ, MSG_E_MUL_XJ, MSG_XJ_SUB_XI])
+def test_propagate_min_prod_and_target_message(case, gnn, msg):
+    """min is compared bit for bit (like max); prod within one rounding per factor; x_j - x_i under
+    every reduction; the two-step path (apply_edges, aggregate_neighbors) gives the fused result."""
+    name, wl, g = case
+    n = wl.num_nodes
+    e = wl.edge_weight if msg == MSG_E_MUL_XJ else None
+    de = dev(e) if e is not None else None
+    x = dev(wl.x)
+    ref_min = oracle.propagate(wl.src, wl.dst, n, wl.x, e, msg, AGGR_MIN)
+    got_min = host(gnn.propagate(g, x, de, msg, AGGR_MIN))
+    np.testing.assert_array_equal(got_min.view(np.uint32), ref_min.view(np.uint32))
+    m = gnn.apply_edges(g, x, de, msg)
+    m_ref = oracle.apply_edges(wl.src, n, wl.x, e, msg, dst=wl.dst)
+    np.testing.assert_array_equal(host(m).view(np.uint32), m_ref.view(np.uint32))
+    two_step = host(gnn.aggregate_neighbors(g, m, AGGR_MIN))
+    np.testing.assert_array_equal(two_step.view(np.uint32), ref_min.view(np.uint32))
+    # products: factors close to +-1 so that thousands of them stay in range
+    xp = (1.0 + 1e-3 * wl.x).astype(np.float32)
+    xp[::3] *= -1.0
+    ep = None if e is None else (1.0 + 1e-3 * e).astype(np.float32)
+    if msg == MSG_XJ_SUB_XI:
+        xp = (wl.x * 1e-2 + np.arange(n, dtype=np.float32)[:, None] * 1e-6).astype(np.float32)
+        xp[::2] += 1.0           # differences near +-1 (or tiny, where products underflow to 0 on both sides)
+    ref_p, sabs_p = oracle.propagate(wl.src, wl.dst, n, xp, ep, msg, AGGR_PROD, with_sabs=True)
+    got_p = host(gnn.propagate(g, dev(xp), dev(ep) if ep is not None else None, msg, AGGR_PROD)).astype(np.float64)
+    assert np.isfinite(got_p).all()
+    assert (np.abs(got_p - ref_p) <= 1.3e-7 * sabs_p + 1e-37).all(), f"{name} prod msg={msg}"
+    if msg == MSG_XJ_SUB_XI:
+        for aggr in (AGGR_SUM, AGGR_MEAN, AGGR_MAX):
+            ref, sabs = oracle.propagate(wl.src, wl.dst, n, wl.x, None, msg, aggr, with_sabs=True)
+            got = host(gnn.propagate(g, x, None, msg, aggr))
+            if aggr == AGGR_MAX:
+                np.testing.assert_array_equal(got.view(np.uint32), ref.view(np.uint32))
+            else:
+                assert_close_sabs(got, ref, sabs, what=f"{name} xj_sub_xi aggr={aggr}")
+
+
+def test_apply_edges_dot_product(case, gnn):
+    name, wl, g = case
+    n = wl.num_nodes
+    ref, sabs = oracle.apply_edges(wl.src, n, wl.x, None, MSG_XI_DOT_XJ, dst=wl.dst, with_sabs=True)
+    got = gnn.apply_edges(g, dev(wl.x), None, MSG_XI_DOT_XJ)
+    assert tuple(got.shape) == (wl.num_edges, 1)
+    assert_close_sabs(host(got), ref, sabs, what=f"{name} xi_dot_xj")
+    _, _, perm, _ = oracle.build_csr(wl.src, wl.dst, n)
+    got_csr = gnn.apply_edges(g, dev(wl.x), None, MSG_XI_DOT_XJ, m_order=gnn.EDGE_ORDER_CSR)
+    np.testing.assert_array_equal(host(got_csr), host(got)[perm])
+    # the scalar messages can be reduced like any other: a width-1 aggregate
+    ref_sum, sabs_sum = oracle.aggregate_neighbors(wl.dst, n, ref, AGGR_SUM, with_sabs=True)
+    assert_close_sabs(host(gnn.aggregate_neighbors(g, dev(ref), AGGR_SUM)), ref_sum, sabs_sum,
+                      what=f"{name} sum of dots")
+
+
+def test_unsupported_backward_combinations(gnn):
+    wl = powerlaw(500, 4000, 8, 200.0)
+    g = gnn.build_csr(dev(wl.src), dev(wl.dst), wl.num_nodes)
+    gt = gnn.build_csr(dev(wl.dst), dev(wl.src), wl.num_nodes)
+    x = dev(wl.x)
+    for msg, aggr in ((MSG_XJ_SUB_XI, AGGR_SUM), (MSG_COPY_XJ, AGGR_MIN), (MSG_COPY_XJ, AGGR_PROD)):
+        with pytest.raises(gnn.GnnError) as err:
+            gnn.propagate_backward(g, gt, x, torch.ones_like(x), None, msg, aggr)
+        assert err.value.code == 4
+    g.close()
+    gt.close()
 
 
 def test_apply_edges_elementwise_and_odd_width(gnn):
