@@ -266,6 +266,51 @@ def gatconv_backward(src, dst, num_nodes: int, x, w, a_src, a_dst, grad_out, neg
     return res
 
 
+def dense(x, w, bias=None, relu: bool = False, with_sabs: bool = False):
+    x, w = _f32(x, "x"), _f32(w, "w")
+    bias = None if bias is None else _f32(bias, "bias")
+    n_rows, k = x.shape
+    if w.shape[0] != k or (bias is not None and bias.shape != (w.shape[1],)):
+        raise ValueError("shape mismatch")
+    out = np.empty((n_rows, w.shape[1]), np.float32)
+    sabs = np.empty(out.shape, np.float64) if with_sabs else None
+    rc = _load().oracle_dense(_p(x), ctypes.c_int32(n_rows), ctypes.c_int32(k), _p(w), ctypes.c_int32(w.shape[1]),
+                              _p(bias), ctypes.c_int32(1 if relu else 0), _p(out), _p(sabs))
+    _check(rc, "dense")
+    return (out, sabs) if with_sabs else out
+
+
+def batchnorm(x, gamma=None, beta=None, eps: float = 1e-5, relu: bool = False, mean=None, var=None):
+    """-> (out, mean, var).  Batch statistics unless mean and var are given."""
+    x = _f32(x, "x")
+    n, f = x.shape
+    gamma = None if gamma is None else _f32(gamma, "gamma")
+    beta = None if beta is None else _f32(beta, "beta")
+    given = mean is not None and var is not None
+    mean_io = _f32(mean, "mean").copy() if given else np.empty(f, np.float32)
+    var_io = _f32(var, "var").copy() if given else np.empty(f, np.float32)
+    out = np.empty_like(x)
+    rc = _load().oracle_batchnorm(_p(x), ctypes.c_int32(n), ctypes.c_int32(f), _p(gamma), _p(beta),
+                                  ctypes.c_float(eps), ctypes.c_int32(1 if relu else 0),
+                                  ctypes.c_int32(1 if given else 0), _p(mean_io), _p(var_io), _p(out))
+    _check(rc, "batchnorm")
+    return out, mean_io, var_io
+
+
+def example_model_forward(src, dst, num_nodes: int, graph_indicator, num_graphs: int, x, params: dict,
+                          eps: float = 1e-5):
+    """The paper's example model (section 3, "Training Example"), step by step with the functions above:
+    GCNConv(f0 => f1) -> BatchNorm(f1) over the nodes of the batch -> relu -> GCNConv(f1 => f2) + relu ->
+    mean pooling per graph -> Dense(f2, f3).  Every intermediate is a stored float tensor.
+    Returns the dict of all intermediates; "y" is the prediction [num_graphs, f3]."""
+    h1 = gcnconv(src, dst, num_nodes, x, params["w1"], params["b1"], True)
+    h2, mean, var = batchnorm(h1, params["gamma"], params["beta"], eps, relu=True)
+    h3 = np.maximum(gcnconv(src, dst, num_nodes, h2, params["w2"], params["b2"], True), np.float32(0))
+    pooled = graph_pool(graph_indicator, num_graphs, h3, AGGR_MEAN)
+    y = dense(pooled, params["w3"], params["b3"])
+    return {"h1": h1, "h2": h2, "mean": mean, "var": var, "h3": h3, "pooled": pooled, "y": y}
+
+
 def gin_update(src, dst, num_nodes: int, x, eps: float = 0.0, with_sabs: bool = False):
     src, dst, x = _i32(src, "src"), _i32(dst, "dst"), _f32(x, "x")
     ne, f = src.shape[0], x.shape[1]

@@ -765,6 +765,72 @@ done:
 }
 
 /*
+ * Dense layer of the paper's example model (section 3, "Training Example": Dense(64, 1)):
+ *   out = act(X W + b),  X [N x k], W [k x n] row-major, b [n] or NULL, act = identity or relu.
+ * sabs = sum_k |x||w| + |b|.
+ */
+int oracle_dense(const float *x, int32_t N, int32_t k, const float *w, int32_t n, const float *bias,
+                 int32_t relu, float *out, double *sabs)
+{
+    if (N < 0 || k <= 0 || n <= 0) return 2;
+    for (int32_t i = 0; i < N; ++i)
+        for (int32_t o = 0; o < n; ++o) {
+            double a = bias ? (double)bias[o] : 0.0, b = fabs(a);
+            for (int32_t q = 0; q < k; ++q) {
+                double t = (double)x[(int64_t)i * k + q] * (double)w[(int64_t)q * n + o];
+                a += t;
+                b += fabs(t);
+            }
+            if (relu && a < 0.0) a = 0.0;
+            out[(int64_t)i * n + o] = (float)a;
+            if (sabs) sabs[(int64_t)i * n + o] = b;
+        }
+    return 0;
+}
+
+/*
+ * Batch normalisation across the node dimension (the example model's BatchNorm(64), "normalize
+ * across node dimension"), followed by an optional relu:
+ *   mean[f] = (1/N) sum_i x[i,f],   var[f] = (1/N) sum_i (x[i,f] - mean[f])^2      (biased variance)
+ *   out[i,f] = act(gamma[f] * (x[i,f] - mean[f]) / sqrt(var[f] + eps) + beta[f]).
+ * With use_given != 0 the statistics are read from mean_io / var_io (inference with stored
+ * statistics) instead of being computed from the batch and written there.
+ * gamma / beta may be NULL (1 and 0).  Returns 2 for N <= 0.
+ */
+int oracle_batchnorm(const float *x, int32_t N, int32_t F, const float *gamma, const float *beta, float eps,
+                     int32_t relu, int32_t use_given, float *mean_io, float *var_io, float *out)
+{
+    if (N <= 0 || F <= 0) return 2;
+    for (int32_t f = 0; f < F; ++f) {
+        double mu, var;
+        if (use_given) {
+            mu = (double)mean_io[f];
+            var = (double)var_io[f];
+        } else {
+            double s = 0.0;
+            for (int32_t i = 0; i < N; ++i) s += (double)x[(int64_t)i * F + f];
+            mu = s / (double)N;
+            double q = 0.0;
+            for (int32_t i = 0; i < N; ++i) {
+                double d = (double)x[(int64_t)i * F + f] - mu;
+                q += d * d;
+            }
+            var = q / (double)N;
+            if (mean_io) mean_io[f] = (float)mu;
+            if (var_io) var_io[f] = (float)var;
+        }
+        double g = gamma ? (double)gamma[f] : 1.0, b = beta ? (double)beta[f] : 0.0;
+        double inv = 1.0 / sqrt(var + (double)eps);
+        for (int32_t i = 0; i < N; ++i) {
+            double y = g * ((double)x[(int64_t)i * F + f] - mu) * inv + b;
+            if (relu && y < 0.0) y = 0.0;
+            out[(int64_t)i * F + f] = (float)y;
+        }
+    }
+    return 0;
+}
+
+/*
  * GIN-style node update without the MLP:  out[i,:] = (1 + eps) x[i,:] + sum_{j->i} x[j,:].
  */
 int oracle_gin_update(const int32_t *src, const int32_t *dst, int64_t E, int32_t N,

@@ -365,3 +365,28 @@ def config4_gat(num_nodes: int = 2_449_029, num_edges: int = 123_718_280, f_in: 
     return Workload("config4_gat", num_nodes, src, dst, x,
                     params={"w": w, "a_src": a_src, "a_dst": a_dst, "heads": heads, "ch": ch,
                             "negative_slope": 0.2})
+
+
+def config5_example_model(num_graphs: int = 32, n: int = 50, p: float = 0.08, f0: int = 16, f1: int = 64,
+                          f2: int = 64, f3: int = 1) -> Workload:
+    """A collated batch for the paper's example model (section 3, "Training Example"): ``num_graphs``
+    random graphs of ``n`` nodes (the listing's n and m are not given: each unordered pair is kept with
+    probability p, both directions emitted), standard-normal node features of width f0, and the model's
+    parameters: Glorot-uniform weights, small uniform biases (so that the bias paths are exercised),
+    batch-norm scale near 1 and shift near 0."""
+    sd = seed_of(5)
+    src, dst, gi, _ = batched_er_graphs(num_graphs, n, n, p, sd)
+    nn = int(gi.shape[0])
+    x = normal_f32(sd, STREAM_FEATURES, nn * f0).reshape(nn, f0)
+    params = {
+        "w1": glorot_uniform(sd, 20, f0, f1, (f0, f1)),
+        "b1": uniform_f32(sd, 21, f1, -0.1, 0.1),
+        "gamma": uniform_f32(sd, 22, f1, 0.9, 1.1),
+        "beta": uniform_f32(sd, 23, f1, -0.1, 0.1),
+        "w2": glorot_uniform(sd, 24, f1, f2, (f1, f2)),
+        "b2": uniform_f32(sd, 25, f2, -0.1, 0.1),
+        "w3": glorot_uniform(sd, 26, f2, f3, (f2, f3)),
+        "b3": uniform_f32(sd, 27, f3, -0.1, 0.1),
+    }
+    return Workload("config5_example_model", nn, src, dst, x, graph_indicator=gi, num_graphs=num_graphs,
+                    params=params)

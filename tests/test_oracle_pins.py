@@ -629,6 +629,64 @@ def test_min_of_signed_zeros_is_minus_zero():
     np.testing.assert_array_equal(prod[:, 0], [-8.0, 0.0, 0.0, -8.0])
 
 
+def test_batchnorm_and_dense_against_numpy():
+    """Batch normalisation over the node dimension against numpy's float64 mean / variance, with what the
+    definition fixes (zero mean and unit variance per feature when gamma = 1, beta = 0, eps = 0; a constant
+    column maps to beta; stored statistics are used as given); the dense layer against a float64 matmul."""
+    n, f = 300, 7
+    x = (synth.normal_f32(97, 2, n * f).reshape(n, f) * np.arange(1, f + 1, dtype=np.float32) + 3.0).astype(np.float32)
+    x[:, 3] = 2.5                                                   # a constant column
+    gamma = synth.uniform_f32(97, 3, f, 0.5, 1.5)
+    beta = synth.uniform_f32(97, 4, f, -1.0, 1.0)
+    out, mean, var = oracle.batchnorm(x, gamma, beta, 1e-5)
+    x64 = x.astype(np.float64)
+    np.testing.assert_allclose(mean, x64.mean(0), rtol=1e-6)
+    np.testing.assert_allclose(var, x64.var(0), rtol=1e-6, atol=1e-12)
+    ref = gamma * (x64 - x64.mean(0)) / np.sqrt(x64.var(0) + np.float32(1e-5)) + beta
+    np.testing.assert_allclose(out, ref, rtol=0, atol=2e-6)
+    np.testing.assert_allclose(out[:, 3], beta[3], atol=1e-6)
+    plain, _, _ = oracle.batchnorm(x[:, [0, 1, 2, 4]].copy(), None, None, 0.0)
+    np.testing.assert_allclose(plain.astype(np.float64).mean(0), 0.0, atol=1e-6)
+    np.testing.assert_allclose(plain.astype(np.float64).var(0), 1.0, rtol=1e-5)
+    relu, _, _ = oracle.batchnorm(x, gamma, beta, 1e-5, relu=True)
+    np.testing.assert_array_equal(relu, np.maximum(out, 0))
+    m_given, v_given = np.zeros(f, np.float32), np.ones(f, np.float32)
+    given, m2, v2 = oracle.batchnorm(x, gamma, beta, 0.0, mean=m_given, var=v_given)
+    np.testing.assert_allclose(given, gamma * x64 + beta, rtol=1e-6, atol=1e-6)
+    np.testing.assert_array_equal(m2, m_given)
+    w = synth.glorot_uniform(97, 5, f, 4, (f, 4))
+    b = synth.uniform_f32(97, 6, 4, -1, 1)
+    y, sabs = oracle.dense(x, w, b, with_sabs=True)
+    ref_y = x64 @ w.astype(np.float64) + b
+    assert (np.abs(y - ref_y) <= 1e-7 * sabs).all()
+    np.testing.assert_array_equal(oracle.dense(x, w, b, relu=True), np.maximum(y, 0))
+    np.testing.assert_allclose(oracle.dense(x, w), x64 @ w.astype(np.float64), rtol=0, atol=1e-6 * sabs.max())
+
+
+def test_example_model_against_dense_float64():
+    """The example model end to end (GCNConv, batch norm over nodes, relu, GCNConv + relu, mean pooling,
+    dense) against a float64 implementation with explicit dense adjacency and membership matrices on a
+    small collated batch; intermediates are never rounded there, so agreement is to ~1e-5."""
+    wl = synth.config5_example_model(num_graphs=5, n=12, p=0.3)
+    n, g_cnt, p = wl.num_nodes, wl.num_graphs, wl.params
+    res = oracle.example_model_forward(wl.src, wl.dst, n, wl.graph_indicator, g_cnt, wl.x, p)
+    a = dense_adjacency(wl.src, wl.dst, n) + np.eye(n)
+    deg = a.sum(1)
+    ahat = a / np.sqrt(np.outer(deg, deg))
+    f64 = lambda k: p[k].astype(np.float64)
+    h1 = ahat @ (wl.x.astype(np.float64) @ f64("w1")) + f64("b1")
+    h2 = np.maximum(f64("gamma") * (h1 - h1.mean(0)) / np.sqrt(h1.var(0) + np.float32(1e-5)) + f64("beta"), 0)
+    h3 = np.maximum(ahat @ (h2 @ f64("w2")) + f64("b2"), 0)
+    member = np.zeros((g_cnt, n))
+    member[wl.graph_indicator, np.arange(n)] = 1.0
+    pooled = (member @ h3) / member.sum(1, keepdims=True)
+    y = pooled @ f64("w3") + f64("b3")
+    np.testing.assert_allclose(res["h1"], h1, rtol=0, atol=1e-5 * np.abs(h1).max())
+    np.testing.assert_allclose(res["h3"], h3, rtol=0, atol=2e-5 * np.abs(h3).max())
+    np.testing.assert_allclose(res["y"], y, rtol=0, atol=2e-5 * np.abs(y).max())
+    assert res["y"].shape == (g_cnt, 1)
+
+
 def test_error_codes():
     src = np.array([0, 5], np.int32)
     dst = np.array([1, 0], np.int32)
