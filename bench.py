@@ -19,6 +19,7 @@ Other workloads measure the remaining steps of the path, one JSON line each:
   tiny     gnn_propagate sum / mean / max on the 2 708-node graph (launch-latency bound)
   backward gnn_propagate_backward (e_mul_xj, sum: grad_x and grad_e) on the headline graph
   gcn_backward gnn_gcnconv_backward (grad X, W, b) on the GCN graph
+  example  gnn_example_model_forward (the paper's example model) on collated batches of 32 and 4 096 graphs
 
 Every line carries `value` (algorithmic GB/s = the byte model of the step / mean step time), a
 `roofline` object for the dominant kernel and a `cpu_baseline` object (the parity oracle, one thread,
@@ -362,6 +363,52 @@ def run_gat_backward(args, torch, gnn, synth):
     return line
 
 
+def run_example(args, torch, gnn, synth):
+    """The paper's example model, forward, on a collated batch: 32 graphs (the listing's batch size) and 4 096."""
+    results = {}
+    for ng in (32, 4096):
+        wl = synth.config5_example_model(num_graphs=ng)
+        n, e, p = wl.num_nodes, wl.num_edges, wl.params
+        g = gnn.build_csr(to_dev(torch, wl.src), to_dev(torch, wl.dst), n)
+        x, gi = to_dev(torch, wl.x), to_dev(torch, wl.graph_indicator)
+        dp = {k: to_dev(torch, v) for k, v in p.items()}
+        f0, f1, f2, f3 = wl.x.shape[1], p["w1"].shape[1], p["w2"].shape[1], p["w3"].shape[1]
+        y = torch.empty((ng, f3), dtype=torch.float32, device="cuda")
+        ws = torch.empty(int(gnn.lib().gnn_example_model_workspace_bytes(n, ng, f1, f2)), dtype=torch.uint8, device="cuda")
+        ms = time_calls(torch, lambda: gnn.example_model_forward(g, gi, ng, x, dp, out=y, workspace=ws), args.steps,
+                        args.warmup)
+        # per layer: GCN = X read, Z written and gathered (E + N rows), output written; batch norm reads its
+        # input three times and writes once; pooling reads h3; plus indices
+        b = (4 * n * (f0 + 2 * f1) + (e + n) * (4 * f1 + 4) + 4 * 4 * n * f1 +
+             4 * n * (f1 + 2 * f2) + (e + n) * (4 * f2 + 4) + 4 * n * f2 + 4 * n)
+        # the same call captured once into a HIP graph and replayed (the chain is ~20 small launches)
+        gph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(gph):
+            gnn.example_model_forward(g, gi, ng, x, dp, out=y, workspace=ws)
+        ms_graph = time_calls(torch, gph.replay, args.steps, args.warmup)
+        results[ng] = (ms, b, n, e, ms_graph)
+        del gph
+        g.close()
+    ms, b, n, e, ms_graph = results[4096]
+    line = base_line("example model forward (GCNConv, BatchNorm, relu, GCNConv+relu, mean pool, Dense), algorithmic GB/s",
+                     b / (ms * 1e-3) / 1e9, ms, args, "config5_example_model:4096_graphs",
+                     {"graphs": 4096, "N": n, "E": e, "widths": "16-64-64-1"})
+    line["roofline"] = hbm_roofline(b / (ms * 1e-3) / 1e9, "whole chain (about 20 small launches)")
+    line["extra"] = {"graphs_per_s": 4096 / (ms * 1e-3), "batch_of_32_graphs_ms": results[32][0],
+                     "batch_of_32_graphs_per_s": 32 / (results[32][0] * 1e-3),
+                     "hip_graph_replay_ms": ms_graph, "batch_of_32_hip_graph_replay_ms": results[32][4],
+                     "note": "the batch of 32 graphs (1 600 nodes) is launch-latency bound"}
+    if not args.no_cpu_baseline:
+        import oracle
+        wl = synth.config5_example_model(num_graphs=4096)
+        t0 = time.perf_counter()
+        oracle.example_model_forward(wl.src, wl.dst, wl.num_nodes, wl.graph_indicator, 4096, wl.x, wl.params)
+        dt = time.perf_counter() - t0
+        line["cpu_baseline"] = {"value": b / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle", "seconds": dt,
+                                "sample": "the whole batch of 4 096 graphs, one pass"}
+    return line
+
+
 def run_batched(args, torch, gnn, synth):
     wl = synth.config3_batched()
     n, e, f, ng = wl.num_nodes, wl.num_edges, wl.x.shape[1], wl.num_graphs
@@ -499,7 +546,7 @@ def run_gcn_backward(args, torch, gnn, synth):
     return line
 
 
-WORKLOADS = {"gat_backward": run_gat_backward, "gcn_backward": run_gcn_backward, "backward": run_backward, "propagate": run_propagate, "csr": run_csr, "softmax": run_softmax, "gcn": run_gcn, "gat": run_gat,
+WORKLOADS = {"example": run_example, "gat_backward": run_gat_backward, "gcn_backward": run_gcn_backward, "backward": run_backward, "propagate": run_propagate, "csr": run_csr, "softmax": run_softmax, "gcn": run_gcn, "gat": run_gat,
              "batched": run_batched, "tiny": run_tiny}
 
 

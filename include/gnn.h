@@ -61,6 +61,7 @@ typedef enum {
 typedef enum { GNN_MSG_COPY_XJ = 0, GNN_MSG_E_MUL_XJ = 1, GNN_MSG_XJ_SUB_XI = 2, GNN_MSG_XI_DOT_XJ = 3 } gnn_msg_op;
 typedef enum { GNN_AGGR_SUM = 0, GNN_AGGR_MEAN = 1, GNN_AGGR_MAX = 2, GNN_AGGR_MIN = 3, GNN_AGGR_PROD = 4 } gnn_aggr;
 typedef enum { GNN_EDGE_ORDER_COO = 0, GNN_EDGE_ORDER_CSR = 1 } gnn_edge_order;
+typedef enum { GNN_ACT_NONE = 0, GNN_ACT_RELU = 1 } gnn_activation;
 
 const char *gnn_status_string(gnn_status s);
 
@@ -191,14 +192,15 @@ gnn_status gnn_propagate_backward(const gnn_graph *g, const gnn_graph *g_by_sour
  * propagate per section 3):   out = D^-1/2 (A [+ I]) D^-1/2 X W + b
  * with d_i = in-degree of i (+1 when add_self_loops != 0; one loop per node is
  * added without looking for loops already present); an edge j -> i carries
- * 1/sqrt(d_i d_j); a node with d = 0 contributes the coefficient 0.  No activation.
+ * 1/sqrt(d_i d_j); a node with d = 0 contributes the coefficient 0.  act = GNN_ACT_RELU applies
+ * max(., 0) to the result (the example's GCNConv(64 => 64, relu)), GNN_ACT_NONE leaves it.
  * d_x [N x f_in], d_w [f_in x f_out] row-major, d_bias [f_out] or NULL, d_out [N x f_out].
  * d_workspace: device scratch of at least gnn_gcnconv_workspace_bytes(N, f_out) bytes.
  */
 size_t gnn_gcnconv_workspace_bytes(int32_t num_nodes, int32_t f_out);
 gnn_status gnn_gcnconv(const gnn_graph *g, const float *d_x, int32_t f_in, const float *d_w,
-                       const float *d_bias, int32_t f_out, int32_t add_self_loops, float *d_out,
-                       void *d_workspace, size_t workspace_bytes, void *stream);
+                       const float *d_bias, int32_t f_out, int32_t add_self_loops, gnn_activation act,
+                       float *d_out, void *d_workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Backward of gnn_gcnconv: with Ahat the normalised (self-looped) adjacency of the forward call and
@@ -290,6 +292,39 @@ gnn_status gnn_graph_pool(const int32_t *d_graph_indicator, int32_t num_nodes, i
  */
 gnn_status gnn_gin_update(const gnn_graph *g, const float *d_x, int32_t feat_dim, float eps,
                           float *d_out, void *stream);
+
+/*
+ * The remaining layers of the paper's example model (section 3, "Training Example":
+ * GNNChain(GCNConv(16 => 64), BatchNorm(64), relu, GCNConv(64 => 64, relu), GlobalPool(mean), Dense(64, 1))).
+ *
+ * gnn_batchnorm: normalisation across the row (node) dimension,
+ *   out[i,f] = act(gamma[f] * (x[i,f] - mean[f]) / sqrt(var[f] + eps) + beta[f]),
+ * with mean / biased variance computed from the num_rows rows and WRITTEN to d_mean / d_var [feat_dim]
+ * (use_given_stats == 0), or READ from them (use_given_stats != 0: stored statistics; no workspace
+ * needed).  d_gamma / d_beta [feat_dim] may be NULL (1 and 0).  d_out may alias d_x.
+ *
+ * gnn_dense: out = act(X W + b), X [rows x k], W [k x n] row-major, b [n] or NULL.
+ *
+ * gnn_example_model_forward: the chain above on a collated batch: GCNConv(f0 => f1) with self-loops and
+ * bias, batch norm over all nodes of the batch (batch statistics) + relu, GCNConv(f1 => f2) + relu, mean
+ * pooling per graph (d_graph_indicator as for gnn_graph_pool), Dense(f2, f3).  d_y is [num_graphs x f3].
+ * It only sequences the entry points of this header on the caller's stream.
+ * Workspaces: at least the matching *_workspace_bytes(), 256-byte aligned.
+ */
+size_t gnn_batchnorm_workspace_bytes(int32_t num_rows, int32_t feat_dim);
+gnn_status gnn_batchnorm(const float *d_x, int32_t num_rows, int32_t feat_dim, const float *d_gamma,
+                         const float *d_beta, float eps, gnn_activation act, int32_t use_given_stats,
+                         float *d_mean, float *d_var, float *d_out, void *d_workspace,
+                         size_t workspace_bytes, void *stream);
+gnn_status gnn_dense(const float *d_x, int64_t rows, int32_t k, const float *d_w, int32_t n,
+                     const float *d_bias, gnn_activation act, float *d_out, void *stream);
+size_t gnn_example_model_workspace_bytes(int32_t num_nodes, int32_t num_graphs, int32_t f1, int32_t f2);
+gnn_status gnn_example_model_forward(const gnn_graph *g, const int32_t *d_graph_indicator,
+                                     int32_t num_graphs, const float *d_x, int32_t f0, const float *d_w1,
+                                     const float *d_b1, int32_t f1, const float *d_gamma,
+                                     const float *d_beta, float eps, const float *d_w2, const float *d_b2,
+                                     int32_t f2, const float *d_w3, const float *d_b3, int32_t f3,
+                                     float *d_y, void *d_workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Dense projection Z = X W on the matrix cores (fp32 MFMA, fp32 accumulate), the

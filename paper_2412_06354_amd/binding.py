@@ -45,7 +45,7 @@ SIGNATURES = {
     "gnn_propagate_backward": (_c.c_int, [_vp, _vp, _vp, _i32, _vp, _i32, _c.c_int, _c.c_int, _vp, _vp, _vp, _vp, _vp,
                                           _sz, _vp]),
     "gnn_gcnconv_workspace_bytes": (_sz, [_i32, _i32]),
-    "gnn_gcnconv": (_c.c_int, [_vp, _vp, _i32, _vp, _vp, _i32, _i32, _vp, _vp, _sz, _vp]),
+    "gnn_gcnconv": (_c.c_int, [_vp, _vp, _i32, _vp, _vp, _i32, _i32, _c.c_int, _vp, _vp, _sz, _vp]),
     "gnn_gcnconv_backward_workspace_bytes": (_sz, [_i32, _i32, _i32]),
     "gnn_gcnconv_backward": (_c.c_int, [_vp, _vp, _vp, _i32, _vp, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "gnn_segment_softmax": (_c.c_int, [_vp, _vp, _i32, _c.c_int, _vp, _vp]),
@@ -57,6 +57,12 @@ SIGNATURES = {
                                         _vp, _vp, _vp, _sz, _vp]),
     "gnn_graph_pool": (_c.c_int, [_vp, _i32, _i32, _vp, _i32, _c.c_int, _vp, _vp]),
     "gnn_gin_update": (_c.c_int, [_vp, _vp, _i32, _f32, _vp, _vp]),
+    "gnn_batchnorm_workspace_bytes": (_sz, [_i32, _i32]),
+    "gnn_batchnorm": (_c.c_int, [_vp, _i32, _i32, _vp, _vp, _f32, _c.c_int, _i32, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "gnn_dense": (_c.c_int, [_vp, _i64, _i32, _vp, _i32, _vp, _c.c_int, _vp, _vp]),
+    "gnn_example_model_workspace_bytes": (_sz, [_i32, _i32, _i32, _i32]),
+    "gnn_example_model_forward": (_c.c_int, [_vp, _vp, _i32, _vp, _i32, _vp, _vp, _i32, _vp, _vp, _f32, _vp, _vp, _i32,
+                                             _vp, _vp, _i32, _vp, _vp, _sz, _vp]),
     "gnn_dense_xw": (_c.c_int, [_vp, _i64, _i32, _vp, _i32, _vp, _vp, _vp]),
 }
 
@@ -279,9 +285,12 @@ def propagate_backward(g: Graph, g_by_source: Optional[Graph], x: torch.Tensor, 
     return grad_x, grad_e
 
 
+ACT_NONE, ACT_RELU = 0, 1
+
+
 def gcnconv(g: Graph, x: torch.Tensor, w: torch.Tensor, bias: Optional[torch.Tensor] = None,
             add_self_loops: bool = True, out: Optional[torch.Tensor] = None,
-            workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+            workspace: Optional[torch.Tensor] = None, relu: bool = False) -> torch.Tensor:
     n, f_in = x.shape
     f_out = int(w.shape[1])
     if n != g.num_nodes or w.shape[0] != f_in:
@@ -293,7 +302,8 @@ def gcnconv(g: Graph, x: torch.Tensor, w: torch.Tensor, bias: Optional[torch.Ten
         out = torch.empty((n, f_out), dtype=torch.float32, device=x.device)
     rc = lib().gnn_gcnconv(g._h, _dev(x, torch.float32, "x"), f_in, _dev(w, torch.float32, "w"),
                            _dev(bias, torch.float32, "bias"), f_out, 1 if add_self_loops else 0,
-                           _dev(out, torch.float32, "out"), workspace.data_ptr(), workspace.numel(), _stream())
+                           ACT_RELU if relu else ACT_NONE, _dev(out, torch.float32, "out"), workspace.data_ptr(),
+                           workspace.numel(), _stream())
     _check(rc, "gnn_gcnconv")
     return out
 
@@ -395,6 +405,65 @@ def gatconv_backward(g: Graph, g_by_source: Graph, x: torch.Tensor, w: torch.Ten
                                     gas.data_ptr(), gad.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream())
     _check(rc, "gnn_gatconv_backward")
     return gx, gw, gas, gad
+
+
+def batchnorm(x: torch.Tensor, gamma: Optional[torch.Tensor] = None, beta: Optional[torch.Tensor] = None,
+              eps: float = 1e-5, relu: bool = False, mean: Optional[torch.Tensor] = None,
+              var: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None):
+    """-> (out, mean, var); batch statistics unless both mean and var are given."""
+    n, f = x.shape
+    given = mean is not None and var is not None
+    if not given:
+        mean = torch.empty(f, dtype=torch.float32, device=x.device)
+        var = torch.empty(f, dtype=torch.float32, device=x.device)
+    if out is None:
+        out = torch.empty_like(x)
+    ws = torch.empty(max(int(lib().gnn_batchnorm_workspace_bytes(n, f)), 256), dtype=torch.uint8, device=x.device)
+    rc = lib().gnn_batchnorm(_dev(x, torch.float32, "x"), n, f, _dev(gamma, torch.float32, "gamma"),
+                             _dev(beta, torch.float32, "beta"), float(eps), ACT_RELU if relu else ACT_NONE,
+                             1 if given else 0, _dev(mean, torch.float32, "mean"), _dev(var, torch.float32, "var"),
+                             _dev(out, torch.float32, "out"), ws.data_ptr(), ws.numel(), _stream())
+    _check(rc, "gnn_batchnorm")
+    return out, mean, var
+
+
+def dense(x: torch.Tensor, w: torch.Tensor, bias: Optional[torch.Tensor] = None, relu: bool = False,
+          out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    rows, k = x.shape
+    if int(w.shape[0]) != k:
+        raise ValueError("shape mismatch")
+    n = int(w.shape[1])
+    if out is None:
+        out = torch.empty((rows, n), dtype=torch.float32, device=x.device)
+    rc = lib().gnn_dense(_dev(x, torch.float32, "x"), rows, k, _dev(w, torch.float32, "w"), n,
+                         _dev(bias, torch.float32, "bias"), ACT_RELU if relu else ACT_NONE,
+                         _dev(out, torch.float32, "out"), _stream())
+    _check(rc, "gnn_dense")
+    return out
+
+
+def example_model_forward(g: Graph, graph_indicator: torch.Tensor, num_graphs: int, x: torch.Tensor, params: dict,
+                          eps: float = 1e-5, out: Optional[torch.Tensor] = None,
+                          workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """params: device tensors w1 [f0,f1], b1, gamma, beta, w2 [f1,f2], b2, w3 [f2,f3], b3."""
+    n, f0 = x.shape
+    f1, f2, f3 = int(params["w1"].shape[1]), int(params["w2"].shape[1]), int(params["w3"].shape[1])
+    if (n != g.num_nodes or int(params["w1"].shape[0]) != f0 or int(params["w2"].shape[0]) != f1 or
+            int(params["w3"].shape[0]) != f2 or int(graph_indicator.shape[0]) != n):
+        raise ValueError("shape mismatch")
+    need = int(lib().gnn_example_model_workspace_bytes(n, num_graphs, f1, f2))
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+    if out is None:
+        out = torch.empty((num_graphs, f3), dtype=torch.float32, device=x.device)
+    t = lambda k: _dev(params.get(k), torch.float32, k)
+    rc = lib().gnn_example_model_forward(g._h, _dev(graph_indicator, torch.int32, "graph_indicator"), num_graphs,
+                                         _dev(x, torch.float32, "x"), f0, t("w1"), t("b1"), f1, t("gamma"), t("beta"),
+                                         float(eps), t("w2"), t("b2"), f2, t("w3"), t("b3"), f3,
+                                         _dev(out, torch.float32, "out"), workspace.data_ptr(), workspace.numel(),
+                                         _stream())
+    _check(rc, "gnn_example_model_forward")
+    return out
 
 
 def graph_pool(graph_indicator: torch.Tensor, num_graphs: int, x: torch.Tensor, aggr: int = AGGR_SUM,

@@ -6,7 +6,8 @@
 //   2. Z'[j,:] = dinv[j] * (X W)[j,:]      -- MFMA projection with the source-side factor fused in;
 //   3. out[i,:] = dinv[i] * (sum_{j->i} Z'[j,:] + [self-loop] Z'[i,:]) + b   -- the propagate kernel
 //      (copy_xj, sum) with the self-loop term, the destination-side factor and the bias applied in
-//      its epilogue, so the self-loops are never materialised as edges.
+//      its epilogue, so the self-loops are never materialised as edges; an optional relu (the
+//      example's GCNConv(64 => 64, relu)) is applied there too.
 #include "gnn_internal.h"
 
 namespace {
@@ -33,11 +34,12 @@ size_t gnn_gcnconv_workspace_bytes(int32_t num_nodes, int32_t f_out)
 }
 
 gnn_status gnn_gcnconv(const gnn_graph *g, const float *d_x, int32_t f_in, const float *d_w, const float *d_bias,
-                       int32_t f_out, int32_t add_self_loops, float *d_out, void *d_workspace,
-                       size_t workspace_bytes, void *stream)
+                       int32_t f_out, int32_t add_self_loops, gnn_activation act, float *d_out,
+                       void *d_workspace, size_t workspace_bytes, void *stream)
 {
     if (!g || !d_x || !d_w || !d_out || !d_workspace) return GNN_ERR_NULL;
     if (f_in <= 0 || f_out <= 0) return GNN_ERR_BAD_SIZE;
+    if (act != GNN_ACT_NONE && act != GNN_ACT_RELU) return GNN_ERR_BAD_SIZE;
     const int32_t N = g->num_nodes;
     if (workspace_bytes < gnn_gcnconv_workspace_bytes(N, f_out)) return GNN_ERR_BAD_SIZE;
     if (reinterpret_cast<uintptr_t>(d_workspace) & 255u) return GNN_ERR_BAD_SIZE;
@@ -54,6 +56,7 @@ gnn_status gnn_gcnconv(const gnn_graph *g, const float *d_x, int32_t f_in, const
     epi.self_scale = add_self_loops ? 1.0f : 0.0f;
     epi.row_scale = dinv;
     epi.bias = d_bias;
+    epi.relu = (act == GNN_ACT_RELU);
     return gnn_launch_propagate(g, z, f_out, nullptr, 1, GNN_EDGE_ORDER_CSR, GNN_MSG_COPY_XJ, 0, epi, d_out, s);
 }
 

@@ -89,13 +89,14 @@ size_t gnn_scan_tmp_elems(int64_t n);
 gnn_status gnn_scan_exclusive_i32(const int32_t *d_in, int32_t *d_out, int64_t n, bool append_total,
                                   int32_t *d_tmp, hipStream_t stream);
 
-// Epilogue applied to a finished row reduction:  out = post * (acc + self_scale * x[row]) + bias
+// Epilogue applied to a finished row reduction:  out = act(post * (acc + self_scale * x[row]) + bias)
 // with post = row_scale[row] (or 1), or acc / in-degree for the mean.
 struct gnn_epilogue {
     int mean = 0;                    // divide by the in-degree (0 stays 0)
     float self_scale = 0.f;          // adds self_scale * x[row,:] when non-zero
     const float *row_scale = nullptr;
     const float *bias = nullptr;
+    int relu = 0;                    // max(., 0) last
 };
 
 // Which row of `x` CSR position p gathers: x[colidx[p]] for node features (the default),

@@ -41,7 +41,7 @@ struct PropParams {
     float *out, *scratch;
     const int32_t *small_rows, *item_row, *item_start, *item_slot, *split_rows, *split_slot0;
     int32_t n_small, n_items, n_split, chunk, F, e_coo, item_blocks;
-    int32_t mean;
+    int32_t mean, relu;
     float self_scale;
     const float *row_scale, *bias;
     const int32_t *winners;   // [rows of x][F] winning edge id per element (routed kinds only)
@@ -157,6 +157,10 @@ __device__ __forceinline__ void finish_row(const PropParams &p, int row, int deg
     if (p.bias) {
 #pragma unroll
         for (int c = 0; c < VEC; ++c) acc.v[c] += p.bias[col + c];
+    }
+    if (p.relu) {
+#pragma unroll
+        for (int c = 0; c < VEC; ++c) acc.v[c] = fmaxf(acc.v[c], 0.0f);
     }
     store_row_stream<VEC>(p.out + (int64_t)row * p.F + col, acc);
 }
@@ -527,7 +531,7 @@ gnn_status gnn_launch_propagate(const gnn_graph *g, const float *d_x, int32_t fe
     p.n_small = g->n_small; p.n_items = g->n_items; p.n_split = g->n_split; p.chunk = g->chunk;
     p.F = F; p.e_coo = (e_order == GNN_EDGE_ORDER_COO) ? 1 : 0;
     p.item_blocks = (int32_t)gnn_div_up(g->n_items, kWavesPerBlock);
-    p.mean = epi.mean; p.self_scale = epi.self_scale; p.row_scale = epi.row_scale; p.bias = epi.bias;
+    p.mean = epi.mean; p.relu = epi.relu; p.self_scale = epi.self_scale; p.row_scale = epi.row_scale; p.bias = epi.bias;
     p.winners = d_winners;
 
     if (g->n_slots > 0) GNN_TRY(gnn_graph_reserve_scratch(g, (size_t)g->n_slots * F));

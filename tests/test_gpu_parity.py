@@ -447,6 +447,116 @@ def test_gcnconv_backward(gnn, loops, f_in, f_out):
     gt.close()
 
 
+@pytest.mark.parametrize("n,f", [(5000, 64), (300, 7), (70_000, 200), (1, 5)])
+def test_batchnorm(gnn, n, f):
+    x = (synth.normal_f32(71, 2, n * f).reshape(n, f) * (1.0 + np.arange(f, dtype=np.float32) % 5) + 2.0).astype(np.float32)
+    gamma = synth.uniform_f32(71, 3, f, 0.5, 1.5)
+    beta = synth.uniform_f32(71, 4, f, -1.0, 1.0)
+    for relu in (False, True):
+        ref, mean, var = oracle.batchnorm(x, gamma, beta, 1e-5, relu=relu)
+        got, gm, gv = gnn.batchnorm(dev(x), dev(gamma), dev(beta), 1e-5, relu=relu)
+        np.testing.assert_allclose(host(gm), mean, rtol=1e-5, atol=1e-6)
+        np.testing.assert_allclose(host(gv), var, rtol=1e-5, atol=1e-9)
+        # the terms behind an element: gamma * (x - mean) / sqrt(var + eps) and beta
+        inv = 1.0 / np.sqrt(var.astype(np.float64) + 1e-5)
+        sabs = np.abs(gamma) * inv * (np.abs(x) + np.abs(mean)) + np.abs(beta)
+        assert_close_sabs(host(got), ref, sabs, what=f"batchnorm {n}x{f} relu={relu}")
+    # stored statistics; no scale / shift
+    m0 = synth.uniform_f32(71, 5, f, -1.0, 1.0)
+    v0 = synth.uniform_f32(71, 6, f, 0.5, 2.0)
+    ref, _, _ = oracle.batchnorm(x, None, None, 1e-3, mean=m0, var=v0)
+    got, _, _ = gnn.batchnorm(dev(x), None, None, 1e-3, mean=dev(m0), var=dev(v0))
+    sabs = (np.abs(x) + np.abs(m0)) / np.sqrt(v0.astype(np.float64) + 1e-3)
+    assert_close_sabs(host(got), ref, sabs, what="batchnorm stored statistics")
+
+
+def test_dense_layer(gnn):
+    for rows, k, n in ((32, 64, 1), (4096, 64, 1), (1000, 16, 64), (77, 30, 5)):
+        x = synth.normal_f32(rows + n, 2, rows * k).reshape(rows, k)
+        w = synth.glorot_uniform(n, 4, k, n, (k, n))
+        b = synth.uniform_f32(n, 5, n, -1.0, 1.0)
+        for relu in (False, True):
+            ref, sabs = oracle.dense(x, w, b, relu=relu, with_sabs=True)
+            assert_close_sabs(host(gnn.dense(dev(x), dev(w), dev(b), relu=relu)), ref, sabs, what=f"dense {rows}x{k}x{n}")
+        ref, sabs = oracle.dense(x, w, with_sabs=True)
+        assert_close_sabs(host(gnn.dense(dev(x), dev(w))), ref, sabs, what="dense without bias")
+
+
+def test_example_model(gnn):
+    """Every stage of the example model against the oracle's stage, each fed the oracle's previous
+    intermediate (the strict per-operation bar); then the one-call chain, which runs the same kernels in
+    the same order and must reproduce the stage-by-stage GPU result bit for bit, and agrees with the
+    oracle's end-to-end prediction to 1e-4 (five stages of at most 1e-5 each, none of which amplifies:
+    the normalisation bounds the activations)."""
+    for kwargs in (dict(), dict(num_graphs=300, n=40, p=0.1)):
+        wl = synth.config5_example_model(**kwargs)
+        n, ng, p = wl.num_nodes, wl.num_graphs, wl.params
+        ref = oracle.example_model_forward(wl.src, wl.dst, n, wl.graph_indicator, ng, wl.x, p)
+        g = gnn.build_csr(dev(wl.src), dev(wl.dst), n)
+        dp = {k: dev(v) for k, v in p.items()}
+        gi = dev(wl.graph_indicator)
+        # stage by stage on the oracle's intermediates
+        r1, s1 = oracle.gcnconv(wl.src, wl.dst, n, wl.x, p["w1"], p["b1"], True, with_sabs=True)
+        assert_close_sabs(host(gnn.gcnconv(g, dev(wl.x), dp["w1"], dp["b1"], True)), r1, s1, what="stage 1")
+        got2, _, _ = gnn.batchnorm(dev(ref["h1"]), dp["gamma"], dp["beta"], 1e-5, relu=True)
+        inv = 1.0 / np.sqrt(ref["var"].astype(np.float64) + 1e-5)
+        s2 = np.abs(p["gamma"]) * inv * (np.abs(ref["h1"]) + np.abs(ref["mean"])) + np.abs(p["beta"])
+        assert_close_sabs(host(got2), ref["h2"], s2, what="stage 2")
+        r3, s3 = oracle.gcnconv(wl.src, wl.dst, n, ref["h2"], p["w2"], p["b2"], True, with_sabs=True)
+        assert_close_sabs(host(gnn.gcnconv(g, dev(ref["h2"]), dp["w2"], dp["b2"], True, relu=True)), np.maximum(r3, 0),
+                          s3, what="stage 3")
+        r4, s4 = oracle.graph_pool(wl.graph_indicator, ng, ref["h3"], AGGR_MEAN, with_sabs=True)
+        assert_close_sabs(host(gnn.graph_pool(gi, ng, dev(ref["h3"]), AGGR_MEAN)), r4, s4, what="stage 4")
+        r5, s5 = oracle.dense(ref["pooled"], p["w3"], p["b3"], with_sabs=True)
+        assert_close_sabs(host(gnn.dense(dev(ref["pooled"]), dp["w3"], dp["b3"])), r5, s5, what="stage 5")
+        # the chain
+        h1 = gnn.gcnconv(g, dev(wl.x), dp["w1"], dp["b1"], True)
+        h2, _, _ = gnn.batchnorm(h1, dp["gamma"], dp["beta"], 1e-5, relu=True)
+        h3 = gnn.gcnconv(g, h2, dp["w2"], dp["b2"], True, relu=True)
+        y_steps = gnn.dense(gnn.graph_pool(gi, ng, h3, AGGR_MEAN), dp["w3"], dp["b3"])
+        y = gnn.example_model_forward(g, gi, ng, dev(wl.x), dp)
+        assert torch.equal(y, y_steps)
+        err = np.abs(host(y).astype(np.float64) - ref["y"]).max()
+        assert err <= 1e-4 * np.abs(ref["y"]).max(), err
+        g.close()
+
+
+def test_example_model_hip_graph_replay(gnn):
+    """The chain only launches kernels once its scratch is reserved, so it can be captured into a HIP graph;
+    every replay (with eager work and synchronisation in between) must reproduce the eager result."""
+    wl = synth.config5_example_model()
+    n, ng = wl.num_nodes, wl.num_graphs
+    g = gnn.build_csr(dev(wl.src), dev(wl.dst), n)
+    dp = {k: dev(v) for k, v in wl.params.items()}
+    gi, x = dev(wl.graph_indicator), dev(wl.x)
+    f1, f2 = wl.params["w1"].shape[1], wl.params["w2"].shape[1]
+    ws = torch.empty(int(gnn.lib().gnn_example_model_workspace_bytes(n, ng, f1, f2)), dtype=torch.uint8, device="cuda")
+    y = torch.empty((ng, 1), dtype=torch.float32, device="cuda")
+    eager = gnn.example_model_forward(g, gi, ng, x, dp).clone()
+    gnn.example_model_forward(g, gi, ng, x, dp, out=y, workspace=ws)      # warm-up on the buffers to be captured
+    torch.cuda.synchronize()
+    gph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(gph):
+        gnn.example_model_forward(g, gi, ng, x, dp, out=y, workspace=ws)
+    for it in range(4):
+        y.fill_(float("nan"))
+        ws.random_(0, 255)                                                  # stale scratch must not matter
+        gph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y, eager), it
+        other = gnn.propagate(g, x, None, MSG_COPY_XJ, AGGR_SUM)            # eager work between replays
+        torch.cuda.synchronize()
+        assert bool(torch.isfinite(other).all())
+    # new inputs in the captured buffers are picked up by the next replay
+    x.mul_(0.5)
+    expect = gnn.example_model_forward(g, gi, ng, x, dp).clone()
+    gph.replay()
+    torch.cuda.synchronize()
+    assert torch.equal(y, expect)
+    del gph
+    g.close()
+
+
 @pytest.mark.parametrize("heads", [1, 8, 3])
 def test_segment_softmax(case, gnn, heads):
     name, wl, g = case
