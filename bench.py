@@ -127,6 +127,17 @@ def run_propagate(args, torch, gnn, synth):
             extra[name] = {"ms": t, "GBs_alg": b_alg_propagate(n, e, f, msg) / (t * 1e-3) / 1e9}
         t = time_calls(torch, lambda: gnn.propagate(g, x, ew, 1, 0, e_order=gnn.EDGE_ORDER_COO, out=out), k, 3)
         extra["e_mul_xj_sum_coo_order"] = {"ms": t, "GBs_alg": b_alg_propagate(n, e, f, 1) / (t * 1e-3) / 1e9}
+        if f % 8 == 0:
+            # bfloat16 feature storage (widened exactly, float sums, float output): not the headline -- another
+            # input precision -- reported to show what halving the gathered bytes buys
+            xh = gnn.f32_to_bf16(x)
+            for name, msg, aggr in (("bf16_storage_copy_xj_sum", 0, 0), ("bf16_storage_e_mul_xj_sum", 1, 0),
+                                    ("bf16_storage_copy_xj_max", 0, 2)):
+                ed = e_csr if msg else None
+                t = time_calls(torch, lambda: gnn.propagate_bf16(g, xh, ed, msg, aggr, e_order=gnn.EDGE_ORDER_CSR, out=out), k, 3)
+                b = e * (2 * f + 4 + 4 * msg) + n * 4 * f + (n + 1) * 4
+                extra[name] = {"ms": t, "GBs_alg": b / (t * 1e-3) / 1e9, "edge_feature_per_s": e * f / (t * 1e-3)}
+            del xh
         extra["edge_data_to_csr_ms"] = time_calls(torch, lambda: gnn.edge_data_to_csr(g, ew), k, 2)
         t0 = time.perf_counter()
         for _ in range(3):

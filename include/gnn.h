@@ -137,6 +137,20 @@ gnn_status gnn_propagate(const gnn_graph *g, const float *d_x, int32_t feat_dim,
                          gnn_msg_op msg, gnn_aggr aggr, float *d_out, void *stream);
 
 /*
+ * propagate over node features stored as bfloat16 (the upper 16 bits of a float; half the gather
+ * bytes of the float path).  Values are widened exactly, messages, sums and the result are float:
+ * the result equals gnn_propagate on the widened features up to summation order.
+ * msg = COPY_XJ or E_MUL_XJ with one float weight per edge (d_e [E], e_order as above), aggr = SUM,
+ * MEAN or MAX; anything else GNN_ERR_UNSUPPORTED, as are feat_dim % 8 != 0 or pointers that are not
+ * 16-byte aligned.  d_x_bf16 [N x feat_dim] uint16, d_out [N x feat_dim] float.
+ * gnn_f32_to_bf16 converts finite floats with round-to-nearest-even (ties to the even 16-bit code).
+ */
+gnn_status gnn_propagate_bf16(const gnn_graph *g, const uint16_t *d_x_bf16, int32_t feat_dim,
+                              const float *d_e, gnn_edge_order e_order, gnn_msg_op msg, gnn_aggr aggr,
+                              float *d_out, void *stream);
+gnn_status gnn_f32_to_bf16(const float *d_in, int64_t count, uint16_t *d_out, void *stream);
+
+/*
  * The two un-fused primitives of the paper's listing (section 3, "Message Passing"):
  *
  * apply_edges: one message row per edge,  m[k,:] = msg(x[dst[k],:], x[src[k],:], e[k,:])  with the

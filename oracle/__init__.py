@@ -311,6 +311,17 @@ def example_model_forward(src, dst, num_nodes: int, graph_indicator, num_graphs:
     return {"h1": h1, "h2": h2, "mean": mean, "var": var, "h3": h3, "pooled": pooled, "y": y}
 
 
+def round_bf16(x):
+    """-> (codes uint16, widened float32): finite floats rounded to bfloat16, ties to even."""
+    x = _f32(x, "x")
+    flat = np.ascontiguousarray(x.reshape(-1))
+    codes = np.empty(flat.shape, np.uint16)
+    wide = np.empty(flat.shape, np.float32)
+    rc = _load().oracle_round_bf16(_p(flat), ctypes.c_int64(flat.shape[0]), _p(codes), _p(wide))
+    _check(rc, "round_bf16")
+    return codes.reshape(x.shape), wide.reshape(x.shape)
+
+
 def gin_update(src, dst, num_nodes: int, x, eps: float = 0.0, with_sabs: bool = False):
     src, dst, x = _i32(src, "src"), _i32(dst, "dst"), _f32(x, "x")
     ne, f = src.shape[0], x.shape[1]

@@ -831,6 +831,36 @@ int oracle_batchnorm(const float *x, int32_t N, int32_t F, const float *gamma, c
 }
 
 /*
+ * bfloat16 storage of features (16-bit codes = sign, 8 exponent bits, 7 fraction bits: the upper half of
+ * the IEEE binary32 encoding).  Finite inputs are rounded to the nearest representable value, ties to
+ * the code with an even last bit; this is written out by cases rather than as an integer trick:
+ *   lower = the float with the low 16 bits cleared (truncation towards zero), upper = the next code
+ *   away from zero; the one nearer to x wins, a tie goes to the even code.
+ * codes (may be NULL) receives the 16-bit codes, widened (may be NULL) the rounded values as floats.
+ */
+int oracle_round_bf16(const float *x, int64_t n, uint16_t *codes, float *widened)
+{
+    if (n < 0) return 2;
+    for (int64_t i = 0; i < n; ++i) {
+        uint32_t u;
+        memcpy(&u, &x[i], 4);
+        uint32_t lo_bits = u & 0xffff0000u, hi_bits = lo_bits + 0x10000u;   /* same sign, next magnitude */
+        float lo, hi;
+        memcpy(&lo, &lo_bits, 4);
+        memcpy(&hi, &hi_bits, 4);
+        double hv = isinf(hi) ? copysign(ldexp(1.0, 128), (double)hi) : (double)hi;   /* the value the code after the
+                                                                                          largest finite one would have */
+        double dl = fabs((double)x[i] - (double)lo), dh = fabs(hv - (double)x[i]);
+        uint32_t pick = lo_bits;
+        if (dh < dl) pick = hi_bits;
+        else if (dh == dl && ((lo_bits >> 16) & 1u)) pick = hi_bits;
+        if (codes) codes[i] = (uint16_t)(pick >> 16);
+        if (widened) memcpy(&widened[i], &pick, 4);
+    }
+    return 0;
+}
+
+/*
  * GIN-style node update without the MLP:  out[i,:] = (1 + eps) x[i,:] + sum_{j->i} x[j,:].
  */
 int oracle_gin_update(const int32_t *src, const int32_t *dst, int64_t E, int32_t N,

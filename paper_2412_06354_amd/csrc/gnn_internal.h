@@ -110,6 +110,7 @@ enum gnn_reduce { GNN_REDUCE_SUM = 0, GNN_REDUCE_MAX = 1, GNN_REDUCE_MIN = 2, GN
 // d_winners (optional, sum only, edge data in the caller's order): [rows of x][feat_dim] edge ids; a
 // gathered element x[j,f] only contributes to the edge whose id equals d_winners[j,f] (the routing
 // step of a max aggregation's backward pass).
+// x_is_bf16: d_x points to bfloat16 values (copy_xj or one weight per edge, sum / mean / max, feat_dim % 8 == 0).
 // Shared launcher behind gnn_propagate / gnn_aggregate_neighbors / gnn_gin_update / the sparse half
 // of gnn_gcnconv.
 gnn_status gnn_launch_propagate(const gnn_graph *g, const float *d_x, int32_t feat_dim,
@@ -117,7 +118,7 @@ gnn_status gnn_launch_propagate(const gnn_graph *g, const float *d_x, int32_t fe
                                 gnn_msg_op msg, int reduce, const gnn_epilogue &epi,
                                 float *d_out, hipStream_t stream,
                                 gnn_gather_index gather = GNN_GATHER_SOURCE_NODE,
-                                const int32_t *d_winners = nullptr);
+                                const int32_t *d_winners = nullptr, int x_is_bf16 = 0);
 
 // out[k] = <x[src[k],:], y[dst[k],:]> per edge, in the order out_order names (backward.hip)
 gnn_status gnn_launch_edge_dot(const gnn_graph *g, const float *d_x_src, const float *d_y_dst, int32_t feat_dim,

@@ -57,7 +57,11 @@ struct Row {
 template <int VEC>
 __device__ __forceinline__ void load_row(Row<VEC> &r, const float *__restrict__ p)
 {
-    if constexpr (VEC == 4) {
+    if constexpr (VEC == 8) {
+        const v4f t = reinterpret_cast<const v4f *>(p)[0], u = reinterpret_cast<const v4f *>(p)[1];
+        r.v[0] = t.x; r.v[1] = t.y; r.v[2] = t.z; r.v[3] = t.w;
+        r.v[4] = u.x; r.v[5] = u.y; r.v[6] = u.z; r.v[7] = u.w;
+    } else if constexpr (VEC == 4) {
         const v4f t = *reinterpret_cast<const v4f *>(p);
         r.v[0] = t.x; r.v[1] = t.y; r.v[2] = t.z; r.v[3] = t.w;
     } else {
@@ -70,7 +74,12 @@ __device__ __forceinline__ void load_row(Row<VEC> &r, const float *__restrict__ 
 template <int VEC>
 __device__ __forceinline__ void load_row_stream(Row<VEC> &r, const float *__restrict__ p)
 {
-    if constexpr (VEC == 4) {
+    if constexpr (VEC == 8) {
+        const v4f t = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(p));
+        const v4f u = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(p) + 1);
+        r.v[0] = t.x; r.v[1] = t.y; r.v[2] = t.z; r.v[3] = t.w;
+        r.v[4] = u.x; r.v[5] = u.y; r.v[6] = u.z; r.v[7] = u.w;
+    } else if constexpr (VEC == 4) {
         const v4f t = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(p));
         r.v[0] = t.x; r.v[1] = t.y; r.v[2] = t.z; r.v[3] = t.w;
     } else {
@@ -81,7 +90,11 @@ __device__ __forceinline__ void load_row_stream(Row<VEC> &r, const float *__rest
 template <int VEC>
 __device__ __forceinline__ void store_row(float *__restrict__ p, const Row<VEC> &r)
 {
-    if constexpr (VEC == 4) {
+    if constexpr (VEC == 8) {
+        v4f t = {r.v[0], r.v[1], r.v[2], r.v[3]}, u = {r.v[4], r.v[5], r.v[6], r.v[7]};
+        reinterpret_cast<v4f *>(p)[0] = t;
+        reinterpret_cast<v4f *>(p)[1] = u;
+    } else if constexpr (VEC == 4) {
         v4f t = {r.v[0], r.v[1], r.v[2], r.v[3]};
         *reinterpret_cast<v4f *>(p) = t;
     } else {
@@ -92,11 +105,41 @@ __device__ __forceinline__ void store_row(float *__restrict__ p, const Row<VEC> 
 template <int VEC>
 __device__ __forceinline__ void store_row_stream(float *__restrict__ p, const Row<VEC> &r)
 {
-    if constexpr (VEC == 4) {
+    if constexpr (VEC == 8) {
+        v4f t = {r.v[0], r.v[1], r.v[2], r.v[3]}, u = {r.v[4], r.v[5], r.v[6], r.v[7]};
+        __builtin_nontemporal_store(t, reinterpret_cast<v4f *>(p));
+        __builtin_nontemporal_store(u, reinterpret_cast<v4f *>(p) + 1);
+    } else if constexpr (VEC == 4) {
         v4f t = {r.v[0], r.v[1], r.v[2], r.v[3]};
         __builtin_nontemporal_store(t, reinterpret_cast<v4f *>(p));
     } else {
         __builtin_nontemporal_store(r.v[0], p);
+    }
+}
+
+// Features x[elem ..].  XB = 1: the array holds bfloat16 (the upper half of a float), eight per 128-bit
+// load; load_x only issues the load and keeps the four raw words (so that the loads of several edges stay
+// in flight together), x_value widens value c exactly when it is used.  Sums and results stay in float.
+template <int VEC, int XB>
+__device__ __forceinline__ void load_x(Row<VEC> &r, const float *__restrict__ x, int64_t elem)
+{
+    if constexpr (XB == 0) {
+        load_row<VEC>(r, x + elem);
+    } else {
+        static_assert(VEC == 8, "bfloat16 rows are read eight values at a time");
+        const v4f w = *reinterpret_cast<const v4f *>(reinterpret_cast<const uint16_t *>(x) + elem);
+        r.v[0] = w.x; r.v[1] = w.y; r.v[2] = w.z; r.v[3] = w.w;
+    }
+}
+
+template <int VEC, int XB>
+__device__ __forceinline__ float x_value(const Row<VEC> &r, int c)
+{
+    if constexpr (XB == 0) {
+        return r.v[c];
+    } else {
+        const uint32_t w = __float_as_uint(r.v[c >> 1]);
+        return __uint_as_float((c & 1) ? (w & 0xffff0000u) : (w << 16));
     }
 }
 
@@ -127,7 +170,7 @@ __device__ __forceinline__ void combine(Row<VEC> &acc, const Row<VEC> &m)
 }
 
 // Finishes one output row slice (VEC features starting at col) and stores it.
-template <int VEC, int RED>
+template <int VEC, int RED, int XB = 0>
 __device__ __forceinline__ void finish_row(const PropParams &p, int row, int deg, int col, Row<VEC> acc)
 {
     if constexpr (RED == kRedMin) {
@@ -145,9 +188,9 @@ __device__ __forceinline__ void finish_row(const PropParams &p, int row, int deg
     }
     if (p.self_scale != 0.0f) {
         Row<VEC> xs;
-        load_row<VEC>(xs, p.x + (int64_t)row * p.F + col);
+        load_x<VEC, XB>(xs, p.x, (int64_t)row * p.F + col);
 #pragma unroll
-        for (int c = 0; c < VEC; ++c) acc.v[c] = fmaf(p.self_scale, xs.v[c], acc.v[c]);
+        for (int c = 0; c < VEC; ++c) acc.v[c] = fmaf(p.self_scale, x_value<VEC, XB>(xs, c), acc.v[c]);
     }
     if (p.row_scale) {
         const float s = p.row_scale[row];
@@ -168,30 +211,30 @@ __device__ __forceinline__ void finish_row(const PropParams &p, int row, int deg
 // Issues the loads of one gathered message: x[j, col..] and, for element-wise edge data, e[eid, col..].
 // Nothing is computed here, so that the loads of several edges are in flight together; the
 // message op is applied afterwards by apply_message.
-template <int VEC, int MSG>
+template <int VEC, int MSG, int XB = 0>
 __device__ __forceinline__ void fetch_message(const PropParams &p, bool ok, int j, int eid, int col, Row<VEC> &xv,
                                               Row<VEC> &ev, Row<VEC> &wv)
 {
 #pragma unroll
     for (int c = 0; c < VEC; ++c) { xv.v[c] = 0.0f; ev.v[c] = 0.0f; wv.v[c] = 0.0f; }
     if (ok) {
-        load_row<VEC>(xv, p.x + (int64_t)j * p.F + col);
+        load_x<VEC, XB>(xv, p.x, (int64_t)j * p.F + col);
         if constexpr (msg_base(MSG) == kMsgMulVector) load_row_stream<VEC>(ev, p.e + (int64_t)eid * p.F + col);
         if constexpr (msg_routed(MSG))   // winner ids travel as raw bits in a float row
             load_row<VEC>(wv, reinterpret_cast<const float *>(p.winners) + (int64_t)j * p.F + col);
     }
 }
 
-template <int VEC, int MSG, int RED>
+template <int VEC, int MSG, int RED, int XB = 0>
 __device__ __forceinline__ void apply_message(Row<VEC> &acc, bool ok, const Row<VEC> &xv, float w, const Row<VEC> &ev,
                                               const Row<VEC> &wv, int eid, const Row<VEC> &xi)
 {
 #pragma unroll
     for (int c = 0; c < VEC; ++c) {
-        float m = xv.v[c];
+        float m = x_value<VEC, XB>(xv, c);
         if constexpr (msg_base(MSG) == kMsgMulScalar) m = w * m;
         if constexpr (msg_base(MSG) == kMsgMulVector) m = ev.v[c] * m;
-        if constexpr (msg_base(MSG) == kMsgSubTarget) m = m - xi.v[c];
+        if constexpr (msg_base(MSG) == kMsgSubTarget) m = m - x_value<VEC, XB>(xi, c);
         if constexpr (msg_routed(MSG)) m = (__float_as_int(wv.v[c]) == eid) ? m : 0.0f;
         if constexpr (RED == kRedMin) m = -m;
         if constexpr (red_is_max(RED))
@@ -205,7 +248,7 @@ __device__ __forceinline__ void apply_message(Row<VEC> &acc, bool ok, const Row<
     }
 }
 
-template <int LPR, int VEC, int MSG, int RED>
+template <int LPR, int VEC, int MSG, int RED, int XB>
 __device__ __forceinline__ void short_rows(const PropParams &p, int block)
 {
     constexpr int NSG = 64 / LPR;
@@ -231,7 +274,7 @@ __device__ __forceinline__ void short_rows(const PropParams &p, int block)
         set_identity<VEC, RED>(acc);
         set_identity<VEC, kRedSum>(xi);
         if constexpr (msg_base(MSG) == kMsgSubTarget)
-            if (colok) load_row<VEC>(xi, p.x + (int64_t)row * p.F + col);
+            if (colok) load_x<VEC, XB>(xi, p.x, (int64_t)row * p.F + col);
         for (int base = 0; base < wmax; base += LPR) {
             int my_j = 0, my_eid = 0;
             float my_w = 0.0f;
@@ -258,18 +301,18 @@ __device__ __forceinline__ void short_rows(const PropParams &p, int block)
                     if constexpr (msg_base(MSG) == kMsgMulScalar) w[u] = __shfl(my_w, t, LPR);
                     if constexpr (msg_base(MSG) == kMsgMulVector || msg_routed(MSG)) eid[u] = __shfl(my_eid, t, LPR);
                     ok[u] = colok && (base + t < deg);
-                    fetch_message<VEC, MSG>(p, ok[u], j, eid[u], col, xv[u], ev[u], wv[u]);
+                    fetch_message<VEC, MSG, XB>(p, ok[u], j, eid[u], col, xv[u], ev[u], wv[u]);
                 }
 #pragma unroll
                 for (int u = 0; u < U; ++u)
-                    apply_message<VEC, MSG, RED>(acc, ok[u], xv[u], w[u], ev[u], wv[u], eid[u], xi);
+                    apply_message<VEC, MSG, RED, XB>(acc, ok[u], xv[u], w[u], ev[u], wv[u], eid[u], xi);
             }
         }
-        if (colok) finish_row<VEC, RED>(p, row, deg, col, acc);
+        if (colok) finish_row<VEC, RED, XB>(p, row, deg, col, acc);
     }
 }
 
-template <int LPR, int VEC, int MSG, int RED>
+template <int LPR, int VEC, int MSG, int RED, int XB>
 __device__ __forceinline__ void long_row_pieces(const PropParams &p, int block)
 {
     constexpr int NSG = 64 / LPR;
@@ -291,7 +334,7 @@ __device__ __forceinline__ void long_row_pieces(const PropParams &p, int block)
         set_identity<VEC, RED>(acc);
         set_identity<VEC, kRedSum>(xi);
         if constexpr (msg_base(MSG) == kMsgSubTarget)
-            if (colok) load_row<VEC>(xi, p.x + (int64_t)row * p.F + col);
+            if (colok) load_x<VEC, XB>(xi, p.x, (int64_t)row * p.F + col);
         for (int base = start; base < end; base += 64) {
             const int n = min(64, end - base);
             int my_j = 0, my_eid = 0;
@@ -319,11 +362,11 @@ __device__ __forceinline__ void long_row_pieces(const PropParams &p, int block)
                     if constexpr (msg_base(MSG) == kMsgMulScalar) w[u] = __shfl(my_w, pos, 64);
                     if constexpr (msg_base(MSG) == kMsgMulVector || msg_routed(MSG)) eid[u] = __shfl(my_eid, pos, 64);
                     ok[u] = colok && pos < n;
-                    fetch_message<VEC, MSG>(p, ok[u], j, eid[u], col, xv[u], ev[u], wv[u]);
+                    fetch_message<VEC, MSG, XB>(p, ok[u], j, eid[u], col, xv[u], ev[u], wv[u]);
                 }
 #pragma unroll
                 for (int u = 0; u < U; ++u)
-                    apply_message<VEC, MSG, RED>(acc, ok[u], xv[u], w[u], ev[u], wv[u], eid[u], xi);
+                    apply_message<VEC, MSG, RED, XB>(acc, ok[u], xv[u], w[u], ev[u], wv[u], eid[u], xi);
             }
         }
 #pragma unroll
@@ -335,7 +378,7 @@ __device__ __forceinline__ void long_row_pieces(const PropParams &p, int block)
         }
         if (sg == 0 && colok) {
             if (slot < 0)
-                finish_row<VEC, RED>(p, row, row_end - row_start, col, acc);
+                finish_row<VEC, RED, XB>(p, row, row_end - row_start, col, acc);
             else
                 store_row<VEC>(p.scratch + (int64_t)slot * p.F + col, acc);
         }
@@ -344,19 +387,19 @@ __device__ __forceinline__ void long_row_pieces(const PropParams &p, int block)
 
 // Blocks [0, item_blocks) take the long-row pieces (scheduled first: they are the heaviest),
 // the remaining blocks take the short rows.
-template <int LPR, int VEC, int MSG, int RED>
+template <int LPR, int VEC, int MSG, int RED, int XB = 0>
 __global__ __launch_bounds__(kThreads) void propagate_kernel(const PropParams p)
 {
     if ((int)blockIdx.x < p.item_blocks)
-        long_row_pieces<LPR, VEC, MSG, RED>(p, blockIdx.x);
+        long_row_pieces<LPR, VEC, MSG, RED, XB>(p, blockIdx.x);
     else
-        short_rows<LPR, VEC, MSG, RED>(p, blockIdx.x - p.item_blocks);
+        short_rows<LPR, VEC, MSG, RED, XB>(p, blockIdx.x - p.item_blocks);
 }
 
 // Combines the per-piece partial rows of split rows: one wavefront per split row, its sub-groups
 // take the pieces round-robin (four loads in flight each) and are folded with xor-shuffles; the
 // order of combination is a fixed function of the piece count.
-template <int LPR, int VEC, int RED>
+template <int LPR, int VEC, int RED, int XB = 0>
 __global__ __launch_bounds__(kThreads) void combine_pieces_kernel(const PropParams p)
 {
     constexpr int NSG = 64 / LPR;
@@ -392,7 +435,7 @@ __global__ __launch_bounds__(kThreads) void combine_pieces_kernel(const PropPara
             for (int c = 0; c < VEC; ++c) other.v[c] = __shfl_xor(acc.v[c], off, 64);
             combine<VEC, RED>(acc, other);
         }
-        if (sg == 0 && colok) finish_row<VEC, RED>(p, row, deg, col, acc);
+        if (sg == 0 && colok) finish_row<VEC, RED, XB>(p, row, deg, col, acc);
     }
 }
 
@@ -435,20 +478,20 @@ __global__ __launch_bounds__(kThreads) void apply_edges_kernel(const int32_t *__
     }
 }
 
-template <int LPR, int VEC, int MSG, int RED>
+template <int LPR, int VEC, int MSG, int RED, int XB = 0>
 gnn_status launch_typed(const PropParams &p, hipStream_t stream)
 {
     constexpr int NSG = 64 / LPR;
     const int64_t small_blocks = gnn_div_up(p.n_small, kWavesPerBlock * NSG);
     const int64_t blocks = p.item_blocks + small_blocks;
     if (blocks > 0) {
-        hipLaunchKernelGGL((propagate_kernel<LPR, VEC, MSG, RED>), dim3((unsigned)blocks), dim3(kThreads), 0, stream,
+        hipLaunchKernelGGL((propagate_kernel<LPR, VEC, MSG, RED, XB>), dim3((unsigned)blocks), dim3(kThreads), 0, stream,
                            p);
         GNN_LAUNCH_CHECK();
     }
     if (p.n_split > 0) {
         const int64_t cblocks = gnn_div_up(p.n_split, kWavesPerBlock);
-        hipLaunchKernelGGL((combine_pieces_kernel<LPR, VEC, RED>), dim3((unsigned)cblocks), dim3(kThreads), 0, stream,
+        hipLaunchKernelGGL((combine_pieces_kernel<LPR, VEC, RED, XB>), dim3((unsigned)cblocks), dim3(kThreads), 0, stream,
                            p);
         GNN_LAUNCH_CHECK();
     }
@@ -485,6 +528,30 @@ gnn_status launch_shape(const PropParams &p, int msg, int red, hipStream_t strea
     return GNN_ERR_BAD_SIZE;
 }
 
+// Round-to-nearest-even conversion of finite floats to bfloat16 (the upper 16 bits of the float encoding).
+__global__ __launch_bounds__(kThreads) void f32_to_bf16_kernel(const float *__restrict__ in, int64_t n,
+                                                               uint16_t *__restrict__ out)
+{
+    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += stride) {
+        const uint32_t u = __float_as_uint(in[i]);
+        out[i] = (uint16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
+    }
+}
+
+// bfloat16 feature storage: copy_xj / one weight per edge, sum (mean) / max.
+template <int LPR>
+gnn_status launch_shape_bf16(const PropParams &p, int msg, int red, hipStream_t stream)
+{
+    switch (msg * 4 + red) {
+    case kMsgCopy * 4 + kRedSum: return launch_typed<LPR, 8, kMsgCopy, kRedSum, 1>(p, stream);
+    case kMsgCopy * 4 + kRedMax: return launch_typed<LPR, 8, kMsgCopy, kRedMax, 1>(p, stream);
+    case kMsgMulScalar * 4 + kRedSum: return launch_typed<LPR, 8, kMsgMulScalar, kRedSum, 1>(p, stream);
+    case kMsgMulScalar * 4 + kRedMax: return launch_typed<LPR, 8, kMsgMulScalar, kRedMax, 1>(p, stream);
+    }
+    return GNN_ERR_UNSUPPORTED;
+}
+
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 bool valid_aggr(gnn_aggr a) { return a >= GNN_AGGR_SUM && a <= GNN_AGGR_PROD; }
@@ -504,7 +571,7 @@ int reduce_of(gnn_aggr a)
 gnn_status gnn_launch_propagate(const gnn_graph *g, const float *d_x, int32_t feat_dim, const float *d_e,
                                 int32_t e_dim, gnn_edge_order e_order, gnn_msg_op msg, int reduce,
                                 const gnn_epilogue &epi, float *d_out, hipStream_t stream, gnn_gather_index gather,
-                                const int32_t *d_winners)
+                                const int32_t *d_winners, int x_is_bf16)
 {
     const int F = feat_dim;
     int kmsg = kMsgCopy;
@@ -537,6 +604,14 @@ gnn_status gnn_launch_propagate(const gnn_graph *g, const float *d_x, int32_t fe
     if (g->n_slots > 0) GNN_TRY(gnn_graph_reserve_scratch(g, (size_t)g->n_slots * F));
     p.scratch = g->scratch;
 
+    if (x_is_bf16) {
+        if (F % 8 != 0 || !aligned16(d_x) || !aligned16(d_out) || d_winners) return GNN_ERR_UNSUPPORTED;
+        const int cols = F / 8;
+        if (cols <= 8) return launch_shape_bf16<8>(p, kmsg, red, stream);
+        if (cols <= 16) return launch_shape_bf16<16>(p, kmsg, red, stream);
+        if (cols <= 32) return launch_shape_bf16<32>(p, kmsg, red, stream);
+        return launch_shape_bf16<64>(p, kmsg, red, stream);
+    }
     const bool vec4 = (F % 4 == 0) && aligned16(d_x) && aligned16(d_out) &&
                       (msg_base(kmsg) != kMsgMulVector || aligned16(d_e)) && aligned16(d_winners);
     if (vec4) {
@@ -568,6 +643,38 @@ gnn_status gnn_propagate(const gnn_graph *g, const float *d_x, int32_t feat_dim,
     epi.mean = (aggr == GNN_AGGR_MEAN);
     return gnn_launch_propagate(g, d_x, feat_dim, d_e, e_dim, e_order, msg, reduce_of(aggr), epi, d_out,
                                 static_cast<hipStream_t>(stream));
+}
+
+gnn_status gnn_propagate_bf16(const gnn_graph *g, const uint16_t *d_x_bf16, int32_t feat_dim, const float *d_e,
+                              gnn_edge_order e_order, gnn_msg_op msg, gnn_aggr aggr, float *d_out, void *stream)
+{
+    if (!g || !d_x_bf16 || !d_out) return GNN_ERR_NULL;
+    if (feat_dim <= 0) return GNN_ERR_BAD_SIZE;
+    if (!valid_aggr(aggr)) return GNN_ERR_BAD_SIZE;
+    if (msg < GNN_MSG_COPY_XJ || msg > GNN_MSG_XI_DOT_XJ) return GNN_ERR_BAD_SIZE;
+    if ((msg != GNN_MSG_COPY_XJ && msg != GNN_MSG_E_MUL_XJ) || aggr == GNN_AGGR_MIN || aggr == GNN_AGGR_PROD)
+        return GNN_ERR_UNSUPPORTED;
+    if (msg == GNN_MSG_E_MUL_XJ) {
+        if (e_order != GNN_EDGE_ORDER_COO && e_order != GNN_EDGE_ORDER_CSR) return GNN_ERR_BAD_SIZE;
+        if (!d_e && g->num_edges > 0) return GNN_ERR_NULL;
+    }
+    gnn_epilogue epi;
+    epi.mean = (aggr == GNN_AGGR_MEAN);
+    return gnn_launch_propagate(g, reinterpret_cast<const float *>(d_x_bf16), feat_dim, d_e, 1, e_order, msg,
+                                reduce_of(aggr), epi, d_out, static_cast<hipStream_t>(stream),
+                                GNN_GATHER_SOURCE_NODE, nullptr, 1);
+}
+
+gnn_status gnn_f32_to_bf16(const float *d_in, int64_t count, uint16_t *d_out, void *stream)
+{
+    if (count < 0) return GNN_ERR_BAD_SIZE;
+    if (count == 0) return GNN_OK;
+    if (!d_in || !d_out) return GNN_ERR_NULL;
+    const int blocks = (int)std::min<int64_t>(gnn_div_up(count, kThreads), 256 * 64);
+    hipLaunchKernelGGL(f32_to_bf16_kernel, dim3(blocks), dim3(kThreads), 0, static_cast<hipStream_t>(stream), d_in,
+                       count, d_out);
+    GNN_LAUNCH_CHECK();
+    return GNN_OK;
 }
 
 gnn_status gnn_apply_edges(const gnn_graph *g, const float *d_x, int32_t feat_dim, const float *d_e, int32_t e_dim,

@@ -275,6 +275,58 @@ def test_unsupported_backward_combinations(gnn):
     gt.close()
 
 
+def test_f32_to_bf16_bit_exact(gnn, golden_dir):
+    gd = load_golden(golden_dir, "bf16_rounding.json")
+    bits = np.array([int(c["float_bits"], 16) for c in gd["cases"]], np.uint32)
+    x = np.concatenate([bits.view(np.float32),
+                        (synth.normal_f32(98, 2, 100_003) * np.float32(10.0) ** synth.randint(98, 3, 0, 100_003, -30, 30)
+                         ).astype(np.float32)])
+    codes, _ = oracle.round_bf16(x)
+    got = host(gnn.f32_to_bf16(dev(x))).view(np.uint16)
+    np.testing.assert_array_equal(got, codes)
+
+
+@pytest.mark.parametrize("msg", [MSG_COPY_XJ, MSG_E_MUL_XJ])
+@pytest.mark.parametrize("aggr", [AGGR_SUM, AGGR_MEAN, AGGR_MAX])
+def test_propagate_bf16_storage(case, gnn, msg, aggr):
+    """Features stored as bfloat16, widened exactly, float arithmetic: the reference is the oracle's propagate
+    on the oracle-rounded features, at the usual bar (max bit for bit)."""
+    name, wl, g = case
+    f = wl.x.shape[1]
+    if f % 8 != 0:
+        pytest.skip("bfloat16 rows are read eight values at a time")
+    codes, wide = oracle.round_bf16(wl.x)
+    e = wl.edge_weight if msg == MSG_E_MUL_XJ else None
+    ref, sabs = oracle.propagate(wl.src, wl.dst, wl.num_nodes, wide, e, msg, aggr, with_sabs=True)
+    xh = gnn.f32_to_bf16(dev(wl.x))
+    np.testing.assert_array_equal(host(xh).view(np.uint16), codes)
+    got = host(gnn.propagate_bf16(g, xh, dev(e) if e is not None else None, msg, aggr))
+    if aggr == AGGR_MAX:
+        np.testing.assert_array_equal(got.view(np.uint32), ref.view(np.uint32))
+    else:
+        assert_close_sabs(got, ref, sabs, what=f"{name} bf16 msg={msg} aggr={aggr}")
+    if aggr == AGGR_MAX:     # the float path on the widened features gives the same maxima
+        same = host(gnn.propagate(g, dev(wide), dev(e) if e is not None else None, msg, aggr))
+        np.testing.assert_array_equal(got.view(np.uint32), same.view(np.uint32))
+
+
+def test_propagate_bf16_wide_rows_and_rejections(gnn):
+    wl = powerlaw(3000, 60_000, 256, 1500.0)
+    g = gnn.build_csr(dev(wl.src), dev(wl.dst), wl.num_nodes, 8, 128)
+    codes, wide = oracle.round_bf16(wl.x)
+    ref, sabs = oracle.propagate(wl.src, wl.dst, wl.num_nodes, wide, None, MSG_COPY_XJ, AGGR_SUM, with_sabs=True)
+    xh = dev(codes.view(np.int16))
+    assert_close_sabs(host(gnn.propagate_bf16(g, xh, None, MSG_COPY_XJ, AGGR_SUM)), ref, sabs, what="bf16 F=256")
+    for msg, aggr in ((MSG_XJ_SUB_XI, AGGR_SUM), (MSG_COPY_XJ, AGGR_MIN)):
+        with pytest.raises(gnn.GnnError) as err:
+            gnn.propagate_bf16(g, xh, None, msg, aggr)
+        assert err.value.code == 4
+    with pytest.raises(gnn.GnnError) as err:      # feat_dim % 8 != 0
+        gnn.propagate_bf16(g, xh[:, :12].contiguous(), None, MSG_COPY_XJ, AGGR_SUM)
+    assert err.value.code == 4
+    g.close()
+
+
 def test_apply_edges_elementwise_and_odd_width(gnn):
     wl = powerlaw(2000, 30_000, 6, 900.0)
     g = gnn.build_csr(dev(wl.src), dev(wl.dst), wl.num_nodes, 4, 64)

@@ -687,6 +687,27 @@ def test_example_model_against_dense_float64():
     assert res["y"].shape == (g_cnt, 1)
 
 
+def test_bf16_rounding(golden_dir):
+    """Hand-worked bit patterns, and on random floats the defining property: the result is one of the two
+    neighbouring codes, at most half a unit in the last place away, and a tie lands on the even code."""
+    gd = load_golden(golden_dir, "bf16_rounding.json")
+    bits = np.array([int(c["float_bits"], 16) for c in gd["cases"]], np.uint32)
+    codes, wide = oracle.round_bf16(bits.view(np.float32))
+    np.testing.assert_array_equal(codes, np.array([int(c["bf16"], 16) for c in gd["cases"]], np.uint16))
+    np.testing.assert_array_equal(wide.view(np.uint32) >> 16, codes)
+    x = (synth.normal_f32(99, 2, 20000) * np.float32(10.0) ** synth.randint(99, 3, 0, 20000, -20, 20)).astype(np.float32)
+    codes, wide = oracle.round_bf16(x)
+    ulp = np.abs(wide.astype(np.float64)) * 2.0 ** -7          # spacing is between 2^-8 and 2^-7 of the value
+    assert (np.abs(wide.astype(np.float64) - x) <= 0.5 * ulp).all()
+    trunc = (x.view(np.uint32) & np.uint32(0xFFFF0000)).view(np.float32)
+    nxt = ((x.view(np.uint32) & np.uint32(0xFFFF0000)) + np.uint32(0x10000)).view(np.float32)
+    assert ((wide == trunc) | (wide == nxt)).all()
+    better = np.minimum(np.abs(trunc.astype(np.float64) - x), np.abs(nxt.astype(np.float64) - x))
+    np.testing.assert_array_equal(np.abs(wide.astype(np.float64) - x), better)
+    # representable values are fixed points
+    np.testing.assert_array_equal(oracle.round_bf16(wide)[1], wide)
+
+
 def test_error_codes():
     src = np.array([0, 5], np.int32)
     dst = np.array([1, 0], np.int32)
