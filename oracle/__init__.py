@@ -322,6 +322,28 @@ def round_bf16(x):
     return codes.reshape(x.shape), wide.reshape(x.shape)
 
 
+def hetero_propagate(relations, num_dst_nodes: int, msg: int = MSG_COPY_XJ, aggr: int = AGGR_SUM,
+                     with_sabs: bool = False):
+    """Sum over the relations that end in one destination node type of each relation's propagate.
+    relations: list of dicts with src, dst (indices into the relation's own source / the common
+    destination node set), num_src_nodes, x [num_src_nodes, F] and optionally e [E] or [E, F]."""
+    f = _f32(relations[0]["x"], "x").shape[1]
+    out64 = np.zeros((num_dst_nodes, f), np.float64)
+    sabs = np.zeros((num_dst_nodes, f), np.float64)
+    for r in relations:
+        src, dst, x = _i32(r["src"], "src"), _i32(r["dst"], "dst"), _f32(r["x"], "x")
+        ne = src.shape[0]
+        e, e_dim = _edge_data(r.get("e"), ne, f)
+        rc = _load().oracle_propagate_relation_add(_p(src), _p(dst), ctypes.c_int64(ne),
+                                                   ctypes.c_int32(int(r["num_src_nodes"])),
+                                                   ctypes.c_int32(num_dst_nodes), _p(x), ctypes.c_int32(f), _p(e),
+                                                   ctypes.c_int32(e_dim), ctypes.c_int32(msg), ctypes.c_int32(aggr),
+                                                   _p(out64), _p(sabs))
+        _check(rc, "hetero_propagate")
+    out = out64.astype(np.float32)
+    return (out, sabs) if with_sabs else out
+
+
 def gin_update(src, dst, num_nodes: int, x, eps: float = 0.0, with_sabs: bool = False):
     src, dst, x = _i32(src, "src"), _i32(dst, "dst"), _f32(x, "x")
     ne, f = src.shape[0], x.shape[1]

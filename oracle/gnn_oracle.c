@@ -218,6 +218,49 @@ int oracle_aggregate_neighbors(const int32_t *dst, int64_t E, int32_t N, const f
 }
 
 /*
+ * The reduction of propagate on a graph whose sources and destinations may be different node sets
+ * (a relation of a heterogeneous graph, section 3 "Graph Data Structures": x has N_src rows, the result
+ * N_dst rows), left in double: out64 / sabs64 [N_dst x F].
+ */
+static int propagate_core(const int32_t *src, const int32_t *dst, int64_t E, int32_t N_src, int32_t N_dst,
+                          const float *x, int32_t F, const float *e, int32_t e_dim, int32_t msg, int32_t aggr,
+                          double *out64, double *sabs64)
+{
+    if (N_src <= 0 || N_dst <= 0 || E < 0 || F <= 0) return 2;
+    if (msg < MSG_COPY_XJ || msg > MSG_XJ_SUB_XI) return 2;
+    if (msg == MSG_XJ_SUB_XI && N_src != N_dst) return 2;       /* x_i is a row of the same array */
+    if (aggr < AGGR_SUM || aggr > AGGR_PROD) return 2;
+    if (msg == MSG_E_MUL_XJ && e_dim != 1 && e_dim != F) return 2;
+    for (int64_t k = 0; k < E; ++k)
+        if (src[k] < 0 || src[k] >= N_src || dst[k] < 0 || dst[k] >= N_dst) return 1;
+    size_t nf = (size_t)N_dst * F;
+    double *acc = (double *)calloc(nf, sizeof(double));
+    double *sa = (double *)calloc(nf, sizeof(double));
+    int64_t *cnt = (int64_t *)calloc((size_t)N_dst, sizeof(int64_t));
+    if (!acc || !sa || !cnt) { free(acc); free(sa); free(cnt); return 3; }
+    for (int64_t k = 0; k < E; ++k) {
+        int64_t i = dst[k], j = src[k];
+        for (int32_t f = 0; f < F; ++f)
+            reduce_step(aggr, acc, sa, i * F + f, cnt[i], message_value(msg, x, F, i, j, e, e_dim, k, f));
+        cnt[i]++;
+    }
+    for (int32_t i = 0; i < N_dst; ++i)
+        for (int32_t f = 0; f < F; ++f) {
+            int64_t q = (int64_t)i * F + f;
+            double v = 0.0, sv = 0.0;
+            if (cnt[i] > 0) {
+                v = acc[q];
+                sv = sa[q];
+                if (aggr == AGGR_MEAN) { v /= (double)cnt[i]; sv /= (double)cnt[i]; }
+            }
+            out64[q] = v;
+            if (sabs64) sabs64[q] = sv;
+        }
+    free(acc); free(sa); free(cnt);
+    return 0;
+}
+
+/*
  * propagate = apply_edges then aggregate_neighbors, without storing the
  * [E x F] messages (same values, same order of edges).  xi_dot_xj (a message of another width)
  * is not a propagate message.
@@ -226,25 +269,35 @@ int oracle_propagate(const int32_t *src, const int32_t *dst, int64_t E, int32_t 
                      const float *x, int32_t F, const float *e, int32_t e_dim,
                      int32_t msg, int32_t aggr, float *out, double *sabs)
 {
-    if (N <= 0 || E < 0 || F <= 0) return 2;
-    if (msg < MSG_COPY_XJ || msg > MSG_XJ_SUB_XI) return 2;
-    if (aggr < AGGR_SUM || aggr > AGGR_PROD) return 2;
-    if (msg == MSG_E_MUL_XJ && e_dim != 1 && e_dim != F) return 2;
-    if (check_edges(src, dst, E, N)) return 1;
+    if (N <= 0 || F <= 0) return 2;
     size_t nf = (size_t)N * F;
-    double *acc = (double *)calloc(nf, sizeof(double));
-    double *sa = (double *)calloc(nf, sizeof(double));
-    int64_t *cnt = (int64_t *)calloc((size_t)N, sizeof(int64_t));
-    if (!acc || !sa || !cnt) { free(acc); free(sa); free(cnt); return 3; }
-    for (int64_t k = 0; k < E; ++k) {
-        int64_t i = dst[k], j = src[k];
-        for (int32_t f = 0; f < F; ++f)
-            reduce_step(aggr, acc, sa, i * F + f, cnt[i], message_value(msg, x, F, i, j, e, e_dim, k, f));
-        cnt[i]++;
-    }
-    finish_rows(N, F, aggr, acc, cnt, sa, out, sabs);
-    free(acc); free(sa); free(cnt);
-    return 0;
+    double *o64 = (double *)malloc(nf * sizeof(double));
+    if (!o64) return 3;
+    int rc = propagate_core(src, dst, E, N, N, x, F, e, e_dim, msg, aggr, o64, sabs);
+    if (rc == 0)
+        for (size_t q = 0; q < nf; ++q) out[q] = (float)o64[q];
+    free(o64);
+    return rc;
+}
+
+/*
+ * One relation of a heterogeneous graph: edges from a source node type (N_src nodes, features x) to a
+ * destination node type (N_dst nodes).  The result is ADDED, in double, to out64 / sabs64 [N_dst x F]:
+ * the caller sums the relations that end in one node type and rounds once.
+ */
+int oracle_propagate_relation_add(const int32_t *src, const int32_t *dst, int64_t E, int32_t N_src, int32_t N_dst,
+                                  const float *x, int32_t F, const float *e, int32_t e_dim, int32_t msg,
+                                  int32_t aggr, double *out64, double *sabs64)
+{
+    if (N_dst <= 0 || F <= 0) return 2;
+    size_t nf = (size_t)N_dst * F;
+    double *o = (double *)malloc(nf * sizeof(double)), *sa = (double *)malloc(nf * sizeof(double));
+    if (!o || !sa) { free(o); free(sa); return 3; }
+    int rc = propagate_core(src, dst, E, N_src, N_dst, x, F, e, e_dim, msg, aggr, o, sa);
+    if (rc == 0)
+        for (size_t q = 0; q < nf; ++q) { out64[q] += o[q]; sabs64[q] += sa[q]; }
+    free(o); free(sa);
+    return rc;
 }
 
 /*

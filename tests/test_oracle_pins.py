@@ -708,6 +708,52 @@ def test_bf16_rounding(golden_dir):
     np.testing.assert_array_equal(oracle.round_bf16(wide)[1], wide)
 
 
+def _hetero_relations(seed, n_dst, sizes, edges, f):
+    rels = []
+    for r, (ns, ne) in enumerate(zip(sizes, edges)):
+        src = synth.randint(seed, 10 + r, 0, ne, 0, ns - 1).astype(np.int32)
+        dst = synth.randint(seed, 20 + r, 0, ne, 0, n_dst - 1).astype(np.int32)
+        dst[dst % 5 == 2] = 0                                          # a hub and some empty destinations
+        rels.append({"src": src, "dst": dst, "num_src_nodes": ns,
+                     "x": synth.normal_f32(seed, 30 + r, ns * f).reshape(ns, f),
+                     "e": synth.uniform_f32(seed, 40 + r, ne, -1.0, 1.0)})
+    return rels
+
+
+def test_hetero_propagate_is_a_sum_of_rectangular_products():
+    """Relations into one node type: each is a rectangular (destinations x sources) adjacency product, the
+    relations are summed; with the node types laid side by side it is one homogeneous propagate."""
+    n_dst, sizes, edges, f = 23, [17, 40, 23], [150, 300, 90], 4
+    rels = _hetero_relations(83, n_dst, sizes, edges, f)
+    got = oracle.hetero_propagate(rels, n_dst, MSG_E_MUL_XJ, AGGR_SUM)
+    ref = np.zeros((n_dst, f))
+    ref_mean = np.zeros((n_dst, f))
+    for r in rels:
+        a = np.zeros((n_dst, r["num_src_nodes"]))
+        np.add.at(a, (r["dst"], r["src"]), r["e"].astype(np.float64))
+        ref += a @ r["x"].astype(np.float64)
+        cnt = np.bincount(r["dst"], minlength=n_dst)[:, None]
+        c = np.zeros((n_dst, r["num_src_nodes"]))
+        np.add.at(c, (r["dst"], r["src"]), 1.0)
+        ref_mean += np.where(cnt > 0, (c @ r["x"].astype(np.float64)) / np.maximum(cnt, 1), 0.0)
+    np.testing.assert_allclose(got, ref, rtol=0, atol=1e-6 * np.abs(ref).max())
+    got_mean = oracle.hetero_propagate(rels, n_dst, MSG_COPY_XJ, AGGR_MEAN)
+    np.testing.assert_allclose(got_mean, ref_mean, rtol=0, atol=1e-6 * np.abs(ref_mean).max())
+    # one homogeneous graph: destination type first, then the source types one after the other
+    offs = np.cumsum([n_dst] + sizes)
+    src = np.concatenate([r["src"] + offs[k] for k, r in enumerate(rels)]).astype(np.int32)
+    dst = np.concatenate([r["dst"] for r in rels]).astype(np.int32)
+    x = np.concatenate([np.zeros((n_dst, f), np.float32)] + [r["x"] for r in rels])
+    e = np.concatenate([r["e"] for r in rels])
+    merged = oracle.propagate(src, dst, int(offs[-1]), x, e, MSG_E_MUL_XJ, AGGR_SUM)
+    np.testing.assert_allclose(got, merged[:n_dst], rtol=0, atol=1e-6 * np.abs(ref).max())
+    assert np.abs(merged[n_dst:]).max() == 0
+    # a single relation on one node set is plain propagate
+    one = oracle.hetero_propagate([rels[2]], n_dst, MSG_COPY_XJ, AGGR_MAX)
+    np.testing.assert_array_equal(one, oracle.propagate(rels[2]["src"], rels[2]["dst"], n_dst, rels[2]["x"], None,
+                                                        MSG_COPY_XJ, AGGR_MAX))
+
+
 def test_error_codes():
     src = np.array([0, 5], np.int32)
     dst = np.array([1, 0], np.int32)
