@@ -97,6 +97,19 @@ gnn_status gnn_build_csr_ex(const int32_t *d_src, const int32_t *d_dst, int64_t 
                             int32_t num_nodes, int32_t small_max_degree, int32_t chunk_edges,
                             void *stream, gnn_graph **out_graph);
 
+/*
+ * One relation of a heterogeneous graph (paper section 3, "Graph Data Structures": graphs with several
+ * node and edge types): edges from a source node set of num_src_nodes nodes to a destination node set of
+ * num_dst_nodes nodes.  d_src[k] in [0, num_src_nodes), d_dst[k] in [0, num_dst_nodes); the CSR has one
+ * row per destination node.  Such a handle is accepted by gnn_propagate (x has num_src_nodes rows, the
+ * result num_dst_nodes), gnn_apply_edges / gnn_aggregate_neighbors, gnn_segment_softmax and
+ * gnn_hetero_propagate; what needs a node's own features next to its neighbours' (self-loops, x_j - x_i,
+ * the layers, the backward passes) returns GNN_ERR_UNSUPPORTED.
+ */
+gnn_status gnn_build_csr_bipartite(const int32_t *d_src, const int32_t *d_dst, int64_t num_edges,
+                                   int32_t num_src_nodes, int32_t num_dst_nodes, void *stream,
+                                   gnn_graph **out_graph);
+
 /* Frees everything the graph owns.  The caller makes sure no enqueued work still uses it. */
 gnn_status gnn_graph_destroy(gnn_graph *g);
 
@@ -105,7 +118,8 @@ const int32_t *gnn_graph_rowptr(const gnn_graph *g);   /* [N+1] */
 const int32_t *gnn_graph_colidx(const gnn_graph *g);   /* [E]   */
 const int32_t *gnn_graph_perm(const gnn_graph *g);     /* [E]   */
 const int32_t *gnn_graph_indegree(const gnn_graph *g); /* [N]   */
-int32_t gnn_graph_num_nodes(const gnn_graph *g);
+int32_t gnn_graph_num_nodes(const gnn_graph *g);       /* rows = destination nodes */
+int32_t gnn_graph_num_src_nodes(const gnn_graph *g);   /* differs only for gnn_build_csr_bipartite */
 int64_t gnn_graph_num_edges(const gnn_graph *g);
 /* Host-side sizes of the work lists: rows reduced by a sub-group, wavefront work items, split rows. */
 void gnn_graph_work_sizes(const gnn_graph *g, int32_t *n_small_rows, int32_t *n_items, int32_t *n_split_rows);
@@ -135,6 +149,21 @@ gnn_status gnn_edge_data_to_csr(const gnn_graph *g, const float *d_e, int32_t e_
 gnn_status gnn_propagate(const gnn_graph *g, const float *d_x, int32_t feat_dim,
                          const float *d_e, int32_t e_dim, gnn_edge_order e_order,
                          gnn_msg_op msg, gnn_aggr aggr, float *d_out, void *stream);
+
+/*
+ * Message passing on a heterogeneous graph, for one destination node type: the relations that end in it
+ * are propagated one after the other and their results are summed,
+ *   out[i,:] = sum over relations r of  AGGR over edges k of r with dst[k] = i of msg(x_r[src[k],:], e_r[k,:]).
+ * graphs, d_x and d_e are HOST arrays of num_relations entries: graphs[r] a handle whose rows are the
+ * destination type's nodes (all with the same gnn_graph_num_nodes), d_x[r] the DEVICE features of relation
+ * r's source type [gnn_graph_num_src_nodes(graphs[r]) x feat_dim], d_e[r] its DEVICE edge data [E_r x e_dim]
+ * (d_e may be NULL for COPY_XJ).  msg = COPY_XJ or E_MUL_XJ; aggr applies inside a relation.
+ * Temporal snapshot graphs need nothing extra: one handle per snapshot and one call each.
+ */
+gnn_status gnn_hetero_propagate(int32_t num_relations, const gnn_graph *const *graphs,
+                                const float *const *d_x, const float *const *d_e, int32_t feat_dim,
+                                int32_t e_dim, gnn_edge_order e_order, gnn_msg_op msg, gnn_aggr aggr,
+                                float *d_out, void *stream);
 
 /*
  * propagate over node features stored as bfloat16 (the upper 16 bits of a float; half the gather

@@ -38,6 +38,9 @@ SIGNATURES = {
     "gnn_graph_work_sizes": (None, [_vp, _c.POINTER(_i32), _c.POINTER(_i32), _c.POINTER(_i32)]),
     "gnn_edge_data_to_csr": (_c.c_int, [_vp, _vp, _i32, _vp, _vp]),
     "gnn_propagate": (_c.c_int, [_vp, _vp, _i32, _vp, _i32, _c.c_int, _c.c_int, _c.c_int, _vp, _vp]),
+    "gnn_build_csr_bipartite": (_c.c_int, [_vp, _vp, _i64, _i32, _i32, _vp, _c.POINTER(_vp)]),
+    "gnn_graph_num_src_nodes": (_i32, [_vp]),
+    "gnn_hetero_propagate": (_c.c_int, [_i32, _vp, _vp, _vp, _i32, _i32, _c.c_int, _c.c_int, _c.c_int, _vp, _vp]),
     "gnn_propagate_bf16": (_c.c_int, [_vp, _vp, _i32, _vp, _c.c_int, _c.c_int, _c.c_int, _vp, _vp]),
     "gnn_f32_to_bf16": (_c.c_int, [_vp, _i64, _vp, _vp]),
     "gnn_apply_edges": (_c.c_int, [_vp, _vp, _i32, _vp, _i32, _c.c_int, _c.c_int, _vp, _c.c_int, _vp]),
@@ -120,6 +123,7 @@ class Graph:
         self._h = handle
         self.device = device
         self.num_nodes = int(lib().gnn_graph_num_nodes(handle))
+        self.num_src_nodes = int(lib().gnn_graph_num_src_nodes(handle))
         self.num_edges = int(lib().gnn_graph_num_edges(handle))
 
     def _view(self, ptr: int, count: int) -> torch.Tensor:
@@ -190,6 +194,45 @@ def build_csr(src: torch.Tensor, dst: torch.Tensor, num_nodes: int, small_max_de
     return Graph(out.value, src.device)
 
 
+def build_csr_bipartite(src: torch.Tensor, dst: torch.Tensor, num_src_nodes: int, num_dst_nodes: int) -> Graph:
+    """One relation of a heterogeneous graph: rows are the destination type's nodes."""
+    e = int(src.shape[0])
+    if int(dst.shape[0]) != e:
+        raise ValueError("src and dst must have the same length")
+    out = _vp()
+    rc = lib().gnn_build_csr_bipartite(_dev(src, torch.int32, "src"), _dev(dst, torch.int32, "dst"), e, num_src_nodes,
+                                       num_dst_nodes, _stream(), ctypes.byref(out))
+    _check(rc, "gnn_build_csr_bipartite")
+    return Graph(out.value, src.device)
+
+
+def hetero_propagate(graphs, xs, es=None, msg: int = MSG_COPY_XJ, aggr: int = AGGR_SUM,
+                     e_order: int = EDGE_ORDER_COO, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Sum over relations (graphs[r], xs[r], es[r]) that end in one destination node type."""
+    r = len(graphs)
+    if r == 0 or len(xs) != r or (es is not None and len(es) != r):
+        raise ValueError("one feature matrix (and one edge-data array) per relation")
+    f = int(xs[0].shape[1])
+    e_dim = 1
+    e2 = None
+    if es is not None:
+        e2 = [e.reshape(g.num_edges, -1) for g, e in zip(graphs, es)]
+        e_dim = int(e2[0].shape[1])
+    for g, x in zip(graphs, xs):
+        if tuple(x.shape) != (g.num_src_nodes, f):
+            raise ValueError("x[r] must be [num_src_nodes of relation r, F]")
+    if out is None:
+        out = torch.empty((graphs[0].num_nodes, f), dtype=torch.float32, device=xs[0].device)
+    arr = _vp * r
+    gh = arr(*[g._h for g in graphs])
+    xp = arr(*[_dev(x, torch.float32, "x") for x in xs])
+    ep = arr(*[_dev(e, torch.float32, "e") for e in e2]) if e2 is not None else None
+    rc = lib().gnn_hetero_propagate(r, gh, xp, ep, f, e_dim, e_order, msg, aggr, _dev(out, torch.float32, "out"),
+                                    _stream())
+    _check(rc, "gnn_hetero_propagate")
+    return out
+
+
 def edge_data_to_csr(g: Graph, e: torch.Tensor) -> torch.Tensor:
     e2 = e.reshape(g.num_edges, -1)
     out = torch.empty_like(e2)
@@ -202,14 +245,14 @@ def propagate(g: Graph, x: torch.Tensor, e: Optional[torch.Tensor] = None, msg: 
               aggr: int = AGGR_SUM, e_order: int = EDGE_ORDER_COO,
               out: Optional[torch.Tensor] = None) -> torch.Tensor:
     n, f = x.shape
-    if n != g.num_nodes:
-        raise ValueError("x must have one row per node")
+    if n != g.num_src_nodes:
+        raise ValueError("x must have one row per (source) node")
     e_dim = 1
     if e is not None:
         e = e.reshape(g.num_edges, -1)
         e_dim = int(e.shape[1])
     if out is None:
-        out = torch.empty_like(x)
+        out = torch.empty((g.num_nodes, f), dtype=torch.float32, device=x.device)
     rc = lib().gnn_propagate(g._h, _dev(x, torch.float32, "x"), f, _dev(e, torch.float32, "e"), e_dim,
                              e_order, msg, aggr, _dev(out, torch.float32, "out"), _stream())
     _check(rc, "gnn_propagate")
@@ -246,8 +289,8 @@ def apply_edges(g: Graph, x: torch.Tensor, e: Optional[torch.Tensor] = None, msg
                 e_order: int = EDGE_ORDER_COO, m_order: int = EDGE_ORDER_COO,
                 out: Optional[torch.Tensor] = None) -> torch.Tensor:
     n, f = x.shape
-    if n != g.num_nodes:
-        raise ValueError("x must have one row per node")
+    if n != g.num_src_nodes:
+        raise ValueError("x must have one row per (source) node")
     e_dim = 1
     if e is not None:
         e = e.reshape(g.num_edges, -1)

@@ -288,6 +288,8 @@ gnn_status gnn_propagate_backward(const gnn_graph *g, const gnn_graph *g_by_sour
     if (msg != GNN_MSG_COPY_XJ && msg != GNN_MSG_E_MUL_XJ) return GNN_ERR_BAD_SIZE;
     if (aggr != GNN_AGGR_SUM && aggr != GNN_AGGR_MEAN && aggr != GNN_AGGR_MAX) return GNN_ERR_BAD_SIZE;
     if (aggr == GNN_AGGR_MAX && !d_argmax) return GNN_ERR_NULL;
+    if (g->bipartite) return GNN_ERR_UNSUPPORTED;   // one node set only
+
     const int32_t *winners = aggr == GNN_AGGR_MAX ? d_argmax : nullptr;
     if (msg == GNN_MSG_E_MUL_XJ) {
         if (e_dim != 1 && e_dim != feat_dim) return GNN_ERR_BAD_SIZE;

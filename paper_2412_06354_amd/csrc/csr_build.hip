@@ -16,14 +16,15 @@ constexpr int kThreads = 256;
 // ---------------------------------------------------------------- range check, in-degree histogram
 
 __global__ __launch_bounds__(kThreads) void check_range_kernel(const int32_t *__restrict__ src,
-                                                               const int32_t *__restrict__ dst, int64_t E, int32_t N,
+                                                               const int32_t *__restrict__ dst, int64_t E,
+                                                               int32_t N_src, int32_t N,
                                                                int32_t *__restrict__ bad)
 {
     const int64_t stride = (int64_t)gridDim.x * kThreads;
     int any_bad = 0;
     for (int64_t k = (int64_t)blockIdx.x * kThreads + threadIdx.x; k < E; k += stride) {
         const int32_t s = __builtin_nontemporal_load(src + k), d = __builtin_nontemporal_load(dst + k);
-        any_bad |= ((uint32_t)s >= (uint32_t)N) | ((uint32_t)d >= (uint32_t)N);
+        any_bad |= ((uint32_t)s >= (uint32_t)N_src) | ((uint32_t)d >= (uint32_t)N);
     }
     if (any_bad) atomicOr(bad, 1);
 }
@@ -386,7 +387,8 @@ gnn_status build_impl(const int32_t *d_src, const int32_t *d_dst, int64_t E, int
     GNN_HIP(hipMemsetAsync(g->indeg, 0, (size_t)N * sizeof(int32_t), stream));
     if (E > 0) {
         const int blocks = (int)std::min<int64_t>(gnn_div_up(E, kThreads), 256 * 16);
-        hipLaunchKernelGGL(check_range_kernel, dim3(blocks), dim3(kThreads), 0, stream, d_src, d_dst, E, N, d_flag);
+        hipLaunchKernelGGL(check_range_kernel, dim3(blocks), dim3(kThreads), 0, stream, d_src, d_dst, E,
+                           g->num_src_nodes, N, d_flag);
         GNN_LAUNCH_CHECK();
     }
 
@@ -463,12 +465,13 @@ gnn_status build_impl(const int32_t *d_src, const int32_t *d_dst, int64_t E, int
 
 extern "C" {
 
-gnn_status gnn_build_csr_ex(const int32_t *d_src, const int32_t *d_dst, int64_t num_edges, int32_t num_nodes,
-                            int32_t small_max_degree, int32_t chunk_edges, void *stream, gnn_graph **out_graph)
+static gnn_status build_checked(const int32_t *d_src, const int32_t *d_dst, int64_t num_edges, int32_t num_src_nodes,
+                                int32_t num_nodes, bool bipartite, int32_t small_max_degree, int32_t chunk_edges,
+                                void *stream, gnn_graph **out_graph)
 {
     if (!out_graph) return GNN_ERR_NULL;
     *out_graph = nullptr;
-    if (num_nodes <= 0 || num_edges < 0 || num_edges >= (1ll << 31)) return GNN_ERR_BAD_SIZE;
+    if (num_nodes <= 0 || num_src_nodes <= 0 || num_edges < 0 || num_edges >= (1ll << 31)) return GNN_ERR_BAD_SIZE;
     if (num_edges > 0 && (!d_src || !d_dst)) return GNN_ERR_NULL;
     if (small_max_degree == 0 && chunk_edges == 0) small_max_degree = 16;
     if (chunk_edges == 0) {
@@ -482,6 +485,8 @@ gnn_status gnn_build_csr_ex(const int32_t *d_src, const int32_t *d_dst, int64_t 
     gnn_graph *g = new (std::nothrow) gnn_graph();
     if (!g) return GNN_ERR_ALLOC;
     g->num_nodes = num_nodes;
+    g->num_src_nodes = num_src_nodes;
+    g->bipartite = bipartite;
     g->num_edges = num_edges;
     g->small_max = small_max_degree;
     g->chunk = chunk_edges;
@@ -496,11 +501,26 @@ gnn_status gnn_build_csr_ex(const int32_t *d_src, const int32_t *d_dst, int64_t 
     return GNN_OK;
 }
 
+gnn_status gnn_build_csr_ex(const int32_t *d_src, const int32_t *d_dst, int64_t num_edges, int32_t num_nodes,
+                            int32_t small_max_degree, int32_t chunk_edges, void *stream, gnn_graph **out_graph)
+{
+    return build_checked(d_src, d_dst, num_edges, num_nodes, num_nodes, false, small_max_degree, chunk_edges, stream,
+                         out_graph);
+}
+
+gnn_status gnn_build_csr_bipartite(const int32_t *d_src, const int32_t *d_dst, int64_t num_edges,
+                                   int32_t num_src_nodes, int32_t num_dst_nodes, void *stream, gnn_graph **out_graph)
+{
+    return build_checked(d_src, d_dst, num_edges, num_src_nodes, num_dst_nodes, true, 0, 0, stream, out_graph);
+}
+
 gnn_status gnn_build_csr(const int32_t *d_src, const int32_t *d_dst, int64_t num_edges, int32_t num_nodes,
                          void *stream, gnn_graph **out_graph)
 {
     return gnn_build_csr_ex(d_src, d_dst, num_edges, num_nodes, 0, 0, stream, out_graph);
 }
+
+int32_t gnn_graph_num_src_nodes(const gnn_graph *g) { return g ? g->num_src_nodes : 0; }
 
 gnn_status gnn_graph_destroy(gnn_graph *g)
 {

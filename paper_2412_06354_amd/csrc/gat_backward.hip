@@ -461,6 +461,7 @@ gnn_status gnn_gatconv_backward(const gnn_graph *g, const gnn_graph *g_by_source
         !d_workspace)
         return GNN_ERR_NULL;
     if (f_in <= 0 || heads <= 0 || ch <= 0) return GNN_ERR_BAD_SIZE;
+    if (g->bipartite) return GNN_ERR_UNSUPPORTED;   // one node set only
     if (g_by_source->num_nodes != g->num_nodes || g_by_source->num_edges != g->num_edges) return GNN_ERR_BAD_SIZE;
     const int64_t N = g->num_nodes;
     const int HC = heads * ch;

@@ -339,6 +339,7 @@ gnn_status gnn_gatconv(const gnn_graph *g, const float *d_x, int32_t f_in, const
 {
     if (!g || !d_x || !d_w || !d_a_src || !d_a_dst || !d_out || !d_workspace) return GNN_ERR_NULL;
     if (f_in <= 0 || heads <= 0 || ch <= 0) return GNN_ERR_BAD_SIZE;
+    if (g->bipartite) return GNN_ERR_UNSUPPORTED;   // one node set only
     const int32_t N = g->num_nodes;
     if (workspace_bytes < gnn_gatconv_workspace_bytes(N, heads, ch)) return GNN_ERR_BAD_SIZE;
     if (reinterpret_cast<uintptr_t>(d_workspace) & 255u) return GNN_ERR_BAD_SIZE;

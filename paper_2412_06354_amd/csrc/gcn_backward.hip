@@ -215,6 +215,7 @@ gnn_status gnn_gcnconv_backward(const gnn_graph *g, const gnn_graph *g_by_source
 {
     if (!g || !g_by_source || !d_grad_out || !d_workspace) return GNN_ERR_NULL;
     if (f_in <= 0 || f_out <= 0) return GNN_ERR_BAD_SIZE;
+    if (g->bipartite) return GNN_ERR_UNSUPPORTED;   // one node set only
     if (g_by_source->num_nodes != g->num_nodes || g_by_source->num_edges != g->num_edges) return GNN_ERR_BAD_SIZE;
     if ((d_grad_x && !d_w) || (d_grad_w && !d_x)) return GNN_ERR_NULL;
     const int64_t N = g->num_nodes;

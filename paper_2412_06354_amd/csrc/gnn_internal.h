@@ -50,7 +50,9 @@ struct gnn_temp_pool {
 };
 
 struct gnn_graph {
-    int32_t num_nodes = 0;
+    int32_t num_nodes = 0;        // rows of the CSR = destination nodes
+    int32_t num_src_nodes = 0;    // range of colidx; equals num_nodes unless built from a relation between two node sets
+    bool bipartite = false;       // built by gnn_build_csr_bipartite: sources and destinations are different node sets
     int64_t num_edges = 0;
     int32_t small_max = 0;   // rows with in-degree <= small_max: one sub-group of a wavefront each
     int32_t chunk = 0;       // longer rows: pieces of <= chunk edges, one wavefront each
@@ -97,6 +99,7 @@ struct gnn_epilogue {
     const float *row_scale = nullptr;
     const float *bias = nullptr;
     int relu = 0;                    // max(., 0) last
+    int accumulate = 0;              // out += result instead of out = result (sum over relations)
 };
 
 // Which row of `x` CSR position p gathers: x[colidx[p]] for node features (the default),

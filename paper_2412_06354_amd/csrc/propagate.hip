@@ -41,7 +41,7 @@ struct PropParams {
     float *out, *scratch;
     const int32_t *small_rows, *item_row, *item_start, *item_slot, *split_rows, *split_slot0;
     int32_t n_small, n_items, n_split, chunk, F, e_coo, item_blocks;
-    int32_t mean, relu;
+    int32_t mean, relu, accumulate;
     float self_scale;
     const float *row_scale, *bias;
     const int32_t *winners;   // [rows of x][F] winning edge id per element (routed kinds only)
@@ -204,6 +204,12 @@ __device__ __forceinline__ void finish_row(const PropParams &p, int row, int deg
     if (p.relu) {
 #pragma unroll
         for (int c = 0; c < VEC; ++c) acc.v[c] = fmaxf(acc.v[c], 0.0f);
+    }
+    if (p.accumulate) {   // sum over the relations of a heterogeneous graph: add to what is there
+        Row<VEC> old;
+        load_row<VEC>(old, p.out + (int64_t)row * p.F + col);
+#pragma unroll
+        for (int c = 0; c < VEC; ++c) acc.v[c] = old.v[c] + acc.v[c];
     }
     store_row_stream<VEC>(p.out + (int64_t)row * p.F + col, acc);
 }
@@ -581,6 +587,9 @@ gnn_status gnn_launch_propagate(const gnn_graph *g, const float *d_x, int32_t fe
         kmsg = kMsgSubTarget;
     }
     if (reduce < GNN_REDUCE_SUM || reduce > GNN_REDUCE_PROD) return GNN_ERR_BAD_SIZE;
+    // x[row] (self term, x_j - x_i) only exists when sources and destinations are one node set
+    if ((epi.self_scale != 0.0f || msg == GNN_MSG_XJ_SUB_XI) && g->bipartite)
+        return GNN_ERR_UNSUPPORTED;
     if (d_winners) {
         if (reduce != GNN_REDUCE_SUM || e_order != GNN_EDGE_ORDER_COO || msg == GNN_MSG_XJ_SUB_XI)
             return GNN_ERR_UNSUPPORTED;   // edge ids are compared
@@ -598,7 +607,7 @@ gnn_status gnn_launch_propagate(const gnn_graph *g, const float *d_x, int32_t fe
     p.n_small = g->n_small; p.n_items = g->n_items; p.n_split = g->n_split; p.chunk = g->chunk;
     p.F = F; p.e_coo = (e_order == GNN_EDGE_ORDER_COO) ? 1 : 0;
     p.item_blocks = (int32_t)gnn_div_up(g->n_items, kWavesPerBlock);
-    p.mean = epi.mean; p.relu = epi.relu; p.self_scale = epi.self_scale; p.row_scale = epi.row_scale; p.bias = epi.bias;
+    p.mean = epi.mean; p.relu = epi.relu; p.accumulate = epi.accumulate; p.self_scale = epi.self_scale; p.row_scale = epi.row_scale; p.bias = epi.bias;
     p.winners = d_winners;
 
     if (g->n_slots > 0) GNN_TRY(gnn_graph_reserve_scratch(g, (size_t)g->n_slots * F));
@@ -643,6 +652,35 @@ gnn_status gnn_propagate(const gnn_graph *g, const float *d_x, int32_t feat_dim,
     epi.mean = (aggr == GNN_AGGR_MEAN);
     return gnn_launch_propagate(g, d_x, feat_dim, d_e, e_dim, e_order, msg, reduce_of(aggr), epi, d_out,
                                 static_cast<hipStream_t>(stream));
+}
+
+gnn_status gnn_hetero_propagate(int32_t num_relations, const gnn_graph *const *graphs, const float *const *d_x,
+                                const float *const *d_e, int32_t feat_dim, int32_t e_dim, gnn_edge_order e_order,
+                                gnn_msg_op msg, gnn_aggr aggr, float *d_out, void *stream)
+{
+    if (num_relations <= 0 || feat_dim <= 0) return GNN_ERR_BAD_SIZE;
+    if (!graphs || !d_x || !d_out) return GNN_ERR_NULL;
+    if (msg != GNN_MSG_COPY_XJ && msg != GNN_MSG_E_MUL_XJ) return msg == GNN_MSG_XJ_SUB_XI ? GNN_ERR_UNSUPPORTED
+                                                                                           : GNN_ERR_BAD_SIZE;
+    if (!valid_aggr(aggr)) return GNN_ERR_BAD_SIZE;
+    if (msg == GNN_MSG_E_MUL_XJ) {
+        if (!d_e) return GNN_ERR_NULL;
+        if (e_dim != 1 && e_dim != feat_dim) return GNN_ERR_BAD_SIZE;
+        if (e_order != GNN_EDGE_ORDER_COO && e_order != GNN_EDGE_ORDER_CSR) return GNN_ERR_BAD_SIZE;
+    }
+    for (int32_t r = 0; r < num_relations; ++r) {
+        if (!graphs[r] || !d_x[r]) return GNN_ERR_NULL;
+        if (graphs[r]->num_nodes != graphs[0]->num_nodes) return GNN_ERR_BAD_SIZE;
+        if (msg == GNN_MSG_E_MUL_XJ && !d_e[r] && graphs[r]->num_edges > 0) return GNN_ERR_NULL;
+    }
+    for (int32_t r = 0; r < num_relations; ++r) {
+        gnn_epilogue epi;
+        epi.mean = (aggr == GNN_AGGR_MEAN);
+        epi.accumulate = (r > 0);
+        GNN_TRY(gnn_launch_propagate(graphs[r], d_x[r], feat_dim, d_e ? d_e[r] : nullptr, e_dim, e_order, msg,
+                                     reduce_of(aggr), epi, d_out, static_cast<hipStream_t>(stream)));
+    }
+    return GNN_OK;
 }
 
 gnn_status gnn_propagate_bf16(const gnn_graph *g, const uint16_t *d_x_bf16, int32_t feat_dim, const float *d_e,
@@ -690,6 +728,8 @@ gnn_status gnn_apply_edges(const gnn_graph *g, const float *d_x, int32_t feat_di
     }
     if (g->num_edges == 0) return GNN_OK;
     if (!d_x || !d_m || (msg == GNN_MSG_E_MUL_XJ && !d_e)) return GNN_ERR_NULL;
+    if ((msg == GNN_MSG_XI_DOT_XJ || msg == GNN_MSG_XJ_SUB_XI) && g->bipartite)
+        return GNN_ERR_UNSUPPORTED;
     if (msg == GNN_MSG_XI_DOT_XJ) return gnn_launch_edge_dot(g, d_x, d_x, feat_dim, d_m, m_order, stream);
     int kmsg = kMsgCopy;
     if (msg == GNN_MSG_E_MUL_XJ) kmsg = (e_dim == 1) ? kMsgMulScalar : kMsgMulVector;

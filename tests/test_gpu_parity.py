@@ -327,6 +327,48 @@ def test_propagate_bf16_wide_rows_and_rejections(gnn):
     g.close()
 
 
+def test_hetero_propagate(gnn):
+    """Three relations into one destination node type (power-law destinations so that rows get split),
+    against the oracle's sum over relations; a bipartite handle in plain propagate; and the rejections."""
+    n_dst, f = 4000, 32
+    sizes, edges = [2500, 7000, 4000], [60_000, 90_000, 30_000]
+    w = synth.power_law_weights(n_dst, 1.0, 1.0, 0.05)
+    cdf = np.cumsum(w / w.sum())
+    rels = []
+    for r, (ns, ne) in enumerate(zip(sizes, edges)):
+        src = synth.randint(87, 10 + r, 0, ne, 0, ns - 1).astype(np.int32)
+        dst = np.minimum(np.searchsorted(cdf, synth.uniform01(87, 20 + r, 0, ne)), n_dst - 1).astype(np.int32)
+        rels.append({"src": src, "dst": dst, "num_src_nodes": ns,
+                     "x": synth.normal_f32(87, 30 + r, ns * f).reshape(ns, f),
+                     "e": synth.uniform_f32(87, 40 + r, ne, -1.0, 1.0)})
+    graphs = [gnn.build_csr_bipartite(dev(r["src"]), dev(r["dst"]), r["num_src_nodes"], n_dst) for r in rels]
+    assert any(g.work_sizes()["split_rows"] > 0 for g in graphs)
+    xs, es = [dev(r["x"]) for r in rels], [dev(r["e"]) for r in rels]
+    for msg, aggr in ((MSG_COPY_XJ, AGGR_SUM), (MSG_E_MUL_XJ, AGGR_SUM), (MSG_E_MUL_XJ, AGGR_MEAN),
+                      (MSG_COPY_XJ, AGGR_MAX)):
+        ref, sabs = oracle.hetero_propagate(rels, n_dst, msg, aggr, with_sabs=True)
+        got = host(gnn.hetero_propagate(graphs, xs, es if msg == MSG_E_MUL_XJ else None, msg, aggr))
+        assert_close_sabs(got, ref, sabs, what=f"hetero msg={msg} aggr={aggr}")
+    # one relation through the plain entry points
+    r0 = rels[0]
+    one = oracle.hetero_propagate([r0], n_dst, MSG_COPY_XJ, AGGR_MAX)
+    np.testing.assert_array_equal(host(gnn.propagate(graphs[0], xs[0], None, MSG_COPY_XJ, AGGR_MAX)), one)
+    m = gnn.apply_edges(graphs[0], xs[0], es[0], MSG_E_MUL_XJ)
+    np.testing.assert_array_equal(host(m), r0["e"][:, None] * r0["x"][r0["src"]])
+    # what needs a node's own features is refused on a relation between two node sets
+    # (relation 2 has as many sources as destinations: it is the handle that knows they are different sets)
+    for fn in (lambda: gnn.gin_update(graphs[2], xs[2], 0.0),
+               lambda: gnn.propagate(graphs[2], xs[2], None, MSG_XJ_SUB_XI, AGGR_SUM),
+               lambda: gnn.apply_edges(graphs[2], xs[2], None, MSG_XI_DOT_XJ)):
+        with pytest.raises(gnn.GnnError) as err:
+            fn()
+        assert err.value.code == 4
+    with pytest.raises(gnn.GnnError):     # a source index beyond its node set
+        gnn.build_csr_bipartite(dev(np.array([0, 2500], np.int32)), dev(np.array([1, 1], np.int32)), 2500, n_dst)
+    for g in graphs:
+        g.close()
+
+
 def test_apply_edges_elementwise_and_odd_width(gnn):
     wl = powerlaw(2000, 30_000, 6, 900.0)
     g = gnn.build_csr(dev(wl.src), dev(wl.dst), wl.num_nodes, 4, 64)
