@@ -344,6 +344,69 @@ def hetero_propagate(relations, num_dst_nodes: int, msg: int = MSG_COPY_XJ, aggr
     return (out, sabs) if with_sabs else out
 
 
+def dense_backward(x, w, grad_out):
+    x, w, gy = _f32(x, "x"), _f32(w, "w"), _f32(grad_out, "grad_out")
+    n_rows, k = x.shape
+    n = w.shape[1]
+    gx, gw, gb = np.empty((n_rows, k), np.float32), np.empty((k, n), np.float32), np.empty(n, np.float32)
+    rc = _load().oracle_dense_backward(_p(x), ctypes.c_int32(n_rows), ctypes.c_int32(k), _p(w), ctypes.c_int32(n),
+                                       _p(gy), _p(gx), _p(gw), _p(gb))
+    _check(rc, "dense_backward")
+    return gx, gw, gb
+
+
+def batchnorm_backward(x, gamma, grad_out, eps: float = 1e-5):
+    x, gy = _f32(x, "x"), _f32(grad_out, "grad_out")
+    gamma = None if gamma is None else _f32(gamma, "gamma")
+    n, f = x.shape
+    gx, gg, gb = np.empty_like(x), np.empty(f, np.float32), np.empty(f, np.float32)
+    rc = _load().oracle_batchnorm_backward(_p(x), ctypes.c_int32(n), ctypes.c_int32(f), _p(gamma), ctypes.c_float(eps),
+                                           _p(gy), _p(gx), _p(gg), _p(gb))
+    _check(rc, "batchnorm_backward")
+    return gx, gg, gb
+
+
+def pool_backward(graph_indicator, num_graphs: int, grad_out, aggr: int = AGGR_MEAN):
+    gi, go = _i32(graph_indicator, "graph_indicator"), _f32(grad_out, "grad_out")
+    n, f = gi.shape[0], go.shape[1]
+    gx = np.empty((n, f), np.float32)
+    rc = _load().oracle_pool_backward(_p(gi), ctypes.c_int32(n), ctypes.c_int32(num_graphs), _p(go), ctypes.c_int32(f),
+                                      ctypes.c_int32(aggr), _p(gx))
+    _check(rc, "pool_backward")
+    return gx
+
+
+def adam_step(p, m, v, g, lr: float, t: int, b1: float = 0.9, b2: float = 0.999, eps: float = 1e-8):
+    """-> (p, m, v) after one step; the inputs are not modified."""
+    p2, m2, v2 = (np.ascontiguousarray(_f32(a, "a")).copy() for a in (p, m, v))
+    g = np.ascontiguousarray(_f32(g, "g"))
+    rc = _load().oracle_adam_step(_p(p2), _p(m2), _p(v2), _p(g), ctypes.c_int64(p2.size), ctypes.c_float(lr),
+                                  ctypes.c_float(b1), ctypes.c_float(b2), ctypes.c_float(eps), ctypes.c_int32(t))
+    _check(rc, "adam_step")
+    return p2, m2, v2
+
+
+def example_model_backward(src, dst, num_nodes: int, graph_indicator, num_graphs: int, x, params: dict, target,
+                           eps: float = 1e-5):
+    """Loss = mean squared error of the prediction against target [num_graphs, f3] (the example's loss) and its
+    gradients with respect to every parameter, by the chain rule through the stages of example_model_forward
+    in reverse.  Returns (loss, grads dict, forward intermediates)."""
+    fw = example_model_forward(src, dst, num_nodes, graph_indicator, num_graphs, x, params, eps)
+    diff = fw["y"].astype(np.float64) - _f32(target, "target").astype(np.float64)
+    loss = float((diff ** 2).mean())
+    gy = (2.0 * diff / diff.size).astype(np.float32)
+    g_pooled, gw3, gb3 = dense_backward(fw["pooled"], params["w3"], gy)
+    g_h3 = pool_backward(graph_indicator, num_graphs, g_pooled, AGGR_MEAN)
+    g_z3 = np.where(fw["h3"] > 0, g_h3, np.float32(0)).astype(np.float32)          # relu of the second GCNConv
+    r2 = gcnconv_backward(src, dst, num_nodes, fw["h2"], params["w2"], g_z3, True)
+    g_bn = np.where(fw["h2"] > 0, r2["grad_x"], np.float32(0)).astype(np.float32)    # relu after the batch norm
+    g_h1, ggamma, gbeta = batchnorm_backward(fw["h1"], params["gamma"], g_bn, eps)
+    r1 = gcnconv_backward(src, dst, num_nodes, x, params["w1"], g_h1, True)
+    grads = {"w1": r1["grad_w"], "b1": r1["grad_b"], "gamma": ggamma, "beta": gbeta, "w2": r2["grad_w"],
+             "b2": r2["grad_b"], "w3": gw3, "b3": gb3}
+    return loss, grads, fw
+
+
 def gin_update(src, dst, num_nodes: int, x, eps: float = 0.0, with_sabs: bool = False):
     src, dst, x = _i32(src, "src"), _i32(dst, "dst"), _f32(x, "x")
     ne, f = src.shape[0], x.shape[1]

@@ -914,6 +914,128 @@ int oracle_round_bf16(const float *x, int64_t n, uint16_t *codes, float *widened
 }
 
 /*
+ * Backward passes of the example model's dense-side layers (the training example differentiates the
+ * whole chain, section 3 "Training Example").  All in double, rounded once per output.
+ *
+ * oracle_dense_backward: out = X W + b (no activation; a relu is differentiated by masking gy first)
+ *   gx = gy W^T [N x k],  gw = X^T gy [k x n],  gb = column sums of gy [n].   Each output may be NULL.
+ */
+int oracle_dense_backward(const float *x, int32_t N, int32_t k, const float *w, int32_t n, const float *gy,
+                          float *gx, float *gw, float *gb)
+{
+    if (N < 0 || k <= 0 || n <= 0) return 2;
+    if (gx)
+        for (int32_t i = 0; i < N; ++i)
+            for (int32_t q = 0; q < k; ++q) {
+                double a = 0.0;
+                for (int32_t o = 0; o < n; ++o) a += (double)gy[(int64_t)i * n + o] * (double)w[(int64_t)q * n + o];
+                gx[(int64_t)i * k + q] = (float)a;
+            }
+    if (gw) {
+        double *acc = (double *)calloc((size_t)k * n, sizeof(double));
+        if (!acc) return 3;
+        for (int32_t i = 0; i < N; ++i)
+            for (int32_t q = 0; q < k; ++q)
+                for (int32_t o = 0; o < n; ++o)
+                    acc[(int64_t)q * n + o] += (double)x[(int64_t)i * k + q] * (double)gy[(int64_t)i * n + o];
+        for (int64_t q = 0; q < (int64_t)k * n; ++q) gw[q] = (float)acc[q];
+        free(acc);
+    }
+    if (gb)
+        for (int32_t o = 0; o < n; ++o) {
+            double a = 0.0;
+            for (int32_t i = 0; i < N; ++i) a += (double)gy[(int64_t)i * n + o];
+            gb[o] = (float)a;
+        }
+    return 0;
+}
+
+/*
+ * oracle_batchnorm_backward: y = gamma * xhat + beta with xhat = (x - mean) / sqrt(var + eps) and batch
+ * statistics (mean and biased variance depend on x).  With gy = dL/dy (already masked if a relu followed):
+ *   gbeta[f] = sum_i gy[i,f],   ggamma[f] = sum_i gy[i,f] xhat[i,f],
+ *   gx[i,f]  = gamma[f] / sqrt(var[f] + eps) * (gy[i,f] - gbeta[f] / N - xhat[i,f] * ggamma[f] / N).
+ * mean / var are recomputed from x.  gamma may be NULL (1).
+ */
+int oracle_batchnorm_backward(const float *x, int32_t N, int32_t F, const float *gamma, float eps, const float *gy,
+                              float *gx, float *ggamma, float *gbeta)
+{
+    if (N <= 0 || F <= 0) return 2;
+    for (int32_t f = 0; f < F; ++f) {
+        double s = 0.0;
+        for (int32_t i = 0; i < N; ++i) s += (double)x[(int64_t)i * F + f];
+        double mu = s / (double)N, q = 0.0;
+        for (int32_t i = 0; i < N; ++i) {
+            double d = (double)x[(int64_t)i * F + f] - mu;
+            q += d * d;
+        }
+        double inv = 1.0 / sqrt(q / (double)N + (double)eps);
+        double gb = 0.0, gg = 0.0;
+        for (int32_t i = 0; i < N; ++i) {
+            double g = (double)gy[(int64_t)i * F + f];
+            gb += g;
+            gg += g * ((double)x[(int64_t)i * F + f] - mu) * inv;
+        }
+        double gm = gamma ? (double)gamma[f] : 1.0;
+        if (gx)
+            for (int32_t i = 0; i < N; ++i) {
+                double xh = ((double)x[(int64_t)i * F + f] - mu) * inv;
+                gx[(int64_t)i * F + f] =
+                    (float)(gm * inv * ((double)gy[(int64_t)i * F + f] - gb / (double)N - xh * gg / (double)N));
+            }
+        if (ggamma) ggamma[f] = (float)gg;
+        if (gbeta) gbeta[f] = (float)gb;
+    }
+    return 0;
+}
+
+/*
+ * oracle_pool_backward: graph-level readout by sum or mean; gx[i,:] = gout[g(i),:] (divided by the node
+ * count of graph g(i) for the mean).
+ */
+int oracle_pool_backward(const int32_t *gi, int32_t N, int32_t G, const float *gout, int32_t F, int32_t aggr,
+                         float *gx)
+{
+    if (N < 0 || G <= 0 || F <= 0) return 2;
+    if (aggr != AGGR_SUM && aggr != AGGR_MEAN) return 2;
+    int64_t *cnt = (int64_t *)calloc((size_t)G, sizeof(int64_t));
+    if (!cnt) return 3;
+    for (int32_t i = 0; i < N; ++i) {
+        if (gi[i] < 0 || gi[i] >= G) { free(cnt); return 1; }
+        cnt[gi[i]]++;
+    }
+    for (int32_t i = 0; i < N; ++i)
+        for (int32_t f = 0; f < F; ++f) {
+            double v = (double)gout[(int64_t)gi[i] * F + f];
+            if (aggr == AGGR_MEAN) v /= (double)cnt[gi[i]];
+            gx[(int64_t)i * F + f] = (float)v;
+        }
+    free(cnt);
+    return 0;
+}
+
+/*
+ * One Adam step on a parameter array (the example's optimiser, Adam(1e-4)):
+ *   m = b1 m + (1 - b1) g,  v = b2 v + (1 - b2) g^2,
+ *   p = p - lr * (m / (1 - b1^t)) / (sqrt(v / (1 - b2^t)) + eps),      t = step count starting at 1.
+ * p, m, v are updated in place (each rounded to float once).
+ */
+int oracle_adam_step(float *p, float *m, float *v, const float *g, int64_t n, float lr, float b1, float b2,
+                     float eps, int32_t t)
+{
+    if (n < 0 || t <= 0) return 2;
+    double c1 = 1.0 - pow((double)b1, (double)t), c2 = 1.0 - pow((double)b2, (double)t);
+    for (int64_t i = 0; i < n; ++i) {
+        double mi = (double)b1 * (double)m[i] + (1.0 - (double)b1) * (double)g[i];
+        double vi = (double)b2 * (double)v[i] + (1.0 - (double)b2) * (double)g[i] * (double)g[i];
+        m[i] = (float)mi;
+        v[i] = (float)vi;
+        p[i] = (float)((double)p[i] - (double)lr * (mi / c1) / (sqrt(vi / c2) + (double)eps));
+    }
+    return 0;
+}
+
+/*
  * GIN-style node update without the MLP:  out[i,:] = (1 + eps) x[i,:] + sum_{j->i} x[j,:].
  */
 int oracle_gin_update(const int32_t *src, const int32_t *dst, int64_t E, int32_t N,

@@ -754,6 +754,89 @@ def test_hetero_propagate_is_a_sum_of_rectangular_products():
                                                         MSG_COPY_XJ, AGGR_MAX))
 
 
+def test_example_model_backward_is_the_autograd_gradient():
+    """Loss and all eight parameter gradients of the example model against reverse-mode differentiation of an
+    independent float64 forward built from dense adjacency / membership matrices and library operations
+    (including the library's own batch normalisation in training mode)."""
+    import torch
+    wl = synth.config5_example_model(num_graphs=6, n=14, p=0.25)
+    n, ng, p = wl.num_nodes, wl.num_graphs, wl.params
+    target = synth.normal_f32(77, 9, ng).reshape(ng, 1)
+    loss, grads, _ = oracle.example_model_backward(wl.src, wl.dst, n, wl.graph_indicator, ng, wl.x, p, target)
+    a = dense_adjacency(wl.src, wl.dst, n) + np.eye(n)
+    deg = a.sum(1)
+    ahat = torch.tensor(a / np.sqrt(np.outer(deg, deg)))
+    member = np.zeros((ng, n))
+    member[wl.graph_indicator, np.arange(n)] = 1.0
+    member = torch.tensor(member / member.sum(1, keepdims=True))
+    tp = {k: torch.tensor(v, dtype=torch.float64, requires_grad=True) for k, v in p.items()}
+    xt = torch.tensor(wl.x, dtype=torch.float64)
+    h1 = ahat @ (xt @ tp["w1"]) + tp["b1"]
+    h2 = torch.relu(torch.nn.functional.batch_norm(h1, None, None, tp["gamma"], tp["beta"], training=True, eps=1e-5))
+    h3 = torch.relu(ahat @ (h2 @ tp["w2"]) + tp["b2"])
+    y = (member @ h3) @ tp["w3"] + tp["b3"]
+    ref_loss = ((y - torch.tensor(target, dtype=torch.float64)) ** 2).mean()
+    ref_loss.backward()
+    assert abs(loss - float(ref_loss.detach())) <= 1e-5 * abs(float(ref_loss.detach()))
+    scale = max(float(tp[k].grad.abs().max()) for k in p)
+    for k in p:
+        ref = tp[k].grad.numpy()
+        # (the gradient of b1 is exactly zero: the batch norm removes any constant shift)
+        np.testing.assert_allclose(grads[k], ref, rtol=0, atol=2e-5 * np.abs(ref).max() + 1e-7 * scale, err_msg=k)
+    assert np.abs(grads["b1"]).max() <= 1e-7 * scale
+
+
+def test_dense_batchnorm_pool_backward_pieces():
+    """The pieces on their own: dense backward against float64 products, pooling backward against its
+    definition, batch-norm backward against what its Jacobian fixes (gradients orthogonal to constants and
+    to xhat) and against reverse-mode differentiation."""
+    import torch
+    n, k, m = 50, 6, 3
+    x = synth.normal_f32(79, 2, n * k).reshape(n, k)
+    w = synth.glorot_uniform(79, 3, k, m, (k, m))
+    gy = synth.normal_f32(79, 4, n * m).reshape(n, m)
+    gx, gw, gb = oracle.dense_backward(x, w, gy)
+    np.testing.assert_allclose(gx, gy.astype(np.float64) @ w.astype(np.float64).T, rtol=0, atol=1e-6)
+    np.testing.assert_allclose(gw, x.astype(np.float64).T @ gy.astype(np.float64), rtol=0, atol=1e-5)
+    np.testing.assert_allclose(gb, gy.astype(np.float64).sum(0), rtol=0, atol=1e-5)
+    gi = np.repeat(np.arange(4, dtype=np.int32), [3, 1, 10, 36])
+    go = synth.normal_f32(79, 5, 4 * k).reshape(4, k)
+    np.testing.assert_array_equal(oracle.pool_backward(gi, 4, go, AGGR_SUM), go[gi])
+    np.testing.assert_allclose(oracle.pool_backward(gi, 4, go, AGGR_MEAN), go[gi] / np.array([3, 1, 10, 36])[gi][:, None],
+                               rtol=1e-7)
+    gamma = synth.uniform_f32(79, 6, k, 0.5, 1.5)
+    gyb = synth.normal_f32(79, 7, n * k).reshape(n, k)
+    bx, bg, bb = oracle.batchnorm_backward(x, gamma, gyb, 1e-5)
+    xt = torch.tensor(x, dtype=torch.float64, requires_grad=True)
+    gt = torch.tensor(gamma, dtype=torch.float64, requires_grad=True)
+    bt = torch.zeros(k, dtype=torch.float64, requires_grad=True)
+    out = torch.nn.functional.batch_norm(xt, None, None, gt, bt, training=True, eps=1e-5)
+    (out * torch.tensor(gyb, dtype=torch.float64)).sum().backward()
+    np.testing.assert_allclose(bx, xt.grad.numpy(), rtol=0, atol=1e-6)
+    np.testing.assert_allclose(bg, gt.grad.numpy(), rtol=0, atol=1e-5)
+    np.testing.assert_allclose(bb, bt.grad.numpy(), rtol=0, atol=1e-5)
+    assert np.abs(bx.astype(np.float64).sum(0)).max() <= 1e-5            # shifting x does not change the output
+    xhat = (x - x.mean(0)) / np.sqrt(x.astype(np.float64).var(0) + 1e-5)
+    assert np.abs((bx * xhat).sum(0)).max() <= 1e-4                        # nor does scaling x - mean (up to eps)
+
+
+def test_adam_step_matches_the_library_optimizer():
+    import torch
+    n = 200
+    p0 = synth.normal_f32(81, 2, n)
+    pt = torch.tensor(p0, dtype=torch.float64, requires_grad=True)
+    opt = torch.optim.Adam([pt], lr=1e-2, betas=(0.9, 0.999), eps=1e-8)
+    p, m, v = p0.copy(), np.zeros(n, np.float32), np.zeros(n, np.float32)
+    for t in range(1, 6):
+        g = synth.normal_f32(81, 10 + t, n)
+        pt.grad = torch.tensor(g, dtype=torch.float64)
+        opt.step()
+        p, m, v = oracle.adam_step(p, m, v, g, 1e-2, t)
+        np.testing.assert_allclose(p, pt.detach().numpy(), rtol=0, atol=2e-6)
+    first, _, _ = oracle.adam_step(p0, np.zeros(n, np.float32), np.zeros(n, np.float32), np.ones(n, np.float32), 1e-2, 1)
+    np.testing.assert_allclose(first, p0 - 1e-2, rtol=0, atol=1e-6)      # the first step moves by lr against the sign
+
+
 def test_error_codes():
     src = np.array([0, 5], np.int32)
     dst = np.array([1, 0], np.int32)
