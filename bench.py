@@ -20,6 +20,7 @@ Other workloads measure the remaining steps of the path, one JSON line each:
   backward gnn_propagate_backward (e_mul_xj, sum: grad_x and grad_e) on the headline graph
   gcn_backward gnn_gcnconv_backward (grad X, W, b) on the GCN graph
   example  gnn_example_model_forward (the paper's example model) on collated batches of 32 and 4 096 graphs
+  train    gnn_example_model_train_step (forward, loss, backward, Adam) on the same batches
 
 Every line carries `value` (algorithmic GB/s = the byte model of the step / mean step time), a
 `roofline` object for the dominant kernel and a `cpu_baseline` object (the parity oracle, one thread,
@@ -420,6 +421,61 @@ def run_example(args, torch, gnn, synth):
     return line
 
 
+def run_train(args, torch, gnn, synth):
+    """One training step of the paper's example model (forward, MSE loss, all gradients, Adam) per call."""
+    results = {}
+    for ng in (32, 4096):
+        wl = synth.config5_example_model(num_graphs=ng)
+        n, e, p = wl.num_nodes, wl.num_edges, wl.params
+        src, dst = to_dev(torch, wl.src), to_dev(torch, wl.dst)
+        g, gt = gnn.build_csr(src, dst, n), gnn.build_csr(dst, src, n)
+        x, gi = to_dev(torch, wl.x), to_dev(torch, wl.graph_indicator)
+        target = to_dev(torch, synth.normal_f32(95, 9, ng).reshape(ng, 1))
+        dp = {k: to_dev(torch, v) for k, v in p.items()}
+        dm = {k: torch.zeros_like(v) for k, v in dp.items()}
+        dv = {k: torch.zeros_like(v) for k, v in dp.items()}
+        f0, f1, f2, f3 = wl.x.shape[1], p["w1"].shape[1], p["w2"].shape[1], p["w3"].shape[1]
+        ws = torch.empty(int(gnn.lib().gnn_example_model_train_workspace_bytes(n, ng, f0, f1, f2, f3)), dtype=torch.uint8,
+                         device="cuda")
+        loss = torch.empty(1, dtype=torch.float32, device="cuda")
+        counter = [0]
+
+        def step():
+            counter[0] += 1
+            gnn.example_model_train_step(g, gt, gi, ng, x, target, dp, dm, dv, counter[0], loss=loss, workspace=ws)
+
+        ms = time_calls(torch, step, args.steps, args.warmup)
+        results[ng] = (ms, n, e, float(loss.cpu()[0]))
+        g.close()
+        gt.close()
+    ms, n, e, last_loss = results[4096]
+    f1 = f2 = 64
+    # forward bytes (see the example workload) + backward: two GCN backward passes, batch-norm backward, masks
+    b_fwd = (4 * n * (16 + 2 * f1) + (e + n) * (4 * f1 + 4) + 4 * 4 * n * f1 + 4 * n * (f1 + 2 * f2) + (e + n) * (4 * f2 + 4) +
+             4 * n * f2 + 4 * n)
+    b_bwd = 2 * ((e + n) * (4 * f1 + 4) + 6 * 4 * n * f1) + 5 * 4 * n * f1 + 3 * 4 * n * f2
+    line = base_line("example model training step (forward, MSE, backward, Adam), algorithmic GB/s",
+                     (b_fwd + b_bwd) / (ms * 1e-3) / 1e9, ms, args, "config5_example_model:train:4096_graphs",
+                     {"graphs": 4096, "N": n, "E": e, "widths": "16-64-64-1", "optimizer": "Adam(1e-4)"})
+    line["roofline"] = hbm_roofline((b_fwd + b_bwd) / (ms * 1e-3) / 1e9, "whole step (about 60 small launches)")
+    line["extra"] = {"graphs_per_s": 4096 / (ms * 1e-3), "steps_per_s": 1e3 / ms, "loss_after_timed_steps": last_loss,
+                     "batch_of_32_graphs_ms": results[32][0], "batch_of_32_steps_per_s": 1e3 / results[32][0]}
+    if not args.no_cpu_baseline:
+        import numpy as np
+        import oracle
+        wl = synth.config5_example_model(num_graphs=4096)
+        target = synth.normal_f32(95, 9, 4096).reshape(4096, 1)
+        t0 = time.perf_counter()
+        _, grads, _ = oracle.example_model_backward(wl.src, wl.dst, wl.num_nodes, wl.graph_indicator, 4096, wl.x, wl.params,
+                                                    target)
+        for k, v in wl.params.items():
+            oracle.adam_step(v, np.zeros_like(v), np.zeros_like(v), grads[k], 1e-4, 1)
+        dt = time.perf_counter() - t0
+        line["cpu_baseline"] = {"value": (b_fwd + b_bwd) / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+                                "seconds": dt, "sample": "one whole training step on the batch of 4 096 graphs"}
+    return line
+
+
 def run_batched(args, torch, gnn, synth):
     wl = synth.config3_batched()
     n, e, f, ng = wl.num_nodes, wl.num_edges, wl.x.shape[1], wl.num_graphs
@@ -557,7 +613,7 @@ def run_gcn_backward(args, torch, gnn, synth):
     return line
 
 
-WORKLOADS = {"example": run_example, "gat_backward": run_gat_backward, "gcn_backward": run_gcn_backward, "backward": run_backward, "propagate": run_propagate, "csr": run_csr, "softmax": run_softmax, "gcn": run_gcn, "gat": run_gat,
+WORKLOADS = {"train": run_train, "example": run_example, "gat_backward": run_gat_backward, "gcn_backward": run_gcn_backward, "backward": run_backward, "propagate": run_propagate, "csr": run_csr, "softmax": run_softmax, "gcn": run_gcn, "gat": run_gat,
              "batched": run_batched, "tiny": run_tiny}
 
 

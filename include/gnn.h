@@ -370,6 +370,61 @@ gnn_status gnn_example_model_forward(const gnn_graph *g, const int32_t *d_graph_
                                      float *d_y, void *d_workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Training-side pieces of the paper's example (section 3, "Training Example": mean-squared-error loss,
+ * gradients of the whole chain, Adam update).  No atomics anywhere: a step is bitwise reproducible.
+ *
+ * gnn_mse_loss: *d_loss = mean (pred - target)^2 over `count` values, d_grad = 2 (pred - target) / count
+ *   (either output may be NULL).  d_loss is a DEVICE scalar.
+ * gnn_relu_backward: d_grad_x = d_y > 0 ? d_grad_y : 0, d_y being the relu's OUTPUT; d_grad_x may alias d_grad_y.
+ * gnn_graph_pool_backward: every node of graph g receives d_grad_out[g,:] (SUM) or that divided by the
+ *   graph's node count (MEAN); d_graph_indicator as for gnn_graph_pool; nodes of no graph are left untouched.
+ * gnn_dense_backward: for out = X W + b:  d_grad_x = gy W^T, d_grad_w = X^T gy, d_grad_b = column sums of gy
+ *   (each may be NULL; an activation is differentiated by masking gy first).
+ * gnn_batchnorm_backward: for y = gamma * xhat + beta with batch statistics (d_mean / d_var as written by
+ *   gnn_batchnorm): d_grad_beta = sum_i g, d_grad_gamma = sum_i g xhat,
+ *   d_grad_x = gamma / sqrt(var + eps) * (g - grad_beta / N - xhat * grad_gamma / N) (may be NULL), where
+ *   g = d_grad_y, masked by d_y_relu > 0 when d_y_relu (the output of a fused relu) is not NULL.
+ * gnn_adam_step: m = b1 m + (1 - b1) g;  v = b2 v + (1 - b2) g^2;
+ *   p -= lr * (m / (1 - b1^step)) / (sqrt(v / (1 - b2^step)) + eps);   step counts from 1; p, m, v in place.
+ * gnn_example_model_train_step: forward of gnn_example_model_forward, MSE loss against d_target
+ *   [num_graphs x f3], gradients of all parameters and one Adam step on them.  d_params, d_adam_m, d_adam_v
+ *   are HOST arrays of 8 DEVICE pointers in the order w1 [f0 x f1], b1 [f1], gamma [f1], beta [f1],
+ *   w2 [f1 x f2], b2 [f2], w3 [f2 x f3], b3 [f3]; parameters and optimiser state are updated in place.
+ *   g_by_source = gnn_build_csr(dst, src, ...).  d_loss (DEVICE scalar, may be NULL) receives the loss of
+ *   the forward pass, i.e. before the update.
+ * Workspaces: at least the matching *_workspace_bytes(), 256-byte aligned.
+ */
+gnn_status gnn_mse_loss(const float *d_pred, const float *d_target, int64_t count, float *d_loss,
+                        float *d_grad, void *stream);
+gnn_status gnn_relu_backward(const float *d_y, const float *d_grad_y, int64_t count, float *d_grad_x,
+                             void *stream);
+gnn_status gnn_graph_pool_backward(const int32_t *d_graph_indicator, int32_t num_nodes, int32_t num_graphs,
+                                   const float *d_grad_out, int32_t feat_dim, gnn_aggr aggr,
+                                   float *d_grad_x, void *stream);
+size_t gnn_dense_backward_workspace_bytes(int64_t rows, int32_t k, int32_t n);
+gnn_status gnn_dense_backward(const float *d_x, int64_t rows, int32_t k, const float *d_w, int32_t n,
+                              const float *d_grad_y, float *d_grad_x, float *d_grad_w, float *d_grad_b,
+                              void *d_workspace, size_t workspace_bytes, void *stream);
+size_t gnn_batchnorm_backward_workspace_bytes(int32_t num_rows, int32_t feat_dim);
+gnn_status gnn_batchnorm_backward(const float *d_x, int32_t num_rows, int32_t feat_dim, const float *d_gamma,
+                                  const float *d_mean, const float *d_var, float eps,
+                                  const float *d_grad_y, const float *d_y_relu, float *d_grad_x,
+                                  float *d_grad_gamma, float *d_grad_beta, void *d_workspace,
+                                  size_t workspace_bytes, void *stream);
+gnn_status gnn_adam_step(float *d_param, float *d_m, float *d_v, const float *d_grad, int64_t count, float lr,
+                         float beta1, float beta2, float eps, int32_t step, void *stream);
+size_t gnn_example_model_train_workspace_bytes(int32_t num_nodes, int32_t num_graphs, int32_t f0, int32_t f1,
+                                               int32_t f2, int32_t f3);
+gnn_status gnn_example_model_train_step(const gnn_graph *g, const gnn_graph *g_by_source,
+                                        const int32_t *d_graph_indicator, int32_t num_graphs,
+                                        const float *d_x, int32_t f0, int32_t f1, int32_t f2, int32_t f3,
+                                        const float *d_target, float *const *d_params,
+                                        float *const *d_adam_m, float *const *d_adam_v, float bn_eps,
+                                        float lr, float beta1, float beta2, float adam_eps, int32_t step,
+                                        float *d_loss, void *d_workspace, size_t workspace_bytes,
+                                        void *stream);
+
+/*
  * Dense projection Z = X W on the matrix cores (fp32 MFMA, fp32 accumulate), the
  * contraction inside GCNConv and the GAT layer.  d_x [rows x k], d_w [k x n] row-major,
  * d_z [rows x n].  d_row_scale [rows] or NULL: Z[r,:] is multiplied by d_row_scale[r].

@@ -68,6 +68,18 @@ SIGNATURES = {
     "gnn_example_model_workspace_bytes": (_sz, [_i32, _i32, _i32, _i32]),
     "gnn_example_model_forward": (_c.c_int, [_vp, _vp, _i32, _vp, _i32, _vp, _vp, _i32, _vp, _vp, _f32, _vp, _vp, _i32,
                                              _vp, _vp, _i32, _vp, _vp, _sz, _vp]),
+    "gnn_mse_loss": (_c.c_int, [_vp, _vp, _i64, _vp, _vp, _vp]),
+    "gnn_relu_backward": (_c.c_int, [_vp, _vp, _i64, _vp, _vp]),
+    "gnn_graph_pool_backward": (_c.c_int, [_vp, _i32, _i32, _vp, _i32, _c.c_int, _vp, _vp]),
+    "gnn_dense_backward_workspace_bytes": (_sz, [_i64, _i32, _i32]),
+    "gnn_dense_backward": (_c.c_int, [_vp, _i64, _i32, _vp, _i32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "gnn_batchnorm_backward_workspace_bytes": (_sz, [_i32, _i32]),
+    "gnn_batchnorm_backward": (_c.c_int, [_vp, _i32, _i32, _vp, _vp, _vp, _f32, _vp, _vp, _vp, _vp, _vp, _vp, _sz,
+                                          _vp]),
+    "gnn_adam_step": (_c.c_int, [_vp, _vp, _vp, _vp, _i64, _f32, _f32, _f32, _f32, _i32, _vp]),
+    "gnn_example_model_train_workspace_bytes": (_sz, [_i32, _i32, _i32, _i32, _i32, _i32]),
+    "gnn_example_model_train_step": (_c.c_int, [_vp, _vp, _vp, _i32, _vp, _i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp,
+                                                _f32, _f32, _f32, _f32, _f32, _i32, _vp, _vp, _sz, _vp]),
     "gnn_dense_xw": (_c.c_int, [_vp, _i64, _i32, _vp, _i32, _vp, _vp, _vp]),
 }
 
@@ -535,6 +547,108 @@ def example_model_forward(g: Graph, graph_indicator: torch.Tensor, num_graphs: i
                                          _stream())
     _check(rc, "gnn_example_model_forward")
     return out
+
+
+PARAM_ORDER = ("w1", "b1", "gamma", "beta", "w2", "b2", "w3", "b3")
+
+
+def mse_loss(pred: torch.Tensor, target: torch.Tensor):
+    """-> (loss as a 1-element device tensor, grad with respect to pred)."""
+    if pred.shape != target.shape:
+        raise ValueError("shape mismatch")
+    loss = torch.empty(1, dtype=torch.float32, device=pred.device)
+    grad = torch.empty_like(pred)
+    rc = lib().gnn_mse_loss(_dev(pred, torch.float32, "pred"), _dev(target, torch.float32, "target"), pred.numel(),
+                            loss.data_ptr(), grad.data_ptr(), _stream())
+    _check(rc, "gnn_mse_loss")
+    return loss, grad
+
+
+def relu_backward(y: torch.Tensor, grad_y: torch.Tensor) -> torch.Tensor:
+    out = torch.empty_like(grad_y)
+    rc = lib().gnn_relu_backward(_dev(y, torch.float32, "y"), _dev(grad_y, torch.float32, "grad_y"), y.numel(),
+                                 out.data_ptr(), _stream())
+    _check(rc, "gnn_relu_backward")
+    return out
+
+
+def graph_pool_backward(graph_indicator: torch.Tensor, num_graphs: int, grad_out: torch.Tensor,
+                        aggr: int = AGGR_MEAN) -> torch.Tensor:
+    n, f = int(graph_indicator.shape[0]), int(grad_out.shape[1])
+    gx = torch.zeros((n, f), dtype=torch.float32, device=grad_out.device)
+    rc = lib().gnn_graph_pool_backward(_dev(graph_indicator, torch.int32, "graph_indicator"), n, num_graphs,
+                                       _dev(grad_out, torch.float32, "grad_out"), f, aggr, gx.data_ptr(), _stream())
+    _check(rc, "gnn_graph_pool_backward")
+    return gx
+
+
+def dense_backward(x: torch.Tensor, w: torch.Tensor, grad_y: torch.Tensor):
+    """-> (grad_x, grad_w, grad_b) of out = x w + b."""
+    rows, k = x.shape
+    n = int(w.shape[1])
+    gx = torch.empty_like(x)
+    gw = torch.empty_like(w)
+    gb = torch.empty(n, dtype=torch.float32, device=x.device)
+    ws = torch.empty(int(lib().gnn_dense_backward_workspace_bytes(rows, k, n)), dtype=torch.uint8, device=x.device)
+    rc = lib().gnn_dense_backward(_dev(x, torch.float32, "x"), rows, k, _dev(w, torch.float32, "w"), n,
+                                  _dev(grad_y, torch.float32, "grad_y"), gx.data_ptr(), gw.data_ptr(), gb.data_ptr(),
+                                  ws.data_ptr(), ws.numel(), _stream())
+    _check(rc, "gnn_dense_backward")
+    return gx, gw, gb
+
+
+def batchnorm_backward(x: torch.Tensor, gamma: Optional[torch.Tensor], mean: torch.Tensor, var: torch.Tensor,
+                       grad_y: torch.Tensor, eps: float = 1e-5, y_relu: Optional[torch.Tensor] = None):
+    """-> (grad_x, grad_gamma, grad_beta); y_relu = the output of a relu fused after the normalisation."""
+    n, f = x.shape
+    gx = torch.empty_like(x)
+    gg = torch.empty(f, dtype=torch.float32, device=x.device)
+    gb = torch.empty(f, dtype=torch.float32, device=x.device)
+    ws = torch.empty(int(lib().gnn_batchnorm_backward_workspace_bytes(n, f)), dtype=torch.uint8, device=x.device)
+    rc = lib().gnn_batchnorm_backward(_dev(x, torch.float32, "x"), n, f, _dev(gamma, torch.float32, "gamma"),
+                                      _dev(mean, torch.float32, "mean"), _dev(var, torch.float32, "var"), float(eps),
+                                      _dev(grad_y, torch.float32, "grad_y"), _dev(y_relu, torch.float32, "y_relu"),
+                                      gx.data_ptr(), gg.data_ptr(), gb.data_ptr(), ws.data_ptr(), ws.numel(), _stream())
+    _check(rc, "gnn_batchnorm_backward")
+    return gx, gg, gb
+
+
+def adam_step(p: torch.Tensor, m: torch.Tensor, v: torch.Tensor, g: torch.Tensor, lr: float, step: int,
+              beta1: float = 0.9, beta2: float = 0.999, eps: float = 1e-8) -> None:
+    """Updates p, m, v in place."""
+    rc = lib().gnn_adam_step(_dev(p, torch.float32, "p"), _dev(m, torch.float32, "m"), _dev(v, torch.float32, "v"),
+                             _dev(g, torch.float32, "g"), p.numel(), float(lr), float(beta1), float(beta2), float(eps),
+                             int(step), _stream())
+    _check(rc, "gnn_adam_step")
+
+
+def example_model_train_step(g: Graph, g_by_source: Graph, graph_indicator: torch.Tensor, num_graphs: int,
+                             x: torch.Tensor, target: torch.Tensor, params: dict, adam_m: dict, adam_v: dict,
+                             step: int, lr: float = 1e-4, bn_eps: float = 1e-5, beta1: float = 0.9,
+                             beta2: float = 0.999, adam_eps: float = 1e-8, loss: Optional[torch.Tensor] = None,
+                             workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """One training step of the example model (forward, MSE loss, gradients, Adam); params / adam_m / adam_v are
+    dicts of device tensors keyed as PARAM_ORDER and are updated in place.  Returns the loss (1-element tensor)."""
+    n, f0 = x.shape
+    f1, f2, f3 = int(params["w1"].shape[1]), int(params["w2"].shape[1]), int(params["w3"].shape[1])
+    if n != g.num_nodes or tuple(target.shape) != (num_graphs, f3) or int(graph_indicator.shape[0]) != n:
+        raise ValueError("shape mismatch")
+    need = int(lib().gnn_example_model_train_workspace_bytes(n, num_graphs, f0, f1, f2, f3))
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+    if loss is None:
+        loss = torch.empty(1, dtype=torch.float32, device=x.device)
+    arr = _vp * 8
+    pp = arr(*[_dev(params[k], torch.float32, k) for k in PARAM_ORDER])
+    pm = arr(*[_dev(adam_m[k], torch.float32, k) for k in PARAM_ORDER])
+    pv = arr(*[_dev(adam_v[k], torch.float32, k) for k in PARAM_ORDER])
+    rc = lib().gnn_example_model_train_step(g._h, g_by_source._h, _dev(graph_indicator, torch.int32, "graph_indicator"),
+                                            num_graphs, _dev(x, torch.float32, "x"), f0, f1, f2, f3,
+                                            _dev(target, torch.float32, "target"), pp, pm, pv, float(bn_eps), float(lr),
+                                            float(beta1), float(beta2), float(adam_eps), int(step), loss.data_ptr(),
+                                            workspace.data_ptr(), workspace.numel(), _stream())
+    _check(rc, "gnn_example_model_train_step")
+    return loss
 
 
 def graph_pool(graph_indicator: torch.Tensor, num_graphs: int, x: torch.Tensor, aggr: int = AGGR_SUM,

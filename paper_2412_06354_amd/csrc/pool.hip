@@ -71,7 +71,41 @@ __global__ __launch_bounds__(kThreads) void pool_kernel(const int32_t *__restric
     }
 }
 
+// Backward of sum / mean pooling: every node of graph g receives gout[g,:] (divided by the node count for
+// the mean).  One block per graph, same run search as the forward kernel; rows are written coalesced.
+__global__ __launch_bounds__(kThreads) void pool_backward_kernel(const int32_t *__restrict__ gi, int32_t N,
+                                                                 const float *__restrict__ gout, int32_t F, int mean,
+                                                                 float *__restrict__ gx)
+{
+    const int g = blockIdx.x;
+    const int lo = block_lower_bound(gi, N, g), hi = block_lower_bound(gi, N, g + 1);
+    const int cnt = hi - lo;
+    if (cnt <= 0) return;   // block-uniform
+    const int64_t total = (int64_t)cnt * F;
+    for (int64_t q = threadIdx.x; q < total; q += kThreads) {
+        const int f = (int)(q % F);
+        const float v = gout[(int64_t)g * F + f];
+        gx[(int64_t)lo * F + q] = mean ? v / (float)cnt : v;
+    }
+}
+
 }  // namespace
+
+extern "C" gnn_status gnn_graph_pool_backward(const int32_t *d_graph_indicator, int32_t num_nodes, int32_t num_graphs,
+                                              const float *d_grad_out, int32_t feat_dim, gnn_aggr aggr,
+                                              float *d_grad_x, void *stream)
+{
+    if (num_nodes < 0 || num_graphs <= 0 || feat_dim <= 0) return GNN_ERR_BAD_SIZE;
+    if (aggr == GNN_AGGR_MAX || aggr == GNN_AGGR_MIN || aggr == GNN_AGGR_PROD) return GNN_ERR_UNSUPPORTED;
+    if (aggr != GNN_AGGR_SUM && aggr != GNN_AGGR_MEAN) return GNN_ERR_BAD_SIZE;
+    if (num_nodes == 0) return GNN_OK;
+    if (!d_graph_indicator || !d_grad_out || !d_grad_x) return GNN_ERR_NULL;
+    hipLaunchKernelGGL(pool_backward_kernel, dim3((unsigned)num_graphs), dim3(kThreads), 0,
+                       static_cast<hipStream_t>(stream), d_graph_indicator, num_nodes, d_grad_out, feat_dim,
+                       aggr == GNN_AGGR_MEAN ? 1 : 0, d_grad_x);
+    GNN_LAUNCH_CHECK();
+    return GNN_OK;
+}
 
 extern "C" gnn_status gnn_graph_pool(const int32_t *d_graph_indicator, int32_t num_nodes, int32_t num_graphs,
                                      const float *d_x, int32_t feat_dim, gnn_aggr aggr, float *d_out, void *stream)

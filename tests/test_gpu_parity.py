@@ -651,6 +651,116 @@ def test_example_model_hip_graph_replay(gnn):
     g.close()
 
 
+def test_training_pieces(gnn):
+    """Loss, relu mask, pooling / dense / batch-norm backward and the Adam step, each against the oracle."""
+    # mean squared error
+    pred, target = synth.normal_f32(91, 2, 4096).reshape(4096, 1), synth.normal_f32(91, 3, 4096).reshape(4096, 1)
+    loss, grad = gnn.mse_loss(dev(pred), dev(target))
+    d = pred.astype(np.float64) - target
+    assert abs(float(host(loss)[0]) - (d ** 2).mean()) <= 1e-5 * (d ** 2).mean()
+    np.testing.assert_allclose(host(grad), 2 * d / d.size, rtol=1e-6, atol=1e-12)
+    # relu mask
+    yv, gv = synth.normal_f32(91, 4, 5000), synth.normal_f32(91, 5, 5000)
+    np.testing.assert_array_equal(host(gnn.relu_backward(dev(yv), dev(gv))), np.where(yv > 0, gv, np.float32(0)))
+    # pooling backward on batched graphs, one of them empty
+    wl = synth.config3_batched(num_graphs=300)
+    gi = wl.graph_indicator.copy()
+    gi[gi >= 17] += 1
+    ng, f = 301, 24
+    go = synth.normal_f32(91, 6, ng * f).reshape(ng, f)
+    np.testing.assert_array_equal(host(gnn.graph_pool_backward(dev(gi), ng, dev(go), AGGR_SUM)),
+                                  oracle.pool_backward(gi, ng, go, AGGR_SUM))
+    np.testing.assert_allclose(host(gnn.graph_pool_backward(dev(gi), ng, dev(go), AGGR_MEAN)),
+                               oracle.pool_backward(gi, ng, go, AGGR_MEAN), rtol=2e-7)
+    # dense backward
+    for rows, k, n in ((32, 64, 1), (5000, 64, 1), (3000, 16, 64), (777, 30, 5)):
+        x = synth.normal_f32(rows, 2, rows * k).reshape(rows, k)
+        w = synth.glorot_uniform(n, 4, k, n, (k, n))
+        gy = synth.normal_f32(rows, 7, rows * n).reshape(rows, n)
+        rx, rw, rb = oracle.dense_backward(x, w, gy)
+        gx, gw, gb = gnn.dense_backward(dev(x), dev(w), dev(gy))
+        a = lambda t: np.abs(t).astype(np.float64)
+        assert_close_sabs(host(gx), rx, a(gy) @ a(w).T, what=f"dense grad_x {rows}x{k}x{n}")
+        assert_close_sabs(host(gw), rw, a(x).T @ a(gy), what=f"dense grad_w {rows}x{k}x{n}")
+        assert_close_sabs(host(gb), rb, a(gy).sum(0), what=f"dense grad_b {rows}x{k}x{n}")
+    # batch-norm backward, with and without the relu mask
+    for n, f in ((5000, 64), (300, 7), (70_000, 40)):
+        x = (synth.normal_f32(92, 2, n * f).reshape(n, f) * (1.0 + np.arange(f, dtype=np.float32) % 3) + 1.0).astype(np.float32)
+        gamma, beta = synth.uniform_f32(92, 3, f, 0.5, 1.5), synth.uniform_f32(92, 4, f, -0.5, 0.5)
+        gy = synth.normal_f32(92, 5, n * f).reshape(n, f)
+        y, mean, var = oracle.batchnorm(x, gamma, beta, 1e-5, relu=True)
+        for masked in (False, True):
+            g_in = np.where(y > 0, gy, np.float32(0)).astype(np.float32) if masked else gy
+            rx, rg, rb = oracle.batchnorm_backward(x, gamma, g_in, 1e-5)
+            gx, gg, gb = gnn.batchnorm_backward(dev(x), dev(gamma), dev(mean), dev(var), dev(gy), 1e-5,
+                                                y_relu=dev(y) if masked else None)
+            inv = 1.0 / np.sqrt(var.astype(np.float64) + 1e-5)
+            xh = (x.astype(np.float64) - mean) * inv
+            s_b, s_g = np.abs(g_in).astype(np.float64).sum(0), (np.abs(g_in) * np.abs(xh)).sum(0)
+            assert_close_sabs(host(gb), rb, s_b, what="bn grad_beta")
+            assert_close_sabs(host(gg), rg, s_g, what="bn grad_gamma")
+            s_x = np.abs(gamma) * inv * (np.abs(g_in) + s_b / n + np.abs(xh) * s_g / n)
+            assert_close_sabs(host(gx), rx, s_x, what=f"bn grad_x {n}x{f} masked={masked}")
+    # Adam
+    cnt = 10_000
+    p0, g0 = synth.normal_f32(93, 2, cnt), synth.normal_f32(93, 3, cnt)
+    m0, v0 = 0.1 * synth.normal_f32(93, 4, cnt), np.abs(synth.normal_f32(93, 5, cnt)) * 0.01
+    rp, rm, rv = oracle.adam_step(p0, m0, v0, g0, 1e-3, 7)
+    p, m, v = dev(p0), dev(m0), dev(v0)
+    gnn.adam_step(p, m, v, dev(g0), 1e-3, 7)
+    np.testing.assert_allclose(host(m), rm, rtol=0, atol=3e-7 * (0.9 * np.abs(m0) + 0.1 * np.abs(g0)).max())   # two signed terms
+    np.testing.assert_allclose(host(v), rv, rtol=1e-6, atol=1e-12)
+    np.testing.assert_allclose(host(p), rp, rtol=0, atol=1e-3 * 1e-5 + 2.0 ** -23 * np.abs(rp).max())
+
+
+def test_example_model_train_step(gnn):
+    """Three training steps in one call each against the oracle's loop (forward, loss, backward, Adam):
+    the loss of every step to 1e-4, the parameters after the last step to a small fraction of the total
+    update.  (The gradient of b1 is exactly zero in exact arithmetic -- the batch norm removes it -- so
+    Adam moves b1 by rounding noise of either sign; it is only checked to stay within the size of a step.)
+    Then: two runs are bitwise identical, and a longer run drives the loss down."""
+    wl = synth.config5_example_model(num_graphs=64)
+    n, ng, p0 = wl.num_nodes, wl.num_graphs, wl.params
+    target = synth.normal_f32(95, 9, ng).reshape(ng, 1)
+    lr, steps = 1e-3, 3
+    # oracle loop
+    rp = {k: v.copy() for k, v in p0.items()}
+    rm = {k: np.zeros_like(v) for k, v in p0.items()}
+    rv = {k: np.zeros_like(v) for k, v in p0.items()}
+    ref_losses = []
+    for t in range(1, steps + 1):
+        loss, grads, _ = oracle.example_model_backward(wl.src, wl.dst, n, wl.graph_indicator, ng, wl.x, rp, target)
+        ref_losses.append(loss)
+        for k in rp:
+            a, b, c = oracle.adam_step(rp[k], rm[k], rv[k], grads[k], lr, t)
+            rp[k], rm[k], rv[k] = a.reshape(rp[k].shape), b.reshape(rp[k].shape), c.reshape(rp[k].shape)
+    g = gnn.build_csr(dev(wl.src), dev(wl.dst), n)
+    gt = gnn.build_csr(dev(wl.dst), dev(wl.src), n)
+    gi, x, tg = dev(wl.graph_indicator), dev(wl.x), dev(target)
+
+    def run(count, rate):
+        dp = {k: dev(v.copy()) for k, v in p0.items()}
+        dm = {k: torch.zeros_like(v) for k, v in dp.items()}
+        dv = {k: torch.zeros_like(v) for k, v in dp.items()}
+        losses = [float(host(gnn.example_model_train_step(g, gt, gi, ng, x, tg, dp, dm, dv, t, lr=rate))[0])
+                  for t in range(1, count + 1)]
+        return dp, losses
+
+    dp, losses = run(steps, lr)
+    np.testing.assert_allclose(losses, ref_losses, rtol=1e-4)
+    for k in p0:
+        moved = np.abs(host(dp[k]).astype(np.float64) - p0[k])
+        assert moved.max() <= steps * lr * 1.2, k          # an Adam step is about lr at most in these first steps
+        if k != "b1":
+            np.testing.assert_allclose(host(dp[k]), rp[k], rtol=0, atol=2e-2 * lr, err_msg=k)
+    dp2, losses2 = run(steps, lr)
+    assert losses2 == losses and all(torch.equal(dp[k], dp2[k]) for k in p0)
+    _, long_losses = run(150, 1e-2)
+    assert long_losses[-1] < 0.6 * long_losses[0]
+    g.close()
+    gt.close()
+
+
 @pytest.mark.parametrize("heads", [1, 8, 3])
 def test_segment_softmax(case, gnn, heads):
     name, wl, g = case
