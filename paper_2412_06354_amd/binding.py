@@ -128,6 +128,13 @@ def _dev(t: Optional[torch.Tensor], dtype, name: str) -> Optional[int]:
     return t.data_ptr()
 
 
+def _edge_rows(t: torch.Tensor, num_edges: int) -> torch.Tensor:
+    """[E, width] view of per-edge data given as [E] or [E, width] (also when E == 0)."""
+    if num_edges == 0:
+        return t.reshape(0, int(t.shape[1]) if t.dim() == 2 else 1)
+    return t.reshape(num_edges, -1)
+
+
 class Graph:
     """Owner of a ``gnn_graph`` handle (CSR by destination + work lists, all in device memory)."""
 
@@ -228,7 +235,7 @@ def hetero_propagate(graphs, xs, es=None, msg: int = MSG_COPY_XJ, aggr: int = AG
     e_dim = 1
     e2 = None
     if es is not None:
-        e2 = [e.reshape(g.num_edges, -1) for g, e in zip(graphs, es)]
+        e2 = [_edge_rows(e, g.num_edges) for g, e in zip(graphs, es)]
         e_dim = int(e2[0].shape[1])
     for g, x in zip(graphs, xs):
         if tuple(x.shape) != (g.num_src_nodes, f):
@@ -246,7 +253,7 @@ def hetero_propagate(graphs, xs, es=None, msg: int = MSG_COPY_XJ, aggr: int = AG
 
 
 def edge_data_to_csr(g: Graph, e: torch.Tensor) -> torch.Tensor:
-    e2 = e.reshape(g.num_edges, -1)
+    e2 = _edge_rows(e, g.num_edges)
     out = torch.empty_like(e2)
     _check(lib().gnn_edge_data_to_csr(g._h, _dev(e2, torch.float32, "e"), e2.shape[1],
                                       out.data_ptr(), _stream()), "gnn_edge_data_to_csr")
@@ -261,7 +268,7 @@ def propagate(g: Graph, x: torch.Tensor, e: Optional[torch.Tensor] = None, msg: 
         raise ValueError("x must have one row per (source) node")
     e_dim = 1
     if e is not None:
-        e = e.reshape(g.num_edges, -1)
+        e = _edge_rows(e, g.num_edges)
         e_dim = int(e.shape[1])
     if out is None:
         out = torch.empty((g.num_nodes, f), dtype=torch.float32, device=x.device)
@@ -305,7 +312,7 @@ def apply_edges(g: Graph, x: torch.Tensor, e: Optional[torch.Tensor] = None, msg
         raise ValueError("x must have one row per (source) node")
     e_dim = 1
     if e is not None:
-        e = e.reshape(g.num_edges, -1)
+        e = _edge_rows(e, g.num_edges)
         e_dim = int(e.shape[1])
     if out is None:
         out = torch.empty((g.num_edges, 1 if msg == MSG_XI_DOT_XJ else f), dtype=torch.float32, device=x.device)
@@ -333,7 +340,7 @@ def propagate_argmax(g: Graph, x: torch.Tensor, out_max: torch.Tensor, e: Option
     n, f = x.shape
     e_dim = 1
     if e is not None:
-        e = e.reshape(g.num_edges, -1)
+        e = _edge_rows(e, g.num_edges)
         e_dim = int(e.shape[1])
     am = torch.empty((n, f), dtype=torch.int32, device=x.device)
     rc = lib().gnn_propagate_argmax(g._h, _dev(x, torch.float32, "x"), f, _dev(e, torch.float32, "e"), e_dim, e_order,
@@ -351,7 +358,7 @@ def propagate_backward(g: Graph, g_by_source: Optional[Graph], x: torch.Tensor, 
     e_dim = 1
     e2 = None
     if e is not None:
-        e2 = e.reshape(g.num_edges, -1)
+        e2 = _edge_rows(e, g.num_edges)
         e_dim = int(e2.shape[1])
     grad_x = torch.empty_like(grad_out) if want_grad_x else None
     grad_e = torch.empty_like(e2) if (want_grad_e and e2 is not None and msg == MSG_E_MUL_XJ) else None
@@ -414,7 +421,7 @@ def gcnconv_backward(g: Graph, g_by_source: Graph, x: torch.Tensor, w: torch.Ten
 
 def segment_softmax(g: Graph, scores: torch.Tensor, order: int = EDGE_ORDER_COO,
                     out: Optional[torch.Tensor] = None) -> torch.Tensor:
-    s2 = scores.reshape(g.num_edges, -1)
+    s2 = _edge_rows(scores, g.num_edges)
     if out is None:
         out = torch.empty_like(scores)
     rc = lib().gnn_segment_softmax(g._h, _dev(s2, torch.float32, "scores"), int(s2.shape[1]) if g.num_edges else 1,
@@ -427,7 +434,7 @@ def segment_softmax_backward(g: Graph, alpha: torch.Tensor, grad_alpha: torch.Te
                              out: Optional[torch.Tensor] = None) -> torch.Tensor:
     if alpha.shape != grad_alpha.shape:
         raise ValueError("shape mismatch")
-    a2, g2 = alpha.reshape(g.num_edges, -1), grad_alpha.reshape(g.num_edges, -1)
+    a2, g2 = _edge_rows(alpha, g.num_edges), _edge_rows(grad_alpha, g.num_edges)
     if out is None:
         out = torch.empty_like(alpha)
     rc = lib().gnn_segment_softmax_backward(g._h, _dev(a2, torch.float32, "alpha"),

@@ -944,3 +944,63 @@ def test_pool_one_big_graph(gnn):
             np.testing.assert_array_equal(got, ref)
         else:
             assert_close_sabs(got, ref, sabs, what=f"big pool aggr={aggr}")
+
+
+def test_degenerate_graphs_through_every_entry_point(gnn):
+    """No edges at all, a single node, a single self-loop: every entry point returns what the oracle
+    returns (zeros for empty neighbourhoods, no fault, no stale memory)."""
+    f = 8
+    for n, src, dst in ((5, np.zeros(0, np.int32), np.zeros(0, np.int32)),
+                        (1, np.zeros(0, np.int32), np.zeros(0, np.int32)),
+                        (1, np.zeros(1, np.int32), np.zeros(1, np.int32)),
+                        (3, np.array([2], np.int32), np.array([2], np.int32))):
+        ne = src.shape[0]
+        x = synth.normal_f32(7 + n, 2, n * f).reshape(n, f)
+        w = synth.glorot_uniform(7, 3, f, f, (f, f))
+        g = gnn.build_csr(dev(src), dev(dst), n)
+        gt = gnn.build_csr(dev(dst), dev(src), n)
+        e = synth.uniform_f32(7, 4, max(ne, 1))[:ne]
+        de = dev(e) if ne else torch.zeros(0, dtype=torch.float32, device="cuda")
+        for msg in (MSG_COPY_XJ, MSG_E_MUL_XJ, MSG_XJ_SUB_XI):
+            for aggr in (AGGR_SUM, AGGR_MEAN, AGGR_MAX, AGGR_MIN, AGGR_PROD):
+                ed = e if msg == MSG_E_MUL_XJ else None
+                ref = oracle.propagate(src, dst, n, x, ed, msg, aggr)
+                got = host(gnn.propagate(g, dev(x), de if msg == MSG_E_MUL_XJ else None, msg, aggr))
+                np.testing.assert_allclose(got, ref, rtol=1e-6, atol=1e-7)
+        np.testing.assert_allclose(host(gnn.gcnconv(g, dev(x), dev(w), None, True)),
+                                   oracle.gcnconv(src, dst, n, x, w, None, True), rtol=1e-5, atol=1e-6)
+        np.testing.assert_allclose(host(gnn.gcnconv(g, dev(x), dev(w), None, False)),
+                                   oracle.gcnconv(src, dst, n, x, w, None, False), rtol=1e-5, atol=1e-6)
+        np.testing.assert_allclose(host(gnn.gin_update(g, dev(x), 0.5)), oracle.gin_update(src, dst, n, x, 0.5),
+                                   rtol=1e-6, atol=1e-7)
+        gout = synth.normal_f32(7, 5, n * f).reshape(n, f)
+        ref = oracle.propagate_backward(src, dst, n, x, gout, e if ne else np.zeros(0, np.float32), MSG_E_MUL_XJ, AGGR_SUM)
+        gx, ge = gnn.propagate_backward(g, gt, dev(x), dev(gout), de, MSG_E_MUL_XJ, AGGR_SUM)
+        np.testing.assert_allclose(host(gx), ref["grad_x"], rtol=1e-6, atol=1e-7)
+        if ne:
+            np.testing.assert_allclose(host(ge).reshape(-1), ref["grad_e"].reshape(-1), rtol=1e-5, atol=1e-6)
+        rb = oracle.gcnconv_backward(src, dst, n, x, w, gout, True)
+        bx, bw, bb = gnn.gcnconv_backward(g, gt, dev(x), dev(w), dev(gout), True)
+        np.testing.assert_allclose(host(bx), rb["grad_x"], rtol=1e-5, atol=1e-6)
+        np.testing.assert_allclose(host(bw), rb["grad_w"], rtol=1e-5, atol=1e-6)
+        np.testing.assert_allclose(host(bb), rb["grad_b"], rtol=1e-5, atol=1e-6)
+        heads, ch = 2, 4
+        a_s = synth.uniform_f32(7, 6, heads * ch, -1, 1).reshape(heads, ch)
+        a_d = synth.uniform_f32(7, 8, heads * ch, -1, 1).reshape(heads, ch)
+        stats = torch.empty((n, heads, 2), dtype=torch.float32, device="cuda")
+        out = gnn.gatconv(g, dev(x), dev(w), dev(a_s), dev(a_d), 0.2, softmax_stats=stats)
+        np.testing.assert_allclose(host(out), oracle.gatconv(src, dst, n, x, w, a_s, a_d, 0.2), rtol=1e-5, atol=1e-6)
+        rg = oracle.gatconv_backward(src, dst, n, x, w, a_s, a_d, gout, 0.2)
+        got = gnn.gatconv_backward(g, gt, dev(x), dev(w), dev(a_s), dev(a_d), out, stats, dev(gout), 0.2)
+        for t, k in zip(got, ("grad_x", "grad_w", "grad_a_src", "grad_a_dst")):
+            np.testing.assert_allclose(host(t), rg[k], rtol=1e-4, atol=1e-5, err_msg=k)
+        if ne:
+            sc = synth.normal_f32(7, 9, ne * heads).reshape(ne, heads)
+            al = gnn.segment_softmax(g, dev(sc))
+            np.testing.assert_allclose(host(al), oracle.segment_softmax(dst, n, sc), rtol=1e-6)
+            ga = synth.normal_f32(7, 10, ne * heads).reshape(ne, heads)
+            np.testing.assert_allclose(host(gnn.segment_softmax_backward(g, al, dev(ga))),
+                                       oracle.segment_softmax_backward(dst, n, host(al), ga), rtol=1e-5, atol=1e-6)
+        g.close()
+        gt.close()
+
