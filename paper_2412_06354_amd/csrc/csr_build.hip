@@ -66,83 +66,95 @@ __global__ __launch_bounds__(kThreads) void run_lengths_kernel(const int32_t *__
 
 constexpr int kSortItems = 16;                       // keys per thread
 constexpr int kSortTile = kThreads * kSortItems;     // keys per block
-constexpr int kWaves = kThreads / 64;
 constexpr int kRadixMax = 256;
 
 // Per-tile digit counts, laid out [digit][tile] so that one exclusive scan over the whole
 // array yields, for every (digit, tile), the first output position of that tile's keys.
-__global__ __launch_bounds__(kThreads) void sort_count_kernel(const int32_t *__restrict__ keys, int64_t n, int shift,
-                                                              int bits, int32_t *__restrict__ tile_counts,
-                                                              int num_tiles)
+// Every wavefront counts into its own LDS histogram (fewer colliding atomics), the copies are added at the end.
+constexpr int kCountThreads = 1024;
+constexpr int kCountItems = kSortTile / kCountThreads;
+constexpr int kCountWaves = kCountThreads / 64;
+
+__global__ __launch_bounds__(kCountThreads) void sort_count_kernel(const int32_t *__restrict__ keys, int64_t n, int shift,
+                                                                   int bits, int32_t *__restrict__ tile_counts,
+                                                                   int num_tiles)
 {
-    __shared__ int cnt[kRadixMax];
+    __shared__ int cnt[kCountWaves][kRadixMax];
     const int radix = 1 << bits, mask = radix - 1;
-    for (int d = threadIdx.x; d < radix; d += kThreads) cnt[d] = 0;
-    __syncthreads();
+    const int w = threadIdx.x >> 6;
+    for (int d = threadIdx.x; d < kCountWaves * kRadixMax; d += kCountThreads) (&cnt[0][0])[d] = 0;
     const int64_t base = (int64_t)blockIdx.x * kSortTile;
-#pragma unroll 4
-    for (int i = 0; i < kSortItems; ++i) {
-        const int64_t idx = base + i * kThreads + threadIdx.x;
-        if (idx < n) atomicAdd(&cnt[(keys[idx] >> shift) & mask], 1);
+    int key[kCountItems];
+    bool valid[kCountItems];
+#pragma unroll
+    for (int i = 0; i < kCountItems; ++i) {
+        const int64_t idx = base + i * kCountThreads + threadIdx.x;
+        valid[i] = idx < n;
+        key[i] = valid[i] ? keys[idx] : 0;
     }
     __syncthreads();
-    for (int d = threadIdx.x; d < radix; d += kThreads) tile_counts[(int64_t)d * num_tiles + blockIdx.x] = cnt[d];
-}
-
-__device__ __forceinline__ int block_exclusive_scan_256(int v, int *wave_sums /* [kWaves] in LDS */)
-{
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    int inc = v;
 #pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const int t = __shfl_up(inc, off, 64);
-        if (lane >= off) inc += t;
-    }
-    if (lane == 63) wave_sums[w] = inc;
+    for (int i = 0; i < kCountItems; ++i)
+        if (valid[i]) atomicAdd(&cnt[w][(key[i] >> shift) & mask], 1);
     __syncthreads();
-    int base = 0;
+    for (int d = threadIdx.x; d < radix; d += kCountThreads) {
+        int t = 0;
 #pragma unroll
-    for (int i = 0; i < kWaves; ++i)
-        if (i < w) base += wave_sums[i];
-    return base + inc - v;
+        for (int q = 0; q < kCountWaves; ++q) t += cnt[q][d];
+        tile_counts[(int64_t)d * num_tiles + blockIdx.x] = t;
+    }
 }
 
-// Stable scatter of one pass.  Inside a tile the order is: wavefront, then item, then lane;
-// key `idx` of wavefront w is tile_base + w*64*items + item*64 + lane, so this order is the
-// input order.  A key's position inside the tile's digit-sorted order is
+// Stable scatter of one pass.  A tile (kSortTile consecutive keys) is handled by a block of
+// kScatterThreads threads, kScatterItems keys per thread; inside a tile the order is: wavefront, then
+// item, then lane; key `idx` of wavefront w is tile_base + w*64*items + item*64 + lane, so this order is
+// the input order.  A key's position inside the tile's digit-sorted order is
 //   (keys of smaller digits in the tile) + (same-digit keys of earlier wavefronts)
 //   + (same-digit keys of this wavefront in earlier items or lower lanes);
 // the last term comes from ballots: the lanes holding the same digit are found bit by bit.
-// Keys, values and edge ids are then passed through LDS in that order, so that consecutive
-// threads write consecutive global addresses (each digit of a tile is one contiguous run).
-__global__ __launch_bounds__(kThreads) void sort_scatter_kernel(
+// Keys, values and edge ids are all loaded up front, then passed through LDS in that order in one
+// phase, so that consecutive threads write consecutive global addresses (each digit of a tile is one
+// contiguous run).  Many short per-thread chains (16 wavefronts x 4 items) hide the latency of the
+// ranking loop better than few long ones: 145 us per pass at 20 M keys against 210 us for 4 x 16.
+constexpr int kScatterThreads = 1024;
+constexpr int kScatterItems = kSortTile / kScatterThreads;
+constexpr int kScatterWaves = kScatterThreads / 64;
+static_assert(kScatterItems * kScatterThreads == kSortTile, "tile size");
+
+__global__ __launch_bounds__(kScatterThreads) void sort_scatter_kernel(
     const int32_t *__restrict__ keys_in, const int32_t *__restrict__ val_in, const int32_t *__restrict__ eid_in,
     int64_t n, int shift, int bits, const int32_t *__restrict__ tile_offsets, int num_tiles,
     int32_t *__restrict__ keys_out, int32_t *__restrict__ val_out, int32_t *__restrict__ eid_out)
 {
-    __shared__ int wcnt[kWaves][kRadixMax];
+    __shared__ int wcnt[kScatterWaves][kRadixMax];
     __shared__ int dbase[kRadixMax];   // first tile-local position of each digit
     __shared__ int gbase[kRadixMax];   // global position of that element minus dbase
-    __shared__ int wave_sums[kWaves];
-    __shared__ int stage[kSortTile];
+    __shared__ int wave_sums[kScatterWaves];
+    __shared__ int stage[3][kSortTile];
     const int radix = 1 << bits, mask = radix - 1;
     const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    for (int d = threadIdx.x; d < kWaves * kRadixMax; d += kThreads) (&wcnt[0][0])[d] = 0;
-    __syncthreads();
+    for (int d = threadIdx.x; d < kScatterWaves * kRadixMax; d += kScatterThreads) (&wcnt[0][0])[d] = 0;
 
     const int64_t tile_base = (int64_t)blockIdx.x * kSortTile;
-    const int64_t wbase = tile_base + (int64_t)w * 64 * kSortItems;
+    const int64_t wbase = tile_base + (int64_t)w * 64 * kScatterItems;
     const int tile_count = (int)min((int64_t)kSortTile, n - tile_base);
     const uint64_t lt_mask = (1ull << lane) - 1ull;
     volatile int *my_cnt = wcnt[w];
-    int key[kSortItems];
-    int lpos[kSortItems];
+    int key[kScatterItems], val[kScatterItems], eid[kScatterItems], lpos[kScatterItems];
 #pragma unroll
-    for (int i = 0; i < kSortItems; ++i) {
+    for (int i = 0; i < kScatterItems; ++i) {
         const int64_t idx = wbase + i * 64 + lane;
         const bool valid = idx < n;
-        const int k = valid ? keys_in[idx] : 0;
-        const int d = (k >> shift) & mask;
+        key[i] = valid ? keys_in[idx] : 0;
+        val[i] = valid ? val_in[idx] : 0;
+        eid[i] = valid ? (eid_in ? eid_in[idx] : (int32_t)idx) : 0;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < kScatterItems; ++i) {
+        const int64_t idx = wbase + i * 64 + lane;
+        const bool valid = idx < n;
+        const int d = (key[i] >> shift) & mask;
         uint64_t peers = __ballot(valid);
         for (int b = 0; b < bits; ++b) {
             const bool bit = (d >> b) & 1;
@@ -155,7 +167,6 @@ __global__ __launch_bounds__(kThreads) void sort_scatter_kernel(
         __builtin_amdgcn_wave_barrier();
         if (valid && r == 0) my_cnt[d] = before + __popcll(peers);
         __builtin_amdgcn_wave_barrier();
-        key[i] = k;
         lpos[i] = before + r;
     }
     __syncthreads();
@@ -164,59 +175,55 @@ __global__ __launch_bounds__(kThreads) void sort_scatter_kernel(
     if ((int)threadIdx.x < radix) {
         const int d = threadIdx.x;
 #pragma unroll
-        for (int q = 0; q < kWaves; ++q) {
+        for (int q = 0; q < kScatterWaves; ++q) {
             const int c = wcnt[q][d];
             wcnt[q][d] = total;
             total += c;
         }
     }
-    const int excl = block_exclusive_scan_256(total, wave_sums);
+    int excl;
+    {   // block-wide exclusive scan of `total`
+        int inc = total;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int t = __shfl_up(inc, off, 64);
+            if (lane >= off) inc += t;
+        }
+        if (lane == 63) wave_sums[w] = inc;
+        __syncthreads();
+        int base = 0;
+        for (int q = 0; q < kScatterWaves; ++q)
+            if (q < w) base += wave_sums[q];
+        excl = base + inc - total;
+    }
     if ((int)threadIdx.x < radix) {
         dbase[threadIdx.x] = excl;
         gbase[threadIdx.x] = tile_offsets[(int64_t)threadIdx.x * num_tiles + blockIdx.x] - excl;
     }
     __syncthreads();
 #pragma unroll
-    for (int i = 0; i < kSortItems; ++i) {
+    for (int i = 0; i < kScatterItems; ++i) {
         const int64_t idx = wbase + i * 64 + lane;
         if (idx < n) {
             const int d = (key[i] >> shift) & mask;
-            lpos[i] += dbase[d] + wcnt[w][d];
-            stage[lpos[i]] = key[i];
+            const int pos = lpos[i] + dbase[d] + wcnt[w][d];
+            stage[0][pos] = key[i];
+            stage[1][pos] = val[i];
+            stage[2][pos] = eid[i];
         }
     }
     __syncthreads();
-    int gpos[kSortItems];
 #pragma unroll
-    for (int i = 0; i < kSortItems; ++i) {
-        const int s = i * kThreads + threadIdx.x;
-        gpos[i] = -1;
+    for (int i = 0; i < kScatterItems; ++i) {
+        const int s = i * kScatterThreads + threadIdx.x;
         if (s < tile_count) {
-            const int k = stage[s];
-            gpos[i] = gbase[(k >> shift) & mask] + s;
-            if (keys_out) keys_out[gpos[i]] = k;
+            const int k = stage[0][s];
+            const int gpos = gbase[(k >> shift) & mask] + s;
+            if (keys_out) keys_out[gpos] = k;
+            val_out[gpos] = stage[1][s];
+            eid_out[gpos] = stage[2][s];
         }
     }
-    __syncthreads();
-#pragma unroll
-    for (int i = 0; i < kSortItems; ++i) {
-        const int64_t idx = wbase + i * 64 + lane;
-        if (idx < n) stage[lpos[i]] = val_in[idx];
-    }
-    __syncthreads();
-#pragma unroll
-    for (int i = 0; i < kSortItems; ++i)
-        if (gpos[i] >= 0) val_out[gpos[i]] = stage[i * kThreads + threadIdx.x];
-    __syncthreads();
-#pragma unroll
-    for (int i = 0; i < kSortItems; ++i) {
-        const int64_t idx = wbase + i * 64 + lane;
-        if (idx < n) stage[lpos[i]] = eid_in ? eid_in[idx] : (int32_t)idx;
-    }
-    __syncthreads();
-#pragma unroll
-    for (int i = 0; i < kSortItems; ++i)
-        if (gpos[i] >= 0) eid_out[gpos[i]] = stage[i * kThreads + threadIdx.x];
 }
 
 __global__ __launch_bounds__(kThreads) void iota_copy_kernel(const int32_t *__restrict__ key_in,
@@ -411,11 +418,11 @@ gnn_status build_impl(const int32_t *d_src, const int32_t *d_dst, int64_t E, int
             const int32_t *ki = d_dst, *vi = d_src, *ei = nullptr;
             for (int p = 0; p < passes; ++p) {
                 const int shift = p * bits;
-                hipLaunchKernelGGL(sort_count_kernel, dim3((unsigned)num_tiles), dim3(kThreads), 0, stream, ki, E,
+                hipLaunchKernelGGL(sort_count_kernel, dim3((unsigned)num_tiles), dim3(kCountThreads), 0, stream, ki, E,
                                    shift, bits, counts, (int)num_tiles);
                 GNN_LAUNCH_CHECK();
                 GNN_TRY(gnn_scan_exclusive_i32(counts, counts, num_tiles << bits, false, scan_tmp, stream));
-                hipLaunchKernelGGL(sort_scatter_kernel, dim3((unsigned)num_tiles), dim3(kThreads), 0, stream, ki, vi,
+                hipLaunchKernelGGL(sort_scatter_kernel, dim3((unsigned)num_tiles), dim3(kScatterThreads), 0, stream, ki, vi,
                                    ei, E, shift, bits, counts, (int)num_tiles, bufk[dst_sel], bufv[dst_sel],
                                    bufe[dst_sel]);
                 GNN_LAUNCH_CHECK();

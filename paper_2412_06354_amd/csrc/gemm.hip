@@ -293,7 +293,6 @@ template <int NT>
 gnn_status launch_xw(const float *d_x, int64_t rows, int k, const float *d_w, int n, const float *d_row_scale,
                      float *d_z, bool x_vec4, bool w_vec4, hipStream_t s)
 {
-    constexpr int BN = NT * 32;
     const bool fast = x_vec4 && w_vec4 && k <= 2 * kSlab;   // w_vec4 implies n % 4 == 0
     if (!fast) return launch_general<NT>(d_x, rows, k, d_w, n, d_row_scale, d_z, x_vec4, w_vec4, 0, s);
     if (k <= kSlab) return launch_fast<NT, 1>(d_x, rows, k, d_w, n, d_row_scale, d_z, s);
