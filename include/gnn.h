@@ -110,6 +110,13 @@ gnn_status gnn_build_csr_bipartite(const int32_t *d_src, const int32_t *d_dst, i
                                    int32_t num_src_nodes, int32_t num_dst_nodes, void *stream,
                                    gnn_graph **out_graph);
 
+/*
+ * gnn_build_csr keeps its temporaries (about 16 bytes per edge) in one device buffer per process between
+ * calls, so that building graph after graph does not allocate and free each time.  This call frees that
+ * buffer (GNN_ERR_UNSUPPORTED if a build is using it on another thread); the next build allocates it again.
+ */
+gnn_status gnn_release_cached_memory(void);
+
 /* Frees everything the graph owns.  The caller makes sure no enqueued work still uses it. */
 gnn_status gnn_graph_destroy(gnn_graph *g);
 

@@ -41,6 +41,7 @@ SIGNATURES = {
     "gnn_build_csr_bipartite": (_c.c_int, [_vp, _vp, _i64, _i32, _i32, _vp, _c.POINTER(_vp)]),
     "gnn_graph_num_src_nodes": (_i32, [_vp]),
     "gnn_hetero_propagate": (_c.c_int, [_i32, _vp, _vp, _vp, _i32, _i32, _c.c_int, _c.c_int, _c.c_int, _vp, _vp]),
+    "gnn_release_cached_memory": (_c.c_int, []),
     "gnn_propagate_bf16": (_c.c_int, [_vp, _vp, _i32, _vp, _c.c_int, _c.c_int, _c.c_int, _vp, _vp]),
     "gnn_f32_to_bf16": (_c.c_int, [_vp, _i64, _vp, _vp]),
     "gnn_apply_edges": (_c.c_int, [_vp, _vp, _i32, _vp, _i32, _c.c_int, _c.c_int, _vp, _c.c_int, _vp]),
@@ -211,6 +212,10 @@ def build_csr(src: torch.Tensor, dst: torch.Tensor, num_nodes: int, small_max_de
                                 small_max_degree, chunk_edges, _stream(), ctypes.byref(out))
     _check(rc, "gnn_build_csr")
     return Graph(out.value, src.device)
+
+
+def release_cached_memory() -> None:
+    _check(lib().gnn_release_cached_memory(), "gnn_release_cached_memory")
 
 
 def build_csr_bipartite(src: torch.Tensor, dst: torch.Tensor, num_src_nodes: int, num_dst_nodes: int) -> Graph:

@@ -9,6 +9,9 @@
 // neighbourhood is a contiguous segment.
 #include "gnn_internal.h"
 
+#include <algorithm>
+#include <mutex>
+
 namespace {
 
 constexpr int kThreads = 256;
@@ -29,37 +32,35 @@ __global__ __launch_bounds__(kThreads) void check_range_kernel(const int32_t *__
     if (any_bad) atomicOr(bad, 1);
 }
 
-// Copies the range flag and the four list sizes into one small array (one host read-back).
+// Copies the range flag and the four list sizes into one small array (one host read-back).  pos holds ONE
+// exclusive scan over the four concatenated flag arrays, so a list's size is a difference.
 __global__ void gather_totals_kernel(const int32_t *__restrict__ flag, const int32_t *__restrict__ pos, int64_t np1,
                                      int32_t N, int32_t *__restrict__ out)
 {
     if (threadIdx.x == 0) out[0] = flag[0];
-    if (threadIdx.x < 4) out[1 + threadIdx.x] = pos[threadIdx.x * np1 + N];
+    if (threadIdx.x < 4) out[1 + threadIdx.x] = pos[threadIdx.x * np1 + N] - pos[threadIdx.x * np1];
 }
 
-// In-degree histogram from the sorted destinations: every destination that occurs forms one run;
-// the first kernel records where each run starts, the second (a separate launch, so that all
-// starts are visible) writes run length = in-degree at each run's last element.  Rows that do not
-// occur keep the 0 they were cleared to.
-__global__ __launch_bounds__(kThreads) void run_starts_kernel(const int32_t *__restrict__ keys, int64_t E, int32_t N,
-                                                              int32_t *__restrict__ starts)
+// In-degree histogram from the sorted destinations: every destination that occurs forms one run.  One pass
+// over the edges records where each run starts and (in the in-degree array) where it ends; a pass over
+// the rows turns the pair into the run length.  Rows that do not occur keep 0 - 0.
+__global__ __launch_bounds__(kThreads) void run_bounds_kernel(const int32_t *__restrict__ keys, int64_t E, int32_t N,
+                                                              int32_t *__restrict__ starts,
+                                                              int32_t *__restrict__ ends)
 {
     const int64_t p = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (p >= E) return;
     const int32_t k = keys[p];
     if ((uint32_t)k >= (uint32_t)N) return;   // invalid input: reported through the range flag, never indexed with
     if (p == 0 || keys[p - 1] != k) starts[k] = (int32_t)p;
+    if (p == E - 1 || keys[p + 1] != k) ends[k] = (int32_t)(p + 1);
 }
 
-__global__ __launch_bounds__(kThreads) void run_lengths_kernel(const int32_t *__restrict__ keys, int64_t E, int32_t N,
-                                                               const int32_t *__restrict__ starts,
+__global__ __launch_bounds__(kThreads) void run_lengths_kernel(int32_t N, const int32_t *__restrict__ starts,
                                                                int32_t *__restrict__ indeg)
 {
-    const int64_t p = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (p >= E) return;
-    const int32_t k = keys[p];
-    if ((uint32_t)k >= (uint32_t)N) return;
-    if (p == E - 1 || keys[p + 1] != k) indeg[k] = (int32_t)(p + 1) - starts[k];
+    const int32_t r = blockIdx.x * kThreads + threadIdx.x;
+    if (r < N) indeg[r] -= starts[r];
 }
 
 // ---------------------------------------------------------------- radix sort passes
@@ -253,6 +254,7 @@ __global__ __launch_bounds__(kThreads) void classify_rows_kernel(const int32_t *
 {
     const int32_t r = blockIdx.x * kThreads + threadIdx.x;
     if (r >= N) return;
+    if (r == 0) f_small[N] = f_items[N] = f_slots[N] = f_split[N] = 0;   // the four arrays are scanned as one
     const int32_t deg = indeg[r];
     const int small = deg <= small_max;
     const int items = small ? 0 : (deg + chunk - 1) / chunk;
@@ -271,22 +273,24 @@ __global__ __launch_bounds__(kThreads) void fill_lists_kernel(
 {
     const int32_t r = blockIdx.x * kThreads + threadIdx.x;
     if (r >= N) return;
+    // the four position arrays are slices of one exclusive scan: positions are relative to each slice's first entry
     const int32_t start = rowptr[r], deg = rowptr[r + 1] - start;
     if (deg <= small_max) {
-        small_rows[p_small[r]] = r;
+        small_rows[p_small[r] - p_small[0]] = r;
         return;
     }
     const int items = (deg + chunk - 1) / chunk;
-    const int32_t it0 = p_items[r];
+    const int32_t it0 = p_items[r] - p_items[0];
     if (items == 1) {
         item_row[it0] = r;
         item_start[it0] = start;
         item_slot[it0] = -1;
         return;
     }
-    const int32_t slot0 = p_slots[r];
-    split_rows[p_split[r]] = r;
-    split_slot0[p_split[r]] = slot0;
+    const int32_t slot0 = p_slots[r] - p_slots[0];
+    const int32_t sp = p_split[r] - p_split[0];
+    split_rows[sp] = r;
+    split_slot0[sp] = slot0;
     for (int c = 0; c < items; ++c) {
         item_row[it0 + c] = r;
         item_start[it0 + c] = start + c * chunk;
@@ -344,6 +348,69 @@ gnn_status slab_alloc(void **out, size_t bytes)
     return GNN_OK;
 }
 
+// The temporaries of a build (sort buffers, counts, flags) are kept between calls: one grow-only device
+// buffer per process, lent to one build at a time (a build ends with a stream synchronisation, so the buffer
+// is idle when it is handed back).  A build that finds it lent out, on another device, or that needs more
+// than kTempCacheLimit allocates and frees its own.  gnn_release_cached_memory() frees it.
+constexpr size_t kTempCacheLimit = (size_t)8 << 30;
+
+struct temp_cache {
+    std::mutex mu;
+    void *ptr = nullptr;
+    size_t bytes = 0;
+    int device = -1;
+    bool lent = false;
+};
+temp_cache g_temp_cache;
+
+struct temp_lease {
+    void *ptr = nullptr;
+    bool cached = false;
+    ~temp_lease()
+    {
+        if (!ptr) return;
+        if (cached) {
+            std::lock_guard<std::mutex> lock(g_temp_cache.mu);
+            g_temp_cache.lent = false;
+        } else {
+            (void)hipFree(ptr);
+        }
+    }
+};
+
+gnn_status temp_acquire(temp_lease *lease, size_t bytes)
+{
+    int dev = 0;
+    GNN_HIP(hipGetDevice(&dev));
+    {
+        std::lock_guard<std::mutex> lock(g_temp_cache.mu);
+        temp_cache &c = g_temp_cache;
+        if (!c.lent && bytes <= kTempCacheLimit) {
+            if (c.ptr && (c.device != dev || c.bytes < bytes)) {
+                (void)hipFree(c.ptr);   // nobody holds it: replace by a larger one / one on this device
+                c.ptr = nullptr;
+                c.bytes = 0;
+            }
+            if (!c.ptr) {
+                const size_t want = bytes + bytes / 8;   // some head-room for the next, slightly larger graph
+                if (hipMalloc(&c.ptr, want) != hipSuccess) {
+                    (void)hipGetLastError();
+                    c.ptr = nullptr;
+                    return GNN_ERR_ALLOC;
+                }
+                c.bytes = want;
+                c.device = dev;
+            }
+            c.lent = true;
+            lease->ptr = c.ptr;
+            lease->cached = true;
+            return GNN_OK;
+        }
+    }
+    lease->cached = false;
+    return slab_alloc(&lease->ptr, bytes);
+}
+
 int32_t *at(void *slab, size_t off) { return reinterpret_cast<int32_t *>(static_cast<char *>(slab) + off); }
 
 gnn_status build_impl(const int32_t *d_src, const int32_t *d_dst, int64_t E, int32_t N, hipStream_t stream,
@@ -375,15 +442,15 @@ gnn_status build_impl(const int32_t *d_src, const int32_t *d_dst, int64_t E, int
     g->split_rows = at(g->slab, o_srows);
     g->split_slot0 = at(g->slab, o_sslot);
 
-    // ---- temporaries, one allocation, freed when this function returns
+    // ---- temporaries: one buffer, normally the cached one
     slab_plan pt;
-    const size_t scan_elems = std::max(gnn_scan_tmp_elems((int64_t)np1), gnn_scan_tmp_elems(num_tiles * kRadixMax));
+    const size_t scan_elems = std::max(gnn_scan_tmp_elems((int64_t)(4 * np1)), gnn_scan_tmp_elems(num_tiles * kRadixMax));
     const size_t o_flag = pt.add(64), o_scan = pt.add(scan_elems), o_kb = pt.add(E), o_vb = pt.add(E),
                  o_eb = pt.add(E), o_counts = pt.add((size_t)num_tiles * kRadixMax), o_starts = pt.add(N),
                  o_flags = pt.add(4 * np1), o_pos = pt.add(4 * np1);
-    gnn_temp_pool tmp;
-    char *ts;
-    GNN_TRY(tmp.get(&ts, pt.bytes));
+    temp_lease tmp;
+    GNN_TRY(temp_acquire(&tmp, pt.bytes));
+    char *ts = static_cast<char *>(tmp.ptr);
     int32_t *d_flag = at(ts, o_flag), *scan_tmp = at(ts, o_scan), *kb = at(ts, o_kb), *vb = at(ts, o_vb),
             *eb = at(ts, o_eb), *counts = at(ts, o_counts), *starts = at(ts, o_starts), *flags = at(ts, o_flags),
             *pos = at(ts, o_pos);
@@ -392,6 +459,7 @@ gnn_status build_impl(const int32_t *d_src, const int32_t *d_dst, int64_t E, int
     //      unchecked node id: the sort only uses masked digits and the run kernels skip bad keys)
     GNN_HIP(hipMemsetAsync(d_flag, 0, 64 * sizeof(int32_t), stream));
     GNN_HIP(hipMemsetAsync(g->indeg, 0, (size_t)N * sizeof(int32_t), stream));
+    GNN_HIP(hipMemsetAsync(starts, 0, (size_t)N * sizeof(int32_t), stream));
     if (E > 0) {
         const int blocks = (int)std::min<int64_t>(gnn_div_up(E, kThreads), 256 * 16);
         hipLaunchKernelGGL(check_range_kernel, dim3(blocks), dim3(kThreads), 0, stream, d_src, d_dst, E,
@@ -434,10 +502,10 @@ gnn_status build_impl(const int32_t *d_src, const int32_t *d_dst, int64_t E, int
         }
         // ---- in-degree histogram from the runs of the sorted destinations
         const unsigned eblocks = (unsigned)gnn_div_up(E, kThreads);
-        hipLaunchKernelGGL(run_starts_kernel, dim3(eblocks), dim3(kThreads), 0, stream, g->rowidx, E, N, starts);
+        hipLaunchKernelGGL(run_bounds_kernel, dim3(eblocks), dim3(kThreads), 0, stream, g->rowidx, E, N, starts, g->indeg);
         GNN_LAUNCH_CHECK();
-        hipLaunchKernelGGL(run_lengths_kernel, dim3(eblocks), dim3(kThreads), 0, stream, g->rowidx, E, N, starts,
-                           g->indeg);
+        hipLaunchKernelGGL(run_lengths_kernel, dim3((unsigned)gnn_div_up(N, kThreads)), dim3(kThreads), 0, stream, N,
+                           starts, g->indeg);
         GNN_LAUNCH_CHECK();
     }
 
@@ -449,8 +517,7 @@ gnn_status build_impl(const int32_t *d_src, const int32_t *d_dst, int64_t E, int
     hipLaunchKernelGGL(classify_rows_kernel, dim3(nblocks), dim3(kThreads), 0, stream, g->indeg, N, g->small_max,
                        g->chunk, flags, flags + np1, flags + 2 * np1, flags + 3 * np1);
     GNN_LAUNCH_CHECK();
-    for (int q = 0; q < 4; ++q)
-        GNN_TRY(gnn_scan_exclusive_i32(flags + q * np1, pos + q * np1, N, true, scan_tmp, stream));
+    GNN_TRY(gnn_scan_exclusive_i32(flags, pos, (int64_t)(4 * np1), false, scan_tmp, stream));
     hipLaunchKernelGGL(fill_lists_kernel, dim3(nblocks), dim3(kThreads), 0, stream, g->rowptr, N, g->small_max,
                        g->chunk, pos, pos + np1, pos + 2 * np1, pos + 3 * np1, g->small_rows, g->item_row,
                        g->item_start, g->item_slot, g->split_rows, g->split_slot0);
@@ -528,6 +595,17 @@ gnn_status gnn_build_csr(const int32_t *d_src, const int32_t *d_dst, int64_t num
 }
 
 int32_t gnn_graph_num_src_nodes(const gnn_graph *g) { return g ? g->num_src_nodes : 0; }
+
+gnn_status gnn_release_cached_memory(void)
+{
+    std::lock_guard<std::mutex> lock(g_temp_cache.mu);
+    if (g_temp_cache.lent) return GNN_ERR_UNSUPPORTED;   // a build is running on another thread
+    if (g_temp_cache.ptr) (void)hipFree(g_temp_cache.ptr);
+    g_temp_cache.ptr = nullptr;
+    g_temp_cache.bytes = 0;
+    g_temp_cache.device = -1;
+    return GNN_OK;
+}
 
 gnn_status gnn_graph_destroy(gnn_graph *g)
 {
