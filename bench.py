@@ -42,9 +42,9 @@ MFMA_FP32_PEAK_TFLOPS = 157.3
 # (FETCH_SIZE x 2.000 calibration factor + WRITE_SIZE x 1.000, calibrated on a 1 GiB streaming kernel
 # in the same run).  Only meaningful for the default sizes of each workload; other sizes report null.
 MEASURED_TRAFFIC_BYTES = {
-    ("propagate", 1_000_000, 20_000_000, 64): 2_928_763_241,   # propagate_kernel<16,4,0,false>
-    ("gat", 2_449_029, 126_167_309, 64): 42_071_136_213,       # gat_kernel<16,4>
-    ("gcn", 100_000, 1_000_000, 128): 405_388_176,             # propagate_kernel<32,4,0,false>, GCN epilogue
+    ("propagate", 1_000_000, 20_000_000, 64): 2_924_179_136,   # propagate_kernel<16,4,0,0,0>
+    ("gat", 2_449_029, 126_167_309, 64): 41_987_127_658,       # gat_kernel<16,4>
+    ("gcn", 100_000, 1_000_000, 128): 405_408_528,             # propagate_kernel<32,4,0,0,0>, GCN epilogue
 }
 
 
@@ -148,7 +148,7 @@ def run_propagate(args, torch, gnn, synth):
 
     line = base_line("propagate(copy_xj,sum) algorithmic GB/s, 1M-node/20M-edge power-law graph, F=64", gbs, ms, args,
                      wl.name, {"N": n, "E": e, "F": f, "msg": "copy_xj", "aggr": "sum", "seed": synth.seed_of(2)})
-    line["roofline"] = hbm_roofline(gbs, "propagate_kernel<16,4,copy_xj,sum> (+ combine_pieces_kernel, ~10 us)",
+    line["roofline"] = hbm_roofline(gbs, "propagate_kernel<16,4,0,0,0> = copy_xj, sum (+ combine_pieces_kernel, ~10 us)",
                                     MEASURED_TRAFFIC_BYTES.get(("propagate", n, e, f)))
     line["extra"] = extra
     if not args.no_cpu_baseline:
