@@ -250,7 +250,9 @@ __global__ __launch_bounds__(kThreads) void classify_rows_kernel(const int32_t *
                                                                  int32_t *__restrict__ f_small,
                                                                  int32_t *__restrict__ f_items,
                                                                  int32_t *__restrict__ f_slots,
-                                                                 int32_t *__restrict__ f_split)
+                                                                 int32_t *__restrict__ f_split,
+                                                                 float *__restrict__ dinv_loop,
+                                                                 float *__restrict__ dinv_plain)
 {
     const int32_t r = blockIdx.x * kThreads + threadIdx.x;
     if (r >= N) return;
@@ -262,6 +264,9 @@ __global__ __launch_bounds__(kThreads) void classify_rows_kernel(const int32_t *
     f_items[r] = items;
     f_slots[r] = items > 1 ? items : 0;
     f_split[r] = items > 1;
+    // the two degree factors of the GCN normalisation, kept with the graph
+    dinv_loop[r] = 1.0f / sqrtf((float)(deg + 1));
+    dinv_plain[r] = deg > 0 ? 1.0f / sqrtf((float)deg) : 0.0f;
 }
 
 __global__ __launch_bounds__(kThreads) void fill_lists_kernel(
@@ -427,7 +432,7 @@ gnn_status build_impl(const int32_t *d_src, const int32_t *d_dst, int64_t E, int
     const size_t o_rowptr = pa.add(np1), o_indeg = pa.add(N), o_colidx = pa.add(E), o_perm = pa.add(E),
                  o_rowidx = pa.add(E), o_dstcoo = pa.add(E), o_small = pa.add(N), o_irow = pa.add(max_items),
                  o_istart = pa.add(max_items), o_islot = pa.add(max_items), o_srows = pa.add(max_split),
-                 o_sslot = pa.add(max_split);
+                 o_sslot = pa.add(max_split), o_dinv1 = pa.add(N), o_dinv0 = pa.add(N);
     GNN_TRY(slab_alloc(&g->slab, pa.bytes));
     g->rowptr = at(g->slab, o_rowptr);
     g->indeg = at(g->slab, o_indeg);
@@ -435,6 +440,8 @@ gnn_status build_impl(const int32_t *d_src, const int32_t *d_dst, int64_t E, int
     g->perm = at(g->slab, o_perm);
     g->rowidx = at(g->slab, o_rowidx);
     g->dst_coo = at(g->slab, o_dstcoo);
+    g->dinv_loop = reinterpret_cast<float *>(at(g->slab, o_dinv1));
+    g->dinv_plain = reinterpret_cast<float *>(at(g->slab, o_dinv0));
     g->small_rows = at(g->slab, o_small);
     g->item_row = at(g->slab, o_irow);
     g->item_start = at(g->slab, o_istart);
@@ -515,7 +522,7 @@ gnn_status build_impl(const int32_t *d_src, const int32_t *d_dst, int64_t E, int
     // ---- work lists (positions from scans; sizes are read back afterwards)
     const int nblocks = (int)gnn_div_up(N, kThreads);
     hipLaunchKernelGGL(classify_rows_kernel, dim3(nblocks), dim3(kThreads), 0, stream, g->indeg, N, g->small_max,
-                       g->chunk, flags, flags + np1, flags + 2 * np1, flags + 3 * np1);
+                       g->chunk, flags, flags + np1, flags + 2 * np1, flags + 3 * np1, g->dinv_loop, g->dinv_plain);
     GNN_LAUNCH_CHECK();
     GNN_TRY(gnn_scan_exclusive_i32(flags, pos, (int64_t)(4 * np1), false, scan_tmp, stream));
     hipLaunchKernelGGL(fill_lists_kernel, dim3(nblocks), dim3(kThreads), 0, stream, g->rowptr, N, g->small_max,

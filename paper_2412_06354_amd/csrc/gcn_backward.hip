@@ -19,15 +19,6 @@ namespace {
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 constexpr int kThreads = 256;
 
-__global__ __launch_bounds__(kThreads) void inv_sqrt_degree_kernel(const int32_t *__restrict__ indeg, int32_t N,
-                                                                   int32_t extra, float *__restrict__ dinv)
-{
-    const int32_t i = blockIdx.x * kThreads + threadIdx.x;
-    if (i >= N) return;
-    const int32_t d = indeg[i] + extra;
-    dinv[i] = d > 0 ? 1.0f / sqrtf((float)d) : 0.0f;
-}
-
 __global__ __launch_bounds__(kThreads) void scale_rows_kernel(const float *__restrict__ scale, int64_t N, int F,
                                                               const float *__restrict__ in, float *__restrict__ out)
 {
@@ -119,7 +110,7 @@ __global__ __launch_bounds__(kThreads) void colsum_partial_kernel(const float *_
 // out[q] = sum over chunks of partial[chunk][q], in a fixed order: a block owns 64 elements, its four
 // thread rows take the chunks round-robin (eight loads in flight each) and are folded through LDS.
 __global__ __launch_bounds__(kThreads) void sum_partials_kernel(const float *__restrict__ partial, int chunks,
-                                                                int64_t elems, float *__restrict__ out)
+                                                                int64_t elems, float factor, float *__restrict__ out)
 {
     __shared__ float fold[4][64];
     const int lane = threadIdx.x & 63, slice = threadIdx.x >> 6;
@@ -138,7 +129,10 @@ __global__ __launch_bounds__(kThreads) void sum_partials_kernel(const float *__r
     }
     fold[slice][lane] = s;
     __syncthreads();
-    if (slice == 0 && q < elems) out[q] = (fold[0][lane] + fold[1][lane]) + (fold[2][lane] + fold[3][lane]);
+    if (slice == 0 && q < elems) {
+        const float t = (fold[0][lane] + fold[1][lane]) + (fold[2][lane] + fold[3][lane]);
+        out[q] = factor == 1.0f ? t : t * factor;
+    }
 }
 
 size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
@@ -146,7 +140,7 @@ size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
 int chunk_count(int64_t rows) { return gnn_row_chunk_count(rows); }
 
 struct BackwardLayout {
-    size_t gs, t, dinv, wt, part, total;
+    size_t gs, t, wt, part, total;
 };
 
 BackwardLayout layout(int64_t N, int f_in, int f_out)
@@ -156,8 +150,7 @@ BackwardLayout layout(int64_t N, int f_in, int f_out)
     const int chunks = chunk_count(N);
     l.gs = 0;
     l.t = nf;
-    l.dinv = 2 * nf;
-    l.wt = l.dinv + align256((size_t)N * sizeof(float));
+    l.wt = 2 * nf;
     l.part = l.wt + align256((size_t)f_in * f_out * sizeof(float));
     l.total = l.part + align256((size_t)chunks * std::max(f_in, 1) * f_out * sizeof(float));
     return l;
@@ -170,13 +163,19 @@ int gnn_row_chunk_count(int64_t rows)
     return (int)std::max<int64_t>(1, std::min<int64_t>(2048, gnn_div_up(rows, 256)));
 }
 
-gnn_status gnn_launch_sum_partials(const float *d_partial, int chunks, int64_t elems, float *d_out, hipStream_t s)
+gnn_status gnn_launch_sum_partials_scaled(const float *d_partial, int chunks, int64_t elems, float factor,
+                                          float *d_out, hipStream_t s)
 {
     if (elems <= 0) return GNN_OK;
     hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)gnn_div_up(elems, 64)), dim3(kThreads), 0, s, d_partial,
-                       chunks, elems, d_out);
+                       chunks, elems, factor, d_out);
     GNN_LAUNCH_CHECK();
     return GNN_OK;
+}
+
+gnn_status gnn_launch_sum_partials(const float *d_partial, int chunks, int64_t elems, float *d_out, hipStream_t s)
+{
+    return gnn_launch_sum_partials_scaled(d_partial, chunks, elems, 1.0f, d_out, s);
 }
 
 gnn_status gnn_launch_xty(const float *d_x, const float *d_y, int64_t rows, int f_in, int f_out, float *d_partial,
@@ -225,15 +224,13 @@ gnn_status gnn_gcnconv_backward(const gnn_graph *g, const gnn_graph *g_by_source
     hipStream_t s = static_cast<hipStream_t>(stream);
     char *ws = static_cast<char *>(d_workspace);
     float *gs = reinterpret_cast<float *>(ws + l.gs), *t = reinterpret_cast<float *>(ws + l.t),
-          *dinv = reinterpret_cast<float *>(ws + l.dinv), *wt = reinterpret_cast<float *>(ws + l.wt),
+          *wt = reinterpret_cast<float *>(ws + l.wt),
           *part = reinterpret_cast<float *>(ws + l.part);
     const int chunks = chunk_count(N);
     const int64_t rows_per_chunk = gnn_div_up(N, chunks);
+    const float *dinv = add_self_loops ? g->dinv_loop : g->dinv_plain;   // the forward graph's degree factors
 
     if (d_grad_x || d_grad_w) {
-        hipLaunchKernelGGL(inv_sqrt_degree_kernel, dim3((unsigned)gnn_div_up(N, kThreads)), dim3(kThreads), 0, s,
-                           g->indeg, (int32_t)N, add_self_loops ? 1 : 0, dinv);
-        GNN_LAUNCH_CHECK();
         const int blocks = (int)std::min<int64_t>(gnn_div_up(N * f_out, kThreads), 256 * 64);
         hipLaunchKernelGGL(scale_rows_kernel, dim3(blocks), dim3(kThreads), 0, s, dinv, N, f_out, d_grad_out, gs);
         GNN_LAUNCH_CHECK();

@@ -1,8 +1,8 @@
 // GCNConv forward,  out = D^-1/2 (A [+ I]) D^-1/2 X W + b  (layer used in the paper's training
 // example; a fused special case of propagate in the sense of section 3, "Message Passing").
 //
-// Three steps on the caller's stream:
-//   1. dinv[i] = 1/sqrt(d_i),  d_i = in-degree (+1 with self-loops), 0 where d_i = 0;
+// Steps on the caller's stream:
+//   1. dinv[i] = 1/sqrt(d_i),  d_i = in-degree (+1 with self-loops), 0 where d_i = 0 -- kept with the graph;
 //   2. Z'[j,:] = dinv[j] * (X W)[j,:]      -- MFMA projection with the source-side factor fused in;
 //   3. out[i,:] = dinv[i] * (sum_{j->i} Z'[j,:] + [self-loop] Z'[i,:]) + b   -- the propagate kernel
 //      (copy_xj, sum) with the self-loop term, the destination-side factor and the bias applied in
@@ -11,15 +11,6 @@
 #include "gnn_internal.h"
 
 namespace {
-
-__global__ __launch_bounds__(256) void inv_sqrt_degree_kernel(const int32_t *__restrict__ indeg, int32_t N,
-                                                              int32_t extra, float *__restrict__ dinv)
-{
-    const int32_t i = blockIdx.x * 256 + threadIdx.x;
-    if (i >= N) return;
-    const int32_t d = indeg[i] + extra;
-    dinv[i] = d > 0 ? 1.0f / sqrtf((float)d) : 0.0f;
-}
 
 size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
 
@@ -30,7 +21,7 @@ extern "C" {
 size_t gnn_gcnconv_workspace_bytes(int32_t num_nodes, int32_t f_out)
 {
     if (num_nodes <= 0 || f_out <= 0) return 0;
-    return align256((size_t)num_nodes * f_out * sizeof(float)) + align256((size_t)num_nodes * sizeof(float));
+    return align256((size_t)num_nodes * f_out * sizeof(float));
 }
 
 gnn_status gnn_gcnconv(const gnn_graph *g, const float *d_x, int32_t f_in, const float *d_w, const float *d_bias,
@@ -45,12 +36,8 @@ gnn_status gnn_gcnconv(const gnn_graph *g, const float *d_x, int32_t f_in, const
     if (reinterpret_cast<uintptr_t>(d_workspace) & 255u) return GNN_ERR_BAD_SIZE;
     hipStream_t s = static_cast<hipStream_t>(stream);
     float *z = static_cast<float *>(d_workspace);
-    float *dinv = reinterpret_cast<float *>(static_cast<char *>(d_workspace) +
-                                            align256((size_t)N * f_out * sizeof(float)));
+    const float *dinv = add_self_loops ? g->dinv_loop : g->dinv_plain;   // computed when the graph was built
 
-    hipLaunchKernelGGL(inv_sqrt_degree_kernel, dim3((unsigned)gnn_div_up(N, 256)), dim3(256), 0, s, g->indeg, N,
-                       add_self_loops ? 1 : 0, dinv);
-    GNN_LAUNCH_CHECK();
     GNN_TRY(gnn_dense_xw(d_x, N, f_in, d_w, f_out, dinv, z, stream));
     gnn_epilogue epi;
     epi.self_scale = add_self_loops ? 1.0f : 0.0f;

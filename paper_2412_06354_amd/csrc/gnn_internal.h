@@ -65,6 +65,8 @@ struct gnn_graph {
     int32_t *perm = nullptr;     // [E]
     int32_t *rowidx = nullptr;   // [E] destination of CSR position p (the sorted keys)
     int32_t *dst_coo = nullptr;  // [E] destination of edge k in the caller's order (a copy of the input)
+    float *dinv_loop = nullptr;  // [N] 1/sqrt(in-degree + 1): GCN coefficient with one self-loop per node
+    float *dinv_plain = nullptr; // [N] 1/sqrt(in-degree), 0 where the in-degree is 0
 
     int32_t n_small = 0;
     int32_t *small_rows = nullptr;      // [n_small] row ids, ascending
@@ -81,6 +83,10 @@ struct gnn_graph {
     mutable float *scratch = nullptr;
     mutable size_t scratch_floats = 0;
 };
+
+// sum_partials with a final factor: out[q] = factor * sum over chunks of partial[chunk * elems + q]
+gnn_status gnn_launch_sum_partials_scaled(const float *d_partial, int chunks, int64_t elems, float factor,
+                                          float *d_out, hipStream_t stream);
 
 // Makes sure g->scratch holds at least `floats` floats.
 gnn_status gnn_graph_reserve_scratch(const gnn_graph *g, size_t floats);

@@ -55,10 +55,53 @@ __global__ __launch_bounds__(kThreads) void column_moment_partial_kernel(const f
     }
 }
 
-__global__ __launch_bounds__(kThreads) void scale_vector_kernel(float *__restrict__ v, int n, float factor)
+// Few rows (a collated batch of small graphs): one launch for both statistics.  A block of 1024 threads owns
+// eight columns; its 128 thread rows take the rows round-robin, several loads in flight each, and are folded
+// through LDS by a fixed halving tree; first the mean, then the mean of squared deviations.
+constexpr int kSmallRows = 8192;
+constexpr int kSmallThreads = 1024, kSmallCols = 8, kSmallSlices = kSmallThreads / kSmallCols;
+
+__device__ __forceinline__ float fold_slices(float (*fold)[kSmallCols], int rs, int c0, float v)
 {
-    const int i = blockIdx.x * kThreads + threadIdx.x;
-    if (i < n) v[i] *= factor;
+    __syncthreads();
+    fold[rs][c0] = v;
+    __syncthreads();
+#pragma unroll
+    for (int h = kSmallSlices / 2; h >= 1; h >>= 1) {
+        if (rs < h) fold[rs][c0] += fold[rs + h][c0];
+        __syncthreads();
+    }
+    return fold[0][c0];
+}
+
+__global__ __launch_bounds__(kSmallThreads) void small_column_stats_kernel(const float *__restrict__ x, int N, int F,
+                                                                           float *__restrict__ mean,
+                                                                           float *__restrict__ var)
+{
+    __shared__ float fold[kSmallSlices][kSmallCols];
+    const int c0 = threadIdx.x % kSmallCols, rs = threadIdx.x / kSmallCols;
+    const int col = blockIdx.x * kSmallCols + c0;
+    const bool ok = col < F;
+    const float *xc = x + (ok ? col : 0);
+    float s = 0.0f;
+    if (ok) {
+#pragma unroll 8
+        for (int row = rs; row < N; row += kSmallSlices) s += xc[(int64_t)row * F];
+    }
+    const float mu = fold_slices(fold, rs, c0, s) / (float)N;
+    float q = 0.0f;
+    if (ok) {
+#pragma unroll 8
+        for (int row = rs; row < N; row += kSmallSlices) {
+            const float d = xc[(int64_t)row * F] - mu;
+            q = fmaf(d, d, q);
+        }
+    }
+    const float ss = fold_slices(fold, rs, c0, q);
+    if (rs == 0 && ok) {
+        mean[col] = mu;
+        var[col] = ss / (float)N;
+    }
 }
 
 // out = act(gamma * (x - mean) / sqrt(var + eps) + beta)
@@ -134,25 +177,24 @@ gnn_status gnn_batchnorm(const float *d_x, int32_t num_rows, int32_t feat_dim, c
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int64_t N = num_rows;
     const int F = feat_dim;
-    if (!use_given_stats) {
+    if (!use_given_stats && N <= kSmallRows) {
+        hipLaunchKernelGGL(small_column_stats_kernel, dim3((unsigned)gnn_div_up(F, kSmallCols)), dim3(kSmallThreads), 0, s, d_x, (int)N,
+                           F, d_mean, d_var);
+        GNN_LAUNCH_CHECK();
+    } else if (!use_given_stats) {
         if (!d_workspace) return GNN_ERR_NULL;
         if (workspace_bytes < gnn_batchnorm_workspace_bytes(num_rows, feat_dim)) return GNN_ERR_BAD_SIZE;
         float *part = static_cast<float *>(d_workspace);
         const int chunks = gnn_row_chunk_count(N);
         const int64_t rows_per_chunk = gnn_div_up(N, chunks);
-        const dim3 vec_grid((unsigned)gnn_div_up(F, kThreads));
         hipLaunchKernelGGL(column_moment_partial_kernel<1>, dim3((unsigned)chunks), dim3(kThreads), 0, s, d_x, N, F,
                            (const float *)nullptr, rows_per_chunk, part);
         GNN_LAUNCH_CHECK();
-        GNN_TRY(gnn_launch_sum_partials(part, chunks, F, d_mean, s));
-        hipLaunchKernelGGL(scale_vector_kernel, vec_grid, dim3(kThreads), 0, s, d_mean, F, 1.0f / (float)N);
-        GNN_LAUNCH_CHECK();
+        GNN_TRY(gnn_launch_sum_partials_scaled(part, chunks, F, 1.0f / (float)N, d_mean, s));
         hipLaunchKernelGGL(column_moment_partial_kernel<2>, dim3((unsigned)chunks), dim3(kThreads), 0, s, d_x, N, F,
                            (const float *)d_mean, rows_per_chunk, part);
         GNN_LAUNCH_CHECK();
-        GNN_TRY(gnn_launch_sum_partials(part, chunks, F, d_var, s));
-        hipLaunchKernelGGL(scale_vector_kernel, vec_grid, dim3(kThreads), 0, s, d_var, F, 1.0f / (float)N);
-        GNN_LAUNCH_CHECK();
+        GNN_TRY(gnn_launch_sum_partials_scaled(part, chunks, F, 1.0f / (float)N, d_var, s));
     }
     const int blocks = (int)std::min<int64_t>(gnn_div_up(N * F, kThreads), 256 * 64);
     hipLaunchKernelGGL(normalise_rows_kernel, dim3(blocks), dim3(kThreads), 0, s, d_x, N, F, d_mean, d_var, d_gamma,

@@ -87,6 +87,48 @@ __global__ __launch_bounds__(kThreads) void bn_backward_partial_kernel(const flo
     }
 }
 
+// Few rows: both column sums in one launch.  A block of 1024 threads owns eight columns; its 128 thread rows
+// take the rows round-robin and are folded through LDS by a fixed halving tree.
+constexpr int kSmallRows = 8192;
+constexpr int kSmallThreads = 1024, kSmallCols = 8, kSmallSlices = kSmallThreads / kSmallCols;
+
+__global__ __launch_bounds__(kSmallThreads) void small_bn_backward_sums_kernel(
+    const float *__restrict__ x, int N, int F, const float *__restrict__ mean, const float *__restrict__ var, float eps,
+    const float *__restrict__ gy, const float *__restrict__ y, float *__restrict__ gbeta, float *__restrict__ ggamma)
+{
+    __shared__ float fold_b[kSmallSlices][kSmallCols], fold_g[kSmallSlices][kSmallCols];
+    const int c0 = threadIdx.x % kSmallCols, rs = threadIdx.x / kSmallCols;
+    const int col = blockIdx.x * kSmallCols + c0;
+    const bool ok = col < F;
+    float sb = 0.0f, sg = 0.0f;
+    if (ok) {
+        const float mu = mean[col], inv = 1.0f / sqrtf(var[col] + eps);
+#pragma unroll 4
+        for (int row = rs; row < N; row += kSmallSlices) {
+            const int64_t q = (int64_t)row * F + col;
+            float g = gy[q];
+            if (y) g = y[q] > 0.0f ? g : 0.0f;
+            sb += g;
+            sg = fmaf(g, (x[q] - mu) * inv, sg);
+        }
+    }
+    fold_b[rs][c0] = sb;
+    fold_g[rs][c0] = sg;
+    __syncthreads();
+#pragma unroll
+    for (int h = kSmallSlices / 2; h >= 1; h >>= 1) {
+        if (rs < h) {
+            fold_b[rs][c0] += fold_b[rs + h][c0];
+            fold_g[rs][c0] += fold_g[rs + h][c0];
+        }
+        __syncthreads();
+    }
+    if (rs == 0 && ok) {
+        gbeta[col] = fold_b[0][c0];
+        ggamma[col] = fold_g[0][c0];
+    }
+}
+
 // stage 2: gx = gamma * inv * (g - gbeta / N - xhat * ggamma / N)
 __global__ __launch_bounds__(kThreads) void bn_backward_apply_kernel(const float *__restrict__ x, int64_t N, int F,
                                                                      const float *__restrict__ mean,
@@ -138,6 +180,31 @@ __global__ __launch_bounds__(kThreads) void adam_kernel(float *__restrict__ p, f
                                                         float *__restrict__ v, const float *__restrict__ g, int64_t n,
                                                         float lr, float b1, float b2, float eps, float c1, float c2)
 {
+    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += stride) {
+        const float gi = g[i];
+        const float mi = b1 * m[i] + (1.0f - b1) * gi;
+        const float vi = b2 * v[i] + (1.0f - b2) * gi * gi;
+        m[i] = mi;
+        v[i] = vi;
+        p[i] = p[i] - lr * (mi / c1) / (sqrtf(vi / c2) + eps);
+    }
+}
+
+// The eight parameter arrays of the example model in one launch (blockIdx.y = which array).
+struct AdamBatch {
+    float *p[8], *m[8], *v[8];
+    const float *g[8];
+    int64_t n[8];
+};
+
+__global__ __launch_bounds__(kThreads) void adam_batch_kernel(const AdamBatch b, float lr, float b1, float b2, float eps,
+                                                              float c1, float c2)
+{
+    const int a = blockIdx.y;
+    float *p = b.p[a], *m = b.m[a], *v = b.v[a];
+    const float *g = b.g[a];
+    const int64_t n = b.n[a];
     const int64_t stride = (int64_t)gridDim.x * kThreads;
     for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += stride) {
         const float gi = g[i];
@@ -241,11 +308,18 @@ gnn_status gnn_batchnorm_backward(const float *d_x, int32_t num_rows, int32_t fe
     float *part_b = static_cast<float *>(d_workspace);
     float *part_g = reinterpret_cast<float *>(static_cast<char *>(d_workspace) +
                                               align256((size_t)chunks * F * sizeof(float)));
-    hipLaunchKernelGGL(bn_backward_partial_kernel, dim3((unsigned)chunks), dim3(kThreads), 0, s, d_x, N, F, d_mean, d_var,
-                       eps, d_grad_y, d_y_relu, rows_per_chunk, part_b, part_g);
-    GNN_LAUNCH_CHECK();
-    GNN_TRY(gnn_launch_sum_partials(part_b, chunks, F, d_grad_beta, s));
-    GNN_TRY(gnn_launch_sum_partials(part_g, chunks, F, d_grad_gamma, s));
+    if (N <= kSmallRows) {
+        hipLaunchKernelGGL(small_bn_backward_sums_kernel, dim3((unsigned)gnn_div_up(F, kSmallCols)),
+                           dim3(kSmallThreads), 0, s, d_x,
+                           (int)N, F, d_mean, d_var, eps, d_grad_y, d_y_relu, d_grad_beta, d_grad_gamma);
+        GNN_LAUNCH_CHECK();
+    } else {
+        hipLaunchKernelGGL(bn_backward_partial_kernel, dim3((unsigned)chunks), dim3(kThreads), 0, s, d_x, N, F, d_mean,
+                           d_var, eps, d_grad_y, d_y_relu, rows_per_chunk, part_b, part_g);
+        GNN_LAUNCH_CHECK();
+        GNN_TRY(gnn_launch_sum_partials(part_b, chunks, F, d_grad_beta, s));
+        GNN_TRY(gnn_launch_sum_partials(part_g, chunks, F, d_grad_gamma, s));
+    }
     if (d_grad_x) {
         hipLaunchKernelGGL(bn_backward_apply_kernel, dim3(grid_for(N * F)), dim3(kThreads), 0, s, d_x, N, F, d_mean,
                            d_var, eps, d_gamma, d_grad_y, d_y_relu, d_grad_beta, d_grad_gamma, d_grad_x);
@@ -357,10 +431,21 @@ gnn_status gnn_example_model_train_step(const gnn_graph *g, const gnn_graph *g_b
                                  stream));
     // optimiser
     const int64_t counts[8] = {(int64_t)f0 * f1, f1, f1, f1, (int64_t)f1 * f2, f2, (int64_t)f2 * f3, f3};
-    for (int q = 0; q < 8; ++q)
-        GNN_TRY(gnn_adam_step(d_params[q], d_adam_m[q], d_adam_v[q], pg + l.pg_off[q], counts[q], lr, beta1, beta2,
-                              adam_eps, step, stream));
-    (void)s;
+    AdamBatch batch;
+    int64_t largest = 1;
+    for (int q = 0; q < 8; ++q) {
+        batch.p[q] = d_params[q];
+        batch.m[q] = d_adam_m[q];
+        batch.v[q] = d_adam_v[q];
+        batch.g[q] = pg + l.pg_off[q];
+        batch.n[q] = counts[q];
+        largest = std::max(largest, counts[q]);
+    }
+    const float c1 = (float)(1.0 - std::pow((double)beta1, (double)step));
+    const float c2 = (float)(1.0 - std::pow((double)beta2, (double)step));
+    hipLaunchKernelGGL(adam_batch_kernel, dim3((unsigned)std::min<int64_t>(gnn_div_up(largest, kThreads), 1024), 8),
+                       dim3(kThreads), 0, s, batch, lr, beta1, beta2, adam_eps, c1, c2);
+    GNN_LAUNCH_CHECK();
     return GNN_OK;
 }
 

@@ -59,7 +59,7 @@ def test_host_side_argument_errors_need_no_gpu(handle):
     assert f(None, None, 0, 3, None, None) == 1                       # NULL out pointer
     handle.gnn_gcnconv_workspace_bytes.restype = ctypes.c_size_t
     handle.gnn_gcnconv_workspace_bytes.argtypes = [ctypes.c_int32, ctypes.c_int32]
-    assert handle.gnn_gcnconv_workspace_bytes(1000, 128) >= 1000 * 128 * 4 + 1000 * 4
+    assert handle.gnn_gcnconv_workspace_bytes(1000, 128) >= 1000 * 128 * 4   # the projected rows
     p = handle.gnn_propagate
     p.restype = ctypes.c_int
     assert p(None, None, 4, None, 1, 0, 0, 0, None, None) == 1        # NULL graph

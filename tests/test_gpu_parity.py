@@ -541,7 +541,7 @@ def test_gcnconv_backward(gnn, loops, f_in, f_out):
     gt.close()
 
 
-@pytest.mark.parametrize("n,f", [(5000, 64), (300, 7), (70_000, 200), (1, 5)])
+@pytest.mark.parametrize("n,f", [(5000, 64), (300, 7), (70_000, 200), (1, 5), (8192, 9), (8193, 9)])
 def test_batchnorm(gnn, n, f):
     x = (synth.normal_f32(71, 2, n * f).reshape(n, f) * (1.0 + np.arange(f, dtype=np.float32) % 5) + 2.0).astype(np.float32)
     gamma = synth.uniform_f32(71, 3, f, 0.5, 1.5)
@@ -684,7 +684,7 @@ def test_training_pieces(gnn):
         assert_close_sabs(host(gw), rw, a(x).T @ a(gy), what=f"dense grad_w {rows}x{k}x{n}")
         assert_close_sabs(host(gb), rb, a(gy).sum(0), what=f"dense grad_b {rows}x{k}x{n}")
     # batch-norm backward, with and without the relu mask
-    for n, f in ((5000, 64), (300, 7), (70_000, 40)):
+    for n, f in ((5000, 64), (300, 7), (70_000, 40), (8192, 9), (8193, 9)):
         x = (synth.normal_f32(92, 2, n * f).reshape(n, f) * (1.0 + np.arange(f, dtype=np.float32) % 3) + 1.0).astype(np.float32)
         gamma, beta = synth.uniform_f32(92, 3, f, 0.5, 1.5), synth.uniform_f32(92, 4, f, -0.5, 0.5)
         gy = synth.normal_f32(92, 5, n * f).reshape(n, f)
