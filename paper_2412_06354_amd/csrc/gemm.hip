@@ -25,6 +25,7 @@ namespace {
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int kThreads = 256;
+constexpr int kFastWaves = 12, kFastThreads = 64 * kFastWaves;   // fast kernel: one block fills a compute unit
 constexpr int kRowsPerWave = 32;
 constexpr int kRowsPerBlock = 4 * kRowsPerWave;
 constexpr int kSlab = 64;             // k-values per X register buffer / per staged W slab in the fallback
@@ -124,79 +125,94 @@ __device__ __forceinline__ void store_tile(const floatx16 (&acc)[NT], int64_t ro
         }
 }
 
-// Stages W[k0 .. k0+kk_count) x [n0 .. n0+BN) into LDS, transposed and swizzled (zero-filled outside
-// the matrix).  kk_count is a multiple of 32 and is the LDS row length.
-template <int BN>
-__device__ __forceinline__ void stage_w(float *ws, const float *__restrict__ w, int k, int n, int k0, int kk_count,
-                                        int n0, bool vec4)
-{
-    if (vec4) {   // n % 4 == 0 and w is 16-byte aligned: a group of four columns is inside or outside as a whole
-        constexpr int G = BN / 4;
-        const int total = kk_count * G;
-#pragma unroll 8
-        for (int idx = threadIdx.x; idx < total; idx += kThreads) {
+// Stages W[k0 .. k0+KK) x [n0 .. n0+BN) into LDS, transposed and swizzled (zero-filled outside the matrix).
+// KK is a multiple of 32 and is the LDS row length.  vec4 = n % 4 == 0 and w is 16-byte aligned: a group of four
+// columns is inside or outside the matrix as a whole.  All of a thread's loads are issued before the first LDS
+// write (addresses outside the matrix are replaced by the matrix's first group, values by zero: no branches
+// between the loads, so one round trip to memory instead of one per pass).
+template <int BN, int KK, int NTHREADS>
+struct WStage {
+    static constexpr int G = BN / 4, TOTAL = KK * G, ITERS = (TOTAL + NTHREADS - 1) / NTHREADS;
+    float4 v[ITERS];
+
+    __device__ __forceinline__ void load(const float *__restrict__ w, int k, int n, int k0, int n0)
+    {
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it) {
+            const int idx = min((int)threadIdx.x + it * NTHREADS, TOTAL - 1);   // a last, partial pass loads something valid
             const int kk = idx / G, c = (idx - kk * G) * 4;
-            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (k0 + kk < k && n0 + c < n) v = *reinterpret_cast<const float4 *>(w + (int64_t)(k0 + kk) * n + n0 + c);
-            ws[w_lds_index(c + 0, kk, kk_count)] = v.x;
-            ws[w_lds_index(c + 1, kk, kk_count)] = v.y;
-            ws[w_lds_index(c + 2, kk, kk_count)] = v.z;
-            ws[w_lds_index(c + 3, kk, kk_count)] = v.w;
+            const bool inside = k0 + kk < k && n0 + c < n;
+            const float *p = inside ? w + (int64_t)(k0 + kk) * n + n0 + c : w;
+            v[it] = *reinterpret_cast<const float4 *>(p);
         }
+    }
+
+    __device__ __forceinline__ void store(float *ws, int k, int n, int k0, int n0) const
+    {
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it) {
+            const int idx = threadIdx.x + it * NTHREADS;
+            const int kk = idx / G, c = (idx - kk * G) * 4;
+            const bool inside = k0 + kk < k && n0 + c < n;
+            if (idx < TOTAL) {
+                ws[w_lds_index(c + 0, kk, KK)] = inside ? v[it].x : 0.0f;
+                ws[w_lds_index(c + 1, kk, KK)] = inside ? v[it].y : 0.0f;
+                ws[w_lds_index(c + 2, kk, KK)] = inside ? v[it].z : 0.0f;
+                ws[w_lds_index(c + 3, kk, KK)] = inside ? v[it].w : 0.0f;
+            }
+        }
+    }
+};
+
+template <int BN, int KK, int NTHREADS>
+__device__ __forceinline__ void stage_w(float *ws, const float *__restrict__ w, int k, int n, int k0, int n0, bool vec4)
+{
+    if (vec4) {
+        WStage<BN, KK, NTHREADS> st;
+        st.load(w, k, n, k0, n0);
+        st.store(ws, k, n, k0, n0);
     } else {
-        const int total = kk_count * BN;
+        constexpr int TOTAL = KK * BN;
 #pragma unroll 8
-        for (int idx = threadIdx.x; idx < total; idx += kThreads) {
+        for (int idx = threadIdx.x; idx < TOTAL; idx += NTHREADS) {
             const int kk = idx / BN, c = idx - kk * BN;
             float v = 0.0f;
             if (k0 + kk < k && n0 + c < n) v = w[(int64_t)(k0 + kk) * n + n0 + c];
-            ws[w_lds_index(c, kk, kk_count)] = v;
+            ws[w_lds_index(c, kk, KK)] = v;
         }
     }
 }
 
 // Fast path: k <= 64*NSUB <= 128, k and n multiples of 4, 16-byte aligned rows (a ragged last row tile
 // is handled by clamped loads and a guarded store, a ragged last column block by zero-filled W and a
-// guarded store).  Blocks are persistent: they stage their column block of W once and then walk over row
-// tiles.  Per tile a wavefront issues all of its X loads (no branches), runs the MFMAs and writes
-// the tile with 128-bit stores; several wavefronts per SIMD overlap one another's load latency
-// with MFMAs (register use is kept low for that: no second X buffer).
-template <int NT, int NSUB, bool SCALED>
-__global__ __launch_bounds__(kThreads) void xw_fast_kernel(const float *__restrict__ x, int k,
-                                                           const float *__restrict__ w, int n,
-                                                           const float *__restrict__ row_scale,
-                                                           float *__restrict__ z, int64_t rows)
+// guarded store).  One block of twelve wavefronts per compute unit (three per SIMD, what the registers allow):
+// it stages its columns of W once -- one copy in LDS serves all twelve -- and then every wavefront walks over
+// 32-row tiles on its own.  Per tile a wavefront issues all of its X loads (no branches), runs the MFMAs and
+// writes the tile with 128-bit stores; the wavefronts of a SIMD overlap one another's load latency with MFMAs
+// (register use is kept low for that: no second X buffer).
+// One wave tile of the fast kernel: 32 rows x NCB column blocks from the X fragments in registers.  They stay
+// there while the column blocks are worked off one after the other (one accumulator set, reused): X is read
+// once for NCB * BN output columns.
+template <int NT, int NSUB, int NCB>
+__device__ __forceinline__ void fast_wave_tile(const AFrag (&a)[NSUB], const float *ws, float sc, int64_t row,
+                                               int64_t rows, int n, int n0, int r, int half, float *__restrict__ z)
 {
     constexpr int BN = NT * 32;
     constexpr int KP = NSUB * kSlab;
-    extern __shared__ __align__(16) float ws[];   // [BN][KP], swizzled
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int r = lane & 31, half = lane >> 5;
-    const int n0 = blockIdx.y * BN;
-    const int64_t num_row_tiles = (rows + kRowsPerBlock - 1) / kRowsPerBlock;
-
-    stage_w<BN>(ws, w, k, n, 0, KP, n0, true);
-    __syncthreads();
-
-    for (int64_t tile = blockIdx.x; tile < num_row_tiles; tile += gridDim.x) {
-        const int64_t row = tile * kRowsPerBlock + wave * kRowsPerWave + r;
-        AFrag a[NSUB];
 #pragma unroll
-        for (int sub = 0; sub < NSUB; ++sub) load_a<true>(a[sub], x, rows, k, row, sub * kSlab, half);
-        float sc = 1.0f;
-        if constexpr (SCALED) sc = row_scale[min(row, rows - 1)];
-
+    for (int cb = 0; cb < NCB; ++cb) {
         floatx16 acc[NT];
 #pragma unroll
         for (int t = 0; t < NT; ++t)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[t][v] = 0.0f;
 #pragma unroll
-        for (int sub = 0; sub < NSUB; ++sub) mfma_subslab<NT>(acc, a[sub], ws, KP, sub * kSlab + 32 * half, r);
+        for (int sub = 0; sub < NSUB; ++sub)
+            mfma_subslab<NT>(acc, a[sub], ws + cb * BN * KP, KP, sub * kSlab + 32 * half, r);
 
         if (row < rows) {   // false only for lanes past the end in a ragged last tile
-            float *zrow = z + row * n + n0 + 4 * half;
-            const int ncols = n - n0 - 4 * half;   // n % 4 == 0: a group of four columns is inside or outside as a whole
+            float *zrow = z + row * n + n0 + cb * BN + 4 * half;
+            const int ncols = n - n0 - cb * BN - 4 * half;   // n % 4 == 0: a group of four columns is inside or outside as a whole
 #pragma unroll
             for (int t = 0; t < NT; ++t)
 #pragma unroll
@@ -206,6 +222,59 @@ __global__ __launch_bounds__(kThreads) void xw_fast_kernel(const float *__restri
                             make_float4(acc[t][4 * g] * sc, acc[t][4 * g + 1] * sc, acc[t][4 * g + 2] * sc,
                                         acc[t][4 * g + 3] * sc);
         }
+    }
+}
+
+template <int NT, int NSUB, int NCB, bool SCALED>
+__global__ __launch_bounds__(kFastThreads) void xw_fast_kernel(const float *__restrict__ x, int k,
+                                                               const float *__restrict__ w, int n,
+                                                               const float *__restrict__ row_scale,
+                                                               float *__restrict__ z, int64_t rows)
+{
+    constexpr int BN = NT * 32;
+    constexpr int KP = NSUB * kSlab;
+    // W is staged by the first kStageThreads threads: the number of 16-byte groups (a power of two) is a
+    // multiple of it, so every staging thread makes the same number of passes and all loads go out at once.
+    constexpr int kStageThreads = (KP * BN * NCB / 4) < 512 ? (KP * BN * NCB / 4) : 512;
+    static_assert((KP * BN * NCB / 4) % kStageThreads == 0 && kStageThreads <= kFastThreads, "staging passes");
+    extern __shared__ __align__(16) float ws[];   // [NCB * BN][KP], swizzled
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int r = lane & 31, half = lane >> 5;
+    const int n0 = blockIdx.y * (BN * NCB);
+    const int64_t num_wave_tiles = (rows + kRowsPerWave - 1) / kRowsPerWave;
+
+    // Wave tile numbers go round the blocks first, then round the wavefronts of a block, so that a last, partly
+    // filled round puts one tile on as many compute units as possible.
+    const int64_t wt_stride = (int64_t)gridDim.x * kFastWaves;
+    int64_t wt = (int64_t)wave * gridDim.x + blockIdx.x;
+    int64_t row = wt * kRowsPerWave + r;
+
+    // W's loads are issued first, then the first tile's X loads (clamped addresses: safe also for a wavefront
+    // without a tile), which stay in flight while W is written to LDS: loads return in order, so waiting for W
+    // does not wait for X.
+    AFrag a[NSUB];
+    float sc = 1.0f;
+    {
+        WStage<BN * NCB, KP, kStageThreads> st;
+        const bool stager = threadIdx.x < kStageThreads;   // whole wavefronts
+        if (stager) st.load(w, k, n, 0, n0);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int sub = 0; sub < NSUB; ++sub) load_a<true>(a[sub], x, rows, k, row, sub * kSlab, half);
+        if constexpr (SCALED) sc = row_scale[min(row, rows - 1)];
+        __builtin_amdgcn_sched_barrier(0);
+        if (stager) st.store(ws, k, n, 0, n0);
+    }
+    __syncthreads();
+
+    // From here on the wavefronts are independent.  The first tile (already loaded) is peeled off the loop.
+    if (wt < num_wave_tiles) fast_wave_tile<NT, NSUB, NCB>(a, ws, sc, row, rows, n, n0, r, half, z);
+    for (wt += wt_stride; wt < num_wave_tiles; wt += wt_stride) {
+        row = wt * kRowsPerWave + r;
+#pragma unroll
+        for (int sub = 0; sub < NSUB; ++sub) load_a<true>(a[sub], x, rows, k, row, sub * kSlab, half);
+        if constexpr (SCALED) sc = row_scale[min(row, rows - 1)];
+        fast_wave_tile<NT, NSUB, NCB>(a, ws, sc, row, rows, n, n0, r, half, z);
     }
 }
 
@@ -232,7 +301,7 @@ __global__ __launch_bounds__(kThreads) void xw_slab_kernel(const float *__restri
         AFrag a;
         load_a<VEC4>(a, x, rows, k, row0 + r, k0, half);
         __syncthreads();
-        stage_w<BN>(ws, w, k, n, k0, kSlab, n0, w_vec4 != 0);
+        stage_w<BN, kSlab, kThreads>(ws, w, k, n, k0, n0, w_vec4 != 0);
         __syncthreads();
         mfma_subslab<NT>(acc, a, ws, kSlab, 32 * half, r);
     }
@@ -269,34 +338,39 @@ gnn_status launch_general(const float *d_x, int64_t rows, int k, const float *d_
     return GNN_OK;
 }
 
-template <int NT, int NSUB>
+template <int NT, int NSUB, int NCB>
 gnn_status launch_fast(const float *d_x, int64_t rows, int k, const float *d_w, int n, const float *d_row_scale,
                        float *d_z, hipStream_t s)
 {
-    constexpr int BN = NT * 32;
-    const int64_t full_tiles = gnn_div_up(rows, kRowsPerBlock);
+    constexpr int BN = NT * 32 * NCB;   // output columns per block
+    const int64_t wave_tiles = gnn_div_up(rows, kRowsPerWave);
     const size_t lds = (size_t)NSUB * kSlab * BN * sizeof(float);
-    const int per_cu = (int)std::max<size_t>(1, std::min<size_t>(4, (160 * 1024) / lds));
-    const dim3 grid((unsigned)std::min<int64_t>(full_tiles, (int64_t)device_cu_count() * per_cu),
-                    (unsigned)gnn_div_up(n, BN));
+    // One resident block per compute unit (fewer where there are several column blocks or few rows: then at
+    // least one wave tile per block, so that small inputs still spread over the chip).
+    const int col_blocks = (int)gnn_div_up(n, BN);
+    const int64_t blocks = std::max<int64_t>(1, std::min<int64_t>(device_cu_count() / col_blocks, wave_tiles));
+    const dim3 grid((unsigned)blocks, (unsigned)col_blocks);
     if (d_row_scale)
-        hipLaunchKernelGGL((xw_fast_kernel<NT, NSUB, true>), grid, dim3(kThreads), lds, s, d_x, k, d_w, n, d_row_scale,
-                           d_z, rows);
+        hipLaunchKernelGGL((xw_fast_kernel<NT, NSUB, NCB, true>), grid, dim3(kFastThreads), lds, s, d_x, k, d_w, n,
+                           d_row_scale, d_z, rows);
     else
-        hipLaunchKernelGGL((xw_fast_kernel<NT, NSUB, false>), grid, dim3(kThreads), lds, s, d_x, k, d_w, n,
+        hipLaunchKernelGGL((xw_fast_kernel<NT, NSUB, NCB, false>), grid, dim3(kFastThreads), lds, s, d_x, k, d_w, n,
                            d_row_scale, d_z, rows);
     GNN_LAUNCH_CHECK();
     return GNN_OK;
 }
 
+// Fast path: column tiles of 32 (n <= 32) or 64, two of them per block where the matrix is wider than one.
 template <int NT>
-gnn_status launch_xw(const float *d_x, int64_t rows, int k, const float *d_w, int n, const float *d_row_scale,
-                     float *d_z, bool x_vec4, bool w_vec4, hipStream_t s)
+gnn_status launch_fast_for_k(const float *d_x, int64_t rows, int k, const float *d_w, int n, const float *d_row_scale,
+                             float *d_z, hipStream_t s)
 {
-    const bool fast = x_vec4 && w_vec4 && k <= 2 * kSlab;   // w_vec4 implies n % 4 == 0
-    if (!fast) return launch_general<NT>(d_x, rows, k, d_w, n, d_row_scale, d_z, x_vec4, w_vec4, 0, s);
-    if (k <= kSlab) return launch_fast<NT, 1>(d_x, rows, k, d_w, n, d_row_scale, d_z, s);
-    return launch_fast<NT, 2>(d_x, rows, k, d_w, n, d_row_scale, d_z, s);
+    if (n > NT * 32) {
+        if (k <= kSlab) return launch_fast<NT, 1, 2>(d_x, rows, k, d_w, n, d_row_scale, d_z, s);
+        return launch_fast<NT, 2, 2>(d_x, rows, k, d_w, n, d_row_scale, d_z, s);
+    }
+    if (k <= kSlab) return launch_fast<NT, 1, 1>(d_x, rows, k, d_w, n, d_row_scale, d_z, s);
+    return launch_fast<NT, 2, 1>(d_x, rows, k, d_w, n, d_row_scale, d_z, s);
 }
 
 }  // namespace
@@ -310,16 +384,19 @@ extern "C" gnn_status gnn_dense_xw(const float *d_x, int64_t rows, int32_t k, co
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool x_vec4 = (k % 4 == 0) && ((reinterpret_cast<uintptr_t>(d_x) & 15u) == 0);
     const bool w_vec4 = (n % 4 == 0) && ((reinterpret_cast<uintptr_t>(d_w) & 15u) == 0);
-    // Column tile: 64 or 32 if it divides n (fast path; narrow tiles keep register use low and
-    // occupancy high), else 128 wide when n is
-    // large enough, else the smallest multiple of 32 covering n.
+    if (x_vec4 && w_vec4 && k <= 2 * kSlab) {   // w_vec4 implies n % 4 == 0
+        if (n <= 32) return launch_fast_for_k<1>(d_x, rows, k, d_w, n, d_row_scale, d_z, s);
+        return launch_fast_for_k<2>(d_x, rows, k, d_w, n, d_row_scale, d_z, s);
+    }
+    // General kernel.  Column tile: 64 or 32 if it divides n, else 128 wide when n is large enough, else the
+    // smallest multiple of 32 covering n.
     int nt = n > 96 ? 4 : (n + 31) / 32;
     if (n % 64 == 0) nt = 2;
     else if (n % 32 == 0) nt = 1;
     switch (nt) {
-    case 1: return launch_xw<1>(d_x, rows, k, d_w, n, d_row_scale, d_z, x_vec4, w_vec4, s);
-    case 2: return launch_xw<2>(d_x, rows, k, d_w, n, d_row_scale, d_z, x_vec4, w_vec4, s);
-    case 3: return launch_xw<3>(d_x, rows, k, d_w, n, d_row_scale, d_z, x_vec4, w_vec4, s);
-    default: return launch_xw<4>(d_x, rows, k, d_w, n, d_row_scale, d_z, x_vec4, w_vec4, s);
+    case 1: return launch_general<1>(d_x, rows, k, d_w, n, d_row_scale, d_z, x_vec4, w_vec4, 0, s);
+    case 2: return launch_general<2>(d_x, rows, k, d_w, n, d_row_scale, d_z, x_vec4, w_vec4, 0, s);
+    case 3: return launch_general<3>(d_x, rows, k, d_w, n, d_row_scale, d_z, x_vec4, w_vec4, 0, s);
+    default: return launch_general<4>(d_x, rows, k, d_w, n, d_row_scale, d_z, x_vec4, w_vec4, 0, s);
     }
 }
