@@ -72,6 +72,26 @@ def time_calls(torch, fn, steps, warmup):
     return start.elapsed_time(stop) / steps
 
 
+def launch_distribution(torch, fn, launches=50, between=None):
+    """Per-launch times (HIP events around every call): median, minimum and 95th percentile in milliseconds.
+    `between` runs untimed before every launch (the cold regime: something that evicts the caches)."""
+    for _ in range(3):
+        fn()
+    pairs = []
+    for _ in range(launches):
+        if between is not None:
+            between()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        fn()
+        b.record()
+        pairs.append((a, b))
+    torch.cuda.synchronize()
+    t = sorted(a.elapsed_time(b) for a, b in pairs)
+    return {"median_ms": t[len(t) // 2], "min_ms": t[0], "p95_ms": t[min(len(t) - 1, int(0.95 * len(t)))],
+            "launches": launches}
+
+
 def streaming_probe(torch):
     """A plain streaming kernel (reads 1 GiB, writes 1 GiB): second denominator next to the spec-sheet
     peak, and the calibration dispatch for hardware-counter runs."""
@@ -120,6 +140,14 @@ def run_propagate(args, torch, gnn, synth):
     extra.update(streaming_probe(torch))
     if not args.no_extra:
         k = max(5, args.steps // 10)
+        # warm = launches back to back; cold = 1 GiB streamed through the chip before every launch, which evicts
+        # the L2s and the Infinity Cache (the graph's 0.6 GB working set does not fit them either way)
+        headline = lambda: gnn.propagate(g, x, None, gnn.MSG_COPY_XJ, gnn.AGGR_SUM, out=out)
+        extra["per_launch_warm"] = launch_distribution(torch, headline)
+        evict_a = torch.zeros(256 * 1024 * 1024, dtype=torch.float32, device="cuda")
+        evict_b = torch.empty_like(evict_a)
+        extra["per_launch_cold"] = launch_distribution(torch, headline, between=lambda: torch.add(evict_a, 1.0, out=evict_b))
+        del evict_a, evict_b
         e_csr = gnn.edge_data_to_csr(g, ew)
         for name, msg, aggr in (("e_mul_xj_sum", 1, 0), ("e_mul_xj_mean", 1, 1), ("e_mul_xj_max", 1, 2),
                                 ("copy_xj_mean", 0, 1), ("copy_xj_max", 0, 2)):

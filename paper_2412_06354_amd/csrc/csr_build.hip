@@ -18,9 +18,12 @@ constexpr int kThreads = 256;
 
 // ---------------------------------------------------------------- range check, in-degree histogram
 
+// Range check of both index arrays; the same pass keeps a copy of the destinations in the caller's edge order
+// (dst_copy may be null).
 __global__ __launch_bounds__(kThreads) void check_range_kernel(const int32_t *__restrict__ src,
                                                                const int32_t *__restrict__ dst, int64_t E,
                                                                int32_t N_src, int32_t N,
+                                                               int32_t *__restrict__ dst_copy,
                                                                int32_t *__restrict__ bad)
 {
     const int64_t stride = (int64_t)gridDim.x * kThreads;
@@ -28,6 +31,7 @@ __global__ __launch_bounds__(kThreads) void check_range_kernel(const int32_t *__
     for (int64_t k = (int64_t)blockIdx.x * kThreads + threadIdx.x; k < E; k += stride) {
         const int32_t s = __builtin_nontemporal_load(src + k), d = __builtin_nontemporal_load(dst + k);
         any_bad |= ((uint32_t)s >= (uint32_t)N_src) | ((uint32_t)d >= (uint32_t)N);
+        if (dst_copy) __builtin_nontemporal_store(d, dst_copy + k);
     }
     if (any_bad) atomicOr(bad, 1);
 }
@@ -41,26 +45,34 @@ __global__ void gather_totals_kernel(const int32_t *__restrict__ flag, const int
     if (threadIdx.x < 4) out[1 + threadIdx.x] = pos[threadIdx.x * np1 + N] - pos[threadIdx.x * np1];
 }
 
-// In-degree histogram from the sorted destinations: every destination that occurs forms one run.  One pass
-// over the edges records where each run starts and (in the in-degree array) where it ends; a pass over
-// the rows turns the pair into the run length.  Rows that do not occur keep 0 - 0.
-__global__ __launch_bounds__(kThreads) void run_bounds_kernel(const int32_t *__restrict__ keys, int64_t E, int32_t N,
-                                                              int32_t *__restrict__ starts,
-                                                              int32_t *__restrict__ ends)
+// Row pointers straight from the sorted destinations: where the key changes from a to b at position p, the
+// rows a+1 .. b start at p (rows that do not occur get the start of the next one that does); before the first
+// key a = -1, after the last one the remaining rows and rowptr[N] get E.  Valid, sorted keys write every entry
+// exactly once.  Keys outside [0, N) -- invalid input, reported through the range flag -- are clamped, so nothing
+// outside rowptr[0 .. N] is written whatever the keys are.  Four positions per thread (one 128-bit load).
+__global__ __launch_bounds__(kThreads) void row_pointers_kernel(const int32_t *__restrict__ keys, int64_t E, int32_t N,
+                                                                int32_t *__restrict__ rowptr)
 {
-    const int64_t p = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (p >= E) return;
-    const int32_t k = keys[p];
-    if ((uint32_t)k >= (uint32_t)N) return;   // invalid input: reported through the range flag, never indexed with
-    if (p == 0 || keys[p - 1] != k) starts[k] = (int32_t)p;
-    if (p == E - 1 || keys[p + 1] != k) ends[k] = (int32_t)(p + 1);
-}
-
-__global__ __launch_bounds__(kThreads) void run_lengths_kernel(int32_t N, const int32_t *__restrict__ starts,
-                                                               int32_t *__restrict__ indeg)
-{
-    const int32_t r = blockIdx.x * kThreads + threadIdx.x;
-    if (r < N) indeg[r] -= starts[r];
+    const int64_t p0 = ((int64_t)blockIdx.x * kThreads + threadIdx.x) * 4;
+    if (p0 >= E) return;
+    int32_t k[5];
+    k[0] = p0 > 0 ? keys[p0 - 1] : -1;
+    const int cnt = (int)min((int64_t)4, E - p0);
+    if (cnt == 4 && (reinterpret_cast<uintptr_t>(keys) & 15u) == 0) {
+        const int4 v = *reinterpret_cast<const int4 *>(keys + p0);
+        k[1] = v.x; k[2] = v.y; k[3] = v.z; k[4] = v.w;
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) k[j + 1] = j < cnt ? keys[p0 + j] : 0;
+    }
+#pragma unroll
+    for (int j = 0; j < 5; ++j) k[j] = min(max(k[j], -1), N - 1);
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        if (j < cnt)
+            for (int32_t r = k[j] + 1; r <= k[j + 1]; ++r) rowptr[r] = (int32_t)(p0 + j);
+    if (p0 + cnt == E)
+        for (int32_t r = k[cnt] + 1; r <= N; ++r) rowptr[r] = (int32_t)E;
 }
 
 // ---------------------------------------------------------------- radix sort passes
@@ -245,8 +257,10 @@ __global__ __launch_bounds__(kThreads) void iota_copy_kernel(const int32_t *__re
 
 // Per row: is it a short row, how many wavefront pieces it needs, how many partial-result
 // slots (pieces of rows made of more than one piece), is it split.
-__global__ __launch_bounds__(kThreads) void classify_rows_kernel(const int32_t *__restrict__ indeg, int32_t N,
+__global__ __launch_bounds__(kThreads) void classify_rows_kernel(const int32_t *__restrict__ rowptr, int32_t N,
                                                                  int32_t small_max, int32_t chunk,
+                                                                 const int32_t *__restrict__ bad,
+                                                                 int32_t *__restrict__ indeg,
                                                                  int32_t *__restrict__ f_small,
                                                                  int32_t *__restrict__ f_items,
                                                                  int32_t *__restrict__ f_slots,
@@ -257,7 +271,9 @@ __global__ __launch_bounds__(kThreads) void classify_rows_kernel(const int32_t *
     const int32_t r = blockIdx.x * kThreads + threadIdx.x;
     if (r >= N) return;
     if (r == 0) f_small[N] = f_items[N] = f_slots[N] = f_split[N] = 0;   // the four arrays are scanned as one
-    const int32_t deg = indeg[r];
+    // invalid input (the build will fail with an error): the row pointers mean nothing, every list stays empty
+    const int32_t deg = bad[0] ? 0 : rowptr[r + 1] - rowptr[r];
+    indeg[r] = deg;
     const int small = deg <= small_max;
     const int items = small ? 0 : (deg + chunk - 1) / chunk;
     f_small[r] = small;
@@ -270,14 +286,14 @@ __global__ __launch_bounds__(kThreads) void classify_rows_kernel(const int32_t *
 }
 
 __global__ __launch_bounds__(kThreads) void fill_lists_kernel(
-    const int32_t *__restrict__ rowptr, int32_t N, int32_t small_max, int32_t chunk,
+    const int32_t *__restrict__ rowptr, int32_t N, int32_t small_max, int32_t chunk, const int32_t *__restrict__ bad,
     const int32_t *__restrict__ p_small, const int32_t *__restrict__ p_items, const int32_t *__restrict__ p_slots,
     const int32_t *__restrict__ p_split, int32_t *__restrict__ small_rows, int32_t *__restrict__ item_row,
     int32_t *__restrict__ item_start, int32_t *__restrict__ item_slot, int32_t *__restrict__ split_rows,
     int32_t *__restrict__ split_slot0)
 {
     const int32_t r = blockIdx.x * kThreads + threadIdx.x;
-    if (r >= N) return;
+    if (r >= N || bad[0]) return;   // invalid input: the lists were sized as empty
     // the four position arrays are slices of one exclusive scan: positions are relative to each slice's first entry
     const int32_t start = rowptr[r], deg = rowptr[r + 1] - start;
     if (deg <= small_max) {
@@ -453,30 +469,28 @@ gnn_status build_impl(const int32_t *d_src, const int32_t *d_dst, int64_t E, int
     slab_plan pt;
     const size_t scan_elems = std::max(gnn_scan_tmp_elems((int64_t)(4 * np1)), gnn_scan_tmp_elems(num_tiles * kRadixMax));
     const size_t o_flag = pt.add(64), o_scan = pt.add(scan_elems), o_kb = pt.add(E), o_vb = pt.add(E),
-                 o_eb = pt.add(E), o_counts = pt.add((size_t)num_tiles * kRadixMax), o_starts = pt.add(N),
+                 o_eb = pt.add(E), o_counts = pt.add((size_t)num_tiles * kRadixMax),
                  o_flags = pt.add(4 * np1), o_pos = pt.add(4 * np1);
     temp_lease tmp;
     GNN_TRY(temp_acquire(&tmp, pt.bytes));
     char *ts = static_cast<char *>(tmp.ptr);
     int32_t *d_flag = at(ts, o_flag), *scan_tmp = at(ts, o_scan), *kb = at(ts, o_kb), *vb = at(ts, o_vb),
-            *eb = at(ts, o_eb), *counts = at(ts, o_counts), *starts = at(ts, o_starts), *flags = at(ts, o_flags),
+            *eb = at(ts, o_eb), *counts = at(ts, o_counts), *flags = at(ts, o_flags),
             *pos = at(ts, o_pos);
 
-    // ---- index range check (the flag is read back at the end; nothing below indexes with an
-    //      unchecked node id: the sort only uses masked digits and the run kernels skip bad keys)
+    // ---- index range check and the copy of the destinations in edge order (the flag is read back at the
+    //      end; nothing below indexes with an unchecked node id: the sort only uses masked digits, the row-pointer
+    //      kernel clamps its keys and the work-list kernels do nothing once the flag is set)
     GNN_HIP(hipMemsetAsync(d_flag, 0, 64 * sizeof(int32_t), stream));
-    GNN_HIP(hipMemsetAsync(g->indeg, 0, (size_t)N * sizeof(int32_t), stream));
-    GNN_HIP(hipMemsetAsync(starts, 0, (size_t)N * sizeof(int32_t), stream));
     if (E > 0) {
         const int blocks = (int)std::min<int64_t>(gnn_div_up(E, kThreads), 256 * 16);
         hipLaunchKernelGGL(check_range_kernel, dim3(blocks), dim3(kThreads), 0, stream, d_src, d_dst, E,
-                           g->num_src_nodes, N, d_flag);
+                           g->num_src_nodes, N, g->dst_coo, d_flag);
         GNN_LAUNCH_CHECK();
     }
 
     // ---- stable radix sort by destination
     if (E > 0) {
-        GNN_HIP(hipMemcpyAsync(g->dst_coo, d_dst, (size_t)E * sizeof(int32_t), hipMemcpyDeviceToDevice, stream));
         const int key_bits = ceil_log2((uint32_t)N);
         if (key_bits == 0) {
             const int blocks = (int)gnn_div_up(E, kThreads);
@@ -507,26 +521,22 @@ gnn_status build_impl(const int32_t *d_src, const int32_t *d_dst, int64_t E, int
                 dst_sel ^= 1;
             }
         }
-        // ---- in-degree histogram from the runs of the sorted destinations
-        const unsigned eblocks = (unsigned)gnn_div_up(E, kThreads);
-        hipLaunchKernelGGL(run_bounds_kernel, dim3(eblocks), dim3(kThreads), 0, stream, g->rowidx, E, N, starts, g->indeg);
+        // ---- row pointers from the runs of the sorted destinations
+        hipLaunchKernelGGL(row_pointers_kernel, dim3((unsigned)gnn_div_up(gnn_div_up(E, 4), kThreads)), dim3(kThreads), 0,
+                           stream, g->rowidx, E, N, g->rowptr);
         GNN_LAUNCH_CHECK();
-        hipLaunchKernelGGL(run_lengths_kernel, dim3((unsigned)gnn_div_up(N, kThreads)), dim3(kThreads), 0, stream, N,
-                           starts, g->indeg);
-        GNN_LAUNCH_CHECK();
+    } else {
+        GNN_HIP(hipMemsetAsync(g->rowptr, 0, np1 * sizeof(int32_t), stream));
     }
-
-    // ---- rowptr = exclusive scan of the in-degrees
-    GNN_TRY(gnn_scan_exclusive_i32(g->indeg, g->rowptr, N, true, scan_tmp, stream));
 
     // ---- work lists (positions from scans; sizes are read back afterwards)
     const int nblocks = (int)gnn_div_up(N, kThreads);
-    hipLaunchKernelGGL(classify_rows_kernel, dim3(nblocks), dim3(kThreads), 0, stream, g->indeg, N, g->small_max,
-                       g->chunk, flags, flags + np1, flags + 2 * np1, flags + 3 * np1, g->dinv_loop, g->dinv_plain);
+    hipLaunchKernelGGL(classify_rows_kernel, dim3(nblocks), dim3(kThreads), 0, stream, g->rowptr, N, g->small_max,
+                       g->chunk, d_flag, g->indeg, flags, flags + np1, flags + 2 * np1, flags + 3 * np1, g->dinv_loop, g->dinv_plain);
     GNN_LAUNCH_CHECK();
     GNN_TRY(gnn_scan_exclusive_i32(flags, pos, (int64_t)(4 * np1), false, scan_tmp, stream));
     hipLaunchKernelGGL(fill_lists_kernel, dim3(nblocks), dim3(kThreads), 0, stream, g->rowptr, N, g->small_max,
-                       g->chunk, pos, pos + np1, pos + 2 * np1, pos + 3 * np1, g->small_rows, g->item_row,
+                       g->chunk, d_flag, pos, pos + np1, pos + 2 * np1, pos + 3 * np1, g->small_rows, g->item_row,
                        g->item_start, g->item_slot, g->split_rows, g->split_slot0);
     GNN_LAUNCH_CHECK();
     hipLaunchKernelGGL(gather_totals_kernel, dim3(1), dim3(64), 0, stream, d_flag, pos, (int64_t)np1, N, d_flag + 8);
