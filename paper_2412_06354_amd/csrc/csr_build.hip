@@ -79,7 +79,8 @@ __global__ __launch_bounds__(kThreads) void row_pointers_kernel(const int32_t *_
 
 constexpr int kSortItems = 16;                       // keys per thread
 constexpr int kSortTile = kThreads * kSortItems;     // keys per block
-constexpr int kRadixMax = 256;
+constexpr int kDigitBitsMax = 8;   // 10-bit digits (two passes at 2^20 nodes) were measured: the scatter pass takes 2.4 x as long
+constexpr int kRadixMax = 1 << kDigitBitsMax;
 
 // Per-tile digit counts, laid out [digit][tile] so that one exclusive scan over the whole
 // array yields, for every (digit, tile), the first output position of that tile's keys.
@@ -88,34 +89,81 @@ constexpr int kCountThreads = 1024;
 constexpr int kCountItems = kSortTile / kCountThreads;
 constexpr int kCountWaves = kCountThreads / 64;
 
+// CHECK: the first pass over the caller's arrays also does the range check of both index arrays and keeps a copy
+// of the destinations (the keys) in the caller's edge order.
+template <bool CHECK>
 __global__ __launch_bounds__(kCountThreads) void sort_count_kernel(const int32_t *__restrict__ keys, int64_t n, int shift,
                                                                    int bits, int32_t *__restrict__ tile_counts,
-                                                                   int num_tiles)
+                                                                   int num_tiles, const int32_t *__restrict__ src,
+                                                                   int32_t N_src, int32_t N,
+                                                                   int32_t *__restrict__ key_copy,
+                                                                   int32_t *__restrict__ bad)
 {
-    __shared__ int cnt[kCountWaves][kRadixMax];
+    __shared__ int cnt[kCountWaves * kRadixMax];   // [wavefront][digit], rows of `radix` entries
     const int radix = 1 << bits, mask = radix - 1;
     const int w = threadIdx.x >> 6;
-    for (int d = threadIdx.x; d < kCountWaves * kRadixMax; d += kCountThreads) (&cnt[0][0])[d] = 0;
-    const int64_t base = (int64_t)blockIdx.x * kSortTile;
-    int key[kCountItems];
-    bool valid[kCountItems];
+    for (int d = threadIdx.x; d < kCountWaves * radix; d += kCountThreads) cnt[d] = 0;
+    const int lane = threadIdx.x & 63;
+    volatile int *my_cnt = cnt + w * radix;
+    // A block walks over several tiles; the next tile's keys are loaded while this one's are counted.
+    int key[kCountItems], next_key[kCountItems], next_src[kCountItems];
+    auto load_tile = [&](int tile) {
+        const int64_t base = (int64_t)tile * kSortTile;
 #pragma unroll
-    for (int i = 0; i < kCountItems; ++i) {
-        const int64_t idx = base + i * kCountThreads + threadIdx.x;
-        valid[i] = idx < n;
-        key[i] = valid[i] ? keys[idx] : 0;
+        for (int i = 0; i < kCountItems; ++i) {
+            const int64_t idx = base + i * kCountThreads + threadIdx.x;
+            const bool there = tile < num_tiles && idx < n;
+            next_key[i] = there ? __builtin_nontemporal_load(keys + idx) : 0;
+            if constexpr (CHECK) next_src[i] = there ? __builtin_nontemporal_load(src + idx) : 0;
+        }
+    };
+    int any_bad = 0;
+    load_tile(blockIdx.x);
+    for (int tile = blockIdx.x; tile < num_tiles; tile += gridDim.x) {
+#pragma unroll
+        for (int i = 0; i < kCountItems; ++i) {
+            key[i] = next_key[i];
+            if constexpr (CHECK) any_bad |= ((uint32_t)next_src[i] >= (uint32_t)N_src) | ((uint32_t)key[i] >= (uint32_t)N);
+        }
+        __syncthreads();   // counters are zero
+        load_tile(tile + gridDim.x);
+        // Atomics on one LDS address are served one lane at a time, and in the later passes the 64 keys of a
+        // wavefront share their low bits, so a hub node fills many lanes with the same digit.  Large groups of
+        // equal digits are therefore peeled off first: the digit of the first remaining lane is compared in all
+        // lanes (one ballot) and the leader adds the group's size without an atomic; what is left -- or
+        // everything, when the first group is small -- goes through the atomics.  (Finding all groups with
+        // ballots, as the scatter pass does for its ranks, was measured: slower on average.)
+#pragma unroll
+        for (int i = 0; i < kCountItems; ++i) {
+            const int64_t idx = (int64_t)tile * kSortTile + i * kCountThreads + threadIdx.x;
+            const bool valid = idx < n;
+            const int d = (key[i] >> shift) & mask;
+            uint64_t todo = __ballot(valid);
+            for (int round = 0; round < 3 && todo; ++round) {
+                const int leader = __ffsll((long long)todo) - 1;
+                const int d0 = __builtin_amdgcn_readlane(d, leader);
+                const uint64_t group = __ballot(valid && d == d0) & todo;
+                if (__popcll(group) < 6) break;
+                if (lane == leader) my_cnt[d0] += __popcll(group);
+                todo &= ~group;
+            }
+            if ((todo >> lane) & 1) atomicAdd(&cnt[w * radix + d], 1);
+            if constexpr (CHECK)
+                if (valid) __builtin_nontemporal_store(key[i], key_copy + idx);
+        }
+        __syncthreads();
+        for (int d = threadIdx.x; d < radix; d += kCountThreads) {
+            int t = 0;
+#pragma unroll
+            for (int q = 0; q < kCountWaves; ++q) {
+                t += cnt[q * radix + d];
+                cnt[q * radix + d] = 0;
+            }
+            tile_counts[(int64_t)d * num_tiles + tile] = t;
+        }
     }
-    __syncthreads();
-#pragma unroll
-    for (int i = 0; i < kCountItems; ++i)
-        if (valid[i]) atomicAdd(&cnt[w][(key[i] >> shift) & mask], 1);
-    __syncthreads();
-    for (int d = threadIdx.x; d < radix; d += kCountThreads) {
-        int t = 0;
-#pragma unroll
-        for (int q = 0; q < kCountWaves; ++q) t += cnt[q][d];
-        tile_counts[(int64_t)d * num_tiles + blockIdx.x] = t;
-    }
+    if constexpr (CHECK)
+        if (any_bad) atomicOr(bad, 1);
 }
 
 // Stable scatter of one pass.  A tile (kSortTile consecutive keys) is handled by a block of
@@ -129,6 +177,7 @@ __global__ __launch_bounds__(kCountThreads) void sort_count_kernel(const int32_t
 // phase, so that consecutive threads write consecutive global addresses (each digit of a tile is one
 // contiguous run).  Many short per-thread chains (16 wavefronts x 4 items) hide the latency of the
 // ranking loop better than few long ones: 145 us per pass at 20 M keys against 210 us for 4 x 16.
+constexpr int kDies = 8;
 constexpr int kScatterThreads = 1024;
 constexpr int kScatterItems = kSortTile / kScatterThreads;
 constexpr int kScatterWaves = kScatterThreads / 64;
@@ -139,20 +188,26 @@ __global__ __launch_bounds__(kScatterThreads) void sort_scatter_kernel(
     int64_t n, int shift, int bits, const int32_t *__restrict__ tile_offsets, int num_tiles,
     int32_t *__restrict__ keys_out, int32_t *__restrict__ val_out, int32_t *__restrict__ eid_out)
 {
-    __shared__ int wcnt[kScatterWaves][kRadixMax];
+    __shared__ int wcnt[kScatterWaves * kRadixMax];   // [wavefront][digit], rows of `radix` entries
     __shared__ int dbase[kRadixMax];   // first tile-local position of each digit
     __shared__ int gbase[kRadixMax];   // global position of that element minus dbase
     __shared__ int wave_sums[kScatterWaves];
     __shared__ int stage[3][kSortTile];
     const int radix = 1 << bits, mask = radix - 1;
     const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    for (int d = threadIdx.x; d < kScatterWaves * kRadixMax; d += kScatterThreads) (&wcnt[0][0])[d] = 0;
+    // Blocks are dealt round-robin to the chip's eight dies, each with an L2 of its own.  A die gets a contiguous
+    // range of tiles: neighbouring tiles' runs of one digit are neighbours in memory, and written through the
+    // same L2 they merge into whole lines before they leave it.  (The grid is rounded up to a multiple of 8.)
+    const int tiles_per_die = (num_tiles + kDies - 1) / kDies;
+    const int tile = (int)(blockIdx.x % kDies) * tiles_per_die + (int)(blockIdx.x / kDies);
+    if (tile >= num_tiles) return;
+    for (int d = threadIdx.x; d < kScatterWaves * radix; d += kScatterThreads) wcnt[d] = 0;
 
-    const int64_t tile_base = (int64_t)blockIdx.x * kSortTile;
+    const int64_t tile_base = (int64_t)tile * kSortTile;
     const int64_t wbase = tile_base + (int64_t)w * 64 * kScatterItems;
     const int tile_count = (int)min((int64_t)kSortTile, n - tile_base);
     const uint64_t lt_mask = (1ull << lane) - 1ull;
-    volatile int *my_cnt = wcnt[w];
+    volatile int *my_cnt = wcnt + w * radix;
     int key[kScatterItems], val[kScatterItems], eid[kScatterItems], lpos[kScatterItems];
 #pragma unroll
     for (int i = 0; i < kScatterItems; ++i) {
@@ -189,8 +244,8 @@ __global__ __launch_bounds__(kScatterThreads) void sort_scatter_kernel(
         const int d = threadIdx.x;
 #pragma unroll
         for (int q = 0; q < kScatterWaves; ++q) {
-            const int c = wcnt[q][d];
-            wcnt[q][d] = total;
+            const int c = wcnt[q * radix + d];
+            wcnt[q * radix + d] = total;
             total += c;
         }
     }
@@ -211,7 +266,7 @@ __global__ __launch_bounds__(kScatterThreads) void sort_scatter_kernel(
     }
     if ((int)threadIdx.x < radix) {
         dbase[threadIdx.x] = excl;
-        gbase[threadIdx.x] = tile_offsets[(int64_t)threadIdx.x * num_tiles + blockIdx.x] - excl;
+        gbase[threadIdx.x] = tile_offsets[(int64_t)threadIdx.x * num_tiles + tile] - excl;
     }
     __syncthreads();
 #pragma unroll
@@ -219,7 +274,7 @@ __global__ __launch_bounds__(kScatterThreads) void sort_scatter_kernel(
         const int64_t idx = wbase + i * 64 + lane;
         if (idx < n) {
             const int d = (key[i] >> shift) & mask;
-            const int pos = lpos[i] + dbase[d] + wcnt[w][d];
+            const int pos = lpos[i] + dbase[d] + wcnt[w * radix + d];
             stage[0][pos] = key[i];
             stage[1][pos] = val[i];
             stage[2][pos] = eid[i];
@@ -478,27 +533,26 @@ gnn_status build_impl(const int32_t *d_src, const int32_t *d_dst, int64_t E, int
             *eb = at(ts, o_eb), *counts = at(ts, o_counts), *flags = at(ts, o_flags),
             *pos = at(ts, o_pos);
 
-    // ---- index range check and the copy of the destinations in edge order (the flag is read back at the
-    //      end; nothing below indexes with an unchecked node id: the sort only uses masked digits, the row-pointer
-    //      kernel clamps its keys and the work-list kernels do nothing once the flag is set)
+    // ---- the index range check and the copy of the destinations in edge order ride on the first counting
+    //      pass of the sort.  The flag is read back at the end; nothing below indexes with an unchecked node id:
+    //      the sort only uses masked digits, the row-pointer kernel clamps its keys and the work-list kernels do
+    //      nothing once the flag is set.
     GNN_HIP(hipMemsetAsync(d_flag, 0, 64 * sizeof(int32_t), stream));
-    if (E > 0) {
-        const int blocks = (int)std::min<int64_t>(gnn_div_up(E, kThreads), 256 * 16);
-        hipLaunchKernelGGL(check_range_kernel, dim3(blocks), dim3(kThreads), 0, stream, d_src, d_dst, E,
-                           g->num_src_nodes, N, g->dst_coo, d_flag);
-        GNN_LAUNCH_CHECK();
-    }
 
     // ---- stable radix sort by destination
     if (E > 0) {
         const int key_bits = ceil_log2((uint32_t)N);
-        if (key_bits == 0) {
+        if (key_bits == 0) {   // one node: nothing to sort
+            const int cblocks = (int)std::min<int64_t>(gnn_div_up(E, kThreads), 256 * 16);
+            hipLaunchKernelGGL(check_range_kernel, dim3(cblocks), dim3(kThreads), 0, stream, d_src, d_dst, E,
+                               g->num_src_nodes, N, g->dst_coo, d_flag);
+            GNN_LAUNCH_CHECK();
             const int blocks = (int)gnn_div_up(E, kThreads);
             hipLaunchKernelGGL(iota_copy_kernel, dim3(blocks), dim3(kThreads), 0, stream, d_dst, d_src, E, g->rowidx,
                                g->colidx, g->perm);
             GNN_LAUNCH_CHECK();
         } else {
-            const int passes = (key_bits + 7) / 8;
+            const int passes = (key_bits + kDigitBitsMax - 1) / kDigitBitsMax;
             const int bits = (key_bits + passes - 1) / passes;
             // Ping-pong between (kb, vb, eb) and the arrays the graph keeps, arranged so that
             // the last pass writes into the graph's arrays.
@@ -507,11 +561,17 @@ gnn_status build_impl(const int32_t *d_src, const int32_t *d_dst, int64_t E, int
             const int32_t *ki = d_dst, *vi = d_src, *ei = nullptr;
             for (int p = 0; p < passes; ++p) {
                 const int shift = p * bits;
-                hipLaunchKernelGGL(sort_count_kernel, dim3((unsigned)num_tiles), dim3(kCountThreads), 0, stream, ki, E,
-                                   shift, bits, counts, (int)num_tiles);
+                const dim3 cgrid((unsigned)std::min<int64_t>(num_tiles, 1024));
+                if (p == 0)   // the pass over the caller's arrays: range check and edge-order copy of dst ride along
+                    hipLaunchKernelGGL(sort_count_kernel<true>, cgrid, dim3(kCountThreads), 0, stream, ki, E, shift, bits,
+                                       counts, (int)num_tiles, d_src, g->num_src_nodes, N, g->dst_coo, d_flag);
+                else
+                    hipLaunchKernelGGL(sort_count_kernel<false>, cgrid, dim3(kCountThreads), 0, stream, ki, E, shift, bits,
+                                       counts, (int)num_tiles, (const int32_t *)nullptr, 0, 0, (int32_t *)nullptr,
+                                       (int32_t *)nullptr);
                 GNN_LAUNCH_CHECK();
                 GNN_TRY(gnn_scan_exclusive_i32(counts, counts, num_tiles << bits, false, scan_tmp, stream));
-                hipLaunchKernelGGL(sort_scatter_kernel, dim3((unsigned)num_tiles), dim3(kScatterThreads), 0, stream, ki, vi,
+                hipLaunchKernelGGL(sort_scatter_kernel, dim3((unsigned)(gnn_div_up(num_tiles, kDies) * kDies)), dim3(kScatterThreads), 0, stream, ki, vi,
                                    ei, E, shift, bits, counts, (int)num_tiles, bufk[dst_sel], bufv[dst_sel],
                                    bufe[dst_sel]);
                 GNN_LAUNCH_CHECK();
