@@ -27,6 +27,7 @@ struct GatBwdParams {
     const int32_t *rowptr, *colidx;      // the graph this pass walks (by destination or by source)
     const float *own_vec, *nbr_vec;      // [N x HC]: by destination G / h, by source h / G
     const float *sl;                     // [N x H]
+    const float *a_src;                  // [H x ch] (by destination: sl[j] recomputed from the gathered h[j])
     const float4 *rec;                   // [N x H]: (sr, segment maximum, 1 / denominator, t)
     float *out_vec;                      // [N x HC], by-source pass only
     float *out_s;                        // [N x H]
@@ -61,14 +62,17 @@ template <int VEC>
 struct Lane {
     float own[VEC];
     float own_sl;      // by source
+    float as[VEC];     // by destination, recomputing: this lane's slice of a_src
     float4 own_rec;    // by destination
     float acc_s;
     float acc_v[VEC];  // by source
 };
 
-template <int VEC, bool BY_SRC>
+template <int VEC, bool BY_SRC, bool RECOMP>
 __device__ __forceinline__ void lane_init(Lane<VEC> &ln, const GatBwdParams &p, bool colok, int row, int col, int hd)
 {
+#pragma unroll
+    for (int c = 0; c < VEC; ++c) ln.as[c] = (RECOMP && colok) ? p.a_src[col + c] : 0.0f;
     ln.own_sl = 0.0f;
     ln.own_rec = make_float4(0.f, 0.f, 0.f, 0.f);
     ln.acc_s = 0.0f;
@@ -83,7 +87,10 @@ __device__ __forceinline__ void lane_init(Lane<VEC> &ln, const GatBwdParams &p, 
 
 // One edge: nv = the neighbour's feature slice, nsl / nrec = the neighbour's scalars (zero when !ok).
 // Runs with every lane of the wavefront active (the shuffle needs its partners).
-template <int VEC, bool BY_SRC>
+// RECOMP (by destination only): the neighbour's sl is not gathered but recomputed from its feature slice --
+// an fma chain from zero per lane, lanes added pairwise: the operations and the order of node_scores_kernel,
+// hence the stored value bit for bit.
+template <int VEC, bool BY_SRC, bool RECOMP>
 __device__ __forceinline__ void lane_edge(Lane<VEC> &ln, const GatBwdParams &p, bool ok, const float *nv, float nsl,
                                           float4 nrec)
 {
@@ -91,6 +98,12 @@ __device__ __forceinline__ void lane_edge(Lane<VEC> &ln, const GatBwdParams &p, 
 #pragma unroll
     for (int c = 0; c < VEC; ++c) dot = fmaf(ln.own[c], nv[c], dot);
     for (int off = 1; off < p.lh; off <<= 1) dot += __shfl_xor(dot, off, 64);   // over the head's lanes
+    if constexpr (RECOMP) {
+        nsl = 0.0f;
+#pragma unroll
+        for (int c = 0; c < VEC; ++c) nsl = fmaf(ln.as[c], nv[c], nsl);
+        for (int off = 1; off < p.lh; off <<= 1) nsl += __shfl_xor(nsl, off, 64);
+    }
     const float v = BY_SRC ? ln.own_sl + nrec.x : nsl + ln.own_rec.x;
     const float mx = BY_SRC ? nrec.y : ln.own_rec.y;
     const float inv = BY_SRC ? nrec.z : ln.own_rec.z;
@@ -111,7 +124,7 @@ __device__ __forceinline__ void lane_write(const Lane<VEC> &ln, const GatBwdPara
     if (col % p.ch == 0) p.out_s[(int64_t)row * p.H + hd] = ln.acc_s;
 }
 
-template <int LPR, int VEC, bool BY_SRC>
+template <int LPR, int VEC, bool BY_SRC, bool RECOMP>
 __device__ __forceinline__ void bwd_short_rows(const GatBwdParams &p, int block)
 {
     constexpr int NSG = 64 / LPR;
@@ -135,7 +148,7 @@ __device__ __forceinline__ void bwd_short_rows(const GatBwdParams &p, int block)
         const bool colok = have && col < p.HC;
         const int hd = colok ? col / p.ch : 0;
         Lane<VEC> ln;
-        lane_init<VEC, BY_SRC>(ln, p, colok, row, col, hd);
+        lane_init<VEC, BY_SRC, RECOMP>(ln, p, colok, row, col, hd);
         for (int base = 0; base < wmax; base += LPR) {
             int my_q = 0;
             if (base + sl_ < deg) my_q = p.colidx[start + base + sl_];
@@ -156,18 +169,18 @@ __device__ __forceinline__ void bwd_short_rows(const GatBwdParams &p, int block)
                     if (ok[u]) {
                         load_vec<VEC>(nv[u], p.nbr_vec + (int64_t)q * p.HC + col);
                         if constexpr (BY_SRC) nrec[u] = p.rec[(int64_t)q * p.H + hd];
-                        else nsl[u] = p.sl[(int64_t)q * p.H + hd];
+                        else if constexpr (!RECOMP) nsl[u] = p.sl[(int64_t)q * p.H + hd];
                     }
                 }
 #pragma unroll
-                for (int u = 0; u < U; ++u) lane_edge<VEC, BY_SRC>(ln, p, ok[u], nv[u], nsl[u], nrec[u]);
+                for (int u = 0; u < U; ++u) lane_edge<VEC, BY_SRC, RECOMP>(ln, p, ok[u], nv[u], nsl[u], nrec[u]);
             }
         }
         if (colok) lane_write<VEC, BY_SRC>(ln, p, row, col, hd);
     }
 }
 
-template <int LPR, int VEC, bool BY_SRC>
+template <int LPR, int VEC, bool BY_SRC, bool RECOMP>
 __device__ __forceinline__ void bwd_long_pieces(const GatBwdParams &p, int block)
 {
     constexpr int NSG = 64 / LPR;
@@ -186,7 +199,7 @@ __device__ __forceinline__ void bwd_long_pieces(const GatBwdParams &p, int block
         const bool colok = col < p.HC;
         const int hd = colok ? col / p.ch : 0;
         Lane<VEC> ln;
-        lane_init<VEC, BY_SRC>(ln, p, colok, row, col, hd);
+        lane_init<VEC, BY_SRC, RECOMP>(ln, p, colok, row, col, hd);
         for (int base = start; base < end; base += 64) {
             const int n = min(64, end - base);
             int my_q = 0;
@@ -207,11 +220,11 @@ __device__ __forceinline__ void bwd_long_pieces(const GatBwdParams &p, int block
                     if (ok[u]) {
                         load_vec<VEC>(nv[u], p.nbr_vec + (int64_t)q * p.HC + col);
                         if constexpr (BY_SRC) nrec[u] = p.rec[(int64_t)q * p.H + hd];
-                        else nsl[u] = p.sl[(int64_t)q * p.H + hd];
+                        else if constexpr (!RECOMP) nsl[u] = p.sl[(int64_t)q * p.H + hd];
                     }
                 }
 #pragma unroll
-                for (int u = 0; u < U; ++u) lane_edge<VEC, BY_SRC>(ln, p, ok[u], nv[u], nsl[u], nrec[u]);
+                for (int u = 0; u < U; ++u) lane_edge<VEC, BY_SRC, RECOMP>(ln, p, ok[u], nv[u], nsl[u], nrec[u]);
             }
         }
 #pragma unroll
@@ -237,13 +250,13 @@ __device__ __forceinline__ void bwd_long_pieces(const GatBwdParams &p, int block
     }
 }
 
-template <int LPR, int VEC, bool BY_SRC>
+template <int LPR, int VEC, bool BY_SRC, bool RECOMP>
 __global__ __launch_bounds__(kThreads) void gat_backward_kernel(const GatBwdParams p)
 {
     if ((int)blockIdx.x < p.item_blocks)
-        bwd_long_pieces<LPR, VEC, BY_SRC>(p, blockIdx.x);
+        bwd_long_pieces<LPR, VEC, BY_SRC, RECOMP>(p, blockIdx.x);
     else
-        bwd_short_rows<LPR, VEC, BY_SRC>(p, blockIdx.x - p.item_blocks);
+        bwd_short_rows<LPR, VEC, BY_SRC, RECOMP>(p, blockIdx.x - p.item_blocks);
 }
 
 // Split rows: the pieces' partial sums are added in piece order.
@@ -378,7 +391,15 @@ gnn_status launch_pass(const GatBwdParams &p, hipStream_t stream)
     constexpr int NSG = 64 / LPR;
     const int64_t blocks = p.item_blocks + gnn_div_up(p.n_small, kWavesPerBlock * NSG);
     if (blocks > 0) {
-        hipLaunchKernelGGL((gat_backward_kernel<LPR, VEC, BY_SRC>), dim3((unsigned)blocks), dim3(kThreads), 0, stream, p);
+        // by destination, heads of at most 16 channels in 128-bit groups: sl[j] is recomputed from the gathered
+        // slice in node_scores_kernel's tree order (wider heads are summed in another order there: gathered)
+        constexpr bool kCanRecompute = !BY_SRC && VEC == 4;
+        if (kCanRecompute && p.lh <= 4)
+            hipLaunchKernelGGL((gat_backward_kernel<LPR, VEC, BY_SRC, kCanRecompute>), dim3((unsigned)blocks),
+                               dim3(kThreads), 0, stream, p);
+        else
+            hipLaunchKernelGGL((gat_backward_kernel<LPR, VEC, BY_SRC, false>), dim3((unsigned)blocks), dim3(kThreads), 0,
+                               stream, p);
         GNN_LAUNCH_CHECK();
     }
     if (p.n_split > 0) {
@@ -488,7 +509,7 @@ gnn_status gnn_gatconv_backward(const gnn_graph *g, const gnn_graph *g_by_source
     GNN_LAUNCH_CHECK();
 
     GatBwdParams p{};
-    p.sl = sl; p.rec = rec;
+    p.sl = sl; p.a_src = d_a_src; p.rec = rec;
     p.HC = HC; p.H = heads; p.ch = ch; p.lh = lh; p.slope = negative_slope;
     // by destination: dsr
     p.own_vec = d_grad_out; p.nbr_vec = h; p.out_vec = nullptr; p.out_s = dsr;

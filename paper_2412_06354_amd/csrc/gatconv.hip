@@ -19,6 +19,7 @@ constexpr int kWavesPerBlock = kThreads / 64;
 struct GatParams {
     const int32_t *rowptr, *colidx;
     const float *h, *sl, *sr;
+    const float *a_src;                  // [H x ch]: the source half of the attention vector (score recomputation)
     float *out;
     float *stats;                        // optional [N x H x 2]: (segment maximum, denominator) per row and head
     float *slot_acc, *slot_m, *slot_d;   // [slots x HC] each
@@ -106,7 +107,22 @@ __device__ __forceinline__ void write_out(const GatParams &p, int row, int col, 
 
 __device__ __forceinline__ float lrelu(float v, float slope) { return v > 0.0f ? v : slope * v; }
 
-template <int LPR, int VEC>
+// Source half of an edge's score from the gathered feature slice itself: <a_src, h_j> over the head's channels,
+// which LPH consecutive lanes hold VEC at a time.  The per-lane partial is an fma chain from zero, the lanes are
+// added pairwise (xor 1, 2, ...): the same operations in the same order as node_scores_kernel, so the value is
+// bit for bit the stored sl[j, head] -- without the second gather per edge.
+template <int VEC, int LPH>
+__device__ __forceinline__ float source_score(const float *as, const float *hv)
+{
+    float part = 0.0f;
+#pragma unroll
+    for (int c = 0; c < VEC; ++c) part = fmaf(as[c], hv[c], part);
+#pragma unroll
+    for (int off = 1; off < LPH; off <<= 1) part += __shfl_xor(part, off, 64);
+    return part;
+}
+
+template <int LPR, int VEC, int LPH>
 __device__ __forceinline__ void gat_short_rows(const GatParams &p, int block)
 {
     constexpr int NSG = 64 / LPR;
@@ -130,6 +146,9 @@ __device__ __forceinline__ void gat_short_rows(const GatParams &p, int block)
         const bool colok = have && col < p.HC;
         const int hd = colok ? col / p.ch : 0;
         const float sr_i = colok ? p.sr[(int64_t)row * p.H + hd] : 0.0f;
+        float as[VEC];   // LPH > 0: scores are recomputed from the gathered slices
+#pragma unroll
+        for (int c = 0; c < VEC; ++c) as[c] = (LPH > 0 && colok) ? p.a_src[col + c] : 0.0f;
         State<VEC> st;
         state_init(st);
         for (int base = 0; base < wmax; base += LPR) {
@@ -149,18 +168,21 @@ __device__ __forceinline__ void gat_short_rows(const GatParams &p, int block)
                     for (int c = 0; c < VEC; ++c) hv[u][c] = 0.0f;
                     if (ok[u]) {
                         load_vec<VEC>(hv[u], p.h + (int64_t)j * p.HC + col);
-                        sc[u] = p.sl[(int64_t)j * p.H + hd];
+                        if constexpr (LPH == 0) sc[u] = p.sl[(int64_t)j * p.H + hd];
                     }
                 }
 #pragma unroll
-                for (int u = 0; u < U; ++u) state_add<VEC>(st, ok[u], lrelu(sc[u] + sr_i, p.slope), hv[u]);
+                for (int u = 0; u < U; ++u) {
+                    if constexpr (LPH > 0) sc[u] = source_score<VEC, LPH>(as, hv[u]);
+                    state_add<VEC>(st, ok[u], lrelu(sc[u] + sr_i, p.slope), hv[u]);
+                }
             }
         }
         if (colok) write_out<VEC>(p, row, col, st);
     }
 }
 
-template <int LPR, int VEC>
+template <int LPR, int VEC, int LPH>
 __device__ __forceinline__ void gat_long_pieces(const GatParams &p, int block)
 {
     constexpr int NSG = 64 / LPR;
@@ -179,6 +201,9 @@ __device__ __forceinline__ void gat_long_pieces(const GatParams &p, int block)
         const bool colok = col < p.HC;
         const int hd = colok ? col / p.ch : 0;
         const float sr_i = colok ? p.sr[(int64_t)row * p.H + hd] : 0.0f;
+        float as[VEC];   // LPH > 0: scores are recomputed from the gathered slices
+#pragma unroll
+        for (int c = 0; c < VEC; ++c) as[c] = (LPH > 0 && colok) ? p.a_src[col + c] : 0.0f;
         State<VEC> st;
         state_init(st);
         for (int base = start; base < end; base += 64) {
@@ -198,11 +223,14 @@ __device__ __forceinline__ void gat_long_pieces(const GatParams &p, int block)
                     for (int c = 0; c < VEC; ++c) hv[u][c] = 0.0f;
                     if (ok[u]) {
                         load_vec<VEC>(hv[u], p.h + (int64_t)j * p.HC + col);
-                        sc[u] = p.sl[(int64_t)j * p.H + hd];
+                        if constexpr (LPH == 0) sc[u] = p.sl[(int64_t)j * p.H + hd];
                     }
                 }
 #pragma unroll
-                for (int u = 0; u < U; ++u) state_add<VEC>(st, ok[u], lrelu(sc[u] + sr_i, p.slope), hv[u]);
+                for (int u = 0; u < U; ++u) {
+                    if constexpr (LPH > 0) sc[u] = source_score<VEC, LPH>(as, hv[u]);
+                    state_add<VEC>(st, ok[u], lrelu(sc[u] + sr_i, p.slope), hv[u]);
+                }
             }
         }
 #pragma unroll
@@ -229,13 +257,13 @@ __device__ __forceinline__ void gat_long_pieces(const GatParams &p, int block)
     }
 }
 
-template <int LPR, int VEC>
+template <int LPR, int VEC, int LPH>
 __global__ __launch_bounds__(kThreads) void gat_kernel(const GatParams p)
 {
     if ((int)blockIdx.x < p.item_blocks)
-        gat_long_pieces<LPR, VEC>(p, blockIdx.x);
+        gat_long_pieces<LPR, VEC, LPH>(p, blockIdx.x);
     else
-        gat_short_rows<LPR, VEC>(p, blockIdx.x - p.item_blocks);
+        gat_short_rows<LPR, VEC, LPH>(p, blockIdx.x - p.item_blocks);
 }
 
 template <int LPR, int VEC>
@@ -264,26 +292,46 @@ __global__ __launch_bounds__(kThreads) void gat_merge_kernel(const GatParams p)
 }
 
 // sl[i,hd] = <a_src[hd,:], h[i,hd,:]>,  sr[i,hd] = <a_dst[hd,:], h[i,hd,:]>
-// One thread per (node, head); with VEC = 4 the head's channels are read as 128-bit pieces.
+// One thread per (node, head); with VEC = 4 the head's channels are read as 128-bit pieces.  Order of the
+// sum: an fma chain from zero per group of VEC channels; the group sums are added pairwise as a tree when their
+// number is a power of two (the order source_score() uses), else one after the other.
 template <int VEC>
 __global__ __launch_bounds__(kThreads) void node_scores_kernel(const float *__restrict__ h, int64_t N, int H, int ch,
                                                                const float *__restrict__ a_src,
                                                                const float *__restrict__ a_dst,
                                                                float *__restrict__ sl, float *__restrict__ sr)
 {
+    constexpr int kTreeGroups = 4;
     const int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (idx >= N * H) return;
     const int hd = (int)(idx % H);
     const float *hp = h + idx * ch;   // (i*H + hd)*ch
+    const int groups = ch / VEC;
+    const bool tree = groups <= kTreeGroups && (groups & (groups - 1)) == 0;
+    float lt[kTreeGroups] = {0.f, 0.f, 0.f, 0.f}, rt[kTreeGroups] = {0.f, 0.f, 0.f, 0.f};
     float l = 0.0f, r = 0.0f;
-    for (int c = 0; c < ch; c += VEC) {
+    for (int g = 0; g < groups; ++g) {
         float v[VEC];
-        load_vec<VEC>(v, hp + c);
+        load_vec<VEC>(v, hp + g * VEC);
+        float lp = 0.0f, rp = 0.0f;
 #pragma unroll
         for (int q = 0; q < VEC; ++q) {
-            l = fmaf(a_src[hd * ch + c + q], v[q], l);
-            r = fmaf(a_dst[hd * ch + c + q], v[q], r);
+            lp = fmaf(a_src[hd * ch + g * VEC + q], v[q], lp);
+            rp = fmaf(a_dst[hd * ch + g * VEC + q], v[q], rp);
         }
+        if (tree) {
+#pragma unroll
+            for (int t = 0; t < kTreeGroups; ++t)
+                if (t == g) { lt[t] = lp; rt[t] = rp; }
+        } else {
+            l += lp;
+            r += rp;
+        }
+    }
+    if (tree) {
+        if (groups == 1) { l = lt[0]; r = rt[0]; }
+        else if (groups == 2) { l = lt[0] + lt[1]; r = rt[0] + rt[1]; }
+        else { l = (lt[0] + lt[1]) + (lt[2] + lt[3]); r = (rt[0] + rt[1]) + (rt[2] + rt[3]); }
     }
     sl[idx] = l;
     sr[idx] = r;
@@ -295,7 +343,18 @@ gnn_status launch_gat(const GatParams &p, hipStream_t stream)
     constexpr int NSG = 64 / LPR;
     const int64_t blocks = p.item_blocks + gnn_div_up(p.n_small, kWavesPerBlock * NSG);
     if (blocks > 0) {
-        hipLaunchKernelGGL((gat_kernel<LPR, VEC>), dim3((unsigned)blocks), dim3(kThreads), 0, stream, p);
+        // Heads of 4, 8 or 16 channels (1, 2 or 4 lanes of a 128-bit column group): the source half of the score
+        // is recomputed from the gathered slice; other widths gather it from the per-node array.
+        const int lph = (VEC == 4 && p.ch % 4 == 0) ? p.ch / 4 : 0;
+        const dim3 grid((unsigned)blocks);
+        if (VEC == 4 && lph == 1)
+            hipLaunchKernelGGL((gat_kernel<LPR, VEC, (VEC == 4 ? 1 : 0)>), grid, dim3(kThreads), 0, stream, p);
+        else if (VEC == 4 && lph == 2 && LPR >= 2)
+            hipLaunchKernelGGL((gat_kernel<LPR, VEC, (VEC == 4 ? 2 : 0)>), grid, dim3(kThreads), 0, stream, p);
+        else if (VEC == 4 && lph == 4 && LPR >= 4)
+            hipLaunchKernelGGL((gat_kernel<LPR, VEC, (VEC == 4 ? 4 : 0)>), grid, dim3(kThreads), 0, stream, p);
+        else
+            hipLaunchKernelGGL((gat_kernel<LPR, VEC, 0>), grid, dim3(kThreads), 0, stream, p);
         GNN_LAUNCH_CHECK();
     }
     if (p.n_split > 0) {
@@ -356,7 +415,7 @@ gnn_status gnn_gatconv(const gnn_graph *g, const float *d_x, int32_t f_in, const
 
     GatParams p{};
     p.rowptr = g->rowptr; p.colidx = g->colidx;
-    p.h = h; p.sl = sl; p.sr = sr; p.out = d_out; p.stats = d_softmax_stats;
+    p.h = h; p.sl = sl; p.sr = sr; p.a_src = d_a_src; p.out = d_out; p.stats = d_softmax_stats;
     p.small_rows = g->small_rows; p.item_row = g->item_row; p.item_start = g->item_start;
     p.item_slot = g->item_slot; p.split_rows = g->split_rows; p.split_slot0 = g->split_slot0;
     p.n_small = g->n_small; p.n_items = g->n_items; p.n_split = g->n_split; p.chunk = g->chunk;
