@@ -19,13 +19,63 @@ namespace {
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 constexpr int kThreads = 256;
 
-__global__ __launch_bounds__(kThreads) void scale_rows_kernel(const float *__restrict__ scale, int64_t N, int F,
-                                                              const float *__restrict__ in, float *__restrict__ out)
+// One pass over G for both of its uses: out[r,:] = scale[r] * G[r,:] (the rows the propagate gathers; out may be
+// null) and partial[chunk][j] = sum over the chunk's rows of G[r][j] (the bias gradient's first stage; partial may
+// be null).  A block owns a row chunk; its threads form (row slice, column group) pairs, a slice takes every
+// `slices`-th row, and the slices' sums are folded through LDS in slice order.
+template <int VEC>
+__global__ __launch_bounds__(kThreads) void scale_rows_colsum_kernel(const float *__restrict__ scale, int64_t N, int F,
+                                                                     const float *__restrict__ g,
+                                                                     int64_t rows_per_chunk, float *__restrict__ out,
+                                                                     float *__restrict__ partial)
 {
-    const int64_t total = N * F;
-    const int64_t stride = (int64_t)gridDim.x * kThreads;
-    for (int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x; idx < total; idx += stride)
-        out[idx] = in[idx] * scale[idx / F];
+    __shared__ float fold[kThreads * VEC];
+    const int fv = F / VEC;
+    const int width = min(fv, kThreads), slices = kThreads / width;
+    const int cg0 = threadIdx.x % width, sl = threadIdx.x / width;
+    const int64_t r0 = (int64_t)blockIdx.x * rows_per_chunk, r1 = min(N, r0 + rows_per_chunk);
+    for (int cbase = 0; cbase < fv; cbase += width) {
+        const int cg = cbase + cg0;
+        const bool active = sl < slices && cg < fv;
+        float sum[VEC];
+#pragma unroll
+        for (int c = 0; c < VEC; ++c) sum[c] = 0.0f;
+        if (active) {
+#pragma unroll 4
+            for (int64_t r = r0 + sl; r < r1; r += slices) {
+                float v[VEC];
+                if constexpr (VEC == 4) {
+                    const float4 t = *reinterpret_cast<const float4 *>(g + r * F + cg * 4);
+                    v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+                } else {
+                    v[0] = g[r * F + cg];
+                }
+#pragma unroll
+                for (int c = 0; c < VEC; ++c) sum[c] += v[c];
+                if (out) {
+                    const float sc = scale[r];
+                    if constexpr (VEC == 4)
+                        *reinterpret_cast<float4 *>(out + r * F + cg * 4) = make_float4(v[0] * sc, v[1] * sc, v[2] * sc, v[3] * sc);
+                    else
+                        out[r * F + cg] = v[0] * sc;
+                }
+            }
+        }
+        if (partial) {   // block-uniform
+#pragma unroll
+            for (int c = 0; c < VEC; ++c) fold[threadIdx.x * VEC + c] = sum[c];
+            __syncthreads();
+            if (sl == 0 && cg < fv) {
+#pragma unroll
+                for (int c = 0; c < VEC; ++c) {
+                    float t = 0.0f;
+                    for (int q = 0; q < slices; ++q) t += fold[(q * width + cg0) * VEC + c];
+                    partial[(int64_t)blockIdx.x * F + cg * VEC + c] = t;
+                }
+            }
+            __syncthreads();
+        }
+    }
 }
 
 __global__ __launch_bounds__(kThreads) void transpose_kernel(const float *__restrict__ w, int rows, int cols,
@@ -50,7 +100,6 @@ __global__ __launch_bounds__(kThreads) void xty_partial_kernel(const float *__re
     const int i0 = (blockIdx.y * 4 + wave) * 32;
     const int j0 = blockIdx.z * NT * 32;
     const int64_t r0 = (int64_t)blockIdx.x * rows_per_chunk, r1 = min(rows, r0 + rows_per_chunk);
-    const bool i_ok = i0 + c < f_in;
 
     floatx16 acc[NT];
 #pragma unroll
@@ -59,23 +108,34 @@ __global__ __launch_bounds__(kThreads) void xty_partial_kernel(const float *__re
         for (int v = 0; v < 16; ++v) acc[t][v] = 0.0f;
 
     if (i0 < f_in) {   // wavefront-uniform
-        for (int64_t rp = r0; rp < r1; rp += 2 * U) {
-            float a[U], b[U][NT];
+        // Two register sets: the loads of the next U row pairs are in flight while the MFMAs of the current
+        // ones run (rows past the chunk load nothing and multiply zeros).
+        auto load_set = [&](float (&a)[U], float (&b)[U][NT], int64_t rp) {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
+                // Unconditional loads from clamped addresses, no branches between them.  A row past the chunk is
+                // cancelled by a zero factor on the X side alone (inputs are finite by contract); columns past
+                // the matrices only feed accumulator entries that are never stored.
                 const int64_t row = rp + 2 * u + kk;
-                const bool ok = row < r1;
-                a[u] = (ok && i_ok) ? x[row * f_in + i0 + c] : 0.0f;
+                const int64_t rc = min(row, r1 - 1);
+                a[u] = x[rc * f_in + min(i0 + c, f_in - 1)] * (row < r1 ? 1.0f : 0.0f);
 #pragma unroll
-                for (int t = 0; t < NT; ++t) {
-                    const int j = j0 + t * 32 + c;
-                    b[u][t] = (ok && j < f_out) ? y[row * f_out + j] : 0.0f;
-                }
+                for (int t = 0; t < NT; ++t) b[u][t] = y[rc * f_out + min(j0 + t * 32 + c, f_out - 1)];
             }
+        };
+        auto mfma_set = [&](const float (&a)[U], const float (&b)[U][NT]) {
 #pragma unroll
             for (int u = 0; u < U; ++u)
 #pragma unroll
                 for (int t = 0; t < NT; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u], b[u][t], acc[t], 0, 0, 0);
+        };
+        float a0[U], b0[U][NT], a1[U], b1[U][NT];
+        load_set(a0, b0, r0);
+        for (int64_t rp = r0; rp < r1; rp += 4 * U) {
+            load_set(a1, b1, rp + 2 * U);
+            mfma_set(a0, b0);
+            load_set(a0, b0, rp + 4 * U);
+            mfma_set(a1, b1);
         }
         // accumulator register v of lane l: row 8*(v/4) + 4*(l/32) + v%4, column l%32
         float *out = partial + (int64_t)blockIdx.x * f_in * f_out;
@@ -87,23 +147,6 @@ __global__ __launch_bounds__(kThreads) void xty_partial_kernel(const float *__re
                 const int j = j0 + t * 32 + c;
                 if (i < f_in && j < f_out) out[(int64_t)i * f_out + j] = acc[t][v];
             }
-    }
-}
-
-// partial[chunk][j] = sum over the chunk's rows of G[row][j]
-__global__ __launch_bounds__(kThreads) void colsum_partial_kernel(const float *__restrict__ g, int64_t rows, int F,
-                                                                  int64_t rows_per_chunk, float *__restrict__ partial)
-{
-    const int64_t r0 = (int64_t)blockIdx.x * rows_per_chunk, r1 = min(rows, r0 + rows_per_chunk);
-    for (int j = threadIdx.x; j < F; j += kThreads) {
-        float s[4] = {0.0f, 0.0f, 0.0f, 0.0f};   // four interleaved running sums: loads stay independent
-        int64_t r = r0;
-        for (; r + 4 <= r1; r += 4) {
-#pragma unroll
-            for (int u = 0; u < 4; ++u) s[u] += g[(r + u) * F + j];
-        }
-        for (; r < r1; ++r) s[0] += g[r * F + j];
-        partial[(int64_t)blockIdx.x * F + j] = (s[0] + s[1]) + (s[2] + s[3]);
     }
 }
 
@@ -160,7 +203,11 @@ BackwardLayout layout(int64_t N, int f_in, int f_out)
 
 int gnn_row_chunk_count(int64_t rows)
 {
-    return (int)std::max<int64_t>(1, std::min<int64_t>(2048, gnn_div_up(rows, 256)));
+    // about 256 rows per chunk, at most 2048 chunks; above one chunk per compute unit the count is rounded up to
+    // a multiple of 256, so that blocks working on one chunk each come in whole rounds over the chip
+    int64_t c = std::max<int64_t>(1, gnn_div_up(rows, 256));
+    if (c > 256) c = gnn_div_up(c, 256) * 256;
+    return (int)std::min<int64_t>(2048, c);
 }
 
 gnn_status gnn_launch_sum_partials_scaled(const float *d_partial, int chunks, int64_t elems, float factor,
@@ -227,13 +274,28 @@ gnn_status gnn_gcnconv_backward(const gnn_graph *g, const gnn_graph *g_by_source
           *wt = reinterpret_cast<float *>(ws + l.wt),
           *part = reinterpret_cast<float *>(ws + l.part);
     const int chunks = chunk_count(N);
-    const int64_t rows_per_chunk = gnn_div_up(N, chunks);
     const float *dinv = add_self_loops ? g->dinv_loop : g->dinv_plain;   // the forward graph's degree factors
 
-    if (d_grad_x || d_grad_w) {
-        const int blocks = (int)std::min<int64_t>(gnn_div_up(N * f_out, kThreads), 256 * 64);
-        hipLaunchKernelGGL(scale_rows_kernel, dim3(blocks), dim3(kThreads), 0, s, dinv, N, f_out, d_grad_out, gs);
+    const bool need_t = d_grad_x || d_grad_w;
+    if (need_t || d_grad_b) {
+        // G is read once: scaled rows for the propagate and the first stage of the bias gradient (64-row chunks:
+        // enough blocks to stream at full rate; the partial sums fit the workspace's partial-result area)
+        const int64_t bias_chunks = std::max<int64_t>(
+            1, std::min<int64_t>(std::min<int64_t>(2048, gnn_div_up(N, 64)), (int64_t)chunks * f_in));
+        const int64_t bias_rows = gnn_div_up(N, bias_chunks);
+        const dim3 grid((unsigned)gnn_div_up(N, bias_rows));
+        const bool vec4 = f_out % 4 == 0 && ((reinterpret_cast<uintptr_t>(d_grad_out) | reinterpret_cast<uintptr_t>(gs)) & 15u) == 0;
+        float *scaled = need_t ? gs : nullptr, *bias_part = d_grad_b ? part : nullptr;
+        if (vec4)
+            hipLaunchKernelGGL(scale_rows_colsum_kernel<4>, grid, dim3(kThreads), 0, s, dinv, N, f_out, d_grad_out,
+                               bias_rows, scaled, bias_part);
+        else
+            hipLaunchKernelGGL(scale_rows_colsum_kernel<1>, grid, dim3(kThreads), 0, s, dinv, N, f_out, d_grad_out,
+                               bias_rows, scaled, bias_part);
         GNN_LAUNCH_CHECK();
+        if (d_grad_b) GNN_TRY(gnn_launch_sum_partials(part, (int)grid.x, (int64_t)f_out, d_grad_b, s));
+    }
+    if (need_t) {
         gnn_epilogue epi;
         epi.self_scale = add_self_loops ? 1.0f : 0.0f;
         epi.row_scale = dinv;
@@ -245,12 +307,6 @@ gnn_status gnn_gcnconv_backward(const gnn_graph *g, const gnn_graph *g_by_source
         GNN_TRY(gnn_dense_xw(t, N, f_out, wt, f_in, nullptr, d_grad_x, stream));
     }
     if (d_grad_w) GNN_TRY(gnn_launch_xty(d_x, t, N, f_in, f_out, part, d_grad_w, s));
-    if (d_grad_b) {
-        hipLaunchKernelGGL(colsum_partial_kernel, dim3((unsigned)chunks), dim3(kThreads), 0, s, d_grad_out, N, f_out,
-                           rows_per_chunk, part);
-        GNN_LAUNCH_CHECK();
-        GNN_TRY(gnn_launch_sum_partials(part, chunks, (int64_t)f_out, d_grad_b, s));
-    }
     return GNN_OK;
 }
 
