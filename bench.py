@@ -42,9 +42,9 @@ MFMA_FP32_PEAK_TFLOPS = 157.3
 # (FETCH_SIZE x 2.000 calibration factor + WRITE_SIZE x 1.000, calibrated on a 1 GiB streaming kernel
 # in the same run).  Only meaningful for the default sizes of each workload; other sizes report null.
 MEASURED_TRAFFIC_BYTES = {
-    ("propagate", 1_000_000, 20_000_000, 64): 2_924_179_136,   # propagate_kernel<16,4,0,0,0>
-    ("gat", 2_449_029, 126_167_309, 64): 41_987_127_658,       # gat_kernel<16,4>
-    ("gcn", 100_000, 1_000_000, 128): 405_408_528,             # propagate_kernel<32,4,0,0,0>, GCN epilogue
+    ("propagate", 1_000_000, 20_000_000, 64): 2_924_144_576,   # propagate_kernel<16,4,0,0,0>
+    ("gat", 2_449_029, 126_167_309, 64): 27_475_721_024,       # gat_kernel<16,4,2>
+    ("gcn", 100_000, 1_000_000, 128): 405_483_808,             # propagate_kernel<32,4,0,0,0>, GCN epilogue
 }
 
 
@@ -293,7 +293,7 @@ def run_gcn(args, torch, gnn, synth):
                      "xw_roofline": {"bound": "mfma", "achieved": flops / (ms_xw * 1e-3) / 1e12,
                                      "peak": MFMA_FP32_PEAK_TFLOPS, "unit": "TFLOP/s",
                                      "frac": flops / (ms_xw * 1e-3) / 1e12 / MFMA_FP32_PEAK_TFLOPS,
-                                     "hbm_GBs": bytes_xw / (ms_xw * 1e-3) / 1e9, "kernel": "xw_kernel<4,true>"}}
+                                     "hbm_GBs": bytes_xw / (ms_xw * 1e-3) / 1e9, "kernel": "xw_fast_kernel<2,2,2,true>"}}
     if not args.no_cpu_baseline:
         import oracle
         t0 = time.perf_counter()
@@ -329,14 +329,14 @@ def run_gat(args, torch, gnn, synth):
                      wl.name, {"N": n, "E": e, "f_in": f_in, "heads": heads, "ch": ch})
     line["steps"] = steps
     line["roofline"] = hbm_roofline(bytes_att / (ms_att * 1e-3) / 1e9,
-                                    "gat_kernel<16,4> (+ node_scores_kernel, gat_merge_kernel); time = layer - X W",
+                                    "gat_kernel<16,4,2> (+ node_scores_kernel, gat_merge_kernel); time = layer - X W",
                                     MEASURED_TRAFFIC_BYTES.get(("gat", n, e, hc)))
     line["extra"] = {"xw_ms": ms_xw, "attention_ms": ms_att, "B_alg_attention_bytes": bytes_att,
                      "edge_feature_per_s": e * hc / (ms_att * 1e-3), "work_lists": g.work_sizes(),
                      "xw_roofline": {"bound": "mfma", "achieved": flops / (ms_xw * 1e-3) / 1e12,
                                      "peak": MFMA_FP32_PEAK_TFLOPS, "unit": "TFLOP/s",
                                      "frac": flops / (ms_xw * 1e-3) / 1e12 / MFMA_FP32_PEAK_TFLOPS,
-                                     "hbm_GBs": bytes_xw / (ms_xw * 1e-3) / 1e9, "kernel": "xw_kernel<2,true>"}}
+                                     "hbm_GBs": bytes_xw / (ms_xw * 1e-3) / 1e9, "kernel": "xw_fast_kernel<2,2,1,false>"}}
     if not args.no_cpu_baseline:
         import oracle
         es = min(args.cpu_sample_edges // 4, e)        # a prefix of the edge list over a node prefix

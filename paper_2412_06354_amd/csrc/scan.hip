@@ -2,7 +2,8 @@
 // also used for the radix sort's digit offsets and for compacting the work lists).
 //
 // Two levels: every block reduces its tile, one block scans the block sums, every block
-// then scans its tile starting from its offset.  A tile is 256 threads x 8 values.
+// then scans its tile starting from its offset.  A tile is 256 threads x 8 values.  Up to 2048 tiles the
+// middle step is folded into the last one (each block adds up the sums before it); one tile is one kernel.
 #include "gnn_internal.h"
 
 namespace {
@@ -79,10 +80,22 @@ __global__ __launch_bounds__(kThreads) void scan_single_block_kernel(int32_t *__
     }
 }
 
+// OFFSETS: 0 = the tile starts at zero (a one-tile scan), 1 = block_offsets holds the scanned block sums,
+// 2 = block_offsets holds the raw block sums and the block adds up those before its own (at most kTile of them:
+// saves the single-block kernel in between).
+template <int OFFSETS>
 __global__ __launch_bounds__(kThreads) void scan_downsweep_kernel(const int32_t *in, int32_t *out, int64_t n,
                                                                   int64_t n_out,
                                                                   const int32_t *__restrict__ block_offsets)
 {
+    int offset = 0;
+    if constexpr (OFFSETS == 1) offset = block_offsets[blockIdx.x];
+    if constexpr (OFFSETS == 2) {
+        int mine = 0;
+        for (int i = threadIdx.x; i < (int)blockIdx.x; i += kThreads) mine += block_offsets[i];
+        int ignored = block_exclusive_scan(mine, &offset);
+        (void)ignored;
+    }
     const int64_t base = (int64_t)blockIdx.x * kTile + (int64_t)threadIdx.x * kItems;
     int v[kItems];
     int s = 0;
@@ -92,7 +105,7 @@ __global__ __launch_bounds__(kThreads) void scan_downsweep_kernel(const int32_t 
         s += v[i];
     }
     int total;
-    int run = block_offsets[blockIdx.x] + block_exclusive_scan(s, &total);
+    int run = offset + block_exclusive_scan(s, &total);
 #pragma unroll
     for (int i = 0; i < kItems; ++i) {
         if (base + i < n_out) out[base + i] = run;   // position n (if asked for) receives the grand total
@@ -114,11 +127,23 @@ gnn_status gnn_scan_exclusive_i32(const int32_t *d_in, int32_t *d_out, int64_t n
     const int64_t n_out = n + (append_total ? 1 : 0);
     if (n_out == 0) return GNN_OK;
     const int64_t blocks = gnn_div_up(n_out, kTile);
+    if (blocks == 1) {   // one tile: one kernel
+        hipLaunchKernelGGL(scan_downsweep_kernel<0>, dim3(1), dim3(kThreads), 0, stream, d_in, d_out, n, n_out,
+                           (const int32_t *)nullptr);
+        GNN_LAUNCH_CHECK();
+        return GNN_OK;
+    }
     hipLaunchKernelGGL(scan_reduce_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, stream, d_in, n, d_tmp);
     GNN_LAUNCH_CHECK();
+    if (blocks <= kTile) {   // every block adds up the sums of the blocks before it: two kernels
+        hipLaunchKernelGGL(scan_downsweep_kernel<2>, dim3((unsigned)blocks), dim3(kThreads), 0, stream, d_in, d_out, n,
+                           n_out, d_tmp);
+        GNN_LAUNCH_CHECK();
+        return GNN_OK;
+    }
     hipLaunchKernelGGL(scan_single_block_kernel, dim3(1), dim3(kThreads), 0, stream, d_tmp, blocks);
     GNN_LAUNCH_CHECK();
-    hipLaunchKernelGGL(scan_downsweep_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, stream, d_in, d_out, n,
+    hipLaunchKernelGGL(scan_downsweep_kernel<1>, dim3((unsigned)blocks), dim3(kThreads), 0, stream, d_in, d_out, n,
                        n_out, d_tmp);
     GNN_LAUNCH_CHECK();
     return GNN_OK;
