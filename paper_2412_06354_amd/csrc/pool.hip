@@ -2,7 +2,7 @@
 // batch is the block-diagonal union of many small graphs with one graph id per node, ids
 // non-decreasing, so every graph is a contiguous run of node rows.
 //
-// One block per graph: the run's bounds come from two block-wide searches in the sorted ids; the
+// One block per graph: the run's bounds come from two interleaved block-wide searches in the sorted ids; the
 // block's threads are arranged as (node slot, feature lane), node slots stride over the run and
 // are combined through LDS in slot order, so the result does not depend on scheduling.
 #include "gnn_internal.h"
@@ -18,24 +18,39 @@ __device__ __forceinline__ float max_pz(float a, float b)
     return __uint_as_float(__float_as_uint(a) & __float_as_uint(b));
 }
 
-// First index whose value is >= key in the sorted array a[0..n), found by the whole block: every
-// round the 256 threads probe evenly spaced positions of the remaining range and count how many
-// are still below the key, which narrows the range 256-fold (a handful of rounds instead of
-// log2(n) dependent loads).
-__device__ __forceinline__ int block_lower_bound(const int32_t *__restrict__ a, int n, int key)
+// Lower bound (first index whose value is >= key) in the sorted array a[0..n), found by the whole block: every
+// round the 256 threads probe evenly spaced positions of the remaining range and count how many are still below
+// the key, which narrows the range 256-fold (a handful of rounds instead of log2(n) dependent loads).
+// Both ends of graph g's run at once: the lower bounds of g and of g + 1, searched in the same rounds so that
+// the two chains of dependent loads overlap (a block spends most of its time in these searches).
+__device__ __forceinline__ void block_run_bounds(const int32_t *__restrict__ a, int n, int g, int *first, int *last)
 {
-    int lo = 0, hi = n;   // the answer lies in [lo, hi]
-    while (lo < hi) {
-        const int step = (hi - lo + kThreads - 1) / kThreads;
-        const int pos = lo + (int)threadIdx.x * step;
-        const int below = (pos < hi) && (a[pos] < key);
-        const int c = __syncthreads_count(below);   // the array is sorted: exactly probes 0 .. c-1 are below the key
-        if (c == 0) return lo;
-        const int new_hi = min(hi, lo + c * step);  // probe c (if inside) is >= key
-        lo = lo + (c - 1) * step + 1;               // probe c-1 is below the key
-        hi = new_hi;
+    int lo0 = 0, hi0 = n, lo1 = 0, hi1 = n;
+    while (lo0 < hi0 || lo1 < hi1) {   // block-uniform
+        const int step0 = max(1, (hi0 - lo0 + kThreads - 1) / kThreads), step1 = max(1, (hi1 - lo1 + kThreads - 1) / kThreads);
+        const int pos0 = lo0 + (int)threadIdx.x * step0, pos1 = lo1 + (int)threadIdx.x * step1;
+        const int v0 = pos0 < hi0 ? a[pos0] : 0, v1 = pos1 < hi1 ? a[pos1] : 0;   // both loads before either count
+        const int c0 = __syncthreads_count(pos0 < hi0 && v0 < g);
+        const int c1 = __syncthreads_count(pos1 < hi1 && v1 < g + 1);
+        if (lo0 < hi0) {
+            if (c0 == 0) hi0 = lo0;
+            else {
+                const int nh = min(hi0, lo0 + c0 * step0);
+                lo0 = lo0 + (c0 - 1) * step0 + 1;
+                hi0 = nh;
+            }
+        }
+        if (lo1 < hi1) {
+            if (c1 == 0) hi1 = lo1;
+            else {
+                const int nh = min(hi1, lo1 + c1 * step1);
+                lo1 = lo1 + (c1 - 1) * step1 + 1;
+                hi1 = nh;
+            }
+        }
     }
-    return lo;
+    *first = lo0;
+    *last = lo1;
 }
 
 template <bool MAX>
@@ -45,7 +60,8 @@ __global__ __launch_bounds__(kThreads) void pool_kernel(const int32_t *__restric
 {
     __shared__ float part[kThreads];
     const int g = blockIdx.x;
-    const int lo = block_lower_bound(gi, N, g), hi = block_lower_bound(gi, N, g + 1);
+    int lo, hi;
+    block_run_bounds(gi, N, g, &lo, &hi);
     const int fl = threadIdx.x % lanes, slot = threadIdx.x / lanes, slots = kThreads / lanes;
     for (int f0 = 0; f0 < F; f0 += lanes) {
         const int f = f0 + fl;
@@ -78,7 +94,8 @@ __global__ __launch_bounds__(kThreads) void pool_backward_kernel(const int32_t *
                                                                  float *__restrict__ gx)
 {
     const int g = blockIdx.x;
-    const int lo = block_lower_bound(gi, N, g), hi = block_lower_bound(gi, N, g + 1);
+    int lo, hi;
+    block_run_bounds(gi, N, g, &lo, &hi);
     const int cnt = hi - lo;
     if (cnt <= 0) return;   // block-uniform
     const int64_t total = (int64_t)cnt * F;

@@ -490,7 +490,8 @@ def test_propagate_argument_errors(case, gnn):
 def test_dense_xw_matches_numpy(gnn):
     for rows, k, n in ((1000, 128, 128), (777, 100, 64), (130, 37, 50), (5, 8, 200), (4096, 16, 64),
                        (70_000, 128, 128), (500, 300, 128), (300, 520, 40), (900, 200, 64), (257, 64, 33),
-                       (3000, 64, 100), (1500, 128, 36), (640, 100, 20), (333, 12, 4)):
+                       (3000, 64, 100), (1500, 128, 36), (640, 100, 20), (333, 12, 4), (6000, 32, 300),
+                       (150_000, 64, 128)):   # the last two: three column-block pairs; several tiles per wavefront
         x = synth.normal_f32(rows + k, 2, rows * k).reshape(rows, k)
         w = synth.glorot_uniform(n, 4, k, n, (k, n))
         sc = synth.uniform_f32(3, 5, rows, 0.5, 2.0)
