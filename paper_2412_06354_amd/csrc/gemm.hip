@@ -133,14 +133,29 @@ __device__ __forceinline__ void store_tile(const floatx16 (&acc)[NT], int64_t ro
 template <int BN, int KK, int NTHREADS>
 struct WStage {
     static constexpr int G = BN / 4, TOTAL = KK * G, ITERS = (TOTAL + NTHREADS - 1) / NTHREADS;
+    static_assert(KK % 16 == 0 && G % 4 == 0, "staging blocks of 16 k-values x 4 column groups");
     float4 v[ITERS];
+
+    // Which 128-bit group (row kk of W, four columns from c) a staging index stands for.  64 consecutive
+    // indices -- a wavefront -- cover 16 consecutive rows x 4 neighbouring column groups: the global reads come in
+    // 64-byte pieces, and the four transposed LDS writes of a pass spread over all banks (16 k-values of a column
+    // are 16 consecutive words; the neighbouring column groups land in other bank groups through the swizzle),
+    // where one row x 64 column groups would put every lane of a write into the same bank.
+    static __device__ __forceinline__ void decode(int idx, int &kk, int &c)
+    {
+        constexpr int KBLOCKS = KK / 16;
+        const int blk = idx >> 6, l = idx & 63;
+        kk = (blk % KBLOCKS) * 16 + (l & 15);
+        c = ((blk / KBLOCKS) * 4 + (l >> 4)) * 4;
+    }
 
     __device__ __forceinline__ void load(const float *__restrict__ w, int k, int n, int k0, int n0)
     {
 #pragma unroll
         for (int it = 0; it < ITERS; ++it) {
             const int idx = min((int)threadIdx.x + it * NTHREADS, TOTAL - 1);   // a last, partial pass loads something valid
-            const int kk = idx / G, c = (idx - kk * G) * 4;
+            int kk, c;
+            decode(idx, kk, c);
             const bool inside = k0 + kk < k && n0 + c < n;
             const float *p = inside ? w + (int64_t)(k0 + kk) * n + n0 + c : w;
             v[it] = *reinterpret_cast<const float4 *>(p);
@@ -152,7 +167,8 @@ struct WStage {
 #pragma unroll
         for (int it = 0; it < ITERS; ++it) {
             const int idx = threadIdx.x + it * NTHREADS;
-            const int kk = idx / G, c = (idx - kk * G) * 4;
+            int kk, c;
+            decode(min(idx, TOTAL - 1), kk, c);
             const bool inside = k0 + kk < k && n0 + c < n;
             if (idx < TOTAL) {
                 ws[w_lds_index(c + 0, kk, KK)] = inside ? v[it].x : 0.0f;
