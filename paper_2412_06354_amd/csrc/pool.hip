@@ -10,6 +10,7 @@
 namespace {
 
 constexpr int kThreads = 256;
+constexpr int kSmallGraphNodes = 128;   // average nodes per graph up to which a wavefront takes a graph
 
 __device__ __forceinline__ float max_pz(float a, float b)
 {
@@ -87,6 +88,66 @@ __global__ __launch_bounds__(kThreads) void pool_kernel(const int32_t *__restric
     }
 }
 
+// Batches of small graphs: one wavefront per graph (four graphs per block), no block-wide barriers.  The run's
+// bounds come from the same interleaved search with 64 probes per round; lanes are (node slot, feature lane),
+// node slots stride over the run and are combined by a fixed xor-shuffle tree.
+template <bool MAX>
+__global__ __launch_bounds__(kThreads) void pool_wave_kernel(const int32_t *__restrict__ gi, int32_t N,
+                                                             const float *__restrict__ x, int32_t F,
+                                                             int32_t lanes /* power of two <= 64 */, int mean,
+                                                             int32_t num_graphs, float *__restrict__ out)
+{
+    const int lane = threadIdx.x & 63;
+    const int g = blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
+    if (g >= num_graphs) return;   // wavefront-uniform
+    int lo0 = 0, hi0 = N, lo1 = 0, hi1 = N;
+    while (lo0 < hi0 || lo1 < hi1) {   // wavefront-uniform
+        const int step0 = max(1, (hi0 - lo0 + 63) / 64), step1 = max(1, (hi1 - lo1 + 63) / 64);
+        const int pos0 = lo0 + lane * step0, pos1 = lo1 + lane * step1;
+        const int v0 = pos0 < hi0 ? gi[pos0] : 0, v1 = pos1 < hi1 ? gi[pos1] : 0;
+        const int c0 = __popcll(__ballot(pos0 < hi0 && v0 < g));
+        const int c1 = __popcll(__ballot(pos1 < hi1 && v1 < g + 1));
+        if (lo0 < hi0) {
+            if (c0 == 0) hi0 = lo0;
+            else {
+                const int nh = min(hi0, lo0 + c0 * step0);
+                lo0 = lo0 + (c0 - 1) * step0 + 1;
+                hi0 = nh;
+            }
+        }
+        if (lo1 < hi1) {
+            if (c1 == 0) hi1 = lo1;
+            else {
+                const int nh = min(hi1, lo1 + c1 * step1);
+                lo1 = lo1 + (c1 - 1) * step1 + 1;
+                hi1 = nh;
+            }
+        }
+    }
+    const int lo = lo0, hi = lo1, cnt = hi - lo;
+    const int fl = lane % lanes, slot = lane / lanes, slots = 64 / lanes;
+    for (int f0 = 0; f0 < F; f0 += lanes) {
+        const int f = f0 + fl;
+        float acc = MAX ? -INFINITY : 0.0f;
+        if (f < F) {
+#pragma unroll 4
+            for (int i = lo + slot; i < hi; i += slots) {
+                const float v = x[(int64_t)i * F + f];
+                acc = MAX ? max_pz(acc, v) : acc + v;
+            }
+        }
+        for (int off = lanes; off < 64; off <<= 1) {
+            const float other = __shfl_xor(acc, off, 64);
+            acc = MAX ? max_pz(acc, other) : acc + other;
+        }
+        if (slot == 0 && f < F) {
+            if (cnt == 0) acc = 0.0f;
+            if (mean && cnt > 0) acc = acc / (float)cnt;
+            out[(int64_t)g * F + f] = acc;
+        }
+    }
+}
+
 // Backward of sum / mean pooling: every node of graph g receives gout[g,:] (divided by the node count for
 // the mean).  One block per graph, same run search as the forward kernel; rows are written coalesced.
 __global__ __launch_bounds__(kThreads) void pool_backward_kernel(const int32_t *__restrict__ gi, int32_t N,
@@ -131,15 +192,29 @@ extern "C" gnn_status gnn_graph_pool(const int32_t *d_graph_indicator, int32_t n
     if (num_nodes < 0 || num_graphs <= 0 || feat_dim <= 0) return GNN_ERR_BAD_SIZE;
     if (aggr != GNN_AGGR_SUM && aggr != GNN_AGGR_MEAN && aggr != GNN_AGGR_MAX) return GNN_ERR_BAD_SIZE;
     if (num_nodes > 0 && (!d_graph_indicator || !d_x)) return GNN_ERR_NULL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int mean = aggr == GNN_AGGR_MEAN ? 1 : 0;
+    if ((int64_t)num_nodes <= (int64_t)num_graphs * kSmallGraphNodes) {   // small graphs on average: a wavefront each
+        int lanes = 1;
+        while (lanes < feat_dim && lanes < 64) lanes <<= 1;
+        const dim3 grid((unsigned)gnn_div_up(num_graphs, kThreads / 64));
+        if (aggr == GNN_AGGR_MAX)
+            hipLaunchKernelGGL(pool_wave_kernel<true>, grid, dim3(kThreads), 0, s, d_graph_indicator, num_nodes, d_x,
+                               feat_dim, lanes, 0, num_graphs, d_out);
+        else
+            hipLaunchKernelGGL(pool_wave_kernel<false>, grid, dim3(kThreads), 0, s, d_graph_indicator, num_nodes, d_x,
+                               feat_dim, lanes, mean, num_graphs, d_out);
+        GNN_LAUNCH_CHECK();
+        return GNN_OK;
+    }
     int lanes = 1;
     while (lanes < feat_dim && lanes < kThreads) lanes <<= 1;
-    hipStream_t s = static_cast<hipStream_t>(stream);
     if (aggr == GNN_AGGR_MAX)
         hipLaunchKernelGGL(pool_kernel<true>, dim3((unsigned)num_graphs), dim3(kThreads), 0, s, d_graph_indicator,
                            num_nodes, d_x, feat_dim, lanes, 0, d_out);
     else
         hipLaunchKernelGGL(pool_kernel<false>, dim3((unsigned)num_graphs), dim3(kThreads), 0, s, d_graph_indicator,
-                           num_nodes, d_x, feat_dim, lanes, aggr == GNN_AGGR_MEAN ? 1 : 0, d_out);
+                           num_nodes, d_x, feat_dim, lanes, mean, d_out);
     GNN_LAUNCH_CHECK();
     return GNN_OK;
 }

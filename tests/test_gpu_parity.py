@@ -930,6 +930,16 @@ def test_gin_and_pool_batched(gnn):
     got = host(gnn.graph_pool(gi, ng + 3, dev(x7), AGGR_MEAN))
     np.testing.assert_allclose(got, ref, rtol=1e-5, atol=1e-6)
     assert (got[ng:] == 0).all()
+    # wide and single-column features on the same small graphs (several feature passes per wavefront; 64 node slots)
+    for f in (200, 1):
+        xf = synth.normal_f32(5, f, n * f).reshape(n, f)
+        for aggr in (AGGR_SUM, AGGR_MEAN, AGGR_MAX):
+            ref, sabs = oracle.graph_pool(wl.graph_indicator, ng, xf, aggr, with_sabs=True)
+            got = host(gnn.graph_pool(gi, ng, dev(xf), aggr))
+            if aggr == AGGR_MAX:
+                np.testing.assert_array_equal(got, ref)
+            else:
+                assert_close_sabs(got, ref, sabs, what=f"pool F={f} aggr={aggr}")
     g.close()
 
 
