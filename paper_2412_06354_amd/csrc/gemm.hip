@@ -30,6 +30,13 @@ constexpr int kRowsPerWave = 32;
 constexpr int kRowsPerBlock = 4 * kRowsPerWave;
 constexpr int kSlab = 64;             // k-values per X register buffer / per staged W slab in the fallback
 
+// What the store does after the product: optional per-row scale, per-column bias, relu (in that order).
+struct XwEpilogue {
+    const float *row_scale = nullptr;
+    const float *bias = nullptr;
+    int relu = 0;
+};
+
 struct AFrag {
     float v[8][4];
 };
@@ -107,11 +114,12 @@ __device__ __forceinline__ void mfma_subslab(floatx16 (&acc)[NT], const AFrag &a
     }
 }
 
-// Guarded store of the (transposed) accumulator tiles, for ragged edges.
+// Guarded store of the (transposed) accumulator tiles, for ragged edges.  Epilogue: optional per-row scale,
+// then optional per-column bias, then optional relu.
 template <int NT>
 __device__ __forceinline__ void store_tile(const floatx16 (&acc)[NT], int64_t row0, int64_t rows, int n0, int n,
                                            int r, int half, const float *__restrict__ row_scale,
-                                           float *__restrict__ z)
+                                           const float *__restrict__ bias, int relu, float *__restrict__ z)
 {
     const int64_t row = row0 + r;
     if (row >= rows) return;
@@ -121,7 +129,12 @@ __device__ __forceinline__ void store_tile(const floatx16 (&acc)[NT], int64_t ro
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int col = n0 + t * 32 + 8 * (v / 4) + 4 * half + (v % 4);
-            if (col < n) z[row * n + col] = acc[t][v] * sc;
+            if (col < n) {
+                float o = acc[t][v] * sc;
+                if (bias) o += bias[col];
+                if (relu) o = fmaxf(o, 0.0f);
+                z[row * n + col] = o;
+            }
         }
 }
 
@@ -211,7 +224,8 @@ __device__ __forceinline__ void stage_w(float *ws, const float *__restrict__ w, 
 // once for NCB * BN output columns.
 template <int NT, int NSUB, int NCB>
 __device__ __forceinline__ void fast_wave_tile(const AFrag (&a)[NSUB], const float *ws, float sc, int64_t row,
-                                               int64_t rows, int n, int n0, int r, int half, float *__restrict__ z)
+                                               int64_t rows, int n, int n0, int r, int half,
+                                               const float *__restrict__ bias, int relu, float *__restrict__ z)
 {
     constexpr int BN = NT * 32;
     constexpr int KP = NSUB * kSlab;
@@ -233,10 +247,16 @@ __device__ __forceinline__ void fast_wave_tile(const AFrag (&a)[NSUB], const flo
             for (int t = 0; t < NT; ++t)
 #pragma unroll
                 for (int g = 0; g < 4; ++g)
-                    if (t * 32 + 8 * g < ncols)
-                        *reinterpret_cast<float4 *>(zrow + t * 32 + 8 * g) =
-                            make_float4(acc[t][4 * g] * sc, acc[t][4 * g + 1] * sc, acc[t][4 * g + 2] * sc,
-                                        acc[t][4 * g + 3] * sc);
+                    if (t * 32 + 8 * g < ncols) {
+                        float4 o = make_float4(acc[t][4 * g] * sc, acc[t][4 * g + 1] * sc, acc[t][4 * g + 2] * sc,
+                                               acc[t][4 * g + 3] * sc);
+                        if (bias) {   // n % 4 == 0 and the group lies inside: four bias values are there
+                            const float *bp = bias + n0 + cb * BN + 4 * half + t * 32 + 8 * g;
+                            o.x += bp[0]; o.y += bp[1]; o.z += bp[2]; o.w += bp[3];
+                        }
+                        if (relu) o = make_float4(fmaxf(o.x, 0.0f), fmaxf(o.y, 0.0f), fmaxf(o.z, 0.0f), fmaxf(o.w, 0.0f));
+                        *reinterpret_cast<float4 *>(zrow + t * 32 + 8 * g) = o;
+                    }
         }
     }
 }
@@ -245,6 +265,7 @@ template <int NT, int NSUB, int NCB, bool SCALED>
 __global__ __launch_bounds__(kFastThreads) void xw_fast_kernel(const float *__restrict__ x, int k,
                                                                const float *__restrict__ w, int n,
                                                                const float *__restrict__ row_scale,
+                                                               const float *__restrict__ bias, int relu,
                                                                float *__restrict__ z, int64_t rows)
 {
     constexpr int BN = NT * 32;
@@ -284,21 +305,22 @@ __global__ __launch_bounds__(kFastThreads) void xw_fast_kernel(const float *__re
     __syncthreads();
 
     // From here on the wavefronts are independent.  The first tile (already loaded) is peeled off the loop.
-    if (wt < num_wave_tiles) fast_wave_tile<NT, NSUB, NCB>(a, ws, sc, row, rows, n, n0, r, half, z);
+    if (wt < num_wave_tiles) fast_wave_tile<NT, NSUB, NCB>(a, ws, sc, row, rows, n, n0, r, half, bias, relu, z);
     for (wt += wt_stride; wt < num_wave_tiles; wt += wt_stride) {
         row = wt * kRowsPerWave + r;
 #pragma unroll
         for (int sub = 0; sub < NSUB; ++sub) load_a<true>(a[sub], x, rows, k, row, sub * kSlab, half);
         if constexpr (SCALED) sc = row_scale[min(row, rows - 1)];
-        fast_wave_tile<NT, NSUB, NCB>(a, ws, sc, row, rows, n, n0, r, half, z);
+        fast_wave_tile<NT, NSUB, NCB>(a, ws, sc, row, rows, n, n0, r, half, bias, relu, z);
     }
 }
 
 template <int NT, bool VEC4>
 __global__ __launch_bounds__(kThreads) void xw_slab_kernel(const float *__restrict__ x, int64_t rows, int k,
                                                            const float *__restrict__ w, int n,
-                                                           const float *__restrict__ row_scale, float *__restrict__ z,
-                                                           int w_vec4, int64_t first_row_tile)
+                                                           const float *__restrict__ row_scale,
+                                                           const float *__restrict__ bias, int relu,
+                                                           float *__restrict__ z, int w_vec4, int64_t first_row_tile)
 {
     constexpr int BN = NT * 32;
     __shared__ __align__(16) float ws[kSlab * BN];
@@ -321,7 +343,7 @@ __global__ __launch_bounds__(kThreads) void xw_slab_kernel(const float *__restri
         __syncthreads();
         mfma_subslab<NT>(acc, a, ws, kSlab, 32 * half, r);
     }
-    store_tile<NT>(acc, row0, rows, n0, n, r, half, row_scale, z);
+    store_tile<NT>(acc, row0, rows, n0, n, r, half, row_scale, bias, relu, z);
 }
 
 int device_cu_count()
@@ -338,24 +360,24 @@ int device_cu_count()
 }
 
 template <int NT>
-gnn_status launch_general(const float *d_x, int64_t rows, int k, const float *d_w, int n, const float *d_row_scale,
+gnn_status launch_general(const float *d_x, int64_t rows, int k, const float *d_w, int n, const XwEpilogue &ep,
                           float *d_z, bool x_vec4, bool w_vec4, int64_t first_row_tile, hipStream_t s)
 {
     const int64_t row_tiles = gnn_div_up(rows, kRowsPerBlock) - first_row_tile;
     if (row_tiles <= 0) return GNN_OK;
     const dim3 grid((unsigned)row_tiles, (unsigned)gnn_div_up(n, NT * 32));
     if (x_vec4)
-        hipLaunchKernelGGL((xw_slab_kernel<NT, true>), grid, dim3(kThreads), 0, s, d_x, rows, k, d_w, n, d_row_scale,
-                           d_z, w_vec4 ? 1 : 0, first_row_tile);
+        hipLaunchKernelGGL((xw_slab_kernel<NT, true>), grid, dim3(kThreads), 0, s, d_x, rows, k, d_w, n, ep.row_scale,
+                           ep.bias, ep.relu, d_z, w_vec4 ? 1 : 0, first_row_tile);
     else
-        hipLaunchKernelGGL((xw_slab_kernel<NT, false>), grid, dim3(kThreads), 0, s, d_x, rows, k, d_w, n, d_row_scale,
-                           d_z, w_vec4 ? 1 : 0, first_row_tile);
+        hipLaunchKernelGGL((xw_slab_kernel<NT, false>), grid, dim3(kThreads), 0, s, d_x, rows, k, d_w, n, ep.row_scale,
+                           ep.bias, ep.relu, d_z, w_vec4 ? 1 : 0, first_row_tile);
     GNN_LAUNCH_CHECK();
     return GNN_OK;
 }
 
 template <int NT, int NSUB, int NCB>
-gnn_status launch_fast(const float *d_x, int64_t rows, int k, const float *d_w, int n, const float *d_row_scale,
+gnn_status launch_fast(const float *d_x, int64_t rows, int k, const float *d_w, int n, const XwEpilogue &ep,
                        float *d_z, hipStream_t s)
 {
     constexpr int BN = NT * 32 * NCB;   // output columns per block
@@ -366,43 +388,46 @@ gnn_status launch_fast(const float *d_x, int64_t rows, int k, const float *d_w, 
     const int col_blocks = (int)gnn_div_up(n, BN);
     const int64_t blocks = std::max<int64_t>(1, std::min<int64_t>(device_cu_count() / col_blocks, wave_tiles));
     const dim3 grid((unsigned)blocks, (unsigned)col_blocks);
-    if (d_row_scale)
+    if (ep.row_scale)
         hipLaunchKernelGGL((xw_fast_kernel<NT, NSUB, NCB, true>), grid, dim3(kFastThreads), lds, s, d_x, k, d_w, n,
-                           d_row_scale, d_z, rows);
+                           ep.row_scale, ep.bias, ep.relu, d_z, rows);
     else
         hipLaunchKernelGGL((xw_fast_kernel<NT, NSUB, NCB, false>), grid, dim3(kFastThreads), lds, s, d_x, k, d_w, n,
-                           d_row_scale, d_z, rows);
+                           ep.row_scale, ep.bias, ep.relu, d_z, rows);
     GNN_LAUNCH_CHECK();
     return GNN_OK;
 }
 
 // Fast path: column tiles of 32 (n <= 32) or 64, two of them per block where the matrix is wider than one.
 template <int NT>
-gnn_status launch_fast_for_k(const float *d_x, int64_t rows, int k, const float *d_w, int n, const float *d_row_scale,
+gnn_status launch_fast_for_k(const float *d_x, int64_t rows, int k, const float *d_w, int n, const XwEpilogue &ep,
                              float *d_z, hipStream_t s)
 {
     if (n > NT * 32) {
-        if (k <= kSlab) return launch_fast<NT, 1, 2>(d_x, rows, k, d_w, n, d_row_scale, d_z, s);
-        return launch_fast<NT, 2, 2>(d_x, rows, k, d_w, n, d_row_scale, d_z, s);
+        if (k <= kSlab) return launch_fast<NT, 1, 2>(d_x, rows, k, d_w, n, ep, d_z, s);
+        return launch_fast<NT, 2, 2>(d_x, rows, k, d_w, n, ep, d_z, s);
     }
-    if (k <= kSlab) return launch_fast<NT, 1, 1>(d_x, rows, k, d_w, n, d_row_scale, d_z, s);
-    return launch_fast<NT, 2, 1>(d_x, rows, k, d_w, n, d_row_scale, d_z, s);
+    if (k <= kSlab) return launch_fast<NT, 1, 1>(d_x, rows, k, d_w, n, ep, d_z, s);
+    return launch_fast<NT, 2, 1>(d_x, rows, k, d_w, n, ep, d_z, s);
 }
 
 }  // namespace
 
-extern "C" gnn_status gnn_dense_xw(const float *d_x, int64_t rows, int32_t k, const float *d_w, int32_t n,
-                                   const float *d_row_scale, float *d_z, void *stream)
+gnn_status gnn_launch_xw(const float *d_x, int64_t rows, int32_t k, const float *d_w, int32_t n,
+                         const float *d_row_scale, const float *d_bias, bool relu, float *d_z, hipStream_t s)
 {
     if (!d_x || !d_w || !d_z) return GNN_ERR_NULL;
     if (rows < 0 || k <= 0 || n <= 0) return GNN_ERR_BAD_SIZE;
     if (rows == 0) return GNN_OK;
-    hipStream_t s = static_cast<hipStream_t>(stream);
+    XwEpilogue ep;
+    ep.row_scale = d_row_scale;
+    ep.bias = d_bias;
+    ep.relu = relu ? 1 : 0;
     const bool x_vec4 = (k % 4 == 0) && ((reinterpret_cast<uintptr_t>(d_x) & 15u) == 0);
     const bool w_vec4 = (n % 4 == 0) && ((reinterpret_cast<uintptr_t>(d_w) & 15u) == 0);
     if (x_vec4 && w_vec4 && k <= 2 * kSlab) {   // w_vec4 implies n % 4 == 0
-        if (n <= 32) return launch_fast_for_k<1>(d_x, rows, k, d_w, n, d_row_scale, d_z, s);
-        return launch_fast_for_k<2>(d_x, rows, k, d_w, n, d_row_scale, d_z, s);
+        if (n <= 32) return launch_fast_for_k<1>(d_x, rows, k, d_w, n, ep, d_z, s);
+        return launch_fast_for_k<2>(d_x, rows, k, d_w, n, ep, d_z, s);
     }
     // General kernel.  Column tile: 64 or 32 if it divides n, else 128 wide when n is large enough, else the
     // smallest multiple of 32 covering n.
@@ -410,9 +435,15 @@ extern "C" gnn_status gnn_dense_xw(const float *d_x, int64_t rows, int32_t k, co
     if (n % 64 == 0) nt = 2;
     else if (n % 32 == 0) nt = 1;
     switch (nt) {
-    case 1: return launch_general<1>(d_x, rows, k, d_w, n, d_row_scale, d_z, x_vec4, w_vec4, 0, s);
-    case 2: return launch_general<2>(d_x, rows, k, d_w, n, d_row_scale, d_z, x_vec4, w_vec4, 0, s);
-    case 3: return launch_general<3>(d_x, rows, k, d_w, n, d_row_scale, d_z, x_vec4, w_vec4, 0, s);
-    default: return launch_general<4>(d_x, rows, k, d_w, n, d_row_scale, d_z, x_vec4, w_vec4, 0, s);
+    case 1: return launch_general<1>(d_x, rows, k, d_w, n, ep, d_z, x_vec4, w_vec4, 0, s);
+    case 2: return launch_general<2>(d_x, rows, k, d_w, n, ep, d_z, x_vec4, w_vec4, 0, s);
+    case 3: return launch_general<3>(d_x, rows, k, d_w, n, ep, d_z, x_vec4, w_vec4, 0, s);
+    default: return launch_general<4>(d_x, rows, k, d_w, n, ep, d_z, x_vec4, w_vec4, 0, s);
     }
+}
+
+extern "C" gnn_status gnn_dense_xw(const float *d_x, int64_t rows, int32_t k, const float *d_w, int32_t n,
+                                   const float *d_row_scale, float *d_z, void *stream)
+{
+    return gnn_launch_xw(d_x, rows, k, d_w, n, d_row_scale, nullptr, false, d_z, static_cast<hipStream_t>(stream));
 }

@@ -144,6 +144,9 @@ gnn_status gnn_launch_xty(const float *d_x, const float *d_y, int64_t rows, int 
 gnn_status gnn_launch_sum_partials(const float *d_partial, int chunks, int64_t elems, float *d_out,
                                    hipStream_t stream);
 // wt[cols x rows] = w[rows x cols]^T
+// Z = X W with the store's epilogue: optional per-row scale, then per-column bias, then relu (gemm.hip).
+gnn_status gnn_launch_xw(const float *d_x, int64_t rows, int32_t k, const float *d_w, int32_t n,
+                         const float *d_row_scale, const float *d_bias, bool relu, float *d_z, hipStream_t s);
 gnn_status gnn_launch_transpose(const float *d_w, int rows, int cols, float *d_wt, hipStream_t stream);
 // sl[i,hd] = <a_src[hd,:], h[i,hd,:]>, sr[i,hd] = <a_dst[hd,:], h[i,hd,:]>  (gatconv.hip)
 gnn_status gnn_launch_node_scores(const float *d_h, int64_t N, int heads, int ch, const float *d_a_src,

@@ -123,19 +123,6 @@ __global__ __launch_bounds__(kThreads) void normalise_rows_kernel(const float *_
     }
 }
 
-// z = act(z + bias), in place
-__global__ __launch_bounds__(kThreads) void bias_activation_kernel(float *__restrict__ z, int64_t rows, int n,
-                                                                   const float *__restrict__ bias, int relu)
-{
-    const int64_t total = rows * n;
-    const int64_t stride = (int64_t)gridDim.x * kThreads;
-    for (int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x; idx < total; idx += stride) {
-        float v = z[idx] + (bias ? bias[idx % n] : 0.0f);
-        if (relu) v = fmaxf(v, 0.0f);
-        z[idx] = v;
-    }
-}
-
 size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
 
 struct ChainLayout {
@@ -207,13 +194,9 @@ gnn_status gnn_dense(const float *d_x, int64_t rows, int32_t k, const float *d_w
                      gnn_activation act, float *d_out, void *stream)
 {
     if (act != GNN_ACT_NONE && act != GNN_ACT_RELU) return GNN_ERR_BAD_SIZE;
-    GNN_TRY(gnn_dense_xw(d_x, rows, k, d_w, n, nullptr, d_out, stream));
-    if (rows > 0 && (d_bias || act == GNN_ACT_RELU)) {
-        const int blocks = (int)std::min<int64_t>(gnn_div_up(rows * n, kThreads), 256 * 64);
-        hipLaunchKernelGGL(bias_activation_kernel, dim3(blocks), dim3(kThreads), 0, static_cast<hipStream_t>(stream),
-                           d_out, rows, n, d_bias, act == GNN_ACT_RELU ? 1 : 0);
-        GNN_LAUNCH_CHECK();
-    }
+    // bias and activation ride in the product's store
+    GNN_TRY(gnn_launch_xw(d_x, rows, k, d_w, n, nullptr, d_bias, act == GNN_ACT_RELU, d_out,
+                          static_cast<hipStream_t>(stream)));
     return GNN_OK;
 }
 
