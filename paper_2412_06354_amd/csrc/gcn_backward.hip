@@ -150,30 +150,39 @@ __global__ __launch_bounds__(kThreads) void xty_partial_kernel(const float *__re
     }
 }
 
-// out[q] = sum over chunks of partial[chunk][q], in a fixed order: a block owns 64 elements, its four
-// thread rows take the chunks round-robin (eight loads in flight each) and are folded through LDS.
-__global__ __launch_bounds__(kThreads) void sum_partials_kernel(const float *__restrict__ partial, int chunks,
-                                                                int64_t elems, float factor, float *__restrict__ out)
+// out[q] = factor * sum over chunks of partial[chunk][q], in a fixed order: a block owns 64 elements, its SLICES
+// thread rows take the chunks round-robin (eight loads in flight each) and are folded through LDS in slice order.
+// SLICES = 16 where there are few elements (few blocks) and many chunks: the chain of dependent adds is what
+// takes the time there.
+template <int SLICES>
+__global__ __launch_bounds__(64 * SLICES) void sum_partials_kernel(const float *__restrict__ partial, int chunks,
+                                                                   int64_t elems, float factor, float *__restrict__ out)
 {
-    __shared__ float fold[4][64];
+    __shared__ float fold[SLICES][64];
     const int lane = threadIdx.x & 63, slice = threadIdx.x >> 6;
     const int64_t q = (int64_t)blockIdx.x * 64 + lane;
     float s = 0.0f;
     if (q < elems) {
         int ch = slice;
-        for (; ch + 28 < chunks; ch += 32) {
+        for (; ch + 7 * SLICES < chunks; ch += 8 * SLICES) {
             float v[8];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) v[u] = partial[(int64_t)(ch + 4 * u) * elems + q];
+            for (int u = 0; u < 8; ++u) v[u] = partial[(int64_t)(ch + SLICES * u) * elems + q];
 #pragma unroll
             for (int u = 0; u < 8; ++u) s += v[u];
         }
-        for (; ch < chunks; ch += 4) s += partial[(int64_t)ch * elems + q];
+        for (; ch < chunks; ch += SLICES) s += partial[(int64_t)ch * elems + q];
     }
     fold[slice][lane] = s;
     __syncthreads();
     if (slice == 0 && q < elems) {
-        const float t = (fold[0][lane] + fold[1][lane]) + (fold[2][lane] + fold[3][lane]);
+        float t = 0.0f;
+        if constexpr (SLICES == 4) {
+            t = (fold[0][lane] + fold[1][lane]) + (fold[2][lane] + fold[3][lane]);
+        } else {
+#pragma unroll
+            for (int k = 0; k < SLICES; ++k) t += fold[k][lane];
+        }
         out[q] = factor == 1.0f ? t : t * factor;
     }
 }
@@ -214,8 +223,11 @@ gnn_status gnn_launch_sum_partials_scaled(const float *d_partial, int chunks, in
                                           float *d_out, hipStream_t s)
 {
     if (elems <= 0) return GNN_OK;
-    hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)gnn_div_up(elems, 64)), dim3(kThreads), 0, s, d_partial,
-                       chunks, elems, factor, d_out);
+    const dim3 grid((unsigned)gnn_div_up(elems, 64));
+    if (elems <= 4096 && chunks >= 64)
+        hipLaunchKernelGGL(sum_partials_kernel<16>, grid, dim3(64 * 16), 0, s, d_partial, chunks, elems, factor, d_out);
+    else
+        hipLaunchKernelGGL(sum_partials_kernel<4>, grid, dim3(64 * 4), 0, s, d_partial, chunks, elems, factor, d_out);
     GNN_LAUNCH_CHECK();
     return GNN_OK;
 }

@@ -1,12 +1,13 @@
 // The dense-side layers of the paper's example model (section 3, "Training Example":
 // GNNChain(GCNConv(16 => 64), BatchNorm(64), relu, GCNConv(64 => 64, relu), GlobalPool(mean),
 // Dense(64, 1))) and the chain itself as one call:
-//   * batch normalisation across the node dimension, with batch statistics (two passes: mean, then the
-//     mean of squared deviations -- no cancellation) or stored ones, optional relu fused;
+//   * batch normalisation across the node dimension, with batch statistics (one pass over the rows with running
+//     (mean, squared-deviation) pairs that merge exactly -- no cancellation; few rows: two passes in one launch)
+//     or stored ones, optional relu fused;
 //   * a dense layer act(X W + b) on the MFMA projection kernel;
 //   * the forward chain, which only sequences entry points of this library on the caller's stream.
-// Column statistics use the two-stage scheme of the backward passes: per-chunk partial sums,
-// then a fixed-order sum over chunks (deterministic, no atomics).
+// Column statistics use the two-stage scheme of the backward passes: per-chunk partial results,
+// then a fixed-order merge over chunks (deterministic, no atomics).
 #include "gnn_internal.h"
 
 #include <algorithm>
@@ -15,43 +16,93 @@ namespace {
 
 constexpr int kThreads = 256;
 
-// partial[chunk][f] = sum over the chunk's rows of (x[row,f] - centre[f])^POW   (centre may be NULL = 0)
-template <int POW>
-__global__ __launch_bounds__(kThreads) void column_moment_partial_kernel(const float *__restrict__ x, int64_t N,
-                                                                         int F, const float *__restrict__ centre,
-                                                                         int64_t rows_per_chunk,
-                                                                         float *__restrict__ partial)
+// One pass over x for both statistics.  Running (count, mean, sum of squared deviations) per thread in the
+// single-pass form that does not cancel (each value updates the mean and adds (x - old mean)(x - new mean)); two
+// such triples over disjoint row sets merge exactly:
+//     n = na + nb,  delta = mb - ma,  m = ma + delta nb / n,  q = qa + qb + delta^2 na nb / n.
+// Threads, then chunks, are merged in a fixed order: deterministic, and x is read once instead of twice.
+struct Moments {
+    float n, m, q;
+};
+
+__device__ __forceinline__ void moments_add(Moments &a, float v)
 {
-    __shared__ float fold[kThreads];
+    a.n += 1.0f;
+    const float d = v - a.m;
+    a.m += d * __builtin_amdgcn_rcpf(a.n);
+    a.q = fmaf(d, v - a.m, a.q);
+}
+
+__device__ __forceinline__ void moments_merge(Moments &a, const Moments &b)
+{
+    if (b.n == 0.0f) return;
+    const float n = a.n + b.n, delta = b.m - a.m, w = b.n / n;
+    a.m = fmaf(delta, w, a.m);
+    a.q = a.q + b.q + delta * delta * (a.n * w);
+    a.n = n;
+}
+
+// part_m[chunk][f], part_q[chunk][f]: mean and sum of squared deviations of the chunk's rows (the count follows from
+// the chunk's bounds).
+__global__ __launch_bounds__(kThreads) void column_moments_partial_kernel(const float *__restrict__ x, int64_t N, int F,
+                                                                          int64_t rows_per_chunk,
+                                                                          float *__restrict__ part_m,
+                                                                          float *__restrict__ part_q)
+{
+    __shared__ float fn[kThreads], fm[kThreads], fq[kThreads];
     const int cw = min(F, kThreads), slices = kThreads / cw;
     const int rs = threadIdx.x / cw, c0 = threadIdx.x % cw;
     const int64_t r0 = (int64_t)blockIdx.x * rows_per_chunk, r1 = min(N, r0 + rows_per_chunk);
     for (int cbase = 0; cbase < F; cbase += cw) {
         const int col = cbase + c0;
-        float s[2] = {0.0f, 0.0f};   // two interleaved running sums
+        Moments a{0.0f, 0.0f, 0.0f};
         if (rs < slices && col < F) {
-            const float mu = centre ? centre[col] : 0.0f;
-            int64_t row = r0 + rs;
-            for (; row + slices < r1; row += 2 * slices) {
-#pragma unroll
-                for (int u = 0; u < 2; ++u) {
-                    const float d = x[(row + u * slices) * F + col] - mu;
-                    s[u] += POW == 2 ? d * d : d;
-                }
-            }
-            if (row < r1) {
-                const float d = x[row * F + col] - mu;
-                s[0] += POW == 2 ? d * d : d;
-            }
+#pragma unroll 4
+            for (int64_t row = r0 + rs; row < r1; row += slices) moments_add(a, x[row * F + col]);
         }
-        fold[threadIdx.x] = s[0] + s[1];
+        fn[threadIdx.x] = a.n;
+        fm[threadIdx.x] = a.m;
+        fq[threadIdx.x] = a.q;
         __syncthreads();
         if (rs == 0 && col < F) {
-            float t = 0.0f;
-            for (int q = 0; q < slices; ++q) t += fold[q * cw + c0];
-            partial[(int64_t)blockIdx.x * F + col] = t;
+            for (int s = 1; s < slices; ++s) moments_merge(a, Moments{fn[s * cw + c0], fm[s * cw + c0], fq[s * cw + c0]});
+            part_m[(int64_t)blockIdx.x * F + col] = a.m;
+            part_q[(int64_t)blockIdx.x * F + col] = a.q;
         }
         __syncthreads();
+    }
+}
+
+// mean[f], var[f] (biased) from the chunks' pairs: a block owns 64 columns, its 16 thread rows take the chunks
+// round-robin and are merged in slice order.
+constexpr int kMergeSlices = 16;
+
+__global__ __launch_bounds__(64 * kMergeSlices) void column_moments_merge_kernel(const float *__restrict__ part_m,
+                                                                                 const float *__restrict__ part_q,
+                                                                                 int chunks, int64_t N,
+                                                                                 int64_t rows_per_chunk, int F,
+                                                                                 float *__restrict__ mean,
+                                                                                 float *__restrict__ var)
+{
+    __shared__ float fn[kMergeSlices][64], fm[kMergeSlices][64], fq[kMergeSlices][64];
+    const int lane = threadIdx.x & 63, slice = threadIdx.x >> 6;
+    const int col = blockIdx.x * 64 + lane;
+    Moments a{0.0f, 0.0f, 0.0f};
+    if (col < F) {
+        for (int ch = slice; ch < chunks; ch += kMergeSlices) {
+            const int64_t r0 = (int64_t)ch * rows_per_chunk;
+            const int64_t cnt = min(N, r0 + rows_per_chunk) - r0;
+            if (cnt > 0) moments_merge(a, Moments{(float)cnt, part_m[(int64_t)ch * F + col], part_q[(int64_t)ch * F + col]});
+        }
+    }
+    fn[slice][lane] = a.n;
+    fm[slice][lane] = a.m;
+    fq[slice][lane] = a.q;
+    __syncthreads();
+    if (slice == 0 && col < F) {
+        for (int s = 1; s < kMergeSlices; ++s) moments_merge(a, Moments{fn[s][lane], fm[s][lane], fq[s][lane]});
+        mean[col] = a.m;
+        var[col] = a.q / (float)N;
     }
 }
 
@@ -150,7 +201,7 @@ extern "C" {
 size_t gnn_batchnorm_workspace_bytes(int32_t num_rows, int32_t feat_dim)
 {
     if (num_rows <= 0 || feat_dim <= 0) return 0;
-    return align256((size_t)gnn_row_chunk_count(num_rows) * feat_dim * sizeof(float));
+    return align256(2 * (size_t)gnn_row_chunk_count(num_rows) * feat_dim * sizeof(float));   // (mean, M2) per chunk
 }
 
 gnn_status gnn_batchnorm(const float *d_x, int32_t num_rows, int32_t feat_dim, const float *d_gamma,
@@ -171,17 +222,15 @@ gnn_status gnn_batchnorm(const float *d_x, int32_t num_rows, int32_t feat_dim, c
     } else if (!use_given_stats) {
         if (!d_workspace) return GNN_ERR_NULL;
         if (workspace_bytes < gnn_batchnorm_workspace_bytes(num_rows, feat_dim)) return GNN_ERR_BAD_SIZE;
-        float *part = static_cast<float *>(d_workspace);
         const int chunks = gnn_row_chunk_count(N);
         const int64_t rows_per_chunk = gnn_div_up(N, chunks);
-        hipLaunchKernelGGL(column_moment_partial_kernel<1>, dim3((unsigned)chunks), dim3(kThreads), 0, s, d_x, N, F,
-                           (const float *)nullptr, rows_per_chunk, part);
+        float *part_m = static_cast<float *>(d_workspace), *part_q = part_m + (size_t)chunks * F;
+        hipLaunchKernelGGL(column_moments_partial_kernel, dim3((unsigned)chunks), dim3(kThreads), 0, s, d_x, N, F,
+                           rows_per_chunk, part_m, part_q);
         GNN_LAUNCH_CHECK();
-        GNN_TRY(gnn_launch_sum_partials_scaled(part, chunks, F, 1.0f / (float)N, d_mean, s));
-        hipLaunchKernelGGL(column_moment_partial_kernel<2>, dim3((unsigned)chunks), dim3(kThreads), 0, s, d_x, N, F,
-                           (const float *)d_mean, rows_per_chunk, part);
+        hipLaunchKernelGGL(column_moments_merge_kernel, dim3((unsigned)gnn_div_up(F, 64)), dim3(64 * kMergeSlices), 0, s,
+                           part_m, part_q, chunks, N, rows_per_chunk, F, d_mean, d_var);
         GNN_LAUNCH_CHECK();
-        GNN_TRY(gnn_launch_sum_partials_scaled(part, chunks, F, 1.0f / (float)N, d_var, s));
     }
     const int blocks = (int)std::min<int64_t>(gnn_div_up(N * F, kThreads), 256 * 64);
     hipLaunchKernelGGL(normalise_rows_kernel, dim3(blocks), dim3(kThreads), 0, s, d_x, N, F, d_mean, d_var, d_gamma,
