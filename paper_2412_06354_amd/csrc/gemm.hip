@@ -45,14 +45,16 @@ struct AFrag {
 // precisely and the next buffer's loads stay in flight): rows past the end are clamped to the last
 // row (their results are never stored) and k positions past the end are clamped into the row (their
 // values meet zero-filled rows of W in LDS, and inputs are finite by contract).
-template <bool VEC4>
+// KSTEPS (even, <= 8) = groups of four k-values a lane reads: a sub-slab then spans 8 * KSTEPS k-values, the
+// lower half of the wavefront taking the first 4 * KSTEPS of them (narrow inputs do a fraction of the MFMA work).
+template <bool VEC4, int KSTEPS = 8>
 __device__ __forceinline__ void load_a(AFrag &a, const float *__restrict__ x, int64_t rows, int k, int64_t row,
                                        int k0, int half)
 {
     const float *xrow = x + min(row, rows - 1) * (int64_t)k;
 #pragma unroll
-    for (int s = 0; s < 8; ++s) {
-        const int kb = k0 + 32 * half + 4 * s;
+    for (int s = 0; s < KSTEPS; ++s) {
+        const int kb = k0 + 4 * KSTEPS * half + 4 * s;
         if constexpr (VEC4) {
             const float4 t = *reinterpret_cast<const float4 *>(xrow + min(kb, k - 4));   // k % 4 == 0
             a.v[s][0] = t.x; a.v[s][1] = t.y; a.v[s][2] = t.z; a.v[s][3] = t.w;
@@ -95,20 +97,21 @@ __device__ __forceinline__ void mfma_step(floatx16 (&acc)[NT], const float (&a)[
     for (int t = 0; t < NT; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(b[t].w, a[3], acc[t], 0, 0, 0);
 }
 
-template <int NT>
+template <int NT, int KSTEPS = 8>
 __device__ __forceinline__ void mfma_subslab(floatx16 (&acc)[NT], const AFrag &a, const float *ws, int kp, int kbase,
                                              int r)
 {
     // W fragments are read one step ahead of the MFMAs that use them; the scheduling barriers keep
-    // the compiler from hoisting all eight steps' reads (which would cost occupancy).
+    // the compiler from hoisting all the steps' reads (which would cost occupancy).
+    static_assert(KSTEPS % 2 == 0 && KSTEPS <= 8, "steps come in pairs");
     float4 b0[NT], b1[NT];
     load_b<NT>(b0, ws, kp, kbase, r);
 #pragma unroll
-    for (int s = 0; s < 8; s += 2) {
+    for (int s = 0; s < KSTEPS; s += 2) {
         load_b<NT>(b1, ws, kp, kbase + 4 * (s + 1), r);
         mfma_step<NT>(acc, a.v[s], b0);
         __builtin_amdgcn_sched_barrier(0);
-        if (s + 2 < 8) load_b<NT>(b0, ws, kp, kbase + 4 * (s + 2), r);
+        if (s + 2 < KSTEPS) load_b<NT>(b0, ws, kp, kbase + 4 * (s + 2), r);
         mfma_step<NT>(acc, a.v[s + 1], b1);
         __builtin_amdgcn_sched_barrier(0);
     }
@@ -222,7 +225,7 @@ __device__ __forceinline__ void stage_w(float *ws, const float *__restrict__ w, 
 // One wave tile of the fast kernel: 32 rows x NCB column blocks from the X fragments in registers.  They stay
 // there while the column blocks are worked off one after the other (one accumulator set, reused): X is read
 // once for NCB * BN output columns.
-template <int NT, int NSUB, int NCB>
+template <int NT, int NSUB, int NCB, int KSTEPS>
 __device__ __forceinline__ void fast_wave_tile(const AFrag (&a)[NSUB], const float *ws, float sc, int64_t row,
                                                int64_t rows, int n, int n0, int r, int half,
                                                const float *__restrict__ bias, int relu, float *__restrict__ z)
@@ -238,7 +241,7 @@ __device__ __forceinline__ void fast_wave_tile(const AFrag (&a)[NSUB], const flo
             for (int v = 0; v < 16; ++v) acc[t][v] = 0.0f;
 #pragma unroll
         for (int sub = 0; sub < NSUB; ++sub)
-            mfma_subslab<NT>(acc, a[sub], ws + cb * BN * KP, KP, sub * kSlab + 32 * half, r);
+            mfma_subslab<NT, KSTEPS>(acc, a[sub], ws + cb * BN * KP, KP, sub * kSlab + 4 * KSTEPS * half, r);
 
         if (row < rows) {   // false only for lanes past the end in a ragged last tile
             float *zrow = z + row * n + n0 + cb * BN + 4 * half;
@@ -261,7 +264,7 @@ __device__ __forceinline__ void fast_wave_tile(const AFrag (&a)[NSUB], const flo
     }
 }
 
-template <int NT, int NSUB, int NCB, bool SCALED>
+template <int NT, int NSUB, int NCB, bool SCALED, int KSTEPS>
 __global__ __launch_bounds__(kFastThreads) void xw_fast_kernel(const float *__restrict__ x, int k,
                                                                const float *__restrict__ w, int n,
                                                                const float *__restrict__ row_scale,
@@ -297,7 +300,7 @@ __global__ __launch_bounds__(kFastThreads) void xw_fast_kernel(const float *__re
         if (stager) st.load(w, k, n, 0, n0);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int sub = 0; sub < NSUB; ++sub) load_a<true>(a[sub], x, rows, k, row, sub * kSlab, half);
+        for (int sub = 0; sub < NSUB; ++sub) load_a<true, KSTEPS>(a[sub], x, rows, k, row, sub * kSlab, half);
         if constexpr (SCALED) sc = row_scale[min(row, rows - 1)];
         __builtin_amdgcn_sched_barrier(0);
         if (stager) st.store(ws, k, n, 0, n0);
@@ -305,13 +308,13 @@ __global__ __launch_bounds__(kFastThreads) void xw_fast_kernel(const float *__re
     __syncthreads();
 
     // From here on the wavefronts are independent.  The first tile (already loaded) is peeled off the loop.
-    if (wt < num_wave_tiles) fast_wave_tile<NT, NSUB, NCB>(a, ws, sc, row, rows, n, n0, r, half, bias, relu, z);
+    if (wt < num_wave_tiles) fast_wave_tile<NT, NSUB, NCB, KSTEPS>(a, ws, sc, row, rows, n, n0, r, half, bias, relu, z);
     for (wt += wt_stride; wt < num_wave_tiles; wt += wt_stride) {
         row = wt * kRowsPerWave + r;
 #pragma unroll
-        for (int sub = 0; sub < NSUB; ++sub) load_a<true>(a[sub], x, rows, k, row, sub * kSlab, half);
+        for (int sub = 0; sub < NSUB; ++sub) load_a<true, KSTEPS>(a[sub], x, rows, k, row, sub * kSlab, half);
         if constexpr (SCALED) sc = row_scale[min(row, rows - 1)];
-        fast_wave_tile<NT, NSUB, NCB>(a, ws, sc, row, rows, n, n0, r, half, bias, relu, z);
+        fast_wave_tile<NT, NSUB, NCB, KSTEPS>(a, ws, sc, row, rows, n, n0, r, half, bias, relu, z);
     }
 }
 
@@ -376,7 +379,7 @@ gnn_status launch_general(const float *d_x, int64_t rows, int k, const float *d_
     return GNN_OK;
 }
 
-template <int NT, int NSUB, int NCB>
+template <int NT, int NSUB, int NCB, int KSTEPS = 8>
 gnn_status launch_fast(const float *d_x, int64_t rows, int k, const float *d_w, int n, const XwEpilogue &ep,
                        float *d_z, hipStream_t s)
 {
@@ -389,26 +392,24 @@ gnn_status launch_fast(const float *d_x, int64_t rows, int k, const float *d_w, 
     const int64_t blocks = std::max<int64_t>(1, std::min<int64_t>(device_cu_count() / col_blocks, wave_tiles));
     const dim3 grid((unsigned)blocks, (unsigned)col_blocks);
     if (ep.row_scale)
-        hipLaunchKernelGGL((xw_fast_kernel<NT, NSUB, NCB, true>), grid, dim3(kFastThreads), lds, s, d_x, k, d_w, n,
+        hipLaunchKernelGGL((xw_fast_kernel<NT, NSUB, NCB, true, KSTEPS>), grid, dim3(kFastThreads), lds, s, d_x, k, d_w, n,
                            ep.row_scale, ep.bias, ep.relu, d_z, rows);
     else
-        hipLaunchKernelGGL((xw_fast_kernel<NT, NSUB, NCB, false>), grid, dim3(kFastThreads), lds, s, d_x, k, d_w, n,
+        hipLaunchKernelGGL((xw_fast_kernel<NT, NSUB, NCB, false, KSTEPS>), grid, dim3(kFastThreads), lds, s, d_x, k, d_w, n,
                            ep.row_scale, ep.bias, ep.relu, d_z, rows);
     GNN_LAUNCH_CHECK();
     return GNN_OK;
 }
 
-// Fast path: column tiles of 32 (n <= 32) or 64, two of them per block where the matrix is wider than one.
-template <int NT>
+template <int NT, int NCB>
 gnn_status launch_fast_for_k(const float *d_x, int64_t rows, int k, const float *d_w, int n, const XwEpilogue &ep,
                              float *d_z, hipStream_t s)
 {
-    if (n > NT * 32) {
-        if (k <= kSlab) return launch_fast<NT, 1, 2>(d_x, rows, k, d_w, n, ep, d_z, s);
-        return launch_fast<NT, 2, 2>(d_x, rows, k, d_w, n, ep, d_z, s);
-    }
-    if (k <= kSlab) return launch_fast<NT, 1, 1>(d_x, rows, k, d_w, n, ep, d_z, s);
-    return launch_fast<NT, 2, 1>(d_x, rows, k, d_w, n, ep, d_z, s);
+    // up to 64 k-values: one sub-slab of 16, 32 or 64 (two, four or eight steps); up to 128: two full sub-slabs
+    if (k <= 16) return launch_fast<NT, 1, NCB, 2>(d_x, rows, k, d_w, n, ep, d_z, s);
+    if (k <= 32) return launch_fast<NT, 1, NCB, 4>(d_x, rows, k, d_w, n, ep, d_z, s);
+    if (k <= kSlab) return launch_fast<NT, 1, NCB, 8>(d_x, rows, k, d_w, n, ep, d_z, s);
+    return launch_fast<NT, 2, NCB, 8>(d_x, rows, k, d_w, n, ep, d_z, s);
 }
 
 }  // namespace
@@ -426,8 +427,10 @@ gnn_status gnn_launch_xw(const float *d_x, int64_t rows, int32_t k, const float 
     const bool x_vec4 = (k % 4 == 0) && ((reinterpret_cast<uintptr_t>(d_x) & 15u) == 0);
     const bool w_vec4 = (n % 4 == 0) && ((reinterpret_cast<uintptr_t>(d_w) & 15u) == 0);
     if (x_vec4 && w_vec4 && k <= 2 * kSlab) {   // w_vec4 implies n % 4 == 0
-        if (n <= 32) return launch_fast_for_k<1>(d_x, rows, k, d_w, n, ep, d_z, s);
-        return launch_fast_for_k<2>(d_x, rows, k, d_w, n, ep, d_z, s);
+        // column tiles of 32 (n <= 32) or 64, two of them per block where the matrix is wider than one
+        if (n <= 32) return launch_fast_for_k<1, 1>(d_x, rows, k, d_w, n, ep, d_z, s);
+        if (n <= 64) return launch_fast_for_k<2, 1>(d_x, rows, k, d_w, n, ep, d_z, s);
+        return launch_fast_for_k<2, 2>(d_x, rows, k, d_w, n, ep, d_z, s);
     }
     // General kernel.  Column tile: 64 or 32 if it divides n, else 128 wide when n is large enough, else the
     // smallest multiple of 32 covering n.
