@@ -212,10 +212,13 @@ BackwardLayout layout(int64_t N, int f_in, int f_out)
 
 int gnn_row_chunk_count(int64_t rows)
 {
-    // about 256 rows per chunk, at most 2048 chunks; above one chunk per compute unit the count is rounded up to
-    // a multiple of 256, so that blocks working on one chunk each come in whole rounds over the chip
+    // About 256 rows per chunk, at most 2048 chunks.  Above one chunk per compute unit the count is rounded up
+    // to a multiple of 256, so that blocks working on one chunk each come in whole rounds over the chip; below,
+    // chunks shrink to as few as 32 rows so that small inputs still spread over many blocks (a block's walk over
+    // its rows is a chain of dependent memory round trips).
     int64_t c = std::max<int64_t>(1, gnn_div_up(rows, 256));
     if (c > 256) c = gnn_div_up(c, 256) * 256;
+    else c = std::min<int64_t>(256, std::max<int64_t>(1, gnn_div_up(rows, 32)));
     return (int)std::min<int64_t>(2048, c);
 }
 

@@ -10,7 +10,8 @@
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kSmallGraphNodes = 128;   // average nodes per graph up to which a wavefront takes a graph
+constexpr int kSmallGraphNodes = 128;   // average nodes per graph up to which a wavefront takes a graph ...
+constexpr int kManyGraphs = 1024;       // ... in batches of at least this many graphs
 
 __device__ __forceinline__ float max_pz(float a, float b)
 {
@@ -194,7 +195,8 @@ extern "C" gnn_status gnn_graph_pool(const int32_t *d_graph_indicator, int32_t n
     if (num_nodes > 0 && (!d_graph_indicator || !d_x)) return GNN_ERR_NULL;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int mean = aggr == GNN_AGGR_MEAN ? 1 : 0;
-    if ((int64_t)num_nodes <= (int64_t)num_graphs * kSmallGraphNodes) {   // small graphs on average: a wavefront each
+    // many small graphs: a wavefront each (with few graphs the block-per-graph kernel has more loads in flight)
+    if ((int64_t)num_nodes <= (int64_t)num_graphs * kSmallGraphNodes && num_graphs >= kManyGraphs) {
         int lanes = 1;
         while (lanes < feat_dim && lanes < 64) lanes <<= 1;
         const dim3 grid((unsigned)gnn_div_up(num_graphs, kThreads / 64));
