@@ -240,16 +240,26 @@ gnn_status gnn_launch_sum_partials(const float *d_partial, int chunks, int64_t e
     return gnn_launch_sum_partials_scaled(d_partial, chunks, elems, 1.0f, d_out, s);
 }
 
-gnn_status gnn_launch_xty(const float *d_x, const float *d_y, int64_t rows, int f_in, int f_out, float *d_partial,
-                          float *d_out, hipStream_t s)
+template <int NT>
+static gnn_status launch_xty_tiles(const float *d_x, const float *d_y, int64_t rows, int f_in, int f_out, int chunks,
+                                   float *d_partial, hipStream_t s)
 {
-    constexpr int NT = 4;
-    const int chunks = gnn_row_chunk_count(rows);
     const int64_t rows_per_chunk = gnn_div_up(rows, chunks);
     const dim3 grid((unsigned)chunks, (unsigned)gnn_div_up(f_in, 128), (unsigned)gnn_div_up(f_out, NT * 32));
     hipLaunchKernelGGL(xty_partial_kernel<NT>, grid, dim3(kThreads), 0, s, d_x, d_y, rows, f_in, f_out, rows_per_chunk,
                        d_partial);
     GNN_LAUNCH_CHECK();
+    return GNN_OK;
+}
+
+gnn_status gnn_launch_xty(const float *d_x, const float *d_y, int64_t rows, int f_in, int f_out, float *d_partial,
+                          float *d_out, hipStream_t s)
+{
+    // a wavefront holds 1, 2 or 4 accumulator tiles of 32 columns: no MFMA work on columns that do not exist
+    const int chunks = gnn_row_chunk_count(rows);
+    if (f_out <= 32) GNN_TRY(launch_xty_tiles<1>(d_x, d_y, rows, f_in, f_out, chunks, d_partial, s));
+    else if (f_out <= 64) GNN_TRY(launch_xty_tiles<2>(d_x, d_y, rows, f_in, f_out, chunks, d_partial, s));
+    else GNN_TRY(launch_xty_tiles<4>(d_x, d_y, rows, f_in, f_out, chunks, d_partial, s));
     return gnn_launch_sum_partials(d_partial, chunks, (int64_t)f_in * f_out, d_out, s);
 }
 

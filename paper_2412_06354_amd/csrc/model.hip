@@ -89,10 +89,21 @@ __global__ __launch_bounds__(64 * kMergeSlices) void column_moments_merge_kernel
     const int col = blockIdx.x * 64 + lane;
     Moments a{0.0f, 0.0f, 0.0f};
     if (col < F) {
-        for (int ch = slice; ch < chunks; ch += kMergeSlices) {
-            const int64_t r0 = (int64_t)ch * rows_per_chunk;
-            const int64_t cnt = min(N, r0 + rows_per_chunk) - r0;
-            if (cnt > 0) moments_merge(a, Moments{(float)cnt, part_m[(int64_t)ch * F + col], part_q[(int64_t)ch * F + col]});
+        // eight chunks per round, their loads issued before the chain of merges (empty trailing chunks have
+        // count zero and merge as nothing; their partials were written as zeros)
+        for (int ch0 = slice; ch0 < chunks; ch0 += 8 * kMergeSlices) {
+            float pm[8], pq[8], pn[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int ch = min(ch0 + u * kMergeSlices, chunks - 1);
+                const int64_t r0 = (int64_t)ch * rows_per_chunk;
+                const int64_t cnt = min(N, r0 + rows_per_chunk) - r0;
+                pn[u] = (ch0 + u * kMergeSlices < chunks && cnt > 0) ? (float)cnt : 0.0f;
+                pm[u] = part_m[(int64_t)ch * F + col];
+                pq[u] = part_q[(int64_t)ch * F + col];
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) moments_merge(a, Moments{pn[u], pm[u], pq[u]});
         }
     }
     fn[slice][lane] = a.n;

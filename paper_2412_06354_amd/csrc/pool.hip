@@ -89,18 +89,10 @@ __global__ __launch_bounds__(kThreads) void pool_kernel(const int32_t *__restric
     }
 }
 
-// Batches of small graphs: one wavefront per graph (four graphs per block), no block-wide barriers.  The run's
-// bounds come from the same interleaved search with 64 probes per round; lanes are (node slot, feature lane),
-// node slots stride over the run and are combined by a fixed xor-shuffle tree.
-template <bool MAX>
-__global__ __launch_bounds__(kThreads) void pool_wave_kernel(const int32_t *__restrict__ gi, int32_t N,
-                                                             const float *__restrict__ x, int32_t F,
-                                                             int32_t lanes /* power of two <= 64 */, int mean,
-                                                             int32_t num_graphs, float *__restrict__ out)
+// The same search by one wavefront (64 probes per round, ballots instead of block-wide counts).
+__device__ __forceinline__ void wave_run_bounds(const int32_t *__restrict__ gi, int N, int g, int lane, int *first,
+                                                int *last)
 {
-    const int lane = threadIdx.x & 63;
-    const int g = blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
-    if (g >= num_graphs) return;   // wavefront-uniform
     int lo0 = 0, hi0 = N, lo1 = 0, hi1 = N;
     while (lo0 < hi0 || lo1 < hi1) {   // wavefront-uniform
         const int step0 = max(1, (hi0 - lo0 + 63) / 64), step1 = max(1, (hi1 - lo1 + 63) / 64);
@@ -125,7 +117,25 @@ __global__ __launch_bounds__(kThreads) void pool_wave_kernel(const int32_t *__re
             }
         }
     }
-    const int lo = lo0, hi = lo1, cnt = hi - lo;
+    *first = lo0;
+    *last = lo1;
+}
+
+// Batches of small graphs: one wavefront per graph (four graphs per block), no block-wide barriers.  The run's
+// bounds come from the same interleaved search with 64 probes per round; lanes are (node slot, feature lane),
+// node slots stride over the run and are combined by a fixed xor-shuffle tree.
+template <bool MAX>
+__global__ __launch_bounds__(kThreads) void pool_wave_kernel(const int32_t *__restrict__ gi, int32_t N,
+                                                             const float *__restrict__ x, int32_t F,
+                                                             int32_t lanes /* power of two <= 64 */, int mean,
+                                                             int32_t num_graphs, float *__restrict__ out)
+{
+    const int lane = threadIdx.x & 63;
+    const int g = blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
+    if (g >= num_graphs) return;   // wavefront-uniform
+    int lo, hi;
+    wave_run_bounds(gi, N, g, lane, &lo, &hi);
+    const int cnt = hi - lo;
     const int fl = lane % lanes, slot = lane / lanes, slots = 64 / lanes;
     for (int f0 = 0; f0 < F; f0 += lanes) {
         const int f = f0 + fl;
@@ -168,6 +178,27 @@ __global__ __launch_bounds__(kThreads) void pool_backward_kernel(const int32_t *
     }
 }
 
+// The same for batches of many small graphs: one wavefront per graph.
+__global__ __launch_bounds__(kThreads) void pool_backward_wave_kernel(const int32_t *__restrict__ gi, int32_t N,
+                                                                      const float *__restrict__ gout, int32_t F,
+                                                                      int mean, int32_t num_graphs,
+                                                                      float *__restrict__ gx)
+{
+    const int lane = threadIdx.x & 63;
+    const int g = blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
+    if (g >= num_graphs) return;   // wavefront-uniform
+    int lo, hi;
+    wave_run_bounds(gi, N, g, lane, &lo, &hi);
+    const int cnt = hi - lo;
+    if (cnt <= 0) return;
+    const int64_t total = (int64_t)cnt * F;
+    for (int64_t q = lane; q < total; q += 64) {
+        const int f = (int)(q % F);
+        const float v = gout[(int64_t)g * F + f];
+        gx[(int64_t)lo * F + q] = mean ? v / (float)cnt : v;
+    }
+}
+
 }  // namespace
 
 extern "C" gnn_status gnn_graph_pool_backward(const int32_t *d_graph_indicator, int32_t num_nodes, int32_t num_graphs,
@@ -179,9 +210,14 @@ extern "C" gnn_status gnn_graph_pool_backward(const int32_t *d_graph_indicator, 
     if (aggr != GNN_AGGR_SUM && aggr != GNN_AGGR_MEAN) return GNN_ERR_BAD_SIZE;
     if (num_nodes == 0) return GNN_OK;
     if (!d_graph_indicator || !d_grad_out || !d_grad_x) return GNN_ERR_NULL;
-    hipLaunchKernelGGL(pool_backward_kernel, dim3((unsigned)num_graphs), dim3(kThreads), 0,
-                       static_cast<hipStream_t>(stream), d_graph_indicator, num_nodes, d_grad_out, feat_dim,
-                       aggr == GNN_AGGR_MEAN ? 1 : 0, d_grad_x);
+    if ((int64_t)num_nodes <= (int64_t)num_graphs * kSmallGraphNodes && num_graphs >= kManyGraphs)
+        hipLaunchKernelGGL(pool_backward_wave_kernel, dim3((unsigned)gnn_div_up(num_graphs, kThreads / 64)),
+                           dim3(kThreads), 0, static_cast<hipStream_t>(stream), d_graph_indicator, num_nodes,
+                           d_grad_out, feat_dim, aggr == GNN_AGGR_MEAN ? 1 : 0, num_graphs, d_grad_x);
+    else
+        hipLaunchKernelGGL(pool_backward_kernel, dim3((unsigned)num_graphs), dim3(kThreads), 0,
+                           static_cast<hipStream_t>(stream), d_graph_indicator, num_nodes, d_grad_out, feat_dim,
+                           aggr == GNN_AGGR_MEAN ? 1 : 0, d_grad_x);
     GNN_LAUNCH_CHECK();
     return GNN_OK;
 }

@@ -45,6 +45,7 @@ __global__ __launch_bounds__(kThreads) void relu_mask_kernel(const float *__rest
 
 // Batch-norm backward, stage 1: per row chunk and column, sum of g and of g * xhat, where
 // g = gy masked by (y > 0) when y is given (the relu that followed) and xhat = (x - mean) / sqrt(var + eps).
+template <bool MASK>
 __global__ __launch_bounds__(kThreads) void bn_backward_partial_kernel(const float *__restrict__ x, int64_t N, int F,
                                                                        const float *__restrict__ mean,
                                                                        const float *__restrict__ var, float eps,
@@ -63,10 +64,28 @@ __global__ __launch_bounds__(kThreads) void bn_backward_partial_kernel(const flo
         float sb = 0.0f, sg = 0.0f;
         if (rs < slices && col < F) {
             const float mu = mean[col], inv = 1.0f / sqrtf(var[col] + eps);
-            for (int64_t row = r0 + rs; row < r1; row += slices) {
+            // four rows per round, all loads first (no branch in the body: the mask is a template parameter)
+            int64_t row = r0 + rs;
+            for (; row + 3 * slices < r1; row += 4 * slices) {
+                float gv[4], xv[4], yv[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int64_t q = (row + u * slices) * F + col;
+                    gv[u] = gy[q];
+                    xv[u] = x[q];
+                    yv[u] = MASK ? y[q] : 1.0f;
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const float g = yv[u] > 0.0f ? gv[u] : 0.0f;
+                    sb += g;
+                    sg = fmaf(g, (xv[u] - mu) * inv, sg);
+                }
+            }
+            for (; row < r1; row += slices) {
                 const int64_t q = row * F + col;
                 float g = gy[q];
-                if (y) g = y[q] > 0.0f ? g : 0.0f;
+                if (MASK) g = y[q] > 0.0f ? g : 0.0f;
                 sb += g;
                 sg = fmaf(g, (x[q] - mu) * inv, sg);
             }
@@ -314,8 +333,12 @@ gnn_status gnn_batchnorm_backward(const float *d_x, int32_t num_rows, int32_t fe
                            (int)N, F, d_mean, d_var, eps, d_grad_y, d_y_relu, d_grad_beta, d_grad_gamma);
         GNN_LAUNCH_CHECK();
     } else {
-        hipLaunchKernelGGL(bn_backward_partial_kernel, dim3((unsigned)chunks), dim3(kThreads), 0, s, d_x, N, F, d_mean,
-                           d_var, eps, d_grad_y, d_y_relu, rows_per_chunk, part_b, part_g);
+        if (d_y_relu)
+            hipLaunchKernelGGL(bn_backward_partial_kernel<true>, dim3((unsigned)chunks), dim3(kThreads), 0, s, d_x, N, F,
+                               d_mean, d_var, eps, d_grad_y, d_y_relu, rows_per_chunk, part_b, part_g);
+        else
+            hipLaunchKernelGGL(bn_backward_partial_kernel<false>, dim3((unsigned)chunks), dim3(kThreads), 0, s, d_x, N, F,
+                               d_mean, d_var, eps, d_grad_y, d_y_relu, rows_per_chunk, part_b, part_g);
         GNN_LAUNCH_CHECK();
         GNN_TRY(gnn_launch_sum_partials(part_b, chunks, F, d_grad_beta, s));
         GNN_TRY(gnn_launch_sum_partials(part_g, chunks, F, d_grad_gamma, s));
