@@ -88,18 +88,26 @@ __global__ __launch_bounds__(kThreads) void transpose_kernel(const float *__rest
 }
 
 // partial[chunk][i][j] = sum over the chunk's rows of X[row][i] * Y[row][j].
-// Block = 4 wavefronts = four 32-wide strips of i; a wavefront holds NT 32x32 accumulator tiles.
-template <int NT>
+// A block of 4 wavefronts covers STRIPS (1, 2 or 4) 32-wide strips of i and all its columns j in NT accumulator
+// tiles of 32; with fewer than four strips the spare wavefronts take every other (every fourth) batch of rows
+// of the chunk and their tiles are added through LDS in a fixed order at the end.  The kernel lives on loads in
+// flight -- one MFMA consumes two rows of both operands in 64 cycles, a memory round trip takes thousands --
+// hence two register sets of U row pairs each and all four wavefronts at work.
+template <int NT, int STRIPS>
 __global__ __launch_bounds__(kThreads) void xty_partial_kernel(const float *__restrict__ x, const float *__restrict__ y,
                                                                int64_t rows, int f_in, int f_out,
                                                                int64_t rows_per_chunk, float *__restrict__ partial)
 {
-    constexpr int U = 4;   // row pairs in flight
+    constexpr int U = NT >= 4 ? 4 : 8;   // row pairs per register set
+    constexpr int RG = 4 / STRIPS;       // row groups
+    __shared__ float red[RG > 1 ? (RG - 1) * STRIPS * NT * 1024 : 1];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int c = lane & 31, kk = lane >> 5;
-    const int i0 = (blockIdx.y * 4 + wave) * 32;
+    const int strip = wave % STRIPS, rg = wave / STRIPS;
+    const int i0 = (blockIdx.y * STRIPS + strip) * 32;
     const int j0 = blockIdx.z * NT * 32;
     const int64_t r0 = (int64_t)blockIdx.x * rows_per_chunk, r1 = min(rows, r0 + rows_per_chunk);
+    const bool active = i0 < f_in && r0 < r1;   // wavefront-uniform
 
     floatx16 acc[NT];
 #pragma unroll
@@ -107,10 +115,10 @@ __global__ __launch_bounds__(kThreads) void xty_partial_kernel(const float *__re
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[t][v] = 0.0f;
 
-    if (i0 < f_in) {   // wavefront-uniform
-        // Two register sets: the loads of the next U row pairs are in flight while the MFMAs of the current
-        // ones run (rows past the chunk load nothing and multiply zeros).
-        auto load_set = [&](float (&a)[U], float (&b)[U][NT], int64_t rp) {
+    if (active) {
+        // Batch s covers the rows r0 + 2 U s ... ; row group rg takes the batches s = rg, rg + RG, ...
+        auto load_set = [&](float (&a)[U], float (&b)[U][NT], int64_t s) {
+            const int64_t rp = r0 + s * (2 * U);
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 // Unconditional loads from clamped addresses, no branches between them.  A row past the chunk is
@@ -130,13 +138,35 @@ __global__ __launch_bounds__(kThreads) void xty_partial_kernel(const float *__re
                 for (int t = 0; t < NT; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u], b[u][t], acc[t], 0, 0, 0);
         };
         float a0[U], b0[U][NT], a1[U], b1[U][NT];
-        load_set(a0, b0, r0);
-        for (int64_t rp = r0; rp < r1; rp += 4 * U) {
-            load_set(a1, b1, rp + 2 * U);
+        load_set(a0, b0, rg);
+        for (int64_t s = rg; r0 + s * (2 * U) < r1; s += 2 * RG) {
+            load_set(a1, b1, s + RG);
             mfma_set(a0, b0);
-            load_set(a0, b0, rp + 4 * U);
+            load_set(a0, b0, s + 2 * RG);
             mfma_set(a1, b1);
         }
+    }
+    if constexpr (RG > 1) {   // the spare row groups hand their tiles to group 0, which adds them in group order
+        if (active && rg > 0) {
+            float *mine = red + ((rg - 1) * STRIPS + strip) * NT * 1024;
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) mine[(t * 16 + v) * 64 + lane] = acc[t][v];
+        }
+        __syncthreads();
+        if (active && rg == 0) {
+#pragma unroll
+            for (int q = 1; q < RG; ++q) {
+                const float *theirs = red + ((q - 1) * STRIPS + strip) * NT * 1024;
+#pragma unroll
+                for (int t = 0; t < NT; ++t)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) acc[t][v] += theirs[(t * 16 + v) * 64 + lane];
+            }
+        }
+    }
+    if (i0 < f_in && rg == 0) {   // an empty trailing chunk still writes its zeros: the sum over chunks reads them
         // accumulator register v of lane l: row 8*(v/4) + 4*(l/32) + v%4, column l%32
         float *out = partial + (int64_t)blockIdx.x * f_in * f_out;
 #pragma unroll
@@ -240,16 +270,25 @@ gnn_status gnn_launch_sum_partials(const float *d_partial, int chunks, int64_t e
     return gnn_launch_sum_partials_scaled(d_partial, chunks, elems, 1.0f, d_out, s);
 }
 
+template <int NT, int STRIPS>
+static gnn_status launch_xty_shape(const float *d_x, const float *d_y, int64_t rows, int f_in, int f_out, int chunks,
+                                   float *d_partial, hipStream_t s)
+{
+    const int64_t rows_per_chunk = gnn_div_up(rows, chunks);
+    const dim3 grid((unsigned)chunks, (unsigned)gnn_div_up(f_in, 32 * STRIPS), (unsigned)gnn_div_up(f_out, NT * 32));
+    hipLaunchKernelGGL((xty_partial_kernel<NT, STRIPS>), grid, dim3(kThreads), 0, s, d_x, d_y, rows, f_in, f_out,
+                       rows_per_chunk, d_partial);
+    GNN_LAUNCH_CHECK();
+    return GNN_OK;
+}
+
 template <int NT>
 static gnn_status launch_xty_tiles(const float *d_x, const float *d_y, int64_t rows, int f_in, int f_out, int chunks,
                                    float *d_partial, hipStream_t s)
 {
-    const int64_t rows_per_chunk = gnn_div_up(rows, chunks);
-    const dim3 grid((unsigned)chunks, (unsigned)gnn_div_up(f_in, 128), (unsigned)gnn_div_up(f_out, NT * 32));
-    hipLaunchKernelGGL(xty_partial_kernel<NT>, grid, dim3(kThreads), 0, s, d_x, d_y, rows, f_in, f_out, rows_per_chunk,
-                       d_partial);
-    GNN_LAUNCH_CHECK();
-    return GNN_OK;
+    if (f_in <= 32) return launch_xty_shape<NT, 1>(d_x, d_y, rows, f_in, f_out, chunks, d_partial, s);
+    if (f_in <= 64) return launch_xty_shape<NT, 2>(d_x, d_y, rows, f_in, f_out, chunks, d_partial, s);
+    return launch_xty_shape<NT, 4>(d_x, d_y, rows, f_in, f_out, chunks, d_partial, s);
 }
 
 gnn_status gnn_launch_xty(const float *d_x, const float *d_y, int64_t rows, int f_in, int f_out, float *d_partial,

@@ -36,7 +36,7 @@ __device__ __forceinline__ void moments_add(Moments &a, float v)
 __device__ __forceinline__ void moments_merge(Moments &a, const Moments &b)
 {
     if (b.n == 0.0f) return;
-    const float n = a.n + b.n, delta = b.m - a.m, w = b.n / n;
+    const float n = a.n + b.n, delta = b.m - a.m, w = b.n * __builtin_amdgcn_rcpf(n);   // weight to within an ulp
     a.m = fmaf(delta, w, a.m);
     a.q = a.q + b.q + delta * delta * (a.n * w);
     a.n = n;
@@ -87,7 +87,7 @@ __global__ __launch_bounds__(64 * kMergeSlices) void column_moments_merge_kernel
     __shared__ float fn[kMergeSlices][64], fm[kMergeSlices][64], fq[kMergeSlices][64];
     const int lane = threadIdx.x & 63, slice = threadIdx.x >> 6;
     const int col = blockIdx.x * 64 + lane;
-    Moments a{0.0f, 0.0f, 0.0f};
+    Moments a{0.0f, 0.0f, 0.0f}, a2{0.0f, 0.0f, 0.0f};
     if (col < F) {
         // eight chunks per round, their loads issued before the chain of merges (empty trailing chunks have
         // count zero and merge as nothing; their partials were written as zeros)
@@ -102,9 +102,14 @@ __global__ __launch_bounds__(64 * kMergeSlices) void column_moments_merge_kernel
                 pm[u] = part_m[(int64_t)ch * F + col];
                 pq[u] = part_q[(int64_t)ch * F + col];
             }
+            // two independent chains (even and odd chunks of the round), joined at the end: half the dependent depth
 #pragma unroll
-            for (int u = 0; u < 8; ++u) moments_merge(a, Moments{pn[u], pm[u], pq[u]});
+            for (int u = 0; u < 8; u += 2) {
+                moments_merge(a, Moments{pn[u], pm[u], pq[u]});
+                moments_merge(a2, Moments{pn[u + 1], pm[u + 1], pq[u + 1]});
+            }
         }
+        moments_merge(a, a2);
     }
     fn[slice][lane] = a.n;
     fm[slice][lane] = a.m;
