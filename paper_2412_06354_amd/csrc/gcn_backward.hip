@@ -217,6 +217,43 @@ __global__ __launch_bounds__(64 * SLICES) void sum_partials_kernel(const float *
     }
 }
 
+// The same sum for few elements and many chunks: a block of 1024 threads owns eight elements, its 128 thread
+// rows take the chunks round-robin (eight loads in flight each) and are added through LDS by a fixed halving
+// tree -- the chain of dependent adds, which is what takes the time here, is chunks / 128 + 7 long.
+constexpr int kTreeThreads = 1024, kTreeCols = 8, kTreeSlots = kTreeThreads / kTreeCols;
+
+__global__ __launch_bounds__(kTreeThreads) void sum_partials_tree_kernel(const float *__restrict__ partial, int chunks,
+                                                                         int64_t elems, float factor,
+                                                                         float *__restrict__ out)
+{
+    __shared__ float fold[kTreeSlots][kTreeCols];
+    const int c0 = threadIdx.x % kTreeCols, slot = threadIdx.x / kTreeCols;
+    const int64_t q = (int64_t)blockIdx.x * kTreeCols + c0;
+    const bool ok = q < elems;
+    const int64_t qc = ok ? q : 0;
+    float s = 0.0f;
+    int ch = slot;
+    for (; ch + 7 * kTreeSlots < chunks; ch += 8 * kTreeSlots) {
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = partial[(int64_t)(ch + kTreeSlots * u) * elems + qc];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) s += v[u];
+    }
+    for (; ch < chunks; ch += kTreeSlots) s += partial[(int64_t)ch * elems + qc];
+    fold[slot][c0] = s;
+    __syncthreads();
+#pragma unroll
+    for (int h = kTreeSlots / 2; h >= 1; h >>= 1) {
+        if (slot < h) fold[slot][c0] += fold[slot + h][c0];
+        __syncthreads();
+    }
+    if (slot == 0 && ok) {
+        const float t = fold[0][c0];
+        out[q] = factor == 1.0f ? t : t * factor;
+    }
+}
+
 size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
 
 int chunk_count(int64_t rows) { return gnn_row_chunk_count(rows); }
@@ -258,7 +295,8 @@ gnn_status gnn_launch_sum_partials_scaled(const float *d_partial, int chunks, in
     if (elems <= 0) return GNN_OK;
     const dim3 grid((unsigned)gnn_div_up(elems, 64));
     if (elems <= 4096 && chunks >= 64)
-        hipLaunchKernelGGL(sum_partials_kernel<16>, grid, dim3(64 * 16), 0, s, d_partial, chunks, elems, factor, d_out);
+        hipLaunchKernelGGL(sum_partials_tree_kernel, dim3((unsigned)gnn_div_up(elems, kTreeCols)), dim3(kTreeThreads), 0,
+                           s, d_partial, chunks, elems, factor, d_out);
     else
         hipLaunchKernelGGL(sum_partials_kernel<4>, grid, dim3(64 * 4), 0, s, d_partial, chunks, elems, factor, d_out);
     GNN_LAUNCH_CHECK();

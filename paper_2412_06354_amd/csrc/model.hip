@@ -73,50 +73,53 @@ __global__ __launch_bounds__(kThreads) void column_moments_partial_kernel(const 
     }
 }
 
-// mean[f], var[f] (biased) from the chunks' pairs: a block owns 64 columns, its 16 thread rows take the chunks
-// round-robin and are merged in slice order.
-constexpr int kMergeSlices = 16;
+// mean[f], var[f] (biased) from the chunks' pairs.  A block of 1024 threads owns eight columns; its 128 thread
+// rows take the chunks round-robin (eight loads in flight each) and are then merged through LDS by a fixed
+// halving tree: a short chain of dependent merges instead of one per chunk.
+constexpr int kMergeThreads = 1024, kMergeCols = 8, kMergeSlots = kMergeThreads / kMergeCols;
 
-__global__ __launch_bounds__(64 * kMergeSlices) void column_moments_merge_kernel(const float *__restrict__ part_m,
-                                                                                 const float *__restrict__ part_q,
-                                                                                 int chunks, int64_t N,
-                                                                                 int64_t rows_per_chunk, int F,
-                                                                                 float *__restrict__ mean,
-                                                                                 float *__restrict__ var)
+__global__ __launch_bounds__(kMergeThreads) void column_moments_merge_kernel(const float *__restrict__ part_m,
+                                                                             const float *__restrict__ part_q,
+                                                                             int chunks, int64_t N,
+                                                                             int64_t rows_per_chunk, int F,
+                                                                             float *__restrict__ mean,
+                                                                             float *__restrict__ var)
 {
-    __shared__ float fn[kMergeSlices][64], fm[kMergeSlices][64], fq[kMergeSlices][64];
-    const int lane = threadIdx.x & 63, slice = threadIdx.x >> 6;
-    const int col = blockIdx.x * 64 + lane;
-    Moments a{0.0f, 0.0f, 0.0f}, a2{0.0f, 0.0f, 0.0f};
-    if (col < F) {
-        // eight chunks per round, their loads issued before the chain of merges (empty trailing chunks have
-        // count zero and merge as nothing; their partials were written as zeros)
-        for (int ch0 = slice; ch0 < chunks; ch0 += 8 * kMergeSlices) {
-            float pm[8], pq[8], pn[8];
+    __shared__ float fn[kMergeSlots][kMergeCols], fm[kMergeSlots][kMergeCols], fq[kMergeSlots][kMergeCols];
+    const int c0 = threadIdx.x % kMergeCols, slot = threadIdx.x / kMergeCols;
+    const int col = blockIdx.x * kMergeCols + c0;
+    const bool ok = col < F;
+    const int colc = ok ? col : 0;
+    Moments a{0.0f, 0.0f, 0.0f};
+    for (int ch0 = slot; ch0 < chunks; ch0 += 8 * kMergeSlots) {   // block-uniform trip count would not matter: no barrier inside
+        float pm[8], pq[8], pn[8];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int ch = min(ch0 + u * kMergeSlices, chunks - 1);
-                const int64_t r0 = (int64_t)ch * rows_per_chunk;
-                const int64_t cnt = min(N, r0 + rows_per_chunk) - r0;
-                pn[u] = (ch0 + u * kMergeSlices < chunks && cnt > 0) ? (float)cnt : 0.0f;
-                pm[u] = part_m[(int64_t)ch * F + col];
-                pq[u] = part_q[(int64_t)ch * F + col];
-            }
-            // two independent chains (even and odd chunks of the round), joined at the end: half the dependent depth
-#pragma unroll
-            for (int u = 0; u < 8; u += 2) {
-                moments_merge(a, Moments{pn[u], pm[u], pq[u]});
-                moments_merge(a2, Moments{pn[u + 1], pm[u + 1], pq[u + 1]});
-            }
+        for (int u = 0; u < 8; ++u) {
+            const int ch = min(ch0 + u * kMergeSlots, chunks - 1);
+            const int64_t r0 = (int64_t)ch * rows_per_chunk;
+            const int64_t cnt = min(N, r0 + rows_per_chunk) - r0;
+            pn[u] = (ok && ch0 + u * kMergeSlots < chunks && cnt > 0) ? (float)cnt : 0.0f;
+            pm[u] = part_m[(int64_t)ch * F + colc];
+            pq[u] = part_q[(int64_t)ch * F + colc];
         }
-        moments_merge(a, a2);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) moments_merge(a, Moments{pn[u], pm[u], pq[u]});
     }
-    fn[slice][lane] = a.n;
-    fm[slice][lane] = a.m;
-    fq[slice][lane] = a.q;
+    fn[slot][c0] = a.n;
+    fm[slot][c0] = a.m;
+    fq[slot][c0] = a.q;
     __syncthreads();
-    if (slice == 0 && col < F) {
-        for (int s = 1; s < kMergeSlices; ++s) moments_merge(a, Moments{fn[s][lane], fm[s][lane], fq[s][lane]});
+#pragma unroll
+    for (int h = kMergeSlots / 2; h >= 1; h >>= 1) {
+        if (slot < h) {
+            moments_merge(a, Moments{fn[slot + h][c0], fm[slot + h][c0], fq[slot + h][c0]});
+            fn[slot][c0] = a.n;
+            fm[slot][c0] = a.m;
+            fq[slot][c0] = a.q;
+        }
+        __syncthreads();
+    }
+    if (slot == 0 && ok) {
         mean[col] = a.m;
         var[col] = a.q / (float)N;
     }
@@ -244,8 +247,8 @@ gnn_status gnn_batchnorm(const float *d_x, int32_t num_rows, int32_t feat_dim, c
         hipLaunchKernelGGL(column_moments_partial_kernel, dim3((unsigned)chunks), dim3(kThreads), 0, s, d_x, N, F,
                            rows_per_chunk, part_m, part_q);
         GNN_LAUNCH_CHECK();
-        hipLaunchKernelGGL(column_moments_merge_kernel, dim3((unsigned)gnn_div_up(F, 64)), dim3(64 * kMergeSlices), 0, s,
-                           part_m, part_q, chunks, N, rows_per_chunk, F, d_mean, d_var);
+        hipLaunchKernelGGL(column_moments_merge_kernel, dim3((unsigned)gnn_div_up(F, kMergeCols)), dim3(kMergeThreads), 0,
+                           s, part_m, part_q, chunks, N, rows_per_chunk, F, d_mean, d_var);
         GNN_LAUNCH_CHECK();
     }
     const int blocks = (int)std::min<int64_t>(gnn_div_up(N * F, kThreads), 256 * 64);
