@@ -124,7 +124,9 @@ __device__ __forceinline__ void wave_run_bounds(const int32_t *__restrict__ gi, 
 // Batches of small graphs: one wavefront per graph (four graphs per block), no block-wide barriers.  The run's
 // bounds come from the same interleaved search with 64 probes per round; lanes are (node slot, feature lane),
 // node slots stride over the run and are combined by a fixed xor-shuffle tree.
-template <bool MAX>
+// VEC = 4: a feature lane holds four neighbouring columns (128-bit loads; F % 4 == 0, rows 16-byte aligned), which
+// leaves four times as many node slots per wavefront.
+template <bool MAX, int VEC>
 __global__ __launch_bounds__(kThreads) void pool_wave_kernel(const int32_t *__restrict__ gi, int32_t N,
                                                              const float *__restrict__ x, int32_t F,
                                                              int32_t lanes /* power of two <= 64 */, int mean,
@@ -137,24 +139,40 @@ __global__ __launch_bounds__(kThreads) void pool_wave_kernel(const int32_t *__re
     wave_run_bounds(gi, N, g, lane, &lo, &hi);
     const int cnt = hi - lo;
     const int fl = lane % lanes, slot = lane / lanes, slots = 64 / lanes;
-    for (int f0 = 0; f0 < F; f0 += lanes) {
+    const int fv = F / VEC;   // column groups
+    for (int f0 = 0; f0 < fv; f0 += lanes) {
         const int f = f0 + fl;
-        float acc = MAX ? -INFINITY : 0.0f;
-        if (f < F) {
+        float acc[VEC];
+#pragma unroll
+        for (int c = 0; c < VEC; ++c) acc[c] = MAX ? -INFINITY : 0.0f;
+        if (f < fv) {
 #pragma unroll 4
             for (int i = lo + slot; i < hi; i += slots) {
-                const float v = x[(int64_t)i * F + f];
-                acc = MAX ? max_pz(acc, v) : acc + v;
+                float v[VEC];
+                if constexpr (VEC == 4) {
+                    const float4 t = *reinterpret_cast<const float4 *>(x + (int64_t)i * F + f * 4);
+                    v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+                } else {
+                    v[0] = x[(int64_t)i * F + f];
+                }
+#pragma unroll
+                for (int c = 0; c < VEC; ++c) acc[c] = MAX ? max_pz(acc[c], v[c]) : acc[c] + v[c];
             }
         }
         for (int off = lanes; off < 64; off <<= 1) {
-            const float other = __shfl_xor(acc, off, 64);
-            acc = MAX ? max_pz(acc, other) : acc + other;
+#pragma unroll
+            for (int c = 0; c < VEC; ++c) {
+                const float other = __shfl_xor(acc[c], off, 64);
+                acc[c] = MAX ? max_pz(acc[c], other) : acc[c] + other;
+            }
         }
-        if (slot == 0 && f < F) {
-            if (cnt == 0) acc = 0.0f;
-            if (mean && cnt > 0) acc = acc / (float)cnt;
-            out[(int64_t)g * F + f] = acc;
+        if (slot == 0 && f < fv) {
+#pragma unroll
+            for (int c = 0; c < VEC; ++c) {
+                if (cnt == 0) acc[c] = 0.0f;
+                if (mean && cnt > 0) acc[c] = acc[c] / (float)cnt;
+                out[(int64_t)g * F + f * VEC + c] = acc[c];
+            }
         }
     }
 }
@@ -191,11 +209,24 @@ __global__ __launch_bounds__(kThreads) void pool_backward_wave_kernel(const int3
     wave_run_bounds(gi, N, g, lane, &lo, &hi);
     const int cnt = hi - lo;
     if (cnt <= 0) return;
-    const int64_t total = (int64_t)cnt * F;
-    for (int64_t q = lane; q < total; q += 64) {
-        const int f = (int)(q % F);
-        const float v = gout[(int64_t)g * F + f];
-        gx[(int64_t)lo * F + q] = mean ? v / (float)cnt : v;
+    const bool vec4 = F % 4 == 0 && ((reinterpret_cast<uintptr_t>(gout) | reinterpret_cast<uintptr_t>(gx)) & 15u) == 0;
+    if (vec4) {
+        const int fv = F / 4;
+        const int64_t total = (int64_t)cnt * fv;
+#pragma unroll 4
+        for (int64_t q = lane; q < total; q += 64) {
+            const int f = (int)(q % fv);
+            const float4 v = *reinterpret_cast<const float4 *>(gout + (int64_t)g * F + f * 4);
+            *reinterpret_cast<float4 *>(gx + (int64_t)lo * F + q * 4) =
+                mean ? make_float4(v.x / (float)cnt, v.y / (float)cnt, v.z / (float)cnt, v.w / (float)cnt) : v;
+        }
+    } else {
+        const int64_t total = (int64_t)cnt * F;
+        for (int64_t q = lane; q < total; q += 64) {
+            const int f = (int)(q % F);
+            const float v = gout[(int64_t)g * F + f];
+            gx[(int64_t)lo * F + q] = mean ? v / (float)cnt : v;
+        }
     }
 }
 
@@ -233,15 +264,26 @@ extern "C" gnn_status gnn_graph_pool(const int32_t *d_graph_indicator, int32_t n
     const int mean = aggr == GNN_AGGR_MEAN ? 1 : 0;
     // many small graphs: a wavefront each (with few graphs the block-per-graph kernel has more loads in flight)
     if ((int64_t)num_nodes <= (int64_t)num_graphs * kSmallGraphNodes && num_graphs >= kManyGraphs) {
+        const bool vec4 = feat_dim % 4 == 0 && (reinterpret_cast<uintptr_t>(d_x) & 15u) == 0;
+        const int groups = vec4 ? feat_dim / 4 : feat_dim;
         int lanes = 1;
-        while (lanes < feat_dim && lanes < 64) lanes <<= 1;
+        while (lanes < groups && lanes < 64) lanes <<= 1;
         const dim3 grid((unsigned)gnn_div_up(num_graphs, kThreads / 64));
-        if (aggr == GNN_AGGR_MAX)
-            hipLaunchKernelGGL(pool_wave_kernel<true>, grid, dim3(kThreads), 0, s, d_graph_indicator, num_nodes, d_x,
-                               feat_dim, lanes, 0, num_graphs, d_out);
-        else
-            hipLaunchKernelGGL(pool_wave_kernel<false>, grid, dim3(kThreads), 0, s, d_graph_indicator, num_nodes, d_x,
-                               feat_dim, lanes, mean, num_graphs, d_out);
+        if (aggr == GNN_AGGR_MAX) {
+            if (vec4)
+                hipLaunchKernelGGL((pool_wave_kernel<true, 4>), grid, dim3(kThreads), 0, s, d_graph_indicator, num_nodes,
+                                   d_x, feat_dim, lanes, 0, num_graphs, d_out);
+            else
+                hipLaunchKernelGGL((pool_wave_kernel<true, 1>), grid, dim3(kThreads), 0, s, d_graph_indicator, num_nodes,
+                                   d_x, feat_dim, lanes, 0, num_graphs, d_out);
+        } else {
+            if (vec4)
+                hipLaunchKernelGGL((pool_wave_kernel<false, 4>), grid, dim3(kThreads), 0, s, d_graph_indicator, num_nodes,
+                                   d_x, feat_dim, lanes, mean, num_graphs, d_out);
+            else
+                hipLaunchKernelGGL((pool_wave_kernel<false, 1>), grid, dim3(kThreads), 0, s, d_graph_indicator, num_nodes,
+                                   d_x, feat_dim, lanes, mean, num_graphs, d_out);
+        }
         GNN_LAUNCH_CHECK();
         return GNN_OK;
     }
