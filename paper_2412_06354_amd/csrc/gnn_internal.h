@@ -144,6 +144,11 @@ gnn_status gnn_launch_xty(const float *d_x, const float *d_y, int64_t rows, int 
 gnn_status gnn_launch_sum_partials(const float *d_partial, int chunks, int64_t elems, float *d_out,
                                    hipStream_t stream);
 // wt[cols x rows] = w[rows x cols]^T
+// Backward of sum / mean pooling; d_relu_y (optional, [N x F]) = the pooled rows when they were relu outputs: the
+// relu's backward rides in the same pass (pool.hip).
+gnn_status gnn_launch_pool_backward(const int32_t *d_graph_indicator, int32_t num_nodes, int32_t num_graphs,
+                                    const float *d_grad_out, int32_t feat_dim, gnn_aggr aggr, const float *d_relu_y,
+                                    float *d_grad_x, hipStream_t stream);
 // Z = X W with the store's epilogue: optional per-row scale, then per-column bias, then relu (gemm.hip).
 gnn_status gnn_launch_xw(const float *d_x, int64_t rows, int32_t k, const float *d_w, int32_t n,
                          const float *d_row_scale, const float *d_bias, bool relu, float *d_z, hipStream_t s);

@@ -179,8 +179,11 @@ __global__ __launch_bounds__(kThreads) void pool_wave_kernel(const int32_t *__re
 
 // Backward of sum / mean pooling: every node of graph g receives gout[g,:] (divided by the node count for
 // the mean).  One block per graph, same run search as the forward kernel; rows are written coalesced.
+// relu_y (optional, [N x F]): the pooled rows were relu outputs; the gradient is zeroed where they are not positive
+// (the relu's backward in the same pass).
 __global__ __launch_bounds__(kThreads) void pool_backward_kernel(const int32_t *__restrict__ gi, int32_t N,
                                                                  const float *__restrict__ gout, int32_t F, int mean,
+                                                                 const float *__restrict__ relu_y,
                                                                  float *__restrict__ gx)
 {
     const int g = blockIdx.x;
@@ -191,8 +194,10 @@ __global__ __launch_bounds__(kThreads) void pool_backward_kernel(const int32_t *
     const int64_t total = (int64_t)cnt * F;
     for (int64_t q = threadIdx.x; q < total; q += kThreads) {
         const int f = (int)(q % F);
-        const float v = gout[(int64_t)g * F + f];
-        gx[(int64_t)lo * F + q] = mean ? v / (float)cnt : v;
+        float v = gout[(int64_t)g * F + f];
+        if (mean) v = v / (float)cnt;
+        if (relu_y) v = relu_y[(int64_t)lo * F + q] > 0.0f ? v : 0.0f;
+        gx[(int64_t)lo * F + q] = v;
     }
 }
 
@@ -200,6 +205,7 @@ __global__ __launch_bounds__(kThreads) void pool_backward_kernel(const int32_t *
 __global__ __launch_bounds__(kThreads) void pool_backward_wave_kernel(const int32_t *__restrict__ gi, int32_t N,
                                                                       const float *__restrict__ gout, int32_t F,
                                                                       int mean, int32_t num_graphs,
+                                                                      const float *__restrict__ relu_y,
                                                                       float *__restrict__ gx)
 {
     const int lane = threadIdx.x & 63;
@@ -209,48 +215,64 @@ __global__ __launch_bounds__(kThreads) void pool_backward_wave_kernel(const int3
     wave_run_bounds(gi, N, g, lane, &lo, &hi);
     const int cnt = hi - lo;
     if (cnt <= 0) return;
-    const bool vec4 = F % 4 == 0 && ((reinterpret_cast<uintptr_t>(gout) | reinterpret_cast<uintptr_t>(gx)) & 15u) == 0;
-    if (vec4) {
+    uintptr_t align = reinterpret_cast<uintptr_t>(gout) | reinterpret_cast<uintptr_t>(gx);
+    if (relu_y) align |= reinterpret_cast<uintptr_t>(relu_y);
+    if (F % 4 == 0 && (align & 15u) == 0) {
         const int fv = F / 4;
         const int64_t total = (int64_t)cnt * fv;
 #pragma unroll 4
         for (int64_t q = lane; q < total; q += 64) {
             const int f = (int)(q % fv);
-            const float4 v = *reinterpret_cast<const float4 *>(gout + (int64_t)g * F + f * 4);
-            *reinterpret_cast<float4 *>(gx + (int64_t)lo * F + q * 4) =
-                mean ? make_float4(v.x / (float)cnt, v.y / (float)cnt, v.z / (float)cnt, v.w / (float)cnt) : v;
+            float4 v = *reinterpret_cast<const float4 *>(gout + (int64_t)g * F + f * 4);
+            if (mean) v = make_float4(v.x / (float)cnt, v.y / (float)cnt, v.z / (float)cnt, v.w / (float)cnt);
+            if (relu_y) {
+                const float4 y = *reinterpret_cast<const float4 *>(relu_y + (int64_t)lo * F + q * 4);
+                v = make_float4(y.x > 0.0f ? v.x : 0.0f, y.y > 0.0f ? v.y : 0.0f, y.z > 0.0f ? v.z : 0.0f,
+                                y.w > 0.0f ? v.w : 0.0f);
+            }
+            *reinterpret_cast<float4 *>(gx + (int64_t)lo * F + q * 4) = v;
         }
     } else {
         const int64_t total = (int64_t)cnt * F;
         for (int64_t q = lane; q < total; q += 64) {
             const int f = (int)(q % F);
-            const float v = gout[(int64_t)g * F + f];
-            gx[(int64_t)lo * F + q] = mean ? v / (float)cnt : v;
+            float v = gout[(int64_t)g * F + f];
+            if (mean) v = v / (float)cnt;
+            if (relu_y) v = relu_y[(int64_t)lo * F + q] > 0.0f ? v : 0.0f;
+            gx[(int64_t)lo * F + q] = v;
         }
     }
 }
 
 }  // namespace
 
-extern "C" gnn_status gnn_graph_pool_backward(const int32_t *d_graph_indicator, int32_t num_nodes, int32_t num_graphs,
-                                              const float *d_grad_out, int32_t feat_dim, gnn_aggr aggr,
-                                              float *d_grad_x, void *stream)
+gnn_status gnn_launch_pool_backward(const int32_t *d_graph_indicator, int32_t num_nodes, int32_t num_graphs,
+                                    const float *d_grad_out, int32_t feat_dim, gnn_aggr aggr, const float *d_relu_y,
+                                    float *d_grad_x, hipStream_t stream)
 {
     if (num_nodes < 0 || num_graphs <= 0 || feat_dim <= 0) return GNN_ERR_BAD_SIZE;
     if (aggr == GNN_AGGR_MAX || aggr == GNN_AGGR_MIN || aggr == GNN_AGGR_PROD) return GNN_ERR_UNSUPPORTED;
     if (aggr != GNN_AGGR_SUM && aggr != GNN_AGGR_MEAN) return GNN_ERR_BAD_SIZE;
     if (num_nodes == 0) return GNN_OK;
     if (!d_graph_indicator || !d_grad_out || !d_grad_x) return GNN_ERR_NULL;
+    const int mean = aggr == GNN_AGGR_MEAN ? 1 : 0;
     if ((int64_t)num_nodes <= (int64_t)num_graphs * kSmallGraphNodes && num_graphs >= kManyGraphs)
         hipLaunchKernelGGL(pool_backward_wave_kernel, dim3((unsigned)gnn_div_up(num_graphs, kThreads / 64)),
-                           dim3(kThreads), 0, static_cast<hipStream_t>(stream), d_graph_indicator, num_nodes,
-                           d_grad_out, feat_dim, aggr == GNN_AGGR_MEAN ? 1 : 0, num_graphs, d_grad_x);
+                           dim3(kThreads), 0, stream, d_graph_indicator, num_nodes, d_grad_out, feat_dim, mean,
+                           num_graphs, d_relu_y, d_grad_x);
     else
-        hipLaunchKernelGGL(pool_backward_kernel, dim3((unsigned)num_graphs), dim3(kThreads), 0,
-                           static_cast<hipStream_t>(stream), d_graph_indicator, num_nodes, d_grad_out, feat_dim,
-                           aggr == GNN_AGGR_MEAN ? 1 : 0, d_grad_x);
+        hipLaunchKernelGGL(pool_backward_kernel, dim3((unsigned)num_graphs), dim3(kThreads), 0, stream,
+                           d_graph_indicator, num_nodes, d_grad_out, feat_dim, mean, d_relu_y, d_grad_x);
     GNN_LAUNCH_CHECK();
     return GNN_OK;
+}
+
+extern "C" gnn_status gnn_graph_pool_backward(const int32_t *d_graph_indicator, int32_t num_nodes, int32_t num_graphs,
+                                              const float *d_grad_out, int32_t feat_dim, gnn_aggr aggr,
+                                              float *d_grad_x, void *stream)
+{
+    return gnn_launch_pool_backward(d_graph_indicator, num_nodes, num_graphs, d_grad_out, feat_dim, aggr, nullptr,
+                                    d_grad_x, static_cast<hipStream_t>(stream));
 }
 
 extern "C" gnn_status gnn_graph_pool(const int32_t *d_graph_indicator, int32_t num_nodes, int32_t num_graphs,

@@ -445,8 +445,8 @@ gnn_status gnn_example_model_train_step(const gnn_graph *g, const gnn_graph *g_b
     // loss and the chain rule in reverse
     GNN_TRY(gnn_mse_loss(y, d_target, (int64_t)num_graphs * f3, d_loss, gy, stream));
     GNN_TRY(gnn_dense_backward(pooled, num_graphs, f2, w3, f3, gy, gpooled, gw3, gb3, dense_b, dense_b_bytes, stream));
-    GNN_TRY(gnn_graph_pool_backward(d_graph_indicator, N, num_graphs, gpooled, f2, GNN_AGGR_MEAN, gh3, stream));
-    GNN_TRY(gnn_relu_backward(h3, gh3, (int64_t)N * f2, gh3, stream));
+    // pooling backward with the second layer's relu mask in the same pass
+    GNN_TRY(gnn_launch_pool_backward(d_graph_indicator, N, num_graphs, gpooled, f2, GNN_AGGR_MEAN, h3, gh3, s));
     GNN_TRY(gnn_gcnconv_backward(g, g_by_source, h2, f1, w2, f2, 1, gh3, gh2, gw2, gb2, gcn_b, gcn_b_bytes, stream));
     GNN_TRY(gnn_batchnorm_backward(h1, N, f1, gamma, mean, var, bn_eps, gh2, h2, gh1, ggamma, gbeta, bn, bn_bytes,
                                    stream));
