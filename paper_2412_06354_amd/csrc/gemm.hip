@@ -2,9 +2,8 @@
 // inside GCNConv and the GAT layer (layers named in the paper, section 3).  X is tall and
 // skinny ([rows x k], k ~ 100), W is small ([k x n], n <= a few hundred).
 //
-// A tile is 128 rows x BN columns, worked on by a block of 4 wavefronts; each wavefront owns 32
-// rows and BN/32 accumulator tiles of v_mfma_f32_32x32x2_f32.  X fragments go from global memory
-// straight to registers, 64 k-values ("sub-slab") at a time: the lane (r = lane % 32, half = lane / 32)
+// A wavefront owns 32 rows and BN/32 accumulator tiles of v_mfma_f32_32x32x2_f32.  X fragments go from global
+// memory straight to registers, 64 k-values ("sub-slab") at a time: the lane (r = lane % 32, half = lane / 32)
 // reads the 32 consecutive floats X[row0 + r][k0 + 32*half ..] -- one full 128-byte line per lane,
 // eight 128-bit loads issued back to back -- and feeds value j of its s-th group of four to MFMA
 // (s, j), whose B operand is W[k0 + 32*half + 4*s + j][col].  The k order inside a sub-slab is thus
@@ -13,9 +12,14 @@
 // one 128-bit LDS read; the 16-byte groups of a column are xor-swizzled with (col % 8) so that the
 // lanes of a read (same group, consecutive columns) fall into different banks without padding.
 //
-// Fast kernel (k <= 128, k and n multiples of 4): blocks are persistent, stage their column block of W once,
-// then walk over row tiles.
-// General kernel (any shape, ragged edges): one tile per block, W re-staged per 64-k slab.
+// Fast kernel (k <= 128, k and n multiples of 4): one block of twelve wavefronts per compute unit stages its
+// columns of W once, then every wavefront walks over 32-row tiles.
+// General kernel (any shape, ragged edges): one 128-row tile per block of four wavefronts, W re-staged per 64-k slab.
+//
+// What the direct global-to-register path costs (timestamps taken inside the fast kernel at the GCN size): the
+// address unit takes a 128-bit load whose lanes lie in different rows at about one lane per cycle, so issuing the
+// sixteen loads of a tile for twelve wavefronts keeps a compute unit busy for 8-9 us before the first MFMA --
+// whether the two halves of a wavefront share lines or not (both layouts were measured).
 #include "gnn_internal.h"
 
 #include <algorithm>
