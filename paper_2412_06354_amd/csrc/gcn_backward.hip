@@ -336,7 +336,7 @@ gnn_status gnn_launch_xty(const float *d_x, const float *d_y, int64_t rows, int 
     const int chunks = gnn_row_chunk_count(rows);
     if (f_out <= 32) GNN_TRY(launch_xty_tiles<1>(d_x, d_y, rows, f_in, f_out, chunks, d_partial, s));
     else if (f_out <= 64) GNN_TRY(launch_xty_tiles<2>(d_x, d_y, rows, f_in, f_out, chunks, d_partial, s));
-    else GNN_TRY(launch_xty_tiles<4>(d_x, d_y, rows, f_in, f_out, chunks, d_partial, s));
+    else GNN_TRY(launch_xty_tiles<2>(d_x, d_y, rows, f_in, f_out, chunks, d_partial, s));   // wider: 64-column blocks
     return gnn_launch_sum_partials(d_partial, chunks, (int64_t)f_in * f_out, d_out, s);
 }
 
