@@ -26,6 +26,13 @@
  *
  * All device work runs on the device that is current when gnn_build_csr is
  * called; the caller keeps that device current for later calls on the graph.
+ *
+ * Concurrency: a graph handle carries scratch memory for rows that are split over several wavefronts
+ * (allocated on first use, reused afterwards), so compute calls on ONE handle must not overlap: issue them
+ * on one stream, or order them with events.  Calls on different handles are independent and may come from
+ * different host threads; the process-wide buffer that graph builds share is handed to one build at a time
+ * (a concurrent build allocates its own temporaries).  Caller-provided workspaces follow the same rule as
+ * the handle: one call at a time per workspace.
  */
 #ifndef GNN_MI355X_H
 #define GNN_MI355X_H
