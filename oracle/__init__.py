@@ -322,6 +322,17 @@ def round_bf16(x):
     return codes.reshape(x.shape), wide.reshape(x.shape)
 
 
+def round_f16(x):
+    """-> (codes uint16, widened float32): finite floats rounded to IEEE binary16, ties to even."""
+    x = _f32(x, "x")
+    flat = np.ascontiguousarray(x.reshape(-1))
+    codes = np.empty(flat.shape, np.uint16)
+    wide = np.empty(flat.shape, np.float32)
+    rc = _load().oracle_round_f16(_p(flat), ctypes.c_int64(flat.shape[0]), _p(codes), _p(wide))
+    _check(rc, "round_f16")
+    return codes.reshape(x.shape), wide.reshape(x.shape)
+
+
 def hetero_propagate(relations, num_dst_nodes: int, msg: int = MSG_COPY_XJ, aggr: int = AGGR_SUM,
                      with_sabs: bool = False):
     """Sum over the relations that end in one destination node type of each relation's propagate.

@@ -914,6 +914,50 @@ int oracle_round_bf16(const float *x, int64_t n, uint16_t *codes, float *widened
 }
 
 /*
+ * Rounding of finite floats to IEEE 754 binary16 ("half": 1 sign, 5 exponent, 10 fraction bits; the 16-bit
+ * feature storage named next to bfloat16 among the next steps), round to nearest, ties to even, written
+ * from the definition: inside the binade 2^e <= |x| < 2^(e+1) (e clamped to -14, the subnormal range) the
+ * representable values are n * 2^(e-10) for whole n; |x| / 2^(e-10) is exact in double, its two whole neighbours
+ * are compared by distance, a tie goes to the even n.  |x| >= 65520 (half way from the largest finite value
+ * 65504 to 2^16) gives infinity.  codes / widened may be NULL.
+ */
+int oracle_round_f16(const float *x, int64_t n_values, uint16_t *codes, float *widened)
+{
+    if (n_values < 0) return 2;
+    for (int64_t i = 0; i < n_values; ++i) {
+        const double v = (double)x[i], a = fabs(v);
+        const uint16_t sign = signbit(x[i]) ? 0x8000u : 0u;
+        uint16_t code;
+        double back;
+        if (a >= 65520.0) {
+            code = 0x7C00u;
+            back = INFINITY;
+        } else {
+            int e = -14;
+            if (a >= ldexp(1.0, -14)) {
+                (void)frexp(a, &e);   /* a = f * 2^e with 0.5 <= f < 1 */
+                e -= 1;
+            }
+            const double q = ldexp(1.0, e - 10), k = a / q;
+            double lo = floor(k);
+            const double frac = k - lo;
+            if (frac > 0.5 || (frac == 0.5 && fmod(lo, 2.0) == 1.0)) lo += 1.0;
+            int64_t nn = (int64_t)lo;   /* 0 .. 2048 */
+            if (nn == 2048) {
+                nn = 1024;
+                e += 1;
+            }
+            back = (double)nn * ldexp(1.0, e - 10);
+            if (nn < 1024) code = (uint16_t)nn;                                   /* subnormal or zero (e = -14) */
+            else code = (uint16_t)(((e + 15) << 10) | (int)(nn - 1024));
+        }
+        if (codes) codes[i] = (uint16_t)(sign | code);
+        if (widened) widened[i] = (float)(sign ? -back : back);
+    }
+    return 0;
+}
+
+/*
  * Backward passes of the example model's dense-side layers (the training example differentiates the
  * whole chain, section 3 "Training Example").  All in double, rounded once per output.
  *

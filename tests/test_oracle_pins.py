@@ -708,6 +708,30 @@ def test_bf16_rounding(golden_dir):
     np.testing.assert_array_equal(oracle.round_bf16(wide)[1], wide)
 
 
+def test_f16_rounding(golden_dir):
+    """Hand-worked bit patterns (ties, both ends of the subnormal range, overflow), numpy's own float16 conversion
+    on random floats over the whole range (an independent IEEE implementation), and the defining property."""
+    gd = load_golden(golden_dir, "f16_rounding.json")
+    bits = np.array([int(c["float_bits"], 16) for c in gd["cases"]], np.uint32)
+    codes, wide = oracle.round_f16(bits.view(np.float32))
+    np.testing.assert_array_equal(codes, np.array([int(c["f16"], 16) for c in gd["cases"]], np.uint16))
+    x = (synth.normal_f32(98, 2, 50000) * np.float32(10.0) ** synth.randint(98, 3, 0, 50000, -10, 6)).astype(np.float32)
+    codes, wide = oracle.round_f16(x)
+    with np.errstate(over="ignore"):
+        ref = x.astype(np.float16)
+    np.testing.assert_array_equal(codes, ref.view(np.uint16))
+    np.testing.assert_array_equal(wide.view(np.uint32), ref.astype(np.float32).view(np.uint32))
+    # nearest: no representable value is closer (neighbouring codes of the same sign, where finite)
+    fin = np.isfinite(wide) & (np.abs(x) < 60000)
+    mag = (codes & 0x7FFF).astype(np.int32)
+    for step in (-1, 1):
+        nb = np.clip(mag + step, 0, 0x7BFF).astype(np.uint16) | (codes & 0x8000)
+        nbv = nb.view(np.float16).astype(np.float64)
+        assert (np.abs(wide[fin].astype(np.float64) - x[fin]) <= np.abs(nbv[fin] - x[fin])).all()
+    # representable values are fixed points
+    np.testing.assert_array_equal(oracle.round_f16(wide[fin])[1], wide[fin])
+
+
 def _hetero_relations(seed, n_dst, sizes, edges, f):
     rels = []
     for r, (ns, ne) in enumerate(zip(sizes, edges)):
