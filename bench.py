@@ -167,6 +167,12 @@ def run_propagate(args, torch, gnn, synth):
                 b = e * (2 * f + 4 + 4 * msg) + n * 4 * f + (n + 1) * 4
                 extra[name] = {"ms": t, "GBs_alg": b / (t * 1e-3) / 1e9, "edge_feature_per_s": e * f / (t * 1e-3)}
             del xh
+            xh = gnn.f32_to_f16(x)      # IEEE binary16 storage: the same kernels with another widening
+            t = time_calls(torch, lambda: gnn.propagate_f16(g, xh, None, 0, 0, out=out), k, 3)
+            b = e * (2 * f + 4) + n * 4 * f + (n + 1) * 4
+            extra["f16_storage_copy_xj_sum"] = {"ms": t, "GBs_alg": b / (t * 1e-3) / 1e9,
+                                                "edge_feature_per_s": e * f / (t * 1e-3)}
+            del xh
         extra["edge_data_to_csr_ms"] = time_calls(torch, lambda: gnn.edge_data_to_csr(g, ew), k, 2)
         t0 = time.perf_counter()
         for _ in range(3):

@@ -187,11 +187,19 @@ gnn_status gnn_hetero_propagate(int32_t num_relations, const gnn_graph *const *g
  * MEAN or MAX; anything else GNN_ERR_UNSUPPORTED, as are feat_dim % 8 != 0 or pointers that are not
  * 16-byte aligned.  d_x_bf16 [N x feat_dim] uint16, d_out [N x feat_dim] float.
  * gnn_f32_to_bf16 converts finite floats with round-to-nearest-even (ties to the even 16-bit code).
+ *
+ * gnn_propagate_f16 / gnn_f32_to_f16: the same with IEEE binary16 storage (1 sign, 5 exponent, 10 fraction
+ * bits; subnormals kept, |x| >= 65520 becomes infinity in the conversion -- features are expected to lie
+ * inside the format's range, and propagate itself takes finite values only).
  */
 gnn_status gnn_propagate_bf16(const gnn_graph *g, const uint16_t *d_x_bf16, int32_t feat_dim,
                               const float *d_e, gnn_edge_order e_order, gnn_msg_op msg, gnn_aggr aggr,
                               float *d_out, void *stream);
 gnn_status gnn_f32_to_bf16(const float *d_in, int64_t count, uint16_t *d_out, void *stream);
+gnn_status gnn_propagate_f16(const gnn_graph *g, const uint16_t *d_x_f16, int32_t feat_dim,
+                             const float *d_e, gnn_edge_order e_order, gnn_msg_op msg, gnn_aggr aggr,
+                             float *d_out, void *stream);
+gnn_status gnn_f32_to_f16(const float *d_in, int64_t count, uint16_t *d_out, void *stream);
 
 /*
  * The two un-fused primitives of the paper's listing (section 3, "Message Passing"):

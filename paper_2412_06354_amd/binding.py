@@ -44,6 +44,8 @@ SIGNATURES = {
     "gnn_release_cached_memory": (_c.c_int, []),
     "gnn_propagate_bf16": (_c.c_int, [_vp, _vp, _i32, _vp, _c.c_int, _c.c_int, _c.c_int, _vp, _vp]),
     "gnn_f32_to_bf16": (_c.c_int, [_vp, _i64, _vp, _vp]),
+    "gnn_propagate_f16": (_c.c_int, [_vp, _vp, _i32, _vp, _c.c_int, _c.c_int, _c.c_int, _vp, _vp]),
+    "gnn_f32_to_f16": (_c.c_int, [_vp, _i64, _vp, _vp]),
     "gnn_apply_edges": (_c.c_int, [_vp, _vp, _i32, _vp, _i32, _c.c_int, _c.c_int, _vp, _c.c_int, _vp]),
     "gnn_aggregate_neighbors": (_c.c_int, [_vp, _vp, _i32, _c.c_int, _c.c_int, _vp, _vp]),
     "gnn_propagate_backward_workspace_bytes": (_sz, [_i32, _i32, _c.c_int]),
@@ -306,6 +308,32 @@ def propagate_bf16(g: Graph, x_bf16: torch.Tensor, e: Optional[torch.Tensor] = N
     rc = lib().gnn_propagate_bf16(g._h, _dev(x_bf16, torch.int16, "x_bf16"), f, _dev(e, torch.float32, "e"), e_order,
                                   msg, aggr, _dev(out, torch.float32, "out"), _stream())
     _check(rc, "gnn_propagate_bf16")
+    return out
+
+
+def f32_to_f16(x: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """float32 -> IEEE binary16 codes (an int16 tensor holding the 16-bit patterns), round to nearest even."""
+    if out is None:
+        out = torch.empty(x.shape, dtype=torch.int16, device=x.device)
+    rc = lib().gnn_f32_to_f16(_dev(x, torch.float32, "x"), x.numel(), _dev(out, torch.int16, "out"), _stream())
+    _check(rc, "gnn_f32_to_f16")
+    return out
+
+
+def propagate_f16(g: Graph, x_f16: torch.Tensor, e: Optional[torch.Tensor] = None, msg: int = MSG_COPY_XJ,
+                  aggr: int = AGGR_SUM, e_order: int = EDGE_ORDER_COO,
+                  out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """x_f16: [N, F] int16 tensor of binary16 codes (from f32_to_f16, or a torch.float16 tensor viewed as int16)."""
+    n, f = x_f16.shape
+    if n != g.num_nodes:
+        raise ValueError("x must have one row per node")
+    if e is not None and e.numel() != g.num_edges:
+        raise ValueError("one weight per edge")
+    if out is None:
+        out = torch.empty((n, f), dtype=torch.float32, device=x_f16.device)
+    rc = lib().gnn_propagate_f16(g._h, _dev(x_f16, torch.int16, "x_f16"), f, _dev(e, torch.float32, "e"), e_order,
+                                 msg, aggr, _dev(out, torch.float32, "out"), _stream())
+    _check(rc, "gnn_propagate_f16")
     return out
 
 

@@ -117,16 +117,16 @@ __device__ __forceinline__ void store_row_stream(float *__restrict__ p, const Ro
     }
 }
 
-// Features x[elem ..].  XB = 1: the array holds bfloat16 (the upper half of a float), eight per 128-bit
-// load; load_x only issues the load and keeps the four raw words (so that the loads of several edges stay
-// in flight together), x_value widens value c exactly when it is used.  Sums and results stay in float.
+// Features x[elem ..].  XB = 1: the array holds bfloat16 (the upper half of a float), XB = 2: IEEE binary16,
+// eight per 128-bit load; load_x only issues the load and keeps the four raw words (so that the loads of several
+// edges stay in flight together), x_value widens value c exactly when it is used.  Sums and results stay in float.
 template <int VEC, int XB>
 __device__ __forceinline__ void load_x(Row<VEC> &r, const float *__restrict__ x, int64_t elem)
 {
     if constexpr (XB == 0) {
         load_row<VEC>(r, x + elem);
     } else {
-        static_assert(VEC == 8, "bfloat16 rows are read eight values at a time");
+        static_assert(VEC == 8, "16-bit rows are read eight values at a time");
         const v4f w = *reinterpret_cast<const v4f *>(reinterpret_cast<const uint16_t *>(x) + elem);
         r.v[0] = w.x; r.v[1] = w.y; r.v[2] = w.z; r.v[3] = w.w;
     }
@@ -139,7 +139,14 @@ __device__ __forceinline__ float x_value(const Row<VEC> &r, int c)
         return r.v[c];
     } else {
         const uint32_t w = __float_as_uint(r.v[c >> 1]);
-        return __uint_as_float((c & 1) ? (w & 0xffff0000u) : (w << 16));
+        if constexpr (XB == 1) {
+            return __uint_as_float((c & 1) ? (w & 0xffff0000u) : (w << 16));
+        } else {
+            // binary16 -> binary32 is exact: the hardware conversion (subnormal halves included: kernels are
+            // built with 16-bit denormals enabled, and the parity tests cover them bit for bit)
+            const uint16_t h = (uint16_t)((c & 1) ? (w >> 16) : (w & 0xffffu));
+            return (float)__builtin_bit_cast(_Float16, h);
+        }
     }
 }
 
@@ -545,17 +552,53 @@ __global__ __launch_bounds__(kThreads) void f32_to_bf16_kernel(const float *__re
     }
 }
 
-// bfloat16 feature storage: copy_xj / one weight per edge, sum (mean) / max.
-template <int LPR>
-gnn_status launch_shape_bf16(const PropParams &p, int msg, int red, hipStream_t stream)
+// Round-to-nearest-even conversion of finite floats to IEEE binary16 with integer operations (and one float add in
+// the default rounding mode for the subnormal range): |x| >= 65520 gives infinity, |x| < 2^-14 a subnormal code
+// n = round(|x| * 2^24), else the float's 23-bit fraction is rounded to 10 bits and the exponent rebiased.
+__global__ __launch_bounds__(kThreads) void f32_to_f16_kernel(const float *__restrict__ in, int64_t n,
+                                                              uint16_t *__restrict__ out)
+{
+    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += stride) {
+        const uint32_t u = __float_as_uint(in[i]);
+        const uint32_t sign = (u >> 16) & 0x8000u, a = u & 0x7fffffffu;
+        uint32_t code;
+        if (a >= 0x477ff000u) {            // 65520
+            code = 0x7c00u;
+        } else if (a < 0x38800000u) {      // below 2^-14: whole multiples of 2^-24
+            // the fraction bits of |x| + 0.5 (for |x| < 2^-14 < 0.5 the sum lies in [0.5, 1), spacing 2^-24) are
+            // |x| rounded to a multiple of 2^-24 by the float adder itself: round to nearest, ties to even
+            // (fraction of 0.5 is zero, i.e. even)
+            const float t = __uint_as_float(a) + 0.5f;
+            code = __float_as_uint(t) - 0x3f000000u;   // = n, 0 .. 1024 (1024 = 0x0400 is the smallest normal)
+        } else {
+            const uint32_t r = a + 0xfffu + ((a >> 13) & 1u);
+            code = (r >> 13) - (112u << 10);
+        }
+        out[i] = (uint16_t)(sign | code);
+    }
+}
+
+// 16-bit feature storage (XB = 1 bfloat16, 2 binary16): copy_xj / one weight per edge, sum (mean) / max.
+template <int LPR, int XB>
+gnn_status launch_shape_16bit(const PropParams &p, int msg, int red, hipStream_t stream)
 {
     switch (msg * 4 + red) {
-    case kMsgCopy * 4 + kRedSum: return launch_typed<LPR, 8, kMsgCopy, kRedSum, 1>(p, stream);
-    case kMsgCopy * 4 + kRedMax: return launch_typed<LPR, 8, kMsgCopy, kRedMax, 1>(p, stream);
-    case kMsgMulScalar * 4 + kRedSum: return launch_typed<LPR, 8, kMsgMulScalar, kRedSum, 1>(p, stream);
-    case kMsgMulScalar * 4 + kRedMax: return launch_typed<LPR, 8, kMsgMulScalar, kRedMax, 1>(p, stream);
+    case kMsgCopy * 4 + kRedSum: return launch_typed<LPR, 8, kMsgCopy, kRedSum, XB>(p, stream);
+    case kMsgCopy * 4 + kRedMax: return launch_typed<LPR, 8, kMsgCopy, kRedMax, XB>(p, stream);
+    case kMsgMulScalar * 4 + kRedSum: return launch_typed<LPR, 8, kMsgMulScalar, kRedSum, XB>(p, stream);
+    case kMsgMulScalar * 4 + kRedMax: return launch_typed<LPR, 8, kMsgMulScalar, kRedMax, XB>(p, stream);
     }
     return GNN_ERR_UNSUPPORTED;
+}
+
+template <int XB>
+gnn_status launch_16bit(const PropParams &p, int cols, int msg, int red, hipStream_t stream)
+{
+    if (cols <= 8) return launch_shape_16bit<8, XB>(p, msg, red, stream);
+    if (cols <= 16) return launch_shape_16bit<16, XB>(p, msg, red, stream);
+    if (cols <= 32) return launch_shape_16bit<32, XB>(p, msg, red, stream);
+    return launch_shape_16bit<64, XB>(p, msg, red, stream);
 }
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -613,13 +656,10 @@ gnn_status gnn_launch_propagate(const gnn_graph *g, const float *d_x, int32_t fe
     if (g->n_slots > 0) GNN_TRY(gnn_graph_reserve_scratch(g, (size_t)g->n_slots * F));
     p.scratch = g->scratch;
 
-    if (x_is_bf16) {
+    if (x_is_bf16) {   // 1 = bfloat16, 2 = binary16
         if (F % 8 != 0 || !aligned16(d_x) || !aligned16(d_out) || d_winners) return GNN_ERR_UNSUPPORTED;
-        const int cols = F / 8;
-        if (cols <= 8) return launch_shape_bf16<8>(p, kmsg, red, stream);
-        if (cols <= 16) return launch_shape_bf16<16>(p, kmsg, red, stream);
-        if (cols <= 32) return launch_shape_bf16<32>(p, kmsg, red, stream);
-        return launch_shape_bf16<64>(p, kmsg, red, stream);
+        if (x_is_bf16 == 1) return launch_16bit<1>(p, F / 8, kmsg, red, stream);
+        return launch_16bit<2>(p, F / 8, kmsg, red, stream);
     }
     const bool vec4 = (F % 4 == 0) && aligned16(d_x) && aligned16(d_out) &&
                       (msg_base(kmsg) != kMsgMulVector || aligned16(d_e)) && aligned16(d_winners);
@@ -683,10 +723,11 @@ gnn_status gnn_hetero_propagate(int32_t num_relations, const gnn_graph *const *g
     return GNN_OK;
 }
 
-gnn_status gnn_propagate_bf16(const gnn_graph *g, const uint16_t *d_x_bf16, int32_t feat_dim, const float *d_e,
-                              gnn_edge_order e_order, gnn_msg_op msg, gnn_aggr aggr, float *d_out, void *stream)
+static gnn_status propagate_16bit(const gnn_graph *g, const uint16_t *d_x16, int storage, int32_t feat_dim,
+                                  const float *d_e, gnn_edge_order e_order, gnn_msg_op msg, gnn_aggr aggr, float *d_out,
+                                  void *stream)
 {
-    if (!g || !d_x_bf16 || !d_out) return GNN_ERR_NULL;
+    if (!g || !d_x16 || !d_out) return GNN_ERR_NULL;
     if (feat_dim <= 0) return GNN_ERR_BAD_SIZE;
     if (!valid_aggr(aggr)) return GNN_ERR_BAD_SIZE;
     if (msg < GNN_MSG_COPY_XJ || msg > GNN_MSG_XI_DOT_XJ) return GNN_ERR_BAD_SIZE;
@@ -698,9 +739,21 @@ gnn_status gnn_propagate_bf16(const gnn_graph *g, const uint16_t *d_x_bf16, int3
     }
     gnn_epilogue epi;
     epi.mean = (aggr == GNN_AGGR_MEAN);
-    return gnn_launch_propagate(g, reinterpret_cast<const float *>(d_x_bf16), feat_dim, d_e, 1, e_order, msg,
+    return gnn_launch_propagate(g, reinterpret_cast<const float *>(d_x16), feat_dim, d_e, 1, e_order, msg,
                                 reduce_of(aggr), epi, d_out, static_cast<hipStream_t>(stream),
-                                GNN_GATHER_SOURCE_NODE, nullptr, 1);
+                                GNN_GATHER_SOURCE_NODE, nullptr, storage);
+}
+
+gnn_status gnn_propagate_bf16(const gnn_graph *g, const uint16_t *d_x_bf16, int32_t feat_dim, const float *d_e,
+                              gnn_edge_order e_order, gnn_msg_op msg, gnn_aggr aggr, float *d_out, void *stream)
+{
+    return propagate_16bit(g, d_x_bf16, 1, feat_dim, d_e, e_order, msg, aggr, d_out, stream);
+}
+
+gnn_status gnn_propagate_f16(const gnn_graph *g, const uint16_t *d_x_f16, int32_t feat_dim, const float *d_e,
+                             gnn_edge_order e_order, gnn_msg_op msg, gnn_aggr aggr, float *d_out, void *stream)
+{
+    return propagate_16bit(g, d_x_f16, 2, feat_dim, d_e, e_order, msg, aggr, d_out, stream);
 }
 
 gnn_status gnn_f32_to_bf16(const float *d_in, int64_t count, uint16_t *d_out, void *stream)
@@ -710,6 +763,18 @@ gnn_status gnn_f32_to_bf16(const float *d_in, int64_t count, uint16_t *d_out, vo
     if (!d_in || !d_out) return GNN_ERR_NULL;
     const int blocks = (int)std::min<int64_t>(gnn_div_up(count, kThreads), 256 * 64);
     hipLaunchKernelGGL(f32_to_bf16_kernel, dim3(blocks), dim3(kThreads), 0, static_cast<hipStream_t>(stream), d_in,
+                       count, d_out);
+    GNN_LAUNCH_CHECK();
+    return GNN_OK;
+}
+
+gnn_status gnn_f32_to_f16(const float *d_in, int64_t count, uint16_t *d_out, void *stream)
+{
+    if (count < 0) return GNN_ERR_BAD_SIZE;
+    if (count == 0) return GNN_OK;
+    if (!d_in || !d_out) return GNN_ERR_NULL;
+    const int blocks = (int)std::min<int64_t>(gnn_div_up(count, kThreads), 256 * 64);
+    hipLaunchKernelGGL(f32_to_f16_kernel, dim3(blocks), dim3(kThreads), 0, static_cast<hipStream_t>(stream), d_in,
                        count, d_out);
     GNN_LAUNCH_CHECK();
     return GNN_OK;

@@ -327,6 +327,58 @@ def test_propagate_bf16_wide_rows_and_rejections(gnn):
     g.close()
 
 
+def test_f32_to_f16_bit_exact(gnn, golden_dir):
+    gd = load_golden(golden_dir, "f16_rounding.json")
+    bits = np.array([int(c["float_bits"], 16) for c in gd["cases"]], np.uint32)
+    x = np.concatenate([bits.view(np.float32),
+                        (synth.normal_f32(97, 2, 100_003) * np.float32(10.0) ** synth.randint(97, 3, 0, 100_003, -12, 6)
+                         ).astype(np.float32)])
+    codes, _ = oracle.round_f16(x)
+    got = host(gnn.f32_to_f16(dev(x))).view(np.uint16)
+    np.testing.assert_array_equal(got, codes)
+
+
+@pytest.mark.parametrize("msg", [MSG_COPY_XJ, MSG_E_MUL_XJ])
+@pytest.mark.parametrize("aggr", [AGGR_SUM, AGGR_MEAN, AGGR_MAX])
+def test_propagate_f16_storage(case, gnn, msg, aggr):
+    """Features stored as IEEE binary16, widened exactly, float arithmetic: the reference is the oracle's propagate
+    on the oracle-rounded features, at the usual bar (max bit for bit)."""
+    name, wl, g = case
+    f = wl.x.shape[1]
+    if f % 8 != 0:
+        pytest.skip("16-bit rows are read eight values at a time")
+    codes, wide = oracle.round_f16(wl.x)
+    e = wl.edge_weight if msg == MSG_E_MUL_XJ else None
+    ref, sabs = oracle.propagate(wl.src, wl.dst, wl.num_nodes, wide, e, msg, aggr, with_sabs=True)
+    xh = gnn.f32_to_f16(dev(wl.x))
+    np.testing.assert_array_equal(host(xh).view(np.uint16), codes)
+    got = host(gnn.propagate_f16(g, xh, dev(e) if e is not None else None, msg, aggr))
+    if aggr == AGGR_MAX:
+        np.testing.assert_array_equal(got.view(np.uint32), ref.view(np.uint32))
+    else:
+        assert_close_sabs(got, ref, sabs, what=f"{name} f16 msg={msg} aggr={aggr}")
+
+
+def test_propagate_f16_subnormal_features_and_rejections(gnn):
+    """Features deep in binary16's subnormal range are widened exactly (copy_xj + max returns them bit for bit)."""
+    wl = powerlaw(3000, 60_000, 64, 1500.0)
+    g = gnn.build_csr(dev(wl.src), dev(wl.dst), wl.num_nodes, 8, 128)
+    tiny = (wl.x * np.float32(2.0 ** -20)).astype(np.float32)          # |values| around 1e-6: subnormal halves
+    codes, wide = oracle.round_f16(tiny)
+    assert ((codes & 0x7C00) == 0).mean() > 0.9
+    xh = dev(codes.view(np.int16))
+    ref = oracle.propagate(wl.src, wl.dst, wl.num_nodes, wide, None, MSG_COPY_XJ, AGGR_MAX)
+    np.testing.assert_array_equal(host(gnn.propagate_f16(g, xh, None, MSG_COPY_XJ, AGGR_MAX)).view(np.uint32),
+                                  ref.view(np.uint32))
+    ref, sabs = oracle.propagate(wl.src, wl.dst, wl.num_nodes, wide, None, MSG_COPY_XJ, AGGR_SUM, with_sabs=True)
+    assert_close_sabs(host(gnn.propagate_f16(g, xh, None, MSG_COPY_XJ, AGGR_SUM)), ref, sabs, what="f16 subnormal sum")
+    for msg, aggr in ((MSG_XJ_SUB_XI, AGGR_SUM), (MSG_COPY_XJ, AGGR_PROD)):
+        with pytest.raises(gnn.GnnError) as err:
+            gnn.propagate_f16(g, xh, None, msg, aggr)
+        assert err.value.code == 4
+    g.close()
+
+
 def test_hetero_propagate(gnn):
     """Three relations into one destination node type (power-law destinations so that rows get split),
     against the oracle's sum over relations; a bipartite handle in plain propagate; and the rejections."""
