@@ -17,7 +17,7 @@ __device__ __forceinline__ float max_pz(float a, float b)
 {
     if (a > b) return a;
     if (b > a) return b;
-    return __uint_as_float(__float_as_uint(a) & __float_as_uint(b));
+    return __uint_as_float(__float_as_uint(a) & __float_as_uint(b));   // equal, or the pair (-0, +0): +0
 }
 
 // Lower bound (first index whose value is >= key) in the sorted array a[0..n), found by the whole block: every

@@ -156,9 +156,12 @@ __device__ __forceinline__ float load_stream(const float *p) { return __builtin_
 // The larger of two finite floats; for the pair (-0, +0) the result is +0.
 __device__ __forceinline__ float max_pz(float a, float b)
 {
-    if (a > b) return a;
-    if (b > a) return b;
-    return __uint_as_float(__float_as_uint(a) & __float_as_uint(b));
+    // one v_max_f32: the hardware maximum orders -0 below +0 whichever operand comes first (checked on the
+    // device: max(+0, -0) = max(-0, +0) = +0, max(-0, -0) = -0); inputs are finite.  Written as the instruction
+    // itself: fmaxf() would first pass both operands through a NaN-quieting max of their own.
+    float r;
+    asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
 }
 
 template <int VEC, int RED>
