@@ -42,9 +42,9 @@ MFMA_FP32_PEAK_TFLOPS = 157.3
 # (FETCH_SIZE x 2.000 calibration factor + WRITE_SIZE x 1.000, calibrated on a 1 GiB streaming kernel
 # in the same run).  Only meaningful for the default sizes of each workload; other sizes report null.
 MEASURED_TRAFFIC_BYTES = {
-    ("propagate", 1_000_000, 20_000_000, 64): 2_924_020_832,   # propagate_kernel<16,4,0,0,0>
-    ("gat", 2_449_029, 126_167_309, 64): 27_475_071_488,       # gat_kernel<16,4,2>
-    ("gcn", 100_000, 1_000_000, 128): 405_432_288,             # propagate_kernel<32,4,0,0,0>, GCN epilogue
+    ("propagate", 1_000_000, 20_000_000, 64): 2_924_025_344,   # propagate_kernel<16,4,0,0,0>
+    ("gat", 2_449_029, 126_167_309, 64): 27_475_696_405,       # gat_kernel<16,4,2>
+    ("gcn", 100_000, 1_000_000, 128): 405_440_464,             # propagate_kernel<32,4,0,0,0>, GCN epilogue
 }
 
 
