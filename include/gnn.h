@@ -261,6 +261,9 @@ gnn_status gnn_propagate_backward(const gnn_graph *g, const gnn_graph *g_by_sour
  * max(., 0) to the result (the example's GCNConv(64 => 64, relu)), GNN_ACT_NONE leaves it.
  * d_x [N x f_in], d_w [f_in x f_out] row-major, d_bias [f_out] or NULL, d_out [N x f_out].
  * d_workspace: device scratch of at least gnn_gcnconv_workspace_bytes(N, f_out) bytes.
+ * The two products are taken in the order that gathers the narrower rows: (Ahat X) W when f_in < f_out,
+ * Ahat (X W) otherwise; results of the two orders differ by rounding only.  A handle built by
+ * gnn_build_csr_bipartite is refused (GNN_ERR_UNSUPPORTED).
  */
 size_t gnn_gcnconv_workspace_bytes(int32_t num_nodes, int32_t f_out);
 gnn_status gnn_gcnconv(const gnn_graph *g, const float *d_x, int32_t f_in, const float *d_w,

@@ -10,6 +10,9 @@
 //     both operands are read along rows (coalesced); row chunks give partial [f_in x f_out] blocks
 //     that a second kernel adds up in chunk order (deterministic);
 //   * the bias gradient uses the same two-stage scheme.
+// A layer that widens (f_in < f_out) is differentiated in the order its forward runs in, so that both gathers move
+// rows of f_in values:   dL/dW = (Ahat X)^T G  (Ahat X recomputed by the forward's narrow propagate),
+// dL/dX = Ahat^T (G W^T)  (projection first, destination-side factor in its store, then the propagate by source).
 #include "gnn_internal.h"
 
 #include <algorithm>
@@ -378,7 +381,8 @@ gnn_status gnn_gcnconv_backward(const gnn_graph *g, const gnn_graph *g_by_source
     const int chunks = chunk_count(N);
     const float *dinv = add_self_loops ? g->dinv_loop : g->dinv_plain;   // the forward graph's degree factors
 
-    const bool need_t = d_grad_x || d_grad_w;
+    const bool narrow_first = f_in < f_out;   // the order gnn_gcnconv runs this shape in
+    const bool need_t = !narrow_first && (d_grad_x || d_grad_w);
     if (need_t || d_grad_b) {
         // G is read once: scaled rows for the propagate and the first stage of the bias gradient (64-row chunks:
         // enough blocks to stream at full rate; the partial sums fit the workspace's partial-result area)
@@ -396,6 +400,26 @@ gnn_status gnn_gcnconv_backward(const gnn_graph *g, const gnn_graph *g_by_source
                                bias_rows, scaled, bias_part);
         GNN_LAUNCH_CHECK();
         if (d_grad_b) GNN_TRY(gnn_launch_sum_partials(part, (int)grid.x, (int64_t)f_out, d_grad_b, s));
+    }
+    if (narrow_first) {
+        if (d_grad_w) {   // t = Ahat X [N x f_in], then (Ahat X)^T G
+            gnn_epilogue agg;
+            agg.self_scale = add_self_loops ? 1.0f : 0.0f;
+            agg.row_scale = dinv;
+            agg.source_scale = dinv;
+            GNN_TRY(gnn_launch_propagate(g, d_x, f_in, nullptr, 1, GNN_EDGE_ORDER_CSR, GNN_MSG_COPY_XJ, 0, agg, t, s));
+            GNN_TRY(gnn_launch_xty(t, d_grad_out, N, f_in, f_out, part, d_grad_w, s));
+        }
+        if (d_grad_x) {   // gs = dinv * (G W^T) [N x f_in], then the propagate over the transposed topology
+            GNN_TRY(gnn_launch_transpose(d_w, f_in, f_out, wt, s));
+            GNN_TRY(gnn_launch_xw(d_grad_out, N, f_out, wt, f_in, dinv, nullptr, false, gs, s));
+            gnn_epilogue epi;
+            epi.self_scale = add_self_loops ? 1.0f : 0.0f;
+            epi.row_scale = dinv;
+            GNN_TRY(gnn_launch_propagate(g_by_source, gs, f_in, nullptr, 1, GNN_EDGE_ORDER_CSR, GNN_MSG_COPY_XJ, 0,
+                                         epi, d_grad_x, s));
+        }
+        return GNN_OK;
     }
     if (need_t) {
         gnn_epilogue epi;

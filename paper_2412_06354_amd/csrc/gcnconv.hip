@@ -8,6 +8,11 @@
 //      (copy_xj, sum) with the self-loop term, the destination-side factor and the bias applied in
 //      its epilogue, so the self-loops are never materialised as edges; an optional relu (the
 //      example's GCNConv(64 => 64, relu)) is applied there too.
+// A layer that widens (f_in < f_out, the example's GCNConv(16 => 64)) runs in the other order, so that the gather
+// moves rows of f_in values instead of f_out:
+//   2'. T[i,:] = dinv[i] * (sum_{j->i} dinv[j] X[j,:] + [self-loop] dinv[i] X[i,:])   -- the propagate kernel with one
+//       weight per edge looked up by source node (X is never rescaled in memory);
+//   3'. out = T W + b  -- MFMA projection with bias and relu in its store.
 #include "gnn_internal.h"
 
 namespace {
@@ -31,6 +36,7 @@ gnn_status gnn_gcnconv(const gnn_graph *g, const float *d_x, int32_t f_in, const
     if (!g || !d_x || !d_w || !d_out || !d_workspace) return GNN_ERR_NULL;
     if (f_in <= 0 || f_out <= 0) return GNN_ERR_BAD_SIZE;
     if (act != GNN_ACT_NONE && act != GNN_ACT_RELU) return GNN_ERR_BAD_SIZE;
+    if (g->bipartite) return GNN_ERR_UNSUPPORTED;   // one node set only: X has a row per node of the graph
     const int32_t N = g->num_nodes;
     if (workspace_bytes < gnn_gcnconv_workspace_bytes(N, f_out)) return GNN_ERR_BAD_SIZE;
     if (reinterpret_cast<uintptr_t>(d_workspace) & 255u) return GNN_ERR_BAD_SIZE;
@@ -38,6 +44,14 @@ gnn_status gnn_gcnconv(const gnn_graph *g, const float *d_x, int32_t f_in, const
     float *z = static_cast<float *>(d_workspace);
     const float *dinv = add_self_loops ? g->dinv_loop : g->dinv_plain;   // computed when the graph was built
 
+    if (f_in < f_out) {   // aggregate the narrow rows first
+        gnn_epilogue agg;
+        agg.self_scale = add_self_loops ? 1.0f : 0.0f;
+        agg.row_scale = dinv;
+        agg.source_scale = dinv;
+        GNN_TRY(gnn_launch_propagate(g, d_x, f_in, nullptr, 1, GNN_EDGE_ORDER_CSR, GNN_MSG_COPY_XJ, 0, agg, z, s));
+        return gnn_launch_xw(z, N, f_in, d_w, f_out, nullptr, d_bias, act == GNN_ACT_RELU, d_out, s);
+    }
     GNN_TRY(gnn_dense_xw(d_x, N, f_in, d_w, f_out, dinv, z, stream));
     gnn_epilogue epi;
     epi.self_scale = add_self_loops ? 1.0f : 0.0f;

@@ -106,6 +106,9 @@ struct gnn_epilogue {
     const float *bias = nullptr;
     int relu = 0;                    // max(., 0) last
     int accumulate = 0;              // out += result instead of out = result (sum over relations)
+    // copy_xj with sum only: edge j -> i carries source_scale[j] * x[j,:] and the self term becomes
+    // self_scale * source_scale[row] * x[row,:]  (a diagonal scaling of x that is never written out)
+    const float *source_scale = nullptr;
 };
 
 // Which row of `x` CSR position p gathers: x[colidx[p]] for node features (the default),
@@ -143,7 +146,6 @@ gnn_status gnn_launch_xty(const float *d_x, const float *d_y, int64_t rows, int 
 // out[q] = sum over chunks (fixed order) of partial[chunk * elems + q]
 gnn_status gnn_launch_sum_partials(const float *d_partial, int chunks, int64_t elems, float *d_out,
                                    hipStream_t stream);
-// wt[cols x rows] = w[rows x cols]^T
 // Backward of sum / mean pooling; d_relu_y (optional, [N x F]) = the pooled rows when they were relu outputs: the
 // relu's backward rides in the same pass (pool.hip).
 gnn_status gnn_launch_pool_backward(const int32_t *d_graph_indicator, int32_t num_nodes, int32_t num_graphs,
@@ -152,6 +154,7 @@ gnn_status gnn_launch_pool_backward(const int32_t *d_graph_indicator, int32_t nu
 // Z = X W with the store's epilogue: optional per-row scale, then per-column bias, then relu (gemm.hip).
 gnn_status gnn_launch_xw(const float *d_x, int64_t rows, int32_t k, const float *d_w, int32_t n,
                          const float *d_row_scale, const float *d_bias, bool relu, float *d_z, hipStream_t s);
+// wt[cols x rows] = w[rows x cols]^T
 gnn_status gnn_launch_transpose(const float *d_w, int rows, int cols, float *d_wt, hipStream_t stream);
 // sl[i,hd] = <a_src[hd,:], h[i,hd,:]>, sr[i,hd] = <a_dst[hd,:], h[i,hd,:]>  (gatconv.hip)
 gnn_status gnn_launch_node_scores(const float *d_h, int64_t N, int heads, int ch, const float *d_a_src,

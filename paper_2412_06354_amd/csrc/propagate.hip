@@ -42,6 +42,7 @@ struct PropParams {
     const int32_t *small_rows, *item_row, *item_start, *item_slot, *split_rows, *split_slot0;
     int32_t n_small, n_items, n_split, chunk, F, e_coo, item_blocks;
     int32_t mean, relu, accumulate;
+    int32_t w_by_source;   // one weight per edge, looked up by the edge's source node: e[j] instead of e[edge]
     float self_scale;
     const float *row_scale, *bias;
     const int32_t *winners;   // [rows of x][F] winning edge id per element (routed kinds only)
@@ -199,8 +200,9 @@ __device__ __forceinline__ void finish_row(const PropParams &p, int row, int deg
     if (p.self_scale != 0.0f) {
         Row<VEC> xs;
         load_x<VEC, XB>(xs, p.x, (int64_t)row * p.F + col);
+        const float ss = p.w_by_source ? p.self_scale * p.e[row] : p.self_scale;
 #pragma unroll
-        for (int c = 0; c < VEC; ++c) acc.v[c] = fmaf(p.self_scale, x_value<VEC, XB>(xs, c), acc.v[c]);
+        for (int c = 0; c < VEC; ++c) acc.v[c] = fmaf(ss, x_value<VEC, XB>(xs, c), acc.v[c]);
     }
     if (p.row_scale) {
         const float s = p.row_scale[row];
@@ -299,7 +301,8 @@ __device__ __forceinline__ void short_rows(const PropParams &p, int block)
                 my_j = p.colidx ? load_stream(p.colidx + q) : q;   // no index array: row q itself
                 if constexpr (MSG != kMsgCopy) {
                     my_eid = p.e_coo ? load_stream(p.perm + q) : q;
-                    if constexpr (msg_base(MSG) == kMsgMulScalar) my_w = load_stream(p.e + my_eid);
+                    if constexpr (msg_base(MSG) == kMsgMulScalar)
+                        my_w = p.w_by_source ? p.e[my_j] : load_stream(p.e + my_eid);
                 }
             }
             const int cnt = min(LPR, wmax - base);
@@ -360,7 +363,8 @@ __device__ __forceinline__ void long_row_pieces(const PropParams &p, int block)
                 my_j = p.colidx ? load_stream(p.colidx + q) : q;   // no index array: row q itself
                 if constexpr (MSG != kMsgCopy) {
                     my_eid = p.e_coo ? load_stream(p.perm + q) : q;
-                    if constexpr (msg_base(MSG) == kMsgMulScalar) my_w = load_stream(p.e + my_eid);
+                    if constexpr (msg_base(MSG) == kMsgMulScalar)
+                        my_w = p.w_by_source ? p.e[my_j] : load_stream(p.e + my_eid);
                 }
             }
             // sub-group sg takes batch positions sg, sg + NSG, sg + 2*NSG, ...
@@ -641,13 +645,20 @@ gnn_status gnn_launch_propagate(const gnn_graph *g, const float *d_x, int32_t fe
             return GNN_ERR_UNSUPPORTED;   // edge ids are compared
         kmsg += kMsgRouted;
     }
+    if (epi.source_scale) {   // a per-source weight is the one-weight-per-edge kernel with another index
+        if (msg != GNN_MSG_COPY_XJ || reduce != GNN_REDUCE_SUM || gather != GNN_GATHER_SOURCE_NODE || d_winners ||
+            x_is_bf16 || g->bipartite)
+            return GNN_ERR_UNSUPPORTED;
+        kmsg = kMsgMulScalar;
+    }
     const int red = reduce == GNN_REDUCE_SUM ? kRedSum
                     : reduce == GNN_REDUCE_PROD ? kRedProd : reduce == GNN_REDUCE_MIN ? kRedMin : kRedMax;
 
     PropParams p{};
     p.rowptr = g->rowptr; p.perm = g->perm;
     p.colidx = gather == GNN_GATHER_SOURCE_NODE ? g->colidx : (gather == GNN_GATHER_EDGE_COO ? g->perm : nullptr);
-    p.x = d_x; p.e = d_e; p.out = d_out;
+    p.x = d_x; p.e = epi.source_scale ? epi.source_scale : d_e; p.out = d_out;
+    p.w_by_source = epi.source_scale ? 1 : 0;
     p.small_rows = g->small_rows; p.item_row = g->item_row; p.item_start = g->item_start;
     p.item_slot = g->item_slot; p.split_rows = g->split_rows; p.split_slot0 = g->split_slot0;
     p.n_small = g->n_small; p.n_items = g->n_items; p.n_split = g->n_split; p.chunk = g->chunk;

@@ -411,7 +411,8 @@ def test_hetero_propagate(gnn):
     # (relation 2 has as many sources as destinations: it is the handle that knows they are different sets)
     for fn in (lambda: gnn.gin_update(graphs[2], xs[2], 0.0),
                lambda: gnn.propagate(graphs[2], xs[2], None, MSG_XJ_SUB_XI, AGGR_SUM),
-               lambda: gnn.apply_edges(graphs[2], xs[2], None, MSG_XI_DOT_XJ)):
+               lambda: gnn.apply_edges(graphs[2], xs[2], None, MSG_XI_DOT_XJ),
+               lambda: gnn.gcnconv(graphs[2], xs[2], dev(np.ones((xs[2].shape[1], 4), np.float32)), None, False)):
         with pytest.raises(gnn.GnnError) as err:
             fn()
         assert err.value.code == 4
@@ -574,6 +575,22 @@ def test_gcnconv(gnn, loops, golden_dir):
         d = np.sqrt(np.bincount(wl.dst, minlength=wl.num_nodes) + 1.0).astype(np.float32).reshape(-1, 1)
         out = host(gnn.gcnconv(g, dev(d), dev(np.ones((1, 1), np.float32)), None, True))
         np.testing.assert_allclose(out, d, rtol=2e-6)
+    g.close()
+
+
+@pytest.mark.parametrize("loops,f_in,f_out,relu", [(True, 16, 64, True), (False, 16, 64, False), (True, 37, 50, False),
+                                                   (True, 64, 16, True), (True, 3, 130, False)])
+def test_gcnconv_widths(gnn, loops, f_in, f_out, relu):
+    """Widening layers aggregate first and project afterwards, narrowing ones the other way round: both orders, odd
+    widths and the activation against the same oracle."""
+    wl = synth.config1_gcn(num_nodes=6000, pairs=30_000, f_in=f_in, f_out=f_out)
+    bias = synth.uniform_f32(9, 5, f_out, -1, 1)
+    g = gnn.build_csr(dev(wl.src), dev(wl.dst), wl.num_nodes, 8, 64)
+    ref, sabs = oracle.gcnconv(wl.src, wl.dst, wl.num_nodes, wl.x, wl.params["w"], bias, loops, with_sabs=True)
+    if relu:
+        ref = np.maximum(ref, 0.0)
+    got = host(gnn.gcnconv(g, dev(wl.x), dev(wl.params["w"]), dev(bias), loops, relu=relu))
+    assert_close_sabs(got, ref, sabs, what=f"gcnconv {f_in}->{f_out} loops={loops} relu={relu}")
     g.close()
 
 
