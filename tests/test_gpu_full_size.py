@@ -243,3 +243,55 @@ def test_gatconv_backward_mid_size_all_gradients(gnn):
     assert_close_sabs(host(gad), ref["grad_a_dst"], ref["sabs_a_dst"], what="gat grad_a_dst")
     g.close()
     gt.close()
+
+
+# ----------------------------------------------------------------------------- offsets beyond 2^31 elements
+
+def test_element_offsets_beyond_2_to_31(gnn):
+    """Feature and message arrays of more than 2^31 elements: N x F = 5 M x 512 (2.56 G floats) for the node side,
+    E x F = 6 M x 512 (3.07 G floats) for the materialised messages.  A 32-bit element offset anywhere in the kernels
+    would wrap in the upper half of these arrays; the sampled rows and edges are taken from both halves.  Features are
+    a closed-form pattern (multiples of 1/64, exact in float) filled in on the device and recomputed on the host for
+    the sampled rows only."""
+    n, f, e = 5_000_000, 512, 6_000_000
+    src = synth.randint(77, 1, 0, e, 0, n - 1).astype(np.int32)
+    dst = synth.randint(77, 2, 0, e, 0, n - 1).astype(np.int32)
+
+    def pattern(rows):   # x[i, c] = (((131 i + 7 c) mod 1001) - 500) / 64
+        i = np.asarray(rows, np.int64).reshape(-1, 1)
+        c = np.arange(f, dtype=np.int64).reshape(1, -1)
+        return (((131 * i + 7 * c) % 1001 - 500) / 64.0).astype(np.float32)
+
+    say("large offsets: filling 10 GB of features on the device")
+    x = torch.empty((n, f), dtype=torch.float32, device="cuda")
+    cols = torch.arange(f, dtype=torch.int64, device="cuda").reshape(1, -1)
+    for r0 in range(0, n, 250_000):
+        r1 = min(n, r0 + 250_000)
+        i = torch.arange(r0, r1, dtype=torch.int64, device="cuda").reshape(-1, 1)
+        x[r0:r1] = ((131 * i + 7 * cols) % 1001 - 500).to(torch.float32) / 64.0
+    g = gnn.build_csr(dev(src), dev(dst), n)
+    rows = np.unique(np.concatenate([synth.randint(77, 3, 0, 1500, 0, n - 1),
+                                     synth.randint(77, 4, 0, 1500, n - n // 8, n - 1), [0, n - 1]])).astype(np.int64)
+    s_src, s_dst, nodes, local_rows, eid = subgraph_for_rows(src, dst, rows)
+    xs = pattern(nodes)
+    rows_d = torch.from_numpy(rows).cuda()
+    for aggr in (AGGR_SUM, AGGR_MAX):
+        out = gnn.propagate(g, x, None, MSG_COPY_XJ, aggr)
+        ref, sabs = oracle.propagate(s_src, s_dst, nodes.shape[0], xs, None, MSG_COPY_XJ, aggr, with_sabs=True)
+        got = host(out[rows_d])
+        if aggr == AGGR_MAX:
+            np.testing.assert_array_equal(got.view(np.uint32), ref[local_rows].view(np.uint32))
+        else:
+            assert_close_sabs(got, ref[local_rows], sabs[local_rows], what="large offsets, sum")
+        say(f"large offsets: propagate aggr={aggr} ok on {rows.shape[0]} rows")
+    del out
+    # materialised messages, 12 GB: message k is the source's row, bit for bit; reduced again they give the fused result
+    m = gnn.apply_edges(g, x, None, MSG_COPY_XJ)
+    ks = np.unique(np.concatenate([synth.randint(77, 5, 0, 2000, 0, e - 1),
+                                   synth.randint(77, 6, 0, 2000, e - e // 8, e - 1), [0, e - 1]])).astype(np.int64)
+    np.testing.assert_array_equal(host(m[torch.from_numpy(ks).cuda()]).view(np.uint32), pattern(src[ks]).view(np.uint32))
+    again = gnn.aggregate_neighbors(g, m, AGGR_SUM)
+    ref, sabs = oracle.propagate(s_src, s_dst, nodes.shape[0], xs, None, MSG_COPY_XJ, AGGR_SUM, with_sabs=True)
+    assert_close_sabs(host(again[rows_d]), ref[local_rows], sabs[local_rows], what="large offsets, aggregate_neighbors")
+    say("large offsets: apply_edges / aggregate_neighbors ok")
+    g.close()
