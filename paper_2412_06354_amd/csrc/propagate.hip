@@ -27,13 +27,16 @@ constexpr int kWavesPerBlock = kThreads / 64;
 // The "routed" kinds (+4) are used by the backward pass of a max aggregation: the
 // gathered row is the upstream gradient of the edge's destination and a feature only contributes
 // if the recorded winner of that (destination, feature) is this very edge.
-enum { kMsgCopy = 0, kMsgMulScalar = 1, kMsgMulVector = 2, kMsgSubTarget = 3, kMsgRouted = 4 };
+// kMsgMulSource is one weight per edge looked up by the edge's source node, w = e[j] (a diagonal scaling of x that
+// is never written out); the row's self term is then scaled by e[row] as well.
+enum { kMsgCopy = 0, kMsgMulScalar = 1, kMsgMulVector = 2, kMsgSubTarget = 3, kMsgRouted = 4, kMsgMulSource = 8 };
 // Reductions.  min runs as max over negated messages, negated back at the end: negation is exact and
 // turns "+0 above -0" into "-0 below +0".
 enum { kRedSum = 0, kRedMax = 1, kRedProd = 2, kRedMin = 3 };
 constexpr bool red_is_max(int red) { return red == kRedMax || red == kRedMin; }
-constexpr int msg_base(int msg) { return msg % kMsgRouted; }
-constexpr bool msg_routed(int msg) { return msg >= kMsgRouted; }
+constexpr bool msg_by_source(int msg) { return msg == kMsgMulSource; }
+constexpr int msg_base(int msg) { return msg_by_source(msg) ? kMsgMulScalar : msg % kMsgRouted; }
+constexpr bool msg_routed(int msg) { return msg >= kMsgRouted && msg < kMsgMulSource; }
 
 struct PropParams {
     const int32_t *rowptr, *colidx, *perm;
@@ -42,7 +45,6 @@ struct PropParams {
     const int32_t *small_rows, *item_row, *item_start, *item_slot, *split_rows, *split_slot0;
     int32_t n_small, n_items, n_split, chunk, F, e_coo, item_blocks;
     int32_t mean, relu, accumulate;
-    int32_t w_by_source;   // one weight per edge, looked up by the edge's source node: e[j] instead of e[edge]
     float self_scale;
     const float *row_scale, *bias;
     const int32_t *winners;   // [rows of x][F] winning edge id per element (routed kinds only)
@@ -181,7 +183,7 @@ __device__ __forceinline__ void combine(Row<VEC> &acc, const Row<VEC> &m)
 }
 
 // Finishes one output row slice (VEC features starting at col) and stores it.
-template <int VEC, int RED, int XB = 0>
+template <int VEC, int RED, int XB = 0, bool BYSRC = false>
 __device__ __forceinline__ void finish_row(const PropParams &p, int row, int deg, int col, Row<VEC> acc)
 {
     if constexpr (RED == kRedMin) {
@@ -200,7 +202,8 @@ __device__ __forceinline__ void finish_row(const PropParams &p, int row, int deg
     if (p.self_scale != 0.0f) {
         Row<VEC> xs;
         load_x<VEC, XB>(xs, p.x, (int64_t)row * p.F + col);
-        const float ss = p.w_by_source ? p.self_scale * p.e[row] : p.self_scale;
+        float ss = p.self_scale;
+        if constexpr (BYSRC) ss *= p.e[row];
 #pragma unroll
         for (int c = 0; c < VEC; ++c) acc.v[c] = fmaf(ss, x_value<VEC, XB>(xs, c), acc.v[c]);
     }
@@ -299,10 +302,11 @@ __device__ __forceinline__ void short_rows(const PropParams &p, int block)
             if (base + sl < deg) {
                 const int q = start + base + sl;
                 my_j = p.colidx ? load_stream(p.colidx + q) : q;   // no index array: row q itself
-                if constexpr (MSG != kMsgCopy) {
+                if constexpr (msg_by_source(MSG)) {
+                    my_w = p.e[my_j];
+                } else if constexpr (MSG != kMsgCopy) {
                     my_eid = p.e_coo ? load_stream(p.perm + q) : q;
-                    if constexpr (msg_base(MSG) == kMsgMulScalar)
-                        my_w = p.w_by_source ? p.e[my_j] : load_stream(p.e + my_eid);
+                    if constexpr (msg_base(MSG) == kMsgMulScalar) my_w = load_stream(p.e + my_eid);
                 }
             }
             const int cnt = min(LPR, wmax - base);
@@ -327,7 +331,7 @@ __device__ __forceinline__ void short_rows(const PropParams &p, int block)
                     apply_message<VEC, MSG, RED, XB>(acc, ok[u], xv[u], w[u], ev[u], wv[u], eid[u], xi);
             }
         }
-        if (colok) finish_row<VEC, RED, XB>(p, row, deg, col, acc);
+        if (colok) finish_row<VEC, RED, XB, msg_by_source(MSG)>(p, row, deg, col, acc);
     }
 }
 
@@ -361,10 +365,11 @@ __device__ __forceinline__ void long_row_pieces(const PropParams &p, int block)
             if (lane < n) {
                 const int q = base + lane;
                 my_j = p.colidx ? load_stream(p.colidx + q) : q;   // no index array: row q itself
-                if constexpr (MSG != kMsgCopy) {
+                if constexpr (msg_by_source(MSG)) {
+                    my_w = p.e[my_j];
+                } else if constexpr (MSG != kMsgCopy) {
                     my_eid = p.e_coo ? load_stream(p.perm + q) : q;
-                    if constexpr (msg_base(MSG) == kMsgMulScalar)
-                        my_w = p.w_by_source ? p.e[my_j] : load_stream(p.e + my_eid);
+                    if constexpr (msg_base(MSG) == kMsgMulScalar) my_w = load_stream(p.e + my_eid);
                 }
             }
             // sub-group sg takes batch positions sg, sg + NSG, sg + 2*NSG, ...
@@ -398,7 +403,7 @@ __device__ __forceinline__ void long_row_pieces(const PropParams &p, int block)
         }
         if (sg == 0 && colok) {
             if (slot < 0)
-                finish_row<VEC, RED, XB>(p, row, row_end - row_start, col, acc);
+                finish_row<VEC, RED, XB, msg_by_source(MSG)>(p, row, row_end - row_start, col, acc);
             else
                 store_row<VEC>(p.scratch + (int64_t)slot * p.F + col, acc);
         }
@@ -419,7 +424,7 @@ __global__ __launch_bounds__(kThreads) void propagate_kernel(const PropParams p)
 // Combines the per-piece partial rows of split rows: one wavefront per split row, its sub-groups
 // take the pieces round-robin (four loads in flight each) and are folded with xor-shuffles; the
 // order of combination is a fixed function of the piece count.
-template <int LPR, int VEC, int RED, int XB = 0>
+template <int LPR, int VEC, int RED, int XB = 0, bool BYSRC = false>
 __global__ __launch_bounds__(kThreads) void combine_pieces_kernel(const PropParams p)
 {
     constexpr int NSG = 64 / LPR;
@@ -455,7 +460,7 @@ __global__ __launch_bounds__(kThreads) void combine_pieces_kernel(const PropPara
             for (int c = 0; c < VEC; ++c) other.v[c] = __shfl_xor(acc.v[c], off, 64);
             combine<VEC, RED>(acc, other);
         }
-        if (sg == 0 && colok) finish_row<VEC, RED, XB>(p, row, deg, col, acc);
+        if (sg == 0 && colok) finish_row<VEC, RED, XB, BYSRC>(p, row, deg, col, acc);
     }
 }
 
@@ -511,7 +516,7 @@ gnn_status launch_typed(const PropParams &p, hipStream_t stream)
     }
     if (p.n_split > 0) {
         const int64_t cblocks = gnn_div_up(p.n_split, kWavesPerBlock);
-        hipLaunchKernelGGL((combine_pieces_kernel<LPR, VEC, RED, XB>), dim3((unsigned)cblocks), dim3(kThreads), 0, stream,
+        hipLaunchKernelGGL((combine_pieces_kernel<LPR, VEC, RED, XB, msg_by_source(MSG)>), dim3((unsigned)cblocks), dim3(kThreads), 0, stream,
                            p);
         GNN_LAUNCH_CHECK();
     }
@@ -538,6 +543,7 @@ gnn_status launch_shape(const PropParams &p, int msg, int red, hipStream_t strea
     case kMsgSubTarget * 4 + kRedMax: return launch_typed<LPR, VEC, kMsgSubTarget, kRedMax>(p, stream);
     case kMsgSubTarget * 4 + kRedProd: return launch_typed<LPR, VEC, kMsgSubTarget, kRedProd>(p, stream);
     case kMsgSubTarget * 4 + kRedMin: return launch_typed<LPR, VEC, kMsgSubTarget, kRedMin>(p, stream);
+    case kMsgMulSource * 4 + kRedSum: return launch_typed<LPR, VEC, kMsgMulSource, kRedSum>(p, stream);
     case (kMsgRouted + kMsgCopy) * 4 + kRedSum:
         return launch_typed<LPR, VEC, kMsgRouted + kMsgCopy, kRedSum>(p, stream);
     case (kMsgRouted + kMsgMulScalar) * 4 + kRedSum:
@@ -649,7 +655,7 @@ gnn_status gnn_launch_propagate(const gnn_graph *g, const float *d_x, int32_t fe
         if (msg != GNN_MSG_COPY_XJ || reduce != GNN_REDUCE_SUM || gather != GNN_GATHER_SOURCE_NODE || d_winners ||
             x_is_bf16 || g->bipartite)
             return GNN_ERR_UNSUPPORTED;
-        kmsg = kMsgMulScalar;
+        kmsg = kMsgMulSource;
     }
     const int red = reduce == GNN_REDUCE_SUM ? kRedSum
                     : reduce == GNN_REDUCE_PROD ? kRedProd : reduce == GNN_REDUCE_MIN ? kRedMin : kRedMax;
@@ -658,7 +664,6 @@ gnn_status gnn_launch_propagate(const gnn_graph *g, const float *d_x, int32_t fe
     p.rowptr = g->rowptr; p.perm = g->perm;
     p.colidx = gather == GNN_GATHER_SOURCE_NODE ? g->colidx : (gather == GNN_GATHER_EDGE_COO ? g->perm : nullptr);
     p.x = d_x; p.e = epi.source_scale ? epi.source_scale : d_e; p.out = d_out;
-    p.w_by_source = epi.source_scale ? 1 : 0;
     p.small_rows = g->small_rows; p.item_row = g->item_row; p.item_start = g->item_start;
     p.item_slot = g->item_slot; p.split_rows = g->split_rows; p.split_slot0 = g->split_slot0;
     p.n_small = g->n_small; p.n_items = g->n_items; p.n_split = g->n_split; p.chunk = g->chunk;
