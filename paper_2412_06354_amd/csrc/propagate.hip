@@ -685,6 +685,7 @@ gnn_status gnn_launch_propagate(const gnn_graph *g, const float *d_x, int32_t fe
                       (msg_base(kmsg) != kMsgMulVector || aligned16(d_e)) && aligned16(d_winners);
     if (vec4) {
         const int cols = F / 4;
+        if (cols <= 4) return launch_shape<4, 4>(p, kmsg, red, stream);   // F <= 16: sixteen rows per wavefront
         if (cols <= 8) return launch_shape<8, 4>(p, kmsg, red, stream);
         if (cols <= 16) return launch_shape<16, 4>(p, kmsg, red, stream);
         if (cols <= 32) return launch_shape<32, 4>(p, kmsg, red, stream);

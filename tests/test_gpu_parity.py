@@ -147,7 +147,7 @@ def test_propagate_f64(case, gnn, msg, aggr):
     np.testing.assert_array_equal(again.view(np.uint32), got.view(np.uint32))
 
 
-@pytest.mark.parametrize("feat", [4, 7, 32, 100, 128, 260, 515])
+@pytest.mark.parametrize("feat", [4, 7, 12, 16, 32, 100, 128, 260, 515])
 def test_propagate_feature_widths(gnn, feat):
     wl = powerlaw(4000, 60_000, feat, 2500.0)
     g = gnn.build_csr(dev(wl.src), dev(wl.dst), wl.num_nodes, 8, 128)
