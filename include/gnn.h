@@ -119,12 +119,17 @@ gnn_status gnn_build_csr_bipartite(const int32_t *d_src, const int32_t *d_dst, i
 
 /*
  * gnn_build_csr keeps its temporaries (about 16 bytes per edge) in one device buffer per process between
- * calls, so that building graph after graph does not allocate and free each time.  This call frees that
- * buffer (GNN_ERR_UNSUPPORTED if a build is using it on another thread); the next build allocates it again.
+ * calls, and gnn_graph_destroy keeps the arrays of one destroyed graph (the largest it has seen) for the next
+ * build of a similar size, so that building and destroying graph after graph -- one per mini-batch -- does not
+ * allocate and free each time.  This call frees both (GNN_ERR_UNSUPPORTED, with the graph arrays already
+ * freed, if a build is using the temporaries on another thread); the next build allocates again.
  */
 gnn_status gnn_release_cached_memory(void);
 
-/* Frees everything the graph owns.  The caller makes sure no enqueued work still uses it. */
+/*
+ * Destroys the graph.  The caller makes sure no enqueued work still uses it: its device arrays are freed or
+ * handed to a later gnn_build_csr call (see gnn_release_cached_memory).
+ */
 gnn_status gnn_graph_destroy(gnn_graph *g);
 
 /* Borrowed device pointers / sizes, valid until gnn_graph_destroy.  NULL / 0 for a NULL graph. */

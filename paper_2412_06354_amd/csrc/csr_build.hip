@@ -394,12 +394,36 @@ int ceil_log2(uint32_t n)
     return b;
 }
 
+// The arrays of a destroyed graph are kept for the next build: one block per process (the larger one wins), so
+// that a loop which builds a graph per mini-batch and destroys the previous one neither allocates nor frees in
+// steady state (an allocation plus a free cost about as much as the kernels of a 20 M-edge build).  A build takes
+// the block if it is on the current device, large enough and at most twice what it needs.
+// gnn_release_cached_memory() frees it.
+struct slab_cache {
+    std::mutex mu;
+    void *ptr = nullptr;
+    size_t bytes = 0;
+    int device = -1;
+};
+slab_cache g_slab_cache;
+
 void free_graph_arrays(gnn_graph *g)
 {
-    void *ptrs[] = {g->slab, g->scratch};
-    for (void *p : ptrs)
-        if (p) (void)hipFree(p);
+    void *drop = g->slab;
+    if (g->slab) {
+        std::lock_guard<std::mutex> lock(g_slab_cache.mu);
+        slab_cache &c = g_slab_cache;
+        if (!c.ptr || c.bytes < g->slab_bytes) {
+            drop = c.ptr;
+            c.ptr = g->slab;
+            c.bytes = g->slab_bytes;
+            c.device = g->device;
+        }
+    }
+    if (drop) (void)hipFree(drop);
+    if (g->scratch) (void)hipFree(g->scratch);
     g->slab = nullptr;
+    g->slab_bytes = 0;
     g->scratch = nullptr;
 }
 
@@ -421,6 +445,28 @@ gnn_status slab_alloc(void **out, size_t bytes)
         *out = nullptr;
         return GNN_ERR_ALLOC;
     }
+    return GNN_OK;
+}
+
+gnn_status graph_slab_acquire(gnn_graph *g, size_t bytes)
+{
+    int dev = 0;
+    GNN_HIP(hipGetDevice(&dev));
+    g->device = dev;
+    {
+        std::lock_guard<std::mutex> lock(g_slab_cache.mu);
+        slab_cache &c = g_slab_cache;
+        if (c.ptr && c.device == dev && c.bytes >= bytes && c.bytes / 2 <= bytes) {
+            g->slab = c.ptr;
+            g->slab_bytes = c.bytes;
+            c.ptr = nullptr;
+            c.bytes = 0;
+            c.device = -1;
+            return GNN_OK;
+        }
+    }
+    GNN_TRY(slab_alloc(&g->slab, bytes));
+    g->slab_bytes = bytes ? bytes : 256;
     return GNN_OK;
 }
 
@@ -504,7 +550,7 @@ gnn_status build_impl(const int32_t *d_src, const int32_t *d_dst, int64_t E, int
                  o_rowidx = pa.add(E), o_dstcoo = pa.add(E), o_small = pa.add(N), o_irow = pa.add(max_items),
                  o_istart = pa.add(max_items), o_islot = pa.add(max_items), o_srows = pa.add(max_split),
                  o_sslot = pa.add(max_split), o_dinv1 = pa.add(N), o_dinv0 = pa.add(N);
-    GNN_TRY(slab_alloc(&g->slab, pa.bytes));
+    GNN_TRY(graph_slab_acquire(g, pa.bytes));
     g->rowptr = at(g->slab, o_rowptr);
     g->indeg = at(g->slab, o_indeg);
     g->colidx = at(g->slab, o_colidx);
@@ -675,6 +721,13 @@ int32_t gnn_graph_num_src_nodes(const gnn_graph *g) { return g ? g->num_src_node
 
 gnn_status gnn_release_cached_memory(void)
 {
+    {
+        std::lock_guard<std::mutex> lock(g_slab_cache.mu);
+        if (g_slab_cache.ptr) (void)hipFree(g_slab_cache.ptr);
+        g_slab_cache.ptr = nullptr;
+        g_slab_cache.bytes = 0;
+        g_slab_cache.device = -1;
+    }
     std::lock_guard<std::mutex> lock(g_temp_cache.mu);
     if (g_temp_cache.lent) return GNN_ERR_UNSUPPORTED;   // a build is running on another thread
     if (g_temp_cache.ptr) (void)hipFree(g_temp_cache.ptr);

@@ -58,6 +58,8 @@ struct gnn_graph {
     int32_t chunk = 0;       // longer rows: pieces of <= chunk edges, one wavefront each
 
     void *slab = nullptr;        // the one allocation holding every array below
+    size_t slab_bytes = 0;       // its size, and the device it lives on (it may be handed to a later build)
+    int device = -1;
 
     int32_t *rowptr = nullptr;   // [N+1]
     int32_t *indeg = nullptr;    // [N]

@@ -105,6 +105,30 @@ def test_csr_hand_worked_and_edge_cases(gnn, golden_dir):
     g1.close()
 
 
+def test_build_after_destroy_reuses_arrays(gnn):
+    """A destroyed graph's device arrays are handed to the next build of a similar size: builds of a larger, a
+    slightly smaller, an empty and a much smaller graph in a row, each destroyed before the next, all bit-exact;
+    then the cache is released and a build allocates again."""
+    cases = [powerlaw(6000, 90_000, 4, 2000.0), powerlaw(5000, 70_000, 4, 2000.0),
+             synth.Workload("empty", 5000, np.zeros(0, np.int32), np.zeros(0, np.int32), np.zeros((5000, 4), np.float32)),
+             powerlaw(300, 2000, 4, 100.0), powerlaw(6000, 90_000, 4, 2000.0)]
+    for step, wl in enumerate(cases):
+        if step == 4:
+            gnn.release_cached_memory()
+        g = gnn.build_csr(dev(wl.src), dev(wl.dst), wl.num_nodes)
+        rowptr, colidx, perm, indeg = oracle.build_csr(wl.src, wl.dst, wl.num_nodes)
+        np.testing.assert_array_equal(host(g.rowptr), rowptr)
+        np.testing.assert_array_equal(host(g.indegree), indeg)
+        np.testing.assert_array_equal(host(g.perm), perm)
+        np.testing.assert_array_equal(host(g.colidx), colidx)
+        x = dev(wl.x)
+        ref = oracle.propagate(wl.src, wl.dst, wl.num_nodes, wl.x, None, MSG_COPY_XJ, AGGR_MAX)
+        np.testing.assert_array_equal(host(gnn.propagate(g, x, None, MSG_COPY_XJ, AGGR_MAX)).view(np.uint32),
+                                      ref.view(np.uint32))
+        g.close()
+    gnn.release_cached_memory()
+
+
 def test_csr_rejects_out_of_range(gnn):
     src = dev(np.array([0, 1, 7], np.int32))
     dst = dev(np.array([1, 2, 0], np.int32))
