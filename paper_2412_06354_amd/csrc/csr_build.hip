@@ -82,12 +82,12 @@ constexpr int kSortTile = kThreads * kSortItems;     // keys per block
 constexpr int kDigitBitsMax = 8;   // 10-bit digits (two passes at 2^20 nodes) were measured: the scatter pass takes 2.4 x as long
 constexpr int kRadixMax = 1 << kDigitBitsMax;
 
-// Per-tile digit counts, laid out [digit][tile] so that one exclusive scan over the whole
-// array yields, for every (digit, tile), the first output position of that tile's keys.
-// Every wavefront counts into its own LDS histogram (fewer colliding atomics), the copies are added at the end.
+// Per-tile digit counts, laid out [digit][tile]: an exclusive scan along each digit's row gives, for every
+// (digit, tile), the number of that digit's keys in earlier tiles, and the row totals give the digits' first
+// positions in the output (added up by the scatter pass itself).
 constexpr int kCountThreads = 1024;
 constexpr int kCountItems = kSortTile / kCountThreads;
-constexpr int kCountWaves = kCountThreads / 64;
+constexpr int kCountCopies = 8;
 
 // CHECK: the first pass over the caller's arrays also does the range check of both index arrays and keeps a copy
 // of the destinations (the keys) in the caller's edge order.
@@ -99,12 +99,13 @@ __global__ __launch_bounds__(kCountThreads) void sort_count_kernel(const int32_t
                                                                    int32_t *__restrict__ key_copy,
                                                                    int32_t *__restrict__ bad)
 {
-    __shared__ int cnt[kCountWaves * kRadixMax];   // [wavefront][digit], rows of `radix` entries
+    // Every digit has kCountCopies counters, lane l adds to copy l % kCountCopies: lanes that hold the same digit
+    // (a hub node fills many lanes of a wavefront in the later passes, whose input is sorted by the low bits)
+    // spread over several LDS addresses in different banks instead of queueing on one.
+    __shared__ int cnt[kRadixMax * kCountCopies];   // [digit][copy]
     const int radix = 1 << bits, mask = radix - 1;
-    const int w = threadIdx.x >> 6;
-    for (int d = threadIdx.x; d < kCountWaves * radix; d += kCountThreads) cnt[d] = 0;
-    const int lane = threadIdx.x & 63;
-    volatile int *my_cnt = cnt + w * radix;
+    for (int d = threadIdx.x; d < radix * kCountCopies; d += kCountThreads) cnt[d] = 0;
+    const int copy = threadIdx.x & (kCountCopies - 1);
     // A block walks over several tiles; the next tile's keys are loaded while this one's are counted.
     int key[kCountItems], next_key[kCountItems], next_src[kCountItems];
     auto load_tile = [&](int tile) {
@@ -127,27 +128,12 @@ __global__ __launch_bounds__(kCountThreads) void sort_count_kernel(const int32_t
         }
         __syncthreads();   // counters are zero
         load_tile(tile + gridDim.x);
-        // Atomics on one LDS address are served one lane at a time, and in the later passes the 64 keys of a
-        // wavefront share their low bits, so a hub node fills many lanes with the same digit.  Large groups of
-        // equal digits are therefore peeled off first: the digit of the first remaining lane is compared in all
-        // lanes (one ballot) and the leader adds the group's size without an atomic; what is left -- or
-        // everything, when the first group is small -- goes through the atomics.  (Finding all groups with
-        // ballots, as the scatter pass does for its ranks, was measured: slower on average.)
 #pragma unroll
         for (int i = 0; i < kCountItems; ++i) {
             const int64_t idx = (int64_t)tile * kSortTile + i * kCountThreads + threadIdx.x;
             const bool valid = idx < n;
             const int d = (key[i] >> shift) & mask;
-            uint64_t todo = __ballot(valid);
-            for (int round = 0; round < 3 && todo; ++round) {
-                const int leader = __ffsll((long long)todo) - 1;
-                const int d0 = __builtin_amdgcn_readlane(d, leader);
-                const uint64_t group = __ballot(valid && d == d0) & todo;
-                if (__popcll(group) < 6) break;
-                if (lane == leader) my_cnt[d0] += __popcll(group);
-                todo &= ~group;
-            }
-            if ((todo >> lane) & 1) atomicAdd(&cnt[w * radix + d], 1);
+            if (valid) atomicAdd(&cnt[d * kCountCopies + copy], 1);
             if constexpr (CHECK)
                 if (valid) __builtin_nontemporal_store(key[i], key_copy + idx);
         }
@@ -155,9 +141,9 @@ __global__ __launch_bounds__(kCountThreads) void sort_count_kernel(const int32_t
         for (int d = threadIdx.x; d < radix; d += kCountThreads) {
             int t = 0;
 #pragma unroll
-            for (int q = 0; q < kCountWaves; ++q) {
-                t += cnt[q * radix + d];
-                cnt[q * radix + d] = 0;
+            for (int q = 0; q < kCountCopies; ++q) {
+                t += cnt[d * kCountCopies + q];
+                cnt[d * kCountCopies + q] = 0;
             }
             tile_counts[(int64_t)d * num_tiles + tile] = t;
         }
@@ -185,13 +171,14 @@ static_assert(kScatterItems * kScatterThreads == kSortTile, "tile size");
 
 __global__ __launch_bounds__(kScatterThreads) void sort_scatter_kernel(
     const int32_t *__restrict__ keys_in, const int32_t *__restrict__ val_in, const int32_t *__restrict__ eid_in,
-    int64_t n, int shift, int bits, const int32_t *__restrict__ tile_offsets, int num_tiles,
+    int64_t n, int shift, int bits, const int32_t *__restrict__ tile_offsets,
+    const int32_t *__restrict__ digit_totals, int num_tiles,
     int32_t *__restrict__ keys_out, int32_t *__restrict__ val_out, int32_t *__restrict__ eid_out)
 {
     __shared__ int wcnt[kScatterWaves * kRadixMax];   // [wavefront][digit], rows of `radix` entries
     __shared__ int dbase[kRadixMax];   // first tile-local position of each digit
     __shared__ int gbase[kRadixMax];   // global position of that element minus dbase
-    __shared__ int wave_sums[kScatterWaves];
+    __shared__ long long wave_sums[kScatterWaves];
     __shared__ int stage[3][kSortTile];
     const int radix = 1 << bits, mask = radix - 1;
     const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -208,6 +195,11 @@ __global__ __launch_bounds__(kScatterThreads) void sort_scatter_kernel(
     const int tile_count = (int)min((int64_t)kSortTile, n - tile_base);
     const uint64_t lt_mask = (1ull << lane) - 1ull;
     volatile int *my_cnt = wcnt + w * radix;
+    // tile_offsets[digit][tile] counts the digit's keys in earlier tiles; the digit's first position in the whole
+    // output is the sum of the smaller digits' totals, taken below in the same scan as the tile-local bases
+    const bool digit_thread = (int)threadIdx.x < radix;
+    const int digit_total = digit_thread ? digit_totals[threadIdx.x] : 0;
+    const int digit_earlier = digit_thread ? tile_offsets[(int64_t)threadIdx.x * num_tiles + tile] : 0;
     int key[kScatterItems], val[kScatterItems], eid[kScatterItems], lpos[kScatterItems];
 #pragma unroll
     for (int i = 0; i < kScatterItems; ++i) {
@@ -240,7 +232,7 @@ __global__ __launch_bounds__(kScatterThreads) void sort_scatter_kernel(
     __syncthreads();
     // per digit: offsets of the wavefronts inside the digit, digit totals -> tile-local digit bases
     int total = 0;
-    if ((int)threadIdx.x < radix) {
+    if (digit_thread) {
         const int d = threadIdx.x;
 #pragma unroll
         for (int q = 0; q < kScatterWaves; ++q) {
@@ -249,24 +241,29 @@ __global__ __launch_bounds__(kScatterThreads) void sort_scatter_kernel(
             total += c;
         }
     }
-    int excl;
-    {   // block-wide exclusive scan of `total`
-        int inc = total;
+    int excl, digit_first;
+    {   // block-wide exclusive scan over the digits of two sums at once: the tile's counts (at most kSortTile in
+        // all, the low 16 bits) and the whole input's counts (less than 2^31 in all, the bits above)
+        static_assert(kSortTile < (1 << 16), "tile-local counts share a word with the global ones");
+        const long long both = ((long long)digit_total << 16) | (long long)total;
+        long long inc = both;
 #pragma unroll
         for (int off = 1; off < 64; off <<= 1) {
-            const int t = __shfl_up(inc, off, 64);
+            const long long t = __shfl_up(inc, off, 64);
             if (lane >= off) inc += t;
         }
         if (lane == 63) wave_sums[w] = inc;
         __syncthreads();
-        int base = 0;
+        long long base = 0;
         for (int q = 0; q < kScatterWaves; ++q)
             if (q < w) base += wave_sums[q];
-        excl = base + inc - total;
+        const long long before = base + inc - both;
+        excl = (int)(before & 0xffff);
+        digit_first = (int)(before >> 16);
     }
-    if ((int)threadIdx.x < radix) {
+    if (digit_thread) {
         dbase[threadIdx.x] = excl;
-        gbase[threadIdx.x] = tile_offsets[(int64_t)threadIdx.x * num_tiles + tile] - excl;
+        gbase[threadIdx.x] = digit_first + digit_earlier - excl;
     }
     __syncthreads();
 #pragma unroll
@@ -568,16 +565,16 @@ gnn_status build_impl(const int32_t *d_src, const int32_t *d_dst, int64_t E, int
 
     // ---- temporaries: one buffer, normally the cached one
     slab_plan pt;
-    const size_t scan_elems = std::max(gnn_scan_tmp_elems((int64_t)(4 * np1)), gnn_scan_tmp_elems(num_tiles * kRadixMax));
+    const size_t scan_elems = gnn_scan_tmp_elems((int64_t)(4 * np1));
     const size_t o_flag = pt.add(64), o_scan = pt.add(scan_elems), o_kb = pt.add(E), o_vb = pt.add(E),
-                 o_eb = pt.add(E), o_counts = pt.add((size_t)num_tiles * kRadixMax),
+                 o_eb = pt.add(E), o_counts = pt.add((size_t)num_tiles * kRadixMax), o_dtot = pt.add(kRadixMax),
                  o_flags = pt.add(4 * np1), o_pos = pt.add(4 * np1);
     temp_lease tmp;
     GNN_TRY(temp_acquire(&tmp, pt.bytes));
     char *ts = static_cast<char *>(tmp.ptr);
     int32_t *d_flag = at(ts, o_flag), *scan_tmp = at(ts, o_scan), *kb = at(ts, o_kb), *vb = at(ts, o_vb),
-            *eb = at(ts, o_eb), *counts = at(ts, o_counts), *flags = at(ts, o_flags),
-            *pos = at(ts, o_pos);
+            *eb = at(ts, o_eb), *counts = at(ts, o_counts), *digit_totals = at(ts, o_dtot),
+            *flags = at(ts, o_flags), *pos = at(ts, o_pos);
 
     // ---- the index range check and the copy of the destinations in edge order ride on the first counting
     //      pass of the sort.  The flag is read back at the end; nothing below indexes with an unchecked node id:
@@ -616,9 +613,9 @@ gnn_status build_impl(const int32_t *d_src, const int32_t *d_dst, int64_t E, int
                                        counts, (int)num_tiles, (const int32_t *)nullptr, 0, 0, (int32_t *)nullptr,
                                        (int32_t *)nullptr);
                 GNN_LAUNCH_CHECK();
-                GNN_TRY(gnn_scan_exclusive_i32(counts, counts, num_tiles << bits, false, scan_tmp, stream));
+                GNN_TRY(gnn_scan_rows_exclusive_i32(counts, 1 << bits, num_tiles, digit_totals, stream));
                 hipLaunchKernelGGL(sort_scatter_kernel, dim3((unsigned)(gnn_div_up(num_tiles, kDies) * kDies)), dim3(kScatterThreads), 0, stream, ki, vi,
-                                   ei, E, shift, bits, counts, (int)num_tiles, bufk[dst_sel], bufv[dst_sel],
+                                   ei, E, shift, bits, counts, digit_totals, (int)num_tiles, bufk[dst_sel], bufv[dst_sel],
                                    bufe[dst_sel]);
                 GNN_LAUNCH_CHECK();
                 ki = bufk[dst_sel];

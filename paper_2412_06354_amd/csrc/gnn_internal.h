@@ -98,6 +98,10 @@ gnn_status gnn_graph_reserve_scratch(const gnn_graph *g, size_t floats);
 size_t gnn_scan_tmp_elems(int64_t n);
 gnn_status gnn_scan_exclusive_i32(const int32_t *d_in, int32_t *d_out, int64_t n, bool append_total,
                                   int32_t *d_tmp, hipStream_t stream);
+// Exclusive prefix sums along every row of a row-major [rows x cols] array, in place; d_row_totals[r] receives the
+// sum of row r.
+gnn_status gnn_scan_rows_exclusive_i32(int32_t *d_data, int rows, int64_t cols, int32_t *d_row_totals,
+                                       hipStream_t stream);
 
 // Epilogue applied to a finished row reduction:  out = act(post * (acc + self_scale * x[row]) + bias)
 // with post = row_scale[row] (or 1), or acc / in-degree for the mean.

@@ -4,6 +4,8 @@
 // Two levels: every block reduces its tile, one block scans the block sums, every block
 // then scans its tile starting from its offset.  A tile is 256 threads x 8 values.  Up to 2048 tiles the
 // middle step is folded into the last one (each block adds up the sums before it); one tile is one kernel.
+// The radix sort's [digit][tile] counts are scanned row by row instead (one block per digit, one kernel); the
+// scatter pass adds the digits' bases itself.
 #include "gnn_internal.h"
 
 namespace {
@@ -113,7 +115,60 @@ __global__ __launch_bounds__(kThreads) void scan_downsweep_kernel(const int32_t 
     }
 }
 
+// Exclusive prefix sums along every row of a [rows x cols] array, in place, and the row totals: one block of
+// kRowThreads threads per row, kItems consecutive values per thread, chunk after chunk with a running carry.
+constexpr int kRowThreads = 1024;
+
+__global__ __launch_bounds__(kRowThreads) void scan_rows_kernel(int32_t *__restrict__ data, int64_t cols,
+                                                                int32_t *__restrict__ row_totals)
+{
+    __shared__ int wave_sums[kRowThreads / 64];
+    int32_t *row = data + (int64_t)blockIdx.x * cols;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    int carry = 0;
+    for (int64_t chunk = 0; chunk < cols; chunk += (int64_t)kRowThreads * kItems) {
+        const int64_t base = chunk + (int64_t)threadIdx.x * kItems;
+        int v[kItems];
+        int s = 0;
+#pragma unroll
+        for (int i = 0; i < kItems; ++i) {
+            v[i] = (base + i < cols) ? row[base + i] : 0;
+            s += v[i];
+        }
+        const int inc = wave_inclusive_scan(s);
+        if (lane == 63) wave_sums[w] = inc;
+        __syncthreads();
+        int before = 0, total = 0;
+#pragma unroll
+        for (int q = 0; q < kRowThreads / 64; ++q) {
+            const int t = wave_sums[q];
+            if (q < w) before += t;
+            total += t;
+        }
+        __syncthreads();   // wave_sums is rewritten by the next chunk
+        int run = carry + before + inc - s;
+#pragma unroll
+        for (int i = 0; i < kItems; ++i) {
+            if (base + i < cols) row[base + i] = run;
+            run += v[i];
+        }
+        carry += total;
+    }
+    if (threadIdx.x == 0) row_totals[blockIdx.x] = carry;
+}
+
 }  // namespace
+
+gnn_status gnn_scan_rows_exclusive_i32(int32_t *d_data, int rows, int64_t cols, int32_t *d_row_totals,
+                                       hipStream_t stream)
+{
+    if (rows < 0 || cols < 0) return GNN_ERR_BAD_SIZE;
+    if (rows == 0) return GNN_OK;
+    hipLaunchKernelGGL(scan_rows_kernel, dim3((unsigned)rows), dim3(kRowThreads), 0, stream, d_data, cols,
+                       d_row_totals);
+    GNN_LAUNCH_CHECK();
+    return GNN_OK;
+}
 
 size_t gnn_scan_tmp_elems(int64_t n)
 {
