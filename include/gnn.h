@@ -142,6 +142,17 @@ int32_t gnn_graph_num_src_nodes(const gnn_graph *g);   /* differs only for gnn_b
 int64_t gnn_graph_num_edges(const gnn_graph *g);
 /* Host-side sizes of the work lists: rows reduced by a sub-group, wavefront work items, split rows. */
 void gnn_graph_work_sizes(const gnn_graph *g, int32_t *n_small_rows, int32_t *n_items, int32_t *n_split_rows);
+/*
+ * Borrowed device pointers to the work lists themselves (introspection and tests; any argument may be NULL):
+ *   small_rows[n_small_rows]   the short rows, ascending;
+ *   item_row / item_start / item_slot [n_items]   one entry per piece of a longer row, rows ascending and a row's
+ *     pieces in order: the row, the piece's first CSR position, and its partial-result slot (-1 when the row is one
+ *     piece; a split row's pieces have consecutive slots);
+ *   split_rows / split_slot0 [n_split_rows]   the rows made of several pieces, ascending, and their first slot.
+ */
+void gnn_graph_work_lists(const gnn_graph *g, const int32_t **small_rows, const int32_t **item_row,
+                          const int32_t **item_start, const int32_t **item_slot, const int32_t **split_rows,
+                          const int32_t **split_slot0);
 
 /*
  * Per-edge data from the caller's COO order into CSR order:

@@ -36,6 +36,7 @@ SIGNATURES = {
     "gnn_graph_num_nodes": (_i32, [_vp]),
     "gnn_graph_num_edges": (_i64, [_vp]),
     "gnn_graph_work_sizes": (None, [_vp, _c.POINTER(_i32), _c.POINTER(_i32), _c.POINTER(_i32)]),
+    "gnn_graph_work_lists": (None, [_vp] + [_c.POINTER(_vp)] * 6),
     "gnn_edge_data_to_csr": (_c.c_int, [_vp, _vp, _i32, _vp, _vp]),
     "gnn_propagate": (_c.c_int, [_vp, _vp, _i32, _vp, _i32, _c.c_int, _c.c_int, _c.c_int, _vp, _vp]),
     "gnn_build_csr_bipartite": (_c.c_int, [_vp, _vp, _i64, _i32, _i32, _vp, _c.POINTER(_vp)]),
@@ -176,6 +177,15 @@ class Graph:
         a, b, c = _i32(), _i32(), _i32()
         lib().gnn_graph_work_sizes(self._h, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c))
         return {"small_rows": a.value, "items": b.value, "split_rows": c.value}
+
+    def work_lists(self):
+        """Copies of the work lists as int32 tensors (see gnn_graph_work_lists)."""
+        sizes = self.work_sizes()
+        ptrs = [_vp() for _ in range(6)]
+        lib().gnn_graph_work_lists(self._h, *[ctypes.byref(p) for p in ptrs])
+        names = ("small_rows", "item_row", "item_start", "item_slot", "split_rows", "split_slot0")
+        counts = (sizes["small_rows"],) + (sizes["items"],) * 3 + (sizes["split_rows"],) * 2
+        return {k: self._view(p.value or 0, c) for k, p, c in zip(names, ptrs, counts)}
 
     def close(self):
         if self._h:

@@ -756,6 +756,18 @@ void gnn_graph_work_sizes(const gnn_graph *g, int32_t *n_small_rows, int32_t *n_
     if (n_split_rows) *n_split_rows = g ? g->n_split : 0;
 }
 
+void gnn_graph_work_lists(const gnn_graph *g, const int32_t **small_rows, const int32_t **item_row,
+                          const int32_t **item_start, const int32_t **item_slot, const int32_t **split_rows,
+                          const int32_t **split_slot0)
+{
+    if (small_rows) *small_rows = g ? g->small_rows : nullptr;
+    if (item_row) *item_row = g ? g->item_row : nullptr;
+    if (item_start) *item_start = g ? g->item_start : nullptr;
+    if (item_slot) *item_slot = g ? g->item_slot : nullptr;
+    if (split_rows) *split_rows = g ? g->split_rows : nullptr;
+    if (split_slot0) *split_slot0 = g ? g->split_slot0 : nullptr;
+}
+
 gnn_status gnn_edge_data_to_csr(const gnn_graph *g, const float *d_e, int32_t e_dim, float *d_e_csr, void *stream)
 {
     if (!g) return GNN_ERR_NULL;

@@ -105,6 +105,53 @@ def test_csr_hand_worked_and_edge_cases(gnn, golden_dir):
     g1.close()
 
 
+def expected_work_lists(rowptr, small_max, chunk):
+    """The degree-bucketed schedule as gnn.h states it, written out row by row."""
+    small, item_row, item_start, item_slot, split_rows, split_slot0 = [], [], [], [], [], []
+    slots = 0
+    for r in range(len(rowptr) - 1):
+        start, deg = int(rowptr[r]), int(rowptr[r + 1] - rowptr[r])
+        if deg <= small_max:
+            small.append(r)
+            continue
+        pieces = -(-deg // chunk)
+        if pieces > 1:
+            split_rows.append(r)
+            split_slot0.append(slots)
+        for c in range(pieces):
+            item_row.append(r)
+            item_start.append(start + c * chunk)
+            item_slot.append(slots + c if pieces > 1 else -1)
+        if pieces > 1:
+            slots += pieces
+    return {"small_rows": small, "item_row": item_row, "item_start": item_start, "item_slot": item_slot,
+            "split_rows": split_rows, "split_slot0": split_slot0}
+
+
+@pytest.mark.parametrize("n,e,small_max,chunk", [(20_000, 300_000, 16, 256), (5000, 120_000, 4, 64), (3000, 50_000, 0, 64),
+                                                 (1, 700, 8, 128), (2500, 0, 16, 256), (4097, 30_000, 64, 65536)])
+def test_work_lists(gnn, n, e, small_max, chunk):
+    """Every entry of the work lists against the schedule computed on the host from the oracle's row pointers
+    (several list-kernel blocks, a ragged last block, one-node, edge-free and all-short graphs)."""
+    if e == 0:
+        src = dst = np.zeros(0, np.int32)
+    elif n == 1:
+        src = dst = np.zeros(e, np.int32)
+    else:
+        wl = powerlaw(n, e, 4, max(50.0, e / 40.0))
+        src, dst = wl.src, wl.dst
+    g = gnn.build_csr(dev(src), dev(dst), n, small_max, chunk)
+    rowptr, _, _, _ = oracle.build_csr(src, dst, n)
+    want = expected_work_lists(rowptr, small_max, chunk)
+    got = g.work_lists()
+    sizes = g.work_sizes()
+    assert sizes == {"small_rows": len(want["small_rows"]), "items": len(want["item_row"]),
+                     "split_rows": len(want["split_rows"])}
+    for name, ref in want.items():
+        np.testing.assert_array_equal(host(got[name]), np.array(ref, np.int32), err_msg=name)
+    g.close()
+
+
 def test_build_after_destroy_reuses_arrays(gnn):
     """A destroyed graph's device arrays are handed to the next build of a similar size: builds of a larger, a
     slightly smaller, an empty and a much smaller graph in a row, each destroyed before the next, all bit-exact;
