@@ -36,15 +36,6 @@ __global__ __launch_bounds__(kThreads) void check_range_kernel(const int32_t *__
     if (any_bad) atomicOr(bad, 1);
 }
 
-// Copies the range flag and the four list sizes into one small array (one host read-back).  pos holds ONE
-// exclusive scan over the four concatenated flag arrays, so a list's size is a difference.
-__global__ void gather_totals_kernel(const int32_t *__restrict__ flag, const int32_t *__restrict__ pos, int64_t np1,
-                                     int32_t N, int32_t *__restrict__ out)
-{
-    if (threadIdx.x == 0) out[0] = flag[0];
-    if (threadIdx.x < 4) out[1 + threadIdx.x] = pos[threadIdx.x * np1 + N] - pos[threadIdx.x * np1];
-}
-
 // Row pointers straight from the sorted destinations: where the key changes from a to b at position p, the
 // rows a+1 .. b start at p (rows that do not occur get the start of the next one that does); before the first
 // key a = -1, after the last one the remaining rows and rowptr[N] get E.  Valid, sorted keys write every entry
@@ -307,67 +298,155 @@ __global__ __launch_bounds__(kThreads) void iota_copy_kernel(const int32_t *__re
 
 // ---------------------------------------------------------------- work lists
 
-// Per row: is it a short row, how many wavefront pieces it needs, how many partial-result
-// slots (pieces of rows made of more than one piece), is it split.
+// Two kernels and a small scan in between.  A block owns kListRows consecutive rows, a thread kListRowsPerThread of
+// them.  Per row: is it a short row, how many wavefront pieces it needs, how many partial-result slots (pieces of
+// rows made of more than one piece), is it split.  classify_rows_kernel writes what is kept per row (in-degree,
+// the two degree factors of the GCN normalisation) and the block's four sums; a row-wise scan turns the sums into
+// each block's first position in the four lists (and the lists' sizes); fill_lists_kernel classifies its rows again
+// -- cheaper than storing and re-reading four flags per row -- scans inside the block and writes the lists.
+// Everything is in row order and free of atomics, so the lists are the same on every run.
+constexpr int kListRowsPerThread = 4;
+constexpr int kListRows = kThreads * kListRowsPerThread;
+
+struct RowCounts {
+    long long small_split = 0;   // short rows in the low 32 bits, split rows above
+    long long items_slots = 0;   // pieces in the low 32 bits, slots above
+};
+
+// Sums fit their halves: at most kListRows rows per block, and less than 2^31 / 64 + kListRows pieces.
+__device__ __forceinline__ void count_row(RowCounts &c, int deg, int small_max, int chunk)
+{
+    const int small = deg <= small_max;
+    const int items = small ? 0 : (deg + chunk - 1) / chunk;
+    const int split = items > 1;
+    c.small_split += (long long)small | ((long long)split << 32);
+    c.items_slots += (long long)items | ((long long)(split ? items : 0) << 32);
+}
+
+// Exclusive scan of one value per thread over the block; *total receives the block's sum.
+__device__ __forceinline__ long long block_exclusive_scan_i64(long long v, long long *total)
+{
+    __shared__ long long wave_sums[kThreads / 64];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    long long inc = v;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const long long t = __shfl_up(inc, off, 64);
+        if (lane >= off) inc += t;
+    }
+    if (lane == 63) wave_sums[w] = inc;
+    __syncthreads();
+    long long before = 0, all = 0;
+#pragma unroll
+    for (int q = 0; q < kThreads / 64; ++q) {
+        const long long t = wave_sums[q];
+        if (q < w) before += t;
+        all += t;
+    }
+    __syncthreads();   // wave_sums is written again by the next call
+    *total = all;
+    return before + inc - v;
+}
+
+// Row pointers of the thread's rows: rp[i] = rowptr[r0 + i] for r0 + i <= N (0 beyond).
+__device__ __forceinline__ void load_row_pointers(const int32_t *__restrict__ rowptr, int32_t N, int64_t r0,
+                                                  int32_t (&rp)[kListRowsPerThread + 1])
+{
+#pragma unroll
+    for (int i = 0; i <= kListRowsPerThread; ++i) rp[i] = (r0 + i <= N) ? rowptr[r0 + i] : 0;
+}
+
 __global__ __launch_bounds__(kThreads) void classify_rows_kernel(const int32_t *__restrict__ rowptr, int32_t N,
                                                                  int32_t small_max, int32_t chunk,
                                                                  const int32_t *__restrict__ bad,
                                                                  int32_t *__restrict__ indeg,
-                                                                 int32_t *__restrict__ f_small,
-                                                                 int32_t *__restrict__ f_items,
-                                                                 int32_t *__restrict__ f_slots,
-                                                                 int32_t *__restrict__ f_split,
                                                                  float *__restrict__ dinv_loop,
-                                                                 float *__restrict__ dinv_plain)
+                                                                 float *__restrict__ dinv_plain,
+                                                                 int32_t *__restrict__ block_sums, int num_blocks)
 {
-    const int32_t r = blockIdx.x * kThreads + threadIdx.x;
-    if (r >= N) return;
-    if (r == 0) f_small[N] = f_items[N] = f_slots[N] = f_split[N] = 0;   // the four arrays are scanned as one
-    // invalid input (the build will fail with an error): the row pointers mean nothing, every list stays empty
-    const int32_t deg = bad[0] ? 0 : rowptr[r + 1] - rowptr[r];
-    indeg[r] = deg;
-    const int small = deg <= small_max;
-    const int items = small ? 0 : (deg + chunk - 1) / chunk;
-    f_small[r] = small;
-    f_items[r] = items;
-    f_slots[r] = items > 1 ? items : 0;
-    f_split[r] = items > 1;
-    // the two degree factors of the GCN normalisation, kept with the graph
-    dinv_loop[r] = 1.0f / sqrtf((float)(deg + 1));
-    dinv_plain[r] = deg > 0 ? 1.0f / sqrtf((float)deg) : 0.0f;
+    const int64_t r0 = (int64_t)blockIdx.x * kListRows + (int64_t)threadIdx.x * kListRowsPerThread;
+    // invalid input (the build will fail with an error): the row pointers mean nothing, every row counts as empty
+    const bool invalid = bad[0] != 0;
+    int32_t rp[kListRowsPerThread + 1];
+    load_row_pointers(rowptr, N, r0, rp);
+    RowCounts c;
+#pragma unroll
+    for (int i = 0; i < kListRowsPerThread; ++i) {
+        const int64_t r = r0 + i;
+        if (r < N) {
+            const int32_t deg = invalid ? 0 : rp[i + 1] - rp[i];
+            indeg[r] = deg;
+            // the two degree factors of the GCN normalisation, kept with the graph
+            dinv_loop[r] = 1.0f / sqrtf((float)(deg + 1));
+            dinv_plain[r] = deg > 0 ? 1.0f / sqrtf((float)deg) : 0.0f;
+            count_row(c, deg, small_max, chunk);
+        }
+    }
+    long long ss, is;
+    (void)block_exclusive_scan_i64(c.small_split, &ss);
+    (void)block_exclusive_scan_i64(c.items_slots, &is);
+    if (threadIdx.x == 0) {   // [list][block]: small rows, pieces, slots, split rows
+        block_sums[0 * (int64_t)num_blocks + blockIdx.x] = (int32_t)(ss & 0xffffffffll);
+        block_sums[1 * (int64_t)num_blocks + blockIdx.x] = (int32_t)(is & 0xffffffffll);
+        block_sums[2 * (int64_t)num_blocks + blockIdx.x] = (int32_t)(is >> 32);
+        block_sums[3 * (int64_t)num_blocks + blockIdx.x] = (int32_t)(ss >> 32);
+    }
 }
 
+// block_first: block_sums after the exclusive scan along each of its four rows; list_sizes: the four row totals.
+// info[0] = the range flag, info[1 .. 4] = the sizes of the lists (one host read-back for all five).
 __global__ __launch_bounds__(kThreads) void fill_lists_kernel(
     const int32_t *__restrict__ rowptr, int32_t N, int32_t small_max, int32_t chunk, const int32_t *__restrict__ bad,
-    const int32_t *__restrict__ p_small, const int32_t *__restrict__ p_items, const int32_t *__restrict__ p_slots,
-    const int32_t *__restrict__ p_split, int32_t *__restrict__ small_rows, int32_t *__restrict__ item_row,
-    int32_t *__restrict__ item_start, int32_t *__restrict__ item_slot, int32_t *__restrict__ split_rows,
-    int32_t *__restrict__ split_slot0)
+    const int32_t *__restrict__ block_first, int num_blocks, const int32_t *__restrict__ list_sizes,
+    int32_t *__restrict__ small_rows, int32_t *__restrict__ item_row, int32_t *__restrict__ item_start,
+    int32_t *__restrict__ item_slot, int32_t *__restrict__ split_rows, int32_t *__restrict__ split_slot0,
+    int32_t *__restrict__ info)
 {
-    const int32_t r = blockIdx.x * kThreads + threadIdx.x;
-    if (r >= N || bad[0]) return;   // invalid input: the lists were sized as empty
-    // the four position arrays are slices of one exclusive scan: positions are relative to each slice's first entry
-    const int32_t start = rowptr[r], deg = rowptr[r + 1] - start;
-    if (deg <= small_max) {
-        small_rows[p_small[r] - p_small[0]] = r;
-        return;
-    }
-    const int items = (deg + chunk - 1) / chunk;
-    const int32_t it0 = p_items[r] - p_items[0];
-    if (items == 1) {
-        item_row[it0] = r;
-        item_start[it0] = start;
-        item_slot[it0] = -1;
-        return;
-    }
-    const int32_t slot0 = p_slots[r] - p_slots[0];
-    const int32_t sp = p_split[r] - p_split[0];
-    split_rows[sp] = r;
-    split_slot0[sp] = slot0;
-    for (int c = 0; c < items; ++c) {
-        item_row[it0 + c] = r;
-        item_start[it0 + c] = start + c * chunk;
-        item_slot[it0 + c] = slot0 + c;
+    const bool invalid = bad[0] != 0;
+    if (blockIdx.x == 0 && threadIdx.x < 4) info[1 + threadIdx.x] = list_sizes[threadIdx.x];
+    if (blockIdx.x == 0 && threadIdx.x == 0) info[0] = invalid ? 1 : 0;
+    if (invalid) return;   // the whole grid leaves: the lists were sized for empty rows
+    const int64_t r0 = (int64_t)blockIdx.x * kListRows + (int64_t)threadIdx.x * kListRowsPerThread;
+    int32_t rp[kListRowsPerThread + 1];
+    load_row_pointers(rowptr, N, r0, rp);
+    RowCounts c;
+#pragma unroll
+    for (int i = 0; i < kListRowsPerThread; ++i)
+        if (r0 + i < N) count_row(c, rp[i + 1] - rp[i], small_max, chunk);
+    long long unused;
+    const long long ss = block_exclusive_scan_i64(c.small_split, &unused);
+    const long long is = block_exclusive_scan_i64(c.items_slots, &unused);
+    int32_t p_small = block_first[0 * (int64_t)num_blocks + blockIdx.x] + (int32_t)(ss & 0xffffffffll);
+    int32_t p_item = block_first[1 * (int64_t)num_blocks + blockIdx.x] + (int32_t)(is & 0xffffffffll);
+    int32_t p_slot = block_first[2 * (int64_t)num_blocks + blockIdx.x] + (int32_t)(is >> 32);
+    int32_t p_split = block_first[3 * (int64_t)num_blocks + blockIdx.x] + (int32_t)(ss >> 32);
+#pragma unroll
+    for (int i = 0; i < kListRowsPerThread; ++i) {
+        const int64_t r = r0 + i;
+        if (r >= N) break;
+        const int32_t start = rp[i], deg = rp[i + 1] - rp[i];
+        if (deg <= small_max) {
+            small_rows[p_small++] = (int32_t)r;
+            continue;
+        }
+        const int items = (deg + chunk - 1) / chunk;
+        if (items == 1) {
+            item_row[p_item] = (int32_t)r;
+            item_start[p_item] = start;
+            item_slot[p_item] = -1;
+            ++p_item;
+            continue;
+        }
+        split_rows[p_split] = (int32_t)r;
+        split_slot0[p_split] = p_slot;
+        ++p_split;
+        for (int q = 0; q < items; ++q) {
+            item_row[p_item + q] = (int32_t)r;
+            item_start[p_item + q] = start + q * chunk;
+            item_slot[p_item + q] = p_slot + q;
+        }
+        p_item += items;
+        p_slot += items;
     }
 }
 
@@ -565,16 +644,16 @@ gnn_status build_impl(const int32_t *d_src, const int32_t *d_dst, int64_t E, int
 
     // ---- temporaries: one buffer, normally the cached one
     slab_plan pt;
-    const size_t scan_elems = gnn_scan_tmp_elems((int64_t)(4 * np1));
-    const size_t o_flag = pt.add(64), o_scan = pt.add(scan_elems), o_kb = pt.add(E), o_vb = pt.add(E),
+    const int list_blocks = (int)gnn_div_up(N, kListRows);
+    const size_t o_flag = pt.add(64), o_kb = pt.add(E), o_vb = pt.add(E),
                  o_eb = pt.add(E), o_counts = pt.add((size_t)num_tiles * kRadixMax), o_dtot = pt.add(kRadixMax),
-                 o_flags = pt.add(4 * np1), o_pos = pt.add(4 * np1);
+                 o_bsum = pt.add(4 * (size_t)list_blocks), o_sizes = pt.add(4);
     temp_lease tmp;
     GNN_TRY(temp_acquire(&tmp, pt.bytes));
     char *ts = static_cast<char *>(tmp.ptr);
-    int32_t *d_flag = at(ts, o_flag), *scan_tmp = at(ts, o_scan), *kb = at(ts, o_kb), *vb = at(ts, o_vb),
+    int32_t *d_flag = at(ts, o_flag), *kb = at(ts, o_kb), *vb = at(ts, o_vb),
             *eb = at(ts, o_eb), *counts = at(ts, o_counts), *digit_totals = at(ts, o_dtot),
-            *flags = at(ts, o_flags), *pos = at(ts, o_pos);
+            *block_sums = at(ts, o_bsum), *list_sizes = at(ts, o_sizes);
 
     // ---- the index range check and the copy of the destinations in edge order ride on the first counting
     //      pass of the sort.  The flag is read back at the end; nothing below indexes with an unchecked node id:
@@ -633,16 +712,13 @@ gnn_status build_impl(const int32_t *d_src, const int32_t *d_dst, int64_t E, int
     }
 
     // ---- work lists (positions from scans; sizes are read back afterwards)
-    const int nblocks = (int)gnn_div_up(N, kThreads);
-    hipLaunchKernelGGL(classify_rows_kernel, dim3(nblocks), dim3(kThreads), 0, stream, g->rowptr, N, g->small_max,
-                       g->chunk, d_flag, g->indeg, flags, flags + np1, flags + 2 * np1, flags + 3 * np1, g->dinv_loop, g->dinv_plain);
+    hipLaunchKernelGGL(classify_rows_kernel, dim3(list_blocks), dim3(kThreads), 0, stream, g->rowptr, N, g->small_max,
+                       g->chunk, d_flag, g->indeg, g->dinv_loop, g->dinv_plain, block_sums, list_blocks);
     GNN_LAUNCH_CHECK();
-    GNN_TRY(gnn_scan_exclusive_i32(flags, pos, (int64_t)(4 * np1), false, scan_tmp, stream));
-    hipLaunchKernelGGL(fill_lists_kernel, dim3(nblocks), dim3(kThreads), 0, stream, g->rowptr, N, g->small_max,
-                       g->chunk, d_flag, pos, pos + np1, pos + 2 * np1, pos + 3 * np1, g->small_rows, g->item_row,
-                       g->item_start, g->item_slot, g->split_rows, g->split_slot0);
-    GNN_LAUNCH_CHECK();
-    hipLaunchKernelGGL(gather_totals_kernel, dim3(1), dim3(64), 0, stream, d_flag, pos, (int64_t)np1, N, d_flag + 8);
+    GNN_TRY(gnn_scan_rows_exclusive_i32(block_sums, 4, list_blocks, list_sizes, stream));
+    hipLaunchKernelGGL(fill_lists_kernel, dim3(list_blocks), dim3(kThreads), 0, stream, g->rowptr, N, g->small_max,
+                       g->chunk, d_flag, block_sums, list_blocks, list_sizes, g->small_rows, g->item_row,
+                       g->item_start, g->item_slot, g->split_rows, g->split_slot0, d_flag + 8);
     GNN_LAUNCH_CHECK();
     int32_t h_info[5] = {0, 0, 0, 0, 0};
     GNN_HIP(hipMemcpyAsync(h_info, d_flag + 8, sizeof(h_info), hipMemcpyDeviceToHost, stream));
