@@ -160,9 +160,10 @@ constexpr int kScatterItems = kSortTile / kScatterThreads;
 constexpr int kScatterWaves = kScatterThreads / 64;
 static_assert(kScatterItems * kScatterThreads == kSortTile, "tile size");
 
+template <int BITS>
 __global__ __launch_bounds__(kScatterThreads) void sort_scatter_kernel(
     const int32_t *__restrict__ keys_in, const int32_t *__restrict__ val_in, const int32_t *__restrict__ eid_in,
-    int64_t n, int shift, int bits, const int32_t *__restrict__ tile_offsets,
+    int64_t n, int shift, const int32_t *__restrict__ tile_offsets,
     const int32_t *__restrict__ digit_totals, int num_tiles,
     int32_t *__restrict__ keys_out, int32_t *__restrict__ val_out, int32_t *__restrict__ eid_out)
 {
@@ -171,7 +172,7 @@ __global__ __launch_bounds__(kScatterThreads) void sort_scatter_kernel(
     __shared__ int gbase[kRadixMax];   // global position of that element minus dbase
     __shared__ long long wave_sums[kScatterWaves];
     __shared__ int stage[3][kSortTile];
-    const int radix = 1 << bits, mask = radix - 1;
+    constexpr int radix = 1 << BITS, mask = radix - 1;
     const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
     // Blocks are dealt round-robin to the chip's eight dies, each with an L2 of its own.  A die gets a contiguous
     // range of tiles: neighbouring tiles' runs of one digit are neighbours in memory, and written through the
@@ -185,7 +186,6 @@ __global__ __launch_bounds__(kScatterThreads) void sort_scatter_kernel(
     const int64_t wbase = tile_base + (int64_t)w * 64 * kScatterItems;
     const int tile_count = (int)min((int64_t)kSortTile, n - tile_base);
     const uint64_t lt_mask = (1ull << lane) - 1ull;
-    volatile int *my_cnt = wcnt + w * radix;
     // tile_offsets[digit][tile] counts the digit's keys in earlier tiles; the digit's first position in the whole
     // output is the sum of the smaller digits' totals, taken below in the same scan as the tile-local bases
     const bool digit_thread = (int)threadIdx.x < radix;
@@ -206,18 +206,21 @@ __global__ __launch_bounds__(kScatterThreads) void sort_scatter_kernel(
         const int64_t idx = wbase + i * 64 + lane;
         const bool valid = idx < n;
         const int d = (key[i] >> shift) & mask;
-        uint64_t peers = __ballot(valid);
-        for (int b = 0; b < bits; ++b) {
-            const bool bit = (d >> b) & 1;
-            const uint64_t m = __ballot(bit);
-            peers &= bit ? m : ~m;
+        uint64_t peers = __ballot(valid);   // lanes of this wavefront that hold the same digit (and a key at all)
+#pragma unroll
+        for (int b = 0; b < BITS; ++b) {
+            const int32_t x = (int32_t)((uint32_t)d << (31 - b)) >> 31;   // all ones where bit b is set
+            const uint64_t m = __ballot(x != 0);
+            const uint64_t xx = ((uint64_t)(uint32_t)x << 32) | (uint32_t)x;
+            peers &= ~(m ^ xx);   // lanes whose bit b equals mine
         }
         const int r = __popcll(peers & lt_mask);
+        // the first lane of every group takes the group's places in the wavefront's counter row (one lane per
+        // digit: no two lanes share an address) and hands the old count to the others
         int before = 0;
-        if (valid) before = my_cnt[d];
-        __builtin_amdgcn_wave_barrier();
-        if (valid && r == 0) my_cnt[d] = before + __popcll(peers);
-        __builtin_amdgcn_wave_barrier();
+        if (valid && r == 0) before = atomicAdd(&wcnt[w * radix + d], __popcll(peers));
+        const int leader = (__ffsll((long long)peers) - 1) & 63;
+        before = __shfl(before, leader, 64);
         lpos[i] = before + r;
     }
     __syncthreads();
@@ -280,6 +283,35 @@ __global__ __launch_bounds__(kScatterThreads) void sort_scatter_kernel(
             eid_out[gpos] = stage[2][s];
         }
     }
+}
+
+// The digit width is a compile-time constant of the scatter kernel (its bit-by-bit matching loop is unrolled).
+template <int BITS>
+gnn_status launch_scatter_bits(int64_t blocks, hipStream_t stream, const int32_t *ki, const int32_t *vi, const int32_t *ei,
+                               int64_t E, int shift, const int32_t *counts, const int32_t *digit_totals, int num_tiles,
+                               int32_t *ko, int32_t *vo, int32_t *eo)
+{
+    hipLaunchKernelGGL(sort_scatter_kernel<BITS>, dim3((unsigned)blocks), dim3(kScatterThreads), 0, stream, ki, vi, ei, E,
+                       shift, counts, digit_totals, num_tiles, ko, vo, eo);
+    GNN_LAUNCH_CHECK();
+    return GNN_OK;
+}
+
+gnn_status launch_scatter(int bits, int64_t blocks, hipStream_t stream, const int32_t *ki, const int32_t *vi,
+                          const int32_t *ei, int64_t E, int shift, const int32_t *counts, const int32_t *digit_totals,
+                          int num_tiles, int32_t *ko, int32_t *vo, int32_t *eo)
+{
+    switch (bits) {
+    case 1: return launch_scatter_bits<1>(blocks, stream, ki, vi, ei, E, shift, counts, digit_totals, num_tiles, ko, vo, eo);
+    case 2: return launch_scatter_bits<2>(blocks, stream, ki, vi, ei, E, shift, counts, digit_totals, num_tiles, ko, vo, eo);
+    case 3: return launch_scatter_bits<3>(blocks, stream, ki, vi, ei, E, shift, counts, digit_totals, num_tiles, ko, vo, eo);
+    case 4: return launch_scatter_bits<4>(blocks, stream, ki, vi, ei, E, shift, counts, digit_totals, num_tiles, ko, vo, eo);
+    case 5: return launch_scatter_bits<5>(blocks, stream, ki, vi, ei, E, shift, counts, digit_totals, num_tiles, ko, vo, eo);
+    case 6: return launch_scatter_bits<6>(blocks, stream, ki, vi, ei, E, shift, counts, digit_totals, num_tiles, ko, vo, eo);
+    case 7: return launch_scatter_bits<7>(blocks, stream, ki, vi, ei, E, shift, counts, digit_totals, num_tiles, ko, vo, eo);
+    case 8: return launch_scatter_bits<8>(blocks, stream, ki, vi, ei, E, shift, counts, digit_totals, num_tiles, ko, vo, eo);
+    }
+    return GNN_ERR_BAD_SIZE;
 }
 
 __global__ __launch_bounds__(kThreads) void iota_copy_kernel(const int32_t *__restrict__ key_in,
@@ -693,10 +725,8 @@ gnn_status build_impl(const int32_t *d_src, const int32_t *d_dst, int64_t E, int
                                        (int32_t *)nullptr);
                 GNN_LAUNCH_CHECK();
                 GNN_TRY(gnn_scan_rows_exclusive_i32(counts, 1 << bits, num_tiles, digit_totals, stream));
-                hipLaunchKernelGGL(sort_scatter_kernel, dim3((unsigned)(gnn_div_up(num_tiles, kDies) * kDies)), dim3(kScatterThreads), 0, stream, ki, vi,
-                                   ei, E, shift, bits, counts, digit_totals, (int)num_tiles, bufk[dst_sel], bufv[dst_sel],
-                                   bufe[dst_sel]);
-                GNN_LAUNCH_CHECK();
+                GNN_TRY(launch_scatter(bits, gnn_div_up(num_tiles, kDies) * kDies, stream, ki, vi, ei, E, shift, counts,
+                                       digit_totals, (int)num_tiles, bufk[dst_sel], bufv[dst_sel], bufe[dst_sel]));
                 ki = bufk[dst_sel];
                 vi = bufv[dst_sel];
                 ei = bufe[dst_sel];
