@@ -42,9 +42,9 @@ MFMA_FP32_PEAK_TFLOPS = 157.3
 # (FETCH_SIZE x 2.000 calibration factor + WRITE_SIZE x 1.000, calibrated on a 1 GiB streaming kernel
 # in the same run).  Only meaningful for the default sizes of each workload; other sizes report null.
 MEASURED_TRAFFIC_BYTES = {
-    ("propagate", 1_000_000, 20_000_000, 64): 2_924_135_040,   # propagate_kernel<16,4,0,0,0>
-    ("gat", 2_449_029, 126_167_309, 64): 27_475_277_077,       # gat_kernel<16,4,2>
-    ("gcn", 100_000, 1_000_000, 128): 405_503_936,             # propagate_kernel<32,4,0,0,0>, GCN epilogue
+    ("propagate", 1_000_000, 20_000_000, 64): 2_923_834_560,   # propagate_kernel<16,4,0,0,0>
+    ("gat", 2_449_029, 126_167_309, 64): 27_474_537_984,       # gat_kernel<16,4,2>
+    ("gcn", 100_000, 1_000_000, 128): 405_539_984,             # propagate_kernel<32,4,0,0,0>, GCN epilogue
 }
 
 
