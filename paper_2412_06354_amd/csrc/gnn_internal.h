@@ -93,11 +93,6 @@ gnn_status gnn_launch_sum_partials_scaled(const float *d_partial, int chunks, in
 // Makes sure g->scratch holds at least `floats` floats.
 gnn_status gnn_graph_reserve_scratch(const gnn_graph *g, size_t floats);
 
-// Exclusive prefix sum of n int32 values; writes n outputs, plus the grand total as
-// output n when append_total.  d_tmp must hold gnn_scan_tmp_elems(n) int32.  in == out is allowed.
-size_t gnn_scan_tmp_elems(int64_t n);
-gnn_status gnn_scan_exclusive_i32(const int32_t *d_in, int32_t *d_out, int64_t n, bool append_total,
-                                  int32_t *d_tmp, hipStream_t stream);
 // Exclusive prefix sums along every row of a row-major [rows x cols] array, in place; d_row_totals[r] receives the
 // sum of row r.
 gnn_status gnn_scan_rows_exclusive_i32(int32_t *d_data, int rows, int64_t cols, int32_t *d_row_totals,
