@@ -872,3 +872,150 @@ def test_error_codes():
         oracle.propagate(src, dst, 3, x)
     with pytest.raises(oracle.OracleError):
         oracle.graph_pool(np.array([0, 1, 9], np.int32), 2, x)
+
+
+# ----------------------------------------------------------------------------- gradients per edge and S_abs magnitudes
+
+def test_g5_sabs_and_gradients_by_hand(golden_dir):
+    """Hand-worked S_abs of the forward (a row whose signed terms cancel to zero keeps the sum of their absolute
+    values) and hand-worked gradients with their S_abs, element by element."""
+    g5 = load_golden(golden_dir, "g5_propagate.json")
+    hw = load_golden(golden_dir, "sabs_handworked.json")["g5"]
+    src, dst = np.array(g5["src"], np.int32), np.array(g5["dst"], np.int32)
+    x, w = np.array(g5["x"], np.float32), np.array(g5["w"], np.float32)
+    for msg_name, msg in (("copy_xj", MSG_COPY_XJ), ("e_mul_xj", MSG_E_MUL_XJ)):
+        for aggr_name in ("sum", "mean"):
+            _, sabs = oracle.propagate(src, dst, 4, x, w if msg else None, msg, AGGRS[aggr_name], with_sabs=True)
+            np.testing.assert_allclose(sabs, np.array(hw[f"{msg_name}_{aggr_name}"]), rtol=1e-15, atol=0,
+                                       err_msg=f"{msg_name} {aggr_name}")
+    g = np.array(hw["grad_out"], np.float32)
+    for aggr_name in ("sum", "mean"):
+        bw = oracle.propagate_backward(src, dst, 4, x, g, w, MSG_E_MUL_XJ, AGGRS[aggr_name], with_sabs=True)
+        np.testing.assert_allclose(bw["grad_e"][:, 0], np.array(hw[f"grad_e_{aggr_name}"]), rtol=1e-7)
+        np.testing.assert_allclose(bw["sabs_e"][:, 0], np.array(hw[f"sabs_e_{aggr_name}"]), rtol=1e-15)
+        np.testing.assert_allclose(bw["grad_x"], np.array(hw[f"grad_x_{aggr_name}"]), rtol=1e-7)
+        np.testing.assert_allclose(bw["sabs_x"], np.array(hw[f"sabs_x_{aggr_name}"]), rtol=1e-15)
+
+
+def test_path3_layer_sabs_by_hand(golden_dir):
+    """GCN and attention layer on the 3-node path with inputs whose products cancel inside X W: the magnitude
+    is built from |X||W|, not from |X W|; hand-worked values of the outputs, their S_abs and the GCN gradients."""
+    hw = load_golden(golden_dir, "sabs_handworked.json")["path3"]
+    src, dst = np.array(hw["src"], np.int32), np.array(hw["dst"], np.int32)
+    x, w, b = np.array(hw["x"], np.float32), np.array(hw["w"], np.float32), np.array(hw["bias"], np.float32)
+    out, sabs = oracle.gcnconv(src, dst, 3, x, w, b, True, with_sabs=True)
+    np.testing.assert_allclose(out, np.array(hw["gcn_out"]), rtol=1e-7)
+    np.testing.assert_allclose(sabs, np.array(hw["gcn_sabs"]), rtol=1e-15)
+    g = np.array(hw["gcn_grad_out"], np.float32)
+    t, tabs = np.array(hw["gcn_T"]), np.array(hw["gcn_Tabs"])
+    bw = oracle.gcnconv_backward(src, dst, 3, x, w, g, True)
+    np.testing.assert_allclose(bw["grad_x"], np.stack([t, t], 1), rtol=1e-6)               # W = [[1],[1]]
+    np.testing.assert_allclose(bw["sabs_x"], np.stack([tabs, tabs], 1), rtol=1e-15)
+    np.testing.assert_allclose(bw["grad_w"][:, 0], [1 * t[0] + 2 * t[1], -1 * t[0] + 3 * t[2]], rtol=1e-6)
+    np.testing.assert_allclose(bw["sabs_w"][:, 0], [1 * tabs[0] + 2 * tabs[1], 1 * tabs[0] + 3 * tabs[2]], rtol=1e-15)
+    np.testing.assert_allclose(bw["grad_b"], hw["gcn_grad_b"], rtol=0)
+    np.testing.assert_allclose(bw["sabs_b"], hw["gcn_sabs_b"], rtol=0)
+    a_s, a_d = np.array(hw["a_src"], np.float32), np.array(hw["a_dst"], np.float32)
+    out, sabs = oracle.gatconv(src, dst, 3, x, w, a_s, a_d, 0.2, with_sabs=True)
+    np.testing.assert_allclose(out, np.array(hw["gat_out"]), rtol=1e-7)
+    np.testing.assert_allclose(sabs, np.array(hw["gat_sabs"]), rtol=1e-14)
+
+
+@pytest.mark.parametrize("aggr", [AGGR_SUM, AGGR_MEAN])
+@pytest.mark.parametrize("e_kind", ["scalar", "vector"])
+def test_grad_e_and_backward_sabs_brute_force(aggr, e_kind):
+    """Every element of grad_e, not only its pairing with e: grad_e[k] = <x[src k], g[dst k]> (one weight per edge)
+    or the element-wise product (one weight per edge and feature), divided by the in-degree of dst k for the mean;
+    and the S_abs outputs of the backward are the same sums over absolute values.  Python loops over the edges of a
+    multigraph with a hub, duplicate edges, self-loops and isolated nodes."""
+    n, f = 40, 4
+    src, dst = rng_graph(97, n, 500, star=True)
+    ne = src.shape[0]
+    x = synth.normal_f32(97, 2, n * f).reshape(n, f)
+    g = synth.normal_f32(97, 7, n * f).reshape(n, f)
+    e = synth.uniform_f32(97, 3, ne, -1, 1) if e_kind == "scalar" else synth.normal_f32(97, 3, ne * f).reshape(ne, f)
+    bw = oracle.propagate_backward(src, dst, n, x, g, e, MSG_E_MUL_XJ, aggr, with_sabs=True)
+    indeg = np.bincount(dst, minlength=n)
+    x64, g64, e64 = x.astype(np.float64), g.astype(np.float64), e.astype(np.float64).reshape(ne, -1)
+    ge = np.zeros_like(e64)
+    se = np.zeros_like(e64)
+    gx, sx = np.zeros((n, f)), np.zeros((n, f))
+    for k in range(ne):
+        gi = g64[dst[k]] / (indeg[dst[k]] if aggr == AGGR_MEAN else 1.0)
+        prod = x64[src[k]] * gi
+        if e_kind == "scalar":
+            ge[k, 0], se[k, 0] = prod.sum(), np.abs(prod).sum()
+        else:
+            ge[k], se[k] = prod, np.abs(prod)
+        gx[src[k]] += e64[k] * gi
+        sx[src[k]] += np.abs(e64[k] * gi)
+    np.testing.assert_allclose(bw["grad_e"], ge, rtol=0, atol=2e-7 * np.abs(ge).max())
+    np.testing.assert_allclose(bw["sabs_e"], se, rtol=1e-12)
+    np.testing.assert_allclose(bw["grad_x"], gx, rtol=0, atol=2e-7 * np.abs(gx).max())
+    np.testing.assert_allclose(bw["sabs_x"], sx, rtol=1e-12)
+
+
+def test_forward_sabs_is_the_operator_on_absolute_values():
+    """S_abs of propagate / GCNConv / the attention layer against dense float64 products of the absolute values
+    (|A| |X|, Ahat |X||W| + |b|, alpha-weighted |X||W| with alpha from a per-row numpy softmax): a magnitude that is
+    too large by any factor, or built from |X W| instead of |X||W|, fails."""
+    n, f_in, f_out = 48, 5, 3
+    src, dst = rng_graph(61, n, 400, star=True)
+    ne = src.shape[0]
+    x = synth.normal_f32(61, 2, n * f_in).reshape(n, f_in)
+    e = synth.uniform_f32(61, 3, ne, -1, 1)
+    indeg = np.bincount(dst, minlength=n)
+    a_abs = dense_adjacency(src, dst, n, np.abs(e))
+    for aggr in (AGGR_SUM, AGGR_MEAN):
+        _, sabs = oracle.propagate(src, dst, n, x, e, MSG_E_MUL_XJ, aggr, with_sabs=True)
+        # the product e * x is rounded to float before it is summed: its magnitude is that float's
+        ref = np.zeros((n, f_in))
+        for k in range(ne):
+            ref[dst[k]] += np.abs((e[k] * x[src[k]]).astype(np.float32)).astype(np.float64)
+        if aggr == AGGR_MEAN:
+            ref = ref / np.maximum(indeg, 1)[:, None]
+        np.testing.assert_allclose(sabs, ref, rtol=1e-12)
+        np.testing.assert_allclose(sabs, (a_abs @ np.abs(x).astype(np.float64)) /
+                                   (np.maximum(indeg, 1)[:, None] if aggr == AGGR_MEAN else 1.0), rtol=1e-6)
+    w = synth.glorot_uniform(61, 4, f_in, f_out, (f_in, f_out))
+    b = synth.uniform_f32(61, 5, f_out, -1, 1)
+    zabs = np.abs(x).astype(np.float64) @ np.abs(w).astype(np.float64)
+    for loops in (True, False):
+        a = dense_adjacency(src, dst, n) + (np.eye(n) if loops else 0.0)
+        d = a.sum(1)
+        dinv = np.where(d > 0, 1.0 / np.sqrt(np.maximum(d, 1e-300)), 0.0)
+        _, sabs = oracle.gcnconv(src, dst, n, x, w, b, loops, with_sabs=True)
+        np.testing.assert_allclose(sabs, (dinv[:, None] * a * dinv[None, :]) @ zabs + np.abs(b), rtol=1e-12)
+    heads, ch = 3, 1
+    a_s = synth.uniform_f32(61, 6, heads * ch, -1, 1).reshape(heads, ch)
+    a_d = synth.uniform_f32(61, 7, heads * ch, -1, 1).reshape(heads, ch)
+    _, sabs = oracle.gatconv(src, dst, n, x, w, a_s, a_d, 0.2, with_sabs=True)
+    h = (x.astype(np.float64) @ w.astype(np.float64)).astype(np.float32).astype(np.float64).reshape(n, heads, ch)
+    sl, sr = (h * a_s[None]).sum(-1), (h * a_d[None]).sum(-1)
+    ref = np.zeros((n, heads, ch))
+    inc = incoming(dst, n)
+    for i in range(n):
+        if inc[i].size:
+            j = src[inc[i]]
+            sc = sl[j] + sr[i][None]
+            sc = np.where(sc > 0, sc, 0.2 * sc)
+            ex = np.exp(sc - sc.max(0))
+            ref[i] = ((ex / ex.sum(0))[:, :, None] * zabs.reshape(n, heads, ch)[j]).sum(0)
+    np.testing.assert_allclose(sabs.reshape(n, heads, ch), ref, rtol=1e-7)
+
+
+def test_gcn_backward_sabs_is_the_operator_on_absolute_values():
+    n, f_in, f_out = 40, 5, 3
+    src, dst = rng_graph(95, n, 300, star=True)
+    x = synth.normal_f32(95, 2, n * f_in).reshape(n, f_in)
+    w = synth.glorot_uniform(95, 4, f_in, f_out, (f_in, f_out))
+    g = synth.normal_f32(95, 7, n * f_out).reshape(n, f_out)
+    for loops in (True, False):
+        bw = oracle.gcnconv_backward(src, dst, n, x, w, g, loops)
+        a = dense_adjacency(src, dst, n) + (np.eye(n) if loops else 0.0)
+        d = a.sum(1)
+        dinv = np.where(d > 0, 1.0 / np.sqrt(np.maximum(d, 1e-300)), 0.0)
+        tabs = (dinv[:, None] * a * dinv[None, :]).T @ np.abs(g).astype(np.float64)
+        np.testing.assert_allclose(bw["sabs_x"], tabs @ np.abs(w).astype(np.float64).T, rtol=1e-12)
+        np.testing.assert_allclose(bw["sabs_w"], np.abs(x).astype(np.float64).T @ tabs, rtol=1e-12)
+        np.testing.assert_allclose(bw["sabs_b"], np.abs(g).astype(np.float64).sum(0), rtol=1e-12)
