@@ -37,7 +37,7 @@ def build(force: bool = True) -> str:
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         tmp = _LIB + ".tmp.%d" % os.getpid()
         subprocess.check_call(["gcc", "-O2", "-std=c11", "-ffp-contract=off", "-fno-fast-math",
-                               "-Wall", "-Wextra", "-shared", "-fPIC", "-o", tmp, _SRC, "-lm"])
+                               "-Wall", "-Wextra", "-fopenmp", "-shared", "-fPIC", "-o", tmp, _SRC, "-lm"])
         os.replace(tmp, _LIB)
     return _LIB
 
@@ -140,6 +140,23 @@ def propagate(src, dst, num_nodes: int, x, e=None, msg: int = MSG_COPY_XJ, aggr:
                                   ctypes.c_int32(msg), ctypes.c_int32(aggr), _p(out), _p(sabs))
     _check(rc, "propagate")
     return (out, sabs) if with_sabs else out
+
+
+def propagate_all_cores(src, dst, num_nodes: int, x, e=None, msg: int = MSG_COPY_XJ, aggr: int = AGGR_SUM):
+    """propagate with the rows dealt to OpenMP threads (the all-cores CPU baseline) -> (out, threads used);
+    bit-identical to propagate()."""
+    src, dst, x = _i32(src, "src"), _i32(dst, "dst"), _f32(x, "x")
+    ne, f = src.shape[0], x.shape[1]
+    e, e_dim = _edge_data(e, ne, f)
+    if msg == MSG_E_MUL_XJ and e is None:
+        raise ValueError("e_mul_xj needs edge data")
+    out = np.empty((num_nodes, f), np.float32)
+    threads = ctypes.c_int32(0)
+    rc = _load().oracle_propagate_all_cores(_p(src), _p(dst), ctypes.c_int64(ne), ctypes.c_int32(num_nodes),
+                                            _p(x), ctypes.c_int32(f), _p(e), ctypes.c_int32(e_dim),
+                                            ctypes.c_int32(msg), ctypes.c_int32(aggr), _p(out), ctypes.byref(threads))
+    _check(rc, "propagate_all_cores")
+    return out, int(threads.value)
 
 
 def propagate_backward(src, dst, num_nodes: int, x, grad_out, e=None, msg: int = MSG_COPY_XJ,

@@ -31,6 +31,7 @@
  * condition number the tests scale their floating-point tolerance with.
  */
 #include <math.h>
+#include <omp.h>
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
@@ -277,6 +278,61 @@ int oracle_propagate(const int32_t *src, const int32_t *dst, int64_t E, int32_t 
     if (rc == 0)
         for (size_t q = 0; q < nf; ++q) out[q] = (float)o64[q];
     free(o64);
+    return rc;
+}
+
+/*
+ * propagate once more, for the timing of a CPU baseline on all host cores: the rows of the by-destination
+ * sparse form (oracle_build_csr) are dealt to OpenMP threads, each row reducing its own messages in
+ * increasing edge index -- per element the very additions oracle_propagate makes in the very same order, so
+ * the result is the same bit for bit (a test checks this).  *threads_used receives the team size.
+ */
+int oracle_propagate_all_cores(const int32_t *src, const int32_t *dst, int64_t E, int32_t N,
+                               const float *x, int32_t F, const float *e, int32_t e_dim,
+                               int32_t msg, int32_t aggr, float *out, int32_t *threads_used)
+{
+    if (N <= 0 || E < 0 || F <= 0) return 2;
+    if (msg < MSG_COPY_XJ || msg > MSG_XJ_SUB_XI) return 2;
+    if (aggr < AGGR_SUM || aggr > AGGR_PROD) return 2;
+    if (msg == MSG_E_MUL_XJ && e_dim != 1 && e_dim != F) return 2;
+    int32_t *rowptr = (int32_t *)malloc(((size_t)N + 1) * sizeof(int32_t));
+    int32_t *colidx = (int32_t *)malloc((size_t)(E > 0 ? E : 1) * sizeof(int32_t));
+    int32_t *perm = (int32_t *)malloc((size_t)(E > 0 ? E : 1) * sizeof(int32_t));
+    int32_t *indeg = (int32_t *)malloc((size_t)N * sizeof(int32_t));
+    int rc = 3, failed = 0, team = 1;
+    if (!rowptr || !colidx || !perm || !indeg) goto done;
+    rc = oracle_build_csr(src, dst, E, N, rowptr, colidx, perm, indeg);
+    if (rc) goto done;
+#pragma omp parallel
+    {
+        double *acc = (double *)malloc((size_t)F * sizeof(double));
+        double *sa = (double *)malloc((size_t)F * sizeof(double));
+        if (!acc || !sa) {
+#pragma omp atomic write
+            failed = 1;
+        }
+#pragma omp single
+        team = omp_get_num_threads();
+#pragma omp for schedule(dynamic, 64)
+        for (int32_t i = 0; i < N; ++i) {
+            if (!acc || !sa) continue;
+            for (int32_t f = 0; f < F; ++f) { acc[f] = 0.0; sa[f] = 0.0; }
+            int64_t cnt = 0;
+            for (int32_t p = rowptr[i]; p < rowptr[i + 1]; ++p, ++cnt)
+                for (int32_t f = 0; f < F; ++f)
+                    reduce_step(aggr, acc, sa, f, cnt, message_value(msg, x, F, i, colidx[p], e, e_dim, perm[p], f));
+            for (int32_t f = 0; f < F; ++f) {
+                double v = cnt > 0 ? acc[f] : 0.0;
+                if (aggr == AGGR_MEAN && cnt > 0) v /= (double)cnt;
+                out[(int64_t)i * F + f] = (float)v;
+            }
+        }
+        free(acc); free(sa);
+    }
+    if (failed) rc = 3;
+    if (threads_used) *threads_used = team;
+done:
+    free(rowptr); free(colidx); free(perm); free(indeg);
     return rc;
 }
 

@@ -1019,3 +1019,23 @@ def test_gcn_backward_sabs_is_the_operator_on_absolute_values():
         np.testing.assert_allclose(bw["sabs_x"], tabs @ np.abs(w).astype(np.float64).T, rtol=1e-12)
         np.testing.assert_allclose(bw["sabs_w"], np.abs(x).astype(np.float64).T @ tabs, rtol=1e-12)
         np.testing.assert_allclose(bw["sabs_b"], np.abs(g).astype(np.float64).sum(0), rtol=1e-12)
+
+
+@pytest.mark.parametrize("msg,aggr", [(MSG_COPY_XJ, AGGR_SUM), (MSG_E_MUL_XJ, AGGR_MEAN), (MSG_E_MUL_XJ, AGGR_MAX),
+                                      (MSG_XJ_SUB_XI, AGGR_MIN), (MSG_COPY_XJ, AGGR_PROD)])
+def test_all_cores_variant_is_the_same_function(msg, aggr):
+    """The row-parallel variant timed as the all-cores CPU baseline: dense float64 A X for the sum, and the very
+    bits of the single-threaded edge loop for every message and reduction."""
+    wl = synth.config2_weighted(num_nodes=3000, num_edges=40000, feat=8, cap=400.0)
+    n, src, dst = wl.num_nodes, wl.src, wl.dst
+    e = wl.edge_weight if msg == MSG_E_MUL_XJ else None
+    got, threads = oracle.propagate_all_cores(src, dst, n, wl.x, e, msg, aggr)
+    assert threads >= 1
+    np.testing.assert_array_equal(got.view(np.uint32), oracle.propagate(src, dst, n, wl.x, e, msg, aggr).view(np.uint32))
+    if msg == MSG_COPY_XJ and aggr == AGGR_SUM:
+        sub = slice(0, 64)   # dense check on the rows of the first 64 nodes
+        a = np.zeros((64, n))
+        m = dst < 64
+        np.add.at(a, (dst[m], src[m]), 1.0)
+        ref = a @ wl.x.astype(np.float64)
+        np.testing.assert_allclose(got[sub], ref, rtol=0, atol=2e-7 * np.abs(ref).max())
