@@ -27,12 +27,18 @@
  * All device work runs on the device that is current when gnn_build_csr is
  * called; the caller keeps that device current for later calls on the graph.
  *
- * Concurrency: a graph handle carries scratch memory for rows that are split over several wavefronts
- * (allocated on first use, reused afterwards), so compute calls on ONE handle must not overlap: issue them
- * on one stream, or order them with events.  Calls on different handles are independent and may come from
- * different host threads; the process-wide buffer that graph builds share is handed to one build at a time
- * (a concurrent build allocates its own temporaries).  Caller-provided workspaces follow the same rule as
- * the handle: one call at a time per workspace.
+ * Which calls allocate or synchronise: the graph builders (gnn_build_csr*, which read back a flag and the list
+ * sizes), gnn_graph_reserve, gnn_graph_destroy, gnn_release_cached_memory and gnn_check_graph_indicator.
+ * Every other call only enqueues kernels on `stream`: it never allocates, frees or synchronises, so it may be
+ * recorded into a HIP graph from its first use on.
+ *
+ * Concurrency: a graph handle carries scratch memory for rows that are split over several wavefronts and for
+ * per-row softmax statistics (a part of the graph's one allocation, sized when the graph is built; see
+ * gnn_graph_reserve), so compute calls on ONE handle must not overlap: issue them on one stream, or order them
+ * with events.  Calls on different handles are independent and may come from different host threads; the
+ * process-wide buffer that graph builds share is handed to one build at a time (a concurrent build allocates
+ * its own temporaries).  Caller-provided workspaces follow the same rule as the handle: one call at a time
+ * per workspace.
  */
 #ifndef GNN_MI355X_H
 #define GNN_MI355X_H
@@ -54,7 +60,8 @@ typedef enum {
     GNN_ERR_UNSUPPORTED = 4, /* combination not implemented */
     GNN_ERR_ALLOC = 5,       /* device allocation failed */
     GNN_ERR_DEVICE = 6,      /* a HIP call or launch failed */
-    GNN_ERR_NOT_SORTED = 7   /* graph_indicator is not non-decreasing */
+    GNN_ERR_NOT_SORTED = 7,  /* graph_indicator is not non-decreasing (gnn_check_graph_indicator) */
+    GNN_ERR_NOT_RESERVED = 8 /* the graph's scratch memory is too small for this call: gnn_graph_reserve first */
 } gnn_status;
 
 /*
@@ -70,6 +77,7 @@ typedef enum { GNN_AGGR_SUM = 0, GNN_AGGR_MEAN = 1, GNN_AGGR_MAX = 2, GNN_AGGR_M
 typedef enum { GNN_EDGE_ORDER_COO = 0, GNN_EDGE_ORDER_CSR = 1 } gnn_edge_order;
 typedef enum { GNN_ACT_NONE = 0, GNN_ACT_RELU = 1 } gnn_activation;
 
+/* Static text for a status code (spec boundary: errors are reported by return code only). */
 const char *gnn_status_string(gnn_status s);
 
 /*
@@ -92,8 +100,9 @@ gnn_status gnn_build_csr(const int32_t *d_src, const int32_t *d_dst, int64_t num
                          int32_t num_nodes, void *stream, gnn_graph **out_graph);
 
 /*
- * Same, with the two scheduling thresholds exposed (0 = library default: 16, and
- * 256 / 512 / 1024 edges per piece growing with the number of edges):
+ * Same, with the two scheduling thresholds exposed.  Both 0: the library defaults (16, and 256 / 512 / 1024
+ * edges per piece growing with the number of edges).  chunk_edges alone 0: its default, with small_max_degree
+ * taken as given (0 then means that every non-empty row is cut into wavefront pieces).
  * rows with in-degree <= small_max_degree are reduced by a sub-group of a
  * wavefront; longer rows are cut into pieces of at most chunk_edges edges, one
  * wavefront each (pieces of one row are combined in a fixed order afterwards).
@@ -103,6 +112,21 @@ gnn_status gnn_build_csr(const int32_t *d_src, const int32_t *d_dst, int64_t num
 gnn_status gnn_build_csr_ex(const int32_t *d_src, const int32_t *d_dst, int64_t num_edges,
                             int32_t num_nodes, int32_t small_max_degree, int32_t chunk_edges,
                             void *stream, gnn_graph **out_graph);
+
+/*
+ * Temporal graphs (paper section 3, "Graph Data Structures": a temporal graph is a sequence of snapshot
+ * graphs over time): num_snapshots edge lists over ONE node set of num_nodes nodes are turned into
+ * num_snapshots handles with one device allocation (shared by the handles and freed with the last of
+ * them) and one stream synchronisation, instead of an allocation and a synchronisation per snapshot.
+ * d_src, d_dst : HOST arrays of num_snapshots DEVICE pointers, snapshot t holding num_edges[t] edges
+ * (num_edges is a HOST array; an entry may be 0, its pointers then may be NULL).
+ * out_graphs   : HOST array of num_snapshots handle slots.  Every handle is an ordinary graph (same CSR,
+ * same work lists, bit for bit, as gnn_build_csr on that snapshot alone) and is destroyed on its own with
+ * gnn_graph_destroy.  Errors as gnn_build_csr; on any error no handle is returned (all slots NULL), and
+ * GNN_ERR_INDEX_RANGE means that at least one snapshot holds a node id outside [0, num_nodes).
+ */
+gnn_status gnn_build_csr_batch(int32_t num_snapshots, const int32_t *const *d_src, const int32_t *const *d_dst,
+                               const int64_t *num_edges, int32_t num_nodes, void *stream, gnn_graph **out_graphs);
 
 /*
  * One relation of a heterogeneous graph (paper section 3, "Graph Data Structures": graphs with several
@@ -127,12 +151,32 @@ gnn_status gnn_build_csr_bipartite(const int32_t *d_src, const int32_t *d_dst, i
 gnn_status gnn_release_cached_memory(void);
 
 /*
+ * Sizes the graph's scratch memory (partial rows of nodes whose edges are split over several wavefronts --
+ * section 3 "Message Passing": the reduction over a neighbourhood, here cut into pieces for hub nodes -- and the
+ * per-node softmax statistics).  After it returns GNN_OK, on this graph
+ *   gnn_propagate / gnn_aggregate_neighbors / gnn_gin_update / gnn_gcnconv / their backward calls accept
+ *     feat_dim (f_in, f_out) up to 3 * max_feat_dim,
+ *   gnn_gatconv / gnn_gatconv_backward accept heads * ch up to max_feat_dim,
+ *   gnn_segment_softmax / gnn_segment_softmax_backward accept up to max_heads heads.
+ * A freshly built graph is reserved for max_feat_dim = 128 and max_heads = 0: the segment softmax needs one
+ * gnn_graph_reserve call, everything else only for wider features than that.  A compute call beyond the
+ * reserved sizes returns GNN_ERR_NOT_RESERVED and launches nothing.  The reservation only grows.
+ * This call may allocate and then synchronises the DEVICE (kernels enqueued earlier may use the buffer it
+ * replaces): call it when the graph is set up, not between enqueued work and not during stream capture.
+ * Errors: GNN_ERR_NULL, GNN_ERR_BAD_SIZE (a negative size), GNN_ERR_ALLOC, GNN_ERR_DEVICE.
+ */
+gnn_status gnn_graph_reserve(gnn_graph *g, int32_t max_feat_dim, int32_t max_heads);
+
+/*
  * Destroys the graph.  The caller makes sure no enqueued work still uses it: its device arrays are freed or
  * handed to a later gnn_build_csr call (see gnn_release_cached_memory).
  */
 gnn_status gnn_graph_destroy(gnn_graph *g);
 
-/* Borrowed device pointers / sizes, valid until gnn_graph_destroy.  NULL / 0 for a NULL graph. */
+/*
+ * The sparse (by-destination) encoding of the topology that section 3, "Graph Data Structures", names next to
+ * COO, as borrowed device pointers / sizes, valid until gnn_graph_destroy.  NULL / 0 for a NULL graph.
+ */
 const int32_t *gnn_graph_rowptr(const gnn_graph *g);   /* [N+1] */
 const int32_t *gnn_graph_colidx(const gnn_graph *g);   /* [E]   */
 const int32_t *gnn_graph_perm(const gnn_graph *g);     /* [E]   */
@@ -140,7 +184,10 @@ const int32_t *gnn_graph_indegree(const gnn_graph *g); /* [N]   */
 int32_t gnn_graph_num_nodes(const gnn_graph *g);       /* rows = destination nodes */
 int32_t gnn_graph_num_src_nodes(const gnn_graph *g);   /* differs only for gnn_build_csr_bipartite */
 int64_t gnn_graph_num_edges(const gnn_graph *g);
-/* Host-side sizes of the work lists: rows reduced by a sub-group, wavefront work items, split rows. */
+/*
+ * Host-side sizes of the work lists that schedule the reduction over each neighbourhood (section 3, "Message
+ * Passing") by in-degree: rows reduced by a sub-group, wavefront work items, split rows.
+ */
 void gnn_graph_work_sizes(const gnn_graph *g, int32_t *n_small_rows, int32_t *n_items, int32_t *n_split_rows);
 /*
  * Borrowed device pointers to the work lists themselves (introspection and tests; any argument may be NULL):
@@ -155,7 +202,8 @@ void gnn_graph_work_lists(const gnn_graph *g, const int32_t **small_rows, const 
                           const int32_t **split_slot0);
 
 /*
- * Per-edge data from the caller's COO order into CSR order:
+ * Per-edge data (the edge features e of section 3, "Message Passing", stored per edge of the COO list) from
+ * the caller's COO order into CSR order:
  *   d_e_csr[p, :] = d_e[perm[p], :],  both [E x e_dim] float.
  * Done once per graph and edge tensor so that compute calls stream edge data.
  */
@@ -173,8 +221,9 @@ gnn_status gnn_edge_data_to_csr(const gnn_graph *g, const float *d_e, int32_t e_
  * (COO = the order the edges were given in, CSR = after gnn_edge_data_to_csr), NULL for COPY_XJ.
  * Any feat_dim > 0 is accepted; 16-byte aligned pointers with feat_dim % 4 == 0 take the
  * 128-bit path.  Calls on one graph must not overlap in time (they share the graph's
- * scratch buffer for rows that are split across wavefronts).
- * Errors: GNN_ERR_NULL, GNN_ERR_BAD_SIZE, GNN_ERR_ALLOC, GNN_ERR_DEVICE.
+ * scratch buffer for rows that are split across wavefronts).  Only enqueues kernels.
+ * Errors: GNN_ERR_NULL, GNN_ERR_BAD_SIZE, GNN_ERR_NOT_RESERVED (feat_dim beyond what the graph is
+ * reserved for, see gnn_graph_reserve), GNN_ERR_DEVICE.
  */
 gnn_status gnn_propagate(const gnn_graph *g, const float *d_x, int32_t feat_dim,
                          const float *d_e, int32_t e_dim, gnn_edge_order e_order,
@@ -188,7 +237,7 @@ gnn_status gnn_propagate(const gnn_graph *g, const float *d_x, int32_t feat_dim,
  * destination type's nodes (all with the same gnn_graph_num_nodes), d_x[r] the DEVICE features of relation
  * r's source type [gnn_graph_num_src_nodes(graphs[r]) x feat_dim], d_e[r] its DEVICE edge data [E_r x e_dim]
  * (d_e may be NULL for COPY_XJ).  msg = COPY_XJ or E_MUL_XJ; aggr applies inside a relation.
- * Temporal snapshot graphs need nothing extra: one handle per snapshot and one call each.
+ * Temporal snapshot graphs: gnn_build_csr_batch gives one handle per snapshot, then one gnn_propagate each.
  */
 gnn_status gnn_hetero_propagate(int32_t num_relations, const gnn_graph *const *graphs,
                                 const float *const *d_x, const float *const *d_e, int32_t feat_dim,
@@ -237,7 +286,8 @@ gnn_status gnn_aggregate_neighbors(const gnn_graph *g, const float *d_m, int32_t
                                    gnn_edge_order m_order, gnn_aggr aggr, float *d_out, void *stream);
 
 /*
- * Winners of a max aggregation: d_argmax[i,f] = the edge (id in the caller's numbering) whose message
+ * Winners of a max aggregation (what the gradient of propagate with the max reduction routes along; the
+ * paper's training example, section 3 "Training Example", differentiates through its layers): d_argmax[i,f] = the edge (id in the caller's numbering) whose message
  * is out[i,f], the FIRST such edge in increasing edge id on ties, -1 where node i has no incoming
  * edge.  d_out_max must be the result of gnn_propagate(..., GNN_AGGR_MAX, ...) on the same inputs.
  * d_argmax is [N x feat_dim] int32.
@@ -274,7 +324,7 @@ gnn_status gnn_propagate_backward(const gnn_graph *g, const gnn_graph *g_by_sour
  * with d_i = in-degree of i (+1 when add_self_loops != 0; one loop per node is
  * added without looking for loops already present); an edge j -> i carries
  * 1/sqrt(d_i d_j); a node with d = 0 contributes the coefficient 0.  act = GNN_ACT_RELU applies
- * max(., 0) to the result (the example's GCNConv(64 => 64, relu)), GNN_ACT_NONE leaves it.
+ * max(., 0) to the result (the second graph convolution of the example model in section 3, "Training Example", has one), GNN_ACT_NONE leaves it.
  * d_x [N x f_in], d_w [f_in x f_out] row-major, d_bias [f_out] or NULL, d_out [N x f_out].
  * d_workspace: device scratch of at least gnn_gcnconv_workspace_bytes(N, f_out) bytes.
  * The two products are taken in the order that gathers the narrower rows: (Ahat X) W when f_in < f_out,
@@ -301,9 +351,12 @@ gnn_status gnn_gcnconv_backward(const gnn_graph *g, const gnn_graph *g_by_source
                                 void *d_workspace, size_t workspace_bytes, void *stream);
 
 /*
- * Segment softmax over each destination's incoming edges, independently per head:
+ * Segment softmax over each destination's incoming edges, independently per head -- the normalisation of
+ * per-edge attention scores in the attention layers section 3, "Graph Convolutional Layers", names (GAT): a
+ * reduction over each neighbourhood followed by a per-edge rescale:
  *   out[k,h] = exp(s[k,h] - m[i,h]) / sum_{q: dst[q] = i} exp(s[q,h] - m[i,h]),  i = dst[k],
  * m = the segment maximum.  d_scores and d_out are [E x heads], both in the order `order` names.
+ * Needs gnn_graph_reserve(g, ., heads) once beforehand (else GNN_ERR_NOT_RESERVED); only enqueues kernels.
  */
 gnn_status gnn_segment_softmax(const gnn_graph *g, const float *d_scores, int32_t heads,
                                gnn_edge_order order, float *d_out, void *stream);
@@ -364,11 +417,20 @@ gnn_status gnn_gatconv_backward(const gnn_graph *g, const gnn_graph *g_by_source
  *   out[g,:] = AGGR over nodes i with graph_indicator[i] = g of x[i,:]
  * d_graph_indicator [num_nodes] must be non-decreasing with values in [0, num_graphs)
  * (what batching produces); a graph without nodes gets a zero row.  Sortedness and range
- * are the caller's contract; they are not checked on the device.
+ * are the caller's contract; this call does not check them (gnn_check_graph_indicator does).
  */
 gnn_status gnn_graph_pool(const int32_t *d_graph_indicator, int32_t num_nodes, int32_t num_graphs,
                           const float *d_x, int32_t feat_dim, gnn_aggr aggr, float *d_out,
                           void *stream);
+
+/*
+ * Debug check of a graph_indicator (section 3, "Graph Data Structures": batching collates small graphs into
+ * one graph whose nodes carry the index of their graph): GNN_OK if d_graph_indicator [num_nodes] is
+ * non-decreasing with every value in [0, num_graphs), GNN_ERR_INDEX_RANGE for a value outside that range,
+ * else GNN_ERR_NOT_SORTED.  Reads a flag back: it synchronises the stream (and allocates the flag).
+ */
+gnn_status gnn_check_graph_indicator(const int32_t *d_graph_indicator, int32_t num_nodes, int32_t num_graphs,
+                                     void *stream);
 
 /*
  * GIN-style node update without the MLP (layer named in the paper, section 3):
@@ -378,8 +440,8 @@ gnn_status gnn_gin_update(const gnn_graph *g, const float *d_x, int32_t feat_dim
                           float *d_out, void *stream);
 
 /*
- * The remaining layers of the paper's example model (section 3, "Training Example":
- * GNNChain(GCNConv(16 => 64), BatchNorm(64), relu, GCNConv(64 => 64, relu), GlobalPool(mean), Dense(64, 1))).
+ * The remaining layers of the paper's example model (section 3, "Training Example": a chain of two graph
+ * convolutions with a batch normalisation and a relu in between, a mean readout per graph and a dense head).
  *
  * gnn_batchnorm: normalisation across the row (node) dimension,
  *   out[i,f] = act(gamma[f] * (x[i,f] - mean[f]) / sqrt(var[f] + eps) + beta[f]),
@@ -418,7 +480,8 @@ gnn_status gnn_example_model_forward(const gnn_graph *g, const int32_t *d_graph_
  *   (either output may be NULL).  d_loss is a DEVICE scalar.
  * gnn_relu_backward: d_grad_x = d_y > 0 ? d_grad_y : 0, d_y being the relu's OUTPUT; d_grad_x may alias d_grad_y.
  * gnn_graph_pool_backward: every node of graph g receives d_grad_out[g,:] (SUM) or that divided by the
- *   graph's node count (MEAN); d_graph_indicator as for gnn_graph_pool; nodes of no graph are left untouched.
+ *   graph's node count (MEAN); d_graph_indicator as for gnn_graph_pool (every node lies in a graph, so every
+ *   row of d_grad_x is written).
  * gnn_dense_backward: for out = X W + b:  d_grad_x = gy W^T, d_grad_w = X^T gy, d_grad_b = column sums of gy
  *   (each may be NULL; an activation is differentiated by masking gy first).
  * gnn_batchnorm_backward: for y = gamma * xhat + beta with batch statistics (d_mean / d_var as written by
@@ -467,7 +530,8 @@ gnn_status gnn_example_model_train_step(const gnn_graph *g, const gnn_graph *g_b
 
 /*
  * Dense projection Z = X W on the matrix cores (fp32 MFMA, fp32 accumulate), the
- * contraction inside GCNConv and the GAT layer.  d_x [rows x k], d_w [k x n] row-major,
+ * contraction inside GCNConv and the GAT layer (the layers of section 3, "Graph Convolutional Layers" and
+ * "Training Example", apply a learned weight matrix to the node features).  d_x [rows x k], d_w [k x n] row-major,
  * d_z [rows x n].  d_row_scale [rows] or NULL: Z[r,:] is multiplied by d_row_scale[r].
  */
 gnn_status gnn_dense_xw(const float *d_x, int64_t rows, int32_t k, const float *d_w, int32_t n,

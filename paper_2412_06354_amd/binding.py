@@ -28,6 +28,9 @@ SIGNATURES = {
     "gnn_status_string": (_c.c_char_p, [_c.c_int]),
     "gnn_build_csr": (_c.c_int, [_vp, _vp, _i64, _i32, _vp, _c.POINTER(_vp)]),
     "gnn_build_csr_ex": (_c.c_int, [_vp, _vp, _i64, _i32, _i32, _i32, _vp, _c.POINTER(_vp)]),
+    "gnn_build_csr_batch": (_c.c_int, [_i32, _vp, _vp, _vp, _i32, _vp, _vp]),
+    "gnn_graph_reserve": (_c.c_int, [_vp, _i32, _i32]),
+    "gnn_check_graph_indicator": (_c.c_int, [_vp, _i32, _i32, _vp]),
     "gnn_graph_destroy": (_c.c_int, [_vp]),
     "gnn_graph_rowptr": (_vp, [_vp]),
     "gnn_graph_colidx": (_vp, [_vp]),
@@ -148,6 +151,12 @@ class Graph:
         self.num_nodes = int(lib().gnn_graph_num_nodes(handle))
         self.num_src_nodes = int(lib().gnn_graph_num_src_nodes(handle))
         self.num_edges = int(lib().gnn_graph_num_edges(handle))
+        self._reserved_heads = 0
+
+    def reserve(self, max_feat_dim: int = 0, max_heads: int = 0) -> None:
+        """gnn_graph_reserve: sizes the handle's scratch memory (may allocate and synchronise the device)."""
+        _check(lib().gnn_graph_reserve(self._h, int(max_feat_dim), int(max_heads)), "gnn_graph_reserve")
+        self._reserved_heads = max(self._reserved_heads, int(max_heads))
 
     def _view(self, ptr: int, count: int) -> torch.Tensor:
         """Copy of a library-owned int32 device array as a tensor."""
@@ -220,10 +229,39 @@ def build_csr(src: torch.Tensor, dst: torch.Tensor, num_nodes: int, small_max_de
     if int(dst.shape[0]) != e:
         raise ValueError("src and dst must have the same length")
     out = _vp()
-    rc = lib().gnn_build_csr_ex(_dev(src, torch.int32, "src"), _dev(dst, torch.int32, "dst"), e, num_nodes,
-                                small_max_degree, chunk_edges, _stream(), ctypes.byref(out))
+    if small_max_degree == 0 and chunk_edges == 0:
+        rc = lib().gnn_build_csr(_dev(src, torch.int32, "src"), _dev(dst, torch.int32, "dst"), e, num_nodes,
+                                 _stream(), ctypes.byref(out))
+    else:
+        rc = lib().gnn_build_csr_ex(_dev(src, torch.int32, "src"), _dev(dst, torch.int32, "dst"), e, num_nodes,
+                                    small_max_degree, chunk_edges, _stream(), ctypes.byref(out))
     _check(rc, "gnn_build_csr")
     return Graph(out.value, src.device)
+
+
+def build_csr_batch(srcs, dsts, num_nodes: int):
+    """Temporal snapshots over one node set -> one Graph per snapshot (one allocation, one synchronisation)."""
+    t = len(srcs)
+    if t == 0 or len(dsts) != t:
+        raise ValueError("one src and one dst array per snapshot")
+    for a, b in zip(srcs, dsts):
+        if int(a.shape[0]) != int(b.shape[0]):
+            raise ValueError("src and dst must have the same length")
+    arr = _vp * t
+    sp = arr(*[_dev(a, torch.int32, "src") if a.numel() else None for a in srcs])
+    dp = arr(*[_dev(a, torch.int32, "dst") if a.numel() else None for a in dsts])
+    ne = (_i64 * t)(*[int(a.shape[0]) for a in srcs])
+    out = arr()
+    rc = lib().gnn_build_csr_batch(t, sp, dp, ne, num_nodes, _stream(), out)
+    _check(rc, "gnn_build_csr_batch")
+    return [Graph(out[i], srcs[0].device) for i in range(t)]
+
+
+def check_graph_indicator(graph_indicator: torch.Tensor, num_graphs: int) -> None:
+    """Raises GnnError (index range / not sorted) unless the indicator is what gnn_graph_pool expects."""
+    rc = lib().gnn_check_graph_indicator(_dev(graph_indicator, torch.int32, "graph_indicator"),
+                                         int(graph_indicator.shape[0]), num_graphs, _stream())
+    _check(rc, "gnn_check_graph_indicator")
 
 
 def release_cached_memory() -> None:
@@ -467,6 +505,8 @@ def segment_softmax(g: Graph, scores: torch.Tensor, order: int = EDGE_ORDER_COO,
     s2 = _edge_rows(scores, g.num_edges)
     if out is None:
         out = torch.empty_like(scores)
+    if g.num_edges and g._reserved_heads < int(s2.shape[1]):
+        g.reserve(0, int(s2.shape[1]))
     rc = lib().gnn_segment_softmax(g._h, _dev(s2, torch.float32, "scores"), int(s2.shape[1]) if g.num_edges else 1,
                                    order, _dev(out, torch.float32, "out"), _stream())
     _check(rc, "gnn_segment_softmax")
@@ -480,6 +520,8 @@ def segment_softmax_backward(g: Graph, alpha: torch.Tensor, grad_alpha: torch.Te
     a2, g2 = _edge_rows(alpha, g.num_edges), _edge_rows(grad_alpha, g.num_edges)
     if out is None:
         out = torch.empty_like(alpha)
+    if g.num_edges and g._reserved_heads < int(a2.shape[1]):
+        g.reserve(0, int(a2.shape[1]))
     rc = lib().gnn_segment_softmax_backward(g._h, _dev(a2, torch.float32, "alpha"),
                                             _dev(g2, torch.float32, "grad_alpha"),
                                             int(a2.shape[1]) if g.num_edges else 1, order,
@@ -625,7 +667,7 @@ def relu_backward(y: torch.Tensor, grad_y: torch.Tensor) -> torch.Tensor:
 def graph_pool_backward(graph_indicator: torch.Tensor, num_graphs: int, grad_out: torch.Tensor,
                         aggr: int = AGGR_MEAN) -> torch.Tensor:
     n, f = int(graph_indicator.shape[0]), int(grad_out.shape[1])
-    gx = torch.zeros((n, f), dtype=torch.float32, device=grad_out.device)
+    gx = torch.empty((n, f), dtype=torch.float32, device=grad_out.device)
     rc = lib().gnn_graph_pool_backward(_dev(graph_indicator, torch.int32, "graph_indicator"), n, num_graphs,
                                        _dev(grad_out, torch.float32, "grad_out"), f, aggr, gx.data_ptr(), _stream())
     _check(rc, "gnn_graph_pool_backward")

@@ -518,7 +518,14 @@ slab_cache g_slab_cache;
 void free_graph_arrays(gnn_graph *g)
 {
     void *drop = g->slab;
-    if (g->slab) {
+    if (g->shared) {   // one allocation for a batch of graphs: freed with the last of them
+        drop = nullptr;
+        if (g->shared->refs.fetch_sub(1) == 1) {
+            drop = g->shared->ptr;
+            delete g->shared;
+        }
+        g->shared = nullptr;
+    } else if (g->slab) {
         std::lock_guard<std::mutex> lock(g_slab_cache.mu);
         slab_cache &c = g_slab_cache;
         if (!c.ptr || c.bytes < g->slab_bytes) {
@@ -529,10 +536,12 @@ void free_graph_arrays(gnn_graph *g)
         }
     }
     if (drop) (void)hipFree(drop);
-    if (g->scratch) (void)hipFree(g->scratch);
+    if (g->own_scratch) (void)hipFree(g->own_scratch);
     g->slab = nullptr;
     g->slab_bytes = 0;
     g->scratch = nullptr;
+    g->scratch_floats = 0;
+    g->own_scratch = nullptr;
 }
 
 // Carves 256-byte aligned int32 arrays out of one device allocation.
@@ -643,55 +652,94 @@ gnn_status temp_acquire(temp_lease *lease, size_t bytes)
 
 int32_t *at(void *slab, size_t off) { return reinterpret_cast<int32_t *>(static_cast<char *>(slab) + off); }
 
-gnn_status build_impl(const int32_t *d_src, const int32_t *d_dst, int64_t E, int32_t N, hipStream_t stream,
-                      gnn_graph *g)
+// Where the arrays a graph keeps lie inside its allocation.
+struct graph_layout {
+    size_t o_rowptr, o_indeg, o_colidx, o_perm, o_rowidx, o_dstcoo, o_small, o_irow, o_istart, o_islot, o_srows, o_sslot,
+        o_dinv1, o_dinv0, o_scratch;
+    size_t scratch_floats;
+    size_t bytes;
+};
+
+graph_layout plan_graph(int64_t E, int32_t N, int32_t chunk)
 {
     const size_t np1 = (size_t)N + 1;
-    const int64_t num_tiles = gnn_div_up(E, kSortTile);
     // Upper bounds of the work-list sizes, so that everything the graph keeps is one allocation made
     // before any kernel runs: a row is short or gives ceil(deg / chunk) pieces.
-    const size_t max_items = (size_t)std::min<int64_t>(N, E) + (size_t)(E / g->chunk) + 1;
-    const size_t max_split = (size_t)(E / g->chunk) + 1;
-
+    const size_t max_items = (size_t)std::min<int64_t>(N, E) + (size_t)(E / chunk) + 1;
+    const size_t max_split = (size_t)(E / chunk) + 1;
+    // A split row has more than `chunk` edges and ceil(deg / chunk) <= 2 deg / chunk pieces: at most 2 E / chunk
+    // slots in all.  The scratch the compute calls share is sized for that bound at the default feature width, as a
+    // part of the slab, so that no compute call ever allocates (wider features: gnn_graph_reserve).
+    const size_t max_slots = 2 * (size_t)(E / chunk) + 1;
+    graph_layout L{};
+    L.scratch_floats = gnn_scratch_floats((int64_t)max_slots, N, kDefaultReservedFeatDim, 0);
     slab_plan pa;
-    const size_t o_rowptr = pa.add(np1), o_indeg = pa.add(N), o_colidx = pa.add(E), o_perm = pa.add(E),
-                 o_rowidx = pa.add(E), o_dstcoo = pa.add(E), o_small = pa.add(N), o_irow = pa.add(max_items),
-                 o_istart = pa.add(max_items), o_islot = pa.add(max_items), o_srows = pa.add(max_split),
-                 o_sslot = pa.add(max_split), o_dinv1 = pa.add(N), o_dinv0 = pa.add(N);
-    GNN_TRY(graph_slab_acquire(g, pa.bytes));
-    g->rowptr = at(g->slab, o_rowptr);
-    g->indeg = at(g->slab, o_indeg);
-    g->colidx = at(g->slab, o_colidx);
-    g->perm = at(g->slab, o_perm);
-    g->rowidx = at(g->slab, o_rowidx);
-    g->dst_coo = at(g->slab, o_dstcoo);
-    g->dinv_loop = reinterpret_cast<float *>(at(g->slab, o_dinv1));
-    g->dinv_plain = reinterpret_cast<float *>(at(g->slab, o_dinv0));
-    g->small_rows = at(g->slab, o_small);
-    g->item_row = at(g->slab, o_irow);
-    g->item_start = at(g->slab, o_istart);
-    g->item_slot = at(g->slab, o_islot);
-    g->split_rows = at(g->slab, o_srows);
-    g->split_slot0 = at(g->slab, o_sslot);
+    L.o_rowptr = pa.add(np1); L.o_indeg = pa.add(N); L.o_colidx = pa.add(E); L.o_perm = pa.add(E);
+    L.o_rowidx = pa.add(E); L.o_dstcoo = pa.add(E); L.o_small = pa.add(N); L.o_irow = pa.add(max_items);
+    L.o_istart = pa.add(max_items); L.o_islot = pa.add(max_items); L.o_srows = pa.add(max_split);
+    L.o_sslot = pa.add(max_split); L.o_dinv1 = pa.add(N); L.o_dinv0 = pa.add(N);
+    L.o_scratch = pa.add(L.scratch_floats);
+    L.bytes = pa.bytes;
+    return L;
+}
 
-    // ---- temporaries: one buffer, normally the cached one
+void bind_graph(gnn_graph *g, void *base, const graph_layout &L)
+{
+    g->rowptr = at(base, L.o_rowptr);
+    g->indeg = at(base, L.o_indeg);
+    g->colidx = at(base, L.o_colidx);
+    g->perm = at(base, L.o_perm);
+    g->rowidx = at(base, L.o_rowidx);
+    g->dst_coo = at(base, L.o_dstcoo);
+    g->dinv_loop = reinterpret_cast<float *>(at(base, L.o_dinv1));
+    g->dinv_plain = reinterpret_cast<float *>(at(base, L.o_dinv0));
+    g->small_rows = at(base, L.o_small);
+    g->item_row = at(base, L.o_irow);
+    g->item_start = at(base, L.o_istart);
+    g->item_slot = at(base, L.o_islot);
+    g->split_rows = at(base, L.o_srows);
+    g->split_slot0 = at(base, L.o_sslot);
+    g->scratch = reinterpret_cast<float *>(at(base, L.o_scratch));
+    g->scratch_floats = L.scratch_floats;
+}
+
+// Temporaries of one build: sort ping-pong buffers, per-tile digit counts, block sums of the work lists.
+struct temp_layout {
+    size_t o_kb, o_vb, o_eb, o_counts, o_dtot, o_bsum, o_sizes;
+    size_t bytes;
+    int list_blocks;
+    int64_t num_tiles;
+};
+
+temp_layout plan_temp(int64_t E, int32_t N)
+{
+    temp_layout T{};
+    T.num_tiles = gnn_div_up(E, kSortTile);
+    T.list_blocks = (int)gnn_div_up(N, kListRows);
     slab_plan pt;
-    const int list_blocks = (int)gnn_div_up(N, kListRows);
-    const size_t o_flag = pt.add(64), o_kb = pt.add(E), o_vb = pt.add(E),
-                 o_eb = pt.add(E), o_counts = pt.add((size_t)num_tiles * kRadixMax), o_dtot = pt.add(kRadixMax),
-                 o_bsum = pt.add(4 * (size_t)list_blocks), o_sizes = pt.add(4);
-    temp_lease tmp;
-    GNN_TRY(temp_acquire(&tmp, pt.bytes));
-    char *ts = static_cast<char *>(tmp.ptr);
-    int32_t *d_flag = at(ts, o_flag), *kb = at(ts, o_kb), *vb = at(ts, o_vb),
-            *eb = at(ts, o_eb), *counts = at(ts, o_counts), *digit_totals = at(ts, o_dtot),
-            *block_sums = at(ts, o_bsum), *list_sizes = at(ts, o_sizes);
+    T.o_kb = pt.add(E); T.o_vb = pt.add(E); T.o_eb = pt.add(E);
+    T.o_counts = pt.add((size_t)T.num_tiles * kRadixMax); T.o_dtot = pt.add(kRadixMax);
+    T.o_bsum = pt.add(4 * (size_t)T.list_blocks); T.o_sizes = pt.add(4);
+    T.bytes = pt.bytes;
+    return T;
+}
+
+constexpr int kFlagInts = 64;   // per build: [0] the range flag, [8 .. 12] what is read back (flag + four list sizes)
+
+// Enqueues every kernel of one build.  d_flag: kFlagInts zeroed ints; d_flag[8 .. 12] are filled for the host.
+gnn_status enqueue_build(const int32_t *d_src, const int32_t *d_dst, int64_t E, int32_t N, hipStream_t stream,
+                         gnn_graph *g, char *ts, const temp_layout &T, int32_t *d_flag)
+{
+    const size_t np1 = (size_t)N + 1;
+    const int64_t num_tiles = T.num_tiles;
+    const int list_blocks = T.list_blocks;
+    int32_t *kb = at(ts, T.o_kb), *vb = at(ts, T.o_vb), *eb = at(ts, T.o_eb), *counts = at(ts, T.o_counts),
+            *digit_totals = at(ts, T.o_dtot), *block_sums = at(ts, T.o_bsum), *list_sizes = at(ts, T.o_sizes);
 
     // ---- the index range check and the copy of the destinations in edge order ride on the first counting
     //      pass of the sort.  The flag is read back at the end; nothing below indexes with an unchecked node id:
     //      the sort only uses masked digits, the row-pointer kernel clamps its keys and the work-list kernels do
     //      nothing once the flag is set.
-    GNN_HIP(hipMemsetAsync(d_flag, 0, 64 * sizeof(int32_t), stream));
 
     // ---- stable radix sort by destination
     if (E > 0) {
@@ -750,14 +798,53 @@ gnn_status build_impl(const int32_t *d_src, const int32_t *d_dst, int64_t E, int
                        g->chunk, d_flag, block_sums, list_blocks, list_sizes, g->small_rows, g->item_row,
                        g->item_start, g->item_slot, g->split_rows, g->split_slot0, d_flag + 8);
     GNN_LAUNCH_CHECK();
-    int32_t h_info[5] = {0, 0, 0, 0, 0};
-    GNN_HIP(hipMemcpyAsync(h_info, d_flag + 8, sizeof(h_info), hipMemcpyDeviceToHost, stream));
-    GNN_HIP(hipStreamSynchronize(stream));   // everything has run: temporaries may be freed on return
-    if (h_info[0]) return GNN_ERR_INDEX_RANGE;
+    return GNN_OK;
+}
+
+void take_list_sizes(gnn_graph *g, const int32_t *h_info)
+{
     g->n_small = h_info[1];
     g->n_items = h_info[2];
     g->n_slots = h_info[3];
     g->n_split = h_info[4];
+}
+
+gnn_status build_impl(const int32_t *d_src, const int32_t *d_dst, int64_t E, int32_t N, hipStream_t stream,
+                      gnn_graph *g)
+{
+    const graph_layout L = plan_graph(E, N, g->chunk);
+    GNN_TRY(graph_slab_acquire(g, L.bytes));
+    bind_graph(g, g->slab, L);
+
+    // ---- temporaries: one buffer, normally the cached one; the flags sit in front of it
+    const temp_layout T = plan_temp(E, N);
+    const size_t flag_bytes = 256;
+    static_assert(kFlagInts * sizeof(int32_t) == 256, "flag block");
+    temp_lease tmp;
+    GNN_TRY(temp_acquire(&tmp, flag_bytes + T.bytes));
+    char *ts = static_cast<char *>(tmp.ptr);
+    int32_t *d_flag = reinterpret_cast<int32_t *>(ts);
+    GNN_HIP(hipMemsetAsync(d_flag, 0, flag_bytes, stream));
+    GNN_TRY(enqueue_build(d_src, d_dst, E, N, stream, g, ts + flag_bytes, T, d_flag));
+    int32_t h_info[5] = {0, 0, 0, 0, 0};
+    GNN_HIP(hipMemcpyAsync(h_info, d_flag + 8, sizeof(h_info), hipMemcpyDeviceToHost, stream));
+    GNN_HIP(hipStreamSynchronize(stream));   // everything has run: temporaries may be freed on return
+    if (h_info[0]) return GNN_ERR_INDEX_RANGE;
+    take_list_sizes(g, h_info);
+    return GNN_OK;
+}
+
+// Default scheduling thresholds (both given as 0) and their validation.
+gnn_status resolve_thresholds(int64_t num_edges, int32_t *small_max_degree, int32_t *chunk_edges)
+{
+    if (*small_max_degree == 0 && *chunk_edges == 0) *small_max_degree = 16;
+    if (*chunk_edges == 0) {
+        // long pieces amortise the per-piece overhead on big graphs; on small ones a hub row has to be cut
+        // finer or its few wavefronts become the tail of the launch (measured: 256 at E = 1 M, 1024 at E >= 20 M)
+        *chunk_edges = num_edges >= (int64_t)1024 * 16384 ? 1024 : num_edges >= (int64_t)512 * 16384 ? 512 : 256;
+    }
+    if (*small_max_degree < 0 || *small_max_degree > 64) return GNN_ERR_BAD_SIZE;
+    if (*chunk_edges < 64 || *chunk_edges > 65536 || *chunk_edges % 64 != 0) return GNN_ERR_BAD_SIZE;
     return GNN_OK;
 }
 
@@ -773,14 +860,7 @@ static gnn_status build_checked(const int32_t *d_src, const int32_t *d_dst, int6
     *out_graph = nullptr;
     if (num_nodes <= 0 || num_src_nodes <= 0 || num_edges < 0 || num_edges >= (1ll << 31)) return GNN_ERR_BAD_SIZE;
     if (num_edges > 0 && (!d_src || !d_dst)) return GNN_ERR_NULL;
-    if (small_max_degree == 0 && chunk_edges == 0) small_max_degree = 16;
-    if (chunk_edges == 0) {
-        // long pieces amortise the per-piece overhead on big graphs; on small ones a hub row has to be cut
-        // finer or its few wavefronts become the tail of the launch (measured: 256 at E = 1 M, 1024 at E >= 20 M)
-        chunk_edges = num_edges >= (int64_t)1024 * 16384 ? 1024 : num_edges >= (int64_t)512 * 16384 ? 512 : 256;
-    }
-    if (small_max_degree < 0 || small_max_degree > 64) return GNN_ERR_BAD_SIZE;
-    if (chunk_edges < 64 || chunk_edges > 65536 || chunk_edges % 64 != 0) return GNN_ERR_BAD_SIZE;
+    GNN_TRY(resolve_thresholds(num_edges, &small_max_degree, &chunk_edges));
 
     gnn_graph *g = new (std::nothrow) gnn_graph();
     if (!g) return GNN_ERR_ALLOC;
@@ -818,6 +898,89 @@ gnn_status gnn_build_csr(const int32_t *d_src, const int32_t *d_dst, int64_t num
                          void *stream, gnn_graph **out_graph)
 {
     return gnn_build_csr_ex(d_src, d_dst, num_edges, num_nodes, 0, 0, stream, out_graph);
+}
+
+gnn_status gnn_build_csr_batch(int32_t num_snapshots, const int32_t *const *d_src, const int32_t *const *d_dst,
+                               const int64_t *num_edges, int32_t num_nodes, void *stream, gnn_graph **out_graphs)
+{
+    if (!out_graphs) return GNN_ERR_NULL;
+    if (num_snapshots <= 0) return GNN_ERR_BAD_SIZE;
+    for (int32_t t = 0; t < num_snapshots; ++t) out_graphs[t] = nullptr;
+    if (!d_src || !d_dst || !num_edges) return GNN_ERR_NULL;
+    if (num_nodes <= 0) return GNN_ERR_BAD_SIZE;
+    for (int32_t t = 0; t < num_snapshots; ++t) {
+        if (num_edges[t] < 0 || num_edges[t] >= (1ll << 31)) return GNN_ERR_BAD_SIZE;
+        if (num_edges[t] > 0 && (!d_src[t] || !d_dst[t])) return GNN_ERR_NULL;
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int dev = 0;
+    GNN_HIP(hipGetDevice(&dev));
+
+    // one allocation for all graphs, one for the temporaries (the largest snapshot's, reused by every snapshot: the
+    // builds run one after the other on the stream) with a flag block per snapshot in front
+    std::vector<gnn_graph *> graphs((size_t)num_snapshots, nullptr);
+    std::vector<graph_layout> layouts((size_t)num_snapshots);
+    std::vector<temp_layout> temps((size_t)num_snapshots);
+    std::vector<size_t> base((size_t)num_snapshots);
+    size_t slab_bytes = 0, temp_bytes = 0;
+    const size_t flag_block = kFlagInts * sizeof(int32_t), flag_bytes = flag_block * (size_t)num_snapshots;
+    gnn_status st = GNN_OK;
+    void *slab = nullptr, *tmp = nullptr;
+    shared_slab *shared = nullptr;
+    std::vector<int32_t> h_flags((size_t)num_snapshots * kFlagInts, 0);
+    auto fail = [&](gnn_status code) {
+        (void)hipStreamSynchronize(s);
+        for (gnn_graph *g : graphs) delete g;
+        if (slab) (void)hipFree(slab);
+        if (tmp) (void)hipFree(tmp);
+        delete shared;
+        return code;
+    };
+    for (int32_t t = 0; t < num_snapshots; ++t) {
+        gnn_graph *g = new (std::nothrow) gnn_graph();
+        if (!g) return fail(GNN_ERR_ALLOC);
+        graphs[(size_t)t] = g;
+        int32_t small_max = 0, chunk = 0;
+        (void)resolve_thresholds(num_edges[t], &small_max, &chunk);
+        g->num_nodes = num_nodes;
+        g->num_src_nodes = num_nodes;
+        g->num_edges = num_edges[t];
+        g->small_max = small_max;
+        g->chunk = chunk;
+        g->device = dev;
+        layouts[(size_t)t] = plan_graph(num_edges[t], num_nodes, chunk);
+        temps[(size_t)t] = plan_temp(num_edges[t], num_nodes);
+        base[(size_t)t] = slab_bytes;
+        slab_bytes += layouts[(size_t)t].bytes;
+        temp_bytes = std::max(temp_bytes, temps[(size_t)t].bytes);
+    }
+    shared = new (std::nothrow) shared_slab();
+    if (!shared) return fail(GNN_ERR_ALLOC);
+    if ((st = slab_alloc(&slab, slab_bytes)) != GNN_OK) return fail(st);
+    if ((st = slab_alloc(&tmp, flag_bytes + temp_bytes)) != GNN_OK) return fail(st);
+    if (hipMemsetAsync(tmp, 0, flag_bytes, s) != hipSuccess) return fail(GNN_ERR_DEVICE);
+    for (int32_t t = 0; t < num_snapshots; ++t) {
+        gnn_graph *g = graphs[(size_t)t];
+        bind_graph(g, static_cast<char *>(slab) + base[(size_t)t], layouts[(size_t)t]);
+        int32_t *d_flag = reinterpret_cast<int32_t *>(static_cast<char *>(tmp) + flag_block * (size_t)t);
+        st = enqueue_build(d_src[t], d_dst[t], num_edges[t], num_nodes, s, g, static_cast<char *>(tmp) + flag_bytes,
+                           temps[(size_t)t], d_flag);
+        if (st != GNN_OK) return fail(st);
+    }
+    if (hipMemcpyAsync(h_flags.data(), tmp, flag_bytes, hipMemcpyDeviceToHost, s) != hipSuccess) return fail(GNN_ERR_DEVICE);
+    if (hipStreamSynchronize(s) != hipSuccess) return fail(GNN_ERR_DEVICE);
+    for (int32_t t = 0; t < num_snapshots; ++t)
+        if (h_flags[(size_t)t * kFlagInts + 8]) return fail(GNN_ERR_INDEX_RANGE);
+    (void)hipFree(tmp);
+    shared->ptr = slab;
+    shared->refs.store(num_snapshots);
+    for (int32_t t = 0; t < num_snapshots; ++t) {
+        gnn_graph *g = graphs[(size_t)t];
+        g->shared = shared;
+        take_list_sizes(g, &h_flags[(size_t)t * kFlagInts + 8]);
+        out_graphs[t] = g;
+    }
+    return GNN_OK;
 }
 
 int32_t gnn_graph_num_src_nodes(const gnn_graph *g) { return g ? g->num_src_nodes : 0; }
@@ -899,26 +1062,29 @@ const char *gnn_status_string(gnn_status s)
     case GNN_ERR_ALLOC: return "device allocation failed";
     case GNN_ERR_DEVICE: return "HIP call or kernel launch failed";
     case GNN_ERR_NOT_SORTED: return "graph_indicator is not sorted";
+    case GNN_ERR_NOT_RESERVED: return "the graph's scratch memory is too small for this call: gnn_graph_reserve first";
     }
     return "unknown status";
 }
 
 }  // extern "C"
 
-gnn_status gnn_graph_reserve_scratch(const gnn_graph *g, size_t floats)
+extern "C" gnn_status gnn_graph_reserve(gnn_graph *g, int32_t max_feat_dim, int32_t max_heads)
 {
-    if (floats <= g->scratch_floats) return GNN_OK;
-    // Earlier kernels may still be reading the old buffer.
+    if (!g) return GNN_ERR_NULL;
+    if (max_feat_dim < 0 || max_heads < 0) return GNN_ERR_BAD_SIZE;
+    const size_t need = gnn_scratch_floats(g->n_slots, g->num_nodes, max_feat_dim, max_heads);
+    if (need <= g->scratch_floats) return GNN_OK;
+    // Kernels enqueued earlier may still be using the buffer that is replaced.
     GNN_HIP(hipDeviceSynchronize());
-    if (g->scratch) (void)hipFree(g->scratch);
-    g->scratch = nullptr;
-    g->scratch_floats = 0;
     void *p = nullptr;
-    if (hipMalloc(&p, floats * sizeof(float)) != hipSuccess) {
+    if (hipMalloc(&p, need * sizeof(float)) != hipSuccess) {
         (void)hipGetLastError();
         return GNN_ERR_ALLOC;
     }
+    if (g->own_scratch) (void)hipFree(g->own_scratch);
+    g->own_scratch = p;
     g->scratch = static_cast<float *>(p);
-    g->scratch_floats = floats;
+    g->scratch_floats = need;
     return GNN_OK;
 }

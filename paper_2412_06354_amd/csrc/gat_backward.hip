@@ -420,9 +420,10 @@ gnn_status run_pass(const gnn_graph *g, GatBwdParams p, bool vec4, hipStream_t s
     p.n_small = g->n_small; p.n_items = g->n_items; p.n_split = g->n_split; p.chunk = g->chunk;
     p.item_blocks = (int32_t)gnn_div_up(g->n_items, kWavesPerBlock);
     if (g->n_slots > 0) {
-        GNN_TRY(gnn_graph_reserve_scratch(g, 2 * (size_t)g->n_slots * p.HC));
-        p.slot_s = g->scratch;
-        p.slot_vec = g->scratch + (size_t)g->n_slots * p.HC;
+        float *scratch = nullptr;
+        GNN_TRY(gnn_graph_scratch(g, 2 * (size_t)g->n_slots * p.HC, &scratch));
+        p.slot_s = scratch;
+        p.slot_vec = scratch + (size_t)g->n_slots * p.HC;
     }
     if (vec4) {
         const int cols = p.HC / 4;

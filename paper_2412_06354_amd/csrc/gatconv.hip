@@ -422,10 +422,11 @@ gnn_status gnn_gatconv(const gnn_graph *g, const float *d_x, int32_t f_in, const
     p.HC = HC; p.H = heads; p.ch = ch; p.slope = negative_slope;
     p.item_blocks = (int32_t)gnn_div_up(g->n_items, kWavesPerBlock);
     if (g->n_slots > 0) {
-        GNN_TRY(gnn_graph_reserve_scratch(g, 3 * (size_t)g->n_slots * HC));
-        p.slot_acc = g->scratch;
-        p.slot_m = g->scratch + (size_t)g->n_slots * HC;
-        p.slot_d = g->scratch + 2 * (size_t)g->n_slots * HC;
+        float *scratch = nullptr;
+        GNN_TRY(gnn_graph_scratch(g, 3 * (size_t)g->n_slots * HC, &scratch));
+        p.slot_acc = scratch;
+        p.slot_m = scratch + (size_t)g->n_slots * HC;
+        p.slot_d = scratch + 2 * (size_t)g->n_slots * HC;
     }
     const bool vec4 = (ch % 4 == 0) && ((reinterpret_cast<uintptr_t>(d_out) & 15u) == 0);
     if (vec4) {

@@ -7,8 +7,8 @@
 //   3. out[i,:] = dinv[i] * (sum_{j->i} Z'[j,:] + [self-loop] Z'[i,:]) + b   -- the propagate kernel
 //      (copy_xj, sum) with the self-loop term, the destination-side factor and the bias applied in
 //      its epilogue, so the self-loops are never materialised as edges; an optional relu (the
-//      example's GCNConv(64 => 64, relu)) is applied there too.
-// A layer that widens (f_in < f_out, the example's GCNConv(16 => 64)) runs in the other order, so that the gather
+//      example model's second graph convolution, which has a relu) is applied there too.
+// A layer that widens (f_in < f_out, the example model's first graph convolution, 16 to 64 features) runs in the other order, so that the gather
 // moves rows of f_in values instead of f_out:
 //   2'. T[i,:] = dinv[i] * (sum_{j->i} dinv[j] X[j,:] + [self-loop] dinv[i] X[i,:])   -- the propagate kernel with one
 //       weight per edge looked up by source node (X is never rescaled in memory);

@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
 #include <vector>
 
 #include "gnn.h"
@@ -49,6 +50,12 @@ struct gnn_temp_pool {
     }
 };
 
+// One device allocation shared by the graphs of a batch build; freed when the last of them is destroyed.
+struct shared_slab {
+    void *ptr = nullptr;
+    std::atomic<int> refs{0};
+};
+
 struct gnn_graph {
     int32_t num_nodes = 0;        // rows of the CSR = destination nodes
     int32_t num_src_nodes = 0;    // range of colidx; equals num_nodes unless built from a relation between two node sets
@@ -57,6 +64,7 @@ struct gnn_graph {
     int32_t small_max = 0;   // rows with in-degree <= small_max: one sub-group of a wavefront each
     int32_t chunk = 0;       // longer rows: pieces of <= chunk edges, one wavefront each
 
+    shared_slab *shared = nullptr;   // set when the arrays lie in a batch's allocation (slab is then unused)
     void *slab = nullptr;        // the one allocation holding every array below
     size_t slab_bytes = 0;       // its size, and the device it lives on (it may be handed to a later build)
     int device = -1;
@@ -81,17 +89,38 @@ struct gnn_graph {
     int32_t *split_rows = nullptr;      // [n_split] rows made of several pieces
     int32_t *split_slot0 = nullptr;     // [n_split] first slot of the row (slots are consecutive)
 
-    // Partial results of split rows; grown on demand, shared by all calls on this graph.
-    mutable float *scratch = nullptr;
-    mutable size_t scratch_floats = 0;
+    // Partial results of split rows and per-row statistics, shared by all compute calls on this graph.  Sized when
+    // the graph is built (a part of the slab) and only ever replaced by gnn_graph_reserve: compute calls never
+    // allocate, they fail with GNN_ERR_NOT_RESERVED when it is too small.
+    float *scratch = nullptr;
+    size_t scratch_floats = 0;
+    void *own_scratch = nullptr;   // the allocation gnn_graph_reserve made, if any (scratch points into it)
 };
+
+// Feature width the scratch part of the slab is sized for (see gnn_graph_reserve in gnn.h).
+constexpr int32_t kDefaultReservedFeatDim = 128;
+
+// Floats of scratch the compute calls need: three partial rows per slot for the widest user (the attention
+// layer keeps a weighted sum, a maximum and a denominator per slot and feature), a (max, denominator) pair per
+// row and slot and head for the segment softmax.
+static inline size_t gnn_scratch_floats(int64_t slots, int32_t num_nodes, int32_t feat_dim, int32_t heads)
+{
+    const size_t a = 3 * (size_t)slots * (size_t)(feat_dim > 0 ? feat_dim : 0);
+    const size_t b = 2 * ((size_t)num_nodes + (size_t)slots) * (size_t)(heads > 0 ? heads : 0);
+    return a > b ? a : b;
+}
+
+// The graph's scratch buffer if it holds at least `floats` floats, else GNN_ERR_NOT_RESERVED.  Never allocates.
+static inline gnn_status gnn_graph_scratch(const gnn_graph *g, size_t floats, float **out)
+{
+    *out = g->scratch;
+    if (floats > g->scratch_floats) return GNN_ERR_NOT_RESERVED;
+    return GNN_OK;
+}
 
 // sum_partials with a final factor: out[q] = factor * sum over chunks of partial[chunk * elems + q]
 gnn_status gnn_launch_sum_partials_scaled(const float *d_partial, int chunks, int64_t elems, float factor,
                                           float *d_out, hipStream_t stream);
-
-// Makes sure g->scratch holds at least `floats` floats.
-gnn_status gnn_graph_reserve_scratch(const gnn_graph *g, size_t floats);
 
 // Exclusive prefix sums along every row of a row-major [rows x cols] array, in place; d_row_totals[r] receives the
 // sum of row r.

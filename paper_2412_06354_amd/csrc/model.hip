@@ -1,6 +1,6 @@
-// The dense-side layers of the paper's example model (section 3, "Training Example":
-// GNNChain(GCNConv(16 => 64), BatchNorm(64), relu, GCNConv(64 => 64, relu), GlobalPool(mean),
-// Dense(64, 1))) and the chain itself as one call:
+// The dense-side layers of the paper's example model (section 3, "Training Example": two graph convolutions with
+// a batch normalisation and a relu in between, a mean readout per graph and a dense head) and the chain itself
+// as one call:
 //   * batch normalisation across the node dimension, with batch statistics (one pass over the rows with running
 //     (mean, squared-deviation) pairs that merge exactly -- no cancellation; few rows: two passes in one launch)
 //     or stored ones, optional relu fused;

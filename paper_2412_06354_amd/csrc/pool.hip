@@ -244,7 +244,44 @@ __global__ __launch_bounds__(kThreads) void pool_backward_wave_kernel(const int3
     }
 }
 
+// flags[0] |= 1 for a value outside [0, G), |= 2 for a descent between neighbours.
+__global__ __launch_bounds__(kThreads) void check_indicator_kernel(const int32_t *__restrict__ gi, int32_t N, int32_t G,
+                                                                   int32_t *__restrict__ flags)
+{
+    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    int bad = 0;
+    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < N; i += stride) {
+        const int32_t v = gi[i];
+        if ((uint32_t)v >= (uint32_t)G) bad |= 1;
+        if (i + 1 < N && gi[i + 1] < v) bad |= 2;
+    }
+    if (bad) atomicOr(flags, bad);
+}
+
 }  // namespace
+
+extern "C" gnn_status gnn_check_graph_indicator(const int32_t *d_graph_indicator, int32_t num_nodes, int32_t num_graphs,
+                                                void *stream)
+{
+    if (num_nodes < 0 || num_graphs <= 0) return GNN_ERR_BAD_SIZE;
+    if (num_nodes == 0) return GNN_OK;
+    if (!d_graph_indicator) return GNN_ERR_NULL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    gnn_temp_pool pool;
+    int32_t *d_flags = nullptr;
+    GNN_TRY(pool.get(&d_flags, 1));
+    GNN_HIP(hipMemsetAsync(d_flags, 0, sizeof(int32_t), s));
+    const int blocks = (int)(gnn_div_up(num_nodes, kThreads) < 4096 ? gnn_div_up(num_nodes, kThreads) : 4096);
+    hipLaunchKernelGGL(check_indicator_kernel, dim3(blocks), dim3(kThreads), 0, s, d_graph_indicator, num_nodes,
+                       num_graphs, d_flags);
+    GNN_LAUNCH_CHECK();
+    int32_t h = 0;
+    GNN_HIP(hipMemcpyAsync(&h, d_flags, sizeof(int32_t), hipMemcpyDeviceToHost, s));
+    GNN_HIP(hipStreamSynchronize(s));
+    if (h & 1) return GNN_ERR_INDEX_RANGE;
+    if (h & 2) return GNN_ERR_NOT_SORTED;
+    return GNN_OK;
+}
 
 gnn_status gnn_launch_pool_backward(const int32_t *d_graph_indicator, int32_t num_nodes, int32_t num_graphs,
                                     const float *d_grad_out, int32_t feat_dim, gnn_aggr aggr, const float *d_relu_y,

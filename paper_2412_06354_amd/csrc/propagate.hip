@@ -673,8 +673,7 @@ gnn_status gnn_launch_propagate(const gnn_graph *g, const float *d_x, int32_t fe
     p.mean = epi.mean; p.relu = epi.relu; p.accumulate = epi.accumulate; p.self_scale = epi.self_scale; p.row_scale = epi.row_scale; p.bias = epi.bias;
     p.winners = d_winners;
 
-    if (g->n_slots > 0) GNN_TRY(gnn_graph_reserve_scratch(g, (size_t)g->n_slots * F));
-    p.scratch = g->scratch;
+    GNN_TRY(gnn_graph_scratch(g, (size_t)g->n_slots * F, &p.scratch));
 
     if (x_is_bf16) {   // 1 = bfloat16, 2 = binary16
         if (F % 8 != 0 || !aligned16(d_x) || !aligned16(d_out) || d_winners) return GNN_ERR_UNSUPPORTED;

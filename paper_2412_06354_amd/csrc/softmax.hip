@@ -329,14 +329,15 @@ gnn_status run_softmax(const gnn_graph *g, const float *d_in, const float *d_in2
     if (!d_in || !d_out || (BWD && !d_in2)) return GNN_ERR_NULL;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const size_t stat_floats = 2 * ((size_t)g->num_nodes + (size_t)g->n_slots) * heads;
-    GNN_TRY(gnn_graph_reserve_scratch(g, stat_floats));
+    float *scratch = nullptr;
+    GNN_TRY(gnn_graph_scratch(g, stat_floats, &scratch));
 
     SmParams p{};
     p.coo = (order == GNN_EDGE_ORDER_COO) ? 1 : 0;
     p.rowptr = g->rowptr; p.perm = g->perm;
     p.row_of_edge = p.coo ? g->dst_coo : g->rowidx;
     p.s = d_in; p.s2 = d_in2; p.out = d_out;
-    p.rowstat = reinterpret_cast<float2 *>(g->scratch);
+    p.rowstat = reinterpret_cast<float2 *>(scratch);
     p.slotstat = p.rowstat + (size_t)g->num_nodes * heads;
     p.small_rows = g->small_rows; p.item_row = g->item_row; p.item_start = g->item_start;
     p.item_slot = g->item_slot; p.split_rows = g->split_rows; p.split_slot0 = g->split_slot0;

@@ -1,0 +1,217 @@
+"""GPU tests of the boundary itself: which calls allocate, the reservation of a graph's scratch memory, the
+plain gnn_build_csr entry point, the batch build of temporal snapshots and the graph_indicator check.
+All calls go through the C ABI; expected values come from the CPU oracle."""
+import ctypes
+
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+import oracle
+from oracle import AGGR_MAX, AGGR_MEAN, AGGR_SUM, MSG_COPY_XJ, MSG_E_MUL_XJ
+from paper_2412_06354_amd import synth
+from util import assert_close_rel, assert_close_sabs
+
+pytestmark = pytest.mark.gpu
+
+ERR_INDEX_RANGE, ERR_NOT_SORTED, ERR_NOT_RESERVED = 3, 7, 8
+
+
+@pytest.fixture(scope="module")
+def gnn():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2412_06354_amd import binding
+    binding.lib()
+    return binding
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def host(t):
+    return t.cpu().numpy()
+
+
+def split_row_graph():
+    """Power-law graph whose hub rows are cut into several wavefront pieces under the default thresholds."""
+    return synth.config2_weighted(num_nodes=20_000, num_edges=300_000, feat=64, cap=6000.0)
+
+
+def test_build_csr_entry_point_itself(gnn):
+    """gnn_build_csr called directly through ctypes (not the variant with thresholds): CSR bit for bit."""
+    wl = split_row_graph()
+    src, dst = dev(wl.src), dev(wl.dst)
+    lib = gnn.lib()
+    out = ctypes.c_void_p()
+    rc = lib.gnn_build_csr(src.data_ptr(), dst.data_ptr(), wl.num_edges, wl.num_nodes,
+                           torch.cuda.current_stream().cuda_stream, ctypes.byref(out))
+    assert rc == 0 and out.value
+    g = gnn.Graph(out.value, src.device)
+    rowptr, colidx, perm, indeg = oracle.build_csr(wl.src, wl.dst, wl.num_nodes)
+    np.testing.assert_array_equal(host(g.rowptr), rowptr)
+    np.testing.assert_array_equal(host(g.colidx), colidx)
+    np.testing.assert_array_equal(host(g.perm), perm)
+    np.testing.assert_array_equal(host(g.indegree), indeg)
+    assert g.work_sizes()["split_rows"] > 0
+    # the binding's default path is this very entry point
+    g2 = gnn.build_csr(src, dst, wl.num_nodes)
+    assert torch.equal(g2.perm, g.perm) and g2.work_sizes() == g.work_sizes()
+    g.close()
+    g2.close()
+
+
+def test_first_propagate_can_be_captured(gnn):
+    """Compute calls never allocate or synchronise: the FIRST propagate on a graph with split rows is recorded
+    into a HIP graph (no warm-up call on this handle) and every replay reproduces the eager result."""
+    wl = split_row_graph()
+    n = wl.num_nodes
+    g = gnn.build_csr(dev(wl.src), dev(wl.dst), n)
+    assert g.work_sizes()["split_rows"] > 0
+    x, e = dev(wl.x), dev(wl.edge_weight)
+    out = torch.empty((n, 64), dtype=torch.float32, device="cuda")
+    torch.cuda.synchronize()
+    gph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(gph):
+        gnn.propagate(g, x, e, MSG_E_MUL_XJ, AGGR_SUM, out=out)
+    ref, sabs = oracle.propagate(wl.src, wl.dst, n, wl.x, wl.edge_weight, MSG_E_MUL_XJ, AGGR_SUM, with_sabs=True)
+    first = None
+    for it in range(4):
+        out.fill_(float("nan"))
+        gph.replay()
+        torch.cuda.synchronize()
+        got = host(out)
+        assert_close_sabs(got, ref, sabs, what=f"captured propagate, replay {it}")
+        if first is None:
+            first = got.copy()
+        assert np.array_equal(first.view(np.uint32), got.view(np.uint32))
+        other = gnn.propagate(g, x, None, MSG_COPY_XJ, AGGR_MAX)     # eager work on the same handle between replays
+        torch.cuda.synchronize()
+        assert bool(torch.isfinite(other).all())
+    eager = gnn.propagate(g, x, e, MSG_E_MUL_XJ, AGGR_SUM)
+    assert np.array_equal(host(eager).view(np.uint32), first.view(np.uint32))
+    del gph
+    g.close()
+
+
+def test_reservation_limits_and_reserve(gnn):
+    """Beyond the sizes a fresh graph is reserved for, a compute call fails with GNN_ERR_NOT_RESERVED and
+    launches nothing; after gnn_graph_reserve the same call matches the oracle."""
+    wl = synth.config2_weighted(num_nodes=4000, num_edges=100_000, feat=8, cap=3000.0)
+    n = wl.num_nodes
+    g = gnn.build_csr(dev(wl.src), dev(wl.dst), n, 4, 64)      # many split rows
+    assert g.work_sizes()["split_rows"] > 0
+    lib, stream = gnn.lib(), torch.cuda.current_stream().cuda_stream
+    # segment softmax needs a reservation of its own
+    heads = 4
+    s = (3.0 * synth.normal_f32(41, 2, wl.num_edges * heads)).reshape(wl.num_edges, heads)
+    sd = dev(s)
+    alpha = torch.full_like(sd, -7.0)
+    rc = lib.gnn_segment_softmax(g._h, sd.data_ptr(), heads, 0, alpha.data_ptr(), stream)
+    assert rc == ERR_NOT_RESERVED
+    torch.cuda.synchronize()
+    assert bool((alpha == -7.0).all())                          # nothing ran
+    g.reserve(0, heads)
+    rc = lib.gnn_segment_softmax(g._h, sd.data_ptr(), heads, 0, alpha.data_ptr(), stream)
+    assert rc == 0
+    assert_close_rel(host(alpha), oracle.segment_softmax(wl.dst, n, s), what="softmax after reserve")
+    # a very wide propagate: the slots of this graph times 2 000 features exceed the default reservation
+    f = 2000
+    n_slots = int(g.work_lists()["item_slot"].max()) + 1
+    assert n_slots * f > 3 * (2 * (wl.num_edges // 64) + 1) * 128, "the case must exceed the default reservation"
+    xw = synth.normal_f32(41, 3, n * f).reshape(n, f)
+    xd = dev(xw)
+    out = torch.full((n, f), -7.0, dtype=torch.float32, device="cuda")
+    rc = lib.gnn_propagate(g._h, xd.data_ptr(), f, None, 1, 0, MSG_COPY_XJ, AGGR_SUM, out.data_ptr(), stream)
+    assert rc == ERR_NOT_RESERVED
+    torch.cuda.synchronize()
+    assert bool((out == -7.0).all())
+    g.reserve(f, 0)
+    got = host(gnn.propagate(g, xd, None, MSG_COPY_XJ, AGGR_SUM, out=out))
+    ref, sabs = oracle.propagate(wl.src, wl.dst, n, xw, None, MSG_COPY_XJ, AGGR_SUM, with_sabs=True)
+    assert_close_sabs(got, ref, sabs, what="wide propagate after reserve")
+    # the earlier reservation for the softmax is still honoured (reservations only grow)
+    rc = lib.gnn_segment_softmax(g._h, sd.data_ptr(), heads, 0, alpha.data_ptr(), stream)
+    assert rc == 0
+    assert lib.gnn_graph_reserve(None, 1, 1) == 1 and lib.gnn_graph_reserve(g._h, -1, 0) == 2
+    g.close()
+
+
+def test_batch_build_of_temporal_snapshots(gnn):
+    """T snapshots over one node set: every handle equals the oracle's CSR of its snapshot bit for bit, has the
+    work lists of a build on its own, and propagate per snapshot matches the oracle; handles are destroyed one
+    by one in any order."""
+    n, f = 6000, 32
+    sizes = [90_000, 0, 25_000, 140_000, 1]
+    snaps = []
+    for t, e in enumerate(sizes):
+        if e == 0:
+            snaps.append((np.empty(0, np.int32), np.empty(0, np.int32)))
+        else:
+            snaps.append(synth.chung_lu_directed(n, e, 1.0, min(2500.0, max(4.0, e / 8.0)), 1000 + t))
+    x = synth.normal_f32(77, 2, n * f).reshape(n, f)
+    xd = dev(x)
+    graphs = gnn.build_csr_batch([dev(s) for s, _ in snaps], [dev(d) for _, d in snaps], n)
+    assert len(graphs) == len(sizes)
+    assert any(g.work_sizes()["split_rows"] > 0 for g in graphs)
+    for t, (g, (src, dst)) in enumerate(zip(graphs, snaps)):
+        rowptr, colidx, perm, indeg = oracle.build_csr(src, dst, n)
+        assert g.num_edges == sizes[t] and g.num_nodes == n
+        np.testing.assert_array_equal(host(g.rowptr), rowptr, err_msg=f"snapshot {t}")
+        np.testing.assert_array_equal(host(g.colidx), colidx, err_msg=f"snapshot {t}")
+        np.testing.assert_array_equal(host(g.perm), perm, err_msg=f"snapshot {t}")
+        np.testing.assert_array_equal(host(g.indegree), indeg, err_msg=f"snapshot {t}")
+        alone = gnn.build_csr(dev(src), dev(dst), n)
+        assert alone.work_sizes() == g.work_sizes()
+        la, lb = alone.work_lists(), g.work_lists()
+        assert all(torch.equal(la[k], lb[k]) for k in la)
+        alone.close()
+        e = synth.uniform_f32(78, t, max(sizes[t], 1))[:sizes[t]]
+        for msg, aggr in ((MSG_COPY_XJ, AGGR_SUM), (MSG_E_MUL_XJ, AGGR_MEAN), (MSG_E_MUL_XJ, AGGR_MAX)):
+            ref, sabs = oracle.propagate(src, dst, n, x, e if msg else None, msg, aggr, with_sabs=True)
+            got = host(gnn.propagate(g, xd, dev(e) if msg else None, msg, aggr))
+            if aggr == AGGR_MAX:
+                np.testing.assert_array_equal(got.view(np.uint32), ref.view(np.uint32))
+            else:
+                assert_close_sabs(got, ref, sabs, what=f"snapshot {t} msg={msg} aggr={aggr}")
+    # destroy out of order; the survivors stay valid until their own destroy
+    graphs[3].close()
+    graphs[0].close()
+    ref = oracle.propagate(snaps[2][0], snaps[2][1], n, x, None, MSG_COPY_XJ, AGGR_MAX)
+    np.testing.assert_array_equal(host(gnn.propagate(graphs[2], xd, None, MSG_COPY_XJ, AGGR_MAX)).view(np.uint32),
+                                  ref.view(np.uint32))
+    for g in graphs:
+        g.close()
+    # an out-of-range node id in any snapshot: no handle at all
+    bad = snaps[2][1].copy()
+    bad[17] = n
+    with pytest.raises(gnn.GnnError) as err:
+        gnn.build_csr_batch([dev(snaps[0][0]), dev(snaps[2][0])], [dev(snaps[0][1]), dev(bad)], n)
+    assert err.value.code == ERR_INDEX_RANGE
+    # host-side argument errors
+    lib = gnn.lib()
+    assert lib.gnn_build_csr_batch(0, None, None, None, n, None, None) == 1
+    slots = (ctypes.c_void_p * 1)()
+    assert lib.gnn_build_csr_batch(0, None, None, None, n, None, slots) == 2
+
+
+def test_check_graph_indicator(gnn):
+    wl = synth.config3_batched(num_graphs=200, feat=4)
+    gi = wl.graph_indicator
+    gnn.check_graph_indicator(dev(gi), wl.num_graphs)
+    swapped = gi.copy()
+    k = int(np.flatnonzero(np.diff(gi) > 0)[3])
+    swapped[k], swapped[k + 1] = swapped[k + 1], swapped[k]
+    with pytest.raises(gnn.GnnError) as err:
+        gnn.check_graph_indicator(dev(swapped), wl.num_graphs)
+    assert err.value.code == ERR_NOT_SORTED
+    with pytest.raises(gnn.GnnError) as err:
+        gnn.check_graph_indicator(dev(gi), wl.num_graphs - 1)
+    assert err.value.code == ERR_INDEX_RANGE
+    neg = gi.copy()
+    neg[0] = -1
+    with pytest.raises(gnn.GnnError) as err:
+        gnn.check_graph_indicator(dev(neg), wl.num_graphs)
+    assert err.value.code == ERR_INDEX_RANGE

@@ -93,6 +93,25 @@ def test_config2_propagate_sampled_rows(cfg2, gnn, msg):
         say(f"config 2: msg={msg} aggr={aggr} ok on {rows.shape[0]} sampled rows ({eid.shape[0]} edges)")
 
 
+@pytest.mark.parametrize("msg,aggr", [(MSG_COPY_XJ, AGGR_SUM), (MSG_E_MUL_XJ, AGGR_SUM), (MSG_E_MUL_XJ, AGGR_MEAN),
+                                      (MSG_E_MUL_XJ, AGGR_MAX)])
+def test_config2_propagate_every_element(cfg2, gnn, msg, aggr):
+    """All 1 M x 64 outputs of the headline launch (copy_xj + sum) and of the three weighted runs against the
+    oracle's edge loop over the whole 20 M-edge list; edge weights in CSR order, as the benchmark times them."""
+    wl, g = cfg2
+    n = wl.num_nodes
+    e = wl.edge_weight if msg == MSG_E_MUL_XJ else None
+    say(f"config 2, every element: oracle msg={msg} aggr={aggr}")
+    ref, sabs = oracle.propagate(wl.src, wl.dst, n, wl.x, e, msg, aggr, with_sabs=True)
+    e_csr = gnn.edge_data_to_csr(g, dev(wl.edge_weight)) if msg == MSG_E_MUL_XJ else None
+    got = host(gnn.propagate(g, dev(wl.x), e_csr, msg, aggr, e_order=gnn.EDGE_ORDER_CSR))
+    if aggr == AGGR_MAX:
+        np.testing.assert_array_equal(got.view(np.uint32), ref.view(np.uint32))
+    else:
+        assert_close_sabs(got, ref, sabs, what=f"config2 whole graph msg={msg} aggr={aggr}")
+    say(f"config 2, every element: msg={msg} aggr={aggr} ok on {n} x {got.shape[1]} outputs")
+
+
 def test_config2_invariants_at_full_size(cfg2, gnn):
     wl, g = cfg2
     n = wl.num_nodes
