@@ -158,9 +158,11 @@ gnn_status gnn_release_cached_memory(void);
  *     feat_dim (f_in, f_out) up to 3 * max_feat_dim,
  *   gnn_gatconv / gnn_gatconv_backward accept heads * ch up to max_feat_dim,
  *   gnn_segment_softmax / gnn_segment_softmax_backward accept up to max_heads heads.
- * A freshly built graph is reserved for max_feat_dim = 128 and max_heads = 0: the segment softmax needs one
- * gnn_graph_reserve call, everything else only for wider features than that.  A compute call beyond the
- * reserved sizes returns GNN_ERR_NOT_RESERVED and launches nothing.  The reservation only grows.
+ * A freshly built graph is reserved for max_feat_dim = 128 (384 floats for every partial row its edge count
+ * could give rise to): wider features need this call, and so does the segment softmax on all but small graphs
+ * (it keeps two floats per node and head: call gnn_graph_reserve(g, 0, heads) once before using it).  A
+ * compute call beyond what is reserved returns GNN_ERR_NOT_RESERVED and launches nothing.  The reservation
+ * only grows.
  * This call may allocate and then synchronises the DEVICE (kernels enqueued earlier may use the buffer it
  * replaces): call it when the graph is set up, not between enqueued work and not during stream capture.
  * Errors: GNN_ERR_NULL, GNN_ERR_BAD_SIZE (a negative size), GNN_ERR_ALLOC, GNN_ERR_DEVICE.

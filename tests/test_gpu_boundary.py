@@ -99,13 +99,12 @@ def test_first_propagate_can_be_captured(gnn):
 def test_reservation_limits_and_reserve(gnn):
     """Beyond the sizes a fresh graph is reserved for, a compute call fails with GNN_ERR_NOT_RESERVED and
     launches nothing; after gnn_graph_reserve the same call matches the oracle."""
-    wl = synth.config2_weighted(num_nodes=4000, num_edges=100_000, feat=8, cap=3000.0)
-    n = wl.num_nodes
-    g = gnn.build_csr(dev(wl.src), dev(wl.dst), n, 4, 64)      # many split rows
-    assert g.work_sizes()["split_rows"] > 0
     lib, stream = gnn.lib(), torch.cuda.current_stream().cuda_stream
-    # segment softmax needs a reservation of its own
-    heads = 4
+    # segment softmax: per-node statistics for 32 heads on 20 000 nodes exceed what the build set aside
+    wl = split_row_graph()
+    n, heads = wl.num_nodes, 32
+    g = gnn.build_csr(dev(wl.src), dev(wl.dst), n)
+    assert 2 * n * heads > 3 * (2 * (wl.num_edges // 256) + 1) * 128, "the case must exceed the default reservation"
     s = (3.0 * synth.normal_f32(41, 2, wl.num_edges * heads)).reshape(wl.num_edges, heads)
     sd = dev(s)
     alpha = torch.full_like(sd, -7.0)
@@ -116,27 +115,34 @@ def test_reservation_limits_and_reserve(gnn):
     g.reserve(0, heads)
     rc = lib.gnn_segment_softmax(g._h, sd.data_ptr(), heads, 0, alpha.data_ptr(), stream)
     assert rc == 0
-    assert_close_rel(host(alpha), oracle.segment_softmax(wl.dst, n, s), what="softmax after reserve")
+    ref = oracle.segment_softmax(wl.dst, n, s)
+    assert_close_rel(host(alpha), ref, what="softmax after reserve")
     # a very wide propagate: the slots of this graph times 2 000 features exceed the default reservation
+    wl2 = synth.config2_weighted(num_nodes=4000, num_edges=100_000, feat=8, cap=3000.0)
+    n2 = wl2.num_nodes
+    g2 = gnn.build_csr(dev(wl2.src), dev(wl2.dst), n2, 4, 64)      # many split rows
     f = 2000
-    n_slots = int(g.work_lists()["item_slot"].max()) + 1
-    assert n_slots * f > 3 * (2 * (wl.num_edges // 64) + 1) * 128, "the case must exceed the default reservation"
-    xw = synth.normal_f32(41, 3, n * f).reshape(n, f)
+    n_slots = int(g2.work_lists()["item_slot"].max()) + 1
+    assert n_slots * f > 3 * (2 * (wl2.num_edges // 64) + 1) * 128, "the case must exceed the default reservation"
+    xw = synth.normal_f32(41, 3, n2 * f).reshape(n2, f)
     xd = dev(xw)
-    out = torch.full((n, f), -7.0, dtype=torch.float32, device="cuda")
-    rc = lib.gnn_propagate(g._h, xd.data_ptr(), f, None, 1, 0, MSG_COPY_XJ, AGGR_SUM, out.data_ptr(), stream)
+    out = torch.full((n2, f), -7.0, dtype=torch.float32, device="cuda")
+    rc = lib.gnn_propagate(g2._h, xd.data_ptr(), f, None, 1, 0, MSG_COPY_XJ, AGGR_SUM, out.data_ptr(), stream)
     assert rc == ERR_NOT_RESERVED
     torch.cuda.synchronize()
     assert bool((out == -7.0).all())
-    g.reserve(f, 0)
-    got = host(gnn.propagate(g, xd, None, MSG_COPY_XJ, AGGR_SUM, out=out))
-    ref, sabs = oracle.propagate(wl.src, wl.dst, n, xw, None, MSG_COPY_XJ, AGGR_SUM, with_sabs=True)
-    assert_close_sabs(got, ref, sabs, what="wide propagate after reserve")
-    # the earlier reservation for the softmax is still honoured (reservations only grow)
+    g2.reserve(f, 0)
+    got = host(gnn.propagate(g2, xd, None, MSG_COPY_XJ, AGGR_SUM, out=out))
+    ref2, sabs2 = oracle.propagate(wl2.src, wl2.dst, n2, xw, None, MSG_COPY_XJ, AGGR_SUM, with_sabs=True)
+    assert_close_sabs(got, ref2, sabs2, what="wide propagate after reserve")
+    # reservations only grow: a smaller request afterwards changes nothing
+    g.reserve(64, 1)
     rc = lib.gnn_segment_softmax(g._h, sd.data_ptr(), heads, 0, alpha.data_ptr(), stream)
     assert rc == 0
+    assert_close_rel(host(alpha), ref, what="softmax after a smaller reserve")
     assert lib.gnn_graph_reserve(None, 1, 1) == 1 and lib.gnn_graph_reserve(g._h, -1, 0) == 2
     g.close()
+    g2.close()
 
 
 def test_batch_build_of_temporal_snapshots(gnn):
