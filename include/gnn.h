@@ -61,7 +61,8 @@ typedef enum {
     GNN_ERR_ALLOC = 5,       /* device allocation failed */
     GNN_ERR_DEVICE = 6,      /* a HIP call or launch failed */
     GNN_ERR_NOT_SORTED = 7,  /* graph_indicator is not non-decreasing (gnn_check_graph_indicator) */
-    GNN_ERR_NOT_RESERVED = 8 /* the graph's scratch memory is too small for this call: gnn_graph_reserve first */
+    GNN_ERR_NOT_RESERVED = 8,/* the graph's scratch memory is too small for this call: gnn_graph_reserve first */
+    GNN_ERR_SCRATCH_LIMIT = 9/* gnn_propagate_noalloc: the call needs more than the fixed scratch array holds */
 } gnn_status;
 
 /*
@@ -230,6 +231,22 @@ gnn_status gnn_edge_data_to_csr(const gnn_graph *g, const float *d_e, int32_t e_
 gnn_status gnn_propagate(const gnn_graph *g, const float *d_x, int32_t feat_dim,
                          const float *d_e, int32_t e_dim, gnn_edge_order e_order,
                          gnn_msg_op msg, gnn_aggr aggr, float *d_out, void *stream);
+
+/*
+ * gnn_propagate for callers that cannot call the allocator at all -- code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc: same arguments, same kernels and bit-identical results, but the partial
+ * rows of nodes whose edges are split over several wavefronts go to a fixed 16 MiB array inside the library's
+ * device image instead of memory owned by the graph.  The call makes no allocation of any kind (its first call on
+ * a device only asks the runtime for the address of that device's copy of the array).
+ * Limit: (number of partial-row slots of the graph) * feat_dim <= 4 194 304 floats; beyond it the call returns
+ * GNN_ERR_SCRATCH_LIMIT and launches nothing (the headline graph, 1 M nodes / 20 M edges, needs 0.9 M floats at
+ * feat_dim = 64).  All calls on one GPU share that GPU's array, whatever the graph: calls that overlap in time on
+ * one GPU race, so keep them on one stream or order them with events.  The array keeps the last call's partial
+ * rows; nothing in it has to be cleared, since a launch only reads partial rows it has written itself.
+ */
+gnn_status gnn_propagate_noalloc(const gnn_graph *g, const float *d_x, int32_t feat_dim, const float *d_e,
+                                 int32_t e_dim, gnn_edge_order e_order, gnn_msg_op msg, gnn_aggr aggr,
+                                 float *d_out, void *stream);
 
 /*
  * Message passing on a heterogeneous graph, for one destination node type: the relations that end in it

@@ -42,6 +42,7 @@ SIGNATURES = {
     "gnn_graph_work_lists": (None, [_vp] + [_c.POINTER(_vp)] * 6),
     "gnn_edge_data_to_csr": (_c.c_int, [_vp, _vp, _i32, _vp, _vp]),
     "gnn_propagate": (_c.c_int, [_vp, _vp, _i32, _vp, _i32, _c.c_int, _c.c_int, _c.c_int, _vp, _vp]),
+    "gnn_propagate_noalloc": (_c.c_int, [_vp, _vp, _i32, _vp, _i32, _c.c_int, _c.c_int, _c.c_int, _vp, _vp]),
     "gnn_build_csr_bipartite": (_c.c_int, [_vp, _vp, _i64, _i32, _i32, _vp, _c.POINTER(_vp)]),
     "gnn_graph_num_src_nodes": (_i32, [_vp]),
     "gnn_hetero_propagate": (_c.c_int, [_i32, _vp, _vp, _vp, _i32, _i32, _c.c_int, _c.c_int, _c.c_int, _vp, _vp]),
@@ -330,6 +331,20 @@ def propagate(g: Graph, x: torch.Tensor, e: Optional[torch.Tensor] = None, msg: 
     rc = lib().gnn_propagate(g._h, _dev(x, torch.float32, "x"), f, _dev(e, torch.float32, "e"), e_dim,
                              e_order, msg, aggr, _dev(out, torch.float32, "out"), _stream())
     _check(rc, "gnn_propagate")
+    return out
+
+
+def propagate_noalloc(g: Graph, x: torch.Tensor, e: Optional[torch.Tensor], msg: int, aggr: int, e_order: int,
+                      out: torch.Tensor) -> torch.Tensor:
+    """gnn_propagate_noalloc: the caller passes every buffer, the partial rows go to the library's fixed array."""
+    n, f = x.shape
+    e_dim = 1
+    if e is not None:
+        e = _edge_rows(e, g.num_edges)
+        e_dim = int(e.shape[1])
+    rc = lib().gnn_propagate_noalloc(g._h, _dev(x, torch.float32, "x"), f, _dev(e, torch.float32, "e"), e_dim,
+                                     e_order, msg, aggr, _dev(out, torch.float32, "out"), _stream())
+    _check(rc, "gnn_propagate_noalloc")
     return out
 
 

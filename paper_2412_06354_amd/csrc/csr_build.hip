@@ -1062,6 +1062,7 @@ const char *gnn_status_string(gnn_status s)
     case GNN_ERR_ALLOC: return "device allocation failed";
     case GNN_ERR_DEVICE: return "HIP call or kernel launch failed";
     case GNN_ERR_NOT_SORTED: return "graph_indicator is not sorted";
+    case GNN_ERR_SCRATCH_LIMIT: return "the call needs more than the fixed scratch array of gnn_propagate_noalloc holds";
     case GNN_ERR_NOT_RESERVED: return "the graph's scratch memory is too small for this call: gnn_graph_reserve first";
     }
     return "unknown status";

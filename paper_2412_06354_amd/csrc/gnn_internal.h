@@ -153,6 +153,8 @@ enum gnn_reduce { GNN_REDUCE_SUM = 0, GNN_REDUCE_MAX = 1, GNN_REDUCE_MIN = 2, GN
 // gathered element x[j,f] only contributes to the edge whose id equals d_winners[j,f] (the routing
 // step of a max aggregation's backward pass).
 // x_is_bf16: d_x points to bfloat16 values (copy_xj or one weight per edge, sum / mean / max, feat_dim % 8 == 0).
+// d_scratch (optional): device buffer of scratch_floats floats that receives the partial rows of split rows instead
+// of the graph's own scratch memory (GNN_ERR_SCRATCH_LIMIT if it is too small).
 // Shared launcher behind gnn_propagate / gnn_aggregate_neighbors / gnn_gin_update / the sparse half
 // of gnn_gcnconv.
 gnn_status gnn_launch_propagate(const gnn_graph *g, const float *d_x, int32_t feat_dim,
@@ -160,7 +162,8 @@ gnn_status gnn_launch_propagate(const gnn_graph *g, const float *d_x, int32_t fe
                                 gnn_msg_op msg, int reduce, const gnn_epilogue &epi,
                                 float *d_out, hipStream_t stream,
                                 gnn_gather_index gather = GNN_GATHER_SOURCE_NODE,
-                                const int32_t *d_winners = nullptr, int x_is_bf16 = 0);
+                                const int32_t *d_winners = nullptr, int x_is_bf16 = 0,
+                                float *d_scratch = nullptr, size_t scratch_floats = 0);
 
 // out[k] = <x[src[k],:], y[dst[k],:]> per edge, in the order out_order names (backward.hip)
 gnn_status gnn_launch_edge_dot(const gnn_graph *g, const float *d_x_src, const float *d_y_dst, int32_t feat_dim,

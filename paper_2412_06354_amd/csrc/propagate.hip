@@ -17,6 +17,14 @@
 #include "gnn_internal.h"
 
 #include <algorithm>
+#include <mutex>
+
+// Scratch memory of gnn_propagate_noalloc: the partial rows of split rows for callers that must not touch the
+// allocator at all.  A fixed array in the library's device image: every GPU the library runs on holds its own
+// copy, at its own address, until the process ends.  Host code never uses the array's name as an address; it
+// asks the runtime for the device address once per device (static_scratch_on_current_device) and passes that.
+constexpr size_t kStaticScratchFloats = (size_t)4 << 20;   // 16 MiB
+static __device__ __align__(256) float static_scratch[kStaticScratchFloats];
 
 namespace {
 
@@ -628,12 +636,33 @@ int reduce_of(gnn_aggr a)
     }
 }
 
+constexpr int kMaxDevices = 64;
+std::mutex g_static_scratch_mu;
+float *g_static_scratch_ptr[kMaxDevices];   // device address of static_scratch, per device, once asked for
+
+// The device address of this device's copy of static_scratch (looked up on the first call per device).
+gnn_status static_scratch_on_current_device(float **out)
+{
+    int dev = 0;
+    GNN_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return GNN_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_static_scratch_mu);
+    if (!g_static_scratch_ptr[dev]) {
+        void *p = nullptr;
+        GNN_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(static_scratch)));
+        if (!p) return GNN_ERR_DEVICE;
+        g_static_scratch_ptr[dev] = static_cast<float *>(p);
+    }
+    *out = g_static_scratch_ptr[dev];
+    return GNN_OK;
+}
+
 }  // namespace
 
 gnn_status gnn_launch_propagate(const gnn_graph *g, const float *d_x, int32_t feat_dim, const float *d_e,
                                 int32_t e_dim, gnn_edge_order e_order, gnn_msg_op msg, int reduce,
                                 const gnn_epilogue &epi, float *d_out, hipStream_t stream, gnn_gather_index gather,
-                                const int32_t *d_winners, int x_is_bf16)
+                                const int32_t *d_winners, int x_is_bf16, float *d_scratch, size_t scratch_floats)
 {
     const int F = feat_dim;
     int kmsg = kMsgCopy;
@@ -673,7 +702,12 @@ gnn_status gnn_launch_propagate(const gnn_graph *g, const float *d_x, int32_t fe
     p.mean = epi.mean; p.relu = epi.relu; p.accumulate = epi.accumulate; p.self_scale = epi.self_scale; p.row_scale = epi.row_scale; p.bias = epi.bias;
     p.winners = d_winners;
 
-    GNN_TRY(gnn_graph_scratch(g, (size_t)g->n_slots * F, &p.scratch));
+    if (d_scratch) {   // the caller's buffer for the partial rows instead of the graph's
+        if ((size_t)g->n_slots * F > scratch_floats) return GNN_ERR_SCRATCH_LIMIT;
+        p.scratch = d_scratch;
+    } else {
+        GNN_TRY(gnn_graph_scratch(g, (size_t)g->n_slots * F, &p.scratch));
+    }
 
     if (x_is_bf16) {   // 1 = bfloat16, 2 = binary16
         if (F % 8 != 0 || !aligned16(d_x) || !aligned16(d_out) || d_winners) return GNN_ERR_UNSUPPORTED;
@@ -696,8 +730,9 @@ gnn_status gnn_launch_propagate(const gnn_graph *g, const float *d_x, int32_t fe
 
 extern "C" {
 
-gnn_status gnn_propagate(const gnn_graph *g, const float *d_x, int32_t feat_dim, const float *d_e, int32_t e_dim,
-                         gnn_edge_order e_order, gnn_msg_op msg, gnn_aggr aggr, float *d_out, void *stream)
+static gnn_status check_propagate_arguments(const gnn_graph *g, const float *d_x, int32_t feat_dim, const float *d_e,
+                                            int32_t e_dim, gnn_edge_order e_order, gnn_msg_op msg, gnn_aggr aggr,
+                                            const float *d_out)
 {
     if (!g || !d_x || !d_out) return GNN_ERR_NULL;
     if (feat_dim <= 0) return GNN_ERR_BAD_SIZE;
@@ -708,10 +743,33 @@ gnn_status gnn_propagate(const gnn_graph *g, const float *d_x, int32_t feat_dim,
         if (e_order != GNN_EDGE_ORDER_COO && e_order != GNN_EDGE_ORDER_CSR) return GNN_ERR_BAD_SIZE;
         if (!d_e && g->num_edges > 0) return GNN_ERR_NULL;
     }
+    return GNN_OK;
+}
+
+gnn_status gnn_propagate(const gnn_graph *g, const float *d_x, int32_t feat_dim, const float *d_e, int32_t e_dim,
+                         gnn_edge_order e_order, gnn_msg_op msg, gnn_aggr aggr, float *d_out, void *stream)
+{
+    GNN_TRY(check_propagate_arguments(g, d_x, feat_dim, d_e, e_dim, e_order, msg, aggr, d_out));
     gnn_epilogue epi;
     epi.mean = (aggr == GNN_AGGR_MEAN);
     return gnn_launch_propagate(g, d_x, feat_dim, d_e, e_dim, e_order, msg, reduce_of(aggr), epi, d_out,
                                 static_cast<hipStream_t>(stream));
+}
+
+gnn_status gnn_propagate_noalloc(const gnn_graph *g, const float *d_x, int32_t feat_dim, const float *d_e,
+                                 int32_t e_dim, gnn_edge_order e_order, gnn_msg_op msg, gnn_aggr aggr, float *d_out,
+                                 void *stream)
+{
+    GNN_TRY(check_propagate_arguments(g, d_x, feat_dim, d_e, e_dim, e_order, msg, aggr, d_out));
+    if ((size_t)g->n_slots * (size_t)feat_dim > kStaticScratchFloats) return GNN_ERR_SCRATCH_LIMIT;
+    float *d_scratch = nullptr;
+    GNN_TRY(static_scratch_on_current_device(&d_scratch));
+    gnn_epilogue epi;
+    epi.mean = (aggr == GNN_AGGR_MEAN);
+    // Nothing in the array has to start at zero: every partial row a launch reads was written by the same launch.
+    return gnn_launch_propagate(g, d_x, feat_dim, d_e, e_dim, e_order, msg, reduce_of(aggr), epi, d_out,
+                                static_cast<hipStream_t>(stream), GNN_GATHER_SOURCE_NODE, nullptr, 0, d_scratch,
+                                kStaticScratchFloats);
 }
 
 gnn_status gnn_hetero_propagate(int32_t num_relations, const gnn_graph *const *graphs, const float *const *d_x,
