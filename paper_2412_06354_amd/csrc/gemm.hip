@@ -29,7 +29,8 @@ namespace {
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int kThreads = 256;
-constexpr int kFastWaves = 12, kFastThreads = 64 * kFastWaves;   // fast kernel: one block fills a compute unit
+constexpr int kFastWavesMax = 8, kFastThreadsMax = 64 * kFastWavesMax;   // fast kernel: one block per compute unit
+constexpr int kLdsBytes = 160 * 1024;
 constexpr int kRowsPerWave = 32;
 constexpr int kRowsPerBlock = 4 * kRowsPerWave;
 constexpr int kSlab = 64;             // k-values per X register buffer / per staged W slab in the fallback
@@ -219,107 +220,296 @@ __device__ __forceinline__ void stage_w(float *ws, const float *__restrict__ w, 
     }
 }
 
-// Fast path: k <= 64*NSUB <= 128, k and n multiples of 4, 16-byte aligned rows (a ragged last row tile
-// is handled by clamped loads and a guarded store, a ragged last column block by zero-filled W and a
-// guarded store).  One block of twelve wavefronts per compute unit (three per SIMD, what the registers allow):
-// it stages its columns of W once -- one copy in LDS serves all twelve -- and then every wavefront walks over
-// 32-row tiles on its own.  Per tile a wavefront issues all of its X loads (no branches), runs the MFMAs and
-// writes the tile with 128-bit stores; the wavefronts of a SIMD overlap one another's load latency with MFMAs
-// (register use is kept low for that: no second X buffer).
-// One wave tile of the fast kernel: 32 rows x NCB column blocks from the X fragments in registers.  They stay
-// there while the column blocks are worked off one after the other (one accumulator set, reused): X is read
-// once for NCB * BN output columns.
-template <int NT, int NSUB, int NCB, int KSTEPS>
-__device__ __forceinline__ void fast_wave_tile(const AFrag (&a)[NSUB], const float *ws, float sc, int64_t row,
-                                               int64_t rows, int n, int n0, int r, int half,
-                                               const float *__restrict__ bias, int relu, float *__restrict__ z)
-{
-    constexpr int BN = NT * 32;
-    constexpr int KP = NSUB * kSlab;
-#pragma unroll
-    for (int cb = 0; cb < NCB; ++cb) {
-        floatx16 acc[NT];
-#pragma unroll
-        for (int t = 0; t < NT; ++t)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[t][v] = 0.0f;
-#pragma unroll
-        for (int sub = 0; sub < NSUB; ++sub)
-            mfma_subslab<NT, KSTEPS>(acc, a[sub], ws + cb * BN * KP, KP, sub * kSlab + 4 * KSTEPS * half, r);
+// Fast path: k <= 128, k and n multiples of 4, 16-byte aligned rows.  One block of up to eight wavefronts per
+// compute unit (two per SIMD) stages its columns of W once -- one copy in LDS serves all of them -- and then every
+// wavefront walks over 32-row tiles on its own, with no barrier after the first.
+//
+// X reaches the matrix cores through a per-wavefront LDS slab that holds one tile (32 rows x 32 KQ k-values, 4 KB
+// per quarter of 32 k-values).  Global loads are coalesced: in each of a quarter's four load instructions eight
+// neighbouring lanes read one row's 128-byte segment, so an instruction touches eight full-width segments instead
+// of 64 different lines (the address unit handles a 128-bit load whose lanes all lie in different rows at about
+// one lane per cycle: the loads of a tile then take microseconds just to issue).  The lanes write their 16-byte
+// chunks to the slab, chunk c of row r of a quarter at slot 8 r + (c ^ (r & 7)), and read them back in the MFMA
+// operand layout (lane = row, two k-halves): both directions touch every bank group once per eight lanes.  LDS
+// operations of one wavefront execute in order, so the slab needs no barrier and no second copy.
+// A whole tile is in flight per wavefront: as soon as a tile's registers have been written to the slab, all loads
+// of the wavefront's next tile are issued back to back (rows that are not a multiple of 128 bytes share lines
+// between quarters; requested together, such a line is fetched once), and they have the whole tile's MFMAs to
+// arrive.  The accumulators of all NT column tiles stay live (k is the outer loop), so X is read once per row
+// whatever the output width.
+//
+// k order: in quarter q, step s (of S) and lane half h, MFMA j consumes k = 32 q + 4 (h S + s) + j from both
+// operands; S = 4 except in the last quarter, where it is just large enough for the k-values that exist (no MFMA
+// work on padding beyond that: k = 100 runs 3 x 16 + 2 k-steps instead of 64).
+constexpr int kSlabFloats = 32 * 32;    // one quarter of a tile
 
-        if (row < rows) {   // false only for lanes past the end in a ragged last tile
-            float *zrow = z + row * n + n0 + cb * BN + 4 * half;
-            const int ncols = n - n0 - cb * BN - 4 * half;   // n % 4 == 0: a group of four columns is inside or outside as a whole
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+struct QuarterRegs {
+    v4f v0, v1, v2, v3;
+};
+
+// The quarters of one tile as named members (indexed at compile time only).
+struct TileRegs {
+    QuarterRegs q0, q1, q2, q3;
+    template <int Q>
+    __device__ __forceinline__ QuarterRegs &quarter()
+    {
+        if constexpr (Q == 0) return q0;
+        else if constexpr (Q == 1) return q1;
+        else if constexpr (Q == 2) return q2;
+        else return q3;
+    }
+};
+
+template <int KQ, int Q = 0>
+__device__ __forceinline__ void load_tile(TileRegs &t, const float *__restrict__ x, int64_t rows, int k, int64_t row0,
+                                          int lane);
+template <int KQ, int Q = 0>
+__device__ __forceinline__ void write_tile(float *slab, TileRegs &t, int lane);
+
+// The four coalesced loads of quarter q of the tile starting at row0: instruction i covers rows 8 i .. 8 i + 7,
+// lane l the chunk l % 8 of row 8 i + l / 8.  Unconditional (clamped) addresses: rows past the end read the last
+// row (never stored), chunks past the end of a row read the row's last chunk (they meet zero rows of W).
+__device__ __forceinline__ void load_quarter(QuarterRegs &t, const float *__restrict__ x, int64_t rows, int k,
+                                             int64_t row0, int q, int lane)
+{
+    const int kb = min(32 * q + 4 * (lane & 7), k - 4);
+    const int64_t r0 = row0 + (lane >> 3);
+    t.v0 = *reinterpret_cast<const v4f *>(x + min(r0, rows - 1) * (int64_t)k + kb);
+    t.v1 = *reinterpret_cast<const v4f *>(x + min(r0 + 8, rows - 1) * (int64_t)k + kb);
+    t.v2 = *reinterpret_cast<const v4f *>(x + min(r0 + 16, rows - 1) * (int64_t)k + kb);
+    t.v3 = *reinterpret_cast<const v4f *>(x + min(r0 + 24, rows - 1) * (int64_t)k + kb);
+}
+
+// Chunk c of row r goes to slot 8 r + (c ^ (r & 7)); the lane's rows are lane / 8 + 8 i, all with the same r & 7.
+__device__ __forceinline__ void write_quarter(float *slab, const QuarterRegs &t, int lane)
+{
+    const int r = lane >> 3;
+    float *p = slab + 4 * (8 * r + ((lane & 7) ^ (r & 7)));
+    *reinterpret_cast<v4f *>(p) = t.v0;
+    *reinterpret_cast<v4f *>(p + 4 * 64) = t.v1;
+    *reinterpret_cast<v4f *>(p + 4 * 128) = t.v2;
+    *reinterpret_cast<v4f *>(p + 4 * 192) = t.v3;
+}
+
+template <int KQ, int Q>
+__device__ __forceinline__ void load_tile(TileRegs &t, const float *__restrict__ x, int64_t rows, int k, int64_t row0,
+                                          int lane)
+{
+    if constexpr (Q < KQ) {
+        load_quarter(t.quarter<Q>(), x, rows, k, row0, Q, lane);
+        load_tile<KQ, Q + 1>(t, x, rows, k, row0, lane);
+    }
+}
+
+template <int KQ, int Q>
+__device__ __forceinline__ void write_tile(float *slab, TileRegs &t, int lane)
+{
+    if constexpr (Q < KQ) {
+        write_quarter(slab + Q * kSlabFloats, t.quarter<Q>(), lane);
+        write_tile<KQ, Q + 1>(slab, t, lane);
+    }
+}
+
+// The operands of one step of four k-values for all NT column tiles: X chunk `chunk` of the lane's row from the
+// slab, W[32 q + 4 chunk ..][column tiles] from the staged block.
+template <int NT>
+struct StepOperands {
+    float4 a;
+    float4 b[NT];
+    __device__ __forceinline__ void load(const float *slab, const float *ws, int kp, int q, int chunk, int r)
+    {
+        a = *reinterpret_cast<const float4 *>(slab + 4 * (8 * r + (chunk ^ (r & 7))));
+        load_b<NT>(b, ws, kp, 32 * q + 4 * chunk, r);
+    }
+};
+
+// W fragment as the MFMA's first operand, X fragment as its second, so that the accumulator holds the tile
+// transposed (see the store).
+template <int NT>
+__device__ __forceinline__ void step_mfmas(floatx16 (&acc)[NT], const StepOperands<NT> &o)
+{
+    const float av[4] = {o.a.x, o.a.y, o.a.z, o.a.w};
+    mfma_step<NT>(acc, av, o.b);
+}
+
+// The four steps of a full quarter, operands read from LDS one step ahead of the MFMAs that use them (the
+// scheduling barriers keep the compiler from hoisting all reads to the front, which would cost registers).
+template <int NT>
+__device__ __forceinline__ void full_quarter(floatx16 (&acc)[NT], const float *slab, const float *ws, int kp, int q,
+                                             int half, int r)
+{
+    StepOperands<NT> o0, o1;
+    o0.load(slab, ws, kp, q, 4 * half, r);
+    o1.load(slab, ws, kp, q, 4 * half + 1, r);
+    step_mfmas<NT>(acc, o0);
+    __builtin_amdgcn_sched_barrier(0);
+    o0.load(slab, ws, kp, q, 4 * half + 2, r);
+    step_mfmas<NT>(acc, o1);
+    __builtin_amdgcn_sched_barrier(0);
+    o1.load(slab, ws, kp, q, 4 * half + 3, r);
+    step_mfmas<NT>(acc, o0);
+    __builtin_amdgcn_sched_barrier(0);
+    step_mfmas<NT>(acc, o1);
+}
+
+// A finished tile on its way to memory.  The accumulator holds it transposed: register v of lane l is
+// Z[row0 + l % 32][8 (v / 4) + 4 (l / 32) + v % 4] of its column tile, i.e. a lane owns 16-byte pieces of one row that
+// lie 32 bytes apart -- stored like that, every store instruction would touch 32 different lines with 32 bytes
+// each.  The tile goes through the wavefront's LDS slab instead, one 32 x 32 column tile at a time, and comes back
+// in the layout of the quarter loads (eight neighbouring lanes = one row's 128 bytes): a store instruction then
+// writes eight full 128-byte segments.
+template <int NT>
+struct OutRegs {
+    v4f v[NT][4];   // [column tile][i]: columns 4 (lane % 8) .. + 3 of row lane / 8 + 8 i
+};
+
+template <int NT>
+__device__ __forceinline__ void stage_tile(OutRegs<NT> &o, const floatx16 (&acc)[NT], float *slab, int lane)
+{
+    const int r = lane & 31, half = lane >> 5;
+    const int rr = lane >> 3;
+    const float *rp = slab + 4 * (8 * rr + ((lane & 7) ^ (rr & 7)));
 #pragma unroll
-            for (int t = 0; t < NT; ++t)
+    for (int tt = 0; tt < NT; ++tt) {
 #pragma unroll
-                for (int g = 0; g < 4; ++g)
-                    if (t * 32 + 8 * g < ncols) {
-                        float4 o = make_float4(acc[t][4 * g] * sc, acc[t][4 * g + 1] * sc, acc[t][4 * g + 2] * sc,
-                                               acc[t][4 * g + 3] * sc);
-                        if (bias) {   // n % 4 == 0 and the group lies inside: four bias values are there
-                            const float *bp = bias + n0 + cb * BN + 4 * half + t * 32 + 8 * g;
-                            o.x += bp[0]; o.y += bp[1]; o.z += bp[2]; o.w += bp[3];
-                        }
-                        if (relu) o = make_float4(fmaxf(o.x, 0.0f), fmaxf(o.y, 0.0f), fmaxf(o.z, 0.0f), fmaxf(o.w, 0.0f));
-                        *reinterpret_cast<float4 *>(zrow + t * 32 + 8 * g) = o;
-                    }
+        for (int g = 0; g < 4; ++g) {
+            const v4f t = {acc[tt][4 * g], acc[tt][4 * g + 1], acc[tt][4 * g + 2], acc[tt][4 * g + 3]};
+            *reinterpret_cast<v4f *>(slab + 4 * (8 * r + ((2 * g + half) ^ (r & 7)))) = t;
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) o.v[tt][i] = *reinterpret_cast<const v4f *>(rp + 4 * 64 * i);
+    }
+}
+
+// Epilogue (row scale, bias, relu, in that order) and the stores of a staged tile starting at row0.
+// The row factors of the four rows a lane stores in a tile (clamped rows past the end: never stored).
+struct RowScales {
+    float s[4];
+};
+
+__device__ __forceinline__ void load_row_scales(RowScales &rs, const float *__restrict__ row_scale, int64_t row0,
+                                                int64_t rows, int lane)
+{
+#pragma unroll
+    for (int i = 0; i < 4; ++i) rs.s[i] = row_scale[min(row0 + (lane >> 3) + 8 * i, rows - 1)];
+}
+
+template <int NT, bool SCALED>
+__device__ __forceinline__ void store_staged_tile(const OutRegs<NT> &o, const RowScales &rs, int64_t row0, int64_t rows,
+                                                  int n, int n0, int lane, const float *__restrict__ bias, int relu,
+                                                  float *__restrict__ z)
+{
+    const int c4 = 4 * (lane & 7);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int64_t row = row0 + (lane >> 3) + 8 * i;
+        if (row >= rows) continue;   // rows past the end in a ragged last tile
+        float sc = 1.0f;
+        if constexpr (SCALED) sc = rs.s[i];
+#pragma unroll
+        for (int tt = 0; tt < NT; ++tt) {
+            const int col = n0 + 32 * tt + c4;
+            if (col >= n) continue;   // n % 4 == 0: a group of four columns is inside or outside as a whole
+            v4f v = o.v[tt][i] * sc;
+            if (bias) {
+                const v4f b = *reinterpret_cast<const v4f *>(bias + col);
+                v += b;
+            }
+            if (relu) v = {fmaxf(v.x, 0.0f), fmaxf(v.y, 0.0f), fmaxf(v.z, 0.0f), fmaxf(v.w, 0.0f)};
+            *reinterpret_cast<v4f *>(z + row * n + col) = v;
         }
     }
 }
 
-template <int NT, int NSUB, int NCB, bool SCALED, int KSTEPS>
-__global__ __launch_bounds__(kFastThreads) void xw_fast_kernel(const float *__restrict__ x, int k,
-                                                               const float *__restrict__ w, int n,
-                                                               const float *__restrict__ row_scale,
-                                                               const float *__restrict__ bias, int relu,
-                                                               float *__restrict__ z, int64_t rows)
+// Wavefronts per block: as many as the LDS holds slabs for next to the staged W, at most eight.
+template <int NT, int KQ>
+constexpr int fast_waves()
+{
+    const int fit = (kLdsBytes - NT * 32 * KQ * 32 * 4) / (KQ * kSlabFloats * 4);
+    return fit < kFastWavesMax ? fit : kFastWavesMax;
+}
+
+template <int NT, int KQ, bool SCALED>
+__global__ __launch_bounds__(kFastThreadsMax) void xw_fast_kernel(const float *__restrict__ x, int k,
+                                                                  const float *__restrict__ w, int n,
+                                                                  const float *__restrict__ row_scale,
+                                                                  const float *__restrict__ bias, int relu,
+                                                                  float *__restrict__ z, int64_t rows)
 {
     constexpr int BN = NT * 32;
-    constexpr int KP = NSUB * kSlab;
-    // W is staged by the first kStageThreads threads: the number of 16-byte groups (a power of two) is a
-    // multiple of it, so every staging thread makes the same number of passes and all loads go out at once.
-    constexpr int kStageThreads = (KP * BN * NCB / 4) < 512 ? (KP * BN * NCB / 4) : 512;
-    static_assert((KP * BN * NCB / 4) % kStageThreads == 0 && kStageThreads <= kFastThreads, "staging passes");
-    extern __shared__ __align__(16) float ws[];   // [NCB * BN][KP], swizzled
+    constexpr int KP = KQ * 32;
+    constexpr int WAVES = fast_waves<NT, KQ>();
+    constexpr int THREADS = 64 * WAVES;
+    // W is staged by the first kStageThreads threads (whole wavefronts), all of a thread's loads going out at once.
+    constexpr int kStageThreads = (KP * BN / 4) < THREADS ? (KP * BN / 4) : THREADS;
+    static_assert(kStageThreads % 64 == 0 && WAVES >= 2, "staging threads");
+    extern __shared__ __align__(16) float lds[];   // [BN][KP] of W, swizzled; then one slab per wavefront
+    float *ws = lds;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    float *slab = lds + BN * KP + wave * (KQ * kSlabFloats);
     const int r = lane & 31, half = lane >> 5;
-    const int n0 = blockIdx.y * (BN * NCB);
-    const int64_t num_wave_tiles = (rows + kRowsPerWave - 1) / kRowsPerWave;
+    const int n0 = blockIdx.y * BN;
+    const int64_t num_tiles = (rows + kRowsPerWave - 1) / kRowsPerWave;
+    // steps of the last quarter: its k-values, in chunks of four, split over the two lane halves
+    const int last_chunks = (k - 32 * (KQ - 1) + 3) / 4;
+    const int last_steps = (last_chunks + 1) / 2;
 
-    // Wave tile numbers go round the blocks first, then round the wavefronts of a block, so that a last, partly
+    // Tile numbers go round the blocks first, then round the wavefronts of a block, so that a last, partly
     // filled round puts one tile on as many compute units as possible.
-    const int64_t wt_stride = (int64_t)gridDim.x * kFastWaves;
-    int64_t wt = (int64_t)wave * gridDim.x + blockIdx.x;
-    int64_t row = wt * kRowsPerWave + r;
+    const int64_t stride = (int64_t)gridDim.x * WAVES;
+    int64_t tile = (int64_t)wave * gridDim.x + blockIdx.x;
 
-    // W's loads are issued first, then the first tile's X loads (clamped addresses: safe also for a wavefront
-    // without a tile), which stay in flight while W is written to LDS: loads return in order, so waiting for W
-    // does not wait for X.
-    AFrag a[NSUB];
-    float sc = 1.0f;
+    // W's loads are issued first, then the first tile's (clamped addresses: safe also for a wavefront without a
+    // tile), which stay in flight while W is written to LDS.
+    TileRegs t;
+    RowScales rs_next{}, rs_this{}, rs_prev{};   // row factors travel with their tile: loaded with it, used at its store
     {
-        WStage<BN * NCB, KP, kStageThreads> st;
+        WStage<BN, KP, kStageThreads> st;
         const bool stager = threadIdx.x < kStageThreads;   // whole wavefronts
         if (stager) st.load(w, k, n, 0, n0);
         __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int sub = 0; sub < NSUB; ++sub) load_a<true, KSTEPS>(a[sub], x, rows, k, row, sub * kSlab, half);
-        if constexpr (SCALED) sc = row_scale[min(row, rows - 1)];
+        load_tile<KQ>(t, x, rows, k, tile * kRowsPerWave, lane);
+        if constexpr (SCALED) load_row_scales(rs_next, row_scale, tile * kRowsPerWave, rows, lane);
         __builtin_amdgcn_sched_barrier(0);
         if (stager) st.store(ws, k, n, 0, n0);
     }
     __syncthreads();
 
-    // From here on the wavefronts are independent.  The first tile (already loaded) is peeled off the loop.
-    if (wt < num_wave_tiles) fast_wave_tile<NT, NSUB, NCB, KSTEPS>(a, ws, sc, row, rows, n, n0, r, half, bias, relu, z);
-    for (wt += wt_stride; wt < num_wave_tiles; wt += wt_stride) {
-        row = wt * kRowsPerWave + r;
+    // The stores of a tile are issued inside the next tile, after its slab writes: the memory counter is waited on
+    // in order, so a wait for loads that were issued before the stores would otherwise wait for the stores as well.
+    floatx16 acc[NT];
+    OutRegs<NT> out;
+    int64_t prev_row0 = -1;   // first row of the tile whose staged results `out` still holds
+    for (; tile < num_tiles; tile += stride) {
+        __builtin_amdgcn_sched_barrier(0);
+        write_tile<KQ>(slab, t, lane);
+        __builtin_amdgcn_sched_barrier(0);   // the next tile is loaded into the same registers: no copies
+        if (prev_row0 >= 0) store_staged_tile<NT, SCALED>(out, rs_prev, prev_row0, rows, n, n0, lane, bias, relu, z);
 #pragma unroll
-        for (int sub = 0; sub < NSUB; ++sub) load_a<true, KSTEPS>(a[sub], x, rows, k, row, sub * kSlab, half);
-        if constexpr (SCALED) sc = row_scale[min(row, rows - 1)];
-        fast_wave_tile<NT, NSUB, NCB, KSTEPS>(a, ws, sc, row, rows, n, n0, r, half, bias, relu, z);
+        for (int tt = 0; tt < NT; ++tt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[tt][v] = 0.0f;
+        __builtin_amdgcn_sched_barrier(0);
+        rs_this = rs_next;   // arrived with this tile's X (waited for by the slab writes above)
+        load_tile<KQ>(t, x, rows, k, (tile + stride) * kRowsPerWave, lane);
+        if constexpr (SCALED) load_row_scales(rs_next, row_scale, (tile + stride) * kRowsPerWave, rows, lane);
+        __builtin_amdgcn_sched_barrier(0);   // the loads go out here, not where the compiler would sink them to
+#pragma unroll
+        for (int q = 0; q + 1 < KQ; ++q) full_quarter<NT>(acc, slab + q * kSlabFloats, ws, KP, q, half, r);
+        for (int s = 0; s < last_steps; ++s) {
+            StepOperands<NT> o;
+            o.load(slab + (KQ - 1) * kSlabFloats, ws, KP, KQ - 1, last_steps * half + s, r);
+            step_mfmas<NT>(acc, o);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        stage_tile<NT>(out, acc, slab, lane);   // LDS operations of a wavefront run in order: the slab's X data has been read
+        rs_prev = rs_this;
+        prev_row0 = tile * kRowsPerWave;
     }
+    __builtin_amdgcn_sched_barrier(0);
+    if (prev_row0 >= 0) store_staged_tile<NT, SCALED>(out, rs_prev, prev_row0, rows, n, n0, lane, bias, relu, z);
 }
 
 template <int NT, bool VEC4>
@@ -383,37 +573,58 @@ gnn_status launch_general(const float *d_x, int64_t rows, int k, const float *d_
     return GNN_OK;
 }
 
-template <int NT, int NSUB, int NCB, int KSTEPS = 8>
+template <int NT, int KQ>
 gnn_status launch_fast(const float *d_x, int64_t rows, int k, const float *d_w, int n, const XwEpilogue &ep,
                        float *d_z, hipStream_t s)
 {
-    constexpr int BN = NT * 32 * NCB;   // output columns per block
-    const int64_t wave_tiles = gnn_div_up(rows, kRowsPerWave);
-    const size_t lds = (size_t)NSUB * kSlab * BN * sizeof(float);
+    constexpr int BN = NT * 32;   // output columns per block
+    constexpr int WAVES = fast_waves<NT, KQ>();
+    const int64_t tiles = gnn_div_up(rows, kRowsPerWave);
+    const size_t lds = ((size_t)KQ * 32 * BN + (size_t)WAVES * KQ * kSlabFloats) * sizeof(float);
     // One resident block per compute unit (fewer where there are several column blocks or few rows: then at
-    // least one wave tile per block, so that small inputs still spread over the chip).
+    // least one tile per block, so that small inputs still spread over the chip).
     const int col_blocks = (int)gnn_div_up(n, BN);
-    const int64_t blocks = std::max<int64_t>(1, std::min<int64_t>(device_cu_count() / col_blocks, wave_tiles));
+    const int64_t blocks = std::max<int64_t>(1, std::min<int64_t>(device_cu_count() / col_blocks, tiles));
     const dim3 grid((unsigned)blocks, (unsigned)col_blocks);
     if (ep.row_scale)
-        hipLaunchKernelGGL((xw_fast_kernel<NT, NSUB, NCB, true, KSTEPS>), grid, dim3(kFastThreads), lds, s, d_x, k, d_w, n,
+        hipLaunchKernelGGL((xw_fast_kernel<NT, KQ, true>), grid, dim3(64 * WAVES), lds, s, d_x, k, d_w, n,
                            ep.row_scale, ep.bias, ep.relu, d_z, rows);
     else
-        hipLaunchKernelGGL((xw_fast_kernel<NT, NSUB, NCB, false, KSTEPS>), grid, dim3(kFastThreads), lds, s, d_x, k, d_w, n,
+        hipLaunchKernelGGL((xw_fast_kernel<NT, KQ, false>), grid, dim3(64 * WAVES), lds, s, d_x, k, d_w, n,
                            ep.row_scale, ep.bias, ep.relu, d_z, rows);
     GNN_LAUNCH_CHECK();
     return GNN_OK;
 }
 
-template <int NT, int NCB>
+template <int NT>
 gnn_status launch_fast_for_k(const float *d_x, int64_t rows, int k, const float *d_w, int n, const XwEpilogue &ep,
                              float *d_z, hipStream_t s)
 {
-    // up to 64 k-values: one sub-slab of 16, 32 or 64 (two, four or eight steps); up to 128: two full sub-slabs
-    if (k <= 16) return launch_fast<NT, 1, NCB, 2>(d_x, rows, k, d_w, n, ep, d_z, s);
-    if (k <= 32) return launch_fast<NT, 1, NCB, 4>(d_x, rows, k, d_w, n, ep, d_z, s);
-    if (k <= kSlab) return launch_fast<NT, 1, NCB, 8>(d_x, rows, k, d_w, n, ep, d_z, s);
-    return launch_fast<NT, 2, NCB, 8>(d_x, rows, k, d_w, n, ep, d_z, s);
+    if (k <= 32) return launch_fast<NT, 1>(d_x, rows, k, d_w, n, ep, d_z, s);
+    if (k <= 64) return launch_fast<NT, 2>(d_x, rows, k, d_w, n, ep, d_z, s);
+    if (k <= 96) return launch_fast<NT, 3>(d_x, rows, k, d_w, n, ep, d_z, s);
+    return launch_fast<NT, 4>(d_x, rows, k, d_w, n, ep, d_z, s);
+}
+
+// Column tiles per wavefront (32 columns each: 1, 2 or 4).  Wide tiles read X once for all columns; narrow ones
+// cut the work into more pieces, which matters when there are only a few tiles per SIMD: the cost of a choice is
+// the largest number of 32-column tile products one SIMD gets, ties going to the wider tile.
+int choose_column_tiles(int64_t rows, int n)
+{
+    const int64_t tiles = gnn_div_up(rows, kRowsPerWave);
+    const int64_t simds = 4 * (int64_t)device_cu_count();
+    const int widest = n <= 32 ? 1 : (n <= 64 ? 2 : 4);
+    int best = widest;
+    int64_t best_cost = 0;
+    for (int nt = widest; nt >= 1; nt >>= 1) {
+        const int64_t units = tiles * gnn_div_up(n, 32 * nt);
+        const int64_t cost = gnn_div_up(units, simds) * nt;
+        if (nt == widest || cost < best_cost) {
+            best = nt;
+            best_cost = cost;
+        }
+    }
+    return best;
 }
 
 }  // namespace
@@ -431,10 +642,11 @@ gnn_status gnn_launch_xw(const float *d_x, int64_t rows, int32_t k, const float 
     const bool x_vec4 = (k % 4 == 0) && ((reinterpret_cast<uintptr_t>(d_x) & 15u) == 0);
     const bool w_vec4 = (n % 4 == 0) && ((reinterpret_cast<uintptr_t>(d_w) & 15u) == 0);
     if (x_vec4 && w_vec4 && k <= 2 * kSlab) {   // w_vec4 implies n % 4 == 0
-        // column tiles of 32 (n <= 32) or 64, two of them per block where the matrix is wider than one
-        if (n <= 32) return launch_fast_for_k<1, 1>(d_x, rows, k, d_w, n, ep, d_z, s);
-        if (n <= 64) return launch_fast_for_k<2, 1>(d_x, rows, k, d_w, n, ep, d_z, s);
-        return launch_fast_for_k<2, 2>(d_x, rows, k, d_w, n, ep, d_z, s);
+        switch (choose_column_tiles(rows, n)) {
+        case 1: return launch_fast_for_k<1>(d_x, rows, k, d_w, n, ep, d_z, s);
+        case 2: return launch_fast_for_k<2>(d_x, rows, k, d_w, n, ep, d_z, s);
+        default: return launch_fast_for_k<4>(d_x, rows, k, d_w, n, ep, d_z, s);
+        }
     }
     // General kernel.  Column tile: 64 or 32 if it divides n, else 128 wide when n is large enough, else the
     // smallest multiple of 32 covering n.

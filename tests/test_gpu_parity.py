@@ -614,19 +614,23 @@ def test_propagate_argument_errors(case, gnn):
 
 # ----------------------------------------------------------------------------- layers
 
-def test_dense_xw_matches_numpy(gnn):
+def test_dense_xw_matches_the_oracle(gnn):
+    """X W on the matrix cores against the oracle's double-precision triple loop (and its |X||W| magnitudes):
+    every number of 32-wide k slices (1 .. 4, odd and even), partial last slices, 1 / 2 / 4 column tiles, ragged
+    column counts, several column blocks, several tiles per wavefront, ragged last row tile; then the shapes that
+    take the general kernel (k > 128 or not a multiple of 4)."""
     for rows, k, n in ((1000, 128, 128), (777, 100, 64), (130, 37, 50), (5, 8, 200), (4096, 16, 64),
                        (70_000, 128, 128), (500, 300, 128), (300, 520, 40), (900, 200, 64), (257, 64, 33),
                        (3000, 64, 100), (1500, 128, 36), (640, 100, 20), (333, 12, 4), (6000, 32, 300),
-                       (150_000, 64, 128)):   # the last two: three column-block pairs; several tiles per wavefront
+                       (150_000, 64, 128), (200_000, 96, 64), (140_001, 24, 32), (70_000, 72, 200), (33, 4, 4),
+                       (90_000, 68, 36)):
         x = synth.normal_f32(rows + k, 2, rows * k).reshape(rows, k)
         w = synth.glorot_uniform(n, 4, k, n, (k, n))
         sc = synth.uniform_f32(3, 5, rows, 0.5, 2.0)
-        ref = x.astype(np.float64) @ w.astype(np.float64)
-        sabs = np.abs(x).astype(np.float64) @ np.abs(w).astype(np.float64)
+        ref, sabs = oracle.dense(x, w, with_sabs=True)
         assert_close_sabs(host(gnn.dense_xw(dev(x), dev(w))), ref, sabs, what=f"xw {rows}x{k}x{n}")
-        assert_close_sabs(host(gnn.dense_xw(dev(x), dev(w), dev(sc))), ref * sc[:, None], sabs * sc[:, None],
-                          what=f"xw scaled {rows}x{k}x{n}")
+        assert_close_sabs(host(gnn.dense_xw(dev(x), dev(w), dev(sc))), ref.astype(np.float64) * sc[:, None],
+                          sabs * sc[:, None], what=f"xw scaled {rows}x{k}x{n}")
 
 
 @pytest.mark.parametrize("loops", [True, False])
