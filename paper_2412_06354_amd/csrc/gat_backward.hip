@@ -34,6 +34,7 @@ struct GatBwdParams {
     float *slot_vec, *slot_s;            // [slots x HC] each
     const int32_t *small_rows, *item_row, *item_start, *item_slot, *split_rows, *split_slot0;
     int32_t n_small, n_items, n_split, chunk, HC, H, ch, lh, item_blocks;
+    int32_t lh_pow2;   // lh is a power of two: a head's lanes are combined by an xor tree, else by a loop over them
     float slope;
 };
 
@@ -64,6 +65,7 @@ struct Lane {
     float own_sl;      // by source
     float as[VEC];     // by destination, recomputing: this lane's slice of a_src
     float4 own_rec;    // by destination
+    int head_first;    // first lane of this lane's head (heads whose lane count is no power of two)
     float acc_s;
     float acc_v[VEC];  // by source
 };
@@ -75,6 +77,7 @@ __device__ __forceinline__ void lane_init(Lane<VEC> &ln, const GatBwdParams &p, 
     for (int c = 0; c < VEC; ++c) ln.as[c] = (RECOMP && colok) ? p.a_src[col + c] : 0.0f;
     ln.own_sl = 0.0f;
     ln.own_rec = make_float4(0.f, 0.f, 0.f, 0.f);
+    ln.head_first = max(0, (int)(threadIdx.x & 63) - (col % p.ch) / VEC);
     ln.acc_s = 0.0f;
 #pragma unroll
     for (int c = 0; c < VEC; ++c) { ln.own[c] = 0.0f; ln.acc_v[c] = 0.0f; }
@@ -97,7 +100,13 @@ __device__ __forceinline__ void lane_edge(Lane<VEC> &ln, const GatBwdParams &p, 
     float dot = 0.0f;
 #pragma unroll
     for (int c = 0; c < VEC; ++c) dot = fmaf(ln.own[c], nv[c], dot);
-    for (int off = 1; off < p.lh; off <<= 1) dot += __shfl_xor(dot, off, 64);   // over the head's lanes
+    if (p.lh_pow2) {   // over the head's lanes
+        for (int off = 1; off < p.lh; off <<= 1) dot += __shfl_xor(dot, off, 64);
+    } else {           // any lane count: every lane of the head adds the head's partial sums in lane order
+        float tot = 0.0f;
+        for (int t = 0; t < p.lh; ++t) tot += __shfl(dot, min(ln.head_first + t, 63), 64);
+        dot = tot;
+    }
     if constexpr (RECOMP) {
         nsl = 0.0f;
 #pragma unroll
@@ -394,7 +403,7 @@ gnn_status launch_pass(const GatBwdParams &p, hipStream_t stream)
         // by destination, heads of at most 16 channels in 128-bit groups: sl[j] is recomputed from the gathered
         // slice in node_scores_kernel's tree order (wider heads are summed in another order there: gathered)
         constexpr bool kCanRecompute = !BY_SRC && VEC == 4;
-        if (kCanRecompute && p.lh <= 4)
+        if (kCanRecompute && p.lh <= 4 && p.lh_pow2)
             hipLaunchKernelGGL((gat_backward_kernel<LPR, VEC, BY_SRC, kCanRecompute>), dim3((unsigned)blocks),
                                dim3(kThreads), 0, stream, p);
         else
@@ -489,7 +498,9 @@ gnn_status gnn_gatconv_backward(const gnn_graph *g, const gnn_graph *g_by_source
     const int HC = heads * ch;
     const bool vec4 = (ch % 4 == 0) && ((reinterpret_cast<uintptr_t>(d_grad_out) & 15u) == 0);
     const int lh = vec4 ? ch / 4 : ch;   // lanes that share a head
-    if (!is_pow2(lh) || lh > 64) return GNN_ERR_UNSUPPORTED;
+    // a head's lanes must lie in one wavefront pass over the row: always so when their number is a power of two (at
+    // most 64), else only when the whole row fits one pass
+    if (lh > 64 || (!is_pow2(lh) && heads * lh > 64)) return GNN_ERR_UNSUPPORTED;
     const Layout l = layout(N, f_in, heads, ch);
     if (workspace_bytes < l.total) return GNN_ERR_BAD_SIZE;
     if (reinterpret_cast<uintptr_t>(d_workspace) & 255u) return GNN_ERR_BAD_SIZE;
@@ -511,7 +522,7 @@ gnn_status gnn_gatconv_backward(const gnn_graph *g, const gnn_graph *g_by_source
 
     GatBwdParams p{};
     p.sl = sl; p.a_src = d_a_src; p.rec = rec;
-    p.HC = HC; p.H = heads; p.ch = ch; p.lh = lh; p.slope = negative_slope;
+    p.HC = HC; p.H = heads; p.ch = ch; p.lh = lh; p.lh_pow2 = is_pow2(lh) ? 1 : 0; p.slope = negative_slope;
     // by destination: dsr
     p.own_vec = d_grad_out; p.nbr_vec = h; p.out_vec = nullptr; p.out_s = dsr;
     GNN_TRY(run_pass<false>(g, p, vec4, s));
