@@ -239,8 +239,8 @@ gnn_status gnn_propagate(const gnn_graph *g, const float *d_x, int32_t feat_dim,
  * device image instead of memory owned by the graph.  The call makes no allocation of any kind (its first call on
  * a device only asks the runtime for the address of that device's copy of the array).
  * Limit: (number of partial-row slots of the graph) * feat_dim <= 4 194 304 floats; beyond it the call returns
- * GNN_ERR_SCRATCH_LIMIT and launches nothing (the headline graph, 1 M nodes / 20 M edges, needs 0.9 M floats at
- * feat_dim = 64).  All calls on one GPU share that GPU's array, whatever the graph: calls that overlap in time on
+ * GNN_ERR_SCRATCH_LIMIT and launches nothing (the headline graph, 1 M nodes / 20 M edges, has 9 473 slots: 0.6 M
+ * floats at feat_dim = 64).  All calls on one GPU share that GPU's array, whatever the graph: calls that overlap in time on
  * one GPU race, so keep them on one stream or order them with events.  The array keeps the last call's partial
  * rows; nothing in it has to be cleared, since a launch only reads partial rows it has written itself.
  */
