@@ -42,8 +42,8 @@ def test_binding_signatures_cover_the_header():
 
 def test_status_strings(handle):
     handle.gnn_status_string.restype = ctypes.c_char_p
-    seen = {handle.gnn_status_string(c) for c in range(9)}
-    assert len(seen) == 9 and handle.gnn_status_string(0) == b"ok"
+    seen = {handle.gnn_status_string(c) for c in range(10)}
+    assert len(seen) == 10 and handle.gnn_status_string(0) == b"ok"
     assert handle.gnn_status_string(99) == b"unknown status"
 
 
