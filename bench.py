@@ -197,6 +197,20 @@ def run_propagate(args, torch, gnn, synth):
                                                 "edge_feature_per_s": e * f / (t * 1e-3)}
             del xh
         extra["edge_data_to_csr_ms"] = time_calls(torch, lambda: gnn.edge_data_to_csr(g, ew), k, 2)
+        # one float per edge through the two-pass route (gnn_graph_build_edge_route) instead of through perm
+        csr_to_coo_direct = time_calls(torch, lambda: gnn.edge_data_to_coo(g, e_csr), k, 2)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        g.build_edge_route()
+        torch.cuda.synchronize()
+        route_build_ms = (time.perf_counter() - t0) * 1e3
+        t_to_csr = time_calls(torch, lambda: gnn.edge_data_to_csr(g, ew), k, 2)
+        t_to_coo = time_calls(torch, lambda: gnn.edge_data_to_coo(g, e_csr), k, 2)
+        t = time_calls(torch, lambda: gnn.propagate(g, x, ew, 1, 0, e_order=gnn.EDGE_ORDER_COO, out=out), k, 3)
+        extra["edge_route"] = {"build_ms": route_build_ms, "edge_data_to_csr_ms": t_to_csr,
+                               "edge_data_to_coo_ms": t_to_coo, "edge_data_to_coo_direct_ms": csr_to_coo_direct,
+                               "bytes_moved_per_direction": 24 * e, "GBs": 24 * e / (t_to_csr * 1e-3) / 1e9,
+                               "e_mul_xj_sum_coo_order": {"ms": t, "GBs_alg": b_alg_propagate(n, e, f, 1) / (t * 1e-3) / 1e9}}
         gnn.build_csr(src, dst, n).close()      # steady state of a build-per-batch loop: arrays are reused from here on
         t0 = time.perf_counter()
         for _ in range(5):
@@ -691,6 +705,17 @@ def run_backward(args, torch, gnn, synth):
     line["roofline"] = hbm_roofline(bytes_x / (ms_x * 1e-3) / 1e9, "propagate_kernel<16,4,e_mul_xj,sum> on the by-source graph")
     line["extra"] = {"grad_x_ms": ms_x, "grad_e_ms": ms_e, "grad_e_GBs": bytes_e / (ms_e * 1e-3) / 1e9,
                      "B_alg_grad_x_bytes": bytes_x, "B_alg_grad_e_bytes": bytes_e}
+    # the same calls when both graphs carry a route for one float per edge: the weights reach the by-source pass
+    # and the edge gradients leave the by-destination pass in streams instead of through perm
+    g.build_edge_route()
+    gt.build_edge_route()
+    r_ms = time_calls(torch, lambda: gnn.propagate_backward(g, gt, x, gout, ew, gnn.MSG_E_MUL_XJ, gnn.AGGR_SUM), steps, 3)
+    r_x = time_calls(torch, lambda: gnn.propagate_backward(g, gt, x, gout, ew, gnn.MSG_E_MUL_XJ, gnn.AGGR_SUM,
+                                                           want_grad_e=False), steps, 3)
+    r_e = time_calls(torch, lambda: gnn.propagate_backward(g, gt, x, gout, ew, gnn.MSG_E_MUL_XJ, gnn.AGGR_SUM,
+                                                           want_grad_x=False), steps, 3)
+    line["extra"]["with_edge_route"] = {"ms": r_ms, "grad_x_ms": r_x, "grad_e_ms": r_e,
+                                        "GBs_alg": (bytes_x + bytes_e) / (r_ms * 1e-3) / 1e9}
     if not args.no_cpu_baseline:
         import oracle
         es = min(args.cpu_sample_edges // 2, e)

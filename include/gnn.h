@@ -214,6 +214,30 @@ gnn_status gnn_edge_data_to_csr(const gnn_graph *g, const float *d_e, int32_t e_
                                 float *d_e_csr, void *stream);
 
 /*
+ * The way back (gradients with respect to per-edge data come out of the kernels in CSR order, section 3,
+ * "Message Passing"):  d_e[perm[p], :] = d_e_csr[p, :],  both [E x e_dim] float.  Only enqueues kernels.
+ */
+gnn_status gnn_edge_data_to_coo(const gnn_graph *g, const float *d_e_csr, int32_t e_dim,
+                                float *d_e, void *stream);
+
+/*
+ * Optional set-up call for graphs whose per-edge scalars change every step (learned or recomputed edge weights of
+ * section 3's e_mul_xj message): moving ONE float per edge between the caller's order and CSR order by perm is a
+ * random 4-byte access per edge, and each costs a whole 128-byte memory line.  This call splits the permutation,
+ * once, into two passes that only move data inside 16 384-entry ranges held in on-chip memory or in contiguous
+ * runs; afterwards gnn_edge_data_to_csr / gnn_edge_data_to_coo with e_dim == 1, gnn_propagate and
+ * gnn_propagate_backward with one weight per edge in COO order, and the edge gradient of gnn_propagate_backward
+ * take the route (16-byte aligned buffers; anything else keeps the direct path).  Results are bit-identical: the
+ * route only moves values.
+ * Cost: 16 bytes of device memory per edge, owned by the graph (three index arrays, an intermediate buffer and a
+ * CSR-ordered staging buffer for the compute calls; like the scratch memory it is shared by all calls on the graph,
+ * so those must not overlap in time), and two sorting kernels of about three times a build's duration.
+ * Allocates, enqueues on `stream` and waits for it; a second call is a no-op.
+ * Errors: GNN_ERR_NULL, GNN_ERR_ALLOC, GNN_ERR_DEVICE.
+ */
+gnn_status gnn_graph_build_edge_route(gnn_graph *g, void *stream);
+
+/*
  * propagate (paper section 3, "Message Passing"): for every node i
  *   out[i,:] = AGGR over edges k with dst[k] = i of  msg(x[dst[k],:], x[src[k],:], e[k,:])
  * msg  = COPY_XJ: x_j;   E_MUL_XJ: float(e * x_j) with e_dim == 1 (one weight per edge,

@@ -41,6 +41,8 @@ SIGNATURES = {
     "gnn_graph_work_sizes": (None, [_vp, _c.POINTER(_i32), _c.POINTER(_i32), _c.POINTER(_i32)]),
     "gnn_graph_work_lists": (None, [_vp] + [_c.POINTER(_vp)] * 6),
     "gnn_edge_data_to_csr": (_c.c_int, [_vp, _vp, _i32, _vp, _vp]),
+    "gnn_edge_data_to_coo": (_c.c_int, [_vp, _vp, _i32, _vp, _vp]),
+    "gnn_graph_build_edge_route": (_c.c_int, [_vp, _vp]),
     "gnn_propagate": (_c.c_int, [_vp, _vp, _i32, _vp, _i32, _c.c_int, _c.c_int, _c.c_int, _vp, _vp]),
     "gnn_propagate_noalloc": (_c.c_int, [_vp, _vp, _i32, _vp, _i32, _c.c_int, _c.c_int, _c.c_int, _vp, _vp]),
     "gnn_build_csr_bipartite": (_c.c_int, [_vp, _vp, _i64, _i32, _i32, _vp, _c.POINTER(_vp)]),
@@ -158,6 +160,10 @@ class Graph:
         """gnn_graph_reserve: sizes the handle's scratch memory (may allocate and synchronise the device)."""
         _check(lib().gnn_graph_reserve(self._h, int(max_feat_dim), int(max_heads)), "gnn_graph_reserve")
         self._reserved_heads = max(self._reserved_heads, int(max_heads))
+
+    def build_edge_route(self) -> None:
+        """gnn_graph_build_edge_route: one float per edge then moves between COO and CSR order in streams."""
+        _check(lib().gnn_graph_build_edge_route(self._h, _stream()), "gnn_graph_build_edge_route")
 
     def _view(self, ptr: int, count: int) -> torch.Tensor:
         """Copy of a library-owned int32 device array as a tensor."""
@@ -314,6 +320,14 @@ def edge_data_to_csr(g: Graph, e: torch.Tensor) -> torch.Tensor:
     _check(lib().gnn_edge_data_to_csr(g._h, _dev(e2, torch.float32, "e"), e2.shape[1],
                                       out.data_ptr(), _stream()), "gnn_edge_data_to_csr")
     return out.reshape(e.shape)
+
+
+def edge_data_to_coo(g: Graph, e_csr: torch.Tensor) -> torch.Tensor:
+    e2 = _edge_rows(e_csr, g.num_edges)
+    out = torch.empty_like(e2)
+    _check(lib().gnn_edge_data_to_coo(g._h, _dev(e2, torch.float32, "e_csr"), e2.shape[1],
+                                      out.data_ptr(), _stream()), "gnn_edge_data_to_coo")
+    return out.reshape(e_csr.shape)
 
 
 def propagate(g: Graph, x: torch.Tensor, e: Optional[torch.Tensor] = None, msg: int = MSG_COPY_XJ,

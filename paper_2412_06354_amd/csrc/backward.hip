@@ -322,6 +322,11 @@ gnn_status gnn_propagate_backward(const gnn_graph *g, const gnn_graph *g_by_sour
                                      GNN_GATHER_SOURCE_NODE, winners));
     }
     if (d_grad_e && msg == GNN_MSG_E_MUL_XJ && g->num_edges > 0) {
+        if (e_dim == 1 && !winners && g->route && gnn_aligned16(d_grad_e)) {
+            // one gradient per edge: written in CSR order (a stream) and moved to the caller's order by the route
+            GNN_TRY(edge_products(g, F, false, d_x, gp, nullptr, g->route->staged, s, true));
+            return gnn_route_csr_to_coo(g, g->route->staged, d_grad_e, s);
+        }
         return edge_products(g, F, e_dim != 1, d_x, gp, winners, d_grad_e, s, false);
     }
     return GNN_OK;

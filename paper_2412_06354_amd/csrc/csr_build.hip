@@ -537,6 +537,7 @@ void free_graph_arrays(gnn_graph *g)
     }
     if (drop) (void)hipFree(drop);
     if (g->own_scratch) (void)hipFree(g->own_scratch);
+    gnn_route_free(g);
     g->slab = nullptr;
     g->slab_bytes = 0;
     g->scratch = nullptr;
@@ -1043,6 +1044,8 @@ gnn_status gnn_edge_data_to_csr(const gnn_graph *g, const float *d_e, int32_t e_
     if (e_dim <= 0) return GNN_ERR_BAD_SIZE;
     if (g->num_edges == 0) return GNN_OK;
     if (!d_e || !d_e_csr) return GNN_ERR_NULL;
+    if (e_dim == 1 && g->route && gnn_aligned16(d_e) && gnn_aligned16(d_e_csr))
+        return gnn_route_coo_to_csr(g, d_e, d_e_csr, static_cast<hipStream_t>(stream));
     const int64_t total = g->num_edges * e_dim;
     const int blocks = (int)std::min<int64_t>(gnn_div_up(total, kThreads), 256 * 64);
     hipLaunchKernelGGL(permute_rows_kernel, dim3(blocks), dim3(kThreads), 0, static_cast<hipStream_t>(stream),

@@ -56,6 +56,17 @@ struct shared_slab {
     std::atomic<int> refs{0};
 };
 
+// Index arrays and buffers of the two-pass route that moves one float per edge between the caller's edge order and
+// CSR order in streams (route.hip); built on request by gnn_graph_build_edge_route, one allocation.
+struct gnn_edge_route {
+    void *alloc = nullptr;
+    uint16_t *tile_src = nullptr;     // [E] per tile of edge ids: local edge of the k-th item in (bucket, edge id) order
+    int32_t *tile_dst = nullptr;      // [E] its place in `mid`
+    uint16_t *bucket_idx = nullptr;   // [E] per bucket of CSR positions: where in the bucket of `mid` position p's value lies
+    float *mid = nullptr;             // [E] the intermediate order, grouped by bucket
+    float *staged = nullptr;          // [E] CSR-ordered copy of edge data for compute calls that are handed COO order
+};
+
 struct gnn_graph {
     int32_t num_nodes = 0;        // rows of the CSR = destination nodes
     int32_t num_src_nodes = 0;    // range of colidx; equals num_nodes unless built from a relation between two node sets
@@ -95,7 +106,16 @@ struct gnn_graph {
     float *scratch = nullptr;
     size_t scratch_floats = 0;
     void *own_scratch = nullptr;   // the allocation gnn_graph_reserve made, if any (scratch points into it)
+
+    gnn_edge_route *route = nullptr;   // set by gnn_graph_build_edge_route
 };
+
+// out = in moved from the caller's edge order to CSR order / back, one float per edge, through the graph's route
+// (GNN_ERR_UNSUPPORTED without one).  in and out are 16-byte aligned; the route's `mid` buffer is overwritten.
+gnn_status gnn_route_coo_to_csr(const gnn_graph *g, const float *d_in, float *d_out, hipStream_t s);
+gnn_status gnn_route_csr_to_coo(const gnn_graph *g, const float *d_in, float *d_out, hipStream_t s);
+void gnn_route_free(gnn_graph *g);
+static inline bool gnn_aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 // Feature width the scratch part of the slab is sized for (see gnn_graph_reserve in gnn.h).
 constexpr int32_t kDefaultReservedFeatDim = 128;

@@ -689,6 +689,14 @@ gnn_status gnn_launch_propagate(const gnn_graph *g, const float *d_x, int32_t fe
     const int red = reduce == GNN_REDUCE_SUM ? kRedSum
                     : reduce == GNN_REDUCE_PROD ? kRedProd : reduce == GNN_REDUCE_MIN ? kRedMin : kRedMax;
 
+    // One weight per edge in the caller's order: with a route the weights are first moved to CSR order in two
+    // streaming passes (into the route's staging buffer), which costs less than reading them through perm.
+    if (kmsg == kMsgMulScalar && e_order == GNN_EDGE_ORDER_COO && g->route && g->num_edges > 0 && gnn_aligned16(d_e)) {
+        GNN_TRY(gnn_route_coo_to_csr(g, d_e, g->route->staged, stream));
+        d_e = g->route->staged;
+        e_order = GNN_EDGE_ORDER_CSR;
+    }
+
     PropParams p{};
     p.rowptr = g->rowptr; p.perm = g->perm;
     p.colidx = gather == GNN_GATHER_SOURCE_NODE ? g->colidx : (gather == GNN_GATHER_EDGE_COO ? g->perm : nullptr);

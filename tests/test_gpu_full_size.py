@@ -142,6 +142,25 @@ def test_config2_segment_softmax_sampled_rows(cfg2, gnn):
     assert_close_rel(got, ref, what="config2 segment softmax")
 
 
+def test_config2_edge_route_every_element(cfg2, gnn):
+    """The two-pass route for one float per edge at the full size: all 20 M weights land where e[perm] (perm from
+    the oracle) says, the way back restores them, and propagate with COO-ordered weights through the route equals
+    the CSR-ordered call bit for bit.  Runs last of the configuration-2 tests: it adds the route to the shared graph."""
+    wl, g = cfg2
+    _, _, perm, _ = oracle.build_csr(wl.src, wl.dst, wl.num_nodes)
+    e = np.ascontiguousarray(wl.edge_weight, dtype=np.float32).reshape(-1)
+    e_d, x = dev(e), dev(wl.x)
+    before = gnn.propagate(g, x, e_d, MSG_E_MUL_XJ, AGGR_SUM)
+    g.build_edge_route()
+    e_csr = gnn.edge_data_to_csr(g, e_d)
+    np.testing.assert_array_equal(host(e_csr), e[perm])
+    np.testing.assert_array_equal(host(gnn.edge_data_to_coo(g, e_csr)), e)
+    after = gnn.propagate(g, x, e_d, MSG_E_MUL_XJ, AGGR_SUM)
+    assert torch.equal(after, before)
+    from paper_2412_06354_amd.binding import EDGE_ORDER_CSR
+    assert torch.equal(gnn.propagate(g, x, e_csr, MSG_E_MUL_XJ, AGGR_SUM, e_order=EDGE_ORDER_CSR), before)
+
+
 # ----------------------------------------------------------------------------- configuration 1
 
 def test_config1_gcnconv_full(gnn):

@@ -1,0 +1,123 @@
+"""GPU tests of the two-pass route for one float per edge (gnn_graph_build_edge_route): the permutation into CSR
+order and back is bit-exact against e[perm] with perm from the CPU oracle, and the compute calls that take the
+route give what they give without it."""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+import oracle
+from oracle import AGGR_MEAN, AGGR_SUM, MSG_E_MUL_XJ
+from paper_2412_06354_amd import synth
+from util import assert_close_sabs
+
+pytestmark = pytest.mark.gpu
+
+TILE = 16384   # entries per tile / bucket of the route
+
+
+@pytest.fixture(scope="module")
+def gnn():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2412_06354_amd import binding
+    binding.lib()
+    return binding
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def host(t):
+    return t.cpu().numpy()
+
+
+def edge_values(count, seed):
+    return synth.uniform_f32(seed, 2, count, -1.0, 1.0)
+
+
+@pytest.mark.parametrize("num_nodes,num_edges", [
+    (3, 1), (7, 5), (50, 1000), (300, TILE - 1), (300, TILE), (300, TILE + 1), (1000, 3 * TILE + 5),
+    (20_000, 8 * TILE), (100_000, 1_000_003),
+])
+def test_route_is_the_permutation(gnn, num_nodes, num_edges):
+    src, dst = synth.multigraph_uniform(num_nodes, num_edges, seed=900 + num_edges % 97)
+    _, _, perm, _ = oracle.build_csr(src, dst, num_nodes)
+    e = edge_values(num_edges, 11)
+    g = gnn.build_csr(dev(src), dev(dst), num_nodes)
+    e_d = dev(e)
+    # the direct kernels
+    direct = gnn.edge_data_to_csr(g, e_d)
+    np.testing.assert_array_equal(host(direct), e[perm])
+    np.testing.assert_array_equal(host(gnn.edge_data_to_coo(g, direct)), e)
+    # the same two calls through the route, twice (the route's buffers are reused)
+    g.build_edge_route()
+    g.build_edge_route()
+    for _ in range(2):
+        routed = gnn.edge_data_to_csr(g, e_d)
+        np.testing.assert_array_equal(host(routed), e[perm])
+        np.testing.assert_array_equal(host(gnn.edge_data_to_coo(g, routed)), e)
+    # wider records keep the direct path and stay correct on a graph that has a route
+    e3 = edge_values(3 * num_edges, 12).reshape(num_edges, 3)
+    wide = gnn.edge_data_to_csr(g, dev(e3))
+    np.testing.assert_array_equal(host(wide), e3[perm])
+    np.testing.assert_array_equal(host(gnn.edge_data_to_coo(g, wide)), e3)
+    # buffers that are not 16-byte aligned keep the direct path
+    if num_edges > 4:
+        pad = torch.empty(num_edges + 1, dtype=torch.float32, device="cuda")
+        pad[1:] = e_d
+        np.testing.assert_array_equal(host(gnn.edge_data_to_csr(g, pad[1:])), e[perm])
+
+
+def test_route_on_a_hub_graph_and_an_empty_one(gnn):
+    wl = synth.config2_weighted(num_nodes=20_000, num_edges=300_000, feat=16, cap=6000.0)
+    _, _, perm, _ = oracle.build_csr(wl.src, wl.dst, wl.num_nodes)
+    g = gnn.build_csr(dev(wl.src), dev(wl.dst), wl.num_nodes)
+    g.build_edge_route()
+    e = edge_values(wl.num_edges, 13)
+    routed = gnn.edge_data_to_csr(g, dev(e))
+    np.testing.assert_array_equal(host(routed), e[perm])
+    np.testing.assert_array_equal(host(gnn.edge_data_to_coo(g, routed)), e)
+
+    none = np.zeros(0, np.int32)
+    g0 = gnn.build_csr(dev(none), dev(none), 5)
+    g0.build_edge_route()
+    assert gnn.edge_data_to_csr(g0, dev(np.zeros(0, np.float32))).numel() == 0
+
+
+@pytest.mark.parametrize("aggr", [AGGR_SUM, AGGR_MEAN])
+def test_compute_calls_take_the_route(gnn, aggr):
+    """propagate(e_mul_xj) with COO-ordered weights and its backward, with and without a route: identical bits
+    (the route only moves values), and both at the oracle's bar."""
+    wl = synth.config2_weighted(num_nodes=20_000, num_edges=300_000, feat=32, cap=6000.0)
+    n, f = wl.num_nodes, 32
+    x = synth.normal_f32(77, 2, n * f).reshape(n, f)
+    grad_out = synth.normal_f32(78, 2, n * f).reshape(n, f)
+    e = np.ascontiguousarray(wl.edge_weight, dtype=np.float32).reshape(-1)
+    src_d, dst_d, x_d, e_d, go_d = dev(wl.src), dev(wl.dst), dev(x), dev(e), dev(grad_out)
+
+    plain = gnn.build_csr(src_d, dst_d, n)
+    plain_t = gnn.build_csr(dst_d, src_d, n)
+    out_plain = gnn.propagate(plain, x_d, e_d, MSG_E_MUL_XJ, aggr)
+    gx_plain, ge_plain = gnn.propagate_backward(plain, plain_t, x_d, go_d, e_d, MSG_E_MUL_XJ, aggr)
+
+    routed = gnn.build_csr(src_d, dst_d, n)
+    routed_t = gnn.build_csr(dst_d, src_d, n)
+    routed.build_edge_route()
+    routed_t.build_edge_route()
+    out_routed = gnn.propagate(routed, x_d, e_d, MSG_E_MUL_XJ, aggr)
+    gx_routed, ge_routed = gnn.propagate_backward(routed, routed_t, x_d, go_d, e_d, MSG_E_MUL_XJ, aggr)
+    # the caller's weights are untouched and a second call gives the same
+    np.testing.assert_array_equal(host(e_d), e)
+    np.testing.assert_array_equal(host(gnn.propagate(routed, x_d, e_d, MSG_E_MUL_XJ, aggr)), host(out_routed))
+
+    np.testing.assert_array_equal(host(out_routed), host(out_plain))
+    np.testing.assert_array_equal(host(gx_routed), host(gx_plain))
+    np.testing.assert_array_equal(host(ge_routed), host(ge_plain))
+
+    ref, sabs = oracle.propagate(wl.src, wl.dst, n, x, e, MSG_E_MUL_XJ, aggr, with_sabs=True)
+    assert_close_sabs(host(out_routed), ref, sabs, what="routed propagate")
+    back = oracle.propagate_backward(wl.src, wl.dst, n, x, grad_out, e, MSG_E_MUL_XJ, aggr, with_sabs=True)
+    assert_close_sabs(host(gx_routed), back["grad_x"], back["sabs_x"], what="routed grad_x")
+    assert_close_sabs(host(ge_routed).reshape(-1, 1), back["grad_e"], back["sabs_e"], what="routed grad_e")
