@@ -289,6 +289,49 @@ def run_csr(args, torch, gnn, synth):
     return line
 
 
+def run_edge_data(args, torch, gnn, synth):
+    """One float per edge from the caller's order into CSR order and back (gnn_edge_data_to_csr / _to_coo) on the
+    headline graph: through perm directly, and through the two-pass route of gnn_graph_build_edge_route."""
+    wl = synth.config2_weighted(num_nodes=args.nodes, num_edges=args.edges, feat=4)
+    n, e = wl.num_nodes, wl.num_edges
+    src, dst, ew = (to_dev(torch, a) for a in (wl.src, wl.dst, wl.edge_weight))
+    g = gnn.build_csr(src, dst, n)
+    k = max(5, min(args.steps, 50))
+    e_csr = gnn.edge_data_to_csr(g, ew)
+    direct_to_csr = time_calls(torch, lambda: gnn.edge_data_to_csr(g, ew), k, 3)
+    direct_to_coo = time_calls(torch, lambda: gnn.edge_data_to_coo(g, e_csr), k, 3)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    g.build_edge_route()
+    torch.cuda.synchronize()
+    route_build_ms = (time.perf_counter() - t0) * 1e3
+    ms = time_calls(torch, lambda: gnn.edge_data_to_csr(g, ew), k, 3)
+    ms_back = time_calls(torch, lambda: gnn.edge_data_to_coo(g, e_csr), k, 3)
+    bytes_alg = 12 * e          # the value read, its index read, the value written
+    gbs = bytes_alg / (ms * 1e-3) / 1e9
+    line = base_line("edge data COO -> CSR order, one float per edge, algorithmic GB/s (12 bytes per edge)", gbs, ms,
+                     args, wl.name + ":edge_data", {"N": n, "E": e, "e_dim": 1})
+    line["steps"] = k
+    line["roofline"] = hbm_roofline(gbs, "route_tile_forward_kernel + route_bucket_kernel<true>",
+                                    counters_for(f"edge_data:{n}:{e}"), ms * 1e-3, bytes_alg)
+    line["extra"] = {"B_alg_bytes": bytes_alg, "bytes_moved_by_the_route": 24 * e,
+                     "route_GBs_moved": 24 * e / (ms * 1e-3) / 1e9, "to_coo_ms": ms_back,
+                     "direct_to_csr_ms": direct_to_csr, "direct_to_coo_ms": direct_to_coo,
+                     "route_build_ms": route_build_ms, "speedup_to_csr": direct_to_csr / ms}
+    if not args.no_cpu_baseline:
+        import numpy as np
+        import oracle
+        _, _, perm, _ = oracle.build_csr(wl.src, wl.dst, n)
+        w_h = np.ascontiguousarray(wl.edge_weight, dtype=np.float32).reshape(-1)
+        t0 = time.perf_counter()
+        w_h[perm]
+        dt = time.perf_counter() - t0
+        line["cpu_baseline"] = {"value": bytes_alg / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+                                "seconds": dt, "sample": "e[perm] with the oracle's perm, all edges, one pass"}
+    g.close()
+    return line
+
+
 def run_temporal(args, torch, gnn, synth):
     """Temporal snapshots: the headline edge list cut into 8 snapshots over the same nodes, built by one
     gnn_build_csr_batch call (one allocation, one synchronisation) and by 8 separate gnn_build_csr calls."""
@@ -764,7 +807,7 @@ def run_gcn_backward(args, torch, gnn, synth):
     return line
 
 
-WORKLOADS = {"temporal": run_temporal, "train": run_train, "example": run_example, "gat_backward": run_gat_backward, "gcn_backward": run_gcn_backward, "backward": run_backward, "propagate": run_propagate, "csr": run_csr, "softmax": run_softmax, "gcn": run_gcn, "gat": run_gat,
+WORKLOADS = {"edge_data": run_edge_data, "temporal": run_temporal, "train": run_train, "example": run_example, "gat_backward": run_gat_backward, "gcn_backward": run_gcn_backward, "backward": run_backward, "propagate": run_propagate, "csr": run_csr, "softmax": run_softmax, "gcn": run_gcn, "gat": run_gat,
              "batched": run_batched, "tiny": run_tiny}
 
 
