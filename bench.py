@@ -368,6 +368,21 @@ def run_temporal(args, torch, gnn, synth):
     line["roofline"] = hbm_roofline(gbs, "sort_scatter_kernel on 2.5 M-edge snapshots dominates")
     line["extra"] = {"B_alg_bytes": bytes_alg, "separate_builds_ms": ms_sep,
                      "note": "the same 8 snapshots built by 8 gnn_build_csr calls take separate_builds_ms"}
+    # the regime snapshot sequences are usually in: many small graphs.  256 snapshots of 20 000 edges over 10 000 nodes
+    many, ne_small, n_small = 256, 20_000, 10_000
+    s_src = [(src[i * ne_small:(i + 1) * ne_small] % n_small).contiguous() for i in range(many)]
+    s_dst = [(dst[i * ne_small:(i + 1) * ne_small] % n_small).contiguous() for i in range(many)]
+    destroy(gnn.build_csr_batch(s_src, s_dst, n_small))
+    t0 = time.perf_counter()
+    for _ in range(k):
+        destroy(gnn.build_csr_batch(s_src, s_dst, n_small))
+    ms_many = (time.perf_counter() - t0) / k * 1e3
+    t0 = time.perf_counter()
+    for _ in range(k):
+        destroy([gnn.build_csr(a, b, n_small) for a, b in zip(s_src, s_dst)])
+    ms_many_sep = (time.perf_counter() - t0) / k * 1e3
+    line["extra"]["many_small_snapshots"] = {"snapshots": many, "N": n_small, "E_per_snapshot": ne_small,
+                                             "batch_ms": ms_many, "separate_builds_ms": ms_many_sep}
     if not args.no_cpu_baseline:
         import oracle
         t0 = time.perf_counter()

@@ -10,6 +10,7 @@
 #include "gnn_internal.h"
 
 #include <algorithm>
+#include <cstring>
 #include <mutex>
 
 namespace {
@@ -41,8 +42,8 @@ __global__ __launch_bounds__(kThreads) void check_range_kernel(const int32_t *__
 // key a = -1, after the last one the remaining rows and rowptr[N] get E.  Valid, sorted keys write every entry
 // exactly once.  Keys outside [0, N) -- invalid input, reported through the range flag -- are clamped, so nothing
 // outside rowptr[0 .. N] is written whatever the keys are.  Four positions per thread (one 128-bit load).
-__global__ __launch_bounds__(kThreads) void row_pointers_kernel(const int32_t *__restrict__ keys, int64_t E, int32_t N,
-                                                                int32_t *__restrict__ rowptr)
+__device__ __forceinline__ void row_pointers_body(const int32_t *__restrict__ keys, int64_t E, int32_t N,
+                                                  int32_t *__restrict__ rowptr)
 {
     const int64_t p0 = ((int64_t)blockIdx.x * kThreads + threadIdx.x) * 4;
     if (p0 >= E) return;
@@ -66,6 +67,12 @@ __global__ __launch_bounds__(kThreads) void row_pointers_kernel(const int32_t *_
         for (int32_t r = k[cnt] + 1; r <= N; ++r) rowptr[r] = (int32_t)E;
 }
 
+__global__ __launch_bounds__(kThreads) void row_pointers_kernel(const int32_t *__restrict__ keys, int64_t E, int32_t N,
+                                                                int32_t *__restrict__ rowptr)
+{
+    row_pointers_body(keys, E, N, rowptr);
+}
+
 // ---------------------------------------------------------------- radix sort passes
 
 constexpr int kSortItems = 16;                       // keys per thread
@@ -83,12 +90,10 @@ constexpr int kCountCopies = 8;
 // CHECK: the first pass over the caller's arrays also does the range check of both index arrays and keeps a copy
 // of the destinations (the keys) in the caller's edge order.
 template <bool CHECK>
-__global__ __launch_bounds__(kCountThreads) void sort_count_kernel(const int32_t *__restrict__ keys, int64_t n, int shift,
-                                                                   int bits, int32_t *__restrict__ tile_counts,
-                                                                   int num_tiles, const int32_t *__restrict__ src,
-                                                                   int32_t N_src, int32_t N,
-                                                                   int32_t *__restrict__ key_copy,
-                                                                   int32_t *__restrict__ bad)
+__device__ __forceinline__ void sort_count_body(const int32_t *__restrict__ keys, int64_t n, int shift, int bits,
+                                                int32_t *__restrict__ tile_counts, int num_tiles,
+                                                const int32_t *__restrict__ src, int32_t N_src, int32_t N,
+                                                int32_t *__restrict__ key_copy, int32_t *__restrict__ bad)
 {
     // Every digit has kCountCopies counters, lane l adds to copy l % kCountCopies: lanes that hold the same digit
     // (a hub node fills many lanes of a wavefront in the later passes, whose input is sorted by the low bits)
@@ -143,6 +148,17 @@ __global__ __launch_bounds__(kCountThreads) void sort_count_kernel(const int32_t
         if (any_bad) atomicOr(bad, 1);
 }
 
+template <bool CHECK>
+__global__ __launch_bounds__(kCountThreads) void sort_count_kernel(const int32_t *__restrict__ keys, int64_t n, int shift,
+                                                                   int bits, int32_t *__restrict__ tile_counts,
+                                                                   int num_tiles, const int32_t *__restrict__ src,
+                                                                   int32_t N_src, int32_t N,
+                                                                   int32_t *__restrict__ key_copy,
+                                                                   int32_t *__restrict__ bad)
+{
+    sort_count_body<CHECK>(keys, n, shift, bits, tile_counts, num_tiles, src, N_src, N, key_copy, bad);
+}
+
 // Stable scatter of one pass.  A tile (kSortTile consecutive keys) is handled by a block of
 // kScatterThreads threads, kScatterItems keys per thread; inside a tile the order is: wavefront, then
 // item, then lane; key `idx` of wavefront w is tile_base + w*64*items + item*64 + lane, so this order is
@@ -161,7 +177,7 @@ constexpr int kScatterWaves = kScatterThreads / 64;
 static_assert(kScatterItems * kScatterThreads == kSortTile, "tile size");
 
 template <int BITS>
-__global__ __launch_bounds__(kScatterThreads) void sort_scatter_kernel(
+__device__ __forceinline__ void sort_scatter_body(
     const int32_t *__restrict__ keys_in, const int32_t *__restrict__ val_in, const int32_t *__restrict__ eid_in,
     int64_t n, int shift, const int32_t *__restrict__ tile_offsets,
     const int32_t *__restrict__ digit_totals, int num_tiles,
@@ -285,6 +301,17 @@ __global__ __launch_bounds__(kScatterThreads) void sort_scatter_kernel(
     }
 }
 
+template <int BITS>
+__global__ __launch_bounds__(kScatterThreads) void sort_scatter_kernel(
+    const int32_t *__restrict__ keys_in, const int32_t *__restrict__ val_in, const int32_t *__restrict__ eid_in,
+    int64_t n, int shift, const int32_t *__restrict__ tile_offsets,
+    const int32_t *__restrict__ digit_totals, int num_tiles,
+    int32_t *__restrict__ keys_out, int32_t *__restrict__ val_out, int32_t *__restrict__ eid_out)
+{
+    sort_scatter_body<BITS>(keys_in, val_in, eid_in, n, shift, tile_offsets, digit_totals, num_tiles, keys_out, val_out,
+                            eid_out);
+}
+
 // The digit width is a compile-time constant of the scatter kernel (its bit-by-bit matching loop is unrolled).
 template <int BITS>
 gnn_status launch_scatter_bits(int64_t blocks, hipStream_t stream, const int32_t *ki, const int32_t *vi, const int32_t *ei,
@@ -388,13 +415,11 @@ __device__ __forceinline__ void load_row_pointers(const int32_t *__restrict__ ro
     for (int i = 0; i <= kListRowsPerThread; ++i) rp[i] = (r0 + i <= N) ? rowptr[r0 + i] : 0;
 }
 
-__global__ __launch_bounds__(kThreads) void classify_rows_kernel(const int32_t *__restrict__ rowptr, int32_t N,
-                                                                 int32_t small_max, int32_t chunk,
-                                                                 const int32_t *__restrict__ bad,
-                                                                 int32_t *__restrict__ indeg,
-                                                                 float *__restrict__ dinv_loop,
-                                                                 float *__restrict__ dinv_plain,
-                                                                 int32_t *__restrict__ block_sums, int num_blocks)
+__device__ __forceinline__ void classify_rows_body(const int32_t *__restrict__ rowptr, int32_t N, int32_t small_max,
+                                                   int32_t chunk, const int32_t *__restrict__ bad,
+                                                   int32_t *__restrict__ indeg, float *__restrict__ dinv_loop,
+                                                   float *__restrict__ dinv_plain, int32_t *__restrict__ block_sums,
+                                                   int num_blocks)
 {
     const int64_t r0 = (int64_t)blockIdx.x * kListRows + (int64_t)threadIdx.x * kListRowsPerThread;
     // invalid input (the build will fail with an error): the row pointers mean nothing, every row counts as empty
@@ -425,9 +450,20 @@ __global__ __launch_bounds__(kThreads) void classify_rows_kernel(const int32_t *
     }
 }
 
+__global__ __launch_bounds__(kThreads) void classify_rows_kernel(const int32_t *__restrict__ rowptr, int32_t N,
+                                                                 int32_t small_max, int32_t chunk,
+                                                                 const int32_t *__restrict__ bad,
+                                                                 int32_t *__restrict__ indeg,
+                                                                 float *__restrict__ dinv_loop,
+                                                                 float *__restrict__ dinv_plain,
+                                                                 int32_t *__restrict__ block_sums, int num_blocks)
+{
+    classify_rows_body(rowptr, N, small_max, chunk, bad, indeg, dinv_loop, dinv_plain, block_sums, num_blocks);
+}
+
 // block_first: block_sums after the exclusive scan along each of its four rows; list_sizes: the four row totals.
 // info[0] = the range flag, info[1 .. 4] = the sizes of the lists (one host read-back for all five).
-__global__ __launch_bounds__(kThreads) void fill_lists_kernel(
+__device__ __forceinline__ void fill_lists_body(
     const int32_t *__restrict__ rowptr, int32_t N, int32_t small_max, int32_t chunk, const int32_t *__restrict__ bad,
     const int32_t *__restrict__ block_first, int num_blocks, const int32_t *__restrict__ list_sizes,
     int32_t *__restrict__ small_rows, int32_t *__restrict__ item_row, int32_t *__restrict__ item_start,
@@ -480,6 +516,111 @@ __global__ __launch_bounds__(kThreads) void fill_lists_kernel(
         p_item += items;
         p_slot += items;
     }
+}
+
+__global__ __launch_bounds__(kThreads) void fill_lists_kernel(
+    const int32_t *__restrict__ rowptr, int32_t N, int32_t small_max, int32_t chunk, const int32_t *__restrict__ bad,
+    const int32_t *__restrict__ block_first, int num_blocks, const int32_t *__restrict__ list_sizes,
+    int32_t *__restrict__ small_rows, int32_t *__restrict__ item_row, int32_t *__restrict__ item_start,
+    int32_t *__restrict__ item_slot, int32_t *__restrict__ split_rows, int32_t *__restrict__ split_slot0,
+    int32_t *__restrict__ info)
+{
+    fill_lists_body(rowptr, N, small_max, chunk, bad, block_first, num_blocks, list_sizes, small_rows, item_row,
+                    item_start, item_slot, split_rows, split_slot0, info);
+}
+
+// ---------------------------------------------------------------- the same kernels over a batch of builds
+
+// One build of a batch (gnn_build_csr_batch: the snapshots of a temporal graph over one node set): what differs
+// from build to build.  The kernels below are the kernels above with blockIdx.y naming the build; a launch covers
+// every build of the batch, so the launch count does not grow with the number of snapshots.
+struct BuildJob {
+    const int32_t *src, *dst;   // the caller's edge list
+    int64_t E;
+    int32_t num_tiles, small_max, chunk, pad;
+    int32_t *kb, *vb, *eb, *counts, *digit_totals, *block_sums, *list_sizes, *flag;   // temporaries of this build
+    int32_t *rowptr, *indeg, *colidx, *perm, *rowidx, *dst_coo;                       // arrays of its graph
+    float *dinv_loop, *dinv_plain;
+    int32_t *small_rows, *item_row, *item_start, *item_slot, *split_rows, *split_slot0;
+};
+
+// The three arrays a sort pass reads or writes: 0 = the caller's (dst, src, edge id = position), 1 = the
+// temporaries, 2 = the arrays the graph keeps.
+struct SortArrays {
+    int32_t *k, *v, *e;
+};
+
+__device__ __forceinline__ SortArrays sort_arrays(const BuildJob &j, int sel)
+{
+    if (sel == 0) return {const_cast<int32_t *>(j.dst), const_cast<int32_t *>(j.src), nullptr};   // only ever read
+    if (sel == 1) return {j.kb, j.vb, j.eb};
+    return {j.rowidx, j.colidx, j.perm};
+}
+
+template <bool CHECK>
+__global__ __launch_bounds__(kCountThreads) void sort_count_batch_kernel(const BuildJob *__restrict__ jobs, int in_sel,
+                                                                         int shift, int bits, int32_t N)
+{
+    const BuildJob j = jobs[blockIdx.y];
+    const SortArrays in = sort_arrays(j, in_sel);
+    sort_count_body<CHECK>(in.k, j.E, shift, bits, j.counts, j.num_tiles, j.src, N, N, j.dst_coo, j.flag);
+}
+
+template <int BITS>
+__global__ __launch_bounds__(kScatterThreads) void sort_scatter_batch_kernel(const BuildJob *__restrict__ jobs,
+                                                                             int in_sel, int out_sel, int shift)
+{
+    const BuildJob j = jobs[blockIdx.y];
+    const SortArrays in = sort_arrays(j, in_sel), out = sort_arrays(j, out_sel);
+    sort_scatter_body<BITS>(in.k, in.v, in.e, j.E, shift, j.counts, j.digit_totals, j.num_tiles, out.k, out.v, out.e);
+}
+
+__global__ __launch_bounds__(kThreads) void row_pointers_batch_kernel(const BuildJob *__restrict__ jobs, int32_t N)
+{
+    const BuildJob j = jobs[blockIdx.y];
+    row_pointers_body(j.rowidx, j.E, N, j.rowptr);
+}
+
+__global__ __launch_bounds__(kThreads) void classify_rows_batch_kernel(const BuildJob *__restrict__ jobs, int32_t N,
+                                                                       int num_blocks)
+{
+    const BuildJob j = jobs[blockIdx.y];
+    classify_rows_body(j.rowptr, N, j.small_max, j.chunk, j.flag, j.indeg, j.dinv_loop, j.dinv_plain, j.block_sums,
+                       num_blocks);
+}
+
+__global__ __launch_bounds__(kThreads) void fill_lists_batch_kernel(const BuildJob *__restrict__ jobs, int32_t N,
+                                                                    int num_blocks)
+{
+    const BuildJob j = jobs[blockIdx.y];
+    fill_lists_body(j.rowptr, N, j.small_max, j.chunk, j.flag, j.block_sums, num_blocks, j.list_sizes, j.small_rows,
+                    j.item_row, j.item_start, j.item_slot, j.split_rows, j.split_slot0, j.flag + 8);
+}
+
+template <int BITS>
+gnn_status launch_scatter_batch_bits(dim3 grid, hipStream_t stream, const BuildJob *jobs, int in_sel, int out_sel,
+                                     int shift)
+{
+    hipLaunchKernelGGL(sort_scatter_batch_kernel<BITS>, grid, dim3(kScatterThreads), 0, stream, jobs, in_sel, out_sel,
+                       shift);
+    GNN_LAUNCH_CHECK();
+    return GNN_OK;
+}
+
+gnn_status launch_scatter_batch(int bits, dim3 grid, hipStream_t stream, const BuildJob *jobs, int in_sel, int out_sel,
+                                int shift)
+{
+    switch (bits) {
+    case 1: return launch_scatter_batch_bits<1>(grid, stream, jobs, in_sel, out_sel, shift);
+    case 2: return launch_scatter_batch_bits<2>(grid, stream, jobs, in_sel, out_sel, shift);
+    case 3: return launch_scatter_batch_bits<3>(grid, stream, jobs, in_sel, out_sel, shift);
+    case 4: return launch_scatter_batch_bits<4>(grid, stream, jobs, in_sel, out_sel, shift);
+    case 5: return launch_scatter_batch_bits<5>(grid, stream, jobs, in_sel, out_sel, shift);
+    case 6: return launch_scatter_batch_bits<6>(grid, stream, jobs, in_sel, out_sel, shift);
+    case 7: return launch_scatter_batch_bits<7>(grid, stream, jobs, in_sel, out_sel, shift);
+    case 8: return launch_scatter_batch_bits<8>(grid, stream, jobs, in_sel, out_sel, shift);
+    }
+    return GNN_ERR_BAD_SIZE;
 }
 
 __global__ __launch_bounds__(kThreads) void permute_rows_kernel(const int32_t *__restrict__ perm, int64_t E,
@@ -802,6 +943,55 @@ gnn_status enqueue_build(const int32_t *d_src, const int32_t *d_dst, int64_t E, 
     return GNN_OK;
 }
 
+// Enqueues the kernels of a whole batch of builds over one node set (N > 1): every launch covers all builds.
+// d_jobs / d_count_scans / d_list_scans: device copies of the job tables (num_jobs entries each).
+gnn_status enqueue_build_batch(const BuildJob *d_jobs, const gnn_scan_job *d_count_scans,
+                               const gnn_scan_job *d_list_scans, int num_jobs, int64_t max_edges, int32_t N,
+                               hipStream_t stream)
+{
+    const int key_bits = ceil_log2((uint32_t)N);
+    const int passes = (key_bits + kDigitBitsMax - 1) / kDigitBitsMax;
+    const int bits = (key_bits + passes - 1) / passes;
+    const int64_t max_tiles = gnn_div_up(max_edges, kSortTile);
+    const int list_blocks = (int)gnn_div_up(N, kListRows);
+    constexpr int kGroup = 32768;   // builds per launch (the grid's second dimension)
+    for (int first = 0; first < num_jobs; first += kGroup) {
+        const unsigned count = (unsigned)std::min(kGroup, num_jobs - first);
+        const BuildJob *jobs = d_jobs + first;
+        if (max_edges > 0) {
+            // as in a single build: ping-pong between the temporaries (1) and the graph's arrays (2), arranged so
+            // that the last pass writes into the graph's arrays
+            int in_sel = 0, out_sel = (passes % 2 == 1) ? 2 : 1;
+            for (int p = 0; p < passes; ++p) {
+                const int shift = p * bits;
+                const dim3 cgrid((unsigned)std::min<int64_t>(max_tiles, 1024), count);
+                if (p == 0)
+                    hipLaunchKernelGGL(sort_count_batch_kernel<true>, cgrid, dim3(kCountThreads), 0, stream, jobs, in_sel,
+                                       shift, bits, N);
+                else
+                    hipLaunchKernelGGL(sort_count_batch_kernel<false>, cgrid, dim3(kCountThreads), 0, stream, jobs, in_sel,
+                                       shift, bits, N);
+                GNN_LAUNCH_CHECK();
+                GNN_TRY(gnn_scan_rows_exclusive_i32_jobs(d_count_scans + first, (int)count, 1 << bits, stream));
+                const dim3 sgrid((unsigned)(gnn_div_up(max_tiles, kDies) * kDies), count);
+                GNN_TRY(launch_scatter_batch(bits, sgrid, stream, jobs, in_sel, out_sel, shift));
+                in_sel = out_sel;
+                out_sel = (out_sel == 1) ? 2 : 1;
+            }
+            const dim3 rgrid((unsigned)gnn_div_up(gnn_div_up(max_edges, 4), kThreads), count);
+            hipLaunchKernelGGL(row_pointers_batch_kernel, rgrid, dim3(kThreads), 0, stream, jobs, N);
+            GNN_LAUNCH_CHECK();
+        }
+        const dim3 lgrid((unsigned)list_blocks, count);
+        hipLaunchKernelGGL(classify_rows_batch_kernel, lgrid, dim3(kThreads), 0, stream, jobs, N, list_blocks);
+        GNN_LAUNCH_CHECK();
+        GNN_TRY(gnn_scan_rows_exclusive_i32_jobs(d_list_scans + first, (int)count, 4, stream));
+        hipLaunchKernelGGL(fill_lists_batch_kernel, lgrid, dim3(kThreads), 0, stream, jobs, N, list_blocks);
+        GNN_LAUNCH_CHECK();
+    }
+    return GNN_OK;
+}
+
 void take_list_sizes(gnn_graph *g, const int32_t *h_info)
 {
     g->n_small = h_info[1];
@@ -917,23 +1107,30 @@ gnn_status gnn_build_csr_batch(int32_t num_snapshots, const int32_t *const *d_sr
     int dev = 0;
     GNN_HIP(hipGetDevice(&dev));
 
-    // one allocation for all graphs, one for the temporaries (the largest snapshot's, reused by every snapshot: the
-    // builds run one after the other on the stream) with a flag block per snapshot in front
+    // one allocation for all graphs.  The temporaries come from the buffer the library keeps between builds: a flag
+    // block per snapshot in front, then the job tables, then every snapshot's own sort buffers and counts (all
+    // snapshots are built by the same launches: blockIdx.y names the snapshot).  One node (nothing to sort) takes
+    // the builds one after the other with one set of temporaries.
+    const bool one_by_one = num_nodes == 1;
     std::vector<gnn_graph *> graphs((size_t)num_snapshots, nullptr);
     std::vector<graph_layout> layouts((size_t)num_snapshots);
     std::vector<temp_layout> temps((size_t)num_snapshots);
-    std::vector<size_t> base((size_t)num_snapshots);
+    std::vector<size_t> base((size_t)num_snapshots), temp_base((size_t)num_snapshots);
     size_t slab_bytes = 0, temp_bytes = 0;
+    int64_t max_edges = 0;
     const size_t flag_block = kFlagInts * sizeof(int32_t), flag_bytes = flag_block * (size_t)num_snapshots;
+    const size_t jobs_bytes = (sizeof(BuildJob) * (size_t)num_snapshots + 255) & ~(size_t)255;
+    const size_t scans_bytes = (sizeof(gnn_scan_job) * (size_t)num_snapshots + 255) & ~(size_t)255;
+    const size_t table_bytes = one_by_one ? 0 : jobs_bytes + 2 * scans_bytes;
     gnn_status st = GNN_OK;
     void *slab = nullptr, *tmp = nullptr;
+    temp_lease lease;   // handed back when the function returns: every path has synchronised the stream by then
     shared_slab *shared = nullptr;
     std::vector<int32_t> h_flags((size_t)num_snapshots * kFlagInts, 0);
     auto fail = [&](gnn_status code) {
         (void)hipStreamSynchronize(s);
         for (gnn_graph *g : graphs) delete g;
         if (slab) (void)hipFree(slab);
-        if (tmp) (void)hipFree(tmp);
         delete shared;
         return code;
     };
@@ -953,26 +1150,62 @@ gnn_status gnn_build_csr_batch(int32_t num_snapshots, const int32_t *const *d_sr
         temps[(size_t)t] = plan_temp(num_edges[t], num_nodes);
         base[(size_t)t] = slab_bytes;
         slab_bytes += layouts[(size_t)t].bytes;
-        temp_bytes = std::max(temp_bytes, temps[(size_t)t].bytes);
+        temp_base[(size_t)t] = one_by_one ? 0 : temp_bytes;
+        temp_bytes = one_by_one ? std::max(temp_bytes, temps[(size_t)t].bytes) : temp_bytes + temps[(size_t)t].bytes;
+        max_edges = std::max(max_edges, num_edges[t]);
     }
     shared = new (std::nothrow) shared_slab();
     if (!shared) return fail(GNN_ERR_ALLOC);
     if ((st = slab_alloc(&slab, slab_bytes)) != GNN_OK) return fail(st);
-    if ((st = slab_alloc(&tmp, flag_bytes + temp_bytes)) != GNN_OK) return fail(st);
+    if ((st = temp_acquire(&lease, flag_bytes + table_bytes + temp_bytes)) != GNN_OK) return fail(st);
+    tmp = lease.ptr;
     if (hipMemsetAsync(tmp, 0, flag_bytes, s) != hipSuccess) return fail(GNN_ERR_DEVICE);
+    char *tables = static_cast<char *>(tmp) + flag_bytes, *temp0 = tables + table_bytes;
+    std::vector<char> h_tables(table_bytes);
     for (int32_t t = 0; t < num_snapshots; ++t) {
         gnn_graph *g = graphs[(size_t)t];
         bind_graph(g, static_cast<char *>(slab) + base[(size_t)t], layouts[(size_t)t]);
         int32_t *d_flag = reinterpret_cast<int32_t *>(static_cast<char *>(tmp) + flag_block * (size_t)t);
-        st = enqueue_build(d_src[t], d_dst[t], num_edges[t], num_nodes, s, g, static_cast<char *>(tmp) + flag_bytes,
-                           temps[(size_t)t], d_flag);
+        char *ts = temp0 + temp_base[(size_t)t];
+        const temp_layout &T = temps[(size_t)t];
+        if (one_by_one) {
+            st = enqueue_build(d_src[t], d_dst[t], num_edges[t], num_nodes, s, g, ts, T, d_flag);
+            if (st != GNN_OK) return fail(st);
+            continue;
+        }
+        if (num_edges[t] == 0 &&
+            hipMemsetAsync(g->rowptr, 0, ((size_t)num_nodes + 1) * sizeof(int32_t), s) != hipSuccess)
+            return fail(GNN_ERR_DEVICE);
+        BuildJob j{};
+        j.src = d_src[t]; j.dst = d_dst[t]; j.E = num_edges[t];
+        j.num_tiles = (int32_t)T.num_tiles; j.small_max = g->small_max; j.chunk = g->chunk;
+        j.kb = at(ts, T.o_kb); j.vb = at(ts, T.o_vb); j.eb = at(ts, T.o_eb); j.counts = at(ts, T.o_counts);
+        j.digit_totals = at(ts, T.o_dtot); j.block_sums = at(ts, T.o_bsum); j.list_sizes = at(ts, T.o_sizes);
+        j.flag = d_flag;
+        j.rowptr = g->rowptr; j.indeg = g->indeg; j.colidx = g->colidx; j.perm = g->perm; j.rowidx = g->rowidx;
+        j.dst_coo = g->dst_coo; j.dinv_loop = g->dinv_loop; j.dinv_plain = g->dinv_plain;
+        j.small_rows = g->small_rows; j.item_row = g->item_row; j.item_start = g->item_start;
+        j.item_slot = g->item_slot; j.split_rows = g->split_rows; j.split_slot0 = g->split_slot0;
+        std::memcpy(h_tables.data() + sizeof(BuildJob) * (size_t)t, &j, sizeof(j));
+        const gnn_scan_job counts_scan{j.counts, T.num_tiles, j.digit_totals};
+        const gnn_scan_job lists_scan{j.block_sums, T.list_blocks, j.list_sizes};
+        std::memcpy(h_tables.data() + jobs_bytes + sizeof(gnn_scan_job) * (size_t)t, &counts_scan, sizeof(counts_scan));
+        std::memcpy(h_tables.data() + jobs_bytes + scans_bytes + sizeof(gnn_scan_job) * (size_t)t, &lists_scan,
+                    sizeof(lists_scan));
+    }
+    if (!one_by_one) {
+        if (hipMemcpyAsync(tables, h_tables.data(), table_bytes, hipMemcpyHostToDevice, s) != hipSuccess)
+            return fail(GNN_ERR_DEVICE);
+        st = enqueue_build_batch(reinterpret_cast<const BuildJob *>(tables),
+                                 reinterpret_cast<const gnn_scan_job *>(tables + jobs_bytes),
+                                 reinterpret_cast<const gnn_scan_job *>(tables + jobs_bytes + scans_bytes), num_snapshots,
+                                 max_edges, num_nodes, s);
         if (st != GNN_OK) return fail(st);
     }
     if (hipMemcpyAsync(h_flags.data(), tmp, flag_bytes, hipMemcpyDeviceToHost, s) != hipSuccess) return fail(GNN_ERR_DEVICE);
     if (hipStreamSynchronize(s) != hipSuccess) return fail(GNN_ERR_DEVICE);
     for (int32_t t = 0; t < num_snapshots; ++t)
         if (h_flags[(size_t)t * kFlagInts + 8]) return fail(GNN_ERR_INDEX_RANGE);
-    (void)hipFree(tmp);
     shared->ptr = slab;
     shared->refs.store(num_snapshots);
     for (int32_t t = 0; t < num_snapshots; ++t) {

@@ -147,6 +147,15 @@ gnn_status gnn_launch_sum_partials_scaled(const float *d_partial, int chunks, in
 gnn_status gnn_scan_rows_exclusive_i32(int32_t *d_data, int rows, int64_t cols, int32_t *d_row_totals,
                                        hipStream_t stream);
 
+// The same for several arrays with the same number of rows in one launch; d_jobs is a device array of num_jobs
+// entries (cols may differ from job to job; a job with cols == 0 only gets zero totals).
+struct gnn_scan_job {
+    int32_t *data;
+    int64_t cols;
+    int32_t *row_totals;
+};
+gnn_status gnn_scan_rows_exclusive_i32_jobs(const gnn_scan_job *d_jobs, int num_jobs, int rows, hipStream_t stream);
+
 // Epilogue applied to a finished row reduction:  out = act(post * (acc + self_scale * x[row]) + bias)
 // with post = row_scale[row] (or 1), or acc / in-degree for the mean.
 struct gnn_epilogue {

@@ -20,8 +20,8 @@ __device__ __forceinline__ int wave_inclusive_scan(int v)
     return v;
 }
 
-__global__ __launch_bounds__(kRowThreads) void scan_rows_kernel(int32_t *__restrict__ data, int64_t cols,
-                                                                int32_t *__restrict__ row_totals)
+__device__ __forceinline__ void scan_row_body(int32_t *__restrict__ data, int64_t cols,
+                                              int32_t *__restrict__ row_totals)
 {
     __shared__ int wave_sums[kRowThreads / 64];
     int32_t *row = data + (int64_t)blockIdx.x * cols;
@@ -58,6 +58,19 @@ __global__ __launch_bounds__(kRowThreads) void scan_rows_kernel(int32_t *__restr
     if (threadIdx.x == 0) row_totals[blockIdx.x] = carry;
 }
 
+__global__ __launch_bounds__(kRowThreads) void scan_rows_kernel(int32_t *__restrict__ data, int64_t cols,
+                                                                int32_t *__restrict__ row_totals)
+{
+    scan_row_body(data, cols, row_totals);
+}
+
+// One array per job: blockIdx.y names the job, blockIdx.x its row.
+__global__ __launch_bounds__(kRowThreads) void scan_rows_jobs_kernel(const gnn_scan_job *__restrict__ jobs)
+{
+    const gnn_scan_job j = jobs[blockIdx.y];
+    scan_row_body(j.data, j.cols, j.row_totals);
+}
+
 }  // namespace
 
 gnn_status gnn_scan_rows_exclusive_i32(int32_t *d_data, int rows, int64_t cols, int32_t *d_row_totals,
@@ -67,6 +80,16 @@ gnn_status gnn_scan_rows_exclusive_i32(int32_t *d_data, int rows, int64_t cols, 
     if (rows == 0) return GNN_OK;
     hipLaunchKernelGGL(scan_rows_kernel, dim3((unsigned)rows), dim3(kRowThreads), 0, stream, d_data, cols,
                        d_row_totals);
+    GNN_LAUNCH_CHECK();
+    return GNN_OK;
+}
+
+gnn_status gnn_scan_rows_exclusive_i32_jobs(const gnn_scan_job *d_jobs, int num_jobs, int rows, hipStream_t stream)
+{
+    if (rows < 0 || num_jobs < 0) return GNN_ERR_BAD_SIZE;
+    if (rows == 0 || num_jobs == 0) return GNN_OK;
+    hipLaunchKernelGGL(scan_rows_jobs_kernel, dim3((unsigned)rows, (unsigned)num_jobs), dim3(kRowThreads), 0, stream,
+                       d_jobs);
     GNN_LAUNCH_CHECK();
     return GNN_OK;
 }

@@ -203,6 +203,39 @@ def test_batch_build_of_temporal_snapshots(gnn):
     assert lib.gnn_build_csr_batch(0, None, None, None, n, None, slots) == 2
 
 
+def test_batch_build_of_many_small_snapshots(gnn):
+    """Many small snapshots go through the same few launches (the snapshot is a grid dimension): CSR and work lists
+    of every handle equal a build on its own.  A one-node graph takes the builds one after the other."""
+    n = 700
+    sizes = [int(v) for v in synth.randint(31, 6, 0, 37, 0, 3000)]
+    sizes[5] = 0
+    sizes[11] = 4096        # exactly one sort tile
+    sizes[12] = 4097
+    snaps = [synth.multigraph_uniform(n, e, seed=500 + t) if e else (np.empty(0, np.int32), np.empty(0, np.int32))
+             for t, e in enumerate(sizes)]
+    graphs = gnn.build_csr_batch([dev(s) for s, _ in snaps], [dev(d) for _, d in snaps], n)
+    for t, (g, (src, dst)) in enumerate(zip(graphs, snaps)):
+        rowptr, colidx, perm, indeg = oracle.build_csr(src, dst, n)
+        np.testing.assert_array_equal(host(g.rowptr), rowptr, err_msg=f"snapshot {t}")
+        np.testing.assert_array_equal(host(g.colidx), colidx, err_msg=f"snapshot {t}")
+        np.testing.assert_array_equal(host(g.perm), perm, err_msg=f"snapshot {t}")
+        np.testing.assert_array_equal(host(g.indegree), indeg, err_msg=f"snapshot {t}")
+        alone = gnn.build_csr(dev(src), dev(dst), n)
+        assert alone.work_sizes() == g.work_sizes()
+        la, lb = alone.work_lists(), g.work_lists()
+        assert all(torch.equal(la[k], lb[k]) for k in la)
+        alone.close()
+    for g in graphs:
+        g.close()
+    # one node: every edge is a self-loop
+    loops = [np.zeros(e, np.int32) for e in (3, 0, 70)]
+    graphs = gnn.build_csr_batch([dev(a) for a in loops], [dev(a) for a in loops], 1)
+    for g, a in zip(graphs, loops):
+        np.testing.assert_array_equal(host(g.rowptr), [0, a.shape[0]])
+        np.testing.assert_array_equal(host(g.perm), np.arange(a.shape[0]))
+        g.close()
+
+
 def test_check_graph_indicator(gnn):
     wl = synth.config3_batched(num_graphs=200, feat=4)
     gi = wl.graph_indicator
