@@ -469,6 +469,21 @@ gnn_status gnn_graph_pool(const int32_t *d_graph_indicator, int32_t num_nodes, i
                           void *stream);
 
 /*
+ * The same readout (GlobalPool of section 3, "Training Example") for batches of FEW, LARGE graphs -- 8 192 nodes
+ * per graph or more on average, down to one graph that is the whole node set: gnn_graph_pool gives a graph one
+ * thread block, which is slow when a graph has a million nodes.  With a workspace a graph is cut into parts of
+ * about 2 048 nodes, one block each, and the parts are combined in a fixed order (no atomics; sums may differ
+ * from gnn_graph_pool's by rounding order, max is identical).
+ * gnn_graph_pool_workspace_bytes: bytes this needs, 0 when the batch is not of that kind (then gnn_graph_pool_ws
+ * is gnn_graph_pool and d_workspace may be NULL).  d_workspace: 256-byte aligned.  Only enqueues kernels.
+ * Errors: as gnn_graph_pool; GNN_ERR_NULL / GNN_ERR_BAD_SIZE for a missing, small or misaligned workspace.
+ */
+size_t gnn_graph_pool_workspace_bytes(int32_t num_nodes, int32_t num_graphs, int32_t feat_dim);
+gnn_status gnn_graph_pool_ws(const int32_t *d_graph_indicator, int32_t num_nodes, int32_t num_graphs,
+                             const float *d_x, int32_t feat_dim, gnn_aggr aggr, float *d_out,
+                             void *d_workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Debug check of a graph_indicator (section 3, "Graph Data Structures": batching collates small graphs into
  * one graph whose nodes carry the index of their graph): GNN_OK if d_graph_indicator [num_nodes] is
  * non-decreasing with every value in [0, num_graphs), GNN_ERR_INDEX_RANGE for a value outside that range,

@@ -71,6 +71,8 @@ SIGNATURES = {
     "gnn_gatconv_backward": (_c.c_int, [_vp, _vp, _vp, _i32, _vp, _vp, _vp, _i32, _i32, _f32, _vp, _vp, _vp, _vp, _vp,
                                         _vp, _vp, _vp, _sz, _vp]),
     "gnn_graph_pool": (_c.c_int, [_vp, _i32, _i32, _vp, _i32, _c.c_int, _vp, _vp]),
+    "gnn_graph_pool_workspace_bytes": (_c.c_size_t, [_i32, _i32, _i32]),
+    "gnn_graph_pool_ws": (_c.c_int, [_vp, _i32, _i32, _vp, _i32, _c.c_int, _vp, _vp, _c.c_size_t, _vp]),
     "gnn_gin_update": (_c.c_int, [_vp, _vp, _i32, _f32, _vp, _vp]),
     "gnn_batchnorm_workspace_bytes": (_sz, [_i32, _i32]),
     "gnn_batchnorm": (_c.c_int, [_vp, _i32, _i32, _vp, _vp, _f32, _c.c_int, _i32, _vp, _vp, _vp, _vp, _sz, _vp]),
@@ -782,6 +784,24 @@ def graph_pool(graph_indicator: torch.Tensor, num_graphs: int, x: torch.Tensor, 
     rc = lib().gnn_graph_pool(_dev(graph_indicator, torch.int32, "graph_indicator"), n, num_graphs,
                               _dev(x, torch.float32, "x"), f, aggr, _dev(out, torch.float32, "out"), _stream())
     _check(rc, "gnn_graph_pool")
+    return out
+
+
+def graph_pool_ws(graph_indicator: torch.Tensor, num_graphs: int, x: torch.Tensor, aggr: int = AGGR_SUM,
+                  out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """gnn_graph_pool_ws: the readout with several blocks per graph for batches of few, large graphs."""
+    n, f = x.shape
+    if int(graph_indicator.shape[0]) != n:
+        raise ValueError("graph_indicator must have one entry per node")
+    if out is None:
+        out = torch.empty((num_graphs, f), dtype=torch.float32, device=x.device)
+    need = int(lib().gnn_graph_pool_workspace_bytes(n, num_graphs, f))
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=x.device)
+    rc = lib().gnn_graph_pool_ws(_dev(graph_indicator, torch.int32, "graph_indicator"), n, num_graphs,
+                                 _dev(x, torch.float32, "x"), f, aggr, _dev(out, torch.float32, "out"),
+                                 workspace.data_ptr(), workspace.numel(), _stream())
+    _check(rc, "gnn_graph_pool_ws")
     return out
 
 

@@ -5,6 +5,8 @@
 // One block per graph: the run's bounds come from two interleaved block-wide searches in the sorted ids; the
 // block's threads are arranged as (node slot, feature lane), node slots stride over the run and
 // are combined through LDS in slot order, so the result does not depend on scheduling.
+#include <algorithm>
+
 #include "gnn_internal.h"
 
 namespace {
@@ -84,6 +86,85 @@ __global__ __launch_bounds__(kThreads) void pool_kernel(const int32_t *__restric
             if (cnt == 0) acc = 0.0f;
             if (mean && cnt > 0) acc = acc / (float)cnt;
             out[(int64_t)g * F + f] = acc;
+        }
+        __syncthreads();
+    }
+}
+
+// Few, large graphs (needs a workspace): `slices` blocks per graph.
+//   FOLD == false: block (g, s) reduces the s-th of `slices` equal parts of graph g's run of rows of x into
+//                  partial[g * slices + s][:]; block (g, 0) also writes the graph's node count to counts[g].
+//   FOLD == true:  block g reduces the `slices` rows partial[g * slices ..][:] (read through x) and finishes as
+//                  pool_kernel does: an empty graph gives 0, the mean divides by the node count.
+// Threads are (row slot, column-group lane); a lane holds VEC neighbouring columns (VEC = 4: 128-bit loads, F % 4 == 0
+// and 16-byte aligned rows); row slots stride over the rows and are combined through LDS in slot order, parts in
+// part order: the result does not depend on scheduling.
+template <bool MAX, int VEC, bool FOLD>
+__global__ __launch_bounds__(kThreads) void pool_parts_kernel(const int32_t *__restrict__ gi, int32_t N,
+                                                              const float *__restrict__ x, int32_t F,
+                                                              int32_t lanes /* power of two <= 256 */, int mean,
+                                                              int slices, int32_t *__restrict__ counts,
+                                                              float *__restrict__ out)
+{
+    __shared__ float part[kThreads * VEC];
+    int lo, hi;
+    int64_t out_row;
+    int cnt = 1;
+    if constexpr (FOLD) {
+        lo = (int)blockIdx.x * slices;
+        hi = lo + slices;
+        out_row = blockIdx.x;
+        cnt = counts[blockIdx.x];
+    } else {
+        const int g = blockIdx.x / slices, slice = blockIdx.x % slices;
+        block_run_bounds(gi, N, g, &lo, &hi);
+        if (slice == 0 && threadIdx.x == 0) counts[g] = hi - lo;
+        const int64_t len = hi - lo;
+        const int first = lo + (int)(len * slice / slices), last = lo + (int)(len * (slice + 1) / slices);
+        lo = first;
+        hi = last;
+        out_row = blockIdx.x;
+    }
+    const int fl = threadIdx.x % lanes, slot = threadIdx.x / lanes, slots = kThreads / lanes;
+    const int fv = F / VEC;   // column groups
+    for (int f0 = 0; f0 < fv; f0 += lanes) {
+        const int f = f0 + fl;
+        float acc[VEC];
+#pragma unroll
+        for (int c = 0; c < VEC; ++c) acc[c] = MAX ? -INFINITY : 0.0f;
+        if (f < fv) {
+#pragma unroll 4
+            for (int i = lo + slot; i < hi; i += slots) {
+                float v[VEC];
+                if constexpr (VEC == 4) {
+                    const float4 t = *reinterpret_cast<const float4 *>(x + (int64_t)i * F + f * 4);
+                    v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+                } else {
+                    v[0] = x[(int64_t)i * F + f];
+                }
+#pragma unroll
+                for (int c = 0; c < VEC; ++c) acc[c] = MAX ? max_pz(acc[c], v[c]) : acc[c] + v[c];
+            }
+        }
+#pragma unroll
+        for (int c = 0; c < VEC; ++c) part[threadIdx.x * VEC + c] = acc[c];
+        __syncthreads();
+        if (slot == 0 && f < fv) {
+            for (int s = 1; s < slots; ++s) {
+#pragma unroll
+                for (int c = 0; c < VEC; ++c) {
+                    const float v = part[(s * lanes + fl) * VEC + c];
+                    acc[c] = MAX ? max_pz(acc[c], v) : acc[c] + v;
+                }
+            }
+#pragma unroll
+            for (int c = 0; c < VEC; ++c) {
+                if constexpr (FOLD) {
+                    if (cnt == 0) acc[c] = 0.0f;
+                    if (mean && cnt > 0) acc[c] = acc[c] / (float)cnt;
+                }
+                out[out_row * F + f * VEC + c] = acc[c];
+            }
         }
         __syncthreads();
     }
@@ -312,8 +393,60 @@ extern "C" gnn_status gnn_graph_pool_backward(const int32_t *d_graph_indicator, 
                                     d_grad_x, static_cast<hipStream_t>(stream));
 }
 
+namespace {
+
+constexpr int kLargeGraphNodes = 8192;   // average nodes per graph from which a graph is worth several blocks
+constexpr int kSliceNodes = 1024;        // ... of about this many nodes each,
+constexpr int kMaxSlices = 1024;         // at most this many per graph
+
+// Blocks per graph on the path with a workspace (1: the workspace is not used).
+int pool_slices(int32_t num_nodes, int32_t num_graphs)
+{
+    if (num_graphs <= 0 || (int64_t)num_nodes < (int64_t)num_graphs * kLargeGraphNodes) return 1;
+    const int64_t avg = num_nodes / num_graphs;
+    return (int)std::min<int64_t>(kMaxSlices, gnn_div_up(avg, kSliceNodes));
+}
+
+size_t align256(size_t bytes) { return (bytes + 255) & ~(size_t)255; }
+
+gnn_status pool_impl(const int32_t *d_graph_indicator, int32_t num_nodes, int32_t num_graphs, const float *d_x,
+                     int32_t feat_dim, gnn_aggr aggr, float *d_out, void *d_workspace, size_t workspace_bytes,
+                     void *stream);
+
+}  // namespace
+
+extern "C" size_t gnn_graph_pool_workspace_bytes(int32_t num_nodes, int32_t num_graphs, int32_t feat_dim)
+{
+    if (num_nodes <= 0 || num_graphs <= 0 || feat_dim <= 0) return 0;
+    const int slices = pool_slices(num_nodes, num_graphs);
+    if (slices <= 1) return 0;
+    return align256((size_t)num_graphs * slices * feat_dim * sizeof(float)) + align256((size_t)num_graphs * sizeof(int32_t));
+}
+
 extern "C" gnn_status gnn_graph_pool(const int32_t *d_graph_indicator, int32_t num_nodes, int32_t num_graphs,
                                      const float *d_x, int32_t feat_dim, gnn_aggr aggr, float *d_out, void *stream)
+{
+    return pool_impl(d_graph_indicator, num_nodes, num_graphs, d_x, feat_dim, aggr, d_out, nullptr, 0, stream);
+}
+
+extern "C" gnn_status gnn_graph_pool_ws(const int32_t *d_graph_indicator, int32_t num_nodes, int32_t num_graphs,
+                                        const float *d_x, int32_t feat_dim, gnn_aggr aggr, float *d_out,
+                                        void *d_workspace, size_t workspace_bytes, void *stream)
+{
+    const size_t need = gnn_graph_pool_workspace_bytes(num_nodes, num_graphs, feat_dim);
+    if (need > 0) {
+        if (!d_workspace) return GNN_ERR_NULL;
+        if (workspace_bytes < need || (reinterpret_cast<uintptr_t>(d_workspace) & 255u) != 0) return GNN_ERR_BAD_SIZE;
+    }
+    return pool_impl(d_graph_indicator, num_nodes, num_graphs, d_x, feat_dim, aggr, d_out, need ? d_workspace : nullptr,
+                     need, stream);
+}
+
+namespace {
+
+gnn_status pool_impl(const int32_t *d_graph_indicator, int32_t num_nodes, int32_t num_graphs, const float *d_x,
+                     int32_t feat_dim, gnn_aggr aggr, float *d_out, void *d_workspace, size_t workspace_bytes,
+                     void *stream)
 {
     if (!d_out) return GNN_ERR_NULL;
     if (num_nodes < 0 || num_graphs <= 0 || feat_dim <= 0) return GNN_ERR_BAD_SIZE;
@@ -346,6 +479,37 @@ extern "C" gnn_status gnn_graph_pool(const int32_t *d_graph_indicator, int32_t n
         GNN_LAUNCH_CHECK();
         return GNN_OK;
     }
+    // few large graphs and a workspace: several blocks per graph, parts combined in a fixed order afterwards
+    const int slices = d_workspace ? pool_slices(num_nodes, num_graphs) : 1;
+    if (slices > 1) {
+        (void)workspace_bytes;   // checked by the caller against gnn_graph_pool_workspace_bytes
+        float *partial = static_cast<float *>(d_workspace);
+        int32_t *counts = reinterpret_cast<int32_t *>(static_cast<char *>(d_workspace) +
+                                                      align256((size_t)num_graphs * slices * feat_dim * sizeof(float)));
+        const bool vec4 = feat_dim % 4 == 0 && (reinterpret_cast<uintptr_t>(d_x) & 15u) == 0;   // stores are scalar
+        const int groups = vec4 ? feat_dim / 4 : feat_dim;
+        int lanes = 1;
+        while (lanes < groups && lanes < kThreads) lanes <<= 1;
+        const dim3 pgrid((unsigned)((int64_t)num_graphs * slices)), fgrid((unsigned)num_graphs);
+#define GNN_POOL_PARTS(MAXV, VECV)                                                                                   \
+    do {                                                                                                            \
+        hipLaunchKernelGGL((pool_parts_kernel<MAXV, VECV, false>), pgrid, dim3(kThreads), 0, s, d_graph_indicator,  \
+                           num_nodes, d_x, feat_dim, lanes, 0, slices, counts, partial);                            \
+        GNN_LAUNCH_CHECK();                                                                                         \
+        hipLaunchKernelGGL((pool_parts_kernel<MAXV, VECV, true>), fgrid, dim3(kThreads), 0, s,                      \
+                           (const int32_t *)nullptr, 0, partial, feat_dim, lanes, mean, slices, counts, d_out);     \
+        GNN_LAUNCH_CHECK();                                                                                         \
+    } while (0)
+        if (aggr == GNN_AGGR_MAX) {
+            if (vec4) GNN_POOL_PARTS(true, 4);
+            else GNN_POOL_PARTS(true, 1);
+        } else {
+            if (vec4) GNN_POOL_PARTS(false, 4);
+            else GNN_POOL_PARTS(false, 1);
+        }
+#undef GNN_POOL_PARTS
+        return GNN_OK;
+    }
     int lanes = 1;
     while (lanes < feat_dim && lanes < kThreads) lanes <<= 1;
     if (aggr == GNN_AGGR_MAX)
@@ -357,3 +521,5 @@ extern "C" gnn_status gnn_graph_pool(const int32_t *d_graph_indicator, int32_t n
     GNN_LAUNCH_CHECK();
     return GNN_OK;
 }
+
+}  // namespace

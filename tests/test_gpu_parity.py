@@ -1104,6 +1104,43 @@ def test_pool_one_big_graph(gnn):
             assert_close_sabs(got, ref, sabs, what=f"big pool aggr={aggr}")
 
 
+@pytest.mark.parametrize("n,f,bounds", [
+    (300_000, 64, [0, 300_000]),                      # one graph that is the whole node set
+    (400_000, 48, [0, 250_000, 250_000, 399_999, 400_000]),   # a large, an empty, a large and a one-node graph
+    (70_000, 5, [0, 3, 70_000]),                      # a graph smaller than the number of its parts
+    (40_000, 32, [0, 20_000, 40_000]),                # too small for parts: the plain path, no workspace needed
+])
+def test_pool_with_workspace_few_large_graphs(gnn, n, f, bounds):
+    """gnn_graph_pool_ws: several blocks per graph, parts combined in a fixed order; against the oracle, and
+    bit-identical from run to run.  Max equals gnn_graph_pool bit for bit."""
+    ng = len(bounds) - 1
+    x = synth.normal_f32(60 + f, 2, n * f).reshape(n, f)
+    gi = np.zeros(n, np.int32)
+    for g_ in range(ng):
+        gi[bounds[g_]:bounds[g_ + 1]] = g_
+    gid, xd = dev(gi), dev(x)
+    need = int(gnn.lib().gnn_graph_pool_workspace_bytes(n, ng, f))
+    assert (need > 0) == (n >= 8192 * ng)
+    for aggr in (AGGR_SUM, AGGR_MEAN, AGGR_MAX):
+        ref, sabs = oracle.graph_pool(gi, ng, x, aggr, with_sabs=True)
+        got = gnn.graph_pool_ws(gid, ng, xd, aggr)
+        again = gnn.graph_pool_ws(gid, ng, xd, aggr)
+        assert torch.equal(got, again)
+        if aggr == AGGR_MAX:
+            np.testing.assert_array_equal(host(got), ref)
+            assert torch.equal(got, gnn.graph_pool(gid, ng, xd, aggr))
+        else:
+            assert_close_sabs(host(got), ref, sabs, what=f"pool with workspace aggr={aggr}")
+    if need:
+        out = torch.empty((ng, f), dtype=torch.float32, device="cuda")
+        small = torch.empty(need - 256, dtype=torch.uint8, device="cuda")
+        rc = gnn.lib().gnn_graph_pool_ws(gid.data_ptr(), n, ng, xd.data_ptr(), f, AGGR_SUM, out.data_ptr(),
+                                         small.data_ptr(), small.numel(), None)
+        assert rc == 2      # workspace too small
+        rc = gnn.lib().gnn_graph_pool_ws(gid.data_ptr(), n, ng, xd.data_ptr(), f, AGGR_SUM, out.data_ptr(), None, 0, None)
+        assert rc == 1      # no workspace
+
+
 def test_degenerate_graphs_through_every_entry_point(gnn):
     """No edges at all, a single node, a single self-loop: every entry point returns what the oracle
     returns (zeros for empty neighbourhoods, no fault, no stale memory)."""
