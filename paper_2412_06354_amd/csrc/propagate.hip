@@ -890,6 +890,12 @@ gnn_status gnn_apply_edges(const gnn_graph *g, const float *d_x, int32_t feat_di
     const int64_t total = g->num_edges * (vec4 ? F / 4 : F);
     const dim3 grid((unsigned)std::min<int64_t>(gnn_div_up(total, kThreads), 256 * 128)), block(kThreads);
     hipStream_t s = static_cast<hipStream_t>(stream);
+    if (kmsg == kMsgMulScalar && e_order == GNN_EDGE_ORDER_COO && g->route && gnn_aligned16(d_e)) {
+        // one weight per edge in the caller's order: moved to CSR order in two streaming passes first
+        GNN_TRY(gnn_route_coo_to_csr(g, d_e, g->route->staged, s));
+        d_e = g->route->staged;
+        e_order = GNN_EDGE_ORDER_CSR;
+    }
     const int e_coo = (e_order == GNN_EDGE_ORDER_COO), m_coo = (m_order == GNN_EDGE_ORDER_COO);
 #define GNN_APPLY(VEC, MSG)                                                                                      \
     hipLaunchKernelGGL((apply_edges_kernel<VEC, MSG>), grid, block, 0, s, g->colidx, g->rowidx, g->perm, g->num_edges, \

@@ -112,6 +112,10 @@ def test_compute_calls_take_the_route(gnn, aggr):
     np.testing.assert_array_equal(host(e_d), e)
     np.testing.assert_array_equal(host(gnn.propagate(routed, x_d, e_d, MSG_E_MUL_XJ, aggr)), host(out_routed))
 
+    if aggr == AGGR_SUM:   # the un-fused message tensor (rounded products: bit-exact against the oracle)
+        m_ref = oracle.apply_edges(wl.src, n, x, e, MSG_E_MUL_XJ)
+        np.testing.assert_array_equal(host(gnn.apply_edges(routed, x_d, e_d, MSG_E_MUL_XJ)), m_ref)
+        np.testing.assert_array_equal(host(gnn.apply_edges(plain, x_d, e_d, MSG_E_MUL_XJ)), m_ref)
     np.testing.assert_array_equal(host(out_routed), host(out_plain))
     np.testing.assert_array_equal(host(gx_routed), host(gx_plain))
     np.testing.assert_array_equal(host(ge_routed), host(ge_plain))
