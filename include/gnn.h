@@ -445,8 +445,8 @@ gnn_status gnn_gatconv(const gnn_graph *g, const float *d_x, int32_t f_in, const
  * the roles of src and dst exchanged: gnn_build_csr(dst, src, ...).  The derivative of the leaky
  * ReLU at exactly 0 is negative_slope (the branch the forward takes).  No atomics: results are
  * bitwise reproducible.
- * Restriction: with L = ch / 4 when ch is a multiple of 4, else ch (the lanes a head occupies): L <= 64, and
- * L a power of two or heads * L <= 64; otherwise GNN_ERR_UNSUPPORTED (e.g. 3 heads of 30 channels).
+ * Restriction: with L = ch / 4 when ch is a multiple of 4, else ch (the lanes a head occupies): L <= 64,
+ * otherwise GNN_ERR_UNSUPPORTED (e.g. heads of 65 channels).
  * d_workspace: at least gnn_gatconv_backward_workspace_bytes(N, f_in, heads, ch) bytes, 256-byte aligned.
  */
 size_t gnn_gatconv_backward_workspace_bytes(int32_t num_nodes, int32_t f_in, int32_t heads, int32_t ch);

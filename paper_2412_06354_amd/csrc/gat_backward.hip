@@ -35,6 +35,8 @@ struct GatBwdParams {
     const int32_t *small_rows, *item_row, *item_start, *item_slot, *split_rows, *split_slot0;
     int32_t n_small, n_items, n_split, chunk, HC, H, ch, lh, item_blocks;
     int32_t lh_pow2;   // lh is a power of two: a head's lanes are combined by an xor tree, else by a loop over them
+    int32_t pass_lanes;   // lanes of a row's sub-group that hold columns in one pass over the row: all of them, or
+                          // (lh no power of two) the largest multiple of lh, so that no head straddles two passes
     float slope;
 };
 
@@ -152,9 +154,9 @@ __device__ __forceinline__ void bwd_short_rows(const GatBwdParams &p, int block)
 #pragma unroll
     for (int off = LPR; off < 64; off <<= 1) wmax = max(wmax, __shfl_xor(wmax, off, 64));
 
-    for (int cb = 0; cb * LPR * VEC < p.HC; ++cb) {
-        const int col = (cb * LPR + sl_) * VEC;
-        const bool colok = have && col < p.HC;
+    for (int cb = 0; cb * p.pass_lanes * VEC < p.HC; ++cb) {
+        const int col = (cb * p.pass_lanes + sl_) * VEC;
+        const bool colok = have && sl_ < p.pass_lanes && col < p.HC;
         const int hd = colok ? col / p.ch : 0;
         Lane<VEC> ln;
         lane_init<VEC, BY_SRC, RECOMP>(ln, p, colok, row, col, hd);
@@ -203,9 +205,9 @@ __device__ __forceinline__ void bwd_long_pieces(const GatBwdParams &p, int block
     const int slot = p.item_slot[it];
     const int end = min(start + p.chunk, p.rowptr[row + 1]);
 
-    for (int cb = 0; cb * LPR * VEC < p.HC; ++cb) {
-        const int col = (cb * LPR + sl_) * VEC;
-        const bool colok = col < p.HC;
+    for (int cb = 0; cb * p.pass_lanes * VEC < p.HC; ++cb) {
+        const int col = (cb * p.pass_lanes + sl_) * VEC;
+        const bool colok = sl_ < p.pass_lanes && col < p.HC;
         const int hd = colok ? col / p.ch : 0;
         Lane<VEC> ln;
         lane_init<VEC, BY_SRC, RECOMP>(ln, p, colok, row, col, hd);
@@ -279,9 +281,9 @@ __global__ __launch_bounds__(kThreads) void gat_backward_merge_kernel(const GatB
     const int slot0 = p.split_slot0[s];
     const int deg = p.rowptr[row + 1] - p.rowptr[row];
     const int pieces = (deg + p.chunk - 1) / p.chunk;
-    for (int cb = 0; cb * LPR * VEC < p.HC; ++cb) {
-        const int col = (cb * LPR + sl_) * VEC;
-        if (col >= p.HC) continue;
+    for (int cb = 0; cb * p.pass_lanes * VEC < p.HC; ++cb) {
+        const int col = (cb * p.pass_lanes + sl_) * VEC;
+        if (sl_ >= p.pass_lanes || col >= p.HC) continue;
         Lane<VEC> ln;
         ln.acc_s = 0.0f;
 #pragma unroll
@@ -434,14 +436,18 @@ gnn_status run_pass(const gnn_graph *g, GatBwdParams p, bool vec4, hipStream_t s
         p.slot_s = scratch;
         p.slot_vec = scratch + (size_t)g->n_slots * p.HC;
     }
+    // lanes of a sub-group used per pass over a row (a sub-group is never narrower than a head)
+    auto lanes = [&p](int lpr) { p.pass_lanes = p.lh_pow2 ? lpr : (lpr / p.lh) * p.lh; };
     if (vec4) {
         const int cols = p.HC / 4;
-        if (cols <= 8) return launch_pass<8, 4, BY_SRC>(p, s);
-        if (cols <= 16) return launch_pass<16, 4, BY_SRC>(p, s);
-        if (cols <= 32) return launch_pass<32, 4, BY_SRC>(p, s);
+        if (cols <= 8) { lanes(8); return launch_pass<8, 4, BY_SRC>(p, s); }
+        if (cols <= 16) { lanes(16); return launch_pass<16, 4, BY_SRC>(p, s); }
+        if (cols <= 32) { lanes(32); return launch_pass<32, 4, BY_SRC>(p, s); }
+        lanes(64);
         return launch_pass<64, 4, BY_SRC>(p, s);
     }
-    if (p.HC <= 16) return launch_pass<16, 1, BY_SRC>(p, s);
+    if (p.HC <= 16) { lanes(16); return launch_pass<16, 1, BY_SRC>(p, s); }
+    lanes(64);
     return launch_pass<64, 1, BY_SRC>(p, s);
 }
 
@@ -498,9 +504,8 @@ gnn_status gnn_gatconv_backward(const gnn_graph *g, const gnn_graph *g_by_source
     const int HC = heads * ch;
     const bool vec4 = (ch % 4 == 0) && ((reinterpret_cast<uintptr_t>(d_grad_out) & 15u) == 0);
     const int lh = vec4 ? ch / 4 : ch;   // lanes that share a head
-    // a head's lanes must lie in one wavefront pass over the row: always so when their number is a power of two (at
-    // most 64), else only when the whole row fits one pass
-    if (lh > 64 || (!is_pow2(lh) && heads * lh > 64)) return GNN_ERR_UNSUPPORTED;
+    // a head's lanes must lie in one wavefront (passes over a row start at head boundaries)
+    if (lh > 64) return GNN_ERR_UNSUPPORTED;
     const Layout l = layout(N, f_in, heads, ch);
     if (workspace_bytes < l.total) return GNN_ERR_BAD_SIZE;
     if (reinterpret_cast<uintptr_t>(d_workspace) & 255u) return GNN_ERR_BAD_SIZE;

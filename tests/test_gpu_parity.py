@@ -948,7 +948,8 @@ def test_gatconv(gnn, heads, ch, f_in):
 
 
 @pytest.mark.parametrize("heads,ch,f_in", [(8, 8, 100), (2, 4, 16), (1, 64, 32), (4, 16, 24), (3, 2, 10), (2, 1, 6),
-                                           (2, 128, 40), (3, 5, 12), (8, 5, 20), (2, 30, 9), (5, 12, 16), (4, 3, 7)])
+                                           (2, 128, 40), (3, 5, 12), (8, 5, 20), (2, 30, 9), (5, 12, 16), (4, 3, 7),
+                                           (3, 30, 8), (12, 24, 10), (9, 10, 6)])
 def test_gatconv_backward(gnn, heads, ch, f_in):
     wl = synth.config4_gat(num_nodes=5000, num_edges=120_000, f_in=f_in, heads=heads, ch=ch, cap=2500.0)
     p, n, hc = wl.params, wl.num_nodes, heads * ch
@@ -994,11 +995,11 @@ def test_gatconv_backward(gnn, heads, ch, f_in):
 
 
 def test_gatconv_backward_rejects_unsupported_head_width(gnn):
-    wl = synth.config4_gat(num_nodes=300, num_edges=2000, f_in=6, heads=3, ch=30, cap=100.0)   # 90 lanes per row
+    wl = synth.config4_gat(num_nodes=300, num_edges=2000, f_in=6, heads=2, ch=65, cap=100.0)   # a head wider than a wavefront
     p, n = wl.params, wl.num_nodes
     g = gnn.build_csr(dev(wl.src), dev(wl.dst), n)
     gt = gnn.build_csr(dev(wl.dst), dev(wl.src), n)
-    stats = torch.empty((n, 3, 2), dtype=torch.float32, device="cuda")
+    stats = torch.empty((n, 2, 2), dtype=torch.float32, device="cuda")
     args = (dev(wl.x), dev(p["w"]), dev(p["a_src"]), dev(p["a_dst"]))
     out = gnn.gatconv(g, *args, 0.2, softmax_stats=stats)
     with pytest.raises(RuntimeError):
