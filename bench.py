@@ -697,6 +697,23 @@ def run_batched(args, torch, gnn, synth):
     line["roofline"] = hbm_roofline(bytes_gin / (ms_gin * 1e-3) / 1e9, "propagate_kernel<8,4,copy_xj,sum> with self term")
     line["extra"] = {"gin_ms": ms_gin, "pool_ms": ms_pool, "pool_GBs": bytes_pool / (ms_pool * 1e-3) / 1e9,
                      "note": "the whole problem (13 MB of features) fits the caches: launch latency dominates"}
+    if not args.no_extra:
+        # the other end of pooling: few, large graphs (one graph of 1 M nodes, 8 graphs of 125 000 nodes), F = 64 --
+        # one block per graph (gnn_graph_pool) against several blocks per graph (gnn_graph_pool_ws)
+        big_n, big_f = 1_000_000, 64
+        xb = torch.randn((big_n, big_f), dtype=torch.float32, device="cuda")
+        big = {}
+        for graphs in (1, 8):
+            gib = (torch.arange(big_n, device="cuda") // (big_n // graphs)).clamp(max=graphs - 1).to(torch.int32)
+            ob = torch.empty((graphs, big_f), dtype=torch.float32, device="cuda")
+            wsb = torch.empty(int(gnn.lib().gnn_graph_pool_workspace_bytes(big_n, graphs, big_f)), dtype=torch.uint8,
+                              device="cuda")
+            t_ws = time_calls(torch, lambda: gnn.graph_pool_ws(gib, graphs, xb, gnn.AGGR_SUM, out=ob, workspace=wsb), 20, 3)
+            t_one = time_calls(torch, lambda: gnn.graph_pool(gib, graphs, xb, gnn.AGGR_SUM, out=ob), 3, 1)
+            big[f"{graphs}_graphs"] = {"pool_ws_ms": t_ws, "pool_ms": t_one,
+                                       "pool_ws_GBs": big_n * big_f * 4 / (t_ws * 1e-3) / 1e9}
+        line["extra"]["large_graphs_1M_nodes_F64"] = big
+        del xb
     if not args.no_cpu_baseline:
         import oracle
         t0 = time.perf_counter()
