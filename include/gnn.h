@@ -28,13 +28,15 @@
  * called; the caller keeps that device current for later calls on the graph.
  *
  * Which calls allocate or synchronise: the graph builders (gnn_build_csr*, which read back a flag and the list
- * sizes), gnn_graph_reserve, gnn_graph_destroy, gnn_release_cached_memory and gnn_check_graph_indicator.
+ * sizes), gnn_graph_reserve, gnn_graph_build_edge_route, gnn_graph_destroy, gnn_release_cached_memory and
+ * gnn_check_graph_indicator.
  * Every other call only enqueues kernels on `stream`: it never allocates, frees or synchronises, so it may be
  * recorded into a HIP graph from its first use on.
  *
  * Concurrency: a graph handle carries scratch memory for rows that are split over several wavefronts and for
  * per-row softmax statistics (a part of the graph's one allocation, sized when the graph is built; see
- * gnn_graph_reserve), so compute calls on ONE handle must not overlap: issue them on one stream, or order them
+ * gnn_graph_reserve) and, after gnn_graph_build_edge_route, the route's buffers, so compute calls on ONE handle
+ * must not overlap: issue them on one stream, or order them
  * with events.  Calls on different handles are independent and may come from different host threads; the
  * process-wide buffer that graph builds share is handed to one build at a time (a concurrent build allocates
  * its own temporaries).  Caller-provided workspaces follow the same rule as the handle: one call at a time
