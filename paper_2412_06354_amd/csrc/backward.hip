@@ -224,8 +224,13 @@ gnn_status gnn_launch_edge_dot(const gnn_graph *g, const float *d_x_src, const f
                                float *d_out, gnn_edge_order out_order, void *stream)
 {
     if (g->num_edges == 0) return GNN_OK;
-    return edge_products(g, feat_dim, false, d_x_src, d_y_dst, nullptr, d_out, static_cast<hipStream_t>(stream),
-                         out_order == GNN_EDGE_ORDER_CSR);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (out_order == GNN_EDGE_ORDER_COO && g->route && gnn_aligned16(d_out)) {
+        // one scalar per edge: written in CSR order (a stream), moved to the caller's order by the route
+        GNN_TRY(edge_products(g, feat_dim, false, d_x_src, d_y_dst, nullptr, g->route->staged, s, true));
+        return gnn_route_csr_to_coo(g, g->route->staged, d_out, s);
+    }
+    return edge_products(g, feat_dim, false, d_x_src, d_y_dst, nullptr, d_out, s, out_order == GNN_EDGE_ORDER_CSR);
 }
 
 extern "C" {

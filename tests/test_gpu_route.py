@@ -116,6 +116,12 @@ def test_compute_calls_take_the_route(gnn, aggr):
         m_ref = oracle.apply_edges(wl.src, n, x, e, MSG_E_MUL_XJ)
         np.testing.assert_array_equal(host(gnn.apply_edges(routed, x_d, e_d, MSG_E_MUL_XJ)), m_ref)
         np.testing.assert_array_equal(host(gnn.apply_edges(plain, x_d, e_d, MSG_E_MUL_XJ)), m_ref)
+        # one dot product per edge: the same bits with and without a route, the oracle's value within its bar
+        from oracle import MSG_XI_DOT_XJ
+        d_ref, d_sabs = oracle.apply_edges(wl.src, n, x, None, MSG_XI_DOT_XJ, dst=wl.dst, with_sabs=True)
+        d_routed = gnn.apply_edges(routed, x_d, None, MSG_XI_DOT_XJ)
+        assert torch.equal(d_routed, gnn.apply_edges(plain, x_d, None, MSG_XI_DOT_XJ))
+        assert_close_sabs(host(d_routed).reshape(-1, 1), d_ref, d_sabs, what="routed edge dot")
     np.testing.assert_array_equal(host(out_routed), host(out_plain))
     np.testing.assert_array_equal(host(gx_routed), host(gx_plain))
     np.testing.assert_array_equal(host(ge_routed), host(ge_plain))
