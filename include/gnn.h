@@ -230,8 +230,9 @@ gnn_status gnn_edge_data_to_coo(const gnn_graph *g, const float *d_e_csr, int32_
  * random 4-byte access per edge, and each costs a whole 128-byte memory line.  This call splits the permutation,
  * once, into two passes that only move data inside 16 384-entry ranges held in on-chip memory or in contiguous
  * runs; afterwards gnn_edge_data_to_csr / gnn_edge_data_to_coo with e_dim == 1, gnn_propagate, gnn_apply_edges
- * and gnn_propagate_backward with one weight per edge in COO order, the per-edge dot product of gnn_apply_edges
- * and the edge gradient of gnn_propagate_backward take the route (16-byte aligned buffers; anything else keeps the direct path).  Results are bit-identical: the
+ * and gnn_propagate_backward with one weight per edge in COO order, the per-edge dot product of gnn_apply_edges,
+ * the edge gradient of gnn_propagate_backward and gnn_segment_softmax(_backward) with one head in COO order
+ * take the route (16-byte aligned buffers; anything else keeps the direct path).  Results are bit-identical: the
  * route only moves values.
  * Cost: 16 bytes of device memory per edge, owned by the graph (three index arrays, an intermediate buffer and a
  * CSR-ordered staging buffer for the compute calls; like the scratch memory it is shared by all calls on the graph,

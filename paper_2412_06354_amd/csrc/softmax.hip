@@ -328,6 +328,18 @@ gnn_status run_softmax(const gnn_graph *g, const float *d_in, const float *d_in2
     if (g->num_edges == 0) return GNN_OK;
     if (!d_in || !d_out || (BWD && !d_in2)) return GNN_ERR_NULL;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    if (heads == 1 && order == GNN_EDGE_ORDER_COO && g->route && gnn_aligned16(d_in) && gnn_aligned16(d_out) &&
+        (!BWD || gnn_aligned16(d_in2))) {
+        // One score per edge in the caller's order: a gather through perm would cost a memory line per edge.  With an
+        // edge route the inputs are moved to CSR order in streams (the second one of the backward into the output
+        // array, which is free until the end), the CSR-ordered kernels run in place on the route's staging buffer
+        // (element-wise: every thread reads its own element before it writes it), and the result is moved back.
+        float *staged = g->route->staged;
+        GNN_TRY(gnn_route_coo_to_csr(g, d_in, staged, s));
+        if (BWD) GNN_TRY(gnn_route_coo_to_csr(g, d_in2, d_out, s));
+        GNN_TRY((run_softmax<BWD>(g, staged, BWD ? d_out : nullptr, 1, GNN_EDGE_ORDER_CSR, staged, stream)));
+        return gnn_route_csr_to_coo(g, staged, d_out, s);
+    }
     const size_t stat_floats = 2 * ((size_t)g->num_nodes + (size_t)g->n_slots) * heads;
     float *scratch = nullptr;
     GNN_TRY(gnn_graph_scratch(g, stat_floats, &scratch));

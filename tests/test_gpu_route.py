@@ -9,7 +9,7 @@ torch = pytest.importorskip("torch")
 import oracle
 from oracle import AGGR_MEAN, AGGR_SUM, MSG_E_MUL_XJ
 from paper_2412_06354_amd import synth
-from util import assert_close_sabs
+from util import assert_close_rel, assert_close_sabs
 
 pytestmark = pytest.mark.gpu
 
@@ -131,3 +131,28 @@ def test_compute_calls_take_the_route(gnn, aggr):
     back = oracle.propagate_backward(wl.src, wl.dst, n, x, grad_out, e, MSG_E_MUL_XJ, aggr, with_sabs=True)
     assert_close_sabs(host(gx_routed), back["grad_x"], back["sabs_x"], what="routed grad_x")
     assert_close_sabs(host(ge_routed).reshape(-1, 1), back["grad_e"], back["sabs_e"], what="routed grad_e")
+
+
+def test_single_head_softmax_takes_the_route(gnn):
+    """Segment softmax with one score per edge in COO order, forward and backward: the same bits with and without
+    a route (the CSR-ordered kernels run on the moved scores), the oracle's values at its bar, inputs untouched."""
+    wl = synth.config2_weighted(num_nodes=20_000, num_edges=300_000, feat=4, cap=6000.0)
+    n, e = wl.num_nodes, wl.num_edges
+    scores = (3.0 * synth.normal_f32(91, 2, e)).reshape(e, 1)
+    dalpha = synth.normal_f32(92, 2, e).reshape(e, 1)
+    src_d, dst_d = dev(wl.src), dev(wl.dst)
+    plain, routed = gnn.build_csr(src_d, dst_d, n), gnn.build_csr(src_d, dst_d, n)
+    routed.build_edge_route()
+    s_d, da_d = dev(scores), dev(dalpha)
+    a_plain, a_routed = gnn.segment_softmax(plain, s_d), gnn.segment_softmax(routed, s_d)
+    assert torch.equal(a_plain, a_routed)
+    np.testing.assert_array_equal(host(s_d), scores)
+    assert_close_rel(host(a_routed), oracle.segment_softmax(wl.dst, n, scores), what="routed softmax")
+    g_plain = gnn.segment_softmax_backward(plain, a_plain, da_d)
+    g_routed = gnn.segment_softmax_backward(routed, a_routed, da_d)
+    assert torch.equal(g_plain, g_routed)
+    np.testing.assert_array_equal(host(da_d), dalpha)
+    assert torch.equal(a_routed, a_plain)
+    # several heads keep the direct path on a graph with a route
+    s8 = (3.0 * synth.normal_f32(93, 2, e * 8)).reshape(e, 8)
+    assert torch.equal(gnn.segment_softmax(routed, dev(s8)), gnn.segment_softmax(plain, dev(s8)))
