@@ -236,6 +236,27 @@ def test_batch_build_of_many_small_snapshots(gnn):
         g.close()
 
 
+def test_batch_build_beyond_one_launch_group(gnn):
+    """More snapshots than one launch takes in its second grid dimension (32 768): the batch is built in groups;
+    handles on both sides of the group boundary, the first and the last equal the oracle's CSR."""
+    n, t_snap, per = 5, 33_000, 3
+    src_all, dst_all = synth.multigraph_uniform(n, t_snap * per, seed=77)
+    src_d, dst_d = dev(src_all), dev(dst_all)
+    srcs = [src_d[i * per:(i + 1) * per] for i in range(t_snap)]
+    dsts = [dst_d[i * per:(i + 1) * per] for i in range(t_snap)]
+    graphs = gnn.build_csr_batch(srcs, dsts, n)
+    assert len(graphs) == t_snap
+    for t in (0, 1, 32_766, 32_767, 32_768, 32_769, t_snap - 1):
+        rowptr, colidx, perm, indeg = oracle.build_csr(src_all[t * per:(t + 1) * per], dst_all[t * per:(t + 1) * per], n)
+        g = graphs[t]
+        np.testing.assert_array_equal(host(g.rowptr), rowptr, err_msg=f"snapshot {t}")
+        np.testing.assert_array_equal(host(g.colidx), colidx, err_msg=f"snapshot {t}")
+        np.testing.assert_array_equal(host(g.perm), perm, err_msg=f"snapshot {t}")
+        assert g.work_sizes()["small_rows"] == n
+    for g in graphs:
+        g.close()
+
+
 def test_check_graph_indicator(gnn):
     wl = synth.config3_batched(num_graphs=200, feat=4)
     gi = wl.graph_indicator
