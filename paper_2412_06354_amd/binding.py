@@ -170,9 +170,8 @@ class Graph:
     def _view(self, ptr: int, count: int) -> torch.Tensor:
         """Copy of a library-owned int32 device array as a tensor."""
         out = torch.empty(count, dtype=torch.int32, device=self.device)
-        if count:
-            torch.cuda.current_stream().synchronize()
-            _hip_memcpy_d2d(out.data_ptr(), ptr, 4 * count)
+        if count:   # ordered on the caller's stream, like the work that fills and later reads the arrays
+            _hip_memcpy_d2d(out.data_ptr(), ptr, 4 * count, _stream())
         return out
 
     @property
@@ -221,15 +220,17 @@ class Graph:
 _hip = None
 
 
-def _hip_memcpy_d2d(dst: int, src: int, nbytes: int):
+def _hip_memcpy_d2d(dst: int, src: int, nbytes: int, stream: int):
+    """Device-to-device copy enqueued on `stream` (a plain hipMemcpy between device buffers is ordered with the
+    null stream only, which the non-blocking streams PyTorch creates do not wait for)."""
     global _hip
     if _hip is None:
         _hip = ctypes.CDLL("libamdhip64.so")
-        _hip.hipMemcpy.restype = ctypes.c_int
-        _hip.hipMemcpy.argtypes = [_vp, _vp, _sz, ctypes.c_int]
-    rc = _hip.hipMemcpy(dst, src, nbytes, 3)  # hipMemcpyDeviceToDevice
+        _hip.hipMemcpyAsync.restype = ctypes.c_int
+        _hip.hipMemcpyAsync.argtypes = [_vp, _vp, _sz, ctypes.c_int, _vp]
+    rc = _hip.hipMemcpyAsync(dst, src, nbytes, 3, stream)  # hipMemcpyDeviceToDevice
     if rc != 0:
-        raise RuntimeError(f"hipMemcpy failed ({rc})")
+        raise RuntimeError(f"hipMemcpyAsync failed ({rc})")
 
 
 def build_csr(src: torch.Tensor, dst: torch.Tensor, num_nodes: int, small_max_degree: int = 0,

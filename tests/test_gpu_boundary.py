@@ -257,6 +257,44 @@ def test_batch_build_beyond_one_launch_group(gnn):
         g.close()
 
 
+def test_concurrent_builds_and_calls_from_two_threads(gnn):
+    """Two host threads, each with its own stream, build graphs and run propagate at the same time: the buffer the
+    builds share is handed to one build at a time (the other allocates its own temporaries), handles are
+    independent, and every result equals the oracle's."""
+    import threading
+    n, f = 3000, 16
+    work = []
+    for t in range(2):
+        src, dst = synth.chung_lu_directed(n, 60_000, 1.0, 900.0, 700 + t)
+        x = synth.normal_f32(710 + t, 2, n * f).reshape(n, f)
+        work.append((src, dst, x, oracle.build_csr(src, dst, n), oracle.propagate(src, dst, n, x, None, MSG_COPY_XJ, AGGR_MAX)))
+    errors = []
+
+    def body(t):
+        try:
+            src, dst, x, (rowptr, colidx, perm, _), ref = work[t]
+            stream = torch.cuda.Stream()
+            with torch.cuda.stream(stream):
+                sd, dd, xd = dev(src), dev(dst), dev(x)
+                for _ in range(15):
+                    g = gnn.build_csr(sd, dd, n)
+                    out = gnn.propagate(g, xd, None, MSG_COPY_XJ, AGGR_MAX)
+                    stream.synchronize()
+                    assert np.array_equal(host(g.rowptr), rowptr) and np.array_equal(host(g.colidx), colidx)
+                    assert np.array_equal(host(g.perm), perm)
+                    assert np.array_equal(host(out).view(np.uint32), ref.view(np.uint32))
+                    g.close()
+        except Exception as exc:   # reported by the main thread
+            errors.append((t, repr(exc)))
+
+    threads = [threading.Thread(target=body, args=(t,)) for t in range(2)]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join()
+    assert not errors, errors
+
+
 def test_check_graph_indicator(gnn):
     wl = synth.config3_batched(num_graphs=200, feat=4)
     gi = wl.graph_indicator
