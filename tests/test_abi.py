@@ -85,3 +85,39 @@ def test_product_never_imports_the_oracle():
     for name in ("__init__.py", "gnn_oracle.c"):
         text = open(os.path.join(ROOT, "oracle", name)).read()
         assert "paper_2412_06354_amd" not in text and "libgnn_mi355x" not in text, name
+
+
+def test_header_is_plain_c_and_the_library_links_from_c(tmp_path):
+    """include/gnn.h compiles as strict C99 and a C program linked against the library runs its host-side checks."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no C compiler")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    lib_dir = os.path.join(root, "paper_2412_06354_amd")
+    if not os.path.exists(os.path.join(lib_dir, "libgnn_mi355x.so")):
+        pytest.skip("library not built")
+    src = tmp_path / "use_abi.c"
+    src.write_text(r"""
+#include <stdio.h>
+#include <string.h>
+#include "gnn.h"
+int main(void)
+{
+    gnn_graph *g = NULL;
+    if (strcmp(gnn_status_string(GNN_OK), "ok") != 0) return 1;
+    if (gnn_build_csr(NULL, NULL, 5, 3, NULL, &g) != GNN_ERR_NULL || g != NULL) return 2;
+    if (gnn_build_csr(NULL, NULL, 0, 0, NULL, &g) != GNN_ERR_BAD_SIZE) return 3;
+    if (gnn_propagate(NULL, NULL, 4, NULL, 1, GNN_EDGE_ORDER_COO, GNN_MSG_COPY_XJ, GNN_AGGR_SUM, NULL, NULL) != GNN_ERR_NULL) return 4;
+    if (gnn_graph_pool_workspace_bytes(100, 1, 8) != 0) return 5;
+    if (gnn_graph_destroy(NULL) != GNN_OK) return 6;
+    puts("c abi ok");
+    return 0;
+}
+""")
+    exe = tmp_path / "use_abi"
+    subprocess.check_call(["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-I", os.path.join(root, "include"),
+                           str(src), "-o", str(exe), "-L", lib_dir, "-lgnn_mi355x",
+                           "-Wl,-rpath," + lib_dir, "-Wl,-rpath,/opt/rocm/lib"])
+    out = subprocess.run([str(exe)], capture_output=True, text=True, timeout=120)
+    assert out.returncode == 0 and "c abi ok" in out.stdout, (out.returncode, out.stdout, out.stderr)
