@@ -156,3 +156,53 @@ def test_single_head_softmax_takes_the_route(gnn):
     # several heads keep the direct path on a graph with a route
     s8 = (3.0 * synth.normal_f32(93, 2, e * 8)).reshape(e, 8)
     assert torch.equal(gnn.segment_softmax(routed, dev(s8)), gnn.segment_softmax(plain, dev(s8)))
+
+
+def test_routed_calls_can_be_captured(gnn):
+    """Calls that take the route only enqueue kernels: propagate with COO-ordered weights, its backward and the
+    single-head softmax are recorded into one HIP graph; every replay (with eager work on the same handles in
+    between) reproduces the eager results bit for bit."""
+    wl = synth.config2_weighted(num_nodes=20_000, num_edges=300_000, feat=32, cap=6000.0)
+    n, e, f = wl.num_nodes, wl.num_edges, 32
+    x = dev(synth.normal_f32(81, 2, n * f).reshape(n, f))
+    gout = dev(synth.normal_f32(82, 2, n * f).reshape(n, f))
+    w = dev(np.ascontiguousarray(wl.edge_weight, dtype=np.float32).reshape(-1))
+    scores = dev((2.0 * synth.normal_f32(83, 2, e)).reshape(e, 1))
+    src_d, dst_d = dev(wl.src), dev(wl.dst)
+    g, gt = gnn.build_csr(src_d, dst_d, n), gnn.build_csr(dst_d, src_d, n)
+    g.build_edge_route()
+    gt.build_edge_route()
+    g.reserve(0, 1)
+    ws = torch.empty(max(int(gnn.lib().gnn_propagate_backward_workspace_bytes(n, f, AGGR_SUM)), 16), dtype=torch.uint8,
+                     device="cuda")
+    out = torch.empty((n, f), dtype=torch.float32, device="cuda")
+    gx, ge = torch.empty_like(out), torch.empty_like(w)
+    alpha = torch.empty_like(scores)
+    lib = gnn.lib()
+
+    def calls():
+        st = torch.cuda.current_stream().cuda_stream
+        assert lib.gnn_propagate(g._h, x.data_ptr(), f, w.data_ptr(), 1, 0, MSG_E_MUL_XJ, AGGR_SUM, out.data_ptr(), st) == 0
+        assert lib.gnn_propagate_backward(g._h, gt._h, x.data_ptr(), f, w.data_ptr(), 1, MSG_E_MUL_XJ, AGGR_SUM,
+                                          gout.data_ptr(), None, gx.data_ptr(), ge.data_ptr(), ws.data_ptr(), ws.numel(),
+                                          st) == 0
+        assert lib.gnn_segment_softmax(g._h, scores.data_ptr(), 1, 0, alpha.data_ptr(), st) == 0
+
+    calls()
+    torch.cuda.synchronize()
+    eager = [t.clone() for t in (out, gx, ge, alpha)]
+    gph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(gph):
+        calls()
+    for it in range(3):
+        for t in (out, gx, ge, alpha):
+            t.fill_(float("nan"))
+        gph.replay()
+        torch.cuda.synchronize()
+        for got, want in zip((out, gx, ge, alpha), eager):
+            assert torch.equal(got, want), f"replay {it}"
+        gnn.edge_data_to_csr(g, w)      # eager use of the route's buffers between replays
+        torch.cuda.synchronize()
+    del gph
+    g.close()
+    gt.close()
