@@ -1142,6 +1142,50 @@ def test_pool_with_workspace_few_large_graphs(gnn, n, f, bounds):
         assert rc == 1      # no workspace
 
 
+@pytest.mark.parametrize("shape", ["in_star", "out_star", "one_pair"])
+def test_star_graphs(gnn, shape):
+    """One row with every edge (1 172 wavefront pieces at the smallest piece length) / one source gathered by every
+    edge / one edge repeated 300 000 times: propagate, segment softmax, the attention layer and the backward passes against the oracle."""
+    n, e, f, heads, ch = 4000, 300_000, 16, 2, 8
+    other = synth.randint(321, 1, 0, e, 0, n - 1).astype(np.int32)
+    hub = np.full(e, 7, np.int32)
+    if shape == "one_pair":      # the same edge 300 000 times
+        other = np.full(e, 3, np.int32)
+    src, dst = (hub, other) if shape == "out_star" else (other, hub)
+    x = synth.normal_f32(322, 2, n * f).reshape(n, f)
+    w_e = synth.uniform_f32(323, 3, e, 0.0, 1.0)
+    gout = synth.normal_f32(324, 2, n * f).reshape(n, f)
+    g = gnn.build_csr(dev(src), dev(dst), n, 16, 256)
+    gt = gnn.build_csr(dev(dst), dev(src), n, 16, 256)
+    rowptr, colidx, perm, _ = oracle.build_csr(src, dst, n)
+    np.testing.assert_array_equal(host(g.rowptr), rowptr)
+    np.testing.assert_array_equal(host(g.perm), perm)
+    xd, wd = dev(x), dev(w_e)
+    for msg, aggr in ((MSG_COPY_XJ, AGGR_SUM), (MSG_E_MUL_XJ, AGGR_MEAN), (MSG_E_MUL_XJ, AGGR_MAX), (MSG_COPY_XJ, AGGR_MIN)):
+        ref, sabs = oracle.propagate(src, dst, n, x, w_e if msg else None, msg, aggr, with_sabs=True)
+        got = host(gnn.propagate(g, xd, wd if msg else None, msg, aggr))
+        if aggr in (AGGR_MAX, AGGR_MIN):
+            np.testing.assert_array_equal(got.view(np.uint32), ref.view(np.uint32))
+        else:
+            assert_close_sabs(got, ref, sabs, what=f"{shape} propagate {msg} {aggr}")
+    back = oracle.propagate_backward(src, dst, n, x, gout, w_e, MSG_E_MUL_XJ, AGGR_SUM, with_sabs=True)
+    gx, ge = gnn.propagate_backward(g, gt, xd, dev(gout), wd, MSG_E_MUL_XJ, AGGR_SUM)
+    assert_close_sabs(host(gx), back["grad_x"], back["sabs_x"], what=f"{shape} grad_x")
+    assert_close_sabs(host(ge).reshape(-1, 1), back["grad_e"], back["sabs_e"], what=f"{shape} grad_e")
+    scores = (2.0 * synth.normal_f32(325, 2, e * heads)).reshape(e, heads)
+    g.reserve(0, heads)
+    assert_close_rel(host(gnn.segment_softmax(g, dev(scores))), oracle.segment_softmax(dst, n, scores), what=f"{shape} softmax")
+    wgt = synth.glorot_uniform(326, 3, f, heads * ch, (f, heads * ch))
+    a_s = synth.uniform_f32(327, 4, heads * ch, -0.8, 0.8).reshape(heads, ch)
+    a_d = synth.uniform_f32(328, 4, heads * ch, -0.8, 0.8).reshape(heads, ch)
+    ref, sabs = oracle.gatconv(src, dst, n, x, wgt, a_s, a_d, 0.2, with_sabs=True)
+    stats = torch.empty((n, heads, 2), dtype=torch.float32, device="cuda")
+    out = gnn.gatconv(g, xd, dev(wgt), dev(a_s), dev(a_d), 0.2, softmax_stats=stats)
+    assert_close_sabs(host(out), ref, sabs, what=f"{shape} gatconv")
+    g.close()
+    gt.close()
+
+
 def test_degenerate_graphs_through_every_entry_point(gnn):
     """No edges at all, a single node, a single self-loop: every entry point returns what the oracle
     returns (zeros for empty neighbourhoods, no fault, no stale memory)."""
