@@ -1142,6 +1142,89 @@ def test_pool_with_workspace_few_large_graphs(gnn, n, f, bounds):
         assert rc == 1      # no workspace
 
 
+def test_buffers_that_are_not_16_byte_aligned(gnn):
+    """Every float buffer starts 4 bytes past a 16-byte boundary (feature widths that would otherwise take the
+    128-bit paths): the calls fall back to their scalar paths and give the oracle's results."""
+    wl = powerlaw(3000, 60_000, 32, 900.0)
+    n, e, f = wl.num_nodes, wl.num_edges, 32
+    g = gnn.build_csr(dev(wl.src), dev(wl.dst), n, 8, 128)
+    gt = gnn.build_csr(dev(wl.dst), dev(wl.src), n, 8, 128)
+
+    def off(a):   # a device copy of `a` whose first element lies 4 bytes past a 16-byte boundary
+        a = np.ascontiguousarray(a, dtype=np.float32)
+        buf = torch.empty(a.size + 1, dtype=torch.float32, device="cuda")
+        view = buf[1:].view(a.shape)
+        view.copy_(torch.from_numpy(a))
+        assert view.data_ptr() % 16 == 4
+        return view
+
+    def off_out(*shape):
+        return torch.empty(int(np.prod(shape)) + 1, dtype=torch.float32, device="cuda")[1:].view(shape)
+
+    w_e = synth.uniform_f32(901, 3, e, 0.0, 1.0)
+    x_d, e_d = off(wl.x), off(w_e)
+    for msg, aggr in ((MSG_COPY_XJ, AGGR_SUM), (MSG_E_MUL_XJ, AGGR_MEAN), (MSG_E_MUL_XJ, AGGR_MAX)):
+        ref, sabs = oracle.propagate(wl.src, wl.dst, n, wl.x, w_e if msg else None, msg, aggr, with_sabs=True)
+        got = host(gnn.propagate(g, x_d, e_d if msg else None, msg, aggr, out=off_out(n, f)))
+        if aggr == AGGR_MAX:
+            np.testing.assert_array_equal(got.view(np.uint32), ref.view(np.uint32))
+        else:
+            assert_close_sabs(got, ref, sabs, what=f"unaligned propagate {msg} {aggr}")
+    gout = synth.normal_f32(902, 2, n * f).reshape(n, f)
+    back = oracle.propagate_backward(wl.src, wl.dst, n, wl.x, gout, w_e, MSG_E_MUL_XJ, AGGR_SUM, with_sabs=True)
+    gx, ge = gnn.propagate_backward(g, gt, x_d, off(gout), e_d, MSG_E_MUL_XJ, AGGR_SUM)
+    assert_close_sabs(host(gx), back["grad_x"], back["sabs_x"], what="unaligned grad_x")
+    assert_close_sabs(host(ge).reshape(-1, 1), back["grad_e"], back["sabs_e"], what="unaligned grad_e")
+    # dense projection and the GCN layer
+    wgt = synth.glorot_uniform(903, 3, f, 64, (f, 64))
+    bias = synth.uniform_f32(904, 3, 64, -0.5, 0.5)
+    ref = oracle.dense(wl.x, wgt, None, False)
+    assert_close_sabs(host(gnn.dense_xw(x_d, off(wgt), out=off_out(n, 64))), ref,
+                      np.abs(wl.x.astype(np.float64)) @ np.abs(wgt.astype(np.float64)), what="unaligned dense")
+    ref, sabs = oracle.gcnconv(wl.src, wl.dst, n, wl.x, wgt, bias, True, with_sabs=True)
+    assert_close_sabs(host(gnn.gcnconv(g, x_d, off(wgt), off(bias), True, out=off_out(n, 64))), ref, sabs, what="unaligned gcnconv")
+    # segment softmax, attention layer, pooling
+    heads, ch = 4, 8
+    scores = (2.0 * synth.normal_f32(905, 2, e * heads)).reshape(e, heads)
+    assert_close_rel(host(gnn.segment_softmax(g, off(scores), out=off_out(e, heads))), oracle.segment_softmax(wl.dst, n, scores),
+                     what="unaligned softmax")
+    wg = synth.glorot_uniform(906, 3, f, heads * ch, (f, heads * ch))
+    a_s = synth.uniform_f32(907, 4, heads * ch, -0.8, 0.8).reshape(heads, ch)
+    a_d = synth.uniform_f32(908, 4, heads * ch, -0.8, 0.8).reshape(heads, ch)
+    ref, sabs = oracle.gatconv(wl.src, wl.dst, n, wl.x, wg, a_s, a_d, 0.2, with_sabs=True)
+    got = gnn.gatconv(g, x_d, off(wg), off(a_s), off(a_d), 0.2, out=off_out(n, heads * ch))
+    assert_close_sabs(host(got), ref, sabs, what="unaligned gatconv")
+    # backward of the GCN layer and of the attention layer with unaligned inputs (outputs come from the binding)
+    g64 = synth.normal_f32(910, 2, n * 64).reshape(n, 64)
+    rb = oracle.gcnconv_backward(wl.src, wl.dst, n, wl.x, wgt, g64, True)
+    bx, bw, bb = gnn.gcnconv_backward(g, gt, x_d, off(wgt), off(g64), True)
+    assert_close_sabs(host(bx), rb["grad_x"], rb["sabs_x"], what="unaligned gcn grad_x")
+    assert_close_sabs(host(bw), rb["grad_w"], rb["sabs_w"], what="unaligned gcn grad_w")
+    assert_close_sabs(host(bb), rb["grad_b"], rb["sabs_b"], what="unaligned gcn grad_b")
+    # (slope 1: the leaky ReLU has no kink, so no pre-activation can sit on the wrong side of it in float)
+    stats = torch.empty(n * heads * 2 + 1, dtype=torch.float32, device="cuda")[1:].view(n, heads, 2)
+    out_u = gnn.gatconv(g, x_d, off(wg), off(a_s), off(a_d), 1.0, out=off_out(n, heads * ch), softmax_stats=stats)
+    gg = synth.normal_f32(911, 2, n * heads * ch).reshape(n, heads * ch)
+    rg = oracle.gatconv_backward(wl.src, wl.dst, n, wl.x, wg, a_s, a_d, gg, 1.0)
+    ax, aw, aas, aad = gnn.gatconv_backward(g, gt, x_d, off(wg), off(a_s), off(a_d), out_u, stats, off(gg), 1.0)
+    assert_close_sabs(host(ax), rg["grad_x"], rg["sabs_x"], what="unaligned gat grad_x")
+    assert_close_sabs(host(aw), rg["grad_w"], rg["sabs_w"], what="unaligned gat grad_w")
+    assert_close_sabs(host(aas), rg["grad_a_src"], rg["sabs_a_src"], what="unaligned gat grad_a_src")
+    # with slope 1 the destination half of a score cancels in the softmax: this gradient is exactly zero, the
+    # computed one is rounding noise of its terms
+    assert (np.abs(host(aad).astype(np.float64)) <= 1e-5 * rg["sabs_a_dst"]).all()
+    gi = np.sort(synth.randint(909, 1, 0, n, 0, 39)).astype(np.int32)
+    for aggr in (AGGR_SUM, AGGR_MAX):
+        ref, sabs = oracle.graph_pool(gi, 40, wl.x, aggr, with_sabs=True)
+        got = host(gnn.graph_pool(dev(gi), 40, x_d, aggr, out=off_out(40, f)))
+        if aggr == AGGR_MAX:
+            np.testing.assert_array_equal(got, ref)
+        else:
+            assert_close_sabs(got, ref, sabs, what="unaligned pool")
+    g.close()
+    gt.close()
+
+
 @pytest.mark.parametrize("shape", ["in_star", "out_star", "one_pair"])
 def test_star_graphs(gnn, shape):
     """One row with every edge (1 172 wavefront pieces at the smallest piece length) / one source gathered by every
