@@ -64,6 +64,29 @@ def test_host_side_argument_errors_need_no_gpu(handle):
     p = handle.gnn_propagate
     p.restype = ctypes.c_int
     assert p(None, None, 4, None, 1, 0, 0, 0, None, None) == 1        # NULL graph
+    for name in ("gnn_graph_build_edge_route", "gnn_graph_reserve"):
+        fn = getattr(handle, name)
+        fn.restype = ctypes.c_int
+    assert handle.gnn_graph_build_edge_route(None, None) == 1          # NULL graph
+    assert handle.gnn_graph_reserve(None, ctypes.c_int32(64), ctypes.c_int32(8)) == 1
+    for name in ("gnn_edge_data_to_csr", "gnn_edge_data_to_coo"):
+        fn = getattr(handle, name)
+        fn.restype = ctypes.c_int
+        fn.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p]
+        assert fn(None, None, 1, None, None) == 1                      # NULL graph
+    ws = handle.gnn_graph_pool_workspace_bytes
+    ws.restype = ctypes.c_size_t
+    ws.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32]
+    assert ws(1000, 10, 64) == 0                                       # small graphs: no workspace, one block per graph
+    assert ws(1_000_000, 1, 64) >= (1_000_000 // 1024) * 64 * 4        # a part per about 1 024 nodes
+    pw = handle.gnn_graph_pool_ws
+    pw.restype = ctypes.c_int
+    pw.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.c_int32, ctypes.c_int,
+                   ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    assert pw(None, 1_000_000, 1, None, 64, 0, None, None, 0, None) == 1   # a workspace is needed and missing
+    bb = handle.gnn_build_csr_batch
+    bb.restype = ctypes.c_int
+    assert bb(0, None, None, None, 5, None, None) == 1                 # NULL handle array
 
 
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
