@@ -320,7 +320,6 @@ __device__ __forceinline__ void short_rows(const PropParams &p, int block)
             const int cnt = min(LPR, wmax - base);
             for (int t0 = 0; t0 < cnt; t0 += U) {
                 Row<VEC> xv[U], ev[U], wv[U];
-                float w[U];
                 int eid[U];
                 bool ok[U];
 #pragma unroll
@@ -328,15 +327,19 @@ __device__ __forceinline__ void short_rows(const PropParams &p, int block)
                     const int t = t0 + u;
                     const int j = __shfl(my_j, t, LPR);
                     eid[u] = 0;
-                    w[u] = 0.0f;
-                    if constexpr (msg_base(MSG) == kMsgMulScalar) w[u] = __shfl(my_w, t, LPR);
                     if constexpr (msg_base(MSG) == kMsgMulVector || msg_routed(MSG)) eid[u] = __shfl(my_eid, t, LPR);
                     ok[u] = colok && (base + t < deg);
                     fetch_message<VEC, MSG, XB>(p, ok[u], j, eid[u], col, xv[u], ev[u], wv[u]);
                 }
+                // the edges' weights are fetched from their lanes only after the loads have gone out (no register per
+                // edge in flight); the barrier keeps the compiler from moving the shuffles up again
+                if constexpr (msg_base(MSG) == kMsgMulScalar) __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int u = 0; u < U; ++u)
-                    apply_message<VEC, MSG, RED, XB>(acc, ok[u], xv[u], w[u], ev[u], wv[u], eid[u], xi);
+                for (int u = 0; u < U; ++u) {
+                    float w = 0.0f;
+                    if constexpr (msg_base(MSG) == kMsgMulScalar) w = __shfl(my_w, t0 + u, LPR);
+                    apply_message<VEC, MSG, RED, XB>(acc, ok[u], xv[u], w, ev[u], wv[u], eid[u], xi);
+                }
             }
         }
         if (colok) finish_row<VEC, RED, XB, msg_by_source(MSG)>(p, row, deg, col, acc);
@@ -383,7 +386,6 @@ __device__ __forceinline__ void long_row_pieces(const PropParams &p, int block)
             // sub-group sg takes batch positions sg, sg + NSG, sg + 2*NSG, ...
             for (int t0 = 0; t0 * NSG < n; t0 += U) {
                 Row<VEC> xv[U], ev[U], wv[U];
-                float w[U];
                 int eid[U];
                 bool ok[U];
 #pragma unroll
@@ -391,15 +393,17 @@ __device__ __forceinline__ void long_row_pieces(const PropParams &p, int block)
                     const int pos = (t0 + u) * NSG + sg;   // <= 63 because t0 + u < LPR
                     const int j = __shfl(my_j, pos, 64);
                     eid[u] = 0;
-                    w[u] = 0.0f;
-                    if constexpr (msg_base(MSG) == kMsgMulScalar) w[u] = __shfl(my_w, pos, 64);
                     if constexpr (msg_base(MSG) == kMsgMulVector || msg_routed(MSG)) eid[u] = __shfl(my_eid, pos, 64);
                     ok[u] = colok && pos < n;
                     fetch_message<VEC, MSG, XB>(p, ok[u], j, eid[u], col, xv[u], ev[u], wv[u]);
                 }
+                if constexpr (msg_base(MSG) == kMsgMulScalar) __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int u = 0; u < U; ++u)
-                    apply_message<VEC, MSG, RED, XB>(acc, ok[u], xv[u], w[u], ev[u], wv[u], eid[u], xi);
+                for (int u = 0; u < U; ++u) {
+                    float w = 0.0f;
+                    if constexpr (msg_base(MSG) == kMsgMulScalar) w = __shfl(my_w, (t0 + u) * NSG + sg, 64);
+                    apply_message<VEC, MSG, RED, XB>(acc, ok[u], xv[u], w, ev[u], wv[u], eid[u], xi);
+                }
             }
         }
 #pragma unroll
