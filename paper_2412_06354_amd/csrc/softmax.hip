@@ -9,8 +9,9 @@
 //      row, a wavefront per piece of a long row with lanes = (edge slot, head group); a lane owns
 //      one head, or four consecutive heads read with one 128-bit load;
 //      edge ids are fetched in batches and the score loads of a batch are independent; the
-//      running (m, den) pair is updated edge by edge and pairs are merged with the usual
-//      rescaling; pieces of a split row are merged in piece order;
+//      running (m, den) pair is updated edge by edge; the lanes of a head group, and the pieces of
+//      a split row, are combined by taking the common maximum first and adding the denominators
+//      rescaled to it (one exponential per lane or piece);
 //   2. one thread per (edge, head), in the order the scores are stored in (so reads and writes
 //      stream):  out = exp(score - m[row]) / den[row], the row coming from the stored copy of the
 //      destination array (caller's order) or from the sorted destinations (CSR order).
@@ -39,22 +40,12 @@ struct SmParams {
 __device__ __forceinline__ void online_add(float &m, float &d, bool ok, float v)
 {
     const float delta = v - m;
-    const float e = expf(-fabsf(delta));     // exp(-inf) = 0 covers the first score (m = -inf)
+    const float e = __expf(-fabsf(delta));     // exp(-inf) = 0 covers the first score (m = -inf)
     const bool up = delta > 0.0f;
     if (ok) {
         d = up ? d * e + 1.0f : d + e;
         m = up ? v : m;
     }
-}
-
-// (m, d) <- (m, d) merged with (m2, d2)
-__device__ __forceinline__ void online_merge(float &m, float &d, float m2, float d2)
-{
-    const float mm = fmaxf(m, m2);
-    const float f1 = (m == -INFINITY) ? 0.0f : expf(m - mm);
-    const float f2 = (m2 == -INFINITY) ? 0.0f : expf(m2 - mm);
-    d = d * f1 + d2 * f2;
-    m = mm;
 }
 
 // Forward: running (max, denominator).  Backward: d accumulates alpha * dalpha (m is unused).
@@ -63,13 +54,6 @@ __device__ __forceinline__ void acc_add(float &m, float &d, bool ok, float v, fl
 {
     if constexpr (BWD) d += ok ? v * w : 0.0f;
     else online_add(m, d, ok, v);
-}
-
-template <bool BWD>
-__device__ __forceinline__ void acc_merge(float &m, float &d, float m2, float d2)
-{
-    if constexpr (BWD) d += d2;
-    else online_merge(m, d, m2, d2);
 }
 
 template <int HV>
@@ -111,42 +95,39 @@ __device__ __forceinline__ void stats_short_rows(const SmParams &p, int block)
         start = p.rowptr[row];
         deg = p.rowptr[row + 1] - start;
     }
-    int wmax = deg;   // wavefront-uniform loop bound: shuffles run with all lanes active
-#pragma unroll
-    for (int off = HP; off < 64; off <<= 1) wmax = max(wmax, __shfl_xor(wmax, off, 64));
     for (int hb = 0; hb < p.H; hb += HP * HV) {
         const int h = hb + hl * HV;
         const bool hok = have && h < p.H;
         float m[HV], d[HV];
 #pragma unroll
         for (int c = 0; c < HV; ++c) { m[c] = -INFINITY; d[c] = 0.0f; }
-        for (int base = 0; base < wmax; base += HP) {
-            int my_eid = 0;
-            if (base + hl < deg) {
-                const int q = start + base + hl;
-                my_eid = p.coo ? __builtin_nontemporal_load(p.perm + q) : q;
+        // U edges at a time, every lane fetching the edge ids it needs itself (the lanes of a sub-group ask for the
+        // same word): all U score loads of a step are independent and none of them is masked off by the sub-group width.
+        for (int t0 = 0; t0 < deg; t0 += U) {
+            float v[U][HV], w[U][HV];
+            bool ok[U];
+            int64_t at[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int q = start + t0 + u;
+                ok[u] = hok && (t0 + u < deg);
+                int eid = 0;
+                if (ok[u]) eid = p.coo ? __builtin_nontemporal_load(p.perm + q) : q;
+                at[u] = (int64_t)eid * p.H + h;
             }
-            const int cnt = min(HP, wmax - base);
-            for (int t0 = 0; t0 < cnt; t0 += U) {
-                float v[U][HV], w[U][HV];
-                bool ok[U];
 #pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const int t = t0 + u;
-                    const int eid = __shfl(my_eid, t, HP);
-                    ok[u] = hok && (t < HP) && (base + t < deg);
+            for (int u = 0; u < U; ++u) {
 #pragma unroll
-                    for (int c = 0; c < HV; ++c) { v[u][c] = 0.0f; w[u][c] = 0.0f; }
-                    if (ok[u]) {
-                        load_heads<HV>(v[u], p.s + (int64_t)eid * p.H + h);
-                        if constexpr (BWD) load_heads<HV>(w[u], p.s2 + (int64_t)eid * p.H + h);
-                    }
+                for (int c = 0; c < HV; ++c) { v[u][c] = 0.0f; w[u][c] = 0.0f; }
+                if (ok[u]) {
+                    load_heads<HV>(v[u], p.s + at[u]);
+                    if constexpr (BWD) load_heads<HV>(w[u], p.s2 + at[u]);
                 }
-#pragma unroll
-                for (int u = 0; u < U; ++u)
-#pragma unroll
-                    for (int c = 0; c < HV; ++c) acc_add<BWD>(m[c], d[c], ok[u], v[u][c], w[u][c]);
             }
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int c = 0; c < HV; ++c) acc_add<BWD>(m[c], d[c], ok[u], v[u][c], w[u][c]);
         }
         if (hok) store_stats<HV>(p.rowstat + (int64_t)row * p.H + h, m, d);
     }
@@ -192,17 +173,35 @@ __device__ __forceinline__ void stats_long_pieces(const SmParams &p, int block)
                 }
             }
 #pragma unroll
-            for (int u = 0; u < U; ++u)
+            for (int u = 0; u < U; ++u) {
+                if (q0 + u * ES < end) {   // the same for the whole wavefront: an empty step costs no arithmetic
 #pragma unroll
-                for (int c = 0; c < HV; ++c) acc_add<BWD>(m[c], d[c], ok[u], v[u][c], w[u][c]);
+                    for (int c = 0; c < HV; ++c) acc_add<BWD>(m[c], d[c], ok[u], v[u][c], w[u][c]);
+                }
+            }
+        }
+        // Across the edge slots of a head group.  Forward: the common maximum first (exact in any order), then every
+        // lane rescales its denominator once and the denominators are added -- one exponential per lane where a
+        // butterfly of pair merges would take two per step, and that arithmetic is what short pieces spend their time on.
+        if constexpr (!BWD) {
+            float mm[HV];
+#pragma unroll
+            for (int c = 0; c < HV; ++c) mm[c] = m[c];
+#pragma unroll
+            for (int off = HP; off < 64; off <<= 1) {
+#pragma unroll
+                for (int c = 0; c < HV; ++c) mm[c] = fmaxf(mm[c], __shfl_xor(mm[c], off, 64));
+            }
+#pragma unroll
+            for (int c = 0; c < HV; ++c) {
+                d[c] = (m[c] == -INFINITY) ? 0.0f : d[c] * expf(m[c] - mm[c]);
+                m[c] = mm[c];
+            }
         }
 #pragma unroll
         for (int off = HP; off < 64; off <<= 1) {
 #pragma unroll
-            for (int c = 0; c < HV; ++c) {
-                const float m2 = __shfl_xor(m[c], off, 64), d2 = __shfl_xor(d[c], off, 64);
-                acc_merge<BWD>(m[c], d[c], m2, d2);
-            }
+            for (int c = 0; c < HV; ++c) d[c] += __shfl_xor(d[c], off, 64);
         }
         if (es == 0 && hok)
             store_stats<HV>((slot < 0 ? p.rowstat + (int64_t)row * p.H : p.slotstat + (int64_t)slot * p.H) + h, m, d);
@@ -218,38 +217,65 @@ __global__ __launch_bounds__(kThreads) void stats_kernel(const SmParams p)
         stats_short_rows<HP, HV, BWD>(p, blockIdx.x - p.item_blocks);
 }
 
+// A wavefront per (split row, head): lanes take the row's pieces, a butterfly combines the lanes.  Forward: the
+// maximum over the pieces first, then the sum of the denominators rescaled to it; sums of a butterfly are the same
+// in every lane (addition commutes), so any lane may store.
 template <bool BWD>
 __global__ __launch_bounds__(kThreads) void stats_merge_kernel(const SmParams p)
 {
-    const int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    const int lane = threadIdx.x & 63;
+    const int64_t idx = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6);
     const int64_t si = idx / p.H;
     const int h = (int)(idx - si * p.H);
-    if (si >= p.n_split) return;
+    if (si >= p.n_split) return;   // whole wavefront leaves together
     const int row = p.split_rows[si];
-    const int slot0 = p.split_slot0[si];
     const int deg = p.rowptr[row + 1] - p.rowptr[row];
     const int pieces = (deg + p.chunk - 1) / p.chunk;
+    const float2 *st = p.slotstat + (int64_t)p.split_slot0[si] * p.H + h;
     float m = -INFINITY, d = 0.0f;
-    for (int c = 0; c < pieces; ++c) {
-        const float2 st = p.slotstat[(int64_t)(slot0 + c) * p.H + h];
-        acc_merge<BWD>(m, d, st.x, st.y);
+    if constexpr (!BWD) {
+        for (int c = lane; c < pieces; c += 64) m = fmaxf(m, st[(int64_t)c * p.H].x);
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
+        for (int c = lane; c < pieces; c += 64) {
+            const float2 q = st[(int64_t)c * p.H];
+            d += (q.x == -INFINITY) ? 0.0f : q.y * expf(q.x - m);
+        }
+    } else {
+        for (int c = lane; c < pieces; c += 64) d += st[(int64_t)c * p.H].y;
     }
-    p.rowstat[(int64_t)row * p.H + h] = make_float2(m, d);
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) d += __shfl_xor(d, off, 64);
+    if (lane == 0) p.rowstat[(int64_t)row * p.H + h] = make_float2(m, d);
 }
 
-// Position k of the score array belongs to row row_of_edge[k]; scores and weights stream.
-// A thread handles HV consecutive heads of one edge.
+// The element-wise second phase.  Position k of the score array belongs to row row_of_edge[k]; scores and results
+// stream.  A thread handles HV consecutive heads of one edge; a block step covers as many whole edges as its threads
+// hold, so a thread's head group never changes and nothing is divided per element.
+__host__ __device__ inline int edges_per_block_step(int head_groups)
+{
+    return head_groups >= kThreads ? 1 : kThreads / head_groups;
+}
+
+// FN(k, h, st): k = edge position, h = first head of the group, st = the (m, den) records of (row, h ..).
+template <int HV, class FN>
+__device__ __forceinline__ void for_each_edge_head_group(const SmParams &p, FN fn)
+{
+    const int hg = p.H / HV;
+    const int epb = edges_per_block_step(hg);
+    const int el = (int)threadIdx.x / hg, h0 = (int)threadIdx.x - el * hg;
+    if (el >= epb) return;
+    for (int64_t k = (int64_t)blockIdx.x * epb + el; k < p.E; k += (int64_t)gridDim.x * epb) {
+        const int row = __builtin_nontemporal_load(p.row_of_edge + k);
+        // one trip, unless an edge has more head groups than the block has threads
+        for (int g = h0; g < hg; g += kThreads) fn(k, g * HV, p.rowstat + (int64_t)row * p.H + g * HV);
+    }
+}
+
 template <int HV>
 __global__ __launch_bounds__(kThreads) void normalise_kernel(const SmParams p)
 {
-    const int hg = p.H / HV;                       // head groups per edge
-    const int64_t total = p.E * hg;
-    const int64_t stride = (int64_t)gridDim.x * kThreads;
-    for (int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x; idx < total; idx += stride) {
-        const int64_t k = idx / hg;
-        const int h = (int)(idx - k * hg) * HV;
-        const int row = __builtin_nontemporal_load(p.row_of_edge + k);
-        const float2 *st = p.rowstat + (int64_t)row * p.H + h;
+    for_each_edge_head_group<HV>(p, [&](int64_t k, int h, const float2 *st) {
         if constexpr (HV == 4) {
             typedef float v4f __attribute__((ext_vector_type(4)));
             const float4 s0 = reinterpret_cast<const float4 *>(st)[0], s1 = reinterpret_cast<const float4 *>(st)[1];
@@ -261,21 +287,14 @@ __global__ __launch_bounds__(kThreads) void normalise_kernel(const SmParams p)
             const float v = __builtin_nontemporal_load(p.s + k * p.H + h);
             __builtin_nontemporal_store(expf(v - q.x) / q.y, p.out + k * p.H + h);
         }
-    }
+    });
 }
 
 // Backward: gs = alpha * (dalpha - t[row]) with t = the row's sum of alpha * dalpha (rowstat.y).
 template <int HV>
 __global__ __launch_bounds__(kThreads) void jacobian_kernel(const SmParams p)
 {
-    const int hg = p.H / HV;
-    const int64_t total = p.E * hg;
-    const int64_t stride = (int64_t)gridDim.x * kThreads;
-    for (int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x; idx < total; idx += stride) {
-        const int64_t k = idx / hg;
-        const int h = (int)(idx - k * hg) * HV;
-        const int row = __builtin_nontemporal_load(p.row_of_edge + k);
-        const float2 *st = p.rowstat + (int64_t)row * p.H + h;
+    for_each_edge_head_group<HV>(p, [&](int64_t k, int h, const float2 *st) {
         if constexpr (HV == 4) {
             typedef float v4f __attribute__((ext_vector_type(4)));
             const float4 s0 = reinterpret_cast<const float4 *>(st)[0], s1 = reinterpret_cast<const float4 *>(st)[1];
@@ -288,7 +307,7 @@ __global__ __launch_bounds__(kThreads) void jacobian_kernel(const SmParams p)
             const float g = __builtin_nontemporal_load(p.s2 + k * p.H + h);
             __builtin_nontemporal_store(a * (g - st[0].y), p.out + k * p.H + h);
         }
-    }
+    });
 }
 
 template <int HP, int HV, bool BWD>
@@ -365,13 +384,13 @@ gnn_status run_softmax(const gnn_graph *g, const float *d_in, const float *d_in2
     else
         GNN_TRY((launch_stats_hv<1, BWD>(p, heads, s)));
     if (g->n_split > 0) {
-        const unsigned blocks = (unsigned)gnn_div_up((int64_t)g->n_split * heads, kThreads);
+        const unsigned blocks = (unsigned)gnn_div_up((int64_t)g->n_split * heads, kWavesPerBlock);
         hipLaunchKernelGGL(stats_merge_kernel<BWD>, dim3(blocks), dim3(kThreads), 0, s, p);
         GNN_LAUNCH_CHECK();
     }
     {
-        const int64_t total = g->num_edges * (vec4 ? heads / 4 : heads);
-        const unsigned blocks = (unsigned)std::min<int64_t>(gnn_div_up(total, kThreads), 256 * 64);
+        const int epb = edges_per_block_step(vec4 ? heads / 4 : heads);
+        const unsigned blocks = (unsigned)std::min<int64_t>(gnn_div_up(g->num_edges, epb), 256 * 64);
         if (BWD) {
             if (vec4)
                 hipLaunchKernelGGL(jacobian_kernel<4>, dim3(blocks), dim3(kThreads), 0, s, p);

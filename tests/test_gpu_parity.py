@@ -1030,10 +1030,22 @@ def test_segment_softmax_backward(case, gnn, heads):
 def test_segment_softmax_many_heads(gnn):
     wl = powerlaw(2000, 30_000, 4, 1500.0)
     g = gnn.build_csr(dev(wl.src), dev(wl.dst), wl.num_nodes, 4, 64)
-    for heads in (2, 16, 70):
-        s = (2.0 * synth.normal_f32(heads, 2, wl.num_edges * heads)).reshape(wl.num_edges, heads)
-        ref = oracle.segment_softmax(wl.dst, wl.num_nodes, s)
-        assert_close_rel(host(gnn.segment_softmax(g, dev(s))), ref, what=f"softmax H={heads}")
+    # 70 and 300 take the one-head-per-lane kernels, 300 with more head groups per edge than a block has threads;
+    # 1028 the same in the four-heads-per-lane kernels; 3 leaves threads of the element-wise blocks idle.
+    for heads in (2, 3, 16, 70, 300, 1028):
+        E = wl.num_edges if heads <= 70 else 3000
+        gg = g if heads <= 70 else gnn.build_csr(dev(wl.src[:E]), dev(wl.dst[:E]), wl.num_nodes, 4, 64)
+        dst = wl.dst[:E]
+        s = (2.0 * synth.normal_f32(heads, 2, E * heads)).reshape(E, heads)
+        ref = oracle.segment_softmax(dst, wl.num_nodes, s)
+        assert_close_rel(host(gnn.segment_softmax(gg, dev(s))), ref, what=f"softmax H={heads}")
+        galpha = synth.normal_f32(heads, 3, E * heads).reshape(E, heads)
+        alpha = ref.astype(np.float32)
+        refb, sabs = oracle.segment_softmax_backward(dst, wl.num_nodes, alpha, galpha, with_sabs=True)
+        assert_close_sabs(host(gnn.segment_softmax_backward(gg, dev(alpha), dev(galpha))), refb, sabs,
+                          what=f"softmax backward H={heads}")
+        if gg is not g:
+            gg.close()
     g.close()
 
 
