@@ -5,10 +5,14 @@
 // attention weights are ever written to memory.
 //
 //   h = X W (MFMA projection);  sl = <a_src, h> and sr = <a_dst, h> per node and head;
-//   per destination row: running (max, denominator, weighted feature sum) per head updated edge
-//   by edge ("online" softmax), divided once at the end.
+//   per destination row: running (max, denominator, weighted feature sum) per head ("online"
+//   softmax), updated a batch of edges at a time -- the batch's largest score joins the maximum,
+//   the state is rescaled once, each edge adds exp(score - max) times its slice -- and divided
+//   once at the end.
 // Work decomposition is the one of propagate: sub-group per short row, wavefront per piece of a
-// long row, split rows merged afterwards in piece order.
+// long row, split rows merged afterwards in piece order.  Partial states (edge slots of a
+// wavefront, pieces of a split row) are combined by rescaling each to the common maximum and
+// adding.
 #include "gnn_internal.h"
 
 namespace {
@@ -43,32 +47,45 @@ __device__ __forceinline__ void state_init(State<VEC> &s)
     for (int c = 0; c < VEC; ++c) s.acc[c] = 0.0f;
 }
 
-// Adds one edge with score `sc` and feature slice `hv` to the running softmax-weighted sum.
-template <int VEC>
-__device__ __forceinline__ void state_add(State<VEC> &s, bool ok, float sc, const float *hv)
+// e^x through the hardware's 2^x: off by at most about (1 + |x|) * 2^-23 of the result.  The weights of a row
+// are only ever used as ratios (weighted sum over denominator), and the edge loop below lives on arithmetic:
+// the library routine would be a third of its instructions.
+__device__ __forceinline__ float exp_hw(float x) { return __builtin_amdgcn_exp2f(x * 1.44269504088896341f); }
+
+// Adds U edges at once to the running softmax-weighted sum: the largest score of the batch joins the running
+// maximum first, the state is rescaled to it once, and every edge then costs one exponential and VEC + 1
+// multiply-adds.  An edge that is masked off carries the score -inf (weight 0) and a zero slice.
+template <int VEC, int U>
+__device__ __forceinline__ void state_add_batch(State<VEC> &s, const float (&sc)[U], const float (&hv)[U][VEC])
 {
-    const float delta = sc - s.m;
-    const float e = expf(-fabsf(delta));          // exp(-inf) = 0 covers the first edge (m = -inf)
-    const bool up = delta > 0.0f;
-    const float scale = ok ? (up ? e : 1.0f) : 1.0f;
-    const float pe = ok ? (up ? 1.0f : e) : 0.0f;
-    s.m = (ok && up) ? sc : s.m;
-    s.d = s.d * scale + pe;
+    float bm = sc[0];
 #pragma unroll
-    for (int c = 0; c < VEC; ++c) s.acc[c] = s.acc[c] * scale + pe * hv[c];
+    for (int u = 1; u < U; ++u) bm = fmaxf(bm, sc[u]);
+    const float nm = fmaxf(s.m, bm);
+    const float ref = (nm == -INFINITY) ? 0.0f : nm;   // nothing seen so far and nothing valid in the batch
+    const float scale = exp_hw(s.m - ref);              // e^-inf = 0 on the first batch, where d and acc are zero
+    s.m = nm;
+    s.d *= scale;
+#pragma unroll
+    for (int c = 0; c < VEC; ++c) s.acc[c] *= scale;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const float pe = exp_hw(sc[u] - ref);
+        s.d += pe;
+#pragma unroll
+        for (int c = 0; c < VEC; ++c) s.acc[c] = fmaf(pe, hv[u][c], s.acc[c]);
+    }
 }
 
-// Merges state b into a (b's edges come after a's).
+// Brings a state to the maximum `m` (not below its own).
 template <int VEC>
-__device__ __forceinline__ void state_merge(State<VEC> &a, float bm, float bd, const float *bacc)
+__device__ __forceinline__ void state_rescale(State<VEC> &s, float m)
 {
-    const float m = fmaxf(a.m, bm);
-    const float fa = (a.m == -INFINITY) ? 0.0f : expf(a.m - m);
-    const float fb = (bm == -INFINITY) ? 0.0f : expf(bm - m);
-    a.m = m;
-    a.d = a.d * fa + bd * fb;
+    const float f = (s.m == -INFINITY) ? 0.0f : expf(s.m - m);
+    s.m = m;
+    s.d *= f;
 #pragma unroll
-    for (int c = 0; c < VEC; ++c) a.acc[c] = a.acc[c] * fa + bacc[c] * fb;
+    for (int c = 0; c < VEC; ++c) s.acc[c] *= f;
 }
 
 template <int VEC>
@@ -174,8 +191,9 @@ __device__ __forceinline__ void gat_short_rows(const GatParams &p, int block)
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     if constexpr (LPH > 0) sc[u] = source_score<VEC, LPH>(as, hv[u]);
-                    state_add<VEC>(st, ok[u], lrelu(sc[u] + sr_i, p.slope), hv[u]);
+                    sc[u] = ok[u] ? lrelu(sc[u] + sr_i, p.slope) : -INFINITY;
                 }
+                state_add_batch<VEC, U>(st, sc, hv);
             }
         }
         if (colok) write_out<VEC>(p, row, col, st);
@@ -229,17 +247,24 @@ __device__ __forceinline__ void gat_long_pieces(const GatParams &p, int block)
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     if constexpr (LPH > 0) sc[u] = source_score<VEC, LPH>(as, hv[u]);
-                    state_add<VEC>(st, ok[u], lrelu(sc[u] + sr_i, p.slope), hv[u]);
+                    sc[u] = ok[u] ? lrelu(sc[u] + sr_i, p.slope) : -INFINITY;
                 }
+                state_add_batch<VEC, U>(st, sc, hv);
             }
         }
+        // Across the edge slots: the common maximum first (exact in any order), one rescaling per lane, then plain
+        // sums, which come out the same in every lane.
+        {
+            float mm = st.m;
 #pragma unroll
-        for (int off = LPR; off < 64; off <<= 1) {
-            const float om = __shfl_xor(st.m, off, 64), od = __shfl_xor(st.d, off, 64);
-            float oacc[VEC];
+            for (int off = LPR; off < 64; off <<= 1) mm = fmaxf(mm, __shfl_xor(mm, off, 64));
+            state_rescale<VEC>(st, mm);
 #pragma unroll
-            for (int c = 0; c < VEC; ++c) oacc[c] = __shfl_xor(st.acc[c], off, 64);
-            state_merge<VEC>(st, om, od, oacc);
+            for (int off = LPR; off < 64; off <<= 1) {
+                st.d += __shfl_xor(st.d, off, 64);
+#pragma unroll
+                for (int c = 0; c < VEC; ++c) st.acc[c] += __shfl_xor(st.acc[c], off, 64);
+            }
         }
         if (sg == 0 && colok) {
             if (slot < 0) {
@@ -279,13 +304,20 @@ __global__ __launch_bounds__(kThreads) void gat_merge_kernel(const GatParams p)
     for (int cb = 0; cb * LPR * VEC < p.HC; ++cb) {
         const int col = (cb * LPR + sl_) * VEC;
         if (col >= p.HC) continue;
+        // pieces in piece order: the maximum over the pieces first, then every piece rescaled to it and added
         State<VEC> st;
         state_init(st);
+        for (int c = 0; c < pieces; ++c) st.m = fmaxf(st.m, p.slot_m[(int64_t)(slot0 + c) * p.HC + col]);
         for (int c = 0; c < pieces; ++c) {
             const int64_t q = (int64_t)(slot0 + c) * p.HC + col;
-            float acc[VEC];
-            load_vec<VEC>(acc, p.slot_acc + q);
-            state_merge<VEC>(st, p.slot_m[q], p.slot_d[q], acc);
+            State<VEC> pc;
+            pc.m = p.slot_m[q];
+            pc.d = p.slot_d[q];
+            load_vec<VEC>(pc.acc, p.slot_acc + q);
+            state_rescale<VEC>(pc, st.m);
+            st.d += pc.d;
+#pragma unroll
+            for (int k = 0; k < VEC; ++k) st.acc[k] += pc.acc[k];
         }
         write_out<VEC>(p, row, col, st);
     }
