@@ -341,20 +341,33 @@ __global__ __launch_bounds__(kThreads) void node_records_kernel(const float *__r
 }
 
 // dh[i,hd,c] += dsl[i,hd] a_src[hd,c] + dsr[i,hd] a_dst[hd,c]
+// A thread owns VEC consecutive columns (one head's) and walks down the rows: its slices of the attention vectors
+// stay in registers, a block step covers as many whole rows as the block's threads hold, nothing is divided per
+// element.
+template <int VEC>
 __global__ __launch_bounds__(kThreads) void add_score_terms_kernel(float *__restrict__ dh, int64_t N, int H, int ch,
                                                                    const float *__restrict__ dsl,
                                                                    const float *__restrict__ dsr,
                                                                    const float *__restrict__ a_src,
                                                                    const float *__restrict__ a_dst)
 {
-    const int HC = H * ch;
-    const int64_t total = N * HC;
-    const int64_t stride = (int64_t)gridDim.x * kThreads;
-    for (int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x; idx < total; idx += stride) {
-        const int64_t i = idx / HC;
-        const int col = (int)(idx - i * HC);
-        const int hd = col / ch;
-        dh[idx] = fmaf(dsl[i * H + hd], a_src[col], fmaf(dsr[i * H + hd], a_dst[col], dh[idx]));
+    const int HC = H * ch, groups = HC / VEC;
+    const int rows_per_step = groups >= kThreads ? 1 : kThreads / groups;
+    const int rl = (int)threadIdx.x / groups, g0 = (int)threadIdx.x - rl * groups;
+    if (rl >= rows_per_step) return;
+    for (int g = g0; g < groups; g += kThreads) {   // one trip, unless a row has more column groups than the block has threads
+        const int col = g * VEC, hd = col / ch;
+        float as[VEC], ad[VEC];
+        load_vec<VEC>(as, a_src + col);
+        load_vec<VEC>(ad, a_dst + col);
+        for (int64_t i = (int64_t)blockIdx.x * rows_per_step + rl; i < N; i += (int64_t)gridDim.x * rows_per_step) {
+            const float l = dsl[i * H + hd], r = dsr[i * H + hd];
+            float v[VEC];
+            load_vec<VEC>(v, dh + i * HC + col);
+#pragma unroll
+            for (int c = 0; c < VEC; ++c) v[c] = fmaf(l, as[c], fmaf(r, ad[c], v[c]));
+            store_vec<VEC>(dh + i * HC + col, v);
+        }
     }
 }
 
@@ -561,9 +574,17 @@ gnn_status gnn_gatconv_backward(const gnn_graph *g, const gnn_graph *g_by_source
         if (d_grad_a_dst) GNN_TRY(gnn_launch_sum_partials(part_r, chunks, HC, d_grad_a_dst, s));
     }
     if (d_grad_x || d_grad_w) {
-        const int blocks = (int)std::min<int64_t>(gnn_div_up(N * HC, kThreads), 256 * 64);
-        hipLaunchKernelGGL(add_score_terms_kernel, dim3(blocks), dim3(kThreads), 0, s, dh, N, heads, ch, dsl, dsr,
-                           d_a_src, d_a_dst);
+        // 128-bit column groups when a head's channels come in fours and the attention vectors are aligned
+        const bool wide = ch % 4 == 0 && ((reinterpret_cast<uintptr_t>(d_a_src) | reinterpret_cast<uintptr_t>(d_a_dst)) & 15u) == 0;
+        const int groups = wide ? HC / 4 : HC;
+        const int rows_per_step = groups >= kThreads ? 1 : kThreads / groups;
+        const int blocks = (int)std::min<int64_t>(gnn_div_up(N, rows_per_step), 256 * 64);
+        if (wide)
+            hipLaunchKernelGGL(add_score_terms_kernel<4>, dim3(blocks), dim3(kThreads), 0, s, dh, N, heads, ch, dsl, dsr,
+                               d_a_src, d_a_dst);
+        else
+            hipLaunchKernelGGL(add_score_terms_kernel<1>, dim3(blocks), dim3(kThreads), 0, s, dh, N, heads, ch, dsl, dsr,
+                               d_a_src, d_a_dst);
         GNN_LAUNCH_CHECK();
     }
     if (d_grad_w) GNN_TRY(gnn_launch_xty(d_x, dh, N, f_in, HC, part, d_grad_w, s));
