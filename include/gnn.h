@@ -404,6 +404,8 @@ gnn_status gnn_gcnconv_backward(const gnn_graph *g, const gnn_graph *g_by_source
  * reduction over each neighbourhood followed by a per-edge rescale:
  *   out[k,h] = exp(s[k,h] - m[i,h]) / sum_{q: dst[q] = i} exp(s[q,h] - m[i,h]),  i = dst[k],
  * m = the segment maximum.  d_scores and d_out are [E x heads], both in the order `order` names.
+ * Scores must be finite.  float arithmetic; the terms of the denominator are formed with the hardware's 2^x
+ * (each within about (1 + |s - m|) * 2^-23 of its value), the numerator with the accurate exponential.
  * Needs gnn_graph_reserve(g, ., heads) once beforehand (else GNN_ERR_NOT_RESERVED); only enqueues kernels.
  */
 gnn_status gnn_segment_softmax(const gnn_graph *g, const float *d_scores, int32_t heads,
@@ -425,7 +427,8 @@ gnn_status gnn_segment_softmax_backward(const gnn_graph *g, const float *d_alpha
  *   h = X W  [N x heads*ch];  sl[j,hd] = <a_src[hd,:], h[j,hd,:]>;  sr[i,hd] = <a_dst[hd,:], h[i,hd,:]>
  *   s[k,hd] = lrelu(sl[src[k],hd] + sr[dst[k],hd]),  lrelu(v) = v > 0 ? v : negative_slope * v
  *   out[i,hd,:] = sum_k softmax_i(s)[k,hd] * h[src[k],hd,:]      (heads concatenated)
- * No bias, no activation; self-loops only if the edge list holds them.
+ * No bias, no activation; self-loops only if the edge list holds them.  The softmax weights are formed with the
+ * hardware's 2^x (each within about (1 + |s - m|) * 2^-23 of its value; they enter the result only as ratios).
  * d_w [f_in x heads*ch] row-major, d_a_src / d_a_dst [heads x ch], d_out [N x heads*ch].
  * d_softmax_stats (optional, may be NULL): [N x heads x 2] floats that receive, per destination and
  * head, the segment maximum of the scores and the softmax denominator relative to it (-inf and 0
