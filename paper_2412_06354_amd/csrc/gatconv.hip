@@ -204,7 +204,7 @@ template <int LPR, int VEC, int LPH>
 __device__ __forceinline__ void gat_long_pieces(const GatParams &p, int block)
 {
     constexpr int NSG = 64 / LPR;
-    constexpr int U = (LPR >= 8) ? 8 : LPR;
+    constexpr int U = (LPR >= 4) ? 4 : LPR;   // gathers in flight per lane (measured: 8 is slower)
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int sl_ = lane % LPR, sg = lane / LPR;
     const int it = block * kWavesPerBlock + wave;

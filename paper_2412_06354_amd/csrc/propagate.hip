@@ -350,7 +350,7 @@ template <int LPR, int VEC, int MSG, int RED, int XB>
 __device__ __forceinline__ void long_row_pieces(const PropParams &p, int block)
 {
     constexpr int NSG = 64 / LPR;
-    constexpr int U = (LPR >= 8) ? 8 : LPR;
+    constexpr int U = (LPR >= 4) ? 4 : LPR;   // gathers in flight per lane: more of them per wavefront did not pay (measured 2, 3, 4, 6, 8, 16)
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int sl = lane % LPR, sg = lane / LPR;
     const int it = block * kWavesPerBlock + wave;
