@@ -183,6 +183,120 @@ __global__ __launch_bounds__(kThreads) void xty_partial_kernel(const float *__re
     }
 }
 
+// The same contraction with both operands staged through LDS, for shapes whose rows are read as 128-bit pieces
+// (f_in, f_out multiples of 4, aligned arrays).  A block of four wavefronts (2 x 2) owns a row chunk and an output
+// tile of 2*TI*32 x 2*TJ*32; it walks the chunk in steps of kXtyRows rows: every thread loads its 16-byte pieces of
+// the next step's rows of X and Y (whole rows of the tile: coalesced, and each line is requested once per block
+// instead of once per wavefront), the pieces of the current step are written to LDS, and each wavefront reads its
+// MFMA operands from there -- lane (c, kk) takes column c of row 2m + kk, a conflict-free 32-bit read because the
+// LDS rows are padded by 32 floats.  The loads of a step have the whole MFMA work of the previous step to arrive
+// (a second register set, loads two steps ahead, changed nothing).
+constexpr int kXtyRows = 32;   // rows per step
+constexpr int kXtyPad = 32;    // floats between LDS rows: the two row halves of a read fall on different banks
+
+template <int COLS>   // columns of the staged tile
+struct XtyStage {
+    static constexpr int kPiecesPerRow = COLS / 4;
+    static constexpr int kRowsPerPass = kThreads / kPiecesPerRow;
+    static constexpr int kPasses = kXtyRows / kRowsPerPass;
+    static_assert(kThreads % kPiecesPerRow == 0 && kXtyRows % kRowsPerPass == 0, "stage shape");
+    float4 v[kPasses];
+
+    // rows [r, r + kXtyRows) of the chunk ending at r1, columns [c0, c0 + COLS) of a matrix with f columns
+    __device__ __forceinline__ void load(const float *__restrict__ m, int64_t r, int64_t r1, int f, int c0)
+    {
+        const int piece = threadIdx.x % kPiecesPerRow, row = threadIdx.x / kPiecesPerRow;
+        const int col = c0 + piece * 4;
+#pragma unroll
+        for (int q = 0; q < kPasses; ++q) {
+            const int64_t rr = r + q * kRowsPerPass + row;
+            v[q] = make_float4(0.f, 0.f, 0.f, 0.f);   // rows past the chunk and columns past the matrix add nothing
+            if (rr < r1 && col < f) v[q] = *reinterpret_cast<const float4 *>(m + rr * f + col);
+        }
+    }
+    __device__ __forceinline__ void store(float *lds) const
+    {
+        const int piece = threadIdx.x % kPiecesPerRow, row = threadIdx.x / kPiecesPerRow;
+#pragma unroll
+        for (int q = 0; q < kPasses; ++q)
+            *reinterpret_cast<float4 *>(lds + (q * kRowsPerPass + row) * (COLS + kXtyPad) + piece * 4) = v[q];
+    }
+};
+
+template <int TI, int TJ>
+__global__ __launch_bounds__(kThreads) void xty_staged_kernel(const float *__restrict__ x, const float *__restrict__ y,
+                                                              int64_t rows, int f_in, int f_out,
+                                                              int64_t rows_per_chunk, float *__restrict__ partial)
+{
+    constexpr int BI = 2 * TI * 32, BJ = 2 * TJ * 32;
+    __shared__ __align__(16) float xs[kXtyRows * (BI + kXtyPad)];
+    __shared__ __align__(16) float ys[kXtyRows * (BJ + kXtyPad)];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int c = lane & 31, kk = lane >> 5;
+    const int wi = wave & 1, wj = wave >> 1;
+    const int i0 = blockIdx.y * BI, j0 = blockIdx.z * BJ;
+    const int64_t r0 = (int64_t)blockIdx.x * rows_per_chunk, r1 = min(rows, r0 + rows_per_chunk);
+
+    floatx16 acc[TI][TJ];
+#pragma unroll
+    for (int a = 0; a < TI; ++a)
+#pragma unroll
+        for (int b = 0; b < TJ; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.0f;
+
+    const float *xa = xs + kk * (BI + kXtyPad) + wi * TI * 32 + c;
+    const float *yb = ys + kk * (BJ + kXtyPad) + wj * TJ * 32 + c;
+    auto row_pair = [&](int m) {
+        float a[TI], b[TJ];
+#pragma unroll
+        for (int ti = 0; ti < TI; ++ti) a[ti] = xa[2 * m * (BI + kXtyPad) + ti * 32];
+#pragma unroll
+        for (int tj = 0; tj < TJ; ++tj) b[tj] = yb[2 * m * (BJ + kXtyPad) + tj * 32];
+#pragma unroll
+        for (int ti = 0; ti < TI; ++ti)
+#pragma unroll
+            for (int tj = 0; tj < TJ; ++tj)
+                acc[ti][tj] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[ti], b[tj], acc[ti][tj], 0, 0, 0);
+    };
+    XtyStage<BI> sx;
+    XtyStage<BJ> sy;
+    if (r0 < r1) {
+        sx.load(x, r0, r1, f_in, i0);
+        sy.load(y, r0, r1, f_out, j0);
+    }
+    for (int64_t r = r0; r < r1; r += kXtyRows) {   // the same trip count for every thread of the block
+        __syncthreads();                           // the previous step's operand reads are done
+        sx.store(xs);
+        sy.store(ys);
+        __syncthreads();
+        if (r + kXtyRows < r1) {                    // in flight during this step's MFMAs
+            sx.load(x, r + kXtyRows, r1, f_in, i0);
+            sy.load(y, r + kXtyRows, r1, f_out, j0);
+        }
+        if (r + kXtyRows <= r1) {
+#pragma unroll 2
+            for (int m = 0; m < kXtyRows / 2; ++m) row_pair(m);
+        } else {   // a short last step does no work on its zero rows
+            const int pairs = ((int)(r1 - r) + 1) / 2;
+            for (int m = 0; m < pairs; ++m) row_pair(m);
+        }
+    }
+    // accumulator register v of lane l: row 8*(v/4) + 4*(l/32) + v%4, column l%32; an empty trailing chunk
+    // still writes its zeros (the sum over chunks reads them)
+    float *out = partial + (int64_t)blockIdx.x * f_in * f_out;
+#pragma unroll
+    for (int ti = 0; ti < TI; ++ti)
+#pragma unroll
+        for (int tj = 0; tj < TJ; ++tj)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int i = i0 + (wi * TI + ti) * 32 + 8 * (v / 4) + 4 * kk + (v % 4);
+                const int j = j0 + (wj * TJ + tj) * 32 + c;
+                if (i < f_in && j < f_out) out[(int64_t)i * f_out + j] = acc[ti][tj][v];
+            }
+}
+
 // out[q] = factor * sum over chunks of partial[chunk][q], in a fixed order: a block owns 64 elements, its SLICES
 // thread rows take the chunks round-robin (eight loads in flight each) and are folded through LDS in slice order.
 // SLICES = 16 where there are few elements (few blocks) and many chunks: the chain of dependent adds is what
@@ -332,11 +446,33 @@ static gnn_status launch_xty_tiles(const float *d_x, const float *d_y, int64_t r
     return launch_xty_shape<NT, 4>(d_x, d_y, rows, f_in, f_out, chunks, d_partial, s);
 }
 
+template <int TI, int TJ>
+static gnn_status launch_xty_staged(const float *d_x, const float *d_y, int64_t rows, int f_in, int f_out, int chunks,
+                                    float *d_partial, hipStream_t s)
+{
+    const int64_t rows_per_chunk = gnn_div_up(rows, chunks);
+    const dim3 grid((unsigned)chunks, (unsigned)gnn_div_up(f_in, 2 * TI * 32), (unsigned)gnn_div_up(f_out, 2 * TJ * 32));
+    hipLaunchKernelGGL((xty_staged_kernel<TI, TJ>), grid, dim3(kThreads), 0, s, d_x, d_y, rows, f_in, f_out,
+                       rows_per_chunk, d_partial);
+    GNN_LAUNCH_CHECK();
+    return GNN_OK;
+}
+
 gnn_status gnn_launch_xty(const float *d_x, const float *d_y, int64_t rows, int f_in, int f_out, float *d_partial,
                           float *d_out, hipStream_t s)
 {
-    // a wavefront holds 1, 2 or 4 accumulator tiles of 32 columns: no MFMA work on columns that do not exist
     const int chunks = gnn_row_chunk_count(rows);
+    // rows that can be read as 128-bit pieces and an output of at least 64 x 64: operands staged through LDS
+    const bool pieces = f_in % 4 == 0 && f_out % 4 == 0 &&
+                        ((reinterpret_cast<uintptr_t>(d_x) | reinterpret_cast<uintptr_t>(d_y)) & 15u) == 0;
+    if (pieces && f_in > 32 && f_out > 32) {
+        if (f_in > 64 && f_out > 64) GNN_TRY((launch_xty_staged<2, 2>(d_x, d_y, rows, f_in, f_out, chunks, d_partial, s)));
+        else if (f_in > 64) GNN_TRY((launch_xty_staged<2, 1>(d_x, d_y, rows, f_in, f_out, chunks, d_partial, s)));
+        else if (f_out > 64) GNN_TRY((launch_xty_staged<1, 2>(d_x, d_y, rows, f_in, f_out, chunks, d_partial, s)));
+        else GNN_TRY((launch_xty_staged<1, 1>(d_x, d_y, rows, f_in, f_out, chunks, d_partial, s)));
+        return gnn_launch_sum_partials(d_partial, chunks, (int64_t)f_in * f_out, d_out, s);
+    }
+    // a wavefront holds 1, 2 or 4 accumulator tiles of 32 columns: no MFMA work on columns that do not exist
     if (f_out <= 32) GNN_TRY(launch_xty_tiles<1>(d_x, d_y, rows, f_in, f_out, chunks, d_partial, s));
     else if (f_out <= 64) GNN_TRY(launch_xty_tiles<2>(d_x, d_y, rows, f_in, f_out, chunks, d_partial, s));
     else GNN_TRY(launch_xty_tiles<2>(d_x, d_y, rows, f_in, f_out, chunks, d_partial, s));   // wider: 64-column blocks

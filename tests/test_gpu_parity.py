@@ -672,7 +672,10 @@ def test_gcnconv_widths(gnn, loops, f_in, f_out, relu):
     g.close()
 
 
-@pytest.mark.parametrize("loops,f_in,f_out", [(True, 128, 128), (False, 128, 128), (True, 16, 64), (True, 37, 50)])
+@pytest.mark.parametrize("loops,f_in,f_out", [(True, 128, 128), (False, 128, 128), (True, 16, 64), (True, 37, 50),
+                                              # grad_W through the LDS-staged kernel: every tile shape, ragged tiles, several
+                                              # tiles per dimension
+                                              (True, 100, 64), (True, 64, 128), (True, 48, 40), (True, 200, 192)])
 def test_gcnconv_backward(gnn, loops, f_in, f_out):
     wl = synth.config1_gcn(num_nodes=20_000, pairs=100_000, f_in=f_in, f_out=f_out)
     n = wl.num_nodes
