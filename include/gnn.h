@@ -520,7 +520,10 @@ gnn_status gnn_gin_update(const gnn_graph *g, const float *d_x, int32_t feat_dim
  * gnn_example_model_forward: the chain above on a collated batch: GCNConv(f0 => f1) with self-loops and
  * bias, batch norm over all nodes of the batch (batch statistics) + relu, GCNConv(f1 => f2) + relu, mean
  * pooling per graph (d_graph_indicator as for gnn_graph_pool), Dense(f2, f3).  d_y is [num_graphs x f3].
- * It only sequences the entry points of this header on the caller's stream.
+ * It runs the kernels of those entry points on the caller's stream, with one fusion: the normalised
+ * activations are not written -- the second convolution's projection applies the normalisation and relu to the
+ * rows of the first one's output as it reads them (the same arithmetic: results equal the call-by-call chain
+ * bit for bit).
  * Workspaces: at least the matching *_workspace_bytes(), 256-byte aligned.
  */
 size_t gnn_batchnorm_workspace_bytes(int32_t num_rows, int32_t feat_dim);

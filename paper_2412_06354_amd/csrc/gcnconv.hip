@@ -21,17 +21,15 @@ size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
 
 }  // namespace
 
-extern "C" {
-
-size_t gnn_gcnconv_workspace_bytes(int32_t num_nodes, int32_t f_out)
+bool gnn_gcnconv_takes_column_norm(const gnn_graph *g, const float *d_x, int32_t f_in, const float *d_w, int32_t f_out)
 {
-    if (num_nodes <= 0 || f_out <= 0) return 0;
-    return align256((size_t)num_nodes * f_out * sizeof(float));
+    // the projection has to come first (it is what reads X), in the kernel that can normalise on the way in
+    return g && f_in >= f_out && gnn_xw_takes_column_norm(d_x, g->num_nodes, f_in, d_w, f_out);
 }
 
-gnn_status gnn_gcnconv(const gnn_graph *g, const float *d_x, int32_t f_in, const float *d_w, const float *d_bias,
-                       int32_t f_out, int32_t add_self_loops, gnn_activation act, float *d_out,
-                       void *d_workspace, size_t workspace_bytes, void *stream)
+gnn_status gnn_launch_gcnconv(const gnn_graph *g, const float *d_x, int32_t f_in, const float *d_w, const float *d_bias,
+                              int32_t f_out, int32_t add_self_loops, gnn_activation act, float *d_out,
+                              void *d_workspace, size_t workspace_bytes, void *stream, const gnn_column_norm *norm)
 {
     if (!g || !d_x || !d_w || !d_out || !d_workspace) return GNN_ERR_NULL;
     if (f_in <= 0 || f_out <= 0) return GNN_ERR_BAD_SIZE;
@@ -49,16 +47,33 @@ gnn_status gnn_gcnconv(const gnn_graph *g, const float *d_x, int32_t f_in, const
         agg.self_scale = add_self_loops ? 1.0f : 0.0f;
         agg.row_scale = dinv;
         agg.source_scale = dinv;
+        if (norm) return GNN_ERR_UNSUPPORTED;   // the gather reads X here
         GNN_TRY(gnn_launch_propagate(g, d_x, f_in, nullptr, 1, GNN_EDGE_ORDER_CSR, GNN_MSG_COPY_XJ, 0, agg, z, s));
         return gnn_launch_xw(z, N, f_in, d_w, f_out, nullptr, d_bias, act == GNN_ACT_RELU, d_out, s);
     }
-    GNN_TRY(gnn_dense_xw(d_x, N, f_in, d_w, f_out, dinv, z, stream));
+    GNN_TRY(gnn_launch_xw(d_x, N, f_in, d_w, f_out, dinv, nullptr, false, z, s, norm));
     gnn_epilogue epi;
     epi.self_scale = add_self_loops ? 1.0f : 0.0f;
     epi.row_scale = dinv;
     epi.bias = d_bias;
     epi.relu = (act == GNN_ACT_RELU);
     return gnn_launch_propagate(g, z, f_out, nullptr, 1, GNN_EDGE_ORDER_CSR, GNN_MSG_COPY_XJ, 0, epi, d_out, s);
+}
+
+extern "C" {
+
+size_t gnn_gcnconv_workspace_bytes(int32_t num_nodes, int32_t f_out)
+{
+    if (num_nodes <= 0 || f_out <= 0) return 0;
+    return align256((size_t)num_nodes * f_out * sizeof(float));
+}
+
+gnn_status gnn_gcnconv(const gnn_graph *g, const float *d_x, int32_t f_in, const float *d_w, const float *d_bias,
+                       int32_t f_out, int32_t add_self_loops, gnn_activation act, float *d_out,
+                       void *d_workspace, size_t workspace_bytes, void *stream)
+{
+    return gnn_launch_gcnconv(g, d_x, f_in, d_w, d_bias, f_out, add_self_loops, act, d_out, d_workspace,
+                              workspace_bytes, stream, nullptr);
 }
 
 }  // extern "C"

@@ -40,6 +40,7 @@ struct XwEpilogue {
     const float *row_scale = nullptr;
     const float *bias = nullptr;
     int relu = 0;
+    gnn_column_norm norm;   // applied to X on the way in when norm.mean is set (fast kernel only)
 };
 
 struct AFrag {
@@ -313,6 +314,66 @@ __device__ __forceinline__ void write_quarter(float *slab, const QuarterRegs &t,
     *reinterpret_cast<v4f *>(p + 4 * (192 + c1)) = t.v3;
 }
 
+// The column normalisation of the four k-values a lane holds of every row of a quarter (the lane's chunk is the
+// same in all four loads of a quarter): mean, 1/sqrt(var + eps), gamma, beta per value.
+struct NormQuarter {
+    v4f mean, inv, gamma, beta;
+};
+
+struct NormRegs {
+    NormQuarter q0, q1, q2, q3;
+    template <int Q>
+    __device__ __forceinline__ NormQuarter &quarter()
+    {
+        if constexpr (Q == 0) return q0;
+        else if constexpr (Q == 1) return q1;
+        else if constexpr (Q == 2) return q2;
+        else return q3;
+    }
+};
+
+template <int KQ, int Q = 0>
+__device__ __forceinline__ void load_norm(NormRegs &nr, const gnn_column_norm &cn, int k, int lane)
+{
+    if constexpr (Q < KQ) {
+        const int kb = min(32 * Q + 4 * (lane & 7), k - 4);   // the chunk load_quarter reads
+        NormQuarter &nq = nr.quarter<Q>();
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            nq.mean[c] = cn.mean[kb + c];
+            nq.inv[c] = 1.0f / sqrtf(cn.var[kb + c] + cn.eps);
+            nq.gamma[c] = cn.gamma ? cn.gamma[kb + c] : 1.0f;
+            nq.beta[c] = cn.beta ? cn.beta[kb + c] : 0.0f;
+        }
+        load_norm<KQ, Q + 1>(nr, cn, k, lane);
+    }
+}
+
+__device__ __forceinline__ v4f norm_chunk(v4f x, const NormQuarter &nq, int relu)
+{
+    v4f y;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        float v = nq.gamma[c] * ((x[c] - nq.mean[c]) * nq.inv[c]) + nq.beta[c];
+        y[c] = relu ? fmaxf(v, 0.0f) : v;
+    }
+    return y;
+}
+
+template <int KQ, int Q = 0>
+__device__ __forceinline__ void norm_tile(TileRegs &t, NormRegs &nr, int relu)
+{
+    if constexpr (Q < KQ) {
+        QuarterRegs &qr = t.quarter<Q>();
+        const NormQuarter &nq = nr.quarter<Q>();
+        qr.v0 = norm_chunk(qr.v0, nq, relu);
+        qr.v1 = norm_chunk(qr.v1, nq, relu);
+        qr.v2 = norm_chunk(qr.v2, nq, relu);
+        qr.v3 = norm_chunk(qr.v3, nq, relu);
+        norm_tile<KQ, Q + 1>(t, nr, relu);
+    }
+}
+
 template <int KQ, int Q>
 __device__ __forceinline__ void load_tile(TileRegs &t, const float *__restrict__ x, int64_t rows, int k, int64_t row0,
                                           int lane)
@@ -452,12 +513,13 @@ constexpr int fast_waves()
     return fit < kFastWavesMax ? fit : kFastWavesMax;
 }
 
-template <int NT, int KQ, bool SCALED>
+template <int NT, int KQ, bool SCALED, bool NORM = false>
 __global__ __launch_bounds__(kFastThreadsMax) void xw_fast_kernel(const float *__restrict__ x, int k,
                                                                   const float *__restrict__ w, int n,
                                                                   const float *__restrict__ row_scale,
                                                                   const float *__restrict__ bias, int relu,
-                                                                  float *__restrict__ z, int64_t rows)
+                                                                  float *__restrict__ z, int64_t rows,
+                                                                  const gnn_column_norm cn)
 {
     constexpr int BN = NT * 32;
     constexpr int KP = KQ * 32;
@@ -485,6 +547,8 @@ __global__ __launch_bounds__(kFastThreadsMax) void xw_fast_kernel(const float *_
     // W's loads are issued first, then the first tile's (clamped addresses: safe also for a wavefront without a
     // tile), which stay in flight while W is written to LDS.
     TileRegs t;
+    NormRegs nr;
+    if constexpr (NORM) load_norm<KQ>(nr, cn, k, lane);
     RowScales rs_next{}, rs_this{}, rs_prev{};   // row factors travel with their tile: loaded with it, used at its store
     {
         WStage<BN, KP, kStageThreads> st;
@@ -505,6 +569,7 @@ __global__ __launch_bounds__(kFastThreadsMax) void xw_fast_kernel(const float *_
     int64_t prev_row0 = -1;   // first row of the tile whose staged results `out` still holds
     for (; tile < num_tiles; tile += stride) {
         __builtin_amdgcn_sched_barrier(0);
+        if constexpr (NORM) norm_tile<KQ>(t, nr, cn.relu);   // k-values past the row's end meet zero rows of W
         write_tile<KQ>(slab, t, lane);
         __builtin_amdgcn_sched_barrier(0);   // the next tile is loaded into the same registers: no copies
         if (prev_row0 >= 0) store_staged_tile<NT, SCALED>(out, rs_prev, prev_row0, rows, n, n0, lane, bias, relu, z);
@@ -607,12 +672,16 @@ gnn_status launch_fast(const float *d_x, int64_t rows, int k, const float *d_w, 
     const int col_blocks = (int)gnn_div_up(n, BN);
     const int64_t blocks = std::max<int64_t>(1, std::min<int64_t>(device_cu_count() / col_blocks, tiles));
     const dim3 grid((unsigned)blocks, (unsigned)col_blocks);
-    if (ep.row_scale)
+    if (ep.norm.mean) {   // the one user: a graph convolution (row factors) reading batch-normalised rows
+        if (!ep.row_scale) return GNN_ERR_UNSUPPORTED;
+        hipLaunchKernelGGL((xw_fast_kernel<NT, KQ, true, true>), grid, dim3(64 * WAVES), lds, s, d_x, k, d_w, n,
+                           ep.row_scale, ep.bias, ep.relu, d_z, rows, ep.norm);
+    } else if (ep.row_scale)
         hipLaunchKernelGGL((xw_fast_kernel<NT, KQ, true>), grid, dim3(64 * WAVES), lds, s, d_x, k, d_w, n,
-                           ep.row_scale, ep.bias, ep.relu, d_z, rows);
+                           ep.row_scale, ep.bias, ep.relu, d_z, rows, ep.norm);
     else
         hipLaunchKernelGGL((xw_fast_kernel<NT, KQ, false>), grid, dim3(64 * WAVES), lds, s, d_x, k, d_w, n,
-                           ep.row_scale, ep.bias, ep.relu, d_z, rows);
+                           ep.row_scale, ep.bias, ep.relu, d_z, rows, ep.norm);
     GNN_LAUNCH_CHECK();
     return GNN_OK;
 }
@@ -650,8 +719,21 @@ int choose_column_tiles(int64_t rows, int n)
 
 }  // namespace
 
+static bool takes_fast_kernel(const float *d_x, int32_t k, const float *d_w, int32_t n)
+{
+    const bool x_vec4 = (k % 4 == 0) && ((reinterpret_cast<uintptr_t>(d_x) & 15u) == 0);
+    const bool w_vec4 = (n % 4 == 0) && ((reinterpret_cast<uintptr_t>(d_w) & 15u) == 0);
+    return x_vec4 && w_vec4 && k <= 2 * kSlab;   // w_vec4 implies n % 4 == 0
+}
+
+bool gnn_xw_takes_column_norm(const float *d_x, int64_t rows, int32_t k, const float *d_w, int32_t n)
+{
+    return rows > 0 && k > 0 && n > 0 && takes_fast_kernel(d_x, k, d_w, n);
+}
+
 gnn_status gnn_launch_xw(const float *d_x, int64_t rows, int32_t k, const float *d_w, int32_t n,
-                         const float *d_row_scale, const float *d_bias, bool relu, float *d_z, hipStream_t s)
+                         const float *d_row_scale, const float *d_bias, bool relu, float *d_z, hipStream_t s,
+                         const gnn_column_norm *norm)
 {
     if (!d_x || !d_w || !d_z) return GNN_ERR_NULL;
     if (rows < 0 || k <= 0 || n <= 0) return GNN_ERR_BAD_SIZE;
@@ -660,9 +742,13 @@ gnn_status gnn_launch_xw(const float *d_x, int64_t rows, int32_t k, const float 
     ep.row_scale = d_row_scale;
     ep.bias = d_bias;
     ep.relu = relu ? 1 : 0;
+    if (norm) {
+        if (!norm->mean || !norm->var || !d_row_scale || !takes_fast_kernel(d_x, k, d_w, n)) return GNN_ERR_UNSUPPORTED;
+        ep.norm = *norm;
+    }
     const bool x_vec4 = (k % 4 == 0) && ((reinterpret_cast<uintptr_t>(d_x) & 15u) == 0);
     const bool w_vec4 = (n % 4 == 0) && ((reinterpret_cast<uintptr_t>(d_w) & 15u) == 0);
-    if (x_vec4 && w_vec4 && k <= 2 * kSlab) {   // w_vec4 implies n % 4 == 0
+    if (takes_fast_kernel(d_x, k, d_w, n)) {
         switch (choose_column_tiles(rows, n)) {
         case 1: return launch_fast_for_k<1>(d_x, rows, k, d_w, n, ep, d_z, s);
         case 2: return launch_fast_for_k<2>(d_x, rows, k, d_w, n, ep, d_z, s);

@@ -213,9 +213,27 @@ gnn_status gnn_launch_sum_partials(const float *d_partial, int chunks, int64_t e
 gnn_status gnn_launch_pool_backward(const int32_t *d_graph_indicator, int32_t num_nodes, int32_t num_graphs,
                                     const float *d_grad_out, int32_t feat_dim, gnn_aggr aggr, const float *d_relu_y,
                                     float *d_grad_x, hipStream_t stream);
+// A batch normalisation (with its optional relu) applied to the rows of X as they are read, so that the
+// normalised matrix is never written:  x'[r,f] = act(gamma[f] * ((x[r,f] - mean[f]) / sqrt(var[f] + eps)) + beta[f]),
+// the arithmetic of gnn_batchnorm's own pass, operation for operation.  gamma / beta may be null (1 / 0).
+struct gnn_column_norm {
+    const float *mean = nullptr, *var = nullptr, *gamma = nullptr, *beta = nullptr;
+    float eps = 0.0f;
+    int relu = 0;
+};
+// True if gnn_launch_xw would take the kernel that can apply a gnn_column_norm to X for this shape.
+bool gnn_xw_takes_column_norm(const float *d_x, int64_t rows, int32_t k, const float *d_w, int32_t n);
 // Z = X W with the store's epilogue: optional per-row scale, then per-column bias, then relu (gemm.hip).
+// norm (optional): X is normalised on the way in; only where gnn_xw_takes_column_norm says so (else GNN_ERR_UNSUPPORTED).
 gnn_status gnn_launch_xw(const float *d_x, int64_t rows, int32_t k, const float *d_w, int32_t n,
-                         const float *d_row_scale, const float *d_bias, bool relu, float *d_z, hipStream_t s);
+                         const float *d_row_scale, const float *d_bias, bool relu, float *d_z, hipStream_t s,
+                         const gnn_column_norm *norm = nullptr);
+// gnn_gcnconv with an optional batch normalisation of X applied as the projection reads it (gcnconv.hip); with a
+// norm only where gnn_gcnconv_takes_column_norm says so.
+bool gnn_gcnconv_takes_column_norm(const gnn_graph *g, const float *d_x, int32_t f_in, const float *d_w, int32_t f_out);
+gnn_status gnn_launch_gcnconv(const gnn_graph *g, const float *d_x, int32_t f_in, const float *d_w, const float *d_bias,
+                              int32_t f_out, int32_t add_self_loops, gnn_activation act, float *d_out,
+                              void *d_workspace, size_t workspace_bytes, void *stream, const gnn_column_norm *norm);
 // wt[cols x rows] = w[rows x cols]^T
 gnn_status gnn_launch_transpose(const float *d_w, int rows, int cols, float *d_wt, hipStream_t stream);
 // sl[i,hd] = <a_src[hd,:], h[i,hd,:]>, sr[i,hd] = <a_dst[hd,:], h[i,hd,:]>  (gatconv.hip)

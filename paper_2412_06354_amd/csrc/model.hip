@@ -213,6 +213,30 @@ ChainLayout chain_layout(int64_t N, int G, int f1, int f2)
     return l;
 }
 
+// Column means and (biased) variances of x [N x F]: one launch for few rows, else per-chunk moments and their merge.
+gnn_status launch_column_moments(const float *d_x, int64_t N, int F, float *d_mean, float *d_var, void *d_workspace,
+                                 size_t workspace_bytes, hipStream_t s)
+{
+    if (N <= kSmallRows) {
+        hipLaunchKernelGGL(small_column_stats_kernel, dim3((unsigned)gnn_div_up(F, kSmallCols)), dim3(kSmallThreads), 0, s, d_x, (int)N,
+                           F, d_mean, d_var);
+        GNN_LAUNCH_CHECK();
+        return GNN_OK;
+    }
+    if (!d_workspace) return GNN_ERR_NULL;
+    if (workspace_bytes < gnn_batchnorm_workspace_bytes((int32_t)N, F)) return GNN_ERR_BAD_SIZE;
+    const int chunks = gnn_row_chunk_count(N);
+    const int64_t rows_per_chunk = gnn_div_up(N, chunks);
+    float *part_m = static_cast<float *>(d_workspace), *part_q = part_m + (size_t)chunks * F;
+    hipLaunchKernelGGL(column_moments_partial_kernel, dim3((unsigned)chunks), dim3(kThreads), 0, s, d_x, N, F,
+                       rows_per_chunk, part_m, part_q);
+    GNN_LAUNCH_CHECK();
+    hipLaunchKernelGGL(column_moments_merge_kernel, dim3((unsigned)gnn_div_up(F, kMergeCols)), dim3(kMergeThreads), 0,
+                       s, part_m, part_q, chunks, N, rows_per_chunk, F, d_mean, d_var);
+    GNN_LAUNCH_CHECK();
+    return GNN_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -234,23 +258,7 @@ gnn_status gnn_batchnorm(const float *d_x, int32_t num_rows, int32_t feat_dim, c
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int64_t N = num_rows;
     const int F = feat_dim;
-    if (!use_given_stats && N <= kSmallRows) {
-        hipLaunchKernelGGL(small_column_stats_kernel, dim3((unsigned)gnn_div_up(F, kSmallCols)), dim3(kSmallThreads), 0, s, d_x, (int)N,
-                           F, d_mean, d_var);
-        GNN_LAUNCH_CHECK();
-    } else if (!use_given_stats) {
-        if (!d_workspace) return GNN_ERR_NULL;
-        if (workspace_bytes < gnn_batchnorm_workspace_bytes(num_rows, feat_dim)) return GNN_ERR_BAD_SIZE;
-        const int chunks = gnn_row_chunk_count(N);
-        const int64_t rows_per_chunk = gnn_div_up(N, chunks);
-        float *part_m = static_cast<float *>(d_workspace), *part_q = part_m + (size_t)chunks * F;
-        hipLaunchKernelGGL(column_moments_partial_kernel, dim3((unsigned)chunks), dim3(kThreads), 0, s, d_x, N, F,
-                           rows_per_chunk, part_m, part_q);
-        GNN_LAUNCH_CHECK();
-        hipLaunchKernelGGL(column_moments_merge_kernel, dim3((unsigned)gnn_div_up(F, kMergeCols)), dim3(kMergeThreads), 0,
-                           s, part_m, part_q, chunks, N, rows_per_chunk, F, d_mean, d_var);
-        GNN_LAUNCH_CHECK();
-    }
+    if (!use_given_stats) GNN_TRY(launch_column_moments(d_x, N, F, d_mean, d_var, d_workspace, workspace_bytes, s));
     const int blocks = (int)std::min<int64_t>(gnn_div_up(N * F, kThreads), 256 * 64);
     hipLaunchKernelGGL(normalise_rows_kernel, dim3(blocks), dim3(kThreads), 0, s, d_x, N, F, d_mean, d_var, d_gamma,
                        d_beta, eps, act == GNN_ACT_RELU ? 1 : 0, d_out);
@@ -294,8 +302,17 @@ gnn_status gnn_example_model_forward(const gnn_graph *g, const int32_t *d_graph_
     const size_t gcn_bytes = l.bn - l.gcn, bn_bytes = l.total - l.bn;
 
     GNN_TRY(gnn_gcnconv(g, d_x, f0, d_w1, d_b1, f1, 1, GNN_ACT_NONE, h1, gcn_ws, gcn_bytes, stream));
-    GNN_TRY(gnn_batchnorm(h1, N, f1, d_gamma, d_beta, eps, GNN_ACT_RELU, 0, mean, var, h2, bn_ws, bn_bytes, stream));
-    GNN_TRY(gnn_gcnconv(g, h2, f1, d_w2, d_b2, f2, 1, GNN_ACT_RELU, h3, gcn_ws, gcn_bytes, stream));
+    if (gnn_gcnconv_takes_column_norm(g, h1, f1, d_w2, f2) && eps >= 0.0f) {
+        // The normalised activations are never written: the second convolution's projection normalises the rows
+        // of h1 as it reads them (the statistics need their own pass over h1 first).
+        GNN_TRY(launch_column_moments(h1, N, f1, mean, var, bn_ws, bn_bytes, static_cast<hipStream_t>(stream)));
+        gnn_column_norm norm;
+        norm.mean = mean; norm.var = var; norm.gamma = d_gamma; norm.beta = d_beta; norm.eps = eps; norm.relu = 1;
+        GNN_TRY(gnn_launch_gcnconv(g, h1, f1, d_w2, d_b2, f2, 1, GNN_ACT_RELU, h3, gcn_ws, gcn_bytes, stream, &norm));
+    } else {
+        GNN_TRY(gnn_batchnorm(h1, N, f1, d_gamma, d_beta, eps, GNN_ACT_RELU, 0, mean, var, h2, bn_ws, bn_bytes, stream));
+        GNN_TRY(gnn_gcnconv(g, h2, f1, d_w2, d_b2, f2, 1, GNN_ACT_RELU, h3, gcn_ws, gcn_bytes, stream));
+    }
     GNN_TRY(gnn_graph_pool(d_graph_indicator, N, num_graphs, h3, f2, GNN_AGGR_MEAN, pooled, stream));
     return gnn_dense(pooled, num_graphs, f2, d_w3, f3, d_b3, GNN_ACT_NONE, d_y, stream);
 }
