@@ -733,7 +733,11 @@ def test_example_model(gnn):
     the same order and must reproduce the stage-by-stage GPU result bit for bit, and agrees with the
     oracle's end-to-end prediction to 1e-4 (five stages of at most 1e-5 each, none of which amplifies:
     the normalisation bounds the activations)."""
-    for kwargs in (dict(), dict(num_graphs=300, n=40, p=0.1)):
+    # widths: the default takes the fused normalisation in the second convolution's projection (as do 100 => 36:
+    # four k quarters, the last one ragged); 32 => 64 widens (the gather reads the normalised rows: not fused),
+    # 30 => 30 cannot be read in 128-bit pieces (general projection kernel: not fused)
+    for kwargs in (dict(), dict(num_graphs=300, n=40, p=0.1), dict(num_graphs=300, n=40, p=0.1, f1=100, f2=36),
+                   dict(num_graphs=40, n=30, p=0.1, f1=32, f2=64), dict(num_graphs=40, n=30, p=0.1, f1=30, f2=30)):
         wl = synth.config5_example_model(**kwargs)
         n, ng, p = wl.num_nodes, wl.num_graphs, wl.params
         ref = oracle.example_model_forward(wl.src, wl.dst, n, wl.graph_indicator, ng, wl.x, p)
