@@ -148,8 +148,8 @@ gnn_status gnn_build_csr_bipartite(const int32_t *d_src, const int32_t *d_dst, i
 
 /*
  * gnn_build_csr keeps its temporaries (about 16 bytes per edge) in one device buffer per process between
- * calls, and gnn_graph_destroy keeps the arrays of one destroyed graph (the largest it has seen) for the next
- * build of a similar size, so that building and destroying graph after graph -- one per mini-batch -- does not
+ * calls, and gnn_graph_destroy keeps the arrays of one destroyed graph, or of one batch of graphs once its last
+ * handle is destroyed (the largest block it has seen), for the next build or batch build of a similar size, so that building and destroying graph after graph -- one per mini-batch -- does not
  * allocate and free each time.  This call frees both (GNN_ERR_UNSUPPORTED, with the graph arrays already
  * freed, if a build is using the temporaries on another thread); the next build allocates again.
  */

@@ -656,25 +656,46 @@ struct slab_cache {
 };
 slab_cache g_slab_cache;
 
+// Offers a block that is no longer used to the cache; returns the block to free (the offered one, the smaller one
+// it replaces, or none).
+void *slab_cache_put(void *ptr, size_t bytes, int device)
+{
+    if (!ptr) return nullptr;
+    std::lock_guard<std::mutex> lock(g_slab_cache.mu);
+    slab_cache &c = g_slab_cache;
+    if (c.ptr && c.bytes >= bytes) return ptr;
+    void *drop = c.ptr;
+    c.ptr = ptr;
+    c.bytes = bytes;
+    c.device = device;
+    return drop;
+}
+
+// Takes the cached block if it is on this device, large enough and at most twice what is needed.
+bool slab_cache_take(size_t bytes, int device, void **ptr, size_t *got_bytes)
+{
+    std::lock_guard<std::mutex> lock(g_slab_cache.mu);
+    slab_cache &c = g_slab_cache;
+    if (!(c.ptr && c.device == device && c.bytes >= bytes && c.bytes / 2 <= bytes)) return false;
+    *ptr = c.ptr;
+    *got_bytes = c.bytes;
+    c.ptr = nullptr;
+    c.bytes = 0;
+    c.device = -1;
+    return true;
+}
+
 void free_graph_arrays(gnn_graph *g)
 {
-    void *drop = g->slab;
-    if (g->shared) {   // one allocation for a batch of graphs: freed with the last of them
-        drop = nullptr;
+    void *drop = nullptr;
+    if (g->shared) {   // one allocation for a batch of graphs: given up with the last of them
         if (g->shared->refs.fetch_sub(1) == 1) {
-            drop = g->shared->ptr;
+            drop = slab_cache_put(g->shared->ptr, g->shared->bytes, g->shared->device);
             delete g->shared;
         }
         g->shared = nullptr;
     } else if (g->slab) {
-        std::lock_guard<std::mutex> lock(g_slab_cache.mu);
-        slab_cache &c = g_slab_cache;
-        if (!c.ptr || c.bytes < g->slab_bytes) {
-            drop = c.ptr;
-            c.ptr = g->slab;
-            c.bytes = g->slab_bytes;
-            c.device = g->device;
-        }
+        drop = slab_cache_put(g->slab, g->slab_bytes, g->device);
     }
     if (drop) (void)hipFree(drop);
     if (g->own_scratch) (void)hipFree(g->own_scratch);
@@ -712,18 +733,7 @@ gnn_status graph_slab_acquire(gnn_graph *g, size_t bytes)
     int dev = 0;
     GNN_HIP(hipGetDevice(&dev));
     g->device = dev;
-    {
-        std::lock_guard<std::mutex> lock(g_slab_cache.mu);
-        slab_cache &c = g_slab_cache;
-        if (c.ptr && c.device == dev && c.bytes >= bytes && c.bytes / 2 <= bytes) {
-            g->slab = c.ptr;
-            g->slab_bytes = c.bytes;
-            c.ptr = nullptr;
-            c.bytes = 0;
-            c.device = -1;
-            return GNN_OK;
-        }
-    }
+    if (slab_cache_take(bytes, dev, &g->slab, &g->slab_bytes)) return GNN_OK;
     GNN_TRY(slab_alloc(&g->slab, bytes));
     g->slab_bytes = bytes ? bytes : 256;
     return GNN_OK;
@@ -1156,7 +1166,11 @@ gnn_status gnn_build_csr_batch(int32_t num_snapshots, const int32_t *const *d_sr
     }
     shared = new (std::nothrow) shared_slab();
     if (!shared) return fail(GNN_ERR_ALLOC);
-    if ((st = slab_alloc(&slab, slab_bytes)) != GNN_OK) return fail(st);
+    // like a single build, a batch takes over the arrays of a destroyed graph (or batch) of a similar size
+    shared->device = dev;
+    shared->bytes = slab_bytes ? slab_bytes : 256;
+    if (!slab_cache_take(slab_bytes, dev, &slab, &shared->bytes) && (st = slab_alloc(&slab, slab_bytes)) != GNN_OK)
+        return fail(st);
     if ((st = temp_acquire(&lease, flag_bytes + table_bytes + temp_bytes)) != GNN_OK) return fail(st);
     tmp = lease.ptr;
     if (hipMemsetAsync(tmp, 0, flag_bytes, s) != hipSuccess) return fail(GNN_ERR_DEVICE);

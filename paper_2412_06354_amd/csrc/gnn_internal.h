@@ -53,6 +53,8 @@ struct gnn_temp_pool {
 // One device allocation shared by the graphs of a batch build; freed when the last of them is destroyed.
 struct shared_slab {
     void *ptr = nullptr;
+    size_t bytes = 0;
+    int device = -1;
     std::atomic<int> refs{0};
 };
 
