@@ -236,6 +236,46 @@ def test_batch_build_of_many_small_snapshots(gnn):
         g.close()
 
 
+def test_batch_and_single_builds_hand_their_arrays_on(gnn):
+    """The arrays of a destroyed graph, or of a batch whose last handle is gone, serve the next build or batch of a
+    similar size.  Whatever the block held before, every build equals the oracle's CSR and a fresh build's lists."""
+    n = 3000
+    snaps = [synth.chung_lu_directed(n, e, 1.0, 400.0, 900 + t) for t, e in enumerate((40_000, 35_000, 50_000))]
+    whole = (np.concatenate([s for s, _ in snaps]), np.concatenate([d for _, d in snaps]))
+    gnn.lib().gnn_release_cached_memory()
+    fresh = [gnn.build_csr(dev(s), dev(d), n) for s, d in snaps]
+    lists = [(g.work_sizes(), g.work_lists()) for g in fresh]
+    for g in fresh:
+        g.close()
+
+    def check_batch(graphs):
+        for t, (g, (src, dst)) in enumerate(zip(graphs, snaps)):
+            rowptr, colidx, perm, _ = oracle.build_csr(src, dst, n)
+            np.testing.assert_array_equal(host(g.rowptr), rowptr, err_msg=f"snapshot {t}")
+            np.testing.assert_array_equal(host(g.colidx), colidx, err_msg=f"snapshot {t}")
+            np.testing.assert_array_equal(host(g.perm), perm, err_msg=f"snapshot {t}")
+            assert g.work_sizes() == lists[t][0]
+            assert all(torch.equal(g.work_lists()[k], lists[t][1][k]) for k in lists[t][1])
+
+    for _ in range(3):   # batch -> batch (the second and third take the block the previous one gave back)
+        graphs = gnn.build_csr_batch([dev(s) for s, _ in snaps], [dev(d) for _, d in snaps], n)
+        check_batch(graphs)
+        for g in reversed(graphs):
+            g.close()
+    # batch -> single build of about the same total size -> batch
+    g = gnn.build_csr(dev(whole[0]), dev(whole[1]), n)
+    rowptr, colidx, perm, _ = oracle.build_csr(whole[0], whole[1], n)
+    np.testing.assert_array_equal(host(g.rowptr), rowptr)
+    np.testing.assert_array_equal(host(g.colidx), colidx)
+    np.testing.assert_array_equal(host(g.perm), perm)
+    g.close()
+    graphs = gnn.build_csr_batch([dev(s) for s, _ in snaps], [dev(d) for _, d in snaps], n)
+    check_batch(graphs)
+    for g in graphs:
+        g.close()
+    assert gnn.lib().gnn_release_cached_memory() == 0
+
+
 def test_batch_build_beyond_one_launch_group(gnn):
     """More snapshots than one launch takes in its second grid dimension (32 768): the batch is built in groups;
     handles on both sides of the group boundary, the first and the last equal the oracle's CSR."""
