@@ -1,10 +1,10 @@
 // Backward of GCNConv (the layer of the paper's training example, which is differentiated end to
 // end).  With Ahat = D^-1/2 (A [+ I]) D^-1/2 and G = dL/d out:
 //     T = Ahat^T G,    dL/dX = T W^T,    dL/dW = X^T T,    dL/db = column sums of G.
-//   * T is a propagate over the graph sorted by source: rows of G are pre-scaled by the destination
-//     side factor, gathered and summed, and the epilogue adds the self-loop term and applies the
-//     source side factor -- the forward's fused kernel run on the transposed topology (the degree
-//     factors always come from the forward graph's in-degrees);
+//   * T is a propagate over the graph sorted by source: rows of G are gathered with the destination
+//     side factor as a weight looked up per edge (G is never rescaled in memory), summed, and the epilogue
+//     adds the self-loop term and applies the source side factor -- the forward's fused kernel run on the
+//     transposed topology (the degree factors always come from the forward graph's in-degrees);
 //   * T W^T is the MFMA projection kernel on a transposed copy of W;
 //   * X^T T contracts over the N rows: v_mfma_f32_32x32x2_f32 consumes two rows per instruction and
 //     both operands are read along rows (coalesced); row chunks give partial [f_in x f_out] blocks
@@ -22,15 +22,13 @@ namespace {
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 constexpr int kThreads = 256;
 
-// One pass over G for both of its uses: out[r,:] = scale[r] * G[r,:] (the rows the propagate gathers; out may be
-// null) and partial[chunk][j] = sum over the chunk's rows of G[r][j] (the bias gradient's first stage; partial may
-// be null).  A block owns a row chunk; its threads form (row slice, column group) pairs, a slice takes every
-// `slices`-th row, and the slices' sums are folded through LDS in slice order.
+// First stage of the bias gradient: partial[chunk][j] = sum over the chunk's rows of G[r][j].  A block owns a row
+// chunk; its threads form (row slice, column group) pairs, a slice takes every `slices`-th row, and the slices'
+// sums are folded through LDS in slice order.
 template <int VEC>
-__global__ __launch_bounds__(kThreads) void scale_rows_colsum_kernel(const float *__restrict__ scale, int64_t N, int F,
-                                                                     const float *__restrict__ g,
-                                                                     int64_t rows_per_chunk, float *__restrict__ out,
-                                                                     float *__restrict__ partial)
+__global__ __launch_bounds__(kThreads) void column_sums_partial_kernel(int64_t N, int F, const float *__restrict__ g,
+                                                                       int64_t rows_per_chunk,
+                                                                       float *__restrict__ partial)
 {
     __shared__ float fold[kThreads * VEC];
     const int fv = F / VEC;
@@ -55,16 +53,9 @@ __global__ __launch_bounds__(kThreads) void scale_rows_colsum_kernel(const float
                 }
 #pragma unroll
                 for (int c = 0; c < VEC; ++c) sum[c] += v[c];
-                if (out) {
-                    const float sc = scale[r];
-                    if constexpr (VEC == 4)
-                        *reinterpret_cast<float4 *>(out + r * F + cg * 4) = make_float4(v[0] * sc, v[1] * sc, v[2] * sc, v[3] * sc);
-                    else
-                        out[r * F + cg] = v[0] * sc;
-                }
             }
         }
-        if (partial) {   // block-uniform
+        {
 #pragma unroll
             for (int c = 0; c < VEC; ++c) fold[threadIdx.x * VEC + c] = sum[c];
             __syncthreads();
@@ -519,23 +510,20 @@ gnn_status gnn_gcnconv_backward(const gnn_graph *g, const gnn_graph *g_by_source
 
     const bool narrow_first = f_in < f_out;   // the order gnn_gcnconv runs this shape in
     const bool need_t = !narrow_first && (d_grad_x || d_grad_w);
-    if (need_t || d_grad_b) {
-        // G is read once: scaled rows for the propagate and the first stage of the bias gradient (64-row chunks:
-        // enough blocks to stream at full rate; the partial sums fit the workspace's partial-result area)
+    if (d_grad_b) {
+        // column sums of G in two stages (64-row chunks: enough blocks to stream at full rate; the partial sums fit
+        // the workspace's partial-result area)
         const int64_t bias_chunks = std::max<int64_t>(
             1, std::min<int64_t>(std::min<int64_t>(2048, gnn_div_up(N, 64)), (int64_t)chunks * f_in));
         const int64_t bias_rows = gnn_div_up(N, bias_chunks);
         const dim3 grid((unsigned)gnn_div_up(N, bias_rows));
-        const bool vec4 = f_out % 4 == 0 && ((reinterpret_cast<uintptr_t>(d_grad_out) | reinterpret_cast<uintptr_t>(gs)) & 15u) == 0;
-        float *scaled = need_t ? gs : nullptr, *bias_part = d_grad_b ? part : nullptr;
+        const bool vec4 = f_out % 4 == 0 && (reinterpret_cast<uintptr_t>(d_grad_out) & 15u) == 0;
         if (vec4)
-            hipLaunchKernelGGL(scale_rows_colsum_kernel<4>, grid, dim3(kThreads), 0, s, dinv, N, f_out, d_grad_out,
-                               bias_rows, scaled, bias_part);
+            hipLaunchKernelGGL(column_sums_partial_kernel<4>, grid, dim3(kThreads), 0, s, N, f_out, d_grad_out, bias_rows, part);
         else
-            hipLaunchKernelGGL(scale_rows_colsum_kernel<1>, grid, dim3(kThreads), 0, s, dinv, N, f_out, d_grad_out,
-                               bias_rows, scaled, bias_part);
+            hipLaunchKernelGGL(column_sums_partial_kernel<1>, grid, dim3(kThreads), 0, s, N, f_out, d_grad_out, bias_rows, part);
         GNN_LAUNCH_CHECK();
-        if (d_grad_b) GNN_TRY(gnn_launch_sum_partials(part, (int)grid.x, (int64_t)f_out, d_grad_b, s));
+        GNN_TRY(gnn_launch_sum_partials(part, (int)grid.x, (int64_t)f_out, d_grad_b, s));
     }
     if (narrow_first) {
         if (d_grad_w) {   // t = Ahat X [N x f_in], then (Ahat X)^T G
@@ -561,8 +549,9 @@ gnn_status gnn_gcnconv_backward(const gnn_graph *g, const gnn_graph *g_by_source
         gnn_epilogue epi;
         epi.self_scale = add_self_loops ? 1.0f : 0.0f;
         epi.row_scale = dinv;
-        GNN_TRY(gnn_launch_propagate(g_by_source, gs, f_out, nullptr, 1, GNN_EDGE_ORDER_CSR, GNN_MSG_COPY_XJ, 0, epi,
-                                     t, s));
+        epi.source_scale = dinv;   // the gathered row's factor rides on the edge: G is never rescaled in memory
+        GNN_TRY(gnn_launch_propagate(g_by_source, d_grad_out, f_out, nullptr, 1, GNN_EDGE_ORDER_CSR, GNN_MSG_COPY_XJ, 0,
+                                     epi, t, s));
     }
     if (d_grad_x) {
         GNN_TRY(gnn_launch_transpose(d_w, f_in, f_out, wt, s));
