@@ -589,8 +589,7 @@ gnn_status gnn_gatconv_backward(const gnn_graph *g, const gnn_graph *g_by_source
     }
     if (d_grad_w) GNN_TRY(gnn_launch_xty(d_x, dh, N, f_in, HC, part, d_grad_w, s));
     if (d_grad_x) {
-        GNN_TRY(gnn_launch_transpose(d_w, f_in, HC, wt, s));
-        GNN_TRY(gnn_dense_xw(dh, N, HC, wt, f_in, nullptr, d_grad_x, stream));
+        GNN_TRY(gnn_launch_xwt(dh, N, HC, d_w, f_in, nullptr, wt, d_grad_x, s));
     }
     return GNN_OK;
 }

@@ -5,7 +5,8 @@
 //     side factor as a weight looked up per edge (G is never rescaled in memory), summed, and the epilogue
 //     adds the self-loop term and applies the source side factor -- the forward's fused kernel run on the
 //     transposed topology (the degree factors always come from the forward graph's in-degrees);
-//   * T W^T is the MFMA projection kernel on a transposed copy of W;
+//   * T W^T is the MFMA projection kernel, which stages W transposed anyway and reads the forward's W as it is
+//     (shapes that kernel does not take go through a transposed copy of W);
 //   * X^T T contracts over the N rows: v_mfma_f32_32x32x2_f32 consumes two rows per instruction and
 //     both operands are read along rows (coalesced); row chunks give partial [f_in x f_out] blocks
 //     that a second kernel adds up in chunk order (deterministic);
@@ -478,6 +479,15 @@ gnn_status gnn_launch_transpose(const float *d_w, int rows, int cols, float *d_w
     return GNN_OK;
 }
 
+gnn_status gnn_launch_xwt(const float *d_x, int64_t rows, int32_t k, const float *d_w, int32_t n,
+                          const float *d_row_scale, float *d_wt, float *d_z, hipStream_t s)
+{
+    if (gnn_xw_takes_transposed_w(d_x, rows, k, d_w, n))
+        return gnn_launch_xw(d_x, rows, k, d_w, n, d_row_scale, nullptr, false, d_z, s, nullptr, true);
+    GNN_TRY(gnn_launch_transpose(d_w, n, k, d_wt, s));
+    return gnn_launch_xw(d_x, rows, k, d_wt, n, d_row_scale, nullptr, false, d_z, s);
+}
+
 extern "C" {
 
 size_t gnn_gcnconv_backward_workspace_bytes(int32_t num_nodes, int32_t f_in, int32_t f_out)
@@ -535,8 +545,7 @@ gnn_status gnn_gcnconv_backward(const gnn_graph *g, const gnn_graph *g_by_source
             GNN_TRY(gnn_launch_xty(t, d_grad_out, N, f_in, f_out, part, d_grad_w, s));
         }
         if (d_grad_x) {   // gs = dinv * (G W^T) [N x f_in], then the propagate over the transposed topology
-            GNN_TRY(gnn_launch_transpose(d_w, f_in, f_out, wt, s));
-            GNN_TRY(gnn_launch_xw(d_grad_out, N, f_out, wt, f_in, dinv, nullptr, false, gs, s));
+            GNN_TRY(gnn_launch_xwt(d_grad_out, N, f_out, d_w, f_in, dinv, wt, gs, s));
             gnn_epilogue epi;
             epi.self_scale = add_self_loops ? 1.0f : 0.0f;
             epi.row_scale = dinv;
@@ -554,8 +563,7 @@ gnn_status gnn_gcnconv_backward(const gnn_graph *g, const gnn_graph *g_by_source
                                      epi, t, s));
     }
     if (d_grad_x) {
-        GNN_TRY(gnn_launch_transpose(d_w, f_in, f_out, wt, s));
-        GNN_TRY(gnn_dense_xw(t, N, f_out, wt, f_in, nullptr, d_grad_x, stream));
+        GNN_TRY(gnn_launch_xwt(t, N, f_out, d_w, f_in, nullptr, wt, d_grad_x, s));
     }
     if (d_grad_w) GNN_TRY(gnn_launch_xty(d_x, t, N, f_in, f_out, part, d_grad_w, s));
     return GNN_OK;

@@ -41,6 +41,7 @@ struct XwEpilogue {
     const float *bias = nullptr;
     int relu = 0;
     gnn_column_norm norm;   // applied to X on the way in when norm.mean is set (fast kernel only)
+    int w_transposed = 0;   // w is stored [n x k]: the product is X w^T (fast kernel only)
 };
 
 struct AFrag {
@@ -189,7 +190,9 @@ struct WStage {
         c = ((blk / KBLOCKS) * 4 + (l >> 4)) * 4;
     }
 
-    __device__ __forceinline__ void load(const float *__restrict__ w, int k, int n, int k0, int n0)
+    // transposed: w is stored [n x k] (the product is X w^T); the four columns of a group are then four rows of
+    // the array, read as single words -- lanes with neighbouring k still read neighbouring addresses.
+    __device__ __forceinline__ void load(const float *__restrict__ w, int k, int n, int k0, int n0, bool transposed = false)
     {
 #pragma unroll
         for (int it = 0; it < ITERS; ++it) {
@@ -197,8 +200,14 @@ struct WStage {
             int kk, c;
             decode(idx, kk, c);
             const bool inside = k0 + kk < k && n0 + c < n;
-            const float *p = inside ? w + (int64_t)(k0 + kk) * n + n0 + c : w;
-            v[it] = *reinterpret_cast<const float4 *>(p);
+            if (transposed) {   // the same for every thread of the launch
+                const float *p = inside ? w + (int64_t)(n0 + c) * k + k0 + kk : w;
+                const int64_t step = inside ? k : 0;
+                v[it] = make_float4(p[0], p[step], p[2 * step], p[3 * step]);
+            } else {
+                const float *p = inside ? w + (int64_t)(k0 + kk) * n + n0 + c : w;
+                v[it] = *reinterpret_cast<const float4 *>(p);
+            }
         }
     }
 
@@ -519,7 +528,7 @@ __global__ __launch_bounds__(kFastThreadsMax) void xw_fast_kernel(const float *_
                                                                   const float *__restrict__ row_scale,
                                                                   const float *__restrict__ bias, int relu,
                                                                   float *__restrict__ z, int64_t rows,
-                                                                  const gnn_column_norm cn)
+                                                                  const gnn_column_norm cn, int w_transposed)
 {
     constexpr int BN = NT * 32;
     constexpr int KP = KQ * 32;
@@ -553,7 +562,7 @@ __global__ __launch_bounds__(kFastThreadsMax) void xw_fast_kernel(const float *_
     {
         WStage<BN, KP, kStageThreads> st;
         const bool stager = threadIdx.x < kStageThreads;   // whole wavefronts
-        if (stager) st.load(w, k, n, 0, n0);
+        if (stager) st.load(w, k, n, 0, n0, w_transposed != 0);
         __builtin_amdgcn_sched_barrier(0);
         load_tile<KQ>(t, x, rows, k, tile * kRowsPerWave, lane);
         if constexpr (SCALED) load_row_scales(rs_next, row_scale, tile * kRowsPerWave, rows, lane);
@@ -675,13 +684,13 @@ gnn_status launch_fast(const float *d_x, int64_t rows, int k, const float *d_w, 
     if (ep.norm.mean) {   // the one user: a graph convolution (row factors) reading batch-normalised rows
         if (!ep.row_scale) return GNN_ERR_UNSUPPORTED;
         hipLaunchKernelGGL((xw_fast_kernel<NT, KQ, true, true>), grid, dim3(64 * WAVES), lds, s, d_x, k, d_w, n,
-                           ep.row_scale, ep.bias, ep.relu, d_z, rows, ep.norm);
+                           ep.row_scale, ep.bias, ep.relu, d_z, rows, ep.norm, ep.w_transposed);
     } else if (ep.row_scale)
         hipLaunchKernelGGL((xw_fast_kernel<NT, KQ, true>), grid, dim3(64 * WAVES), lds, s, d_x, k, d_w, n,
-                           ep.row_scale, ep.bias, ep.relu, d_z, rows, ep.norm);
+                           ep.row_scale, ep.bias, ep.relu, d_z, rows, ep.norm, ep.w_transposed);
     else
         hipLaunchKernelGGL((xw_fast_kernel<NT, KQ, false>), grid, dim3(64 * WAVES), lds, s, d_x, k, d_w, n,
-                           ep.row_scale, ep.bias, ep.relu, d_z, rows, ep.norm);
+                           ep.row_scale, ep.bias, ep.relu, d_z, rows, ep.norm, ep.w_transposed);
     GNN_LAUNCH_CHECK();
     return GNN_OK;
 }
@@ -731,9 +740,14 @@ bool gnn_xw_takes_column_norm(const float *d_x, int64_t rows, int32_t k, const f
     return rows > 0 && k > 0 && n > 0 && takes_fast_kernel(d_x, k, d_w, n);
 }
 
+bool gnn_xw_takes_transposed_w(const float *d_x, int64_t rows, int32_t k, const float *d_w, int32_t n)
+{
+    return rows > 0 && k > 0 && n > 0 && takes_fast_kernel(d_x, k, d_w, n);
+}
+
 gnn_status gnn_launch_xw(const float *d_x, int64_t rows, int32_t k, const float *d_w, int32_t n,
                          const float *d_row_scale, const float *d_bias, bool relu, float *d_z, hipStream_t s,
-                         const gnn_column_norm *norm)
+                         const gnn_column_norm *norm, bool w_transposed)
 {
     if (!d_x || !d_w || !d_z) return GNN_ERR_NULL;
     if (rows < 0 || k <= 0 || n <= 0) return GNN_ERR_BAD_SIZE;
@@ -745,6 +759,10 @@ gnn_status gnn_launch_xw(const float *d_x, int64_t rows, int32_t k, const float 
     if (norm) {
         if (!norm->mean || !norm->var || !d_row_scale || !takes_fast_kernel(d_x, k, d_w, n)) return GNN_ERR_UNSUPPORTED;
         ep.norm = *norm;
+    }
+    if (w_transposed) {
+        if (!takes_fast_kernel(d_x, k, d_w, n)) return GNN_ERR_UNSUPPORTED;
+        ep.w_transposed = 1;
     }
     const bool x_vec4 = (k % 4 == 0) && ((reinterpret_cast<uintptr_t>(d_x) & 15u) == 0);
     const bool w_vec4 = (n % 4 == 0) && ((reinterpret_cast<uintptr_t>(d_w) & 15u) == 0);

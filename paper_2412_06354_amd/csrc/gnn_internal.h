@@ -229,7 +229,14 @@ bool gnn_xw_takes_column_norm(const float *d_x, int64_t rows, int32_t k, const f
 // norm (optional): X is normalised on the way in; only where gnn_xw_takes_column_norm says so (else GNN_ERR_UNSUPPORTED).
 gnn_status gnn_launch_xw(const float *d_x, int64_t rows, int32_t k, const float *d_w, int32_t n,
                          const float *d_row_scale, const float *d_bias, bool relu, float *d_z, hipStream_t s,
-                         const gnn_column_norm *norm = nullptr);
+                         const gnn_column_norm *norm = nullptr, bool w_transposed = false);
+// w_transposed: d_w is stored [n x k] and the product is X d_w^T (the backward passes multiply by the transpose of
+// the forward's weights); only where gnn_xw_takes_transposed_w says so (else GNN_ERR_UNSUPPORTED).
+bool gnn_xw_takes_transposed_w(const float *d_x, int64_t rows, int32_t k, const float *d_w, int32_t n);
+// Z = X W^T for W stored [n x k]: directly where the projection kernel can read W that way, else through a
+// transposed copy in d_wt (n * k floats).
+gnn_status gnn_launch_xwt(const float *d_x, int64_t rows, int32_t k, const float *d_w, int32_t n,
+                          const float *d_row_scale, float *d_wt, float *d_z, hipStream_t s);
 // gnn_gcnconv with an optional batch normalisation of X applied as the projection reads it (gcnconv.hip); with a
 // norm only where gnn_gcnconv_takes_column_norm says so.
 bool gnn_gcnconv_takes_column_norm(const gnn_graph *g, const float *d_x, int32_t f_in, const float *d_w, int32_t f_out);
