@@ -29,6 +29,8 @@ struct GatBwdParams {
     const float *sl;                     // [N x H]
     const float *a_src;                  // [H x ch] (by destination: sl[j] recomputed from the gathered h[j])
     const float4 *rec;                   // [N x H]: (sr, segment maximum, 1 / denominator, t)
+    const float *a_dst, *term_dsr;       // by-source pass: the rows it writes also take the score terms
+                                         // dsl a_src + dsr a_dst (term_dsr = the by-destination pass's result)
     float *out_vec;                      // [N x HC], by-source pass only
     float *out_s;                        // [N x H]
     float *slot_vec, *slot_s;            // [slots x HC] each
@@ -146,7 +148,15 @@ __device__ __forceinline__ void lane_edge(Lane<VEC> &ln, const GatBwdParams &p, 
 template <int VEC, bool BY_SRC>
 __device__ __forceinline__ void lane_write(const Lane<VEC> &ln, const GatBwdParams &p, int row, int col, int hd)
 {
-    if constexpr (BY_SRC) store_vec<VEC>(p.out_vec + (int64_t)row * p.HC + col, ln.acc_v);
+    if constexpr (BY_SRC) {
+        // dh[i,hd,c] = sum of alpha G  +  dsl[i,hd] a_src[hd,c] + dsr[i,hd] a_dst[hd,c]: this row's dsl is the sum the
+        // lane has just finished (the same in every lane of the head)
+        float v[VEC];
+        const float l = ln.acc_s, r = p.term_dsr[(int64_t)row * p.H + hd];
+#pragma unroll
+        for (int c = 0; c < VEC; ++c) v[c] = fmaf(l, p.a_src[col + c], fmaf(r, p.a_dst[col + c], ln.acc_v[c]));
+        store_vec<VEC>(p.out_vec + (int64_t)row * p.HC + col, v);
+    }
     if (col % p.ch == 0) p.out_s[(int64_t)row * p.H + hd] = ln.acc_s;
 }
 
@@ -340,37 +350,6 @@ __global__ __launch_bounds__(kThreads) void node_records_kernel(const float *__r
     rec[idx] = make_float4(sr[idx], d > 0.0f ? m : 0.0f, d > 0.0f ? 1.0f / d : 0.0f, t);
 }
 
-// dh[i,hd,c] += dsl[i,hd] a_src[hd,c] + dsr[i,hd] a_dst[hd,c]
-// A thread owns VEC consecutive columns (one head's) and walks down the rows: its slices of the attention vectors
-// stay in registers, a block step covers as many whole rows as the block's threads hold, nothing is divided per
-// element.
-template <int VEC>
-__global__ __launch_bounds__(kThreads) void add_score_terms_kernel(float *__restrict__ dh, int64_t N, int H, int ch,
-                                                                   const float *__restrict__ dsl,
-                                                                   const float *__restrict__ dsr,
-                                                                   const float *__restrict__ a_src,
-                                                                   const float *__restrict__ a_dst)
-{
-    const int HC = H * ch, groups = HC / VEC;
-    const int rows_per_step = groups >= kThreads ? 1 : kThreads / groups;
-    const int rl = (int)threadIdx.x / groups, g0 = (int)threadIdx.x - rl * groups;
-    if (rl >= rows_per_step) return;
-    for (int g = g0; g < groups; g += kThreads) {   // one trip, unless a row has more column groups than the block has threads
-        const int col = g * VEC, hd = col / ch;
-        float as[VEC], ad[VEC];
-        load_vec<VEC>(as, a_src + col);
-        load_vec<VEC>(ad, a_dst + col);
-        for (int64_t i = (int64_t)blockIdx.x * rows_per_step + rl; i < N; i += (int64_t)gridDim.x * rows_per_step) {
-            const float l = dsl[i * H + hd], r = dsr[i * H + hd];
-            float v[VEC];
-            load_vec<VEC>(v, dh + i * HC + col);
-#pragma unroll
-            for (int c = 0; c < VEC; ++c) v[c] = fmaf(l, as[c], fmaf(r, ad[c], v[c]));
-            store_vec<VEC>(dh + i * HC + col, v);
-        }
-    }
-}
-
 // partial_l[chunk][col] = sum over the chunk's rows of dsl[row,hd] h[row,col]; partial_r with dsr.
 // A block's threads form (row slice, column) pairs: slice s takes rows s, s + slices, ... of the chunk
 // and the slices are folded through LDS in slice order.
@@ -560,7 +539,7 @@ gnn_status gnn_gatconv_backward(const gnn_graph *g, const gnn_graph *g_by_source
     p.own_vec = d_grad_out; p.nbr_vec = h; p.out_vec = nullptr; p.out_s = dsr;
     GNN_TRY(run_pass<false>(g, p, vec4, s));
     // by source: dsl and the attention-weighted sum of G
-    p.own_vec = h; p.nbr_vec = d_grad_out; p.out_vec = dh; p.out_s = dsl;
+    p.own_vec = h; p.nbr_vec = d_grad_out; p.out_vec = dh; p.out_s = dsl; p.a_dst = d_a_dst; p.term_dsr = dsr;
     GNN_TRY(run_pass<true>(g_by_source, p, vec4, s));
 
     const int chunks = gnn_row_chunk_count(N);
@@ -572,20 +551,6 @@ gnn_status gnn_gatconv_backward(const gnn_graph *g, const gnn_graph *g_by_source
         GNN_LAUNCH_CHECK();
         if (d_grad_a_src) GNN_TRY(gnn_launch_sum_partials(part_l, chunks, HC, d_grad_a_src, s));
         if (d_grad_a_dst) GNN_TRY(gnn_launch_sum_partials(part_r, chunks, HC, d_grad_a_dst, s));
-    }
-    if (d_grad_x || d_grad_w) {
-        // 128-bit column groups when a head's channels come in fours and the attention vectors are aligned
-        const bool wide = ch % 4 == 0 && ((reinterpret_cast<uintptr_t>(d_a_src) | reinterpret_cast<uintptr_t>(d_a_dst)) & 15u) == 0;
-        const int groups = wide ? HC / 4 : HC;
-        const int rows_per_step = groups >= kThreads ? 1 : kThreads / groups;
-        const int blocks = (int)std::min<int64_t>(gnn_div_up(N, rows_per_step), 256 * 64);
-        if (wide)
-            hipLaunchKernelGGL(add_score_terms_kernel<4>, dim3(blocks), dim3(kThreads), 0, s, dh, N, heads, ch, dsl, dsr,
-                               d_a_src, d_a_dst);
-        else
-            hipLaunchKernelGGL(add_score_terms_kernel<1>, dim3(blocks), dim3(kThreads), 0, s, dh, N, heads, ch, dsl, dsr,
-                               d_a_src, d_a_dst);
-        GNN_LAUNCH_CHECK();
     }
     if (d_grad_w) GNN_TRY(gnn_launch_xty(d_x, dh, N, f_in, HC, part, d_grad_w, s));
     if (d_grad_x) {
